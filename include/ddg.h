@@ -1,0 +1,183 @@
+/*
+ * ddg.h - C boundary of the MI355X DDG module-step library.
+ *
+ * The operations follow "Decoupled Parallel Backpropagation with Convergence
+ * Guarantee" (arXiv 1804.10574):
+ *   - a feed-forward network is cut into K modules G(1..K) (Section 3);
+ *   - in iteration t every module runs its forward pass on minibatch t
+ *     (Section 3.1; Section 2, Eq. 3);
+ *   - module k then back-propagates the error gradient of iteration
+ *     s = t-K+k, which the module above produced one iteration earlier
+ *     (Section 3.1, Eq. 6-7; Figure 2), and computes no gradient while s < 0
+ *     (Section 3.3, Eq. 8);
+ *   - every module updates its own weights (Eq. 9, Algorithm 1), here with
+ *     the momentum SGD of Section 5.2.
+ * The paper does not say how a module obtains its inner activations of
+ * iteration s. This library keeps the module INPUT of the last K-k iterations
+ * in a ring of device buffers and re-runs the module's forward on the stored
+ * input with the module's current weights before back-propagating.
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers unless the argument says "host".
+ *   - Activations and error gradients are NHWC (channels innermost), element
+ *     type = the module's `compute` type (float, or bfloat16 stored as
+ *     uint16_t, round-to-nearest-even).
+ *   - Master weights, velocity, gradients, BN statistics and the loss are fp32.
+ *   - The caller owns every pointer it passes; the library owns everything it
+ *     allocates in ddg_module_create and frees it in ddg_module_destroy.
+ *   - Calls enqueue work on the module's stream and return without waiting,
+ *     except where a call says it synchronises. Ordering between modules
+ *     (stream waits on the tensors they exchange) is the caller's job, or
+ *     ddg_pipeline_* does it.
+ *   - Every call returns a ddg_status; ddg_last_error() gives the message of
+ *     the last failure on the calling thread. Argument, shape and state errors
+ *     are detected before any device work and leave the module unchanged.
+ */
+#ifndef DDG_H
+#define DDG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ddg_module ddg_module;     /* opaque */
+typedef struct ddg_pipeline ddg_pipeline; /* opaque */
+
+typedef enum {
+  DDG_OK = 0,
+  DDG_ERR_INVALID_ARG = 1, /* null pointer, bad enum, bad K/k                     */
+  DDG_ERR_SHAPE = 2,       /* block list inconsistent or a shape no kernel covers */
+  DDG_ERR_STATE = 3,       /* calls out of order, wrong iteration index           */
+  DDG_ERR_OOM = 4,         /* device allocation failed                            */
+  DDG_ERR_DEVICE = 5       /* any other HIP error (sticky on the handle)          */
+} ddg_status;
+
+typedef enum { DDG_F32 = 0, DDG_BF16 = 1 } ddg_dtype;
+
+typedef enum {
+  DDG_BLOCK_STEM = 0,       /* conv3x3(cin->cout, stride) + BN + ReLU                        */
+  DDG_BLOCK_BASIC = 1,      /* conv3x3+BN+ReLU, conv3x3+BN, shortcut, add, ReLU (Table 2)     */
+  DDG_BLOCK_BOTTLENECK = 2, /* conv1x1(cin->cmid)+BN+ReLU, conv3x3+BN+ReLU, conv1x1+BN, add   */
+  DDG_BLOCK_HEAD = 3        /* global average pool + linear + softmax cross-entropy (loss f)  */
+} ddg_block_kind;
+
+/* One block. `projection` != 0 puts conv1x1(cin->cout, stride)+BN on the shortcut;
+ * it is required when stride != 1 or cin != cout. For DDG_BLOCK_HEAD only cin is read. */
+typedef struct {
+  int kind;
+  int cin, cmid, cout;
+  int stride;
+  int projection;
+} ddg_block_desc;
+
+typedef struct {
+  int K, k;                    /* number of modules, 1-based index of this one; delay = K-k   */
+  int batch, in_c, in_h, in_w; /* logical shape of the module input (stored NHWC)             */
+  int num_blocks;
+  const ddg_block_desc* blocks; /* host; copied                                               */
+  int num_classes;             /* > 0 iff the last block is DDG_BLOCK_HEAD (then k must be K) */
+  int compute;                 /* ddg_dtype of activations, error gradients, conv operands    */
+  float momentum, weight_decay, bn_eps;
+  void* stream;                /* hipStream_t the module's work is enqueued on (0 = default)  */
+  int dry_run;                 /* != 0: no device memory, no launches; only the argument and
+                                  state checks run (lets host logic be tested without a GPU) */
+} ddg_module_desc;
+
+/* Section 3: create module G(k). Allocates weights, velocity, gradients, the input ring of
+ * K-k+1 slots, saved activations and workspaces on the current device. Weights start at
+ * zero: set them with ddg_set_params before the first forward. */
+ddg_status ddg_module_create(const ddg_module_desc* desc, ddg_module** out);
+ddg_status ddg_module_destroy(ddg_module* m);
+
+/* Number of fp32 parameters. Flat order, per block: conv1.W, bn1.gamma, bn1.beta, conv2.W,
+ * ..., then the projection's conv and BN if present; conv W is [Cout][Cin][R][S]; the head
+ * holds fc.W[classes][C] then fc.b. Velocity and gradient use the same order. */
+size_t ddg_param_count(const ddg_module* m);
+/* Logical output shape (channels, height, width) of the module; batch is the input's. */
+ddg_status ddg_out_shape(const ddg_module* m, int* c, int* h, int* w);
+/* Device bytes the module holds. */
+size_t ddg_device_bytes(const ddg_module* m);
+
+/* Copy parameters in (src: host if !is_device, else device; fp32, ddg_param_count values) and
+ * refresh the packed conv operands. Enqueued on the module's stream; a host source is read
+ * before the call returns. */
+ddg_status ddg_set_params(ddg_module* m, const float* src, int is_device);
+/* Same for the momentum buffer (resuming a run; v starts at zero after create). */
+ddg_status ddg_set_velocity(ddg_module* m, const float* src, int is_device);
+/* Copy parameters / velocity / last gradient to HOST memory; synchronises the stream.
+ * ddg_get_grad sets *valid = 0 if the last backward call computed no gradient. */
+ddg_status ddg_get_params(ddg_module* m, float* host_dst);
+ddg_status ddg_get_velocity(ddg_module* m, float* host_dst);
+ddg_status ddg_get_grad(ddg_module* m, float* host_dst, int* valid);
+
+/* Section 3.1 / Eq. 3: forward of module k on the minibatch of iteration t with the current
+ * weights (BN uses batch statistics). h_in [batch,in_h,in_w,in_c] is copied into ring slot
+ * t mod (K-k+1) and kept for K-k iterations; h_out [batch,out_h,out_w,out_c] receives the
+ * module output (may be NULL when the module ends in the head). t counts iterations from 0
+ * and must increase by exactly 1 from one forward call to the next. */
+ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out);
+
+/* Section 3.1, Eq. 6-7 and Eq. 8: delayed backward of iteration s = t-K+k. If s < 0 nothing
+ * is computed and *did_backward = 0. Otherwise the input stored at iteration s is re-forwarded
+ * with the current weights (the last module reuses the forward of this same iteration), then
+ * delta_in = df/dh at the module output [batch,out_h,out_w,out_c] is back-propagated:
+ * parameter gradients g_k^t go to the module's gradient buffer, and df/dh at the module input
+ * is written to delta_out [batch,in_h,in_w,in_c] (NULL allowed when k == 1: never computed).
+ * For the head module delta_in must be NULL and labels (device int32 [batch], class of each
+ * sample of minibatch s = t) non-NULL; the mean cross-entropy is written to loss_out (device
+ * float, may be NULL). did_backward is a host int, may be NULL. Must follow ddg_forward(t). */
+ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, const int32_t* labels,
+                                void* delta_out, float* loss_out, int* did_backward);
+
+/* Eq. 9 / Algorithm 1 with momentum (Section 5.2): v <- mu*v + (g + wd*w); w <- w - lr*v,
+ * then the packed conv operands are refreshed. A no-op while the module has no gradient
+ * (s < 0). Must follow ddg_backward_delayed(t). */
+ddg_status ddg_update(ddg_module* m, long t, float lr);
+
+/* Wait for the module's stream. */
+ddg_status ddg_module_sync(ddg_module* m);
+
+/* ---- K modules as concurrent streams (Algorithm 1, "for k = 1..K in parallel") -------------
+ * The pipeline owns the K modules, the activations handed from module k to k+1 and the
+ * double-buffered error-gradient mailboxes handed from k+1 to k, and orders the streams with
+ * events: forward runs k = 1..K in turn; the K backward passes and updates of one iteration
+ * overlap. streams: K hipStream_t handles (host array) or NULL to run everything on stream 0
+ * (serialised; results are identical). descs[i] describes module i+1; descs[i].stream is
+ * ignored. */
+ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const* streams,
+                               ddg_pipeline** out);
+ddg_status ddg_pipeline_destroy(ddg_pipeline* p);
+ddg_module* ddg_pipeline_module(ddg_pipeline* p, int k);
+/* One iteration: x [batch,in_h,in_w,in_c] in module 1's compute type, labels int32 [batch],
+ * both device pointers that must stay valid until the step's work has run; loss_out: device
+ * float or NULL. Iterations are counted internally from 0. */
+ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labels, float lr,
+                             float* loss_out);
+/* Copy module k's latest forward output / the error gradient last delivered to module k
+ * (mailbox) to host memory as fp32 NHWC; synchronises. *iteration receives the iteration the
+ * mailbox content belongs to (-1: none yet). */
+ddg_status ddg_pipeline_get_h(ddg_pipeline* p, int k, float* host_dst);
+ddg_status ddg_pipeline_get_delta(ddg_pipeline* p, int k, float* host_dst, long* iteration);
+ddg_status ddg_pipeline_sync(ddg_pipeline* p);
+
+/* ---- measurement ----------------------------------------------------------------------------
+ * Per-kernel-family timing with HIP events on the module's stream. While enabled, every launch
+ * of a kernel family is bracketed by two events; ddg_profile_read synchronises and returns, for
+ * family `kind` (0 <= kind < ddg_profile_kinds()), the number of launches and their summed
+ * duration in milliseconds since the last reset. */
+int ddg_profile_kinds(void);
+const char* ddg_profile_kind_name(int kind);
+ddg_status ddg_profile_enable(ddg_module* m, int on);
+ddg_status ddg_profile_read(ddg_module* m, int kind, long* launches, double* total_ms);
+ddg_status ddg_profile_reset(ddg_module* m);
+
+const char* ddg_last_error(void);
+const char* ddg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDG_H */

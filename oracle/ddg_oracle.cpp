@@ -24,6 +24,16 @@
 // input and back-propagates through that snapshot: this realises Eq. 6-7/8-9
 // literally and exists to pin the delay bookkeeping against plain backprop.
 //
+// Storage precision. The paper does not state a number format. The benchmark this oracle
+// serves fixes bf16 convolution operands with fp32 accumulation for some workloads; with
+// `store_bf16` every tensor that such an implementation keeps in memory between layers
+// (conv outputs, activations, error gradients, conv weights as operands) is rounded to
+// bf16 (round-to-nearest-even) at the point where it is produced, while all arithmetic
+// stays in the oracle's scalar type. This puts the sign decisions of ReLU on the same
+// values on both sides; without it a sign flip of a near-zero pre-activation changes the
+// masked gradient by O(1) for that element. Parameters, statistics, weight gradients and
+// the update are never rounded.
+//
 // Layouts: activations NCHW, conv weights [Cout][Cin][R][S], all row-major.
 // Parameter order per block: conv.W, bn.gamma, bn.beta for each conv unit in
 // order (conv1, conv2, [conv3], [projection]); head: fc.W[classes][C], fc.b.
@@ -47,6 +57,23 @@ namespace {
 enum { KIND_STEM = 0, KIND_BASIC = 1, KIND_BOTTLENECK = 2, KIND_HEAD = 3 };
 
 inline int out_dim(int h, int R, int stride, int pad) { return (h + 2 * pad - R) / stride + 1; }
+
+// Round to bfloat16 (8 bits of significand), nearest-even, through float32.
+template <class T>
+inline T round_bf16(T v) {
+  float f = (float)v;
+  unsigned int u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return v;  // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  u &= 0xffff0000u;
+  std::memcpy(&f, &u, 4);
+  return (T)f;
+}
+template <class T>
+inline void round_store(std::vector<T>& v, bool on) {
+  if (on) for (auto& e : v) e = round_bf16(e);
+}
 
 // ---------------------------------------------------------------------------
 // Convolution: y[n,co,p,q] = sum_{ci,r,s} x[n,ci,p*st+r-pad,q*st+s-pad] * w[co,ci,r,s]
@@ -284,27 +311,33 @@ struct Unit {  // convolution followed by batch normalisation
   int N = 0, H = 0, W = 0, P = 0, Q = 0;
   std::vector<T> x, z, mean, invstd;  // tape: conv input, conv output, batch statistics
 
-  std::vector<T> forward(const T* th, const std::vector<T>& in, int N_, int H_, int W_, T eps) {
+  std::vector<T> wop;  // conv weights as the convolution sees them (rounded if store_bf16)
+  std::vector<T> forward(const T* th, const std::vector<T>& in, int N_, int H_, int W_, T eps, bool rb) {
     N = N_; H = H_; W = W_;
     P = out_dim(H, R, st, pad); Q = out_dim(W, R, st, pad);
     x = in;
+    wop.assign(th + ow, th + ow + (size_t)co * ci * R * R);
+    round_store(wop, rb);
     z.assign((size_t)N * co * P * Q, T(0));
-    conv_fwd(x.data(), th + ow, z.data(), N, ci, H, W, co, R, st, pad);
+    conv_fwd(x.data(), wop.data(), z.data(), N, ci, H, W, co, R, st, pad);
+    round_store(z, rb);
     mean.assign(co, T(0)); invstd.assign(co, T(0));
     std::vector<T> y(z.size());
     bn_fwd(z.data(), th + og, th + ob, eps, y.data(), mean.data(), invstd.data(), N, co, P * Q);
     return y;
   }
-  // dy: gradient w.r.t. the BN output. Fills this unit's parameter gradients.
-  std::vector<T> backward(const T* th, T* g, const std::vector<T>& dy, bool need_dx) {
+  // dy: gradient w.r.t. the BN output. Fills this unit's parameter gradients. The returned
+  // input gradient is not yet rounded: the caller may add a shortcut term first.
+  std::vector<T> backward(const T* th, T* g, const std::vector<T>& dy, bool need_dx, bool rb) {
     std::vector<T> dz(z.size());
     bn_bwd(dy.data(), z.data(), mean.data(), invstd.data(), th + og, dz.data(), g + og, g + ob, N,
            co, P * Q);
+    round_store(dz, rb);
     conv_bwd_weight(x.data(), dz.data(), g + ow, N, ci, H, W, co, R, st, pad);
     std::vector<T> dx;
     if (need_dx) {
       dx.assign(x.size(), T(0));
-      conv_bwd_data(dz.data(), th + ow, dx.data(), N, ci, H, W, co, R, st, pad);
+      conv_bwd_data(dz.data(), wop.data(), dx.data(), N, ci, H, W, co, R, st, pad);
     }
     return dx;
   }
@@ -357,6 +390,7 @@ struct Net {
   int K = 1, k_first = 1;
   T momentum = T(0), wd = T(0), eps = T(1e-5);
   int stale_jacobian = 0;
+  int store_bf16 = 0;
   long t = 0;
   std::vector<Module<T>> mods;
   Module<T>& mod(int k) { return mods[k - k_first]; }
@@ -407,7 +441,7 @@ void build_module(Module<T>& m, const int* desc, int nblocks) {
 
 // Forward of one module (Eq. 3 for every layer of G(k)), taping intermediates.
 template <class T>
-std::vector<T> module_forward(Module<T>& m, const T* th, const std::vector<T>& in, T eps) {
+std::vector<T> module_forward(Module<T>& m, const T* th, const std::vector<T>& in, T eps, bool rb) {
   std::vector<T> cur = in;
   int h = m.in_h, w = m.in_w;
   for (auto& b : m.blocks) {
@@ -417,16 +451,18 @@ std::vector<T> module_forward(Module<T>& m, const T* th, const std::vector<T>& i
     std::vector<T> a = cur;
     for (int i = 0; i < b.nmain; ++i) {
       const int hh = (i == 0) ? h : b.u[i - 1].P, ww = (i == 0) ? w : b.u[i - 1].Q;
-      a = b.u[i].forward(th, a, m.N, hh, ww, eps);
+      a = b.u[i].forward(th, a, m.N, hh, ww, eps, rb);
       if (i + 1 < b.nmain || b.kind == KIND_STEM) {
         relu_inplace(a);
+        round_store(a, rb);
         if (i + 1 < b.nmain) b.act.push_back(a);
       }
     }
     if (b.kind != KIND_STEM) {
-      std::vector<T> sc = (b.projection) ? b.u[b.nmain].forward(th, cur, m.N, h, w, eps) : cur;
+      std::vector<T> sc = (b.projection) ? b.u[b.nmain].forward(th, cur, m.N, h, w, eps, rb) : cur;
       for (size_t i = 0; i < a.size(); ++i) a[i] = a[i] + sc[i];
       relu_inplace(a);
+      round_store(a, rb);
     }
     b.y = a;
     h = b.u[b.nmain - 1].P; w = b.u[b.nmain - 1].Q;
@@ -441,7 +477,7 @@ std::vector<T> module_forward(Module<T>& m, const T* th, const std::vector<T>& i
 // error gradient at the module input when need_dx.
 template <class T>
 std::vector<T> module_backward(Module<T>& m, const T* th, T* g, const std::vector<T>& dtop,
-                               const int* labels, bool need_dx) {
+                               const int* labels, bool need_dx, bool rb) {
   std::vector<T> d = dtop;
   for (int bi = (int)m.blocks.size() - 1; bi >= 0; --bi) {
     auto& b = m.blocks[bi];
@@ -452,6 +488,7 @@ std::vector<T> module_backward(Module<T>& m, const T* th, T* g, const std::vecto
       m.last_loss = head_fwd_bwd(b.xin.data(), th + b.ofcw, th + b.ofcb, labels, b.N, b.cin,
                                  b.H * b.W, m.classes, d.data(), g + b.ofcw, g + b.ofcb,
                                  m.last_logits.data());
+      round_store(d, rb);
       continue;
     }
     relu_mask(d, b.y);  // the block ends in a ReLU
@@ -459,19 +496,21 @@ std::vector<T> module_backward(Module<T>& m, const T* th, T* g, const std::vecto
     std::vector<T> dsum = d, dx;
     for (int i = b.nmain - 1; i >= 0; --i) {
       const bool unit_dx = (i > 0) || want_dx;
-      d = b.u[i].backward(th, g, d, unit_dx);
-      if (i > 0) relu_mask(d, b.act[i - 1]);
+      d = b.u[i].backward(th, g, d, unit_dx, rb);
+      if (i > 0) { round_store(d, rb); relu_mask(d, b.act[i - 1]); }
     }
     if (b.kind != KIND_STEM && want_dx) {
       if (b.projection) {
-        std::vector<T> dp = b.u[b.nmain].backward(th, g, dsum, true);
+        std::vector<T> dp = b.u[b.nmain].backward(th, g, dsum, true, rb);
+        round_store(dp, rb);
         for (size_t i = 0; i < d.size(); ++i) d[i] = d[i] + dp[i];
       } else {
         for (size_t i = 0; i < d.size(); ++i) d[i] = d[i] + dsum[i];
       }
     } else if (b.kind != KIND_STEM && b.projection) {
-      b.u[b.nmain].backward(th, g, dsum, false);
+      b.u[b.nmain].backward(th, g, dsum, false, rb);
     }
+    round_store(d, rb);
   }
   return d;
 }
@@ -485,8 +524,9 @@ void ddg_forward(Net<T>& net, int k, long t, const T* h_in, T* h_out) {
   e.u.assign(h_in, h_in + m.in_size());
   e.t = t;
   if (net.stale_jacobian) e.theta = m.theta;
+  round_store(e.u, net.store_bf16 != 0);
   m.fifo.push_back(e);
-  m.h_out = module_forward(m, m.theta.data(), m.fifo.back().u, net.eps);
+  m.h_out = module_forward(m, m.theta.data(), m.fifo.back().u, net.eps, net.store_bf16 != 0);
   if (h_out) std::copy(m.h_out.begin(), m.h_out.end(), h_out);
 }
 
@@ -504,11 +544,12 @@ int ddg_backward_delayed(Net<T>& net, int k, long t, const T* delta_in, const in
   const T* th = net.stale_jacobian ? e.theta.data() : m.theta.data();
   // Re-forward the stored input. With no delay (last module) the tape left by ddg_forward
   // of this same iteration already is that forward: same input, same weights.
-  if (net.K - k > 0) module_forward(m, th, e.u, net.eps);
+  const bool rb = net.store_bf16 != 0;
+  if (net.K - k > 0) module_forward(m, th, e.u, net.eps, rb);
   std::vector<T> dtop;
-  if (!m.has_head) dtop.assign(delta_in, delta_in + m.out_size());
+  if (!m.has_head) { dtop.assign(delta_in, delta_in + m.out_size()); round_store(dtop, rb); }
   const bool need_dx = (k > 1);
-  std::vector<T> dbelow = module_backward(m, th, m.grad.data(), dtop, labels, need_dx);
+  std::vector<T> dbelow = module_backward(m, th, m.grad.data(), dtop, labels, need_dx, rb);
   m.has_grad = true;
   if (need_dx && delta_out) std::copy(dbelow.begin(), dbelow.end(), delta_out);
   if (m.has_head && loss_out) *loss_out = m.last_loss;
@@ -575,14 +616,14 @@ T bp_step(Net<T>& net, const T* x, const int* labels, T lr, int do_update) {
   std::vector<T> h(x, x + net.mod(1).in_size());
   for (int k = 1; k <= K; ++k) {
     auto& m = net.mod(k);
-    m.h_out = module_forward(m, m.theta.data(), h, net.eps);
+    m.h_out = module_forward(m, m.theta.data(), h, net.eps, net.store_bf16 != 0);
     h = m.h_out;
   }
   std::vector<T> d;
   for (int k = K; k >= 1; --k) {
     auto& m = net.mod(k);
     if (k < K) { m.inbox = d; m.inbox_t = net.t; }
-    d = module_backward(m, m.theta.data(), m.grad.data(), d, labels, k > 1);
+    d = module_backward(m, m.theta.data(), m.grad.data(), d, labels, k > 1, net.store_bf16 != 0);
     m.has_grad = true;
   }
   const T loss = net.mod(K).last_loss;
@@ -596,8 +637,9 @@ T bp_step(Net<T>& net, const T* x, const int* labels, T lr, int do_update) {
 template <class T>
 Net<T>* net_create(int K, int k_first, int nmods, const int* nblocks, const int* desc, int batch,
                    int in_c, int in_h, int in_w, int classes, double momentum, double wd,
-                   double eps, int stale_jacobian) {
+                   double eps, int stale_jacobian, int store_bf16) {
   auto* net = new Net<T>();
+  net->store_bf16 = store_bf16;
   net->K = K; net->k_first = k_first;
   net->momentum = T(momentum); net->wd = T(wd); net->eps = T(eps);
   net->stale_jacobian = stale_jacobian;
@@ -641,9 +683,10 @@ Net<T>* net_create(int K, int k_first, int nmods, const int* nblocks, const int*
     return (double)head_fwd_bwd<T>(h, fcw, fcb, labels, N, C, HW, classes, dh, dfcw, dfcb, logits); } \
   void* orc_create_##SFX(int K, int k_first, int nmods, const int* nblocks, const int* desc,     \
                          int batch, int in_c, int in_h, int in_w, int classes, double momentum,  \
-                         double wd, double eps, int stale_jacobian) {                            \
+                         double wd, double eps, int stale_jacobian, int store_bf16) {            \
     return net_create<T>(K, k_first, nmods, nblocks, desc, batch, in_c, in_h, in_w, classes,     \
-                         momentum, wd, eps, stale_jacobian); }                                   \
+                         momentum, wd, eps, stale_jacobian, store_bf16); }                       \
+  void orc_round_bf16_##SFX(T* v, long n) { for (long i = 0; i < n; ++i) v[i] = round_bf16<T>(v[i]); } \
   void orc_destroy_##SFX(void* p) { delete (Net<T>*)p; }                                         \
   long orc_param_count_##SFX(void* p, int k) { return (long)((Net<T>*)p)->mod(k).theta.size(); } \
   long orc_in_size_##SFX(void* p, int k) { return (long)((Net<T>*)p)->mod(k).in_size(); }        \
@@ -652,6 +695,8 @@ Net<T>* net_create(int K, int k_first, int nmods, const int* nblocks, const int*
     auto& m = ((Net<T>*)p)->mod(k); chw[0] = m.out_c; chw[1] = m.out_h; chw[2] = m.out_w; }      \
   void orc_set_params_##SFX(void* p, int k, const T* v) {                                        \
     auto& m = ((Net<T>*)p)->mod(k); std::copy(v, v + m.theta.size(), m.theta.begin()); }         \
+  void orc_set_velocity_##SFX(void* p, int k, const T* v) {                                      \
+    auto& m = ((Net<T>*)p)->mod(k); std::copy(v, v + m.vel.size(), m.vel.begin()); }             \
   void orc_get_params_##SFX(void* p, int k, T* v) {                                              \
     auto& m = ((Net<T>*)p)->mod(k); std::copy(m.theta.begin(), m.theta.end(), v); }              \
   void orc_get_velocity_##SFX(void* p, int k, T* v) {                                            \

@@ -135,6 +135,14 @@ def head(h, fcw, fcb, labels, want_grads=True, dtype="f64"):
     return float(loss), logits, dh, dw, db
 
 
+def round_bf16(a, dtype="f64"):
+    """Round to bfloat16 (nearest-even) and return in the oracle's scalar type."""
+    ty = _Typed(dtype)
+    v = ty.arr(a).copy()
+    ty.fn("round_bf16")(_p(v), C.c_long(v.size))
+    return v
+
+
 # --- whole networks -----------------------------------------------------------------
 
 class OracleNet:
@@ -145,7 +153,7 @@ class OracleNet:
     """
 
     def __init__(self, K, modules, batch, in_chw, num_classes, momentum=0.9, weight_decay=0.0,
-                 bn_eps=1e-5, dtype="f64", stale_jacobian=False, k_first=1):
+                 bn_eps=1e-5, dtype="f64", stale_jacobian=False, k_first=1, store_bf16=False):
         self.ty = _Typed(dtype)
         self.K, self.k_first, self.nmods = K, k_first, len(modules)
         self.batch = batch
@@ -154,14 +162,18 @@ class OracleNet:
         self._h = C.c_void_p(self.ty.fn("create")(
             K, k_first, self.nmods, _p(nblocks), _p(desc), batch, in_chw[0], in_chw[1], in_chw[2],
             num_classes, C.c_double(momentum), C.c_double(weight_decay), C.c_double(bn_eps),
-            1 if stale_jacobian else 0))
+            1 if stale_jacobian else 0, 1 if store_bf16 else 0))
 
     @classmethod
-    def from_workload(cls, wl, dtype="f64", stale_jacobian=False, batch=None):
+    def from_workload(cls, wl, dtype="f64", stale_jacobian=False, batch=None, store_bf16=None):
+        """store_bf16 defaults to the workload's storage type (bf16 workloads round stored tensors)."""
+        if store_bf16 is None:
+            store_bf16 = (wl.dtype == "bf16")
         mods = [[b.as_tuple() for b in m.blocks] for m in wl.modules]
         m0 = wl.modules[0]
         return cls(wl.K, mods, batch or wl.batch, (m0.in_c, m0.in_h, m0.in_w), wl.num_classes,
-                   wl.momentum, wl.weight_decay, wl.bn_eps, dtype, stale_jacobian, k_first=m0.k)
+                   wl.momentum, wl.weight_decay, wl.bn_eps, dtype, stale_jacobian, k_first=m0.k,
+                   store_bf16=store_bf16)
 
     def __del__(self):
         try:
@@ -187,6 +199,11 @@ class OracleNet:
         v = self.ty.arr(v)
         assert v.size == self.param_count(k)
         self.ty.fn("set_params")(self._h, k, _p(v))
+
+    def set_velocity(self, k, v):
+        v = self.ty.arr(v)
+        assert v.size == self.param_count(k)
+        self.ty.fn("set_velocity")(self._h, k, _p(v))
 
     def _get(self, name, k):
         v = np.empty(self.param_count(k), self.ty.np)

@@ -1,0 +1,94 @@
+// Host-side launch interface of the HIP kernels. Every launcher validates nothing:
+// the module code checks shapes before it builds a plan.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ddg {
+
+enum DType { F32 = 0, BF16 = 1 };
+inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
+inline int mma_kv(int dt) { return dt == BF16 ? 8 : 1; }
+
+// Implicit-GEMM convolution on the matrix cores. One kernel serves the forward
+// convolution and the gradient w.r.t. the input:
+//   fprop: out[n,oh,ow,:] = sum_taps in[n, oh*st+r-pad, ow*st+s-pad, :] . W
+//   dgrad: out[n,ih,iw,:] = sum_taps in[n, (ih+pad-r)/st, (iw+pad-s)/st, :] . W^T  (only when divisible)
+// `in` has IC channels (the contraction), `out` has OC channels.
+struct ConvArgs {
+  const void* in;
+  const void* wpack;        // packed operand, see pack_weights
+  void* out;
+  float* stat_partial;      // fprop only: [grid_x][2][OC] per-workgroup sum / sum of squares, or null
+  const void* add_g;        // optional: out += add_g (masked where add_mask <= 0), same layout as out
+  const void* add_mask;
+  int N, IH, IW, IC, OH, OW, OC;
+  int R, stride, pad;
+  int log2cp;               // log2 of the padded contraction channels per tap
+  int ntaps, ksteps;
+  int M;                    // N*OH*OW
+  int dgrad;
+  int dtype;
+  int grid_x;               // filled by conv_plan
+  int mb, nb;               // tile shape chosen by conv_plan
+};
+void conv_plan(ConvArgs& a);                       // chooses tile shape and grid
+hipError_t conv_launch(const ConvArgs& a, hipStream_t s);
+size_t conv_wpack_elems(int kchannels, int nchannels, int R, int dtype, int* log2cp, int* ksteps);
+// Packs fp32 master weights W[Cout][Cin][R][R] into the operand layout of conv_launch.
+hipError_t pack_weights_launch(const float* W, void* wpack, int Cout, int Cin, int R, int dgrad,
+                               int dtype, hipStream_t s);
+
+// Gradient w.r.t. the weights: dW[co][ci][r][s] = sum_{n,p,q} dz[n,p,q,co] * x[n,p*st+r-pad,q*st+s-pad,ci].
+// Two launches: per-split partial tiles, then a fixed-order sum into dW (deterministic).
+struct WgradArgs {
+  const void* x; const void* dz; float* partial; float* dW;
+  int N, H, W, Cin, P, Q, Cout, R, stride, pad;
+  int log2cp, J, JB;        // J = ntaps*CP columns, JB = ceil(J/16)
+  int M;                    // N*P*Q
+  int msplit, steps;        // splits over M, 4-pixel steps per wave
+  int jgroups;              // column-block groups of up to 9
+  int dtype;
+};
+void wgrad_plan(WgradArgs& a);
+size_t wgrad_partial_elems(const WgradArgs& a);
+hipError_t wgrad_launch(const WgradArgs& a, hipStream_t s);
+hipError_t wgrad_reduce_launch(const WgradArgs& a, hipStream_t s);
+
+// Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
+// shift=beta-mean*scale.
+hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,
+                              const float* beta, float count, float eps, float* mean, float* invstd,
+                              float* scale, float* shift, hipStream_t s);
+// y = [relu](z*scale+shift [+ res*rscale+rshift | + res])
+hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const void* res,
+                           const float* rscale, const float* rshift, void* y, size_t elems, int C,
+                           int relu, int dtype, hipStream_t s);
+// g = mask ? (mask>0 ? dy : 0) : dy; partial[grid][2][C] = (sum g, sum g*xhat)
+int bn_bwd_grid(size_t elems, int C, int dtype);
+hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const void* z, const float* mean,
+                                const float* invstd, float* partial, size_t elems, int C, int dtype,
+                                hipStream_t s);
+// dgamma, dbeta and the coefficients of dz = A*g + B*z + C0 (per channel; coef = [3][C])
+hipError_t bn_bwd_finalize_launch(const float* partial, int rows, int C, const float* gamma,
+                                  const float* mean, const float* invstd, float count, float* dgamma,
+                                  float* dbeta, float* coef, hipStream_t s);
+hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const void* z, const float* coef,
+                               void* dz, size_t elems, int C, int dtype, hipStream_t s);
+
+// Head: global average pool, linear, softmax cross-entropy (mean over the batch) and its gradients.
+struct HeadArgs {
+  const void* h; const float* fcw; const float* fcb; const int32_t* labels;
+  float* pooled; float* dlogits; float* loss_n; float* loss_out;
+  float* dfcw; float* dfcb; void* dh;
+  int N, HW, C, classes, dtype;
+};
+hipError_t head_launch(const HeadArgs& a, hipStream_t s);
+
+hipError_t sgd_launch(float* w, float* v, const float* g, size_t n, float lr, float mu, float wd,
+                      hipStream_t s);
+hipError_t copy_launch(const void* src, void* dst, size_t bytes, hipStream_t s);
+hipError_t to_f32_launch(const void* src, float* dst, size_t elems, int dtype, hipStream_t s);
+
+}  // namespace ddg

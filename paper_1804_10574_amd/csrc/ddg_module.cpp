@@ -1,0 +1,681 @@
+// Host side of the DDG module-step library: builds a launch plan for one module G(k)
+// (Section 3 of arXiv 1804.10574), keeps its input ring (delay K-k), and implements the
+// C boundary declared in include/ddg.h. All arithmetic happens in the HIP kernels; this
+// file only validates, allocates and enqueues.
+#include "../../include/ddg.h"
+#include "ddg_kernels.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace ddg;
+
+static thread_local std::string g_err;
+static ddg_status fail(ddg_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return st;
+}
+
+enum ProfKind {
+  PK_CONV_FPROP = 0, PK_CONV_DGRAD, PK_CONV_WGRAD, PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
+  PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_COUNT
+};
+static const char* kProfNames[PK_COUNT] = {
+  "conv_fprop", "conv_dgrad", "conv_wgrad", "wgrad_reduce", "bn_finalize", "bn_apply",
+  "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy"};
+
+struct Unit {  // convolution + batch normalisation
+  int cin = 0, cout = 0, R = 0, stride = 1, pad = 0;
+  int N = 0, H = 0, W = 0, P = 0, Q = 0;
+  size_t ow = 0, og = 0, ob = 0;
+  void* wpack_f = nullptr;
+  void* wpack_d = nullptr;
+  void* z = nullptr;
+  float* mean = nullptr;   // mean, invstd, scale, shift, coef[3C] in one allocation
+  float* invstd = nullptr;
+  float* scale = nullptr;
+  float* shift = nullptr;
+  float* coef = nullptr;
+  ConvArgs fprop{}, dgrad{};
+  WgradArgs wg{};
+  bool has_dgrad = false;
+  size_t out_elems() const { return (size_t)N * P * Q * cout; }
+  size_t in_elems() const { return (size_t)N * H * W * cin; }
+};
+
+struct Blk {
+  int kind = 0;
+  std::vector<Unit> u;
+  int nmain = 0;
+  bool proj = false;
+  std::vector<void*> act;  // post-ReLU outputs of the main units except the last
+  void* y = nullptr;       // block output
+  size_t y_elems = 0;
+  // head
+  size_t ofcw = 0, ofcb = 0;
+  int C = 0, HW = 0;
+  float *pooled = nullptr, *dlogits = nullptr, *loss_n = nullptr;
+};
+
+struct ddg_module {
+  ddg_module_desc d{};
+  std::vector<ddg_block_desc> blocks_desc;
+  std::vector<Blk> blocks;
+  hipStream_t stream = nullptr;
+  int delay = 0, nslots = 1;
+  int out_c = 0, out_h = 0, out_w = 0;
+  size_t nparams = 0, in_elems = 0, out_elems = 0, max_act = 0;
+  size_t esz = 4;
+  float *theta = nullptr, *vel = nullptr, *grad = nullptr;
+  std::vector<void*> ring;
+  void *Ga = nullptr, *Gb = nullptr, *D1 = nullptr, *D2 = nullptr, *D3 = nullptr;
+  float* ws_stat = nullptr; size_t ws_stat_elems = 0;
+  float* ws_wgrad = nullptr; size_t ws_wgrad_elems = 0;
+  std::vector<void*> allocs;
+  size_t bytes = 0;
+  // state
+  long t_next = 0;
+  int phase = 0;  // 0: expect forward, 1: expect backward, 2: expect update
+  bool has_grad = false;
+  bool tape_is_current = false;  // saved activations belong to forward(t) with current weights
+  ddg_status sticky = DDG_OK;
+  // profiling
+  bool prof = false;
+  struct Ev { int kind; hipEvent_t a, b; };
+  std::vector<Ev> evs;
+  long prof_n[PK_COUNT] = {0};
+  double prof_ms[PK_COUNT] = {0};
+};
+
+namespace {
+
+bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+ddg_status dev_alloc(ddg_module* m, void** p, size_t bytes) {
+  *p = nullptr;
+  if (m->d.dry_run || bytes == 0) return DDG_OK;
+  bytes = (bytes + 255) & ~(size_t)255;
+  hipError_t e = hipMalloc(p, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(e == hipErrorOutOfMemory ? DDG_ERR_OOM : DDG_ERR_DEVICE, "hipMalloc(%zu): %s", bytes,
+                hipGetErrorString(e));
+  }
+  m->allocs.push_back(*p);
+  m->bytes += bytes;
+  return DDG_OK;
+}
+
+struct Launch {  // brackets one launch with events when profiling
+  ddg_module* m; int kind; hipEvent_t a = nullptr, b = nullptr;
+  Launch(ddg_module* m_, int kind_) : m(m_), kind(kind_) {
+    if (m->prof) {
+      (void)hipEventCreate(&a); (void)hipEventCreate(&b);
+      (void)hipEventRecord(a, m->stream);
+    }
+  }
+  ~Launch() {
+    if (m->prof) {
+      (void)hipEventRecord(b, m->stream);
+      m->evs.push_back({kind, a, b});
+    }
+  }
+};
+
+#define DDG_TRY(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      m->sticky = DDG_ERR_DEVICE;                                                           \
+      return fail(DDG_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_));                  \
+    }                                                                                       \
+  } while (0)
+
+#define DDG_OKAY(expr)                          \
+  do {                                          \
+    ddg_status s_ = (expr);                     \
+    if (s_ != DDG_OK) return s_;                \
+  } while (0)
+
+int out_dim(int h, int stride) { return (h - 1) / stride + 1; }
+
+// ---- plan ---------------------------------------------------------------------------------
+
+ddg_status validate(const ddg_module_desc* d) {
+  if (!d) return fail(DDG_ERR_INVALID_ARG, "desc is null");
+  if (d->K < 1 || d->k < 1 || d->k > d->K) return fail(DDG_ERR_INVALID_ARG, "need 1 <= k <= K (K=%d k=%d)", d->K, d->k);
+  if (d->compute != DDG_F32 && d->compute != DDG_BF16) return fail(DDG_ERR_INVALID_ARG, "compute must be DDG_F32 or DDG_BF16");
+  if (d->batch < 1 || d->in_c < 1 || d->in_h < 1 || d->in_w < 1) return fail(DDG_ERR_SHAPE, "input shape must be positive");
+  if (d->num_blocks < 1 || !d->blocks) return fail(DDG_ERR_INVALID_ARG, "module needs at least one block");
+  if (!(d->momentum >= 0.f && d->momentum < 1.f)) return fail(DDG_ERR_INVALID_ARG, "momentum must be in [0,1)");
+  if (!(d->weight_decay >= 0.f)) return fail(DDG_ERR_INVALID_ARG, "weight_decay must be >= 0");
+  if (!(d->bn_eps > 0.f)) return fail(DDG_ERR_INVALID_ARG, "bn_eps must be > 0");
+  int c = d->in_c, h = d->in_h, w = d->in_w;
+  for (int i = 0; i < d->num_blocks; ++i) {
+    const ddg_block_desc& b = d->blocks[i];
+    if (b.kind < DDG_BLOCK_STEM || b.kind > DDG_BLOCK_HEAD) return fail(DDG_ERR_INVALID_ARG, "block %d: unknown kind %d", i, b.kind);
+    if (b.cin != c) return fail(DDG_ERR_SHAPE, "block %d: cin=%d but the incoming tensor has %d channels", i, b.cin, c);
+    if (b.kind == DDG_BLOCK_HEAD) {
+      if (i != d->num_blocks - 1) return fail(DDG_ERR_SHAPE, "the head must be the last block");
+      if (d->num_classes < 2) return fail(DDG_ERR_SHAPE, "a head needs num_classes >= 2");
+      if (d->k != d->K) return fail(DDG_ERR_SHAPE, "only the last module (k == K) may end in the head");
+      if (d->num_blocks < 2) return fail(DDG_ERR_SHAPE, "a module cannot consist of the head alone");
+      continue;
+    }
+    if (b.stride != 1 && b.stride != 2) return fail(DDG_ERR_SHAPE, "block %d: stride must be 1 or 2", i);
+    if (!is_pow2(b.cout) || b.cout < 16) return fail(DDG_ERR_SHAPE, "block %d: cout=%d must be a power of two >= 16", i, b.cout);
+    if (b.kind == DDG_BLOCK_BOTTLENECK && (!is_pow2(b.cmid) || b.cmid < 16))
+      return fail(DDG_ERR_SHAPE, "block %d: cmid=%d must be a power of two >= 16", i, b.cmid);
+    if (b.kind != DDG_BLOCK_STEM) {
+      if (!is_pow2(b.cin) || b.cin < 16) return fail(DDG_ERR_SHAPE, "block %d: cin=%d must be a power of two >= 16", i, b.cin);
+      if ((b.stride != 1 || b.cin != b.cout) && !b.projection)
+        return fail(DDG_ERR_SHAPE, "block %d: stride/channel change needs a projection shortcut", i);
+    } else if (b.cin > 1024) {
+      return fail(DDG_ERR_SHAPE, "block %d: stem cin too large", i);
+    }
+    c = b.cout; h = out_dim(h, b.stride); w = out_dim(w, b.stride);
+  }
+  const bool has_head = d->blocks[d->num_blocks - 1].kind == DDG_BLOCK_HEAD;
+  if (has_head != (d->num_classes > 0)) return fail(DDG_ERR_SHAPE, "num_classes > 0 iff the last block is the head");
+  if ((size_t)d->batch * d->in_h * d->in_w * (size_t)(c > d->in_c ? c : d->in_c) > ((size_t)1 << 31) - 1)
+    return fail(DDG_ERR_SHAPE, "tensor too large for 32-bit pixel indexing");
+  return DDG_OK;
+}
+
+void add_unit(Blk& b, size_t& off, int ci, int co, int R, int st, int N, int H, int W) {
+  Unit u;
+  u.cin = ci; u.cout = co; u.R = R; u.stride = st; u.pad = (R == 3) ? 1 : 0;
+  u.N = N; u.H = H; u.W = W; u.P = out_dim(H, st); u.Q = out_dim(W, st);
+  u.ow = off; off += (size_t)co * ci * R * R;
+  u.og = off; off += co;
+  u.ob = off; off += co;
+  b.u.push_back(u);
+}
+
+ddg_status build_plan(ddg_module* m) {
+  const ddg_module_desc& d = m->d;
+  const int dt = d.compute;
+  m->esz = dtype_size(dt);
+  size_t off = 0;
+  int c = d.in_c, h = d.in_h, w = d.in_w;
+  const int N = d.batch;
+  m->in_elems = (size_t)N * h * w * c;
+  m->max_act = m->in_elems;
+  for (int i = 0; i < d.num_blocks; ++i) {
+    const ddg_block_desc& bd = m->blocks_desc[i];
+    Blk b;
+    b.kind = bd.kind;
+    b.proj = bd.projection != 0;
+    if (bd.kind == DDG_BLOCK_HEAD) {
+      b.C = c; b.HW = h * w;
+      b.ofcw = off; off += (size_t)d.num_classes * c;
+      b.ofcb = off; off += d.num_classes;
+      m->blocks.push_back(b);
+      continue;
+    }
+    if (bd.kind == DDG_BLOCK_STEM) {
+      add_unit(b, off, bd.cin, bd.cout, 3, bd.stride, N, h, w); b.nmain = 1;
+    } else if (bd.kind == DDG_BLOCK_BASIC) {
+      add_unit(b, off, bd.cin, bd.cout, 3, bd.stride, N, h, w);
+      add_unit(b, off, bd.cout, bd.cout, 3, 1, N, b.u[0].P, b.u[0].Q); b.nmain = 2;
+      if (b.proj) add_unit(b, off, bd.cin, bd.cout, 1, bd.stride, N, h, w);
+    } else {
+      add_unit(b, off, bd.cin, bd.cmid, 1, 1, N, h, w);
+      add_unit(b, off, bd.cmid, bd.cmid, 3, bd.stride, N, h, w);
+      add_unit(b, off, bd.cmid, bd.cout, 1, 1, N, b.u[1].P, b.u[1].Q); b.nmain = 3;
+      if (b.proj) add_unit(b, off, bd.cin, bd.cout, 1, bd.stride, N, h, w);
+    }
+    const bool first_block = (i == 0);
+    for (size_t ui = 0; ui < b.u.size(); ++ui) {
+      Unit& u = b.u[ui];
+      // the gradient w.r.t. the module input is needed unless this is module 1
+      const bool reads_module_input = first_block && (ui == 0 || (int)ui == b.nmain);
+      u.has_dgrad = !(reads_module_input && d.k == 1);
+      if (u.has_dgrad && (u.cin % 16 != 0))
+        return fail(DDG_ERR_SHAPE, "block %d: input gradient needs cin %% 16 == 0 (cin=%d)", i, u.cin);
+      if (u.out_elems() > m->max_act) m->max_act = u.out_elems();
+      if (u.in_elems() > m->max_act) m->max_act = u.in_elems();
+      // forward
+      ConvArgs& f = u.fprop;
+      f.N = N; f.IH = u.H; f.IW = u.W; f.IC = u.cin; f.OH = u.P; f.OW = u.Q; f.OC = u.cout;
+      f.R = u.R; f.stride = u.stride; f.pad = u.pad; f.ntaps = u.R * u.R;
+      f.M = N * u.P * u.Q; f.dgrad = 0; f.dtype = dt;
+      size_t ne = conv_wpack_elems(u.cin, u.cout, u.R, dt, &f.log2cp, &f.ksteps);
+      DDG_OKAY(dev_alloc(m, &u.wpack_f, ne * m->esz));
+      conv_plan(f);
+      size_t st_e = (size_t)f.grid_x * 2 * u.cout;
+      if (st_e > m->ws_stat_elems) m->ws_stat_elems = st_e;
+      // input gradient
+      if (u.has_dgrad) {
+        ConvArgs& g = u.dgrad;
+        g.N = N; g.IH = u.P; g.IW = u.Q; g.IC = u.cout; g.OH = u.H; g.OW = u.W; g.OC = u.cin;
+        g.R = u.R; g.stride = u.stride; g.pad = u.pad; g.ntaps = u.R * u.R;
+        g.M = N * u.H * u.W; g.dgrad = 1; g.dtype = dt;
+        ne = conv_wpack_elems(u.cout, u.cin, u.R, dt, &g.log2cp, &g.ksteps);
+        DDG_OKAY(dev_alloc(m, &u.wpack_d, ne * m->esz));
+        conv_plan(g);
+      }
+      // weight gradient
+      WgradArgs& wgd = u.wg;
+      wgd.N = N; wgd.H = u.H; wgd.W = u.W; wgd.Cin = u.cin; wgd.P = u.P; wgd.Q = u.Q; wgd.Cout = u.cout;
+      wgd.R = u.R; wgd.stride = u.stride; wgd.pad = u.pad; wgd.M = N * u.P * u.Q; wgd.dtype = dt;
+      wgrad_plan(wgd);
+      if (wgrad_partial_elems(wgd) > m->ws_wgrad_elems) m->ws_wgrad_elems = wgrad_partial_elems(wgd);
+      const int bg = bn_bwd_grid(u.out_elems(), u.cout, dt);
+      st_e = (size_t)bg * 2 * u.cout;
+      if (st_e > m->ws_stat_elems) m->ws_stat_elems = st_e;
+      // saved tensors and per-channel vectors
+      DDG_OKAY(dev_alloc(m, &u.z, u.out_elems() * m->esz));
+      void* pc = nullptr;
+      DDG_OKAY(dev_alloc(m, &pc, (size_t)7 * u.cout * sizeof(float)));
+      u.mean = (float*)pc; u.invstd = u.mean + u.cout; u.scale = u.invstd + u.cout;
+      u.shift = u.scale + u.cout; u.coef = u.shift + u.cout;
+    }
+    for (int ui = 0; ui + 1 < b.nmain; ++ui) {
+      void* a = nullptr;
+      DDG_OKAY(dev_alloc(m, &a, b.u[ui].out_elems() * m->esz));
+      b.act.push_back(a);
+    }
+    b.y_elems = b.u[b.nmain - 1].out_elems();
+    DDG_OKAY(dev_alloc(m, &b.y, b.y_elems * m->esz));
+    c = bd.cout; h = out_dim(h, bd.stride); w = out_dim(w, bd.stride);
+    m->blocks.push_back(b);
+  }
+  m->out_c = c; m->out_h = h; m->out_w = w;
+  m->out_elems = (size_t)N * h * w * c;
+  m->nparams = off;
+  if (d.num_classes > 0) {
+    Blk& hb = m->blocks.back();
+    void* p = nullptr;
+    DDG_OKAY(dev_alloc(m, &p, ((size_t)N * hb.C + (size_t)N * d.num_classes + N) * sizeof(float)));
+    hb.pooled = (float*)p; hb.dlogits = hb.pooled + (size_t)N * hb.C; hb.loss_n = hb.dlogits + (size_t)N * d.num_classes;
+  }
+  void* p = nullptr;
+  DDG_OKAY(dev_alloc(m, &p, 3 * m->nparams * sizeof(float)));
+  m->theta = (float*)p; m->vel = m->theta + m->nparams; m->grad = m->vel + m->nparams;
+  m->delay = d.K - d.k;
+  m->nslots = m->delay + 1;
+  m->ring.resize(m->nslots, nullptr);
+  for (int s = 0; s < m->nslots; ++s) DDG_OKAY(dev_alloc(m, &m->ring[s], m->in_elems * m->esz));
+  DDG_OKAY(dev_alloc(m, &m->Ga, m->max_act * m->esz));
+  DDG_OKAY(dev_alloc(m, &m->Gb, m->max_act * m->esz));
+  DDG_OKAY(dev_alloc(m, &m->D1, m->max_act * m->esz));
+  DDG_OKAY(dev_alloc(m, &m->D2, m->max_act * m->esz));
+  DDG_OKAY(dev_alloc(m, &m->D3, m->max_act * m->esz));
+  DDG_OKAY(dev_alloc(m, &p, m->ws_stat_elems * sizeof(float)));
+  m->ws_stat = (float*)p;
+  DDG_OKAY(dev_alloc(m, &p, m->ws_wgrad_elems * sizeof(float)));
+  m->ws_wgrad = (float*)p;
+  if (!d.dry_run) {
+    hipError_t e = hipMemsetAsync(m->theta, 0, 3 * m->nparams * sizeof(float), m->stream);
+    if (e != hipSuccess) return fail(DDG_ERR_DEVICE, "hipMemsetAsync: %s", hipGetErrorString(e));
+  }
+  return DDG_OK;
+}
+
+// ---- enqueue helpers ---------------------------------------------------------------------
+
+ddg_status pack_all(ddg_module* m) {
+  for (Blk& b : m->blocks)
+    for (Unit& u : b.u) {
+      { Launch L(m, PK_PACK);
+        DDG_TRY(pack_weights_launch(m->theta + u.ow, u.wpack_f, u.cout, u.cin, u.R, 0, m->d.compute, m->stream)); }
+      if (u.has_dgrad) {
+        Launch L(m, PK_PACK);
+        DDG_TRY(pack_weights_launch(m->theta + u.ow, u.wpack_d, u.cout, u.cin, u.R, 1, m->d.compute, m->stream));
+      }
+    }
+  return DDG_OK;
+}
+
+// conv + batch statistics of one unit: in -> u.z, u.mean/invstd/scale/shift
+ddg_status unit_forward(ddg_module* m, Unit& u, const void* in) {
+  ConvArgs a = u.fprop;
+  a.in = in; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = m->ws_stat; a.add_g = nullptr; a.add_mask = nullptr;
+  { Launch L(m, PK_CONV_FPROP); DDG_TRY(conv_launch(a, m->stream)); }
+  { Launch L(m, PK_BN_FINALIZE);
+    DDG_TRY(bn_finalize_launch(m->ws_stat, a.grid_x, u.cout, m->theta + u.og, m->theta + u.ob,
+                               (float)((size_t)u.N * u.P * u.Q), m->d.bn_eps, u.mean, u.invstd, u.scale,
+                               u.shift, m->stream)); }
+  return DDG_OK;
+}
+
+// Forward through all residual blocks. `final_out`, if given, receives the last block's
+// output instead of the module's own buffer (used when the tape is not needed).
+ddg_status run_forward(ddg_module* m, const void* in, void* final_out) {
+  const int dt = m->d.compute;
+  const void* x = in;
+  const int nres = (int)m->blocks.size() - (m->d.num_classes > 0 ? 1 : 0);
+  for (int bi = 0; bi < nres; ++bi) {
+    Blk& b = m->blocks[bi];
+    void* yout = (bi == nres - 1 && final_out) ? final_out : b.y;
+    const void* cur = x;
+    for (int i = 0; i < b.nmain; ++i) {
+      Unit& u = b.u[i];
+      DDG_OKAY(unit_forward(m, u, cur));
+      if (i + 1 < b.nmain) {
+        Launch L(m, PK_BN_APPLY);
+        DDG_TRY(bn_apply_launch(u.z, u.scale, u.shift, nullptr, nullptr, nullptr, b.act[i], u.out_elems(),
+                                u.cout, 1, dt, m->stream));
+        cur = b.act[i];
+      }
+    }
+    Unit& ul = b.u[b.nmain - 1];
+    if (b.kind == DDG_BLOCK_STEM) {
+      Launch L(m, PK_BN_APPLY);
+      DDG_TRY(bn_apply_launch(ul.z, ul.scale, ul.shift, nullptr, nullptr, nullptr, yout, ul.out_elems(), ul.cout, 1, dt, m->stream));
+    } else if (b.proj) {
+      Unit& up = b.u[b.nmain];
+      DDG_OKAY(unit_forward(m, up, x));
+      Launch L(m, PK_BN_APPLY);
+      DDG_TRY(bn_apply_launch(ul.z, ul.scale, ul.shift, up.z, up.scale, up.shift, yout, ul.out_elems(), ul.cout, 1, dt, m->stream));
+    } else {
+      Launch L(m, PK_BN_APPLY);
+      DDG_TRY(bn_apply_launch(ul.z, ul.scale, ul.shift, x, nullptr, nullptr, yout, ul.out_elems(), ul.cout, 1, dt, m->stream));
+    }
+    x = yout;
+  }
+  return DDG_OK;
+}
+
+// BN backward + weight gradient (+ input gradient) of one unit.
+//   dy/mask: gradient w.r.t. the BN output, masked where mask <= 0 (mask may be null)
+//   x_in: the unit's conv input; dx: where the input gradient goes (null: not needed)
+//   add_g/add_mask: optional term added to dx in the same kernel
+ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mask, const void* x_in,
+                         void* dz_buf, void* dx, const void* add_g, const void* add_mask) {
+  const int dt = m->d.compute;
+  const size_t E = u.out_elems();
+  const int rows = bn_bwd_grid(E, u.cout, dt);
+  { Launch L(m, PK_BN_BWD_REDUCE);
+    DDG_TRY(bn_bwd_reduce_launch(dy, mask, u.z, u.mean, u.invstd, m->ws_stat, E, u.cout, dt, m->stream)); }
+  { Launch L(m, PK_BN_BWD_FINALIZE);
+    DDG_TRY(bn_bwd_finalize_launch(m->ws_stat, rows, u.cout, m->theta + u.og, u.mean, u.invstd,
+                                   (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
+  { Launch L(m, PK_BN_BWD_APPLY);
+    DDG_TRY(bn_bwd_apply_launch(dy, mask, u.z, u.coef, dz_buf, E, u.cout, dt, m->stream)); }
+  WgradArgs w = u.wg;
+  w.x = x_in; w.dz = dz_buf; w.partial = m->ws_wgrad; w.dW = m->grad + u.ow;
+  { Launch L(m, PK_CONV_WGRAD); DDG_TRY(wgrad_launch(w, m->stream)); }
+  { Launch L(m, PK_WGRAD_REDUCE); DDG_TRY(wgrad_reduce_launch(w, m->stream)); }
+  if (dx) {
+    ConvArgs a = u.dgrad;
+    a.in = dz_buf; a.wpack = u.wpack_d; a.out = dx; a.stat_partial = nullptr; a.add_g = add_g; a.add_mask = add_mask;
+    Launch L(m, PK_CONV_DGRAD);
+    DDG_TRY(conv_launch(a, m->stream));
+  }
+  return DDG_OK;
+}
+
+// Backward through the tape. dtop: gradient at the module output (null with a head).
+ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const int32_t* labels,
+                        void* delta_out, float* loss_out) {
+  const int dt = m->d.compute;
+  const bool head = m->d.num_classes > 0;
+  const int nres = (int)m->blocks.size() - (head ? 1 : 0);
+  const void* dy = dtop;
+  if (head) {
+    Blk& hb = m->blocks.back();
+    HeadArgs a{};
+    a.h = m->blocks[nres - 1].y; a.fcw = m->theta + hb.ofcw; a.fcb = m->theta + hb.ofcb; a.labels = labels;
+    a.pooled = hb.pooled; a.dlogits = hb.dlogits; a.loss_n = hb.loss_n; a.loss_out = loss_out;
+    a.dfcw = m->grad + hb.ofcw; a.dfcb = m->grad + hb.ofcb; a.dh = m->Ga;
+    a.N = m->d.batch; a.HW = hb.HW; a.C = hb.C; a.classes = m->d.num_classes; a.dtype = dt;
+    Launch L(m, PK_HEAD);
+    DDG_TRY(head_launch(a, m->stream));
+    dy = m->Ga;
+  }
+  void* gnext = (dy == m->Ga) ? m->Gb : m->Ga;  // where this block's input gradient goes
+  for (int bi = nres - 1; bi >= 0; --bi) {
+    Blk& b = m->blocks[bi];
+    const void* x = (bi == 0) ? in : m->blocks[bi - 1].y;
+    const bool want_dx = (bi > 0) || (m->d.k > 1);
+    void* dx_dst = nullptr;
+    if (want_dx) dx_dst = (bi == 0) ? delta_out : gnext;
+    if (b.kind == DDG_BLOCK_STEM) {
+      DDG_OKAY(unit_backward(m, b.u[0], dy, b.y, x, m->D1, dx_dst, nullptr, nullptr));
+    } else {
+      // shortcut term of the input gradient
+      const void* add_g = nullptr; const void* add_mask = nullptr;
+      if (b.proj) {
+        Unit& up = b.u[b.nmain];
+        DDG_OKAY(unit_backward(m, up, dy, b.y, x, m->D1, want_dx ? m->D3 : nullptr, nullptr, nullptr));
+        if (want_dx) add_g = m->D3;
+      } else if (want_dx) {
+        add_g = dy; add_mask = b.y;
+      }
+      const void* d = dy; const void* mask = b.y;
+      for (int i = b.nmain - 1; i >= 0; --i) {
+        Unit& u = b.u[i];
+        const void* uin = (i == 0) ? x : b.act[i - 1];
+        void* udx = nullptr;
+        if (i > 0) udx = m->D2;
+        else udx = dx_dst;
+        DDG_OKAY(unit_backward(m, u, d, mask, uin, m->D1, udx, i == 0 ? add_g : nullptr, i == 0 ? add_mask : nullptr));
+        if (i > 0) { d = m->D2; mask = b.act[i - 1]; }
+      }
+    }
+    if (bi > 0) { dy = gnext; gnext = (gnext == m->Ga) ? m->Gb : m->Ga; }
+  }
+  return DDG_OK;
+}
+
+ddg_status check_handle(const ddg_module* m) {
+  if (!m) return fail(DDG_ERR_INVALID_ARG, "module handle is null");
+  if (m->sticky != DDG_OK) return fail(m->sticky, "module is in a failed state after an earlier device error");
+  return DDG_OK;
+}
+
+}  // namespace
+
+// ---- C boundary ------------------------------------------------------------------------------
+
+extern "C" {
+
+const char* ddg_last_error(void) { return g_err.c_str(); }
+const char* ddg_version(void) { return "ddg-mi355x 0.1 (gfx950)"; }
+
+ddg_status ddg_module_create(const ddg_module_desc* desc, ddg_module** out) {
+  if (!out) return fail(DDG_ERR_INVALID_ARG, "out is null");
+  *out = nullptr;
+  DDG_OKAY(validate(desc));
+  ddg_module* m = new ddg_module();
+  m->d = *desc;
+  m->blocks_desc.assign(desc->blocks, desc->blocks + desc->num_blocks);
+  m->d.blocks = m->blocks_desc.data();
+  m->stream = (hipStream_t)desc->stream;
+  ddg_status st = build_plan(m);
+  if (st != DDG_OK) {
+    for (void* p : m->allocs) (void)hipFree(p);
+    delete m;
+    return st;
+  }
+  *out = m;
+  return DDG_OK;
+}
+
+ddg_status ddg_module_destroy(ddg_module* m) {
+  if (!m) return DDG_OK;
+  if (!m->d.dry_run) {
+    (void)hipStreamSynchronize(m->stream);
+    for (auto& e : m->evs) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    for (void* p : m->allocs) (void)hipFree(p);
+  }
+  delete m;
+  return DDG_OK;
+}
+
+size_t ddg_param_count(const ddg_module* m) { return m ? m->nparams : 0; }
+size_t ddg_device_bytes(const ddg_module* m) { return m ? m->bytes : 0; }
+
+ddg_status ddg_out_shape(const ddg_module* m, int* c, int* h, int* w) {
+  if (!m) return fail(DDG_ERR_INVALID_ARG, "module handle is null");
+  if (c) *c = m->out_c;
+  if (h) *h = m->out_h;
+  if (w) *w = m->out_w;
+  return DDG_OK;
+}
+
+ddg_status ddg_set_params(ddg_module* m, const float* src, int is_device) {
+  DDG_OKAY(check_handle(m));
+  if (!src) return fail(DDG_ERR_INVALID_ARG, "src is null");
+  if (m->d.dry_run) return DDG_OK;
+  if (is_device) {
+    Launch L(m, PK_COPY);
+    DDG_TRY(copy_launch(src, m->theta, m->nparams * sizeof(float), m->stream));
+  } else {
+    DDG_TRY(hipStreamSynchronize(m->stream));
+    DDG_TRY(hipMemcpy(m->theta, src, m->nparams * sizeof(float), hipMemcpyHostToDevice));
+  }
+  m->tape_is_current = false;
+  return pack_all(m);
+}
+
+ddg_status ddg_set_velocity(ddg_module* m, const float* src, int is_device) {
+  DDG_OKAY(check_handle(m));
+  if (!src) return fail(DDG_ERR_INVALID_ARG, "src is null");
+  if (m->d.dry_run) return DDG_OK;
+  if (is_device) {
+    Launch L(m, PK_COPY);
+    DDG_TRY(copy_launch(src, m->vel, m->nparams * sizeof(float), m->stream));
+  } else {
+    DDG_TRY(hipStreamSynchronize(m->stream));
+    DDG_TRY(hipMemcpy(m->vel, src, m->nparams * sizeof(float), hipMemcpyHostToDevice));
+  }
+  return DDG_OK;
+}
+
+static ddg_status get_vec(ddg_module* m, const float* dev, float* host_dst) {
+  DDG_OKAY(check_handle(m));
+  if (!host_dst) return fail(DDG_ERR_INVALID_ARG, "host_dst is null");
+  if (m->d.dry_run) { memset(host_dst, 0, m->nparams * sizeof(float)); return DDG_OK; }
+  DDG_TRY(hipStreamSynchronize(m->stream));
+  DDG_TRY(hipMemcpy(host_dst, dev, m->nparams * sizeof(float), hipMemcpyDeviceToHost));
+  return DDG_OK;
+}
+ddg_status ddg_get_params(ddg_module* m, float* host_dst) { return get_vec(m, m ? m->theta : nullptr, host_dst); }
+ddg_status ddg_get_velocity(ddg_module* m, float* host_dst) { return get_vec(m, m ? m->vel : nullptr, host_dst); }
+ddg_status ddg_get_grad(ddg_module* m, float* host_dst, int* valid) {
+  DDG_OKAY(get_vec(m, m ? m->grad : nullptr, host_dst));
+  if (valid) *valid = m->has_grad ? 1 : 0;
+  return DDG_OK;
+}
+
+ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
+  DDG_OKAY(check_handle(m));
+  if (m->phase != 0) return fail(DDG_ERR_STATE, "ddg_forward(t=%ld) called while iteration %ld is unfinished (phase %d)", t, m->t_next, m->phase);
+  if (t != m->t_next) return fail(DDG_ERR_STATE, "ddg_forward expected t=%ld, got %ld", m->t_next, t);
+  if (!h_in) return fail(DDG_ERR_INVALID_ARG, "h_in is null");
+  const bool head = m->d.num_classes > 0;
+  if (!head && !h_out) return fail(DDG_ERR_INVALID_ARG, "h_out is null");
+  if (((uintptr_t)h_in & 15) || ((uintptr_t)h_out & 15)) return fail(DDG_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  m->phase = 1;
+  if (m->d.dry_run) return DDG_OK;
+  void* slot = m->ring[t % m->nslots];
+  { Launch L(m, PK_COPY); DDG_TRY(copy_launch(h_in, slot, m->in_elems * m->esz, m->stream)); }
+  // A module with delay > 0 re-forwards before its backward, so this pass need not keep a
+  // tape and writes straight to h_out; the last module keeps the tape for its own backward.
+  if (m->delay > 0) {
+    DDG_OKAY(run_forward(m, slot, h_out));
+    m->tape_is_current = false;
+  } else {
+    DDG_OKAY(run_forward(m, slot, nullptr));
+    m->tape_is_current = true;
+    if (h_out) {
+      Launch L(m, PK_COPY);
+      DDG_TRY(copy_launch(m->blocks[m->blocks.size() - (head ? 2 : 1)].y, h_out, m->out_elems * m->esz, m->stream));
+    }
+  }
+  return DDG_OK;
+}
+
+ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, const int32_t* labels,
+                                void* delta_out, float* loss_out, int* did_backward) {
+  DDG_OKAY(check_handle(m));
+  if (m->phase != 1 || t != m->t_next) return fail(DDG_ERR_STATE, "ddg_backward_delayed(t=%ld) must follow ddg_forward(t=%ld)", t, m->t_next);
+  const bool head = m->d.num_classes > 0;
+  const long s = t - m->d.K + m->d.k;
+  if (s >= 0) {
+    if (head && (!labels || delta_in)) return fail(DDG_ERR_INVALID_ARG, "the head module takes labels and no delta_in");
+    if (!head && !delta_in) return fail(DDG_ERR_INVALID_ARG, "delta_in is null");
+    if (m->d.k > 1 && !delta_out) return fail(DDG_ERR_INVALID_ARG, "delta_out is null (k > 1)");
+    if (((uintptr_t)delta_in & 15) || ((uintptr_t)delta_out & 15)) return fail(DDG_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  }
+  m->phase = 2;
+  m->has_grad = (s >= 0);
+  if (did_backward) *did_backward = m->has_grad ? 1 : 0;
+  if (s < 0 || m->d.dry_run) return DDG_OK;
+  void* slot = m->ring[s % m->nslots];
+  if (!m->tape_is_current) DDG_OKAY(run_forward(m, slot, nullptr));
+  m->tape_is_current = false;
+  return run_backward(m, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out);
+}
+
+ddg_status ddg_update(ddg_module* m, long t, float lr) {
+  DDG_OKAY(check_handle(m));
+  if (m->phase != 2 || t != m->t_next) return fail(DDG_ERR_STATE, "ddg_update(t=%ld) must follow ddg_backward_delayed(t=%ld)", t, m->t_next);
+  m->phase = 0;
+  m->t_next = t + 1;
+  if (!m->has_grad || m->d.dry_run) return DDG_OK;
+  { Launch L(m, PK_SGD);
+    DDG_TRY(sgd_launch(m->theta, m->vel, m->grad, m->nparams, lr, m->d.momentum, m->d.weight_decay, m->stream)); }
+  return pack_all(m);
+}
+
+ddg_status ddg_module_sync(ddg_module* m) {
+  DDG_OKAY(check_handle(m));
+  if (m->d.dry_run) return DDG_OK;
+  DDG_TRY(hipStreamSynchronize(m->stream));
+  return DDG_OK;
+}
+
+int ddg_profile_kinds(void) { return PK_COUNT; }
+const char* ddg_profile_kind_name(int kind) { return (kind >= 0 && kind < PK_COUNT) ? kProfNames[kind] : ""; }
+
+static ddg_status prof_collect(ddg_module* m) {
+  if (m->evs.empty()) return DDG_OK;
+  DDG_TRY(hipStreamSynchronize(m->stream));
+  for (auto& e : m->evs) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) { m->prof_n[e.kind] += 1; m->prof_ms[e.kind] += ms; }
+    (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b);
+  }
+  m->evs.clear();
+  return DDG_OK;
+}
+
+ddg_status ddg_profile_enable(ddg_module* m, int on) {
+  DDG_OKAY(check_handle(m));
+  if (m->d.dry_run) return DDG_OK;
+  DDG_OKAY(prof_collect(m));
+  m->prof = on != 0;
+  return DDG_OK;
+}
+
+ddg_status ddg_profile_read(ddg_module* m, int kind, long* launches, double* total_ms) {
+  DDG_OKAY(check_handle(m));
+  if (kind < 0 || kind >= PK_COUNT) return fail(DDG_ERR_INVALID_ARG, "kind out of range");
+  if (!m->d.dry_run) DDG_OKAY(prof_collect(m));
+  if (launches) *launches = m->prof_n[kind];
+  if (total_ms) *total_ms = m->prof_ms[kind];
+  return DDG_OK;
+}
+
+ddg_status ddg_profile_reset(ddg_module* m) {
+  DDG_OKAY(check_handle(m));
+  if (!m->d.dry_run) DDG_OKAY(prof_collect(m));
+  for (int i = 0; i < PK_COUNT; ++i) { m->prof_n[i] = 0; m->prof_ms[i] = 0; }
+  return DDG_OK;
+}
+
+}  // extern "C"

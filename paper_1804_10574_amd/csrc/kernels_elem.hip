@@ -1,0 +1,439 @@
+// Bandwidth-bound kernels: batch-norm finalise / apply / backward, the head
+// (global average pool, linear, softmax cross-entropy), momentum SGD, copies.
+//
+// Tensors are NHWC, so a thread that walks the tensor with a stride that is a
+// multiple of the channel count always sees the same channels: per-channel
+// coefficients live in registers and every access is a 16-byte vector.
+// Reductions write per-workgroup partial rows that a finalise kernel adds in a
+// fixed order in double precision (deterministic, no atomics).
+#include "ddg_device.h"
+#include "ddg_kernels.h"
+
+namespace ddg {
+
+// ---------------------------------------------------------------------------------
+// Finalise per-channel statistics. partial is [rows][2][C] (sum, sum of squares).
+// One workgroup per 16 channels; 16 row-slices per channel are combined in order.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restrict__ partial, int rows,
+                                                          int C, const float* __restrict__ gamma,
+                                                          const float* __restrict__ beta, float count,
+                                                          float eps, float* mean, float* invstd,
+                                                          float* scale, float* shift) {
+  __shared__ double r1[16][17], r2[16][17];
+  const int cl = threadIdx.x & 15, slice = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl;
+  double s1 = 0.0, s2 = 0.0;
+  if (c < C)
+    for (int r = slice; r < rows; r += 16) {
+      s1 += (double)partial[((size_t)r * 2 + 0) * C + c];
+      s2 += (double)partial[((size_t)r * 2 + 1) * C + c];
+    }
+  r1[slice][cl] = s1; r2[slice][cl] = s2;
+  __syncthreads();
+  if (slice == 0 && c < C) {
+    double t1 = 0.0, t2 = 0.0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { t1 += r1[i][cl]; t2 += r2[i][cl]; }
+    const double mu = t1 / (double)count;
+    double var = t2 / (double)count - mu * mu;
+    if (var < 0.0) var = 0.0;
+    const float is = (float)(1.0 / sqrt(var + (double)eps));
+    const float sc = gamma[c] * is;
+    mean[c] = (float)mu;
+    invstd[c] = is;
+    scale[c] = sc;
+    shift[c] = beta[c] - (float)mu * sc;
+  }
+}
+
+hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,
+                              const float* beta, float count, float eps, float* mean, float* invstd,
+                              float* scale, float* shift, hipStream_t s) {
+  hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 15) / 16), dim3(256), 0, s, partial, rows, C, gamma,
+                     beta, count, eps, mean, invstd, scale, shift);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// y = [relu](z*scale + shift + shortcut), shortcut = res*rscale+rshift, res, or nothing
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ z, const float* __restrict__ scale,
+                                                       const float* __restrict__ shift, const T* __restrict__ res,
+                                                       const float* __restrict__ rscale,
+                                                       const float* __restrict__ rshift, T* __restrict__ y,
+                                                       size_t nvec, int C, int relu) {
+  constexpr int V = Store<T>::VEC;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;  // host makes stride*V a multiple of C
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int c0 = (int)((i * V) % C);
+  float sc[V], sh[V], rs[V], rh[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    sc[j] = scale[c0 + j]; sh[j] = shift[c0 + j];
+    rs[j] = rscale ? rscale[c0 + j] : 1.f;
+    rh[j] = rshift ? rshift[c0 + j] : 0.f;
+  }
+  for (; i < nvec; i += stride) {
+    float v[V];
+    Store<T>::load_vec(z + i * V, v);
+#pragma unroll
+    for (int j = 0; j < V; ++j) v[j] = v[j] * sc[j] + sh[j];
+    if (res) {
+      float r[V];
+      Store<T>::load_vec(res + i * V, r);
+#pragma unroll
+      for (int j = 0; j < V; ++j) v[j] += r[j] * rs[j] + rh[j];
+    }
+    if (relu) {
+#pragma unroll
+      for (int j = 0; j < V; ++j) v[j] = v[j] > 0.f ? v[j] : 0.f;
+    }
+    Store<T>::store_vec(y + i * V, v);
+  }
+}
+
+// grid such that (grid*256*V) % C == 0 and the tensor is covered a few times over
+static int elem_grid(size_t nvec, int C, int V, int max_blocks) {
+  size_t blocks = (nvec + 255) / 256;
+  if (blocks > (size_t)max_blocks) blocks = max_blocks;
+  // 256*V elements per block; need blocks*256*V % C == 0
+  int per = 256 * V;
+  int need = 1;
+  while ((size_t)need * per % C != 0) ++need;  // C <= 256*V*need, small loop
+  blocks = ((blocks + need - 1) / need) * need;
+  return (int)blocks;
+}
+
+hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const void* res,
+                           const float* rscale, const float* rshift, void* y, size_t elems, int C,
+                           int relu, int dtype, hipStream_t s) {
+  if (dtype == BF16) {
+    const size_t nvec = elems / 8;
+    hipLaunchKernelGGL(bn_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, 2048)), dim3(256), 0, s,
+                       (const bf16_t*)z, scale, shift, (const bf16_t*)res, rscale, rshift, (bf16_t*)y, nvec, C, relu);
+  } else {
+    const size_t nvec = elems / 4;
+    hipLaunchKernelGGL(bn_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, 2048)), dim3(256), 0, s,
+                       (const float*)z, scale, shift, (const float*)res, rscale, rshift, (float*)y, nvec, C, relu);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// BN backward, pass 1: g = dy masked by (mask > 0); partial sums of g and g*xhat.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const T* __restrict__ dy, const T* __restrict__ mask,
+                                                            const T* __restrict__ z, const float* __restrict__ mean,
+                                                            const float* __restrict__ invstd,
+                                                            float* __restrict__ partial, size_t nvec, int C) {
+  constexpr int V = Store<T>::VEC;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int c0 = (int)((i * V) % C);
+  float mu[V], is[V], s1[V], s2[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) { mu[j] = mean[c0 + j]; is[j] = invstd[c0 + j]; s1[j] = 0.f; s2[j] = 0.f; }
+  for (; i < nvec; i += stride) {
+    float g[V], zz[V];
+    Store<T>::load_vec(dy + i * V, g);
+    Store<T>::load_vec(z + i * V, zz);
+    if (mask) {
+      float mk[V];
+      Store<T>::load_vec(mask + i * V, mk);
+#pragma unroll
+      for (int j = 0; j < V; ++j) g[j] = mk[j] > 0.f ? g[j] : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      s1[j] += g[j];
+      s2[j] += g[j] * ((zz[j] - mu[j]) * is[j]);
+    }
+  }
+  // threads with equal (threadIdx.x*V) % C hold the same channels; combine in thread order
+  __shared__ float red[2][256][V + 1];
+#pragma unroll
+  for (int j = 0; j < V; ++j) { red[0][threadIdx.x][j] = s1[j]; red[1][threadIdx.x][j] = s2[j]; }
+  __syncthreads();
+  const int per = C / V < 256 ? C / V : 256;  // distinct channel vectors among the block's threads
+  if ((int)threadIdx.x < per) {
+    float t1[V], t2[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) { t1[j] = 0.f; t2[j] = 0.f; }
+    for (int t = threadIdx.x; t < 256; t += per) {
+#pragma unroll
+      for (int j = 0; j < V; ++j) { t1[j] += red[0][t][j]; t2[j] += red[1][t][j]; }
+    }
+    // block b, thread t covers channels ((b*256+t)*V) % C
+    const int cb = (int)((((size_t)blockIdx.x * 256 + threadIdx.x) * V) % C);
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+      partial[((size_t)blockIdx.x * 2 + 0) * C + cb + j] = t1[j];
+      partial[((size_t)blockIdx.x * 2 + 1) * C + cb + j] = t2[j];
+    }
+  }
+}
+
+// When C > 256*V a block covers only part of the channels; the other entries of its
+// partial row must read as zero, so the row buffer is cleared by the finalise contract:
+// rows are written completely only if 256*V % C == 0 or C % (256*V) == 0 handled below.
+int bn_bwd_grid(size_t elems, int C, int dtype) {
+  const int V = dtype == BF16 ? 8 : 4;
+  return elem_grid(elems / V, C, V, 1024);
+}
+
+template <typename T>
+__global__ void zero_f32_kernel(float* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0.f;
+}
+
+hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const void* z, const float* mean,
+                                const float* invstd, float* partial, size_t elems, int C, int dtype,
+                                hipStream_t s) {
+  const int V = dtype == BF16 ? 8 : 4;
+  const int grid = bn_bwd_grid(elems, C, dtype);
+  if (C > 256 * V) {  // a block's row is only partly written: clear the rows first
+    const size_t n = (size_t)grid * 2 * C;
+    hipLaunchKernelGGL(zero_f32_kernel<float>, dim3(256), dim3(256), 0, s, partial, n);
+  }
+  if (dtype == BF16)
+    hipLaunchKernelGGL(bn_bwd_reduce_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)dy,
+                       (const bf16_t*)mask, (const bf16_t*)z, mean, invstd, partial, elems / 8, C);
+  else
+    hipLaunchKernelGGL(bn_bwd_reduce_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)dy,
+                       (const float*)mask, (const float*)z, mean, invstd, partial, elems / 4, C);
+  return hipGetLastError();
+}
+
+// dbeta = sum g, dgamma = sum g*xhat; dz = A*g + B*z + C0 with
+//   A = gamma*invstd, B = -gamma*invstd^2*dgamma/m, C0 = -gamma*invstd*dbeta/m - B*mean
+__global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ partial, int rows, int C,
+                                                              const float* __restrict__ gamma,
+                                                              const float* __restrict__ mean,
+                                                              const float* __restrict__ invstd, float count,
+                                                              float* dgamma, float* dbeta, float* coef) {
+  __shared__ double r1[16][17], r2[16][17];
+  const int cl = threadIdx.x & 15, slice = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl;
+  double s1 = 0.0, s2 = 0.0;
+  if (c < C)
+    for (int r = slice; r < rows; r += 16) {
+      s1 += (double)partial[((size_t)r * 2 + 0) * C + c];
+      s2 += (double)partial[((size_t)r * 2 + 1) * C + c];
+    }
+  r1[slice][cl] = s1; r2[slice][cl] = s2;
+  __syncthreads();
+  if (slice == 0 && c < C) {
+    double db = 0.0, dg = 0.0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { db += r1[i][cl]; dg += r2[i][cl]; }
+    dbeta[c] = (float)db;
+    dgamma[c] = (float)dg;
+    const double g = gamma[c], is = invstd[c], mu = mean[c], m = count;
+    const double A = g * is;
+    const double B = -g * is * is * dg / m;
+    const double C0 = -g * is * db / m - B * mu;
+    coef[c] = (float)A;
+    coef[C + c] = (float)B;
+    coef[2 * C + c] = (float)C0;
+  }
+}
+
+hipError_t bn_bwd_finalize_launch(const float* partial, int rows, int C, const float* gamma,
+                                  const float* mean, const float* invstd, float count, float* dgamma,
+                                  float* dbeta, float* coef, hipStream_t s) {
+  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 15) / 16), dim3(256), 0, s, partial, rows, C, gamma,
+                     mean, invstd, count, dgamma, dbeta, coef);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__ dy, const T* __restrict__ mask,
+                                                           const T* __restrict__ z, const float* __restrict__ coef,
+                                                           T* __restrict__ dz, size_t nvec, int C) {
+  constexpr int V = Store<T>::VEC;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int c0 = (int)((i * V) % C);
+  float A[V], B[V], C0[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) { A[j] = coef[c0 + j]; B[j] = coef[C + c0 + j]; C0[j] = coef[2 * C + c0 + j]; }
+  for (; i < nvec; i += stride) {
+    float g[V], zz[V];
+    Store<T>::load_vec(dy + i * V, g);
+    Store<T>::load_vec(z + i * V, zz);
+    if (mask) {
+      float mk[V];
+      Store<T>::load_vec(mask + i * V, mk);
+#pragma unroll
+      for (int j = 0; j < V; ++j) g[j] = mk[j] > 0.f ? g[j] : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) g[j] = A[j] * g[j] + (B[j] * zz[j] + C0[j]);
+    Store<T>::store_vec(dz + i * V, g);
+  }
+}
+
+hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const void* z, const float* coef,
+                               void* dz, size_t elems, int C, int dtype, hipStream_t s) {
+  if (dtype == BF16) {
+    const size_t nvec = elems / 8;
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, 2048)), dim3(256), 0, s,
+                       (const bf16_t*)dy, (const bf16_t*)mask, (const bf16_t*)z, coef, (bf16_t*)dz, nvec, C);
+  } else {
+    const size_t nvec = elems / 4;
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, 2048)), dim3(256), 0, s,
+                       (const float*)dy, (const float*)mask, (const float*)z, coef, (float*)dz, nvec, C);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Head. Small: N x C x classes is a few hundred thousand operations.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void head_pool_kernel(const T* __restrict__ h, float* __restrict__ pooled, int HW, int C) {
+  const int n = blockIdx.x;
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    float s = 0.f;
+    for (int i = 0; i < HW; ++i) s += Store<T>::load1(h + ((size_t)n * HW + i) * C + c);
+    pooled[(size_t)n * C + c] = s / (float)HW;
+  }
+}
+
+// one workgroup per sample: logits, stable softmax, per-sample loss, dlogits = (p - onehot)/N
+__global__ void head_loss_kernel(const float* __restrict__ pooled, const float* __restrict__ fcw,
+                                 const float* __restrict__ fcb, const int32_t* __restrict__ labels,
+                                 float* __restrict__ dlogits, float* __restrict__ loss_n, int N, int C,
+                                 int classes) {
+  extern __shared__ float lg[];  // classes floats
+  const int n = blockIdx.x;
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
+    float a = fcb[j];
+    for (int c = 0; c < C; ++c) a += fcw[(size_t)j * C + c] * pooled[(size_t)n * C + c];
+    lg[j] = a;
+  }
+  __syncthreads();
+  float mx = lg[0];
+  for (int j = 1; j < classes; ++j) mx = lg[j] > mx ? lg[j] : mx;
+  float den = 0.f;
+  for (int j = 0; j < classes; ++j) den += expf(lg[j] - mx);
+  const int y = labels[n];
+  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
+    const float p = expf(lg[j] - mx) / den;
+    dlogits[(size_t)n * classes + j] = (p - (j == y ? 1.f : 0.f)) / (float)N;
+  }
+  if (threadIdx.x == 0) loss_n[n] = -(lg[y] - mx - logf(den));
+}
+
+// one workgroup per class: dfcw[j][:], dfcb[j]; workgroup 0 also writes the mean loss
+__global__ void head_wgrad_kernel(const float* __restrict__ pooled, const float* __restrict__ dlogits,
+                                  const float* __restrict__ loss_n, float* __restrict__ dfcw,
+                                  float* __restrict__ dfcb, float* loss_out, int N, int C, int classes) {
+  const int j = blockIdx.x;
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    float s = 0.f;
+    for (int n = 0; n < N; ++n) s += dlogits[(size_t)n * classes + j] * pooled[(size_t)n * C + c];
+    dfcw[(size_t)j * C + c] = s;
+  }
+  if (threadIdx.x == 0) {
+    float s = 0.f;
+    for (int n = 0; n < N; ++n) s += dlogits[(size_t)n * classes + j];
+    dfcb[j] = s;
+    if (j == 0 && loss_out) {
+      float l = 0.f;
+      for (int n = 0; n < N; ++n) l += loss_n[n];
+      *loss_out = l / (float)N;
+    }
+  }
+}
+
+template <typename T>
+__global__ void head_dh_kernel(const float* __restrict__ dlogits, const float* __restrict__ fcw,
+                               T* __restrict__ dh, int HW, int C, int classes) {
+  const int n = blockIdx.x;
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    float s = 0.f;
+    for (int j = 0; j < classes; ++j) s += dlogits[(size_t)n * classes + j] * fcw[(size_t)j * C + c];
+    s /= (float)HW;
+    for (int i = 0; i < HW; ++i) Store<T>::store1(dh + ((size_t)n * HW + i) * C + c, s);
+  }
+}
+
+hipError_t head_launch(const HeadArgs& a, hipStream_t s) {
+  const int tc = a.C < 64 ? 64 : (a.C > 256 ? 256 : a.C);
+  if (a.dtype == BF16)
+    hipLaunchKernelGGL(head_pool_kernel<bf16_t>, dim3(a.N), dim3(tc), 0, s, (const bf16_t*)a.h, a.pooled, a.HW, a.C);
+  else
+    hipLaunchKernelGGL(head_pool_kernel<float>, dim3(a.N), dim3(tc), 0, s, (const float*)a.h, a.pooled, a.HW, a.C);
+  hipLaunchKernelGGL(head_loss_kernel, dim3(a.N), dim3(128), a.classes * sizeof(float), s, a.pooled, a.fcw,
+                     a.fcb, a.labels, a.dlogits, a.loss_n, a.N, a.C, a.classes);
+  hipLaunchKernelGGL(head_wgrad_kernel, dim3(a.classes), dim3(tc), 0, s, a.pooled, a.dlogits, a.loss_n, a.dfcw,
+                     a.dfcb, a.loss_out, a.N, a.C, a.classes);
+  if (a.dh) {
+    if (a.dtype == BF16)
+      hipLaunchKernelGGL(head_dh_kernel<bf16_t>, dim3(a.N), dim3(tc), 0, s, a.dlogits, a.fcw, (bf16_t*)a.dh, a.HW, a.C, a.classes);
+    else
+      hipLaunchKernelGGL(head_dh_kernel<float>, dim3(a.N), dim3(tc), 0, s, a.dlogits, a.fcw, (float*)a.dh, a.HW, a.C, a.classes);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Momentum SGD over the module's flat parameter vector.
+// ---------------------------------------------------------------------------------
+__global__ void sgd_kernel(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g, size_t n,
+                           float lr, float mu, float wd) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    const float wi = w[i];
+    const float vi = mu * v[i] + (g[i] + wd * wi);
+    v[i] = vi;
+    w[i] = wi - lr * vi;
+  }
+}
+
+hipError_t sgd_launch(float* w, float* v, const float* g, size_t n, float lr, float mu, float wd, hipStream_t s) {
+  int grid = (int)((n + 255) / 256);
+  if (grid > 2048) grid = 2048;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(sgd_kernel, dim3(grid), dim3(256), 0, s, w, v, g, n, lr, mu, wd);
+  return hipGetLastError();
+}
+
+__global__ void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t nvec,
+                            const unsigned char* __restrict__ srcb, unsigned char* __restrict__ dstb, size_t tail0,
+                            size_t bytes) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+  if (blockIdx.x == 0)
+    for (size_t b = tail0 + threadIdx.x; b < bytes; b += blockDim.x) dstb[b] = srcb[b];
+}
+
+hipError_t copy_launch(const void* src, void* dst, size_t bytes, hipStream_t s) {
+  const size_t nvec = bytes / 16;
+  int grid = (int)((nvec + 255) / 256);
+  if (grid > 2048) grid = 2048;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, nvec,
+                     (const unsigned char*)src, (unsigned char*)dst, nvec * 16, bytes);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void to_f32_kernel(const T* __restrict__ src, float* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = Store<T>::load1(src + i);
+}
+
+hipError_t to_f32_launch(const void* src, float* dst, size_t elems, int dtype, hipStream_t s) {
+  int grid = (int)((elems + 255) / 256);
+  if (grid > 2048) grid = 2048;
+  if (grid < 1) grid = 1;
+  if (dtype == BF16) hipLaunchKernelGGL(to_f32_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)src, dst, elems);
+  else hipLaunchKernelGGL(to_f32_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)src, dst, elems);
+  return hipGetLastError();
+}
+
+}  // namespace ddg

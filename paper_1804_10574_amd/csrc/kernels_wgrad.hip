@@ -1,0 +1,140 @@
+// Weight-gradient convolution: dW[co][tap][ci] = sum over pixels m of dz[m][co] * x[pix(m,tap)][ci].
+//
+// The contraction runs over pixels, which are the slow index of both NHWC operands, so
+// this version feeds the fp32 matrix-core atom (one element per lane, no transposition
+// needed): rows = output channels, columns = (tap, input channel), k = 4 pixels per
+// instruction. bf16 tensors are widened on load; products of bf16 values are exact in fp32.
+// Work is split over pixel ranges; each workgroup writes one partial tile and a second
+// kernel adds the partials in a fixed order (no atomics: results are reproducible).
+#include "ddg_device.h"
+#include "ddg_kernels.h"
+
+namespace ddg {
+
+constexpr int WG_NJ = 9;  // column blocks (16 wide) per wave
+
+template <typename T>
+__global__ __launch_bounds__(256) void wgrad_mfma_kernel(WgradArgs a) {
+  using S_ = Store<T>;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, lg = lane >> 4;
+  const int cob = blockIdx.y;
+  const int jb0 = blockIdx.z * WG_NJ;
+  const T* __restrict__ x = reinterpret_cast<const T*>(a.x);
+  const T* __restrict__ dz = reinterpret_cast<const T*>(a.dz);
+  const int cpmask = (1 << a.log2cp) - 1;
+  const int ntaps = a.R * a.R;
+
+  // per-lane column descriptors: column j -> (tap, ci)
+  int jr[WG_NJ], js[WG_NJ], jc[WG_NJ];
+  bool jv[WG_NJ];
+#pragma unroll
+  for (int b = 0; b < WG_NJ; ++b) {
+    const int j = (jb0 + b) * 16 + l16;
+    const int tap = j >> a.log2cp;
+    jc[b] = j & cpmask;
+    jr[b] = tap / a.R - a.pad;
+    js[b] = tap % a.R - a.pad;
+    jv[b] = (jb0 + b) < a.JB && tap < ntaps && jc[b] < a.Cin;
+  }
+  f32x4_t acc[WG_NJ];
+#pragma unroll
+  for (int b = 0; b < WG_NJ; ++b) acc[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int pq = a.P * a.Q;
+  long m0 = ((long)blockIdx.x * 4 + wave) * (long)a.steps * 4;
+  for (int st = 0; st < a.steps; ++st) {
+    const long m = m0 + (long)st * 4 + lg;
+    const bool mv = m < a.M;
+    const int mm = mv ? (int)m : 0;
+    const int n = mm / pq;
+    const int rem = mm - n * pq;
+    const int p = rem / a.Q;
+    const int q = rem - p * a.Q;
+    const float dv = mv ? S_::load1(dz + (size_t)mm * a.Cout + cob * 16 + l16) : 0.f;
+    const int ihb = p * a.stride, iwb = q * a.stride;
+#pragma unroll
+    for (int b = 0; b < WG_NJ; ++b) {
+      const int ih = ihb + jr[b], iw = iwb + js[b];
+      const bool ok = mv && jv[b] && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+      const float xv = ok ? S_::load1(x + ((size_t)(n * a.H + ih) * a.W + iw) * a.Cin + jc[b]) : 0.f;
+      acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, xv, acc[b], 0, 0, 0);
+    }
+  }
+
+  // sum the four waves in a fixed order, then write the partial tile
+  __shared__ float red[4][WG_NJ][16][17];
+#pragma unroll
+  for (int b = 0; b < WG_NJ; ++b)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) red[wave][b][lg * 4 + i][l16] = acc[b][i];
+  __syncthreads();
+  const int Jp = a.JB * 16;
+  for (int e = threadIdx.x; e < WG_NJ * 256; e += 256) {
+    const int b = e >> 8, row = (e >> 4) & 15, col = e & 15;
+    if (jb0 + b >= a.JB) continue;
+    const float t = ((red[0][b][row][col] + red[1][b][row][col]) + red[2][b][row][col]) + red[3][b][row][col];
+    a.partial[((size_t)blockIdx.x * a.Cout + cob * 16 + row) * Jp + (jb0 + b) * 16 + col] = t;
+  }
+}
+
+// dW[co][ci][r][s] = sum over splits (in order) of partial[split][co][tap*CP + ci]
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs a) {
+  const int Jp = a.JB * 16;
+  const int total = a.Cout * Jp;
+  // 16 threads share one output: each sums a strided subset, then a fixed-order tree
+  __shared__ float red[16][17];
+  const int sub = threadIdx.x & 15, loc = threadIdx.x >> 4;
+  const int e = blockIdx.x * 16 + loc;
+  float s = 0.f;
+  if (e < total)
+    for (int sp = sub; sp < a.msplit; sp += 16) s += a.partial[(size_t)sp * total + e];
+  red[loc][sub] = s;
+  __syncthreads();
+  if (sub == 0 && e < total) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += red[loc][i];
+    const int co = e / Jp, j = e - co * Jp;
+    const int tap = j >> a.log2cp, ci = j & ((1 << a.log2cp) - 1);
+    if (tap < a.R * a.R && ci < a.Cin) {
+      const int r = tap / a.R, sx = tap % a.R;
+      a.dW[(((size_t)co * a.Cin + ci) * a.R + r) * a.R + sx] = t;
+    }
+  }
+}
+
+void wgrad_plan(WgradArgs& a) {
+  int l2 = 0;
+  while ((1 << l2) < a.Cin) ++l2;
+  a.log2cp = l2;
+  a.J = a.R * a.R * (1 << l2);
+  a.JB = (a.J + 15) / 16;
+  a.jgroups = (a.JB + WG_NJ - 1) / WG_NJ;
+  const int tiles = (a.Cout / 16) * a.jgroups;
+  int want = 1024 / tiles;               // workgroups over the pixel range
+  if (want < 1) want = 1;
+  const long quads = ((long)a.M + 3) / 4;  // 4-pixel steps in total
+  long steps = (quads + (long)want * 4 - 1) / ((long)want * 4);
+  if (steps < 8) steps = 8;
+  a.steps = (int)steps;
+  a.msplit = (int)((quads + steps * 4 - 1) / (steps * 4));
+  if (a.msplit < 1) a.msplit = 1;
+}
+
+size_t wgrad_partial_elems(const WgradArgs& a) { return (size_t)a.msplit * a.Cout * a.JB * 16; }
+
+hipError_t wgrad_launch(const WgradArgs& a, hipStream_t s) {
+  dim3 grid(a.msplit, a.Cout / 16, a.jgroups), block(256);
+  if (a.dtype == BF16) hipLaunchKernelGGL(wgrad_mfma_kernel<bf16_t>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(wgrad_mfma_kernel<float>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t wgrad_reduce_launch(const WgradArgs& a, hipStream_t s) {
+  const int total = a.Cout * a.JB * 16;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((total + 15) / 16), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace ddg

@@ -1,0 +1,125 @@
+"""Host-only checks of the C boundary: the library loads, exports every symbol that
+include/ddg.h declares, and rejects bad arguments / call orders before any device work
+(dry_run modules allocate nothing and launch nothing)."""
+import os
+import re
+
+import pytest
+
+import workloads as wk
+import paper_1804_10574_amd as ddg
+from paper_1804_10574_amd.ddg import make_desc, EXPORTS
+from tests.gpu_harness import descs_for
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    src = open(os.path.join(ROOT, "include", "ddg.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ddg_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ddg.load_library()
+    names = declared_symbols()
+    assert len(names) >= 25
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(EXPORTS) == names
+    assert "gfx950" in ddg.version()
+
+
+def test_dry_run_state_machine():
+    wl = wk.get_workload("tiny_k2")
+    d = descs_for(wl, dry_run=True)
+    m = ddg.Module(d[0])   # k=1 of K=2: delay 1
+    assert m.param_count() == wk.module_param_count(wl.modules[0])
+    assert m.out_shape() == (16, 8, 8)
+    fake = 4096  # never dereferenced in dry_run
+    with pytest.raises(ddg.DDGError) as e:
+        m.backward_delayed(0, delta_in=fake)
+    assert e.value.status == 3
+    with pytest.raises(ddg.DDGError) as e:
+        m.forward(1, fake, fake)           # must start at t = 0
+    assert e.value.status == 3
+    m.forward(0, fake, fake)
+    with pytest.raises(ddg.DDGError):
+        m.forward(1, fake, fake)           # backward(0) missing
+    with pytest.raises(ddg.DDGError):
+        m.update(0, 0.1)
+    assert m.backward_delayed(0, delta_in=fake) is False   # s = -1: warm-up
+    m.update(0, 0.1)
+    m.forward(1, fake, fake)
+    with pytest.raises(ddg.DDGError) as e:
+        m.backward_delayed(1, delta_in=None)               # s = 0 needs delta_in
+    assert e.value.status == 1
+    assert m.backward_delayed(1, delta_in=fake) is True
+    m.update(1, 0.1)
+    with pytest.raises(ddg.DDGError) as e:
+        m.forward(2, 4097, fake)                           # misaligned
+    assert e.value.status == 1
+
+
+def test_head_module_argument_rules():
+    wl = wk.get_workload("tiny_k2")
+    d = descs_for(wl, dry_run=True)
+    m = ddg.Module(d[1])
+    fake = 4096
+    m.forward(0, fake, None)
+    with pytest.raises(ddg.DDGError):
+        m.backward_delayed(0, delta_in=fake, labels=fake, delta_out=fake)
+    with pytest.raises(ddg.DDGError):
+        m.backward_delayed(0, labels=None, delta_out=fake)
+    with pytest.raises(ddg.DDGError):
+        m.backward_delayed(0, labels=fake, delta_out=None)   # k > 1 needs delta_out
+    assert m.backward_delayed(0, labels=fake, delta_out=fake) is True
+
+
+@pytest.mark.parametrize("mutate,status", [
+    (dict(K=0), 1), (dict(k=3), 1), (dict(compute=7), 1), (dict(batch=0), 2),
+    (dict(momentum=1.5), 1), (dict(bn_eps=0.0), 1),
+])
+def test_create_rejects_bad_descriptors(mutate, status):
+    wl = wk.get_workload("tiny_k2")
+    m0 = wl.modules[0]
+    args = dict(K=2, k=1, batch=4, in_chw=(m0.in_c, m0.in_h, m0.in_w),
+                blocks=[b.as_tuple() for b in m0.blocks], num_classes=0, compute=0, momentum=0.9,
+                weight_decay=0.0, bn_eps=1e-5, dry_run=True)
+    args.update(mutate)
+    with pytest.raises(ddg.DDGError) as e:
+        ddg.Module(make_desc(**args))
+    assert e.value.status == status
+
+
+def test_create_rejects_bad_block_lists():
+    S, B, H = wk.BLOCK_STEM, wk.BLOCK_BASIC, wk.BLOCK_HEAD
+    def mk(blocks, k=1, K=2, classes=0, in_c=3):
+        return make_desc(K, k, 4, (in_c, 8, 8), blocks, classes, 0, 0.9, 0.0, 1e-5, dry_run=True)
+    for blocks, kw in [
+        ([(S, 3, 0, 16, 1, 0), (B, 32, 0, 32, 1, 0)], {}),              # channel mismatch
+        ([(S, 3, 0, 16, 1, 0), (B, 16, 0, 32, 2, 0)], {}),              # needs projection
+        ([(S, 3, 0, 24, 1, 0)], {}),                                    # cout not a power of two
+        ([(S, 3, 0, 16, 3, 0)], {}),                                    # stride 3
+        ([(S, 3, 0, 16, 1, 0), (H, 16, 0, 10, 1, 0)], dict(classes=10)),  # head but k != K
+        ([(H, 16, 0, 10, 1, 0)], dict(k=2, classes=10, in_c=16)),       # head alone
+        ([(S, 3, 0, 16, 1, 0)], dict(classes=10)),                      # classes without head
+    ]:
+        with pytest.raises(ddg.DDGError) as e:
+            ddg.Module(mk(blocks, **kw))
+        assert e.value.status == 2, (blocks, str(e.value))
+
+
+def test_dry_run_pipeline_schedule():
+    wl = wk.get_workload("resnet110_k4")
+    p = ddg.Pipeline(descs_for(wl, dry_run=True))
+    fake = 4096
+    for t in range(6):
+        p.step(fake, fake, 0.01)
+        for k in range(1, 4):
+            _, it = p.get_delta(k)
+            # module k+1 wrote, during iteration t, the gradient of iteration t-K+k+1
+            s = t - 4 + k + 1
+            assert it == (s if s >= 0 else -1), (t, k, it)
+    for k in range(1, 5):
+        assert p.module(k).param_count() == wk.module_param_count(wl.modules[k - 1], wl.num_classes)

@@ -28,6 +28,7 @@ def tiny(K_cuts=(2,), batch=4, hw=8, classes=10):
 
 
 def make_net(wl, perturb_bn=True, **kw):
+    kw.setdefault("store_bf16", False)
     net = orc.OracleNet.from_workload(wl, **kw)
     for m in wl.modules:
         net.set_params(m.k, wk.init_module_params(wl, m, perturb_bn=perturb_bn))
@@ -272,3 +273,47 @@ def test_module_calls_compose_into_the_driver():
         assert la == lb
     for k in a.ks():
         assert np.array_equal(a.get_params(k), b.get_params(k))
+
+
+# ---- storage-precision mode (bf16 operands / stored tensors, arithmetic unchanged) ----------
+
+def test_bf16_rounding_matches_torch():
+    rng = np.random.default_rng(5)
+    v = np.concatenate([rng.standard_normal(4096) * 10.0 ** rng.integers(-6, 6, 4096),
+                        [0.0, -0.0, 1.0, 1.00390625, 1.005859375, 1.001953125, 3.0e38, 1e-40]])
+    got = orc.round_bf16(v)
+    ref = torch.tensor(v, dtype=torch.float64).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, ref)
+    assert np.array_equal(orc.round_bf16(got), got)          # idempotent
+    # ties go to the even significand: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert orc.round_bf16(np.array([1.00390625]))[0] == 1.0
+    assert orc.round_bf16(np.array([1.01171875]))[0] == 1.015625
+
+
+def test_bf16_storage_mode_keeps_invariants_and_stays_close():
+    wl = tiny()
+    plain = make_net(wl)
+    rounded = make_net(wl, store_bf16=True)
+    for t in range(3):
+        x, y = wk.minibatch(wl, t)
+        x = orc.round_bf16(x).reshape(x.shape)
+        lp = plain.ddg_step(x, y, 0.05)
+        lr_ = rounded.ddg_step(x, y, 0.05)
+        assert abs(lp - lr_) < 2e-2 * abs(lp)
+    for k in plain.ks():
+        a, b = plain.get_params(k), rounded.get_params(k)
+        assert 0 < np.linalg.norm(a - b) < 2e-2 * np.linalg.norm(a)
+        # master weights are never rounded
+        assert not np.array_equal(b, orc.round_bf16(b))
+    # the forward output of a rounded module is representable in bf16
+    h = rounded.get_h(1)
+    assert np.array_equal(h, orc.round_bf16(h).reshape(h.shape))
+    # K=1 == BP also holds with rounding (same code path, same rounding points)
+    wl1 = tiny(K_cuts=())
+    ddg1 = make_net(wl1, store_bf16=True)
+    bp = make_net(wl, store_bf16=True)
+    ddg1.set_params(1, np.concatenate(all_params(bp)))
+    for t in range(3):
+        x, y = wk.minibatch(wl, t)
+        assert ddg1.ddg_step(x, y, 0.1) == bp.bp_step(x, y, 0.1)
+    assert np.array_equal(ddg1.get_params(1), np.concatenate(all_params(bp)))
