@@ -614,6 +614,7 @@ template <class T>
 T bp_step(Net<T>& net, const T* x, const int* labels, T lr, int do_update) {
   const int K = net.K;
   std::vector<T> h(x, x + net.mod(1).in_size());
+  round_store(h, net.store_bf16 != 0);  // the network input is a stored tensor too
   for (int k = 1; k <= K; ++k) {
     auto& m = net.mod(k);
     m.h_out = module_forward(m, m.theta.data(), h, net.eps, net.store_bf16 != 0);
