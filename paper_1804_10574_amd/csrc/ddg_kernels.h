@@ -56,6 +56,13 @@ size_t wgrad_partial_elems(const WgradArgs& a);
 hipError_t wgrad_launch(const WgradArgs& a, hipStream_t s);
 hipError_t wgrad_reduce_launch(const WgradArgs& a, hipStream_t s);
 
+// LDS-tiled bf16 weight gradient for 3x3/stride-1 layers with 16/32/64 channels. Returns 0 rows
+// when the shape is not covered. x may be the saved conv output the activation derives from:
+// then scale/shift give relu(x*scale+shift) on the fly (nullptr: use x as stored).
+int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
+hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* shift, const void* dz,
+                              float* partial, int N, int H, int W, int C, int rows, hipStream_t s);
+
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
 // shift=beta-mean*scale.
 hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,

@@ -49,6 +49,7 @@ struct Unit {  // convolution + batch normalisation
   ConvArgs fprop{}, dgrad{};
   WgradArgs wg{};
   bool has_dgrad = false;
+  int wg_tiled_rows = 0;   // > 0: the LDS-tiled bf16 weight-gradient kernel covers this layer
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
   size_t in_elems() const { return (size_t)N * H * W * cin; }
 };
@@ -270,6 +271,8 @@ ddg_status build_plan(ddg_module* m) {
       wgd.N = N; wgd.H = u.H; wgd.W = u.W; wgd.Cin = u.cin; wgd.P = u.P; wgd.Q = u.Q; wgd.Cout = u.cout;
       wgd.R = u.R; wgd.stride = u.stride; wgd.pad = u.pad; wgd.M = N * u.P * u.Q; wgd.dtype = dt;
       wgrad_plan(wgd);
+      u.wg_tiled_rows = wgrad_tiled_rows(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
+      if (u.wg_tiled_rows > 0) wgd.msplit = u.wg_tiled_rows;  // the reduce kernel sums this many rows
       if (wgrad_partial_elems(wgd) > m->ws_wgrad_elems) m->ws_wgrad_elems = wgrad_partial_elems(wgd);
       const int bg = bn_bwd_grid(u.out_elems(), u.cout, dt);
       st_e = (size_t)bg * 2 * u.cout;
@@ -406,7 +409,13 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     DDG_TRY(bn_bwd_apply_launch(dy, mask, u.z, u.coef, dz_buf, E, u.cout, dt, m->stream)); }
   WgradArgs w = u.wg;
   w.x = x_in; w.dz = dz_buf; w.partial = m->ws_wgrad; w.dW = m->grad + u.ow;
-  { Launch L(m, PK_CONV_WGRAD); DDG_TRY(wgrad_launch(w, m->stream)); }
+  if (u.wg_tiled_rows > 0) {
+    Launch L(m, PK_CONV_WGRAD);
+    DDG_TRY(wgrad_tiled_launch(x_in, nullptr, nullptr, dz_buf, m->ws_wgrad, u.N, u.H, u.W, u.cin, u.wg_tiled_rows, m->stream));
+  } else {
+    Launch L(m, PK_CONV_WGRAD);
+    DDG_TRY(wgrad_launch(w, m->stream));
+  }
   { Launch L(m, PK_WGRAD_REDUCE); DDG_TRY(wgrad_reduce_launch(w, m->stream)); }
   if (dx) {
     ConvArgs a = u.dgrad;

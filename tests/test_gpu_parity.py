@@ -168,11 +168,17 @@ def test_resnet20_full_batch_smooth_quantities(H):
     assert not report, "\n".join(report)
 
 
+# name -> (blocks, batch, height = width)
 SINGLE_BLOCKS = {
-    "basic_identity": [(wk.BLOCK_BASIC, 32, 0, 32, 1, 0)],
-    "basic_projection_s2": [(wk.BLOCK_BASIC, 16, 0, 32, 2, 1)],
-    "bottleneck": [(wk.BLOCK_BOTTLENECK, 64, 16, 64, 1, 0)],
-    "bottleneck_projection_s2": [(wk.BLOCK_BOTTLENECK, 32, 16, 64, 2, 1)],
+    "basic_identity": ([(wk.BLOCK_BASIC, 32, 0, 32, 1, 0)], 6, 9),
+    "basic_projection_s2": ([(wk.BLOCK_BASIC, 16, 0, 32, 2, 1)], 6, 9),
+    "bottleneck": ([(wk.BLOCK_BOTTLENECK, 64, 16, 64, 1, 0)], 6, 9),
+    "bottleneck_projection_s2": ([(wk.BLOCK_BOTTLENECK, 32, 16, 64, 2, 1)], 6, 9),
+    # the CIFAR layer shapes (LDS-tiled kernels), with more tiles than workgroups
+    "cifar_c16_w32": ([(wk.BLOCK_BASIC, 16, 0, 16, 1, 0)], 72, 32),
+    "cifar_c32_w16": ([(wk.BLOCK_BASIC, 32, 0, 32, 1, 0)], 72, 16),
+    "cifar_c64_w8": ([(wk.BLOCK_BASIC, 64, 0, 64, 1, 0)], 40, 8),
+    "cifar_c16_w32_small": ([(wk.BLOCK_BASIC, 16, 0, 16, 1, 0)], 3, 32),
 }
 
 
@@ -186,8 +192,7 @@ def test_single_block_module(H, which, dtype):
     import paper_1804_10574_amd as ddg
     from paper_1804_10574_amd.ddg import make_desc
     from oracle import ddg_oracle as orc
-    blocks = SINGLE_BLOCKS[which]
-    N, Hh = 6, 9
+    blocks, N, Hh = SINGLE_BLOCKS[which]
     cin, cout, stride = blocks[0][1], blocks[0][3], blocks[0][4]
     tol = TOL[dtype]
     # module k=2 of K=3: delay 1, and k > 1 so the input gradient is produced
