@@ -152,10 +152,15 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
 ddg_status ddg_pipeline_destroy(ddg_pipeline* p);
 ddg_module* ddg_pipeline_module(ddg_pipeline* p, int k);
 /* One iteration: x [batch,in_h,in_w,in_c] in module 1's compute type, labels int32 [batch],
- * both device pointers that must stay valid until the step's work has run; loss_out: device
- * float or NULL. Iterations are counted internally from 0. */
+ * both device pointers whose contents are complete when the call is made and stay valid until
+ * the step's work has run (they are first copied to pipeline-owned buffers on the pipeline's
+ * streams); loss_out: device float or NULL. Iterations are counted internally from 0. */
 ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labels, float lr,
                              float* loss_out);
+/* The pipeline replays each module's forward and backward+update launches as captured HIP graphs
+ * once every module computes a gradient (iteration >= K); on = 0 enqueues every kernel
+ * individually instead (same results). Also off when the environment has DDG_NO_GRAPH=1. */
+ddg_status ddg_pipeline_set_graphs(ddg_pipeline* p, int on);
 /* Copy module k's latest forward output / the error gradient last delivered to module k
  * (mailbox) to host memory as fp32 NHWC; synchronises. *iteration receives the iteration the
  * mailbox content belongs to (-1: none yet). */

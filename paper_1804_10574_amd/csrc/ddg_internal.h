@@ -1,0 +1,14 @@
+// Calls shared by the module and the pipeline that are not part of the C boundary.
+#pragma once
+#include "../../include/ddg.h"
+#include <hip/hip_runtime_api.h>
+
+extern "C" {
+// While set, the module's calls advance their host-side state (iteration counter, ring
+// position) and validate arguments but enqueue nothing: the pipeline replays a captured
+// graph of the same call instead.
+void ddg_internal_skip_launches(ddg_module* m, bool skip);
+// The update reads its step size from this device float instead of the call argument.
+void ddg_internal_lr_from(ddg_module* m, const float* lr_dev);
+bool ddg_internal_profiling(const ddg_module* m);
+}

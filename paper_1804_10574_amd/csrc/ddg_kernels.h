@@ -93,8 +93,11 @@ struct HeadArgs {
 };
 hipError_t head_launch(const HeadArgs& a, hipStream_t s);
 
-hipError_t sgd_launch(float* w, float* v, const float* g, size_t n, float lr, float mu, float wd,
-                      hipStream_t s);
+// lr_dev != nullptr: the step size is read from device memory (lets a captured graph be replayed
+// with a different step size).
+hipError_t sgd_launch(float* w, float* v, const float* g, size_t n, float lr, const float* lr_dev,
+                      float mu, float wd, hipStream_t s);
+hipError_t set_scalar_launch(float* dst, float v, hipStream_t s);
 hipError_t copy_launch(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t to_f32_launch(const void* src, float* dst, size_t elems, int dtype, hipStream_t s);
 

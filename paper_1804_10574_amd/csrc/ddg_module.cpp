@@ -4,6 +4,7 @@
 // file only validates, allocates and enqueues.
 #include "../../include/ddg.h"
 #include "ddg_kernels.h"
+#include "ddg_internal.h"
 
 #include <hip/hip_runtime_api.h>
 
@@ -90,6 +91,8 @@ struct ddg_module {
   bool has_grad = false;
   bool tape_is_current = false;  // saved activations belong to forward(t) with current weights
   ddg_status sticky = DDG_OK;
+  bool skip = false;               // advance state only (a captured graph is replayed instead)
+  const float* lr_dev = nullptr;   // step size in device memory, if set
   // profiling
   bool prof = false;
   struct Ev { int kind; hipEvent_t a, b; };
@@ -590,6 +593,7 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   if (((uintptr_t)h_in & 15) || ((uintptr_t)h_out & 15)) return fail(DDG_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
   m->phase = 1;
   if (m->d.dry_run) return DDG_OK;
+  if (m->skip) { m->tape_is_current = (m->delay == 0); return DDG_OK; }
   void* slot = m->ring[t % m->nslots];
   { Launch L(m, PK_COPY); DDG_TRY(copy_launch(h_in, slot, m->in_elems * m->esz, m->stream)); }
   // A module with delay > 0 re-forwards before its backward, so this pass need not keep a
@@ -624,6 +628,7 @@ ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, con
   m->has_grad = (s >= 0);
   if (did_backward) *did_backward = m->has_grad ? 1 : 0;
   if (s < 0 || m->d.dry_run) return DDG_OK;
+  if (m->skip) { m->tape_is_current = false; return DDG_OK; }
   void* slot = m->ring[s % m->nslots];
   if (!m->tape_is_current) DDG_OKAY(run_forward(m, slot, nullptr));
   m->tape_is_current = false;
@@ -635,9 +640,9 @@ ddg_status ddg_update(ddg_module* m, long t, float lr) {
   if (m->phase != 2 || t != m->t_next) return fail(DDG_ERR_STATE, "ddg_update(t=%ld) must follow ddg_backward_delayed(t=%ld)", t, m->t_next);
   m->phase = 0;
   m->t_next = t + 1;
-  if (!m->has_grad || m->d.dry_run) return DDG_OK;
+  if (!m->has_grad || m->d.dry_run || m->skip) return DDG_OK;
   { Launch L(m, PK_SGD);
-    DDG_TRY(sgd_launch(m->theta, m->vel, m->grad, m->nparams, lr, m->d.momentum, m->d.weight_decay, m->stream)); }
+    DDG_TRY(sgd_launch(m->theta, m->vel, m->grad, m->nparams, lr, m->lr_dev, m->d.momentum, m->d.weight_decay, m->stream)); }
   return pack_all(m);
 }
 
@@ -647,6 +652,10 @@ ddg_status ddg_module_sync(ddg_module* m) {
   DDG_TRY(hipStreamSynchronize(m->stream));
   return DDG_OK;
 }
+
+void ddg_internal_skip_launches(ddg_module* m, bool skip) { m->skip = skip; }
+void ddg_internal_lr_from(ddg_module* m, const float* lr_dev) { m->lr_dev = lr_dev; }
+bool ddg_internal_profiling(const ddg_module* m) { return m->prof; }
 
 int ddg_profile_kinds(void) { return PK_COUNT; }
 const char* ddg_profile_kind_name(int kind) { return (kind >= 0 && kind < PK_COUNT) ? kProfNames[kind] : ""; }

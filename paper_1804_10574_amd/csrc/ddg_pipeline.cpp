@@ -6,6 +6,10 @@
 // modules on one stream gives bit-identical results.
 #include "../../include/ddg.h"
 #include "ddg_kernels.h"
+#include "ddg_internal.h"
+
+#include <cstdlib>
+#include <map>
 
 #include <hip/hip_runtime_api.h>
 
@@ -27,7 +31,38 @@ struct ddg_pipeline {
   long t = 0;
   bool dry = false;
   float* scratch_f32 = nullptr; size_t scratch_elems = 0;
+  // HIP-graph replay of each module's forward and backward+update call (steady state only).
+  // A call's launches depend on t only through the ring slot (period K-k+1) and the mailbox
+  // slot (period 2), so one graph per residue of t modulo their least common multiple.
+  bool graphs = true;
+  std::vector<int> period;                                  // [k]
+  std::vector<std::map<int, hipGraphExec_t>> gfwd, gbwd;    // [k][t mod period]
+  void* xin = nullptr;            // staged network input (stable address for the graphs)
+  int32_t* labels_dev = nullptr;  // staged labels
+  float* loss_dev = nullptr;      // loss of the last iteration
+  float* lr_dev = nullptr;        // step size read by the update kernels
+  float lr_host = -1.f;
+  size_t x_bytes = 0;
+  int batch = 0;
 };
+
+namespace {
+int gcd_i(int a, int b) { return b ? gcd_i(b, a % b) : a; }
+
+// Capture what `fn` enqueues on `s` into an executable graph.
+template <class F>
+ddg_status capture(hipStream_t s, hipGraphExec_t* exec, F fn) {
+  if (hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal) != hipSuccess) return DDG_ERR_DEVICE;
+  ddg_status st = fn();
+  hipGraph_t g = nullptr;
+  hipError_t e = hipStreamEndCapture(s, &g);
+  if (st != DDG_OK) { if (g) (void)hipGraphDestroy(g); return st; }
+  if (e != hipSuccess || !g) return DDG_ERR_DEVICE;
+  e = hipGraphInstantiate(exec, g, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(g);
+  return e == hipSuccess ? DDG_OK : DDG_ERR_DEVICE;
+}
+}  // namespace
 
 extern "C" {
 
@@ -44,6 +79,11 @@ ddg_status ddg_pipeline_destroy(ddg_pipeline* p) {
     }
     for (hipEvent_t e : p->fwd_done) if (e) (void)hipEventDestroy(e);
     if (p->scratch_f32) (void)hipFree(p->scratch_f32);
+    for (auto& mp : p->gfwd) for (auto& kv : mp) (void)hipGraphExecDestroy(kv.second);
+    for (auto& mp : p->gbwd) for (auto& kv : mp) (void)hipGraphExecDestroy(kv.second);
+    if (p->xin) (void)hipFree(p->xin);
+    if (p->labels_dev) (void)hipFree(p->labels_dev);
+    if (p->loss_dev) (void)hipFree(p->loss_dev);
   }
   for (ddg_module* m : p->mods) ddg_module_destroy(m);
   delete p;
@@ -101,6 +141,22 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
       }
     }
     if (hipMalloc((void**)&p->scratch_f32, p->scratch_elems * sizeof(float)) != hipSuccess) { ddg_pipeline_destroy(p); return DDG_ERR_OOM; }
+    p->batch = descs[0].batch;
+    p->x_bytes = (size_t)descs[0].batch * descs[0].in_c * descs[0].in_h * descs[0].in_w * ddg::dtype_size(descs[0].compute);
+    void* sc = nullptr;
+    if (hipMalloc(&p->xin, p->x_bytes) != hipSuccess || hipMalloc((void**)&p->labels_dev, p->batch * sizeof(int32_t)) != hipSuccess ||
+        hipMalloc(&sc, 2 * sizeof(float)) != hipSuccess) { ddg_pipeline_destroy(p); return DDG_ERR_OOM; }
+    p->loss_dev = (float*)sc; p->lr_dev = p->loss_dev + 1;
+    const char* env = getenv("DDG_NO_GRAPH");
+    if (env && env[0] == '1') p->graphs = false;
+    if (!streams) p->graphs = false;   // the default stream cannot be captured
+    p->period.assign(K + 1, 1);
+    p->gfwd.resize(K + 1); p->gbwd.resize(K + 1);
+    for (int k = 1; k <= K; ++k) {
+      const int nslots = K - k + 1;
+      p->period[k] = nslots * 2 / gcd_i(nslots, 2);
+      ddg_internal_lr_from(p->mods[k], p->lr_dev);
+    }
   }
   else {
     // dry run: nothing is dereferenced; hand the modules a non-null, aligned placeholder
@@ -112,11 +168,33 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
 
 ddg_module* ddg_pipeline_module(ddg_pipeline* p, int k) { return (p && k >= 1 && k <= p->K) ? p->mods[k] : nullptr; }
 
+ddg_status ddg_pipeline_set_graphs(ddg_pipeline* p, int on) {
+  if (!p) return DDG_ERR_INVALID_ARG;
+  p->graphs = on != 0;
+  return DDG_OK;
+}
+
 ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labels, float lr, float* loss_out) {
   if (!p || !x || !labels) return DDG_ERR_INVALID_ARG;
   const int K = p->K;
   const long t = p->t;
   const int cur = (int)(t & 1), prev = cur ^ 1;
+  bool use_graph = !p->dry && p->graphs && t >= K;   // steady state: every module has a gradient
+  if (use_graph) for (int k = 1; k <= K; ++k) if (ddg_internal_profiling(p->mods[k])) use_graph = false;
+  if (!p->dry) {
+    // stage the caller's tensors at stable addresses; the step size lives in device memory
+    if (ddg::copy_launch(x, p->xin, p->x_bytes, p->streams[1]) != hipSuccess) return DDG_ERR_DEVICE;
+    if (ddg::copy_launch(labels, p->labels_dev, p->batch * sizeof(int32_t), p->streams[K]) != hipSuccess) return DDG_ERR_DEVICE;
+    if (lr != p->lr_host) {
+      // every module's update of the previous iteration must have read the old value
+      for (int k = 1; k <= K; ++k) if (hipStreamSynchronize(p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+      if (ddg::set_scalar_launch(p->lr_dev, lr, p->streams[1]) != hipSuccess) return DDG_ERR_DEVICE;
+      if (hipStreamSynchronize(p->streams[1]) != hipSuccess) return DDG_ERR_DEVICE;
+      p->lr_host = lr;
+    }
+  }
+  const void* x_in = p->dry ? x : p->xin;
+  const int32_t* lab = p->dry ? labels : p->labels_dev;
   // forward, k = 1..K in turn (Section 3.1)
   for (int k = 1; k <= K; ++k) {
     if (!p->dry) {
@@ -124,8 +202,27 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
       // h[k] is still being read by module k+1's forward of the previous iteration
       if (k < K && t > 0) if (hipStreamWaitEvent(p->streams[k], p->fwd_done[k + 1], 0) != hipSuccess) return DDG_ERR_DEVICE;
     }
-    ddg_status st = ddg_forward(p->mods[k], t, k == 1 ? x : p->h[k - 1], k < K ? p->h[k] : nullptr);
-    if (st != DDG_OK) return pfail(st);
+    auto call = [&]() { return ddg_forward(p->mods[k], t, k == 1 ? x_in : p->h[k - 1], k < K ? p->h[k] : nullptr); };
+    ddg_status st;
+    if (use_graph) {
+      const int v = (int)(t % p->period[k]);
+      auto it = p->gfwd[k].find(v);
+      if (it == p->gfwd[k].end()) {
+        hipGraphExec_t ex = nullptr;
+        st = capture(p->streams[k], &ex, call);
+        if (st != DDG_OK) return st;
+        it = p->gfwd[k].emplace(v, ex).first;
+      } else {
+        ddg_internal_skip_launches(p->mods[k], true);
+        st = call();
+        ddg_internal_skip_launches(p->mods[k], false);
+        if (st != DDG_OK) return st;
+      }
+      if (hipGraphLaunch(it->second, p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+    } else {
+      st = call();
+      if (st != DDG_OK) return pfail(st);
+    }
     if (!p->dry) if (hipEventRecord(p->fwd_done[k], p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
   }
   // backward + update: the K modules are independent within one iteration
@@ -140,13 +237,38 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
     const void* din = (k < K) ? p->mail[prev][k] : nullptr;
     void* dout = (k > 1) ? p->mail[cur][k - 1] : nullptr;
     int did = 0;
-    ddg_status st = ddg_backward_delayed(p->mods[k], t, (s >= 0) ? din : nullptr, k == K ? labels : nullptr,
-                                         dout, k == K ? loss_out : nullptr, &did);
-    if (st != DDG_OK) return pfail(st);
+    auto call = [&]() {
+      ddg_status r = ddg_backward_delayed(p->mods[k], t, (s >= 0) ? din : nullptr, k == K ? lab : nullptr, dout,
+                                          k == K ? (p->dry ? loss_out : p->loss_dev) : nullptr, &did);
+      if (r != DDG_OK) return r;
+      return ddg_update(p->mods[k], t, lr);
+    };
+    ddg_status st;
+    if (use_graph) {
+      const int v = (int)(t % p->period[k]);
+      auto it = p->gbwd[k].find(v);
+      if (it == p->gbwd[k].end()) {
+        hipGraphExec_t ex = nullptr;
+        st = capture(p->streams[k], &ex, call);
+        if (st != DDG_OK) return st;
+        it = p->gbwd[k].emplace(v, ex).first;
+      } else {
+        ddg_internal_skip_launches(p->mods[k], true);
+        st = call();
+        ddg_internal_skip_launches(p->mods[k], false);
+        if (st != DDG_OK) return st;
+      }
+      if (hipGraphLaunch(it->second, p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+    } else {
+      st = call();
+      if (st != DDG_OK) return pfail(st);
+    }
     if (k > 1) p->mail_iter[cur][k - 1] = did ? s : -1;
-    st = ddg_update(p->mods[k], t, lr);
-    if (st != DDG_OK) return pfail(st);
-    if (!p->dry) if (hipEventRecord(p->bwd_done[cur][k], p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+    if (!p->dry) {
+      if (k == K && loss_out && s >= 0)
+        if (ddg::copy_launch(p->loss_dev, loss_out, sizeof(float), p->streams[K]) != hipSuccess) return DDG_ERR_DEVICE;
+      if (hipEventRecord(p->bwd_done[cur][k], p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+    }
   }
   p->t = t + 1;
   return DDG_OK;

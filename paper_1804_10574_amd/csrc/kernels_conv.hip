@@ -191,7 +191,7 @@ void conv_plan(ConvArgs& a) {
   const int gy = ocb / a.nb;
   const int tiles = (a.M + 16 * a.mb - 1) / (16 * a.mb);
   int gx = (tiles + 3) / 4;
-  const int cap = 2048 / gy > 1 ? 2048 / gy : 1;
+  const int cap = 512 / gy > 1 ? 512 / gy : 1;   // also the number of statistics rows
   if (gx > cap) gx = cap;
   if (gx < 1) gx = 1;
   a.grid_x = gx;

@@ -15,17 +15,17 @@ namespace ddg {
 // Finalise per-channel statistics. partial is [rows][2][C] (sum, sum of squares).
 // One workgroup per 16 channels; 16 row-slices per channel are combined in order.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restrict__ partial, int rows,
+__global__ __launch_bounds__(1024) void bn_finalize_kernel(const float* __restrict__ partial, int rows,
                                                           int C, const float* __restrict__ gamma,
                                                           const float* __restrict__ beta, float count,
                                                           float eps, float* mean, float* invstd,
                                                           float* scale, float* shift) {
-  __shared__ double r1[16][17], r2[16][17];
+  __shared__ double r1[64][17], r2[64][17];
   const int cl = threadIdx.x & 15, slice = threadIdx.x >> 4;
   const int c = blockIdx.x * 16 + cl;
   double s1 = 0.0, s2 = 0.0;
   if (c < C)
-    for (int r = slice; r < rows; r += 16) {
+    for (int r = slice; r < rows; r += 64) {
       s1 += (double)partial[((size_t)r * 2 + 0) * C + c];
       s2 += (double)partial[((size_t)r * 2 + 1) * C + c];
     }
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restric
   if (slice == 0 && c < C) {
     double t1 = 0.0, t2 = 0.0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { t1 += r1[i][cl]; t2 += r2[i][cl]; }
+    for (int i = 0; i < 64; ++i) { t1 += r1[i][cl]; t2 += r2[i][cl]; }
     const double mu = t1 / (double)count;
     double var = t2 / (double)count - mu * mu;
     if (var < 0.0) var = 0.0;
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restric
 hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                               const float* beta, float count, float eps, float* mean, float* invstd,
                               float* scale, float* shift, hipStream_t s) {
-  hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 15) / 16), dim3(256), 0, s, partial, rows, C, gamma,
+  hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 15) / 16), dim3(1024), 0, s, partial, rows, C, gamma,
                      beta, count, eps, mean, invstd, scale, shift);
   return hipGetLastError();
 }
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const T* __restrict_
 // rows are written completely only if 256*V % C == 0 or C % (256*V) == 0 handled below.
 int bn_bwd_grid(size_t elems, int C, int dtype) {
   const int V = dtype == BF16 ? 8 : 4;
-  return elem_grid(elems / V, C, V, 1024);
+  return elem_grid(elems / V, C, V, 256);
 }
 
 template <typename T>
@@ -209,17 +209,17 @@ hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const void* z,
 
 // dbeta = sum g, dgamma = sum g*xhat; dz = A*g + B*z + C0 with
 //   A = gamma*invstd, B = -gamma*invstd^2*dgamma/m, C0 = -gamma*invstd*dbeta/m - B*mean
-__global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ partial, int rows, int C,
+__global__ __launch_bounds__(1024) void bn_bwd_finalize_kernel(const float* __restrict__ partial, int rows, int C,
                                                               const float* __restrict__ gamma,
                                                               const float* __restrict__ mean,
                                                               const float* __restrict__ invstd, float count,
                                                               float* dgamma, float* dbeta, float* coef) {
-  __shared__ double r1[16][17], r2[16][17];
+  __shared__ double r1[64][17], r2[64][17];
   const int cl = threadIdx.x & 15, slice = threadIdx.x >> 4;
   const int c = blockIdx.x * 16 + cl;
   double s1 = 0.0, s2 = 0.0;
   if (c < C)
-    for (int r = slice; r < rows; r += 16) {
+    for (int r = slice; r < rows; r += 64) {
       s1 += (double)partial[((size_t)r * 2 + 0) * C + c];
       s2 += (double)partial[((size_t)r * 2 + 1) * C + c];
     }
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __res
   if (slice == 0 && c < C) {
     double db = 0.0, dg = 0.0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { db += r1[i][cl]; dg += r2[i][cl]; }
+    for (int i = 0; i < 64; ++i) { db += r1[i][cl]; dg += r2[i][cl]; }
     dbeta[c] = (float)db;
     dgamma[c] = (float)dg;
     const double g = gamma[c], is = invstd[c], mu = mean[c], m = count;
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __res
 hipError_t bn_bwd_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                                   const float* mean, const float* invstd, float count, float* dgamma,
                                   float* dbeta, float* coef, hipStream_t s) {
-  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 15) / 16), dim3(256), 0, s, partial, rows, C, gamma,
+  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 15) / 16), dim3(1024), 0, s, partial, rows, C, gamma,
                      mean, invstd, count, dgamma, dbeta, coef);
   return hipGetLastError();
 }
@@ -385,7 +385,8 @@ hipError_t head_launch(const HeadArgs& a, hipStream_t s) {
 // Momentum SGD over the module's flat parameter vector.
 // ---------------------------------------------------------------------------------
 __global__ void sgd_kernel(float* __restrict__ w, float* __restrict__ v, const float* __restrict__ g, size_t n,
-                           float lr, float mu, float wd) {
+                           float lr, const float* __restrict__ lr_dev, float mu, float wd) {
+  if (lr_dev) lr = *lr_dev;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
     const float wi = w[i];
     const float vi = mu * v[i] + (g[i] + wd * wi);
@@ -394,11 +395,19 @@ __global__ void sgd_kernel(float* __restrict__ w, float* __restrict__ v, const f
   }
 }
 
-hipError_t sgd_launch(float* w, float* v, const float* g, size_t n, float lr, float mu, float wd, hipStream_t s) {
+__global__ void set_scalar_kernel(float* dst, float v) { *dst = v; }
+
+hipError_t set_scalar_launch(float* dst, float v, hipStream_t s) {
+  hipLaunchKernelGGL(set_scalar_kernel, dim3(1), dim3(1), 0, s, dst, v);
+  return hipGetLastError();
+}
+
+hipError_t sgd_launch(float* w, float* v, const float* g, size_t n, float lr, const float* lr_dev, float mu,
+                      float wd, hipStream_t s) {
   int grid = (int)((n + 255) / 256);
   if (grid > 2048) grid = 2048;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL(sgd_kernel, dim3(grid), dim3(256), 0, s, w, v, g, n, lr, mu, wd);
+  hipLaunchKernelGGL(sgd_kernel, dim3(grid), dim3(256), 0, s, w, v, g, n, lr, lr_dev, mu, wd);
   return hipGetLastError();
 }
 

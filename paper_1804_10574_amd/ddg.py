@@ -71,6 +71,7 @@ def load_library():
         "ddg_pipeline_destroy": (st, [vp]),
         "ddg_pipeline_module": (vp, [vp, C.c_int]),
         "ddg_pipeline_step": (st, [vp, vp, vp, C.c_float, vp]),
+        "ddg_pipeline_set_graphs": (st, [vp, C.c_int]),
         "ddg_pipeline_get_h": (st, [vp, C.c_int, vp]),
         "ddg_pipeline_get_delta": (st, [vp, C.c_int, vp, C.POINTER(C.c_long)]),
         "ddg_pipeline_sync": (st, [vp]),
@@ -93,7 +94,7 @@ EXPORTS = ["ddg_module_create", "ddg_module_destroy", "ddg_param_count", "ddg_ou
            "ddg_device_bytes", "ddg_set_params", "ddg_set_velocity", "ddg_get_params", "ddg_get_velocity", "ddg_get_grad",
            "ddg_forward", "ddg_backward_delayed", "ddg_update", "ddg_module_sync",
            "ddg_pipeline_create", "ddg_pipeline_destroy", "ddg_pipeline_module", "ddg_pipeline_step",
-           "ddg_pipeline_get_h", "ddg_pipeline_get_delta", "ddg_pipeline_sync", "ddg_profile_kinds",
+           "ddg_pipeline_set_graphs", "ddg_pipeline_get_h", "ddg_pipeline_get_delta", "ddg_pipeline_sync", "ddg_profile_kinds",
            "ddg_profile_kind_name", "ddg_profile_enable", "ddg_profile_read", "ddg_profile_reset",
            "ddg_last_error", "ddg_version"]
 
@@ -263,6 +264,9 @@ class Pipeline:
 
     def step(self, x, labels, lr, loss_out=None):
         _check(self._lib.ddg_pipeline_step(self._h, _ptr(x), _ptr(labels), lr, _ptr(loss_out)))
+
+    def set_graphs(self, on: bool):
+        _check(self._lib.ddg_pipeline_set_graphs(self._h, 1 if on else 0))
 
     def sync(self):
         _check(self._lib.ddg_pipeline_sync(self._h))
