@@ -37,6 +37,8 @@ void conv_plan(ConvArgs& a);                       // chooses tile shape and gri
 hipError_t conv_launch(const ConvArgs& a, hipStream_t s);
 size_t conv_wpack_elems(int kchannels, int nchannels, int R, int dtype, int* log2cp, int* ksteps);
 // Packs fp32 master weights W[Cout][Cin][R][R] into the operand layout of conv_launch.
+// dgrad: 0 forward operand, 1 input-gradient operand (taps as stored), 2 input-gradient operand
+// with mirrored taps (for kernels that run the input-gradient as a plain 3x3 correlation).
 hipError_t pack_weights_launch(const float* W, void* wpack, int Cout, int Cin, int R, int dgrad,
                                int dtype, hipStream_t s);
 
@@ -63,6 +65,15 @@ int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, 
 hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* shift, const void* dz,
                               float* partial, int N, int H, int W, int C, int rows, hipStream_t s);
 
+// LDS-tiled 3x3/stride-1 convolution for 16/32/64 channels (bf16). Returns the grid (= number of
+// statistics rows), 0 if the shape is not covered. scale/shift: optional relu(in*scale+shift)
+// applied while staging. The same kernel computes the input gradient from an operand packed
+// with mirrored taps.
+int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
+hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const void* wpack,
+                             void* out, float* stat_partial, const void* add_g, const void* add_mask,
+                             int N, int H, int W, int C, int grid, hipStream_t s);
+
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
 // shift=beta-mean*scale.
 hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,
@@ -72,17 +83,20 @@ hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float
 hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const void* res,
                            const float* rscale, const float* rshift, void* y, size_t elems, int C,
                            int relu, int dtype, hipStream_t s);
-// g = mask ? (mask>0 ? dy : 0) : dy; partial[grid][2][C] = (sum g, sum g*xhat)
+// g = dy where the ReLU that follows was active, else 0: active means mask > 0, or
+// mask*mscale+mshift > 0 when mscale is given (the mask tensor is then the conv output the
+// activation derives from); mask == nullptr: g = dy. partial[grid][2][C] = (sum g, sum g*xhat)
 int bn_bwd_grid(size_t elems, int C, int dtype);
-hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const void* z, const float* mean,
-                                const float* invstd, float* partial, size_t elems, int C, int dtype,
-                                hipStream_t s);
+hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const float* mscale, const float* mshift,
+                                const void* z, const float* mean, const float* invstd, float* partial,
+                                size_t elems, int C, int dtype, hipStream_t s);
 // dgamma, dbeta and the coefficients of dz = A*g + B*z + C0 (per channel; coef = [3][C])
 hipError_t bn_bwd_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                                   const float* mean, const float* invstd, float count, float* dgamma,
                                   float* dbeta, float* coef, hipStream_t s);
-hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const void* z, const float* coef,
-                               void* dz, size_t elems, int C, int dtype, hipStream_t s);
+hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const float* mscale, const float* mshift,
+                               const void* z, const float* coef, void* dz, size_t elems, int C, int dtype,
+                               hipStream_t s);
 
 // Head: global average pool, linear, softmax cross-entropy (mean over the batch) and its gradients.
 struct HeadArgs {

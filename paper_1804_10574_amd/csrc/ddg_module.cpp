@@ -51,6 +51,7 @@ struct Unit {  // convolution + batch normalisation
   WgradArgs wg{};
   bool has_dgrad = false;
   int wg_tiled_rows = 0;   // > 0: the LDS-tiled bf16 weight-gradient kernel covers this layer
+  int tiled_grid = 0;      // > 0: the LDS-tiled conv kernel covers this layer (forward and dgrad)
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
   size_t in_elems() const { return (size_t)N * H * W * cin; }
 };
@@ -257,6 +258,8 @@ ddg_status build_plan(ddg_module* m) {
       size_t ne = conv_wpack_elems(u.cin, u.cout, u.R, dt, &f.log2cp, &f.ksteps);
       DDG_OKAY(dev_alloc(m, &u.wpack_f, ne * m->esz));
       conv_plan(f);
+      u.tiled_grid = conv_tiled_grid(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
+      if (u.tiled_grid > f.grid_x) f.grid_x = u.tiled_grid;   // sizes the statistics workspace
       size_t st_e = (size_t)f.grid_x * 2 * u.cout;
       if (st_e > m->ws_stat_elems) m->ws_stat_elems = st_e;
       // input gradient
@@ -288,8 +291,10 @@ ddg_status build_plan(ddg_module* m) {
       u.shift = u.scale + u.cout; u.coef = u.shift + u.cout;
     }
     for (int ui = 0; ui + 1 < b.nmain; ++ui) {
+      // the activation between two units is materialised only if the consumer cannot derive
+      // it from the producer's conv output while loading
       void* a = nullptr;
-      DDG_OKAY(dev_alloc(m, &a, b.u[ui].out_elems() * m->esz));
+      if (b.u[ui + 1].tiled_grid == 0) DDG_OKAY(dev_alloc(m, &a, b.u[ui].out_elems() * m->esz));
       b.act.push_back(a);
     }
     b.y_elems = b.u[b.nmain - 1].out_elems();
@@ -338,19 +343,32 @@ ddg_status pack_all(ddg_module* m) {
         DDG_TRY(pack_weights_launch(m->theta + u.ow, u.wpack_f, u.cout, u.cin, u.R, 0, m->d.compute, m->stream)); }
       if (u.has_dgrad) {
         Launch L(m, PK_PACK);
-        DDG_TRY(pack_weights_launch(m->theta + u.ow, u.wpack_d, u.cout, u.cin, u.R, 1, m->d.compute, m->stream));
+        DDG_TRY(pack_weights_launch(m->theta + u.ow, u.wpack_d, u.cout, u.cin, u.R, u.tiled_grid > 0 ? 2 : 1,
+                                    m->d.compute, m->stream));
       }
     }
   return DDG_OK;
 }
 
-// conv + batch statistics of one unit: in -> u.z, u.mean/invstd/scale/shift
-ddg_status unit_forward(ddg_module* m, Unit& u, const void* in) {
-  ConvArgs a = u.fprop;
-  a.in = in; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = m->ws_stat; a.add_g = nullptr; a.add_mask = nullptr;
-  { Launch L(m, PK_CONV_FPROP); DDG_TRY(conv_launch(a, m->stream)); }
+// conv + batch statistics of one unit: in -> u.z, u.mean/invstd/scale/shift. With in_scale the
+// input is relu(in*in_scale+in_shift), formed while loading (LDS-tiled kernel only).
+ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, const float* in_scale, const float* in_shift) {
+  int rows;
+  if (u.tiled_grid > 0) {
+    rows = u.tiled_grid;
+    Launch L(m, PK_CONV_FPROP);
+    DDG_TRY(conv_tiled_launch(in, in_scale, in_shift, u.wpack_f, u.z, m->ws_stat, nullptr, nullptr, u.N, u.H,
+                              u.W, u.cin, u.tiled_grid, m->stream));
+  } else {
+    ConvArgs a = u.fprop;
+    conv_plan(a);
+    rows = a.grid_x;
+    a.in = in; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = m->ws_stat; a.add_g = nullptr; a.add_mask = nullptr;
+    Launch L(m, PK_CONV_FPROP);
+    DDG_TRY(conv_launch(a, m->stream));
+  }
   { Launch L(m, PK_BN_FINALIZE);
-    DDG_TRY(bn_finalize_launch(m->ws_stat, a.grid_x, u.cout, m->theta + u.og, m->theta + u.ob,
+    DDG_TRY(bn_finalize_launch(m->ws_stat, rows, u.cout, m->theta + u.og, m->theta + u.ob,
                                (float)((size_t)u.N * u.P * u.Q), m->d.bn_eps, u.mean, u.invstd, u.scale,
                                u.shift, m->stream)); }
   return DDG_OK;
@@ -366,14 +384,20 @@ ddg_status run_forward(ddg_module* m, const void* in, void* final_out) {
     Blk& b = m->blocks[bi];
     void* yout = (bi == nres - 1 && final_out) ? final_out : b.y;
     const void* cur = x;
+    const float *csc = nullptr, *csh = nullptr;   // pending relu(bn(.)) of `cur`
     for (int i = 0; i < b.nmain; ++i) {
       Unit& u = b.u[i];
-      DDG_OKAY(unit_forward(m, u, cur));
+      DDG_OKAY(unit_forward(m, u, cur, csc, csh));
+      csc = csh = nullptr;
       if (i + 1 < b.nmain) {
-        Launch L(m, PK_BN_APPLY);
-        DDG_TRY(bn_apply_launch(u.z, u.scale, u.shift, nullptr, nullptr, nullptr, b.act[i], u.out_elems(),
-                                u.cout, 1, dt, m->stream));
-        cur = b.act[i];
+        if (b.act[i]) {
+          Launch L(m, PK_BN_APPLY);
+          DDG_TRY(bn_apply_launch(u.z, u.scale, u.shift, nullptr, nullptr, nullptr, b.act[i], u.out_elems(),
+                                  u.cout, 1, dt, m->stream));
+          cur = b.act[i];
+        } else {
+          cur = u.z; csc = u.scale; csh = u.shift;   // the next conv applies BN + ReLU while loading
+        }
       }
     }
     Unit& ul = b.u[b.nmain - 1];
@@ -382,7 +406,7 @@ ddg_status run_forward(ddg_module* m, const void* in, void* final_out) {
       DDG_TRY(bn_apply_launch(ul.z, ul.scale, ul.shift, nullptr, nullptr, nullptr, yout, ul.out_elems(), ul.cout, 1, dt, m->stream));
     } else if (b.proj) {
       Unit& up = b.u[b.nmain];
-      DDG_OKAY(unit_forward(m, up, x));
+      DDG_OKAY(unit_forward(m, up, x, nullptr, nullptr));
       Launch L(m, PK_BN_APPLY);
       DDG_TRY(bn_apply_launch(ul.z, ul.scale, ul.shift, up.z, up.scale, up.shift, yout, ul.out_elems(), ul.cout, 1, dt, m->stream));
     } else {
@@ -395,36 +419,45 @@ ddg_status run_forward(ddg_module* m, const void* in, void* final_out) {
 }
 
 // BN backward + weight gradient (+ input gradient) of one unit.
-//   dy/mask: gradient w.r.t. the BN output, masked where mask <= 0 (mask may be null)
-//   x_in: the unit's conv input; dx: where the input gradient goes (null: not needed)
-//   add_g/add_mask: optional term added to dx in the same kernel
-ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mask, const void* x_in,
+//   dy: gradient w.r.t. the ReLU output that follows this unit's BN; the ReLU was active where
+//       mask > 0 (or mask*mscale+mshift > 0); mask == null: no ReLU in between
+//   x_in: the unit's conv input, or with x_scale the tensor it derives from by relu(x*s+t)
+//   dx: where the input gradient goes (null: not needed); add_g/add_mask: optional term added
+//       to dx in the same kernel
+ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mask, const float* mscale,
+                         const float* mshift, const void* x_in, const float* x_scale, const float* x_shift,
                          void* dz_buf, void* dx, const void* add_g, const void* add_mask) {
   const int dt = m->d.compute;
   const size_t E = u.out_elems();
   const int rows = bn_bwd_grid(E, u.cout, dt);
   { Launch L(m, PK_BN_BWD_REDUCE);
-    DDG_TRY(bn_bwd_reduce_launch(dy, mask, u.z, u.mean, u.invstd, m->ws_stat, E, u.cout, dt, m->stream)); }
+    DDG_TRY(bn_bwd_reduce_launch(dy, mask, mscale, mshift, u.z, u.mean, u.invstd, m->ws_stat, E, u.cout, dt, m->stream)); }
   { Launch L(m, PK_BN_BWD_FINALIZE);
     DDG_TRY(bn_bwd_finalize_launch(m->ws_stat, rows, u.cout, m->theta + u.og, u.mean, u.invstd,
                                    (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
   { Launch L(m, PK_BN_BWD_APPLY);
-    DDG_TRY(bn_bwd_apply_launch(dy, mask, u.z, u.coef, dz_buf, E, u.cout, dt, m->stream)); }
+    DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, dz_buf, E, u.cout, dt, m->stream)); }
   WgradArgs w = u.wg;
   w.x = x_in; w.dz = dz_buf; w.partial = m->ws_wgrad; w.dW = m->grad + u.ow;
   if (u.wg_tiled_rows > 0) {
     Launch L(m, PK_CONV_WGRAD);
-    DDG_TRY(wgrad_tiled_launch(x_in, nullptr, nullptr, dz_buf, m->ws_wgrad, u.N, u.H, u.W, u.cin, u.wg_tiled_rows, m->stream));
+    DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, dz_buf, m->ws_wgrad, u.N, u.H, u.W, u.cin, u.wg_tiled_rows, m->stream));
   } else {
+    if (x_scale) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
     Launch L(m, PK_CONV_WGRAD);
     DDG_TRY(wgrad_launch(w, m->stream));
   }
   { Launch L(m, PK_WGRAD_REDUCE); DDG_TRY(wgrad_reduce_launch(w, m->stream)); }
   if (dx) {
-    ConvArgs a = u.dgrad;
-    a.in = dz_buf; a.wpack = u.wpack_d; a.out = dx; a.stat_partial = nullptr; a.add_g = add_g; a.add_mask = add_mask;
     Launch L(m, PK_CONV_DGRAD);
-    DDG_TRY(conv_launch(a, m->stream));
+    if (u.tiled_grid > 0) {
+      DDG_TRY(conv_tiled_launch(dz_buf, nullptr, nullptr, u.wpack_d, dx, nullptr, add_g, add_mask, u.N, u.H, u.W,
+                                u.cin, u.tiled_grid, m->stream));
+    } else {
+      ConvArgs a = u.dgrad;
+      a.in = dz_buf; a.wpack = u.wpack_d; a.out = dx; a.stat_partial = nullptr; a.add_g = add_g; a.add_mask = add_mask;
+      DDG_TRY(conv_launch(a, m->stream));
+    }
   }
   return DDG_OK;
 }
@@ -455,26 +488,32 @@ ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const i
     void* dx_dst = nullptr;
     if (want_dx) dx_dst = (bi == 0) ? delta_out : gnext;
     if (b.kind == DDG_BLOCK_STEM) {
-      DDG_OKAY(unit_backward(m, b.u[0], dy, b.y, x, m->D1, dx_dst, nullptr, nullptr));
+      DDG_OKAY(unit_backward(m, b.u[0], dy, b.y, nullptr, nullptr, x, nullptr, nullptr, m->D1, dx_dst, nullptr, nullptr));
     } else {
       // shortcut term of the input gradient
       const void* add_g = nullptr; const void* add_mask = nullptr;
       if (b.proj) {
         Unit& up = b.u[b.nmain];
-        DDG_OKAY(unit_backward(m, up, dy, b.y, x, m->D1, want_dx ? m->D3 : nullptr, nullptr, nullptr));
+        DDG_OKAY(unit_backward(m, up, dy, b.y, nullptr, nullptr, x, nullptr, nullptr, m->D1, want_dx ? m->D3 : nullptr, nullptr, nullptr));
         if (want_dx) add_g = m->D3;
       } else if (want_dx) {
         add_g = dy; add_mask = b.y;
       }
       const void* d = dy; const void* mask = b.y;
+      const float *msc = nullptr, *msh = nullptr;
       for (int i = b.nmain - 1; i >= 0; --i) {
         Unit& u = b.u[i];
-        const void* uin = (i == 0) ? x : b.act[i - 1];
-        void* udx = nullptr;
-        if (i > 0) udx = m->D2;
-        else udx = dx_dst;
-        DDG_OKAY(unit_backward(m, u, d, mask, uin, m->D1, udx, i == 0 ? add_g : nullptr, i == 0 ? add_mask : nullptr));
-        if (i > 0) { d = m->D2; mask = b.act[i - 1]; }
+        // the unit's input: the block input, a materialised activation, or the previous unit's
+        // conv output with its BN + ReLU applied on the fly
+        const void* uin = x; const float *xsc = nullptr, *xsh = nullptr;
+        if (i > 0) {
+          if (b.act[i - 1]) uin = b.act[i - 1];
+          else { uin = b.u[i - 1].z; xsc = b.u[i - 1].scale; xsh = b.u[i - 1].shift; }
+        }
+        void* udx = (i > 0) ? m->D2 : dx_dst;
+        DDG_OKAY(unit_backward(m, u, d, mask, msc, msh, uin, xsc, xsh, m->D1, udx, i == 0 ? add_g : nullptr,
+                               i == 0 ? add_mask : nullptr));
+        if (i > 0) { d = m->D2; mask = uin; msc = xsc; msh = xsh; }
       }
     }
     if (bi > 0) { dy = gnext; gnext = (gnext == m->Ga) ? m->Gb : m->Ga; }

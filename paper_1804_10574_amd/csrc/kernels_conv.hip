@@ -236,7 +236,8 @@ __global__ void pack_weights_kernel(const float* __restrict__ W, T* __restrict__
     const int n = cb * 16 + (lane & 15);
     float v = 0.f;
     if (tap < R * R && c < kc && n < nc) {
-      const int r = tap / R, s = tap % R;
+      int r = tap / R, s = tap % R;
+      if (dgrad == 2) { r = R - 1 - r; s = R - 1 - s; }   // taps mirrored: the input-gradient as a plain correlation
       const int co = dgrad ? c : n, ci = dgrad ? n : c;
       v = W[(((size_t)co * Cin + ci) * R + r) * R + s];
     }

@@ -126,6 +126,8 @@ hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const T* __restrict__ dy, const T* __restrict__ mask,
+                                                            const float* __restrict__ mscale,
+                                                            const float* __restrict__ mshift,
                                                             const T* __restrict__ z, const float* __restrict__ mean,
                                                             const float* __restrict__ invstd,
                                                             float* __restrict__ partial, size_t nvec, int C) {
@@ -133,9 +135,12 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const T* __restrict_
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int c0 = (int)((i * V) % C);
-  float mu[V], is[V], s1[V], s2[V];
+  float mu[V], is[V], s1[V], s2[V], ms[V], mh[V];
 #pragma unroll
-  for (int j = 0; j < V; ++j) { mu[j] = mean[c0 + j]; is[j] = invstd[c0 + j]; s1[j] = 0.f; s2[j] = 0.f; }
+  for (int j = 0; j < V; ++j) {
+    mu[j] = mean[c0 + j]; is[j] = invstd[c0 + j]; s1[j] = 0.f; s2[j] = 0.f;
+    ms[j] = mscale ? mscale[c0 + j] : 1.f; mh[j] = mscale ? mshift[c0 + j] : 0.f;
+  }
   for (; i < nvec; i += stride) {
     float g[V], zz[V];
     Store<T>::load_vec(dy + i * V, g);
@@ -144,7 +149,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const T* __restrict_
       float mk[V];
       Store<T>::load_vec(mask + i * V, mk);
 #pragma unroll
-      for (int j = 0; j < V; ++j) g[j] = mk[j] > 0.f ? g[j] : 0.f;
+      for (int j = 0; j < V; ++j) g[j] = (mk[j] * ms[j] + mh[j]) > 0.f ? g[j] : 0.f;
     }
 #pragma unroll
     for (int j = 0; j < V; ++j) {
@@ -189,9 +194,9 @@ __global__ void zero_f32_kernel(float* p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0.f;
 }
 
-hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const void* z, const float* mean,
-                                const float* invstd, float* partial, size_t elems, int C, int dtype,
-                                hipStream_t s) {
+hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const float* mscale, const float* mshift,
+                                const void* z, const float* mean, const float* invstd, float* partial,
+                                size_t elems, int C, int dtype, hipStream_t s) {
   const int V = dtype == BF16 ? 8 : 4;
   const int grid = bn_bwd_grid(elems, C, dtype);
   if (C > 256 * V) {  // a block's row is only partly written: clear the rows first
@@ -200,10 +205,10 @@ hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const void* z,
   }
   if (dtype == BF16)
     hipLaunchKernelGGL(bn_bwd_reduce_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)dy,
-                       (const bf16_t*)mask, (const bf16_t*)z, mean, invstd, partial, elems / 8, C);
+                       (const bf16_t*)mask, mscale, mshift, (const bf16_t*)z, mean, invstd, partial, elems / 8, C);
   else
     hipLaunchKernelGGL(bn_bwd_reduce_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)dy,
-                       (const float*)mask, (const float*)z, mean, invstd, partial, elems / 4, C);
+                       (const float*)mask, mscale, mshift, (const float*)z, mean, invstd, partial, elems / 4, C);
   return hipGetLastError();
 }
 
@@ -251,15 +256,20 @@ hipError_t bn_bwd_finalize_launch(const float* partial, int rows, int C, const f
 
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__ dy, const T* __restrict__ mask,
+                                                           const float* __restrict__ mscale,
+                                                           const float* __restrict__ mshift,
                                                            const T* __restrict__ z, const float* __restrict__ coef,
                                                            T* __restrict__ dz, size_t nvec, int C) {
   constexpr int V = Store<T>::VEC;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int c0 = (int)((i * V) % C);
-  float A[V], B[V], C0[V];
+  float A[V], B[V], C0[V], ms[V], mh[V];
 #pragma unroll
-  for (int j = 0; j < V; ++j) { A[j] = coef[c0 + j]; B[j] = coef[C + c0 + j]; C0[j] = coef[2 * C + c0 + j]; }
+  for (int j = 0; j < V; ++j) {
+    A[j] = coef[c0 + j]; B[j] = coef[C + c0 + j]; C0[j] = coef[2 * C + c0 + j];
+    ms[j] = mscale ? mscale[c0 + j] : 1.f; mh[j] = mscale ? mshift[c0 + j] : 0.f;
+  }
   for (; i < nvec; i += stride) {
     float g[V], zz[V];
     Store<T>::load_vec(dy + i * V, g);
@@ -268,7 +278,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
       float mk[V];
       Store<T>::load_vec(mask + i * V, mk);
 #pragma unroll
-      for (int j = 0; j < V; ++j) g[j] = mk[j] > 0.f ? g[j] : 0.f;
+      for (int j = 0; j < V; ++j) g[j] = (mk[j] * ms[j] + mh[j]) > 0.f ? g[j] : 0.f;
     }
 #pragma unroll
     for (int j = 0; j < V; ++j) g[j] = A[j] * g[j] + (B[j] * zz[j] + C0[j]);
@@ -276,16 +286,17 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
   }
 }
 
-hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const void* z, const float* coef,
-                               void* dz, size_t elems, int C, int dtype, hipStream_t s) {
+hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const float* mscale, const float* mshift,
+                               const void* z, const float* coef, void* dz, size_t elems, int C, int dtype,
+                               hipStream_t s) {
   if (dtype == BF16) {
     const size_t nvec = elems / 8;
     hipLaunchKernelGGL(bn_bwd_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, 2048)), dim3(256), 0, s,
-                       (const bf16_t*)dy, (const bf16_t*)mask, (const bf16_t*)z, coef, (bf16_t*)dz, nvec, C);
+                       (const bf16_t*)dy, (const bf16_t*)mask, mscale, mshift, (const bf16_t*)z, coef, (bf16_t*)dz, nvec, C);
   } else {
     const size_t nvec = elems / 4;
     hipLaunchKernelGGL(bn_bwd_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, 2048)), dim3(256), 0, s,
-                       (const float*)dy, (const float*)mask, (const float*)z, coef, (float*)dz, nvec, C);
+                       (const float*)dy, (const float*)mask, mscale, mshift, (const float*)z, coef, (float*)dz, nvec, C);
   }
   return hipGetLastError();
 }
