@@ -52,6 +52,7 @@ struct Unit {  // convolution + batch normalisation
   bool has_dgrad = false;
   int wg_tiled_rows = 0;   // > 0: the LDS-tiled bf16 weight-gradient kernel covers this layer
   int tiled_grid = 0;      // > 0: the LDS-tiled conv kernel covers this layer (forward and dgrad)
+  float* wg_partial = nullptr;  // this layer's weight-gradient partial tiles (kept until the update)
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
   size_t in_elems() const { return (size_t)N * H * W * cin; }
 };
@@ -83,7 +84,8 @@ struct ddg_module {
   std::vector<void*> ring;
   void *Ga = nullptr, *Gb = nullptr, *D1 = nullptr, *D2 = nullptr, *D3 = nullptr;
   float* ws_stat = nullptr; size_t ws_stat_elems = 0;
-  float* ws_wgrad = nullptr; size_t ws_wgrad_elems = 0;
+  PackDesc* pack_descs = nullptr; int n_pack = 0;     // device tables for the whole-module kernels
+  WredDesc* wred_descs = nullptr; int n_wred = 0;
   std::vector<void*> allocs;
   size_t bytes = 0;
   // state
@@ -279,7 +281,9 @@ ddg_status build_plan(ddg_module* m) {
       wgrad_plan(wgd);
       u.wg_tiled_rows = wgrad_tiled_rows(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
       if (u.wg_tiled_rows > 0) wgd.msplit = u.wg_tiled_rows;  // the reduce kernel sums this many rows
-      if (wgrad_partial_elems(wgd) > m->ws_wgrad_elems) m->ws_wgrad_elems = wgrad_partial_elems(wgd);
+      { void* wp = nullptr;
+        DDG_OKAY(dev_alloc(m, &wp, wgrad_partial_elems(wgd) * sizeof(float)));
+        u.wg_partial = (float*)wp; }
       const int bg = bn_bwd_grid(u.out_elems(), u.cout, dt);
       st_e = (size_t)bg * 2 * u.cout;
       if (st_e > m->ws_stat_elems) m->ws_stat_elems = st_e;
@@ -325,8 +329,37 @@ ddg_status build_plan(ddg_module* m) {
   DDG_OKAY(dev_alloc(m, &m->D3, m->max_act * m->esz));
   DDG_OKAY(dev_alloc(m, &p, m->ws_stat_elems * sizeof(float)));
   m->ws_stat = (float*)p;
-  DDG_OKAY(dev_alloc(m, &p, m->ws_wgrad_elems * sizeof(float)));
-  m->ws_wgrad = (float*)p;
+  // device tables: one entry per packed operand / per layer
+  std::vector<PackDesc> pd;
+  std::vector<WredDesc> wd;
+  for (Blk& b : m->blocks)
+    for (Unit& u : b.u) {
+      for (int mode = 0; mode < 2; ++mode) {
+        if (mode == 1 && !u.has_dgrad) continue;
+        PackDesc d{};
+        const int md = mode == 0 ? 0 : (u.tiled_grid > 0 ? 2 : 1);
+        const int kc = md ? u.cout : u.cin, nc = md ? u.cin : u.cout;
+        d.W = m->theta + u.ow; d.wpack = mode == 0 ? u.wpack_f : u.wpack_d;
+        d.Cout = u.cout; d.Cin = u.cin; d.R = u.R; d.mode = md;
+        d.total = (unsigned)conv_wpack_elems(kc, nc, u.R, dt, &d.log2cp, &d.ksteps);
+        d.OCB = nc / 16;
+        pd.push_back(d);
+      }
+      WredDesc w{};
+      w.partial = u.wg_partial; w.dW = m->grad + u.ow; w.rows = u.wg.msplit; w.Cout = u.cout; w.Cin = u.cin;
+      w.R = u.R; w.log2cp = u.wg.log2cp; w.Jp = u.wg.JB * 16;
+      wd.push_back(w);
+    }
+  m->n_pack = (int)pd.size(); m->n_wred = (int)wd.size();
+  if (!d.dry_run && m->n_pack) {
+    DDG_OKAY(dev_alloc(m, &p, pd.size() * sizeof(PackDesc)));
+    m->pack_descs = (PackDesc*)p;
+    DDG_OKAY(dev_alloc(m, &p, wd.size() * sizeof(WredDesc)));
+    m->wred_descs = (WredDesc*)p;
+    if (hipMemcpy(m->pack_descs, pd.data(), pd.size() * sizeof(PackDesc), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(m->wred_descs, wd.data(), wd.size() * sizeof(WredDesc), hipMemcpyHostToDevice) != hipSuccess)
+      return fail(DDG_ERR_DEVICE, "copying the layer tables failed");
+  }
   if (!d.dry_run) {
     hipError_t e = hipMemsetAsync(m->theta, 0, 3 * m->nparams * sizeof(float), m->stream);
     if (e != hipSuccess) return fail(DDG_ERR_DEVICE, "hipMemsetAsync: %s", hipGetErrorString(e));
@@ -337,16 +370,8 @@ ddg_status build_plan(ddg_module* m) {
 // ---- enqueue helpers ---------------------------------------------------------------------
 
 ddg_status pack_all(ddg_module* m) {
-  for (Blk& b : m->blocks)
-    for (Unit& u : b.u) {
-      { Launch L(m, PK_PACK);
-        DDG_TRY(pack_weights_launch(m->theta + u.ow, u.wpack_f, u.cout, u.cin, u.R, 0, m->d.compute, m->stream)); }
-      if (u.has_dgrad) {
-        Launch L(m, PK_PACK);
-        DDG_TRY(pack_weights_launch(m->theta + u.ow, u.wpack_d, u.cout, u.cin, u.R, u.tiled_grid > 0 ? 2 : 1,
-                                    m->d.compute, m->stream));
-      }
-    }
+  Launch L(m, PK_PACK);
+  DDG_TRY(pack_all_launch(m->pack_descs, m->n_pack, m->d.compute, m->stream));
   return DDG_OK;
 }
 
@@ -438,16 +463,15 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
   { Launch L(m, PK_BN_BWD_APPLY);
     DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, dz_buf, E, u.cout, dt, m->stream)); }
   WgradArgs w = u.wg;
-  w.x = x_in; w.dz = dz_buf; w.partial = m->ws_wgrad; w.dW = m->grad + u.ow;
+  w.x = x_in; w.dz = dz_buf; w.partial = u.wg_partial; w.dW = m->grad + u.ow;
   if (u.wg_tiled_rows > 0) {
     Launch L(m, PK_CONV_WGRAD);
-    DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, dz_buf, m->ws_wgrad, u.N, u.H, u.W, u.cin, u.wg_tiled_rows, m->stream));
+    DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.wg_tiled_rows, m->stream));
   } else {
     if (x_scale) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
     Launch L(m, PK_CONV_WGRAD);
     DDG_TRY(wgrad_launch(w, m->stream));
   }
-  { Launch L(m, PK_WGRAD_REDUCE); DDG_TRY(wgrad_reduce_launch(w, m->stream)); }
   if (dx) {
     Launch L(m, PK_CONV_DGRAD);
     if (u.tiled_grid > 0) {
@@ -671,7 +695,11 @@ ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, con
   void* slot = m->ring[s % m->nslots];
   if (!m->tape_is_current) DDG_OKAY(run_forward(m, slot, nullptr));
   m->tape_is_current = false;
-  return run_backward(m, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out);
+  DDG_OKAY(run_backward(m, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out));
+  // every layer's weight-gradient partials -> g (one launch for the module, fixed order)
+  Launch L(m, PK_WGRAD_REDUCE);
+  DDG_TRY(wgrad_reduce_all_launch(m->wred_descs, m->n_wred, m->stream));
+  return DDG_OK;
 }
 
 ddg_status ddg_update(ddg_module* m, long t, float lr) {

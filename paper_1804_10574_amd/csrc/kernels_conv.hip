@@ -245,6 +245,38 @@ __global__ void pack_weights_kernel(const float* __restrict__ W, T* __restrict__
   }
 }
 
+template <typename T>
+__global__ void pack_all_kernel(const PackDesc* __restrict__ descs) {
+  constexpr int KV = Mma<T>::KV;
+  const PackDesc d = descs[blockIdx.y];
+  const int kc = d.mode ? d.Cout : d.Cin, nc = d.mode ? d.Cin : d.Cout;
+  T* wpack = reinterpret_cast<T*>(d.wpack);
+  for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < d.total; i += gridDim.x * blockDim.x) {
+    const int j = (int)(i % KV);
+    const int lane = (int)((i / KV) % 64);
+    const int cb = (int)((i / (KV * 64)) % d.OCB);
+    const int ks = (int)(i / ((unsigned)KV * 64 * d.OCB));
+    const int k = (ks * 4 + lane / 16) * KV + j;
+    const int tap = k >> d.log2cp, c = k & ((1 << d.log2cp) - 1);
+    const int n = cb * 16 + (lane & 15);
+    float v = 0.f;
+    if (tap < d.R * d.R && c < kc && n < nc) {
+      int r = tap / d.R, s = tap % d.R;
+      if (d.mode == 2) { r = d.R - 1 - r; s = d.R - 1 - s; }
+      const int co = d.mode ? c : n, ci = d.mode ? n : c;
+      v = d.W[(((size_t)co * d.Cin + ci) * d.R + r) * d.R + s];
+    }
+    Store<T>::store1(wpack + i, v);
+  }
+}
+
+hipError_t pack_all_launch(const PackDesc* dev_descs, int n, int dtype, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  if (dtype == BF16) hipLaunchKernelGGL(pack_all_kernel<bf16_t>, dim3(16, n), dim3(256), 0, s, dev_descs);
+  else hipLaunchKernelGGL(pack_all_kernel<float>, dim3(16, n), dim3(256), 0, s, dev_descs);
+  return hipGetLastError();
+}
+
 hipError_t pack_weights_launch(const float* W, void* wpack, int Cout, int Cin, int R, int dgrad,
                                int dtype, hipStream_t s) {
   int log2cp, ksteps;

@@ -104,6 +104,40 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs a) {
   }
 }
 
+// All layers of a module: blockIdx.y picks the layer, 16 threads share one output.
+__global__ __launch_bounds__(256) void wgrad_reduce_all_kernel(const WredDesc* __restrict__ descs) {
+  const WredDesc d = descs[blockIdx.y];
+  const int total = d.Cout * d.Jp;
+  __shared__ float red[16][17];
+  const int sub = threadIdx.x & 15, loc = threadIdx.x >> 4;
+  for (int base = blockIdx.x * 16; base < total; base += gridDim.x * 16) {
+    const int e = base + loc;
+    float s = 0.f;
+    if (e < total)
+      for (int sp = sub; sp < d.rows; sp += 16) s += d.partial[(size_t)sp * total + e];
+    __syncthreads();
+    red[loc][sub] = s;
+    __syncthreads();
+    if (sub == 0 && e < total) {
+      float t = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) t += red[loc][i];
+      const int co = e / d.Jp, j = e - co * d.Jp;
+      const int tap = j >> d.log2cp, ci = j & ((1 << d.log2cp) - 1);
+      if (tap < d.R * d.R && ci < d.Cin) {
+        const int r = tap / d.R, sx = tap % d.R;
+        d.dW[(((size_t)co * d.Cin + ci) * d.R + r) * d.R + sx] = t;
+      }
+    }
+  }
+}
+
+hipError_t wgrad_reduce_all_launch(const WredDesc* dev_descs, int n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(wgrad_reduce_all_kernel, dim3(48, n), dim3(256), 0, s, dev_descs);
+  return hipGetLastError();
+}
+
 void wgrad_plan(WgradArgs& a) {
   int l2 = 0;
   while ((1 << l2) < a.Cin) ++l2;
