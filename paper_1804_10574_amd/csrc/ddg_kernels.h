@@ -77,9 +77,20 @@ hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* sh
 // statistics rows), 0 if the shape is not covered. scale/shift: optional relu(in*scale+shift)
 // applied while staging. The same kernel computes the input gradient from an operand packed
 // with mirrored taps.
+// Statistics the epilogue accumulates into partial rows [grid][2][C]:
+//   mode 1: sum / sum of squares of the stored outputs (batch-norm forward of this conv)
+//   mode 2: the outputs are an error gradient v; with the ReLU mask of the layer below applied,
+//           g = (mask*mscale+mshift > 0) ? v : 0, the rows hold sum g and sum g*xhat of that
+//           layer's BN (xhat = (z - zmean)*zinvstd): its bn_bwd_reduce pass comes for free
+struct ConvStat {
+  int mode;
+  float* partial;
+  const void* mask; const float* mscale; const float* mshift;
+  const void* z; const float* zmean; const float* zinvstd;
+};
 int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const void* wpack,
-                             void* out, float* stat_partial, const void* add_g, const void* add_mask,
+                             void* out, const ConvStat& st, const void* add_g, const void* add_mask,
                              int N, int H, int W, int C, int grid, hipStream_t s);
 
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,

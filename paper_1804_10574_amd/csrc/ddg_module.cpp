@@ -381,10 +381,13 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, const float* in_
   int rows;
   if (u.tiled_grid > 0) {
     rows = u.tiled_grid;
+    ConvStat st{};
+    st.mode = 1; st.partial = m->ws_stat;
     Launch L(m, PK_CONV_FPROP);
-    DDG_TRY(conv_tiled_launch(in, in_scale, in_shift, u.wpack_f, u.z, m->ws_stat, nullptr, nullptr, u.N, u.H,
+    DDG_TRY(conv_tiled_launch(in, in_scale, in_shift, u.wpack_f, u.z, st, nullptr, nullptr, u.N, u.H,
                               u.W, u.cin, u.tiled_grid, m->stream));
   } else {
+    if (in_scale) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
     ConvArgs a = u.fprop;
     conv_plan(a);
     rows = a.grid_x;
@@ -443,22 +446,38 @@ ddg_status run_forward(ddg_module* m, const void* in, void* final_out) {
   return DDG_OK;
 }
 
+// What the BN-backward sums of a unit need: its ReLU mask and the tensors they read.
+struct BelowBn {
+  const Unit* u = nullptr;           // the conv+BN unit whose backward comes next
+  const void* mask = nullptr;        // its ReLU was active where mask*mscale+mshift > 0
+  const float* mscale = nullptr;
+  const float* mshift = nullptr;
+};
+
 // BN backward + weight gradient (+ input gradient) of one unit.
 //   dy: gradient w.r.t. the ReLU output that follows this unit's BN; the ReLU was active where
 //       mask > 0 (or mask*mscale+mshift > 0); mask == null: no ReLU in between
+//   stats_rows > 0: the partial rows (sum g, sum g*xhat) of this unit are already in the
+//       statistics workspace, written by the kernel that produced dy (that many rows)
 //   x_in: the unit's conv input, or with x_scale the tensor it derives from by relu(x*s+t)
 //   dx: where the input gradient goes (null: not needed); add_g/add_mask: optional term added
 //       to dx in the same kernel
+//   below: if given and the input-gradient kernel supports it, that kernel also forms the
+//       BN-backward sums of the unit below from dx; *below_done reports whether it did
 ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mask, const float* mscale,
-                         const float* mshift, const void* x_in, const float* x_scale, const float* x_shift,
-                         void* dz_buf, void* dx, const void* add_g, const void* add_mask) {
+                         const float* mshift, int stats_rows, const void* x_in, const float* x_scale,
+                         const float* x_shift, void* dz_buf, void* dx, const void* add_g, const void* add_mask,
+                         const BelowBn* below, int* below_rows) {
   const int dt = m->d.compute;
   const size_t E = u.out_elems();
-  const int rows = bn_bwd_grid(E, u.cout, dt);
-  { Launch L(m, PK_BN_BWD_REDUCE);
-    DDG_TRY(bn_bwd_reduce_launch(dy, mask, mscale, mshift, u.z, u.mean, u.invstd, m->ws_stat, E, u.cout, dt, m->stream)); }
+  if (below_rows) *below_rows = 0;
+  if (stats_rows <= 0) {
+    stats_rows = bn_bwd_grid(E, u.cout, dt);
+    Launch L(m, PK_BN_BWD_REDUCE);
+    DDG_TRY(bn_bwd_reduce_launch(dy, mask, mscale, mshift, u.z, u.mean, u.invstd, m->ws_stat, E, u.cout, dt, m->stream));
+  }
   { Launch L(m, PK_BN_BWD_FINALIZE);
-    DDG_TRY(bn_bwd_finalize_launch(m->ws_stat, rows, u.cout, m->theta + u.og, u.mean, u.invstd,
+    DDG_TRY(bn_bwd_finalize_launch(m->ws_stat, stats_rows, u.cout, m->theta + u.og, u.mean, u.invstd,
                                    (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
   { Launch L(m, PK_BN_BWD_APPLY);
     DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, dz_buf, E, u.cout, dt, m->stream)); }
@@ -475,11 +494,19 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
   if (dx) {
     Launch L(m, PK_CONV_DGRAD);
     if (u.tiled_grid > 0) {
-      DDG_TRY(conv_tiled_launch(dz_buf, nullptr, nullptr, u.wpack_d, dx, nullptr, add_g, add_mask, u.N, u.H, u.W,
+      ConvStat st{};
+      if (below && below->u) {
+        st.mode = 2; st.partial = m->ws_stat;
+        st.mask = below->mask; st.mscale = below->mscale; st.mshift = below->mshift;
+        st.z = below->u->z; st.zmean = below->u->mean; st.zinvstd = below->u->invstd;
+        if (below_rows) *below_rows = u.tiled_grid;
+      }
+      DDG_TRY(conv_tiled_launch(dz_buf, nullptr, nullptr, u.wpack_d, dx, st, add_g, add_mask, u.N, u.H, u.W,
                                 u.cin, u.tiled_grid, m->stream));
     } else {
       ConvArgs a = u.dgrad;
-      a.in = dz_buf; a.wpack = u.wpack_d; a.out = dx; a.stat_partial = nullptr; a.add_g = add_g; a.add_mask = add_mask;
+      a.in = dz_buf; a.wpack = u.wpack_d; a.out = dx; a.stat_partial = nullptr;
+      a.add_g = add_g; a.add_mask = add_mask;
       DDG_TRY(conv_launch(a, m->stream));
     }
   }
@@ -505,41 +532,62 @@ ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const i
     dy = m->Ga;
   }
   void* gnext = (dy == m->Ga) ? m->Gb : m->Ga;  // where this block's input gradient goes
+  int top_rows = 0;   // > 0: the BN sums of this block's last unit are already in the workspace
   for (int bi = nres - 1; bi >= 0; --bi) {
     Blk& b = m->blocks[bi];
     const void* x = (bi == 0) ? in : m->blocks[bi - 1].y;
     const bool want_dx = (bi > 0) || (m->d.k > 1);
     void* dx_dst = nullptr;
     if (want_dx) dx_dst = (bi == 0) ? delta_out : gnext;
+    // the BN whose backward follows this block's input gradient: the last main unit of the
+    // block below (its ReLU mask is that block's output)
+    BelowBn below_blk;
+    if (bi > 0) {
+      Blk& pb = m->blocks[bi - 1];
+      below_blk.u = &pb.u[pb.nmain - 1];
+      below_blk.mask = pb.y;
+    }
+    int next_top_rows = 0;
     if (b.kind == DDG_BLOCK_STEM) {
-      DDG_OKAY(unit_backward(m, b.u[0], dy, b.y, nullptr, nullptr, x, nullptr, nullptr, m->D1, dx_dst, nullptr, nullptr));
+      DDG_OKAY(unit_backward(m, b.u[0], dy, b.y, nullptr, nullptr, top_rows, x, nullptr, nullptr, m->D1,
+                             dx_dst, nullptr, nullptr, bi > 0 ? &below_blk : nullptr, &next_top_rows));
     } else {
       // shortcut term of the input gradient
       const void* add_g = nullptr; const void* add_mask = nullptr;
       if (b.proj) {
         Unit& up = b.u[b.nmain];
-        DDG_OKAY(unit_backward(m, up, dy, b.y, nullptr, nullptr, x, nullptr, nullptr, m->D1, want_dx ? m->D3 : nullptr, nullptr, nullptr));
+        DDG_OKAY(unit_backward(m, up, dy, b.y, nullptr, nullptr, 0, x, nullptr, nullptr, m->D1,
+                               want_dx ? m->D3 : nullptr, nullptr, nullptr, nullptr, nullptr));
         if (want_dx) add_g = m->D3;
       } else if (want_dx) {
         add_g = dy; add_mask = b.y;
       }
       const void* d = dy; const void* mask = b.y;
       const float *msc = nullptr, *msh = nullptr;
+      int stats_rows = top_rows;
       for (int i = b.nmain - 1; i >= 0; --i) {
         Unit& u = b.u[i];
         // the unit's input: the block input, a materialised activation, or the previous unit's
         // conv output with its BN + ReLU applied on the fly
         const void* uin = x; const float *xsc = nullptr, *xsh = nullptr;
+        BelowBn below;
         if (i > 0) {
           if (b.act[i - 1]) uin = b.act[i - 1];
           else { uin = b.u[i - 1].z; xsc = b.u[i - 1].scale; xsh = b.u[i - 1].shift; }
+          below.u = &b.u[i - 1]; below.mask = uin; below.mscale = xsc; below.mshift = xsh;
+        } else {
+          below = below_blk;
         }
         void* udx = (i > 0) ? m->D2 : dx_dst;
-        DDG_OKAY(unit_backward(m, u, d, mask, msc, msh, uin, xsc, xsh, m->D1, udx, i == 0 ? add_g : nullptr,
-                               i == 0 ? add_mask : nullptr));
-        if (i > 0) { d = m->D2; mask = uin; msc = xsc; msh = xsh; }
+        int done = 0;
+        DDG_OKAY(unit_backward(m, u, d, mask, msc, msh, stats_rows, uin, xsc, xsh, m->D1, udx,
+                               i == 0 ? add_g : nullptr, i == 0 ? add_mask : nullptr,
+                               (udx && below.u) ? &below : nullptr, &done));
+        if (i > 0) { d = m->D2; mask = uin; msc = xsc; msh = xsh; stats_rows = done; }
+        else next_top_rows = done;
       }
     }
+    top_rows = next_top_rows;
     if (bi > 0) { dy = gnext; gnext = (gnext == m->Ga) ? m->Gb : m->Ga; }
   }
   return DDG_OK;

@@ -24,7 +24,7 @@ struct ConvTiledArgs {
   const float* shift;
   const bf16_t* wpack;     // packed operand [ks][C/16][64][8]
   bf16_t* out;             // [N,H,W,C]
-  float* stat_partial;     // [grid][2][C] or null
+  ConvStat st;             // epilogue statistics: partial rows [grid][2][C]
   const bf16_t* add_g;     // optional epilogue term, same layout as out
   const bf16_t* add_mask;  // add_g counts only where add_mask > 0
   int N, H;
@@ -90,6 +90,18 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   }
 
   float ssum[4] = {0.f, 0.f, 0.f, 0.f}, ssq[4] = {0.f, 0.f, 0.f, 0.f};
+  // mode 2: per-channel constants of the BN below, for this lane's 4 channels
+  float bmu[4], bis[4], bms[4], bmh[4];
+  const bf16_t* st_mask = reinterpret_cast<const bf16_t*>(a.st.mask);
+  const bf16_t* st_z = reinterpret_cast<const bf16_t*>(a.st.z);
+  if (a.st.mode == 2) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = cb * 16 + lg * 4 + j;
+      bmu[j] = a.st.zmean[c]; bis[j] = a.st.zinvstd[c];
+      bms[j] = a.st.mscale ? a.st.mscale[c] : 1.f; bmh[j] = a.st.mscale ? a.st.mshift[c] : 0.f;
+    }
+  }
   const int tiles_per_img = a.H / TH;
 
   uint4 stage[PT];
@@ -180,16 +192,31 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
         for (int j = 0; j < 4; ++j) v[j] += g[j];
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        v[j] = Store<bf16_t>::round(v[j]);
-        ssum[j] += v[j];
-        ssq[j] += v[j] * v[j];
-      }
+      for (int j = 0; j < 4; ++j) v[j] = Store<bf16_t>::round(v[j]);
       Store<bf16_t>::store4(a.out + idx, v[0], v[1], v[2], v[3]);
+      if (a.st.mode == 1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { ssum[j] += v[j]; ssq[j] += v[j] * v[j]; }
+      } else if (a.st.mode == 2) {
+        float mk[4], zz[4];
+        Store<bf16_t>::load4(st_mask + idx, mk);
+        if (st_z == st_mask) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) zz[j] = mk[j];
+        } else {
+          Store<bf16_t>::load4(st_z + idx, zz);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float g = (mk[j] * bms[j] + bmh[j]) > 0.f ? v[j] : 0.f;
+          ssum[j] += g;
+          ssq[j] += g * ((zz[j] - bmu[j]) * bis[j]);
+        }
+      }
     }
   }
 
-  if (a.stat_partial) {
+  if (a.st.mode != 0) {
     // channel cb*16 + lg*4 + j: sum over the 16 pixel lanes, then over the PG waves of this cb
     __shared__ float red[4][2][16];
 #pragma unroll
@@ -209,7 +236,7 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
       float s = 0.f;
 #pragma unroll
       for (int g = 0; g < PG; ++g) s += red[cbb * PG + g][which][cl];
-      a.stat_partial[((size_t)blockIdx.x * 2 + which) * C + c] = s;
+      a.st.partial[((size_t)blockIdx.x * 2 + which) * C + c] = s;
     }
   }
 }
@@ -230,11 +257,11 @@ static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStrea
 }
 
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const void* wpack,
-                             void* out, float* stat_partial, const void* add_g, const void* add_mask,
+                             void* out, const ConvStat& st, const void* add_g, const void* add_mask,
                              int N, int H, int W, int C, int grid, hipStream_t s) {
   ConvTiledArgs a;
   a.in = (const bf16_t*)in; a.scale = scale; a.shift = shift; a.wpack = (const bf16_t*)wpack;
-  a.out = (bf16_t*)out; a.stat_partial = stat_partial; a.add_g = (const bf16_t*)add_g;
+  a.out = (bf16_t*)out; a.st = st; a.add_g = (const bf16_t*)add_g;
   a.add_mask = (const bf16_t*)add_mask; a.N = N; a.H = H; a.tiles = N * (H / 8);
   if (C == 16 && W == 32) return conv_tiled_launch_t<16, 32>(a, grid, s);
   if (C == 32 && W == 16) return conv_tiled_launch_t<32, 16>(a, grid, s);
