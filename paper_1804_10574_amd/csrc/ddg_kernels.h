@@ -11,6 +11,19 @@ enum DType { F32 = 0, BF16 = 1 };
 inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
 inline int mma_kv(int dt) { return dt == BF16 ? 8 : 1; }
 
+// Partial rows of a batch-norm reduction that the consuming kernel finalises itself
+// (partial == nullptr: the per-channel vectors are already final).
+struct BnRows {        // forward: rows [rows][2][C] of (sum, sum of squares)
+  const float* partial; int rows;
+  const float* gamma; const float* beta; float count, eps;
+  float* mean; float* invstd; float* scale; float* shift;   // written by workgroup 0
+};
+struct BnBwdRows {     // backward: rows of (sum g, sum g*xhat)
+  const float* partial; int rows;
+  const float* gamma; const float* mean; const float* invstd; float count;
+  float* dgamma; float* dbeta;                              // written by workgroup 0
+};
+
 // Implicit-GEMM convolution on the matrix cores. One kernel serves the forward
 // convolution and the gradient w.r.t. the input:
 //   fprop: out[n,oh,ow,:] = sum_taps in[n, oh*st+r-pad, ow*st+s-pad, :] . W
@@ -89,19 +102,21 @@ struct ConvStat {
   const void* z; const float* zmean; const float* zinvstd;
 };
 int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
-hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const void* wpack,
-                             void* out, const ConvStat& st, const void* add_g, const void* add_mask,
-                             int N, int H, int W, int C, int grid, hipStream_t s);
+// in_rows (optional): scale/shift are not final yet; the kernel derives them from these rows.
+hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
+                             const void* wpack, void* out, const ConvStat& st, const void* add_g,
+                             const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s);
 
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
 // shift=beta-mean*scale.
 hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                               const float* beta, float count, float eps, float* mean, float* invstd,
                               float* scale, float* shift, hipStream_t s);
-// y = [relu](z*scale+shift [+ res*rscale+rshift | + res])
-hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const void* res,
-                           const float* rscale, const float* rshift, void* y, size_t elems, int C,
-                           int relu, int dtype, hipStream_t s);
+// y = [relu](z*scale+shift [+ res*rscale+rshift | + res]); zrows / rrows (optional, C <= 64):
+// derive scale/shift (rscale/rshift) from partial rows instead of reading final vectors.
+hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const BnRows* zrows,
+                           const void* res, const float* rscale, const float* rshift, const BnRows* rrows,
+                           void* y, size_t elems, int C, int relu, int dtype, hipStream_t s);
 // g = dy where the ReLU that follows was active, else 0: active means mask > 0, or
 // mask*mscale+mshift > 0 when mscale is given (the mask tensor is then the conv output the
 // activation derives from); mask == nullptr: g = dy. partial[grid][2][C] = (sum g, sum g*xhat)
@@ -113,9 +128,10 @@ hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const float* m
 hipError_t bn_bwd_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                                   const float* mean, const float* invstd, float count, float* dgamma,
                                   float* dbeta, float* coef, hipStream_t s);
+// coef: final coefficients [3][C], or rows (optional, C <= 64) to derive them from.
 hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const float* mscale, const float* mshift,
-                               const void* z, const float* coef, void* dz, size_t elems, int C, int dtype,
-                               hipStream_t s);
+                               const void* z, const float* coef, const BnBwdRows* rows, void* dz, size_t elems,
+                               int C, int dtype, hipStream_t s);
 
 // Head: global average pool, linear, softmax cross-entropy (mean over the batch) and its gradients.
 struct HeadArgs {

@@ -53,6 +53,10 @@ struct Unit {  // convolution + batch normalisation
   int wg_tiled_rows = 0;   // > 0: the LDS-tiled bf16 weight-gradient kernel covers this layer
   int tiled_grid = 0;      // > 0: the LDS-tiled conv kernel covers this layer (forward and dgrad)
   float* wg_partial = nullptr;  // this layer's weight-gradient partial tiles (kept until the update)
+  float* fstat = nullptr;       // partial rows of the forward statistics [frows][2][cout]
+  float* bstat = nullptr;       // partial rows of the BN-backward sums [brows][2][cout]
+  int frows = 0;                // rows written by the last forward conv
+  bool small_c() const { return cout <= 64; }   // consumers finalise the rows themselves
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
   size_t in_elems() const { return (size_t)N * H * W * cin; }
 };
@@ -264,6 +268,12 @@ ddg_status build_plan(ddg_module* m) {
       if (u.tiled_grid > f.grid_x) f.grid_x = u.tiled_grid;   // sizes the statistics workspace
       size_t st_e = (size_t)f.grid_x * 2 * u.cout;
       if (st_e > m->ws_stat_elems) m->ws_stat_elems = st_e;
+      { void* sp = nullptr;
+        DDG_OKAY(dev_alloc(m, &sp, st_e * sizeof(float)));
+        u.fstat = (float*)sp;
+        // backward rows come from bn_bwd_reduce (<= 256 rows) or from a tiled input-gradient kernel (<= 512)
+        DDG_OKAY(dev_alloc(m, &sp, (size_t)512 * 2 * u.cout * sizeof(float)));
+        u.bstat = (float*)sp; }
       // input gradient
       if (u.has_dgrad) {
         ConvArgs& g = u.dgrad;
@@ -375,71 +385,96 @@ ddg_status pack_all(ddg_module* m) {
   return DDG_OK;
 }
 
-// conv + batch statistics of one unit: in -> u.z, u.mean/invstd/scale/shift. With in_scale the
-// input is relu(in*in_scale+in_shift), formed while loading (LDS-tiled kernel only).
-ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, const float* in_scale, const float* in_shift) {
-  int rows;
+// The forward statistics of u as partial rows for a consuming kernel.
+BnRows fwd_rows(ddg_module* m, Unit& u) {
+  BnRows r{};
+  r.partial = u.fstat; r.rows = u.frows;
+  r.gamma = m->theta + u.og; r.beta = m->theta + u.ob;
+  r.count = (float)((size_t)u.N * u.P * u.Q); r.eps = m->d.bn_eps;
+  r.mean = u.mean; r.invstd = u.invstd; r.scale = u.scale; r.shift = u.shift;
+  return r;
+}
+
+// conv of one unit: in -> u.z plus partial rows of its batch statistics. For cout <= 64 the
+// consumer of the BN output derives mean/invstd/scale/shift from the rows (and stores them);
+// wider layers get a finalise launch here. `src`, if given, is the unit whose BN + ReLU
+// produces this conv's input from `in` while loading (LDS-tiled kernel only).
+ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src) {
   if (u.tiled_grid > 0) {
-    rows = u.tiled_grid;
+    u.frows = u.tiled_grid;
     ConvStat st{};
-    st.mode = 1; st.partial = m->ws_stat;
+    st.mode = 1; st.partial = u.fstat;
+    BnRows ir{};
+    const bool from_rows = src && src->small_c();
+    if (from_rows) ir = fwd_rows(m, *src);
     Launch L(m, PK_CONV_FPROP);
-    DDG_TRY(conv_tiled_launch(in, in_scale, in_shift, u.wpack_f, u.z, st, nullptr, nullptr, u.N, u.H,
-                              u.W, u.cin, u.tiled_grid, m->stream));
+    DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? src->scale : nullptr, (src && !from_rows) ? src->shift : nullptr,
+                              from_rows ? &ir : nullptr, u.wpack_f, u.z, st, nullptr, nullptr, u.N, u.H, u.W,
+                              u.cin, u.tiled_grid, m->stream));
   } else {
-    if (in_scale) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
+    if (src) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
     ConvArgs a = u.fprop;
     conv_plan(a);
-    rows = a.grid_x;
-    a.in = in; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = m->ws_stat; a.add_g = nullptr; a.add_mask = nullptr;
+    u.frows = a.grid_x;
+    a.in = in; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = u.fstat; a.add_g = nullptr; a.add_mask = nullptr;
     Launch L(m, PK_CONV_FPROP);
     DDG_TRY(conv_launch(a, m->stream));
   }
-  { Launch L(m, PK_BN_FINALIZE);
-    DDG_TRY(bn_finalize_launch(m->ws_stat, rows, u.cout, m->theta + u.og, m->theta + u.ob,
+  if (!u.small_c()) {
+    Launch L(m, PK_BN_FINALIZE);
+    DDG_TRY(bn_finalize_launch(u.fstat, u.frows, u.cout, m->theta + u.og, m->theta + u.ob,
                                (float)((size_t)u.N * u.P * u.Q), m->d.bn_eps, u.mean, u.invstd, u.scale,
-                               u.shift, m->stream)); }
+                               u.shift, m->stream));
+  }
+  return DDG_OK;
+}
+
+// y = relu(bn(u.z) [+ shortcut]); the shortcut is `res` itself or, with ru, bn(ru->z) of a
+// projection unit.
+ddg_status apply_bn(ddg_module* m, Unit& u, const void* res, Unit* ru, void* y) {
+  BnRows zr{}, rr{};
+  const bool zrows = u.small_c(), rrows = ru && ru->small_c();
+  if (zrows) zr = fwd_rows(m, u);
+  if (rrows) rr = fwd_rows(m, *ru);
+  Launch L(m, PK_BN_APPLY);
+  DDG_TRY(bn_apply_launch(u.z, u.scale, u.shift, zrows ? &zr : nullptr, ru ? ru->z : res,
+                          ru ? ru->scale : nullptr, ru ? ru->shift : nullptr, rrows ? &rr : nullptr, y,
+                          u.out_elems(), u.cout, 1, m->d.compute, m->stream));
   return DDG_OK;
 }
 
 // Forward through all residual blocks. `final_out`, if given, receives the last block's
 // output instead of the module's own buffer (used when the tape is not needed).
 ddg_status run_forward(ddg_module* m, const void* in, void* final_out) {
-  const int dt = m->d.compute;
   const void* x = in;
   const int nres = (int)m->blocks.size() - (m->d.num_classes > 0 ? 1 : 0);
   for (int bi = 0; bi < nres; ++bi) {
     Blk& b = m->blocks[bi];
     void* yout = (bi == nres - 1 && final_out) ? final_out : b.y;
     const void* cur = x;
-    const float *csc = nullptr, *csh = nullptr;   // pending relu(bn(.)) of `cur`
+    Unit* src = nullptr;   // pending relu(bn(.)) of `cur`
     for (int i = 0; i < b.nmain; ++i) {
       Unit& u = b.u[i];
-      DDG_OKAY(unit_forward(m, u, cur, csc, csh));
-      csc = csh = nullptr;
+      DDG_OKAY(unit_forward(m, u, cur, src));
+      src = nullptr;
       if (i + 1 < b.nmain) {
         if (b.act[i]) {
-          Launch L(m, PK_BN_APPLY);
-          DDG_TRY(bn_apply_launch(u.z, u.scale, u.shift, nullptr, nullptr, nullptr, b.act[i], u.out_elems(),
-                                  u.cout, 1, dt, m->stream));
+          DDG_OKAY(apply_bn(m, u, nullptr, nullptr, b.act[i]));
           cur = b.act[i];
         } else {
-          cur = u.z; csc = u.scale; csh = u.shift;   // the next conv applies BN + ReLU while loading
+          cur = u.z; src = &u;   // the next conv applies BN + ReLU while loading
         }
       }
     }
     Unit& ul = b.u[b.nmain - 1];
     if (b.kind == DDG_BLOCK_STEM) {
-      Launch L(m, PK_BN_APPLY);
-      DDG_TRY(bn_apply_launch(ul.z, ul.scale, ul.shift, nullptr, nullptr, nullptr, yout, ul.out_elems(), ul.cout, 1, dt, m->stream));
+      DDG_OKAY(apply_bn(m, ul, nullptr, nullptr, yout));
     } else if (b.proj) {
       Unit& up = b.u[b.nmain];
-      DDG_OKAY(unit_forward(m, up, x, nullptr, nullptr));
-      Launch L(m, PK_BN_APPLY);
-      DDG_TRY(bn_apply_launch(ul.z, ul.scale, ul.shift, up.z, up.scale, up.shift, yout, ul.out_elems(), ul.cout, 1, dt, m->stream));
+      DDG_OKAY(unit_forward(m, up, x, nullptr));
+      DDG_OKAY(apply_bn(m, ul, nullptr, &up, yout));
     } else {
-      Launch L(m, PK_BN_APPLY);
-      DDG_TRY(bn_apply_launch(ul.z, ul.scale, ul.shift, x, nullptr, nullptr, yout, ul.out_elems(), ul.cout, 1, dt, m->stream));
+      DDG_OKAY(apply_bn(m, ul, x, nullptr, yout));
     }
     x = yout;
   }
@@ -474,13 +509,22 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
   if (stats_rows <= 0) {
     stats_rows = bn_bwd_grid(E, u.cout, dt);
     Launch L(m, PK_BN_BWD_REDUCE);
-    DDG_TRY(bn_bwd_reduce_launch(dy, mask, mscale, mshift, u.z, u.mean, u.invstd, m->ws_stat, E, u.cout, dt, m->stream));
+    DDG_TRY(bn_bwd_reduce_launch(dy, mask, mscale, mshift, u.z, u.mean, u.invstd, u.bstat, E, u.cout, dt, m->stream));
   }
-  { Launch L(m, PK_BN_BWD_FINALIZE);
-    DDG_TRY(bn_bwd_finalize_launch(m->ws_stat, stats_rows, u.cout, m->theta + u.og, u.mean, u.invstd,
-                                   (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
-  { Launch L(m, PK_BN_BWD_APPLY);
-    DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, dz_buf, E, u.cout, dt, m->stream)); }
+  if (u.small_c()) {
+    // the apply kernel derives dgamma, dbeta and its coefficients from the rows
+    BnBwdRows br{};
+    br.partial = u.bstat; br.rows = stats_rows; br.gamma = m->theta + u.og; br.mean = u.mean; br.invstd = u.invstd;
+    br.count = (float)((size_t)u.N * u.P * u.Q); br.dgamma = m->grad + u.og; br.dbeta = m->grad + u.ob;
+    Launch L(m, PK_BN_BWD_APPLY);
+    DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, nullptr, &br, dz_buf, E, u.cout, dt, m->stream));
+  } else {
+    { Launch L(m, PK_BN_BWD_FINALIZE);
+      DDG_TRY(bn_bwd_finalize_launch(u.bstat, stats_rows, u.cout, m->theta + u.og, u.mean, u.invstd,
+                                     (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
+    Launch L(m, PK_BN_BWD_APPLY);
+    DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
+  }
   WgradArgs w = u.wg;
   w.x = x_in; w.dz = dz_buf; w.partial = u.wg_partial; w.dW = m->grad + u.ow;
   if (u.wg_tiled_rows > 0) {
@@ -496,12 +540,12 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     if (u.tiled_grid > 0) {
       ConvStat st{};
       if (below && below->u) {
-        st.mode = 2; st.partial = m->ws_stat;
+        st.mode = 2; st.partial = below->u->bstat;
         st.mask = below->mask; st.mscale = below->mscale; st.mshift = below->mshift;
         st.z = below->u->z; st.zmean = below->u->mean; st.zinvstd = below->u->invstd;
         if (below_rows) *below_rows = u.tiled_grid;
       }
-      DDG_TRY(conv_tiled_launch(dz_buf, nullptr, nullptr, u.wpack_d, dx, st, add_g, add_mask, u.N, u.H, u.W,
+      DDG_TRY(conv_tiled_launch(dz_buf, nullptr, nullptr, nullptr, u.wpack_d, dx, st, add_g, add_mask, u.N, u.H, u.W,
                                 u.cin, u.tiled_grid, m->stream));
     } else {
       ConvArgs a = u.dgrad;

@@ -15,6 +15,8 @@
 // (sum, sum of squares of the stored values) in registers; one partial row per workgroup.
 #include "ddg_device.h"
 #include "ddg_kernels.h"
+#include "ddg_stats.h"
+#include <cstdlib>
 
 namespace ddg {
 
@@ -22,6 +24,7 @@ struct ConvTiledArgs {
   const bf16_t* in;        // [N,H,W,C]
   const float* scale;      // optional input transform relu(in*scale+shift)
   const float* shift;
+  BnRows in_rows;          // in_rows.partial != null: scale/shift come from these partial rows
   const bf16_t* wpack;     // packed operand [ks][C/16][64][8]
   bf16_t* out;             // [N,H,W,C]
   ConvStat st;             // epilogue statistics: partial rows [grid][2][C]
@@ -64,11 +67,8 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   // staging: chunk v -> (pixel of the halo tile, 8-channel chunk); a thread's channel chunk is
   // the same for all its chunks because 256 % CH == 0
   const int my_ch = tid % CH;
+  const bool xform = a.scale != nullptr || a.in_rows.partial != nullptr;
   float tsc[8], tsh[8];
-  if (a.scale) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { tsc[j] = a.scale[my_ch * 8 + j]; tsh[j] = a.shift[my_ch * 8 + j]; }
-  }
 
   // per-lane LDS byte offsets of the 4 pixel-blocks (tap 0,0; channel 0)
   int pbase[4];
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
       const int v = tid + i * 256;
       if (v < NCHUNK) {
         uint4 q = stage[i];
-        if (a.scale && inimg[i]) {
+        if (xform && inimg[i]) {
           float f[8];
           f[0] = __uint_as_float(q.x << 16); f[1] = __uint_as_float(q.x & 0xffff0000u);
           f[2] = __uint_as_float(q.y << 16); f[3] = __uint_as_float(q.y & 0xffff0000u);
@@ -152,6 +152,16 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
 
   int t = blockIdx.x;
   if (t < a.tiles) issue_loads(t);
+  // per-channel transform of the input; while the first tile's loads are in flight
+  if (a.in_rows.partial) {
+    __shared__ float s_sc[C], s_sh[C];
+    bn_fwd_from_rows(a.in_rows, C, s_sc, s_sh, blockIdx.x == 0);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { tsc[j] = s_sc[my_ch * 8 + j]; tsh[j] = s_sh[my_ch * 8 + j]; }
+  } else if (a.scale) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { tsc[j] = a.scale[my_ch * 8 + j]; tsh[j] = a.shift[my_ch * 8 + j]; }
+  }
   for (; t < a.tiles; t += gridDim.x) {
     __syncthreads();            // the previous tile has been consumed
     write_stage();
@@ -246,7 +256,9 @@ int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, i
   if (!((Cin == 16 && W == 32) || (Cin == 32 && W == 16) || (Cin == 64 && W == 8))) return 0;
   if (H % 8 != 0) return 0;
   const int tiles = N * (H / 8);
-  return tiles < 512 ? tiles : 512;
+  int cap = 512;
+  if (const char* e = getenv("DDG_TUNE_CONV_GRID")) cap = atoi(e) > 0 ? atoi(e) : cap;
+  return tiles < cap ? tiles : cap;
 }
 
 template <int C, int W>
@@ -256,11 +268,12 @@ static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStrea
   return hipGetLastError();
 }
 
-hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const void* wpack,
-                             void* out, const ConvStat& st, const void* add_g, const void* add_mask,
-                             int N, int H, int W, int C, int grid, hipStream_t s) {
+hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
+                             const void* wpack, void* out, const ConvStat& st, const void* add_g,
+                             const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s) {
   ConvTiledArgs a;
   a.in = (const bf16_t*)in; a.scale = scale; a.shift = shift; a.wpack = (const bf16_t*)wpack;
+  if (in_rows) a.in_rows = *in_rows; else a.in_rows = BnRows{};
   a.out = (bf16_t*)out; a.st = st; a.add_g = (const bf16_t*)add_g;
   a.add_mask = (const bf16_t*)add_mask; a.N = N; a.H = H; a.tiles = N * (H / 8);
   if (C == 16 && W == 32) return conv_tiled_launch_t<16, 32>(a, grid, s);

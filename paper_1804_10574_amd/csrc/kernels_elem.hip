@@ -8,6 +8,7 @@
 // fixed order in double precision (deterministic, no atomics).
 #include "ddg_device.h"
 #include "ddg_kernels.h"
+#include "ddg_stats.h"
 
 namespace ddg {
 
@@ -60,14 +61,18 @@ hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ z, const float* __restrict__ scale,
-                                                       const float* __restrict__ shift, const T* __restrict__ res,
+                                                       const float* __restrict__ shift, BnRows zrows,
+                                                       const T* __restrict__ res,
                                                        const float* __restrict__ rscale,
-                                                       const float* __restrict__ rshift, T* __restrict__ y,
-                                                       size_t nvec, int C, int relu) {
+                                                       const float* __restrict__ rshift, BnRows rrows,
+                                                       T* __restrict__ y, size_t nvec, int C, int relu) {
   constexpr int V = Store<T>::VEC;
   const size_t stride = (size_t)gridDim.x * blockDim.x;  // host makes stride*V a multiple of C
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int c0 = (int)((i * V) % C);
+  __shared__ float s_sc[STATS_CMAX], s_sh[STATS_CMAX], s_rs[STATS_CMAX], s_rh[STATS_CMAX];
+  if (zrows.partial) { bn_fwd_from_rows(zrows, C, s_sc, s_sh, blockIdx.x == 0); scale = s_sc; shift = s_sh; }
+  if (rrows.partial) { bn_fwd_from_rows(rrows, C, s_rs, s_rh, blockIdx.x == 0); rscale = s_rs; rshift = s_rh; }
   float sc[V], sh[V], rs[V], rh[V];
 #pragma unroll
   for (int j = 0; j < V; ++j) {
@@ -106,17 +111,20 @@ static int elem_grid(size_t nvec, int C, int V, int max_blocks) {
   return (int)blocks;
 }
 
-hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const void* res,
-                           const float* rscale, const float* rshift, void* y, size_t elems, int C,
-                           int relu, int dtype, hipStream_t s) {
+hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const BnRows* zrows,
+                           const void* res, const float* rscale, const float* rshift, const BnRows* rrows,
+                           void* y, size_t elems, int C, int relu, int dtype, hipStream_t s) {
+  const BnRows zr = zrows ? *zrows : BnRows{}, rr = rrows ? *rrows : BnRows{};
+  // every workgroup re-derives the per-channel vectors from the rows: keep the grid moderate
+  const int maxb = (zrows || rrows) ? 512 : 2048;
   if (dtype == BF16) {
     const size_t nvec = elems / 8;
-    hipLaunchKernelGGL(bn_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, 2048)), dim3(256), 0, s,
-                       (const bf16_t*)z, scale, shift, (const bf16_t*)res, rscale, rshift, (bf16_t*)y, nvec, C, relu);
+    hipLaunchKernelGGL(bn_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, maxb)), dim3(256), 0, s,
+                       (const bf16_t*)z, scale, shift, zr, (const bf16_t*)res, rscale, rshift, rr, (bf16_t*)y, nvec, C, relu);
   } else {
     const size_t nvec = elems / 4;
-    hipLaunchKernelGGL(bn_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, 2048)), dim3(256), 0, s,
-                       (const float*)z, scale, shift, (const float*)res, rscale, rshift, (float*)y, nvec, C, relu);
+    hipLaunchKernelGGL(bn_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, maxb)), dim3(256), 0, s,
+                       (const float*)z, scale, shift, zr, (const float*)res, rscale, rshift, rr, (float*)y, nvec, C, relu);
   }
   return hipGetLastError();
 }
@@ -259,11 +267,13 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
                                                            const float* __restrict__ mscale,
                                                            const float* __restrict__ mshift,
                                                            const T* __restrict__ z, const float* __restrict__ coef,
-                                                           T* __restrict__ dz, size_t nvec, int C) {
+                                                           BnBwdRows rows, T* __restrict__ dz, size_t nvec, int C) {
   constexpr int V = Store<T>::VEC;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int c0 = (int)((i * V) % C);
+  __shared__ float s_coef[3 * STATS_CMAX];
+  if (rows.partial) { bn_bwd_from_rows(rows, C, s_coef, blockIdx.x == 0); coef = s_coef; }
   float A[V], B[V], C0[V], ms[V], mh[V];
 #pragma unroll
   for (int j = 0; j < V; ++j) {
@@ -287,16 +297,18 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
 }
 
 hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const float* mscale, const float* mshift,
-                               const void* z, const float* coef, void* dz, size_t elems, int C, int dtype,
-                               hipStream_t s) {
+                               const void* z, const float* coef, const BnBwdRows* rows, void* dz, size_t elems,
+                               int C, int dtype, hipStream_t s) {
+  const BnBwdRows br = rows ? *rows : BnBwdRows{};
+  const int maxb = rows ? 512 : 2048;
   if (dtype == BF16) {
     const size_t nvec = elems / 8;
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, 2048)), dim3(256), 0, s,
-                       (const bf16_t*)dy, (const bf16_t*)mask, mscale, mshift, (const bf16_t*)z, coef, (bf16_t*)dz, nvec, C);
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, maxb)), dim3(256), 0, s,
+                       (const bf16_t*)dy, (const bf16_t*)mask, mscale, mshift, (const bf16_t*)z, coef, br, (bf16_t*)dz, nvec, C);
   } else {
     const size_t nvec = elems / 4;
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, 2048)), dim3(256), 0, s,
-                       (const float*)dy, (const float*)mask, mscale, mshift, (const float*)z, coef, (float*)dz, nvec, C);
+    hipLaunchKernelGGL(bn_bwd_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, maxb)), dim3(256), 0, s,
+                       (const float*)dy, (const float*)mask, mscale, mshift, (const float*)z, coef, br, (float*)dz, nvec, C);
   }
   return hipGetLastError();
 }
