@@ -82,9 +82,17 @@ hipError_t wgrad_reduce_all_launch(const WredDesc* dev_descs, int n, hipStream_t
 // LDS-tiled bf16 weight gradient for 3x3/stride-1 layers with 16/32/64 channels. Returns 0 rows
 // when the shape is not covered. x may be the saved conv output the activation derives from:
 // then scale/shift give relu(x*scale+shift) on the fly (nullptr: use x as stored).
+// fuse (optional): the kernel forms dz itself, dz = A*g + B*z + C0 with g = dy where
+// mask*mscale+mshift > 0 (mask null: g = dy), coefficients from `coef` or derived from `rows`,
+// and writes it to dz_out for the input-gradient kernel: the BN-backward apply pass is absorbed.
+struct WgradFuse {
+  const void* dy; const void* mask; const float* mscale; const float* mshift;
+  const void* z; const float* coef; const BnBwdRows* rows; void* dz_out;
+};
 int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
 hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* shift, const void* dz,
-                              float* partial, int N, int H, int W, int C, int rows, hipStream_t s);
+                              const WgradFuse* fuse, float* partial, int N, int H, int W, int C, int rows,
+                              hipStream_t s);
 
 // LDS-tiled 3x3/stride-1 convolution for 16/32/64 channels (bf16). Returns the grid (= number of
 // statistics rows), 0 if the shape is not covered. scale/shift: optional relu(in*scale+shift)

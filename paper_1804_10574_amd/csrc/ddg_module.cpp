@@ -511,26 +511,32 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     Launch L(m, PK_BN_BWD_REDUCE);
     DDG_TRY(bn_bwd_reduce_launch(dy, mask, mscale, mshift, u.z, u.mean, u.invstd, u.bstat, E, u.cout, dt, m->stream));
   }
-  if (u.small_c()) {
-    // the apply kernel derives dgamma, dbeta and its coefficients from the rows
-    BnBwdRows br{};
-    br.partial = u.bstat; br.rows = stats_rows; br.gamma = m->theta + u.og; br.mean = u.mean; br.invstd = u.invstd;
-    br.count = (float)((size_t)u.N * u.P * u.Q); br.dgamma = m->grad + u.og; br.dbeta = m->grad + u.ob;
-    Launch L(m, PK_BN_BWD_APPLY);
-    DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, nullptr, &br, dz_buf, E, u.cout, dt, m->stream));
-  } else {
-    { Launch L(m, PK_BN_BWD_FINALIZE);
-      DDG_TRY(bn_bwd_finalize_launch(u.bstat, stats_rows, u.cout, m->theta + u.og, u.mean, u.invstd,
-                                     (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
-    Launch L(m, PK_BN_BWD_APPLY);
-    DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
-  }
+  BnBwdRows br{};
+  br.partial = u.bstat; br.rows = stats_rows; br.gamma = m->theta + u.og; br.mean = u.mean; br.invstd = u.invstd;
+  br.count = (float)((size_t)u.N * u.P * u.Q); br.dgamma = m->grad + u.og; br.dbeta = m->grad + u.ob;
   WgradArgs w = u.wg;
   w.x = x_in; w.dz = dz_buf; w.partial = u.wg_partial; w.dW = m->grad + u.ow;
   if (u.wg_tiled_rows > 0) {
+    // one kernel: dz = BN-backward(dy) formed while staging (coefficients from the rows),
+    // written to dz_buf for the input gradient, and contracted with the input for dW
+    WgradFuse f{};
+    f.dy = dy; f.mask = mask; f.mscale = mscale; f.mshift = mshift; f.z = u.z; f.coef = nullptr; f.rows = &br;
+    f.dz_out = dz_buf;
     Launch L(m, PK_CONV_WGRAD);
-    DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.wg_tiled_rows, m->stream));
+    DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, nullptr, &f, u.wg_partial, u.N, u.H, u.W, u.cin,
+                               u.wg_tiled_rows, m->stream));
   } else {
+    if (u.small_c()) {
+      // the apply kernel derives dgamma, dbeta and its coefficients from the rows
+      Launch L(m, PK_BN_BWD_APPLY);
+      DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, nullptr, &br, dz_buf, E, u.cout, dt, m->stream));
+    } else {
+      { Launch L(m, PK_BN_BWD_FINALIZE);
+        DDG_TRY(bn_bwd_finalize_launch(u.bstat, stats_rows, u.cout, m->theta + u.og, u.mean, u.invstd,
+                                       (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
+      Launch L(m, PK_BN_BWD_APPLY);
+      DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
+    }
     if (x_scale) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
     Launch L(m, PK_CONV_WGRAD);
     DDG_TRY(wgrad_launch(w, m->stream));

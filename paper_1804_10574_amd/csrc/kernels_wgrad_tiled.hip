@@ -12,11 +12,17 @@
 // not nine. The activation a can be produced on the fly from the saved conv output:
 // a = relu(z*scale + shift) is applied while staging (scale == nullptr: use x as stored).
 //
+// The error gradient dz can likewise be formed while staging: with dy given, the kernel applies
+// the ReLU mask and the batch-norm backward formula dz = A*g + B*z + C0 (coefficients final, or
+// derived from the partial rows of the BN-backward sums), uses dz for the contraction and
+// writes it out once for the input-gradient kernel that follows: no separate apply pass.
+//
 // A workgroup walks over tiles of 8 image rows, keeps its accumulators in registers across
 // tiles, and writes one partial tile at the end; wgrad_reduce_kernel adds the partials in a
 // fixed order (deterministic).
 #include "ddg_device.h"
 #include "ddg_kernels.h"
+#include "ddg_stats.h"
 #include <cstdlib>
 
 namespace ddg {
@@ -25,7 +31,10 @@ struct WgradTiledArgs {
   const bf16_t* x;       // [N,H,W,CIN] conv input, or the conv output it is derived from
   const float* scale;    // optional per-channel transform of x: relu(x*scale+shift)
   const float* shift;
-  const bf16_t* dz;      // [N,H,W,COUT]
+  const bf16_t* dz;      // [N,H,W,COUT] (ignored when dy is given)
+  // optional: form dz = A*g + B*zc + C0 with g = dy where mask*mscale+mshift > 0 (mask null: g = dy)
+  const bf16_t* dy; const bf16_t* mask; const float* mscale; const float* mshift;
+  const bf16_t* zc; const float* coef; BnBwdRows rows; bf16_t* dz_out;
   float* partial;        // [grid.x][COUT][9*CIN]
   int N, H, W;
   int tiles;             // N * H/8
@@ -78,57 +87,142 @@ __global__ __launch_bounds__(256) void wgrad_tiled_kernel(WgradTiledArgs a) {
     for (int b = 0; b < CIB; ++b) acc[t][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int tiles_per_img = a.H / TH;
-  for (int tile = blockIdx.x; tile < a.tiles; tile += gridDim.x) {
+  constexpr int XCH = CINW / 8;                 // 16-byte chunks per staged pixel of x
+  constexpr int XVEC = ROWS * W * XCH;
+  constexpr int XPT = (XVEC + 255) / 256;
+  constexpr int ZCH = COUT / 8;
+  constexpr int ZVEC = TH * W * ZCH;            // 512 for all three shapes
+  constexpr int ZPT = ZVEC / 256;
+  static_assert(ZVEC % 256 == 0 && 256 % XCH == 0 && 256 % ZCH == 0, "staging layout");
+  const int xch = tid % XCH, zch = tid % ZCH;   // this thread's channel chunks (fixed)
+  const bool fuse = a.dy != nullptr;
+  const bool two_masks = fuse && a.mask && a.mask != a.zc;
+
+  // registers that hold the next tile while the current one is contracted
+  uint4 xs[XPT], ds[ZPT], zs[ZPT], ms[ZPT];
+  bool xin[XPT];
+  auto issue = [&](int tile) {
     const int n = tile / tiles_per_img, r0 = (tile - n * tiles_per_img) * TH;
-    __syncthreads();  // previous tile fully consumed
-    // ---- stage x^T: rows r0-1 .. r0+TH, all W columns, CINW channels ----
-    constexpr int XCH = CINW / 8;                 // 16-byte chunks per pixel
-    constexpr int XVEC = ROWS * W * XCH;
-    for (int v = tid; v < XVEC; v += 256) {
-      const int ch = v % XCH;
-      const int px = v / XCH;
-      const int col = px % W, rr = px / W;
-      const int ih = r0 - 1 + rr;
-      uint4 q = make_uint4(0, 0, 0, 0);
-      if (ih >= 0 && ih < a.H) {
-        const bf16_t* p = a.x + ((size_t)(n * a.H + ih) * W + col) * CIN + ci0 + ch * 8;
-        q = *reinterpret_cast<const uint4*>(p);
-        if (a.scale) {
-          float f[8];
-          f[0] = __uint_as_float(q.x << 16); f[1] = __uint_as_float(q.x & 0xffff0000u);
-          f[2] = __uint_as_float(q.y << 16); f[3] = __uint_as_float(q.y & 0xffff0000u);
-          f[4] = __uint_as_float(q.z << 16); f[5] = __uint_as_float(q.z & 0xffff0000u);
-          f[6] = __uint_as_float(q.w << 16); f[7] = __uint_as_float(q.w & 0xffff0000u);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float t = f[j] * a.scale[ci0 + ch * 8 + j] + a.shift[ci0 + ch * 8 + j];
-            f[j] = t > 0.f ? t : 0.f;
-          }
-          q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
-          q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
+    for (int i = 0; i < XPT; ++i) {
+      const int v = tid + i * 256;
+      xs[i] = make_uint4(0, 0, 0, 0);
+      xin[i] = false;
+      if (v < XVEC) {
+        const int px = v / XCH;
+        const int col = px % W, rr = px / W;
+        const int ih = r0 - 1 + rr;
+        if (ih >= 0 && ih < a.H) {
+          xin[i] = true;
+          xs[i] = *reinterpret_cast<const uint4*>(a.x + ((size_t)(n * a.H + ih) * W + col) * CIN + ci0 + xch * 8);
         }
       }
-      uint16_t* d = xT + (ch * 8) * PSX + rr * WP + col + 8;
-      d[0 * PSX] = (uint16_t)(q.x & 0xffff); d[1 * PSX] = (uint16_t)(q.x >> 16);
-      d[2 * PSX] = (uint16_t)(q.y & 0xffff); d[3 * PSX] = (uint16_t)(q.y >> 16);
-      d[4 * PSX] = (uint16_t)(q.z & 0xffff); d[5 * PSX] = (uint16_t)(q.z >> 16);
-      d[6 * PSX] = (uint16_t)(q.w & 0xffff); d[7 * PSX] = (uint16_t)(q.w >> 16);
     }
-    // ---- stage dz^T: rows r0 .. r0+TH-1 ----
-    constexpr int ZCH = COUT / 8;
-    constexpr int ZVEC = TH * W * ZCH;
-    for (int v = tid; v < ZVEC; v += 256) {
-      const int ch = v % ZCH;
-      const int px = v / ZCH;  // pixel index inside the tile (row-major)
-      const bf16_t* p = a.dz + ((size_t)(n * a.H + r0) * W + px) * COUT + ch * 8;
-      const uint4 q = *reinterpret_cast<const uint4*>(p);
-      uint16_t* d = zT + (ch * 8) * PSZ + px;
-      d[0 * PSZ] = (uint16_t)(q.x & 0xffff); d[1 * PSZ] = (uint16_t)(q.x >> 16);
-      d[2 * PSZ] = (uint16_t)(q.y & 0xffff); d[3 * PSZ] = (uint16_t)(q.y >> 16);
-      d[4 * PSZ] = (uint16_t)(q.z & 0xffff); d[5 * PSZ] = (uint16_t)(q.z >> 16);
-      d[6 * PSZ] = (uint16_t)(q.w & 0xffff); d[7 * PSZ] = (uint16_t)(q.w >> 16);
+#pragma unroll
+    for (int i = 0; i < ZPT; ++i) {
+      const int px = (tid + i * 256) / ZCH;
+      const size_t gi = ((size_t)(n * a.H + r0) * W + px) * COUT + zch * 8;
+      if (fuse) {
+        ds[i] = *reinterpret_cast<const uint4*>(a.dy + gi);
+        zs[i] = *reinterpret_cast<const uint4*>(a.zc + gi);
+        if (two_masks) ms[i] = *reinterpret_cast<const uint4*>(a.mask + gi);
+      } else {
+        ds[i] = *reinterpret_cast<const uint4*>(a.dz + gi);
+      }
     }
+  };
+
+  int tile = blockIdx.x;
+  if (tile < a.tiles) issue(tile);
+
+  // per-channel constants of this thread's chunks (derived while the first loads are in flight)
+  float tsc[8], tsh[8];
+  if (a.scale) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { tsc[j] = a.scale[ci0 + xch * 8 + j]; tsh[j] = a.shift[ci0 + xch * 8 + j]; }
+  }
+  float cA[8], cB[8], cC[8], cms[8], cmh[8];
+  if (fuse) {
+    __shared__ float s_coef[3 * COUT];
+    const float* coef = a.coef;
+    if (a.rows.partial) {
+      bn_bwd_from_rows(a.rows, COUT, s_coef, blockIdx.x == 0 && blockIdx.y == 0);
+      coef = s_coef;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int c = zch * 8 + j;
+      cA[j] = coef[c]; cB[j] = coef[COUT + c]; cC[j] = coef[2 * COUT + c];
+      cms[j] = a.mscale ? a.mscale[c] : 1.f; cmh[j] = a.mscale ? a.mshift[c] : 0.f;
+    }
+  }
+
+  auto unpack = [](const uint4& q, float (&f)[8]) {
+    f[0] = __uint_as_float(q.x << 16); f[1] = __uint_as_float(q.x & 0xffff0000u);
+    f[2] = __uint_as_float(q.y << 16); f[3] = __uint_as_float(q.y & 0xffff0000u);
+    f[4] = __uint_as_float(q.z << 16); f[5] = __uint_as_float(q.z & 0xffff0000u);
+    f[6] = __uint_as_float(q.w << 16); f[7] = __uint_as_float(q.w & 0xffff0000u);
+  };
+  auto pack = [](const float (&f)[8]) {
+    uint4 q;
+    q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
+    q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
+    return q;
+  };
+  auto scatter = [](uint16_t* d, int stride, const uint4& q) {   // 8 channels -> 8 planes
+    d[0 * stride] = (uint16_t)(q.x & 0xffff); d[1 * stride] = (uint16_t)(q.x >> 16);
+    d[2 * stride] = (uint16_t)(q.y & 0xffff); d[3 * stride] = (uint16_t)(q.y >> 16);
+    d[4 * stride] = (uint16_t)(q.z & 0xffff); d[5 * stride] = (uint16_t)(q.z >> 16);
+    d[6 * stride] = (uint16_t)(q.w & 0xffff); d[7 * stride] = (uint16_t)(q.w >> 16);
+  };
+  // transform the held registers and write them transposed into LDS
+  auto stage = [&](int tile) {
+    const int n = tile / tiles_per_img, r0 = (tile - n * tiles_per_img) * TH;
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+      const int v = tid + i * 256;
+      if (v < XVEC) {
+        uint4 q = xs[i];
+        if (a.scale && xin[i]) {
+          float f[8];
+          unpack(q, f);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { const float t = f[j] * tsc[j] + tsh[j]; f[j] = t > 0.f ? t : 0.f; }
+          q = pack(f);
+        }
+        const int px = v / XCH;
+        scatter(xT + (xch * 8) * PSX + (px / W) * WP + (px % W) + 8, PSX, q);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < ZPT; ++i) {
+      const int px = (tid + i * 256) / ZCH;
+      uint4 q = ds[i];
+      if (fuse) {
+        float g[8], zz[8];
+        unpack(ds[i], g);
+        unpack(zs[i], zz);
+        if (a.mask) {
+          float mk[8];
+          unpack(two_masks ? ms[i] : zs[i], mk);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) g[j] = (mk[j] * cms[j] + cmh[j]) > 0.f ? g[j] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) g[j] = cA[j] * g[j] + (cB[j] * zz[j] + cC[j]);
+        q = pack(g);
+        if (blockIdx.y == 0)
+          *reinterpret_cast<uint4*>(a.dz_out + ((size_t)(n * a.H + r0) * W + px) * COUT + zch * 8) = q;
+      }
+      scatter(zT + (zch * 8) * PSZ + px, PSZ, q);
+    }
+  };
+
+  for (; tile < a.tiles; tile += gridDim.x) {
+    __syncthreads();          // the previous tile has been contracted
+    stage(tile);
     __syncthreads();
+    if (tile + (int)gridDim.x < a.tiles) issue(tile + gridDim.x);   // in flight during the MFMA phase
     // ---- contraction over the tile's pixels ----
     for (int ks = kpart; ks < KSTEPS; ks += KSPLIT) {
       const int px = ks * 32 + lg * 8;           // first of this lane's 8 pixels
@@ -213,9 +307,15 @@ int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, 
 }
 
 hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* shift, const void* dz,
-                              float* partial, int N, int H, int W, int C, int rows, hipStream_t s) {
-  WgradTiledArgs a;
+                              const WgradFuse* fuse, float* partial, int N, int H, int W, int C, int rows,
+                              hipStream_t s) {
+  WgradTiledArgs a{};
   a.x = (const bf16_t*)x; a.scale = scale; a.shift = shift; a.dz = (const bf16_t*)dz; a.partial = partial;
+  if (fuse) {
+    a.dy = (const bf16_t*)fuse->dy; a.mask = (const bf16_t*)fuse->mask; a.mscale = fuse->mscale; a.mshift = fuse->mshift;
+    a.zc = (const bf16_t*)fuse->z; a.coef = fuse->coef; a.dz_out = (bf16_t*)fuse->dz_out;
+    if (fuse->rows) a.rows = *fuse->rows;
+  }
   a.N = N; a.H = H; a.W = W; a.tiles = N * (H / 8);
   if (C == 16 && W == 32) return wgrad_tiled_launch_t<16, 16, 32>(a, rows, s);
   if (C == 32 && W == 16) return wgrad_tiled_launch_t<32, 32, 16>(a, rows, s);
