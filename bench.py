@@ -93,21 +93,23 @@ def traffic_model(wl):
     return fam
 
 
-def build_pipeline(wl):
+def build_pipeline(wl, serial=False, one_stream_per_module=False):
     import torch
     import numpy as np
     import workloads as wk
     import paper_1804_10574_amd as ddg
     from paper_1804_10574_amd.ddg import make_desc
     streams = [torch.cuda.Stream() for _ in range(wl.K)]
+    fstreams = [torch.cuda.Stream() for _ in range(wl.K)]   # forward passes on streams of their own
     descs = []
     for m in wl.modules:
         descs.append(make_desc(wl.K, m.k, wl.batch, (m.in_c, m.in_h, m.in_w),
                                [b.as_tuple() for b in m.blocks],
                                wl.num_classes if m.blocks[-1].kind == wk.BLOCK_HEAD else 0,
                                ddg.DDG_BF16 if wl.dtype == "bf16" else ddg.DDG_F32,
-                               wl.momentum, wl.weight_decay, wl.bn_eps))
-    pipe = ddg.Pipeline(descs, [s.cuda_stream for s in streams])
+                               wl.momentum, wl.weight_decay, wl.bn_eps,
+                               forward_stream=None if (serial or one_stream_per_module) else fstreams[m.k - 1].cuda_stream))
+    pipe = ddg.Pipeline(descs, None if serial else [s.cuda_stream for s in streams])
     for m in wl.modules:
         pipe.module(m.k).set_params(wk.init_module_params(wl, m).astype(np.float32))
     return pipe, streams
@@ -146,6 +148,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="all modules on one stream")
+    ap.add_argument("--one-stream-per-module", action="store_true",
+                    help="forward and delayed backward of a module share one stream")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (modules are concurrent streams on one "
@@ -160,7 +164,7 @@ def main():
     wl = wk.get_workload(args.workload)
     if wl.single_module:
         raise SystemExit("bench.py times full pipelines; single-module workloads are parity cases")
-    pipe, streams = build_pipeline(wl)
+    pipe, streams = build_pipeline(wl, args.serial, args.one_stream_per_module)
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     # a few distinct minibatches, resident in HBM before the timed region
     nbuf = 4
@@ -192,7 +196,7 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "network": wl.notes, "K": wl.K, "global_batch": wl.batch,
-                   "image": "3x32x32", "classes": wl.num_classes, "streams": 1 if args.serial else wl.K,
+                   "image": "3x32x32", "classes": wl.num_classes, "streams": 1 if args.serial else (wl.K if args.one_stream_per_module else 2 * wl.K - 1),
                    "parallelism": "K modules as HIP streams on one GPU"},
         "final_loss": final_loss,
     }

@@ -82,6 +82,10 @@ typedef struct {
   int compute;                 /* ddg_dtype of activations, error gradients, conv operands    */
   float momentum, weight_decay, bn_eps;
   void* stream;                /* hipStream_t the module's work is enqueued on (0 = default)  */
+  void* forward_stream;        /* optional second hipStream_t: when given (and the delay K-k is
+                                  > 0) ddg_forward runs on it, concurrently with the delayed
+                                  backward of the same iteration on `stream` (both read the same
+                                  weights; the update waits for both). 0: everything on `stream` */
   int dry_run;                 /* != 0: no device memory, no launches; only the argument and
                                   state checks run (lets host logic be tested without a GPU) */
 } ddg_module_desc;
@@ -146,7 +150,7 @@ ddg_status ddg_module_sync(ddg_module* m);
  * events: forward runs k = 1..K in turn; the K backward passes and updates of one iteration
  * overlap. streams: K hipStream_t handles (host array) or NULL to run everything on stream 0
  * (serialised; results are identical). descs[i] describes module i+1; descs[i].stream is
- * ignored. */
+ * ignored; descs[i].forward_stream, if set, gives module i+1 a forward stream of its own. */
 ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const* streams,
                                ddg_pipeline** out);
 ddg_status ddg_pipeline_destroy(ddg_pipeline* p);

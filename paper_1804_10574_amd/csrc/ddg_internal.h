@@ -11,4 +11,10 @@ void ddg_internal_skip_launches(ddg_module* m, bool skip);
 // The update reads its step size from this device float instead of the call argument.
 void ddg_internal_lr_from(ddg_module* m, const float* lr_dev);
 bool ddg_internal_profiling(const ddg_module* m);
+// A pipeline orders the module's two streams itself (events around graph launches); the module
+// then records and waits on nothing.
+void ddg_internal_external_sync(ddg_module* m, bool on);
+// The streams ddg_forward and ddg_backward_delayed/ddg_update enqueue on (equal unless the
+// module runs its forward pass on a stream of its own).
+void ddg_internal_streams(ddg_module* m, hipStream_t* fwd, hipStream_t* bwd);
 }

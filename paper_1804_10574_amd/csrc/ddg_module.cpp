@@ -79,7 +79,16 @@ struct ddg_module {
   ddg_module_desc d{};
   std::vector<ddg_block_desc> blocks_desc;
   std::vector<Blk> blocks;
-  hipStream_t stream = nullptr;
+  // Second set of forward buffers (conv outputs, statistics, block outputs) for the forward pass
+  // on the current minibatch when it runs on its own stream next to the delayed backward.
+  std::vector<Blk> fblocks;
+  hipStream_t stream = nullptr;    // the stream the call being executed enqueues on
+  hipStream_t bstream = nullptr;   // backward / update stream (desc.stream)
+  hipStream_t fstream = nullptr;   // forward stream (== bstream unless two_streams)
+  bool two_streams = false;
+  bool external_sync = false;      // a pipeline orders the two streams; the module records/waits nothing
+  hipEvent_t ev_fwd[2] = {nullptr, nullptr};   // forward(t) done, by parity of t
+  hipEvent_t ev_upd = nullptr;                 // last update (or parameter load) done
   int delay = 0, nslots = 1;
   int out_c = 0, out_h = 0, out_w = 0;
   size_t nparams = 0, in_elems = 0, out_elems = 0, max_act = 0;
@@ -445,11 +454,11 @@ ddg_status apply_bn(ddg_module* m, Unit& u, const void* res, Unit* ru, void* y) 
 
 // Forward through all residual blocks. `final_out`, if given, receives the last block's
 // output instead of the module's own buffer (used when the tape is not needed).
-ddg_status run_forward(ddg_module* m, const void* in, void* final_out) {
+ddg_status run_forward(ddg_module* m, std::vector<Blk>& blocks, const void* in, void* final_out) {
   const void* x = in;
-  const int nres = (int)m->blocks.size() - (m->d.num_classes > 0 ? 1 : 0);
+  const int nres = (int)blocks.size() - (m->d.num_classes > 0 ? 1 : 0);
   for (int bi = 0; bi < nres; ++bi) {
-    Blk& b = m->blocks[bi];
+    Blk& b = blocks[bi];
     void* yout = (bi == nres - 1 && final_out) ? final_out : b.y;
     const void* cur = x;
     Unit* src = nullptr;   // pending relu(bn(.)) of `cur`
@@ -643,6 +652,37 @@ ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const i
   return DDG_OK;
 }
 
+// Second set of forward buffers: same plan and packed weights, own conv outputs, statistics
+// and block outputs, so that the forward pass on the current minibatch and the re-forward of
+// the delayed one can be in flight at the same time.
+ddg_status build_forward_shadow(ddg_module* m) {
+  m->fblocks = m->blocks;
+  for (Blk& b : m->fblocks) {
+    if (b.kind == DDG_BLOCK_HEAD) continue;
+    for (Unit& u : b.u) {
+      void* p = nullptr;
+      DDG_OKAY(dev_alloc(m, &p, u.out_elems() * m->esz)); u.z = p;
+      DDG_OKAY(dev_alloc(m, &p, (size_t)u.fprop.grid_x * 2 * u.cout * sizeof(float))); u.fstat = (float*)p;
+      DDG_OKAY(dev_alloc(m, &p, (size_t)7 * u.cout * sizeof(float)));
+      u.mean = (float*)p; u.invstd = u.mean + u.cout; u.scale = u.invstd + u.cout;
+      u.shift = u.scale + u.cout; u.coef = u.shift + u.cout;
+    }
+    for (size_t i = 0; i < b.act.size(); ++i)
+      if (b.act[i]) DDG_OKAY(dev_alloc(m, &b.act[i], b.u[i].out_elems() * m->esz));
+    DDG_OKAY(dev_alloc(m, &b.y, b.y_elems * m->esz));
+  }
+  for (int i = 0; i < 2; ++i)
+    if (hipEventCreateWithFlags(&m->ev_fwd[i], hipEventDisableTiming) != hipSuccess) return fail(DDG_ERR_DEVICE, "event");
+  if (hipEventCreateWithFlags(&m->ev_upd, hipEventDisableTiming) != hipSuccess) return fail(DDG_ERR_DEVICE, "event");
+  return DDG_OK;
+}
+
+ddg_status sync_streams(ddg_module* m) {
+  DDG_TRY(hipStreamSynchronize(m->bstream));
+  if (m->two_streams) DDG_TRY(hipStreamSynchronize(m->fstream));
+  return DDG_OK;
+}
+
 ddg_status check_handle(const ddg_module* m) {
   if (!m) return fail(DDG_ERR_INVALID_ARG, "module handle is null");
   if (m->sticky != DDG_OK) return fail(m->sticky, "module is in a failed state after an earlier device error");
@@ -666,8 +706,14 @@ ddg_status ddg_module_create(const ddg_module_desc* desc, ddg_module** out) {
   m->d = *desc;
   m->blocks_desc.assign(desc->blocks, desc->blocks + desc->num_blocks);
   m->d.blocks = m->blocks_desc.data();
-  m->stream = (hipStream_t)desc->stream;
+  m->bstream = (hipStream_t)desc->stream;
+  m->fstream = m->bstream;
+  m->stream = m->bstream;
+  m->two_streams = desc->forward_stream && desc->forward_stream != desc->stream && (desc->K - desc->k) > 0 &&
+                   !desc->dry_run;
+  if (m->two_streams) m->fstream = (hipStream_t)desc->forward_stream;
   ddg_status st = build_plan(m);
+  if (st == DDG_OK && m->two_streams) st = build_forward_shadow(m);
   if (st != DDG_OK) {
     for (void* p : m->allocs) (void)hipFree(p);
     delete m;
@@ -680,7 +726,10 @@ ddg_status ddg_module_create(const ddg_module_desc* desc, ddg_module** out) {
 ddg_status ddg_module_destroy(ddg_module* m) {
   if (!m) return DDG_OK;
   if (!m->d.dry_run) {
-    (void)hipStreamSynchronize(m->stream);
+    (void)hipStreamSynchronize(m->bstream);
+    if (m->two_streams) (void)hipStreamSynchronize(m->fstream);
+    for (int i = 0; i < 2; ++i) if (m->ev_fwd[i]) (void)hipEventDestroy(m->ev_fwd[i]);
+    if (m->ev_upd) (void)hipEventDestroy(m->ev_upd);
     for (auto& e : m->evs) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (void* p : m->allocs) (void)hipFree(p);
   }
@@ -703,26 +752,30 @@ ddg_status ddg_set_params(ddg_module* m, const float* src, int is_device) {
   DDG_OKAY(check_handle(m));
   if (!src) return fail(DDG_ERR_INVALID_ARG, "src is null");
   if (m->d.dry_run) return DDG_OK;
+  m->stream = m->bstream;
+  DDG_OKAY(sync_streams(m));   // nothing may still be reading the old weights
   if (is_device) {
     Launch L(m, PK_COPY);
     DDG_TRY(copy_launch(src, m->theta, m->nparams * sizeof(float), m->stream));
   } else {
-    DDG_TRY(hipStreamSynchronize(m->stream));
     DDG_TRY(hipMemcpy(m->theta, src, m->nparams * sizeof(float), hipMemcpyHostToDevice));
   }
   m->tape_is_current = false;
-  return pack_all(m);
+  DDG_OKAY(pack_all(m));
+  if (m->two_streams) DDG_TRY(hipStreamSynchronize(m->bstream));   // visible to the forward stream
+  return DDG_OK;
 }
 
 ddg_status ddg_set_velocity(ddg_module* m, const float* src, int is_device) {
   DDG_OKAY(check_handle(m));
   if (!src) return fail(DDG_ERR_INVALID_ARG, "src is null");
   if (m->d.dry_run) return DDG_OK;
+  m->stream = m->bstream;
   if (is_device) {
     Launch L(m, PK_COPY);
     DDG_TRY(copy_launch(src, m->vel, m->nparams * sizeof(float), m->stream));
   } else {
-    DDG_TRY(hipStreamSynchronize(m->stream));
+    DDG_TRY(hipStreamSynchronize(m->bstream));
     DDG_TRY(hipMemcpy(m->vel, src, m->nparams * sizeof(float), hipMemcpyHostToDevice));
   }
   return DDG_OK;
@@ -732,7 +785,7 @@ static ddg_status get_vec(ddg_module* m, const float* dev, float* host_dst) {
   DDG_OKAY(check_handle(m));
   if (!host_dst) return fail(DDG_ERR_INVALID_ARG, "host_dst is null");
   if (m->d.dry_run) { memset(host_dst, 0, m->nparams * sizeof(float)); return DDG_OK; }
-  DDG_TRY(hipStreamSynchronize(m->stream));
+  DDG_OKAY(sync_streams(m));
   DDG_TRY(hipMemcpy(host_dst, dev, m->nparams * sizeof(float), hipMemcpyDeviceToHost));
   return DDG_OK;
 }
@@ -755,15 +808,20 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   m->phase = 1;
   if (m->d.dry_run) return DDG_OK;
   if (m->skip) { m->tape_is_current = (m->delay == 0); return DDG_OK; }
+  m->stream = m->fstream;
+  const bool self_sync = m->two_streams && !m->external_sync;
+  // the forward stream needs the weights of update(t-1) and the ring slot that backward(t-1) read
+  if (self_sync) DDG_TRY(hipStreamWaitEvent(m->fstream, m->ev_upd, 0));
   void* slot = m->ring[t % m->nslots];
   { Launch L(m, PK_COPY); DDG_TRY(copy_launch(h_in, slot, m->in_elems * m->esz, m->stream)); }
   // A module with delay > 0 re-forwards before its backward, so this pass need not keep a
   // tape and writes straight to h_out; the last module keeps the tape for its own backward.
   if (m->delay > 0) {
-    DDG_OKAY(run_forward(m, slot, h_out));
+    DDG_OKAY(run_forward(m, m->two_streams ? m->fblocks : m->blocks, slot, h_out));
     m->tape_is_current = false;
+    if (self_sync) DDG_TRY(hipEventRecord(m->ev_fwd[t & 1], m->fstream));
   } else {
-    DDG_OKAY(run_forward(m, slot, nullptr));
+    DDG_OKAY(run_forward(m, m->blocks, slot, nullptr));
     m->tape_is_current = true;
     if (h_out) {
       Launch L(m, PK_COPY);
@@ -790,8 +848,11 @@ ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, con
   if (did_backward) *did_backward = m->has_grad ? 1 : 0;
   if (s < 0 || m->d.dry_run) return DDG_OK;
   if (m->skip) { m->tape_is_current = false; return DDG_OK; }
+  m->stream = m->bstream;
+  // the stored input of iteration s <= t-1 was written by the forward stream
+  if (m->two_streams && !m->external_sync && t > 0) DDG_TRY(hipStreamWaitEvent(m->bstream, m->ev_fwd[(t - 1) & 1], 0));
   void* slot = m->ring[s % m->nslots];
-  if (!m->tape_is_current) DDG_OKAY(run_forward(m, slot, nullptr));
+  if (!m->tape_is_current) DDG_OKAY(run_forward(m, m->blocks, slot, nullptr));
   m->tape_is_current = false;
   DDG_OKAY(run_backward(m, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out));
   // every layer's weight-gradient partials -> g (one launch for the module, fixed order)
@@ -806,19 +867,26 @@ ddg_status ddg_update(ddg_module* m, long t, float lr) {
   m->phase = 0;
   m->t_next = t + 1;
   if (!m->has_grad || m->d.dry_run || m->skip) return DDG_OK;
+  m->stream = m->bstream;
+  const bool self_sync = m->two_streams && !m->external_sync;
+  // the forward pass of this iteration must have finished reading the weights
+  if (self_sync) DDG_TRY(hipStreamWaitEvent(m->bstream, m->ev_fwd[t & 1], 0));
   { Launch L(m, PK_SGD);
     DDG_TRY(sgd_launch(m->theta, m->vel, m->grad, m->nparams, lr, m->lr_dev, m->d.momentum, m->d.weight_decay, m->stream)); }
-  return pack_all(m);
+  DDG_OKAY(pack_all(m));
+  if (self_sync) DDG_TRY(hipEventRecord(m->ev_upd, m->bstream));
+  return DDG_OK;
 }
 
 ddg_status ddg_module_sync(ddg_module* m) {
   DDG_OKAY(check_handle(m));
   if (m->d.dry_run) return DDG_OK;
-  DDG_TRY(hipStreamSynchronize(m->stream));
-  return DDG_OK;
+  return sync_streams(m);
 }
 
 void ddg_internal_skip_launches(ddg_module* m, bool skip) { m->skip = skip; }
+void ddg_internal_external_sync(ddg_module* m, bool on) { m->external_sync = on; }
+void ddg_internal_streams(ddg_module* m, hipStream_t* fwd, hipStream_t* bwd) { *fwd = m->fstream; *bwd = m->bstream; }
 void ddg_internal_lr_from(ddg_module* m, const float* lr_dev) { m->lr_dev = lr_dev; }
 bool ddg_internal_profiling(const ddg_module* m) { return m->prof; }
 
@@ -827,7 +895,7 @@ const char* ddg_profile_kind_name(int kind) { return (kind >= 0 && kind < PK_COU
 
 static ddg_status prof_collect(ddg_module* m) {
   if (m->evs.empty()) return DDG_OK;
-  DDG_TRY(hipStreamSynchronize(m->stream));
+  DDG_OKAY(sync_streams(m));
   for (auto& e : m->evs) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) { m->prof_n[e.kind] += 1; m->prof_ms[e.kind] += ms; }

@@ -19,13 +19,14 @@
 struct ddg_pipeline {
   int K = 0;
   std::vector<ddg_module*> mods;
-  std::vector<hipStream_t> streams;
+  std::vector<hipStream_t> streams;     // [k] backward / update stream of module k
+  std::vector<hipStream_t> fstreams;    // [k] forward stream (== streams[k] unless the module has its own)
   std::vector<void*> h;                 // h[k], k = 1..K-1 (index k)
   std::vector<void*> mail[2];           // mail[slot][k]: df/dh_k, k = 1..K-1
   std::vector<long> mail_iter[2];       // iteration the slot content belongs to
   std::vector<size_t> h_elems;
   std::vector<int> dtype;
-  std::vector<hipEvent_t> fwd_done;     // [k] recorded after module k's forward
+  std::vector<hipEvent_t> fwd_done[2];  // [t%2][k] recorded after module k's forward
   std::vector<hipEvent_t> bwd_done[2];  // [t%2][k] recorded after module k's backward+update
   hipEvent_t input_free = nullptr;
   long t = 0;
@@ -36,7 +37,7 @@ struct ddg_pipeline {
   // slot (period 2), so one graph per residue of t modulo their least common multiple.
   bool graphs = true;
   std::vector<int> period;                                  // [k]
-  std::vector<std::map<int, hipGraphExec_t>> gfwd, gbwd;    // [k][t mod period]
+  std::vector<std::map<int, hipGraphExec_t>> gfwd, gbwd, gupd;   // [k][t mod period]
   void* xin = nullptr;            // staged network input (stable address for the graphs)
   int32_t* labels_dev = nullptr;  // staged labels
   float* loss_dev = nullptr;      // loss of the last iteration
@@ -72,15 +73,17 @@ ddg_status ddg_pipeline_destroy(ddg_pipeline* p) {
   if (!p) return DDG_OK;
   if (!p->dry) {
     for (hipStream_t s : p->streams) (void)hipStreamSynchronize(s);
+    for (hipStream_t s : p->fstreams) if (s) (void)hipStreamSynchronize(s);
     for (size_t k = 0; k < p->h.size(); ++k) if (p->h[k]) (void)hipFree(p->h[k]);
     for (int sl = 0; sl < 2; ++sl) {
       for (void* q : p->mail[sl]) if (q) (void)hipFree(q);
       for (hipEvent_t e : p->bwd_done[sl]) if (e) (void)hipEventDestroy(e);
     }
-    for (hipEvent_t e : p->fwd_done) if (e) (void)hipEventDestroy(e);
+    for (int sl = 0; sl < 2; ++sl) for (hipEvent_t e : p->fwd_done[sl]) if (e) (void)hipEventDestroy(e);
     if (p->scratch_f32) (void)hipFree(p->scratch_f32);
     for (auto& mp : p->gfwd) for (auto& kv : mp) (void)hipGraphExecDestroy(kv.second);
     for (auto& mp : p->gbwd) for (auto& kv : mp) (void)hipGraphExecDestroy(kv.second);
+    for (auto& mp : p->gupd) for (auto& kv : mp) (void)hipGraphExecDestroy(kv.second);
     if (p->xin) (void)hipFree(p->xin);
     if (p->labels_dev) (void)hipFree(p->labels_dev);
     if (p->loss_dev) (void)hipFree(p->loss_dev);
@@ -101,8 +104,9 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
   p->h.assign(K + 1, nullptr);
   p->h_elems.assign(K + 1, 0);
   p->dtype.assign(K + 1, 0);
-  p->fwd_done.assign(K + 1, nullptr);
+  p->fstreams.assign(K + 1, nullptr);
   for (int sl = 0; sl < 2; ++sl) {
+    p->fwd_done[sl].assign(K + 1, nullptr);
     p->mail[sl].assign(K + 1, nullptr);
     p->mail_iter[sl].assign(K + 1, -1);
     p->bwd_done[sl].assign(K + 1, nullptr);
@@ -111,9 +115,13 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
     ddg_module_desc d = descs[k - 1];
     if (d.K != K || d.k != k) { ddg_pipeline_destroy(p); return DDG_ERR_INVALID_ARG; }
     d.stream = streams ? streams[k - 1] : nullptr;
-    p->streams[k] = (hipStream_t)d.stream;
+    if (!streams) d.forward_stream = nullptr;
     ddg_status st = ddg_module_create(&d, &p->mods[k]);
     if (st != DDG_OK) { ddg_pipeline_destroy(p); return st; }
+    if (!p->dry) {
+      ddg_internal_streams(p->mods[k], &p->fstreams[k], &p->streams[k]);
+      ddg_internal_external_sync(p->mods[k], true);
+    }
     p->dtype[k] = d.compute;
     int c, hh, ww;
     ddg_out_shape(p->mods[k], &c, &hh, &ww);
@@ -134,7 +142,8 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
         if (hipMalloc(&p->h[k], bytes) != hipSuccess || hipMalloc(&p->mail[0][k], bytes) != hipSuccess ||
             hipMalloc(&p->mail[1][k], bytes) != hipSuccess) { ddg_pipeline_destroy(p); return DDG_ERR_OOM; }
       }
-      if (hipEventCreateWithFlags(&p->fwd_done[k], hipEventDisableTiming) != hipSuccess ||
+      if (hipEventCreateWithFlags(&p->fwd_done[0][k], hipEventDisableTiming) != hipSuccess ||
+          hipEventCreateWithFlags(&p->fwd_done[1][k], hipEventDisableTiming) != hipSuccess ||
           hipEventCreateWithFlags(&p->bwd_done[0][k], hipEventDisableTiming) != hipSuccess ||
           hipEventCreateWithFlags(&p->bwd_done[1][k], hipEventDisableTiming) != hipSuccess) {
         ddg_pipeline_destroy(p); return DDG_ERR_DEVICE;
@@ -151,7 +160,7 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
     if (env && env[0] == '1') p->graphs = false;
     if (!streams) p->graphs = false;   // the default stream cannot be captured
     p->period.assign(K + 1, 1);
-    p->gfwd.resize(K + 1); p->gbwd.resize(K + 1);
+    p->gfwd.resize(K + 1); p->gbwd.resize(K + 1); p->gupd.resize(K + 1);
     for (int k = 1; k <= K; ++k) {
       const int nslots = K - k + 1;
       p->period[k] = nslots * 2 / gcd_i(nslots, 2);
@@ -181,95 +190,88 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
   const int cur = (int)(t & 1), prev = cur ^ 1;
   bool use_graph = !p->dry && p->graphs && t >= K;   // steady state: every module has a gradient
   if (use_graph) for (int k = 1; k <= K; ++k) if (ddg_internal_profiling(p->mods[k])) use_graph = false;
+#define DDG_P(expr) do { if ((expr) != hipSuccess) return DDG_ERR_DEVICE; } while (0)
   if (!p->dry) {
     // stage the caller's tensors at stable addresses; the step size lives in device memory
-    if (ddg::copy_launch(x, p->xin, p->x_bytes, p->streams[1]) != hipSuccess) return DDG_ERR_DEVICE;
-    if (ddg::copy_launch(labels, p->labels_dev, p->batch * sizeof(int32_t), p->streams[K]) != hipSuccess) return DDG_ERR_DEVICE;
+    DDG_P(ddg::copy_launch(x, p->xin, p->x_bytes, p->fstreams[1]));
+    DDG_P(ddg::copy_launch(labels, p->labels_dev, p->batch * sizeof(int32_t), p->streams[K]));
     if (lr != p->lr_host) {
       // every module's update of the previous iteration must have read the old value
-      for (int k = 1; k <= K; ++k) if (hipStreamSynchronize(p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
-      if (ddg::set_scalar_launch(p->lr_dev, lr, p->streams[1]) != hipSuccess) return DDG_ERR_DEVICE;
-      if (hipStreamSynchronize(p->streams[1]) != hipSuccess) return DDG_ERR_DEVICE;
+      for (int k = 1; k <= K; ++k) DDG_P(hipStreamSynchronize(p->streams[k]));
+      DDG_P(ddg::set_scalar_launch(p->lr_dev, lr, p->streams[1]));
+      DDG_P(hipStreamSynchronize(p->streams[1]));
       p->lr_host = lr;
     }
   }
   const void* x_in = p->dry ? x : p->xin;
   const int32_t* lab = p->dry ? labels : p->labels_dev;
-  // forward, k = 1..K in turn (Section 3.1)
-  for (int k = 1; k <= K; ++k) {
-    if (!p->dry) {
-      if (k > 1) if (hipStreamWaitEvent(p->streams[k], p->fwd_done[k - 1], 0) != hipSuccess) return DDG_ERR_DEVICE;
-      // h[k] is still being read by module k+1's forward of the previous iteration
-      if (k < K && t > 0) if (hipStreamWaitEvent(p->streams[k], p->fwd_done[k + 1], 0) != hipSuccess) return DDG_ERR_DEVICE;
-    }
-    auto call = [&]() { return ddg_forward(p->mods[k], t, k == 1 ? x_in : p->h[k - 1], k < K ? p->h[k] : nullptr); };
+  // Runs `call` on stream s: eagerly, or as a captured graph (captured at the first use of this
+  // residue of t, replayed afterwards while the module only advances its host-side state).
+  auto run = [&](int k, hipStream_t s, std::map<int, hipGraphExec_t>& cache, auto call) -> ddg_status {
+    if (!use_graph) return call();
+    const int v = (int)(t % p->period[k]);
+    auto it = cache.find(v);
     ddg_status st;
-    if (use_graph) {
-      const int v = (int)(t % p->period[k]);
-      auto it = p->gfwd[k].find(v);
-      if (it == p->gfwd[k].end()) {
-        hipGraphExec_t ex = nullptr;
-        st = capture(p->streams[k], &ex, call);
-        if (st != DDG_OK) return st;
-        it = p->gfwd[k].emplace(v, ex).first;
-      } else {
-        ddg_internal_skip_launches(p->mods[k], true);
-        st = call();
-        ddg_internal_skip_launches(p->mods[k], false);
-        if (st != DDG_OK) return st;
-      }
-      if (hipGraphLaunch(it->second, p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+    if (it == cache.end()) {
+      hipGraphExec_t ex = nullptr;
+      st = capture(s, &ex, call);
+      if (st != DDG_OK) return st;
+      it = cache.emplace(v, ex).first;
     } else {
+      ddg_internal_skip_launches(p->mods[k], true);
       st = call();
-      if (st != DDG_OK) return pfail(st);
+      ddg_internal_skip_launches(p->mods[k], false);
+      if (st != DDG_OK) return st;
     }
-    if (!p->dry) if (hipEventRecord(p->fwd_done[k], p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+    return hipGraphLaunch(it->second, s) == hipSuccess ? DDG_OK : DDG_ERR_DEVICE;
+  };
+  // forward, k = 1..K in turn (Section 3.1), each on its module's forward stream
+  for (int k = 1; k <= K; ++k) {
+    hipStream_t fs = p->dry ? nullptr : p->fstreams[k];
+    if (!p->dry) {
+      if (k > 1) DDG_P(hipStreamWaitEvent(fs, p->fwd_done[cur][k - 1], 0));
+      // h[k] is still being read by module k+1's forward of the previous iteration
+      if (k < K && t > 0) DDG_P(hipStreamWaitEvent(fs, p->fwd_done[prev][k + 1], 0));
+      // a forward stream of its own: the weights of update(t-1), and the ring slot that
+      // backward(t-1) read, come from the module's other stream
+      if (fs != p->streams[k] && t > 0) DDG_P(hipStreamWaitEvent(fs, p->bwd_done[prev][k], 0));
+    }
+    ddg_status st = run(k, fs, p->gfwd[k], [&]() {
+      return ddg_forward(p->mods[k], t, k == 1 ? x_in : p->h[k - 1], k < K ? p->h[k] : nullptr); });
+    if (st != DDG_OK) return st;
+    if (!p->dry) DDG_P(hipEventRecord(p->fwd_done[cur][k], fs));
   }
   // backward + update: the K modules are independent within one iteration
   for (int k = 1; k <= K; ++k) {
     const long s = t - K + k;
+    hipStream_t bs = p->dry ? nullptr : p->streams[k];
+    const bool split = !p->dry && p->fstreams[k] != bs;
     if (!p->dry && s >= 0 && t > 0) {
       // read-after-write: the error gradient for iteration s was written by module k+1 during t-1
-      if (k < K) if (hipStreamWaitEvent(p->streams[k], p->bwd_done[prev][k + 1], 0) != hipSuccess) return DDG_ERR_DEVICE;
+      if (k < K) DDG_P(hipStreamWaitEvent(bs, p->bwd_done[prev][k + 1], 0));
       // write-after-read: slot `cur` of mailbox k-1 was read by module k-1 during t-1
-      if (k > 1) if (hipStreamWaitEvent(p->streams[k], p->bwd_done[prev][k - 1], 0) != hipSuccess) return DDG_ERR_DEVICE;
+      if (k > 1) DDG_P(hipStreamWaitEvent(bs, p->bwd_done[prev][k - 1], 0));
+      // the stored input of iteration s <= t-1 was written by the forward stream
+      if (split) DDG_P(hipStreamWaitEvent(bs, p->fwd_done[prev][k], 0));
     }
     const void* din = (k < K) ? p->mail[prev][k] : nullptr;
     void* dout = (k > 1) ? p->mail[cur][k - 1] : nullptr;
     int did = 0;
-    auto call = [&]() {
-      ddg_status r = ddg_backward_delayed(p->mods[k], t, (s >= 0) ? din : nullptr, k == K ? lab : nullptr, dout,
-                                          k == K ? (p->dry ? loss_out : p->loss_dev) : nullptr, &did);
-      if (r != DDG_OK) return r;
-      return ddg_update(p->mods[k], t, lr);
-    };
-    ddg_status st;
-    if (use_graph) {
-      const int v = (int)(t % p->period[k]);
-      auto it = p->gbwd[k].find(v);
-      if (it == p->gbwd[k].end()) {
-        hipGraphExec_t ex = nullptr;
-        st = capture(p->streams[k], &ex, call);
-        if (st != DDG_OK) return st;
-        it = p->gbwd[k].emplace(v, ex).first;
-      } else {
-        ddg_internal_skip_launches(p->mods[k], true);
-        st = call();
-        ddg_internal_skip_launches(p->mods[k], false);
-        if (st != DDG_OK) return st;
-      }
-      if (hipGraphLaunch(it->second, p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
-    } else {
-      st = call();
-      if (st != DDG_OK) return pfail(st);
-    }
+    ddg_status st = run(k, bs, p->gbwd[k], [&]() {
+      return ddg_backward_delayed(p->mods[k], t, (s >= 0) ? din : nullptr, k == K ? lab : nullptr, dout,
+                                  k == K ? (p->dry ? loss_out : p->loss_dev) : nullptr, &did); });
+    if (st != DDG_OK) return st;
     if (k > 1) p->mail_iter[cur][k - 1] = did ? s : -1;
+    // the update overwrites the weights that this iteration's forward pass reads
+    if (split) DDG_P(hipStreamWaitEvent(bs, p->fwd_done[cur][k], 0));
+    st = run(k, bs, p->gupd[k], [&]() { return ddg_update(p->mods[k], t, lr); });
+    if (st != DDG_OK) return st;
     if (!p->dry) {
-      if (k == K && loss_out && s >= 0)
-        if (ddg::copy_launch(p->loss_dev, loss_out, sizeof(float), p->streams[K]) != hipSuccess) return DDG_ERR_DEVICE;
-      if (hipEventRecord(p->bwd_done[cur][k], p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+      if (k == K && loss_out && s >= 0) DDG_P(ddg::copy_launch(p->loss_dev, loss_out, sizeof(float), bs));
+      DDG_P(hipEventRecord(p->bwd_done[cur][k], bs));
     }
   }
+#undef DDG_P
   p->t = t + 1;
   return DDG_OK;
 }
@@ -277,7 +279,10 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
 ddg_status ddg_pipeline_sync(ddg_pipeline* p) {
   if (!p) return DDG_ERR_INVALID_ARG;
   if (p->dry) return DDG_OK;
-  for (int k = 1; k <= p->K; ++k) if (hipStreamSynchronize(p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+  for (int k = 1; k <= p->K; ++k) {
+    if (hipStreamSynchronize(p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+    if (p->fstreams[k] != p->streams[k] && hipStreamSynchronize(p->fstreams[k]) != hipSuccess) return DDG_ERR_DEVICE;
+  }
   return DDG_OK;
 }
 

@@ -34,14 +34,15 @@ def nhwc_np_to_nchw(a):
     return np.asarray(a, np.float64).transpose(0, 3, 1, 2)
 
 
-def descs_for(wl, streams=None, dry_run=False, batch=None):
+def descs_for(wl, streams=None, dry_run=False, batch=None, fstreams=None):
     out = []
     for i, m in enumerate(wl.modules):
         out.append(make_desc(wl.K, m.k, batch or wl.batch, (m.in_c, m.in_h, m.in_w),
                              [b.as_tuple() for b in m.blocks],
                              wl.num_classes if m.blocks[-1].kind == wk.BLOCK_HEAD else 0,
                              compute_enum(wl), wl.momentum, wl.weight_decay, wl.bn_eps,
-                             stream=(streams[i] if streams else None), dry_run=dry_run))
+                             stream=(streams[i] if streams else None), dry_run=dry_run,
+                             forward_stream=(fstreams[i] if fstreams else None)))
     return out
 
 
@@ -110,7 +111,9 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
     """
     K = wl.K
     st = [torch.cuda.Stream() for _ in range(K)] if streams else None
-    pipe = ddg.Pipeline(descs_for(wl), [s.cuda_stream for s in st] if st else None)
+    fst = [torch.cuda.Stream() for _ in range(K)] if streams else None   # forward streams of their own
+    pipe = ddg.Pipeline(descs_for(wl, fstreams=[s.cuda_stream for s in fst] if fst else None),
+                        [s.cuda_stream for s in st] if st else None)
     mods = {k: pipe.module(k) for k in range(1, K + 1)}
     oracle = orc.OracleNet.from_workload(wl, dtype="f64")
     init_both(wl, mods, oracle, perturb_bn)

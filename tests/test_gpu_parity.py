@@ -80,10 +80,12 @@ def test_streams_graphs_and_single_stream_agree_bitwise(H):
     import paper_1804_10574_amd as ddg
     wl = custom_cifar(1, [1, 3], batch=8, num_classes=10, hw=16, dtype="bf16", name="k3")
     res = []
-    for mode in ("graphs", "streams", "serial"):
+    for mode in ("graphs+forward-streams", "graphs", "streams", "serial"):
         st = [torch.cuda.Stream() for _ in range(wl.K)] if mode != "serial" else None
-        pipe = ddg.Pipeline(H.descs_for(wl), [s.cuda_stream for s in st] if st else None)
-        pipe.set_graphs(mode == "graphs")
+        fst = [torch.cuda.Stream() for _ in range(wl.K)] if mode == "graphs+forward-streams" else None
+        pipe = ddg.Pipeline(H.descs_for(wl, fstreams=[s.cuda_stream for s in fst] if fst else None),
+                            [s.cuda_stream for s in st] if st else None)
+        pipe.set_graphs(mode.startswith("graphs"))
         for m in wl.modules:
             pipe.module(m.k).set_params(wk.init_module_params(wl, m, perturb_bn=True).astype(np.float32))
         keep, snaps = [], []
@@ -118,7 +120,9 @@ def test_bottleneck_module_with_synthetic_delta(H, dtype):
     wl.lr = 0.05
     tol = TOL[dtype]
     m = wl.modules[0]
-    mod = ddg.Module(H.descs_for(wl)[0])
+    # the module orders its own two streams here (forward on one, delayed backward on the other)
+    s_b, s_f = torch.cuda.Stream(), torch.cuda.Stream()
+    mod = ddg.Module(H.descs_for(wl, streams=[s_b.cuda_stream], fstreams=[s_f.cuda_stream])[0])
     oracle = orc.OracleNet.from_workload(wl, dtype="f64")
     H.init_both(wl, {m.k: mod}, oracle)
     shape_in = (wl.batch, m.in_c, m.in_h, m.in_w)
