@@ -24,75 +24,6 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def traffic_model(wl):
-    """Algorithmic bytes and flops per kernel family for one steady-state step.
-
-    Bytes: every operand read once and every result written once in its storage type
-    (conv: input + weights + output; BN/elementwise: the tensors the formula names).
-    Flops: 2*M*N*K per convolution pass. Returns {family: [launches, bytes, flops]}.
-    """
-    import workloads as wk
-    from workloads.configs import conv_units
-    esz = 2 if wl.dtype == "bf16" else 4
-    fam = {}
-
-    def add(name, nbytes, flops=0.0):
-        f = fam.setdefault(name, [0, 0.0, 0.0])
-        f[0] += 1
-        f[1] += nbytes
-        f[2] += flops
-
-    N = wl.batch
-    for m in wl.modules:
-        passes = 2 if m.k < wl.K else 1     # forward, and re-forward when the delay is > 0
-        h, w = m.in_h, m.in_w
-        first = True
-        for b in m.blocks:
-            if b.kind == wk.BLOCK_HEAD:
-                continue
-            units = conv_units(b)
-            nmain = len(units) - (1 if b.projection else 0)
-            ho, wo = (h - 1) // b.stride + 1, (w - 1) // b.stride + 1
-            uh, uw = h, w
-            main_out = []
-            for ui, (name, ci, co, r, st) in enumerate(units):
-                if name == "proj":
-                    ih, iw = h, w
-                else:
-                    ih, iw = uh, uw
-                p, q = (ih - 1) // st + 1, (iw - 1) // st + 1
-                e_in, e_out, e_w = N * ih * iw * ci, N * p * q * co, co * ci * r * r
-                flops = 2.0 * N * p * q * co * ci * r * r
-                for _ in range(passes):
-                    add("conv_fprop", (e_in + e_out + e_w) * esz, flops)
-                    add("bn_finalize", 0)
-                # backward of this unit
-                add("bn_bwd_reduce", 3 * e_out * esz)          # dy, mask, z
-                add("bn_bwd_finalize", 0)
-                add("bn_bwd_apply", 4 * e_out * esz)           # dy, mask, z -> dz
-                add("conv_wgrad", (e_in + e_out) * esz + e_w * 4, flops)
-                add("wgrad_reduce", e_w * 4)
-                needs_dx = not (first and m.k == 1 and (ui == 0 or name == "proj"))
-                if needs_dx:
-                    extra = 0
-                    if name != "proj" and ui == 0 and b.kind != wk.BLOCK_STEM:
-                        extra = e_in * esz * (1 if b.projection else 2)   # shortcut term (+mask)
-                    add("conv_dgrad", (e_in + e_out + e_w) * esz + extra, flops)
-                if name != "proj":
-                    uh, uw = p, q
-                    main_out.append(e_out)
-            # activations: z -> relu(bn(z)) between main units; the block output reads the last
-            # conv output and the shortcut (or the projection's conv output)
-            e_y = N * ho * wo * b.cout
-            for _ in range(passes):
-                for e_mid in main_out[:-1]:
-                    add("bn_apply", 2 * e_mid * esz)
-                add("bn_apply", (2 if b.kind == wk.BLOCK_STEM else 3) * e_y * esz)
-            h, w = ho, wo
-            first = False
-    return fam
-
-
 def build_pipeline(wl, serial=False, one_stream_per_module=False):
     import torch
     import numpy as np
@@ -210,32 +141,29 @@ def main():
         for _ in range(psteps):
             step(it); it += 1
         pipe.sync()
-        fam_t = {}
+        fam = {}
         for m in mods:
-            for name, (n, tms) in m.profile_read().items():
-                a = fam_t.setdefault(name, [0, 0.0]); a[0] += n; a[1] += tms
+            for name, (n, tms, nbytes, flops) in m.profile_read().items():
+                a = fam.setdefault(name, [0, 0.0, 0.0, 0.0])
+                a[0] += n; a[1] += tms; a[2] += nbytes; a[3] += flops
             m.profile_enable(False)
-        model = traffic_model(wl)
         kernels = {}
-        for name, (n, tms) in fam_t.items():
+        for name, (n, tms, nbytes, flops) in fam.items():
             if n == 0:
                 continue
-            launches = n / psteps
-            avg_ms = tms / n
-            e = {"launches_per_step": launches, "avg_us": avg_ms * 1e3, "ms_per_step": tms / psteps}
-            if name in model and model[name][1] > 0:
-                nb, fl = model[name][1], model[name][2]
-                e["algorithmic_GB_per_step"] = nb / 1e9
-                e["GBps"] = nb / 1e9 / (tms / psteps / 1e3)
-                if fl:
-                    e["TFLOPs"] = fl / 1e12 / (tms / psteps / 1e3)
+            e = {"launches_per_step": n / psteps, "avg_us": tms / n * 1e3, "ms_per_step": tms / psteps}
+            if nbytes > 0 and tms > 0:
+                e["algorithmic_MB_per_launch"] = nbytes / n / 1e6
+                e["GBps"] = nbytes / 1e9 / (tms / 1e3)
+            if flops > 0 and tms > 0:
+                e["TFLOPs"] = flops / 1e12 / (tms / 1e3)
             kernels[name] = e
         dom = max((k for k in kernels if "GBps" in kernels[k]), key=lambda k: kernels[k]["ms_per_step"])
         d = kernels[dom]
-        nb, fl = model[dom][1], model[dom][2]
-        ai = fl / nb if nb else 0.0
+        n, tms, nbytes, flops = fam[dom]
+        ai = flops / nbytes if nbytes else 0.0
         ridge = MFMA_PEAK_TFLOPS[wl.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
-        if fl and ai >= ridge:
+        if flops and ai >= ridge:
             roof = {"bound": "mfma", "achieved": d["TFLOPs"], "peak": MFMA_PEAK_TFLOPS[wl.dtype], "unit": "TFLOP/s"}
         else:
             roof = {"bound": "hbm", "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s"}
@@ -244,17 +172,21 @@ def main():
         roof["kernel"] = dom
         roof["avg_launch_us"] = d["avg_us"]
         roof["launches_per_step"] = d["launches_per_step"]
-        roof["algorithmic_bytes_per_launch"] = nb / max(model[dom][0], 1)
-        if fl:
+        roof["algorithmic_bytes_per_launch"] = nbytes / n
+        if flops:
+            roof["arithmetic_intensity_flop_per_byte"] = ai
             roof["mfma_frac"] = d["TFLOPs"] / MFMA_PEAK_TFLOPS[wl.dtype]
         out["roofline"] = roof
         out["kernels"] = kernels
-        conv_ms = sum(kernels[k]["ms_per_step"] for k in ("conv_fprop", "conv_dgrad", "conv_wgrad") if k in kernels)
-        conv_fl = sum(model[k][2] for k in ("conv_fprop", "conv_dgrad", "conv_wgrad") if k in model)
-        out["conv_mfma_util"] = conv_fl / 1e12 / (conv_ms / 1e3) / MFMA_PEAK_TFLOPS[wl.dtype] if conv_ms else None
+        convs = [k for k in ("conv_fprop", "conv_dgrad", "conv_wgrad") if k in kernels]
+        conv_ms = sum(fam[k][1] for k in convs)
+        out["conv_mfma_util"] = sum(fam[k][3] for k in convs) / 1e12 / (conv_ms / 1e3) / MFMA_PEAK_TFLOPS[wl.dtype] if conv_ms else None
+        out["conv_hbm_frac"] = sum(fam[k][2] for k in convs) / 1e9 / (conv_ms / 1e3) / HBM_PEAK_GBS if conv_ms else None
         bn = [k for k in ("bn_apply", "bn_bwd_reduce", "bn_bwd_apply") if k in kernels]
-        bn_ms = sum(kernels[k]["ms_per_step"] for k in bn)
-        out["bn_hbm_frac"] = sum(model[k][1] for k in bn) / 1e9 / (bn_ms / 1e3) / HBM_PEAK_GBS if bn_ms else None
+        bn_ms = sum(fam[k][1] for k in bn)
+        out["bn_hbm_frac"] = sum(fam[k][2] for k in bn) / 1e9 / (bn_ms / 1e3) / HBM_PEAK_GBS if bn_ms else None
+        out["algorithmic_GFLOP_per_step"] = sum(v[3] for v in fam.values()) / psteps / 1e9
+        out["algorithmic_GB_per_step"] = sum(v[2] for v in fam.values()) / psteps / 1e9
 
     pipe.close()
     if not args.no_cpu_baseline:

@@ -175,12 +175,15 @@ ddg_status ddg_pipeline_sync(ddg_pipeline* p);
 /* ---- measurement ----------------------------------------------------------------------------
  * Per-kernel-family timing with HIP events on the module's stream. While enabled, every launch
  * of a kernel family is bracketed by two events; ddg_profile_read synchronises and returns, for
- * family `kind` (0 <= kind < ddg_profile_kinds()), the number of launches and their summed
- * duration in milliseconds since the last reset. */
+ * family `kind` (0 <= kind < ddg_profile_kinds()), since the last reset: the number of launches,
+ * their summed duration in milliseconds, and their summed algorithmic work: bytes (each tensor a
+ * launch must read, once, plus each tensor it must write, once, in its storage type) and flops
+ * (2*M*N*K per convolution pass). Any output pointer may be NULL. */
 int ddg_profile_kinds(void);
 const char* ddg_profile_kind_name(int kind);
 ddg_status ddg_profile_enable(ddg_module* m, int on);
-ddg_status ddg_profile_read(ddg_module* m, int kind, long* launches, double* total_ms);
+ddg_status ddg_profile_read(ddg_module* m, int kind, long* launches, double* total_ms, double* bytes,
+                            double* flops);
 ddg_status ddg_profile_reset(ddg_module* m);
 
 const char* ddg_last_error(void);

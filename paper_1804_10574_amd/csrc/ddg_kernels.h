@@ -2,10 +2,27 @@
 // the module code checks shapes before it builds a plan.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
 namespace ddg {
+
+// Per-launch timing for the measurement pass: when a pair of events is armed, the next kernel
+// launch hands them to the runtime, which stamps them with that kernel's own begin and end
+// times (what a kernel trace shows), not with the time two extra stream markers are processed.
+struct ProfEvents { hipEvent_t a = nullptr, b = nullptr; bool armed = false; };
+extern thread_local ProfEvents g_prof_events;
+#define DDG_LAUNCH(kernel, grid, block, shmem, stream, ...)                                        \
+  do {                                                                                             \
+    if (ddg::g_prof_events.armed) {                                                                \
+      ddg::g_prof_events.armed = false;                                                            \
+      hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, ddg::g_prof_events.a,              \
+                            ddg::g_prof_events.b, 0, __VA_ARGS__);                                 \
+    } else {                                                                                       \
+      hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                         \
+    }                                                                                              \
+  } while (0)
 
 enum DType { F32 = 0, BF16 = 1 };
 inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }

@@ -16,6 +16,8 @@
 
 using namespace ddg;
 
+thread_local ddg::ProfEvents ddg::g_prof_events;
+
 static thread_local std::string g_err;
 static ddg_status fail(ddg_status st, const char* fmt, ...) {
   char buf[512];
@@ -111,10 +113,13 @@ struct ddg_module {
   const float* lr_dev = nullptr;   // step size in device memory, if set
   // profiling
   bool prof = false;
-  struct Ev { int kind; hipEvent_t a, b; };
+  struct Ev { int kind; hipEvent_t a, b; bool bracket; };
   std::vector<Ev> evs;
   long prof_n[PK_COUNT] = {0};
   double prof_ms[PK_COUNT] = {0};
+  double prof_bytes[PK_COUNT] = {0};
+  double prof_empty_ms = 0.0;      // mean length of an empty event bracket, subtracted per launch
+  double prof_flops[PK_COUNT] = {0};
 };
 
 namespace {
@@ -136,18 +141,29 @@ ddg_status dev_alloc(ddg_module* m, void** p, size_t bytes) {
   return DDG_OK;
 }
 
-struct Launch {  // brackets one launch with events when profiling
-  ddg_module* m; int kind; hipEvent_t a = nullptr, b = nullptr;
-  Launch(ddg_module* m_, int kind_) : m(m_), kind(kind_) {
+// Times one launch when profiling, and books the launch's algorithmic work: bytes = every
+// tensor the kernel must read once plus every tensor it must write once, in the storage type;
+// flops = 2*M*N*K of a convolution pass. Single-kernel families arm an event pair that the
+// launch itself stamps with the kernel's begin and end; families of several kernels are
+// bracketed by two stream markers instead.
+struct Launch {
+  ddg_module* m; int kind; hipEvent_t a = nullptr, b = nullptr; bool bracket = false;
+  Launch(ddg_module* m_, int kind_, double bytes = 0.0, double flops = 0.0) : m(m_), kind(kind_) {
     if (m->prof) {
+      m->prof_bytes[kind] += bytes; m->prof_flops[kind] += flops;
       (void)hipEventCreate(&a); (void)hipEventCreate(&b);
-      (void)hipEventRecord(a, m->stream);
+      bracket = (kind == PK_HEAD || kind == PK_BN_BWD_REDUCE);
+      if (bracket) (void)hipEventRecord(a, m->stream);
+      else { g_prof_events.a = a; g_prof_events.b = b; g_prof_events.armed = true; }
     }
   }
   ~Launch() {
     if (m->prof) {
-      (void)hipEventRecord(b, m->stream);
-      m->evs.push_back({kind, a, b});
+      if (bracket) (void)hipEventRecord(b, m->stream);
+      const bool launched = bracket || !g_prof_events.armed;
+      g_prof_events.armed = false;
+      if (launched) m->evs.push_back({kind, a, b, bracket});
+      else { (void)hipEventDestroy(a); (void)hipEventDestroy(b); }
     }
   }
 };
@@ -394,6 +410,10 @@ ddg_status pack_all(ddg_module* m) {
   return DDG_OK;
 }
 
+// Algorithmic work of one convolution pass over unit u.
+double conv_flops(const Unit& u) { return 2.0 * u.N * u.P * u.Q * (double)u.cout * u.cin * u.R * u.R; }
+double wbytes(const ddg_module* m, const Unit& u) { return (double)u.cout * u.cin * u.R * u.R * m->esz; }
+
 // The forward statistics of u as partial rows for a consuming kernel.
 BnRows fwd_rows(ddg_module* m, Unit& u) {
   BnRows r{};
@@ -416,7 +436,7 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src) {
     BnRows ir{};
     const bool from_rows = src && src->small_c();
     if (from_rows) ir = fwd_rows(m, *src);
-    Launch L(m, PK_CONV_FPROP);
+    Launch L(m, PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
     DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? src->scale : nullptr, (src && !from_rows) ? src->shift : nullptr,
                               from_rows ? &ir : nullptr, u.wpack_f, u.z, st, nullptr, nullptr, u.N, u.H, u.W,
                               u.cin, u.tiled_grid, m->stream));
@@ -426,7 +446,7 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src) {
     conv_plan(a);
     u.frows = a.grid_x;
     a.in = in; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = u.fstat; a.add_g = nullptr; a.add_mask = nullptr;
-    Launch L(m, PK_CONV_FPROP);
+    Launch L(m, PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
     DDG_TRY(conv_launch(a, m->stream));
   }
   if (!u.small_c()) {
@@ -445,7 +465,7 @@ ddg_status apply_bn(ddg_module* m, Unit& u, const void* res, Unit* ru, void* y) 
   const bool zrows = u.small_c(), rrows = ru && ru->small_c();
   if (zrows) zr = fwd_rows(m, u);
   if (rrows) rr = fwd_rows(m, *ru);
-  Launch L(m, PK_BN_APPLY);
+  Launch L(m, PK_BN_APPLY, ((res || ru) ? 3.0 : 2.0) * u.out_elems() * m->esz);
   DDG_TRY(bn_apply_launch(u.z, u.scale, u.shift, zrows ? &zr : nullptr, ru ? ru->z : res,
                           ru ? ru->scale : nullptr, ru ? ru->shift : nullptr, rrows ? &rr : nullptr, y,
                           u.out_elems(), u.cout, 1, m->d.compute, m->stream));
@@ -517,7 +537,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
   if (below_rows) *below_rows = 0;
   if (stats_rows <= 0) {
     stats_rows = bn_bwd_grid(E, u.cout, dt);
-    Launch L(m, PK_BN_BWD_REDUCE);
+    Launch L(m, PK_BN_BWD_REDUCE, (mask && mask != u.z ? 3.0 : 2.0) * E * m->esz);
     DDG_TRY(bn_bwd_reduce_launch(dy, mask, mscale, mshift, u.z, u.mean, u.invstd, u.bstat, E, u.cout, dt, m->stream));
   }
   BnBwdRows br{};
@@ -531,27 +551,34 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     WgradFuse f{};
     f.dy = dy; f.mask = mask; f.mscale = mscale; f.mshift = mshift; f.z = u.z; f.coef = nullptr; f.rows = &br;
     f.dz_out = dz_buf;
-    Launch L(m, PK_CONV_WGRAD);
+    // reads x, dy, z (and the mask tensor if it is a different one), writes dz and dW
+    Launch L(m, PK_CONV_WGRAD, (u.in_elems() + (mask && mask != u.z ? 4.0 : 3.0) * E) * m->esz + wbytes(m, u) * 4.0 / m->esz,
+             conv_flops(u));
     DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, nullptr, &f, u.wg_partial, u.N, u.H, u.W, u.cin,
                                u.wg_tiled_rows, m->stream));
   } else {
     if (u.small_c()) {
       // the apply kernel derives dgamma, dbeta and its coefficients from the rows
-      Launch L(m, PK_BN_BWD_APPLY);
+      Launch L(m, PK_BN_BWD_APPLY, (mask && mask != u.z ? 4.0 : 3.0) * E * m->esz);
       DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, nullptr, &br, dz_buf, E, u.cout, dt, m->stream));
     } else {
       { Launch L(m, PK_BN_BWD_FINALIZE);
         DDG_TRY(bn_bwd_finalize_launch(u.bstat, stats_rows, u.cout, m->theta + u.og, u.mean, u.invstd,
                                        (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
-      Launch L(m, PK_BN_BWD_APPLY);
+      Launch L(m, PK_BN_BWD_APPLY, (mask && mask != u.z ? 4.0 : 3.0) * E * m->esz);
       DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
     }
     if (x_scale) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
-    Launch L(m, PK_CONV_WGRAD);
+    Launch L(m, PK_CONV_WGRAD, (u.in_elems() + E) * (double)m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
     DDG_TRY(wgrad_launch(w, m->stream));
   }
   if (dx) {
-    Launch L(m, PK_CONV_DGRAD);
+    // reads dz and the weights, writes dx; plus the shortcut term (and its mask), plus the mask
+    // and conv output of the layer below when its BN-backward sums are formed here
+    const bool fuse_below = u.tiled_grid > 0 && below && below->u;
+    double extra = (add_g ? (add_mask ? 2.0 : 1.0) : 0.0);
+    if (fuse_below) extra += (below->mask == below->u->z) ? 1.0 : 2.0;
+    Launch L(m, PK_CONV_DGRAD, (E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u), conv_flops(u));
     if (u.tiled_grid > 0) {
       ConvStat st{};
       if (below && below->u) {
@@ -813,7 +840,7 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   // the forward stream needs the weights of update(t-1) and the ring slot that backward(t-1) read
   if (self_sync) DDG_TRY(hipStreamWaitEvent(m->fstream, m->ev_upd, 0));
   void* slot = m->ring[t % m->nslots];
-  { Launch L(m, PK_COPY); DDG_TRY(copy_launch(h_in, slot, m->in_elems * m->esz, m->stream)); }
+  { Launch L(m, PK_COPY, 2.0 * m->in_elems * m->esz); DDG_TRY(copy_launch(h_in, slot, m->in_elems * m->esz, m->stream)); }
   // A module with delay > 0 re-forwards before its backward, so this pass need not keep a
   // tape and writes straight to h_out; the last module keeps the tape for its own backward.
   if (m->delay > 0) {
@@ -856,7 +883,7 @@ ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, con
   m->tape_is_current = false;
   DDG_OKAY(run_backward(m, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out));
   // every layer's weight-gradient partials -> g (one launch for the module, fixed order)
-  Launch L(m, PK_WGRAD_REDUCE);
+  Launch L(m, PK_WGRAD_REDUCE, (double)m->nparams * 4.0);
   DDG_TRY(wgrad_reduce_all_launch(m->wred_descs, m->n_wred, m->stream));
   return DDG_OK;
 }
@@ -871,7 +898,7 @@ ddg_status ddg_update(ddg_module* m, long t, float lr) {
   const bool self_sync = m->two_streams && !m->external_sync;
   // the forward pass of this iteration must have finished reading the weights
   if (self_sync) DDG_TRY(hipStreamWaitEvent(m->bstream, m->ev_fwd[t & 1], 0));
-  { Launch L(m, PK_SGD);
+  { Launch L(m, PK_SGD, (double)m->nparams * 20.0);
     DDG_TRY(sgd_launch(m->theta, m->vel, m->grad, m->nparams, lr, m->lr_dev, m->d.momentum, m->d.weight_decay, m->stream)); }
   DDG_OKAY(pack_all(m));
   if (self_sync) DDG_TRY(hipEventRecord(m->ev_upd, m->bstream));
@@ -898,7 +925,10 @@ static ddg_status prof_collect(ddg_module* m) {
   DDG_OKAY(sync_streams(m));
   for (auto& e : m->evs) {
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) { m->prof_n[e.kind] += 1; m->prof_ms[e.kind] += ms; }
+    if (hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) {
+      const double d = (double)ms - (e.bracket ? m->prof_empty_ms : 0.0);
+      m->prof_n[e.kind] += 1; m->prof_ms[e.kind] += d > 0.0 ? d : 0.0;
+    }
     (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b);
   }
   m->evs.clear();
@@ -910,22 +940,44 @@ ddg_status ddg_profile_enable(ddg_module* m, int on) {
   if (m->d.dry_run) return DDG_OK;
   DDG_OKAY(prof_collect(m));
   m->prof = on != 0;
+  if (m->prof) {
+    // An event bracket around nothing still has a length (the two records are processed one
+    // after the other); measure it so that it can be taken off every bracketed launch.
+    DDG_OKAY(sync_streams(m));
+    const int reps = 32;
+    hipEvent_t a[reps], b[reps];
+    for (int i = 0; i < reps; ++i) {
+      DDG_TRY(hipEventCreate(&a[i])); DDG_TRY(hipEventCreate(&b[i]));
+      DDG_TRY(hipEventRecord(a[i], m->bstream)); DDG_TRY(hipEventRecord(b[i], m->bstream));
+    }
+    DDG_TRY(hipStreamSynchronize(m->bstream));
+    double sum = 0.0;
+    for (int i = 0; i < reps; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, a[i], b[i]) == hipSuccess) sum += ms;
+      (void)hipEventDestroy(a[i]); (void)hipEventDestroy(b[i]);
+    }
+    m->prof_empty_ms = sum / reps;
+  }
   return DDG_OK;
 }
 
-ddg_status ddg_profile_read(ddg_module* m, int kind, long* launches, double* total_ms) {
+ddg_status ddg_profile_read(ddg_module* m, int kind, long* launches, double* total_ms, double* bytes,
+                            double* flops) {
   DDG_OKAY(check_handle(m));
   if (kind < 0 || kind >= PK_COUNT) return fail(DDG_ERR_INVALID_ARG, "kind out of range");
   if (!m->d.dry_run) DDG_OKAY(prof_collect(m));
   if (launches) *launches = m->prof_n[kind];
   if (total_ms) *total_ms = m->prof_ms[kind];
+  if (bytes) *bytes = m->prof_bytes[kind];
+  if (flops) *flops = m->prof_flops[kind];
   return DDG_OK;
 }
 
 ddg_status ddg_profile_reset(ddg_module* m) {
   DDG_OKAY(check_handle(m));
   if (!m->d.dry_run) DDG_OKAY(prof_collect(m));
-  for (int i = 0; i < PK_COUNT; ++i) { m->prof_n[i] = 0; m->prof_ms[i] = 0; }
+  for (int i = 0; i < PK_COUNT; ++i) { m->prof_n[i] = 0; m->prof_ms[i] = 0; m->prof_bytes[i] = 0; m->prof_flops[i] = 0; }
   return DDG_OK;
 }
 

@@ -202,8 +202,8 @@ static hipError_t conv_dispatch(const ConvArgs& a, hipStream_t s) {
   dim3 grid(a.grid_x, (a.OC / 16) / a.nb), block(256);
 #define DDG_CONV_CASE(MB_, NB_)                                                          \
   if (a.mb == MB_ && a.nb == NB_) {                                                      \
-    if (a.dgrad) hipLaunchKernelGGL((conv_mfma_kernel<T, MB_, NB_, true>), grid, block, 0, s, a);  \
-    else hipLaunchKernelGGL((conv_mfma_kernel<T, MB_, NB_, false>), grid, block, 0, s, a);         \
+    if (a.dgrad) DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, true>), grid, block, 0, s, a);  \
+    else DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, false>), grid, block, 0, s, a);         \
     return hipGetLastError();                                                            \
   }
   DDG_CONV_CASE(4, 1)
@@ -272,8 +272,8 @@ __global__ void pack_all_kernel(const PackDesc* __restrict__ descs) {
 
 hipError_t pack_all_launch(const PackDesc* dev_descs, int n, int dtype, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  if (dtype == BF16) hipLaunchKernelGGL(pack_all_kernel<bf16_t>, dim3(16, n), dim3(256), 0, s, dev_descs);
-  else hipLaunchKernelGGL(pack_all_kernel<float>, dim3(16, n), dim3(256), 0, s, dev_descs);
+  if (dtype == BF16) DDG_LAUNCH(pack_all_kernel<bf16_t>, dim3(16, n), dim3(256), 0, s, dev_descs);
+  else DDG_LAUNCH(pack_all_kernel<float>, dim3(16, n), dim3(256), 0, s, dev_descs);
   return hipGetLastError();
 }
 
@@ -285,10 +285,10 @@ hipError_t pack_weights_launch(const float* W, void* wpack, int Cout, int Cin, i
   int grid = (int)((total + 255) / 256);
   if (grid > 1024) grid = 1024;
   if (dtype == BF16)
-    hipLaunchKernelGGL(pack_weights_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, W,
+    DDG_LAUNCH(pack_weights_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, W,
                        reinterpret_cast<bf16_t*>(wpack), Cout, Cin, R, dgrad, log2cp, ksteps, nc / 16);
   else
-    hipLaunchKernelGGL(pack_weights_kernel<float>, dim3(grid), dim3(256), 0, s, W,
+    DDG_LAUNCH(pack_weights_kernel<float>, dim3(grid), dim3(256), 0, s, W,
                        reinterpret_cast<float*>(wpack), Cout, Cin, R, dgrad, log2cp, ksteps, nc / 16);
   return hipGetLastError();
 }

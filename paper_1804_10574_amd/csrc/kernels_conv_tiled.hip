@@ -264,7 +264,7 @@ int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, i
 template <int C, int W>
 static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStream_t s) {
   using Cfg = ConvTiledCfg<C, W>;
-  hipLaunchKernelGGL((conv3x3_tiled_kernel<C, W>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+  DDG_LAUNCH((conv3x3_tiled_kernel<C, W>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
   return hipGetLastError();
 }
 

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(1024) void bn_finalize_kernel(const float* __restri
 hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                               const float* beta, float count, float eps, float* mean, float* invstd,
                               float* scale, float* shift, hipStream_t s) {
-  hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 15) / 16), dim3(1024), 0, s, partial, rows, C, gamma,
+  DDG_LAUNCH(bn_finalize_kernel, dim3((C + 15) / 16), dim3(1024), 0, s, partial, rows, C, gamma,
                      beta, count, eps, mean, invstd, scale, shift);
   return hipGetLastError();
 }
@@ -119,11 +119,11 @@ hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift
   const int maxb = (zrows || rrows) ? 512 : 2048;
   if (dtype == BF16) {
     const size_t nvec = elems / 8;
-    hipLaunchKernelGGL(bn_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, maxb)), dim3(256), 0, s,
+    DDG_LAUNCH(bn_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, maxb)), dim3(256), 0, s,
                        (const bf16_t*)z, scale, shift, zr, (const bf16_t*)res, rscale, rshift, rr, (bf16_t*)y, nvec, C, relu);
   } else {
     const size_t nvec = elems / 4;
-    hipLaunchKernelGGL(bn_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, maxb)), dim3(256), 0, s,
+    DDG_LAUNCH(bn_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, maxb)), dim3(256), 0, s,
                        (const float*)z, scale, shift, zr, (const float*)res, rscale, rshift, rr, (float*)y, nvec, C, relu);
   }
   return hipGetLastError();
@@ -209,13 +209,13 @@ hipError_t bn_bwd_reduce_launch(const void* dy, const void* mask, const float* m
   const int grid = bn_bwd_grid(elems, C, dtype);
   if (C > 256 * V) {  // a block's row is only partly written: clear the rows first
     const size_t n = (size_t)grid * 2 * C;
-    hipLaunchKernelGGL(zero_f32_kernel<float>, dim3(256), dim3(256), 0, s, partial, n);
+    DDG_LAUNCH(zero_f32_kernel<float>, dim3(256), dim3(256), 0, s, partial, n);
   }
   if (dtype == BF16)
-    hipLaunchKernelGGL(bn_bwd_reduce_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)dy,
+    DDG_LAUNCH(bn_bwd_reduce_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)dy,
                        (const bf16_t*)mask, mscale, mshift, (const bf16_t*)z, mean, invstd, partial, elems / 8, C);
   else
-    hipLaunchKernelGGL(bn_bwd_reduce_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)dy,
+    DDG_LAUNCH(bn_bwd_reduce_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)dy,
                        (const float*)mask, mscale, mshift, (const float*)z, mean, invstd, partial, elems / 4, C);
   return hipGetLastError();
 }
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(1024) void bn_bwd_finalize_kernel(const float* __re
 hipError_t bn_bwd_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                                   const float* mean, const float* invstd, float count, float* dgamma,
                                   float* dbeta, float* coef, hipStream_t s) {
-  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 15) / 16), dim3(1024), 0, s, partial, rows, C, gamma,
+  DDG_LAUNCH(bn_bwd_finalize_kernel, dim3((C + 15) / 16), dim3(1024), 0, s, partial, rows, C, gamma,
                      mean, invstd, count, dgamma, dbeta, coef);
   return hipGetLastError();
 }
@@ -303,11 +303,11 @@ hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const float* ms
   const int maxb = rows ? 512 : 2048;
   if (dtype == BF16) {
     const size_t nvec = elems / 8;
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, maxb)), dim3(256), 0, s,
+    DDG_LAUNCH(bn_bwd_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, maxb)), dim3(256), 0, s,
                        (const bf16_t*)dy, (const bf16_t*)mask, mscale, mshift, (const bf16_t*)z, coef, br, (bf16_t*)dz, nvec, C);
   } else {
     const size_t nvec = elems / 4;
-    hipLaunchKernelGGL(bn_bwd_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, maxb)), dim3(256), 0, s,
+    DDG_LAUNCH(bn_bwd_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, maxb)), dim3(256), 0, s,
                        (const float*)dy, (const float*)mask, mscale, mshift, (const float*)z, coef, br, (float*)dz, nvec, C);
   }
   return hipGetLastError();
@@ -388,18 +388,18 @@ __global__ void head_dh_kernel(const float* __restrict__ dlogits, const float* _
 hipError_t head_launch(const HeadArgs& a, hipStream_t s) {
   const int tc = a.C < 64 ? 64 : (a.C > 256 ? 256 : a.C);
   if (a.dtype == BF16)
-    hipLaunchKernelGGL(head_pool_kernel<bf16_t>, dim3(a.N), dim3(tc), 0, s, (const bf16_t*)a.h, a.pooled, a.HW, a.C);
+    DDG_LAUNCH(head_pool_kernel<bf16_t>, dim3(a.N), dim3(tc), 0, s, (const bf16_t*)a.h, a.pooled, a.HW, a.C);
   else
-    hipLaunchKernelGGL(head_pool_kernel<float>, dim3(a.N), dim3(tc), 0, s, (const float*)a.h, a.pooled, a.HW, a.C);
-  hipLaunchKernelGGL(head_loss_kernel, dim3(a.N), dim3(128), a.classes * sizeof(float), s, a.pooled, a.fcw,
+    DDG_LAUNCH(head_pool_kernel<float>, dim3(a.N), dim3(tc), 0, s, (const float*)a.h, a.pooled, a.HW, a.C);
+  DDG_LAUNCH(head_loss_kernel, dim3(a.N), dim3(128), a.classes * sizeof(float), s, a.pooled, a.fcw,
                      a.fcb, a.labels, a.dlogits, a.loss_n, a.N, a.C, a.classes);
-  hipLaunchKernelGGL(head_wgrad_kernel, dim3(a.classes), dim3(tc), 0, s, a.pooled, a.dlogits, a.loss_n, a.dfcw,
+  DDG_LAUNCH(head_wgrad_kernel, dim3(a.classes), dim3(tc), 0, s, a.pooled, a.dlogits, a.loss_n, a.dfcw,
                      a.dfcb, a.loss_out, a.N, a.C, a.classes);
   if (a.dh) {
     if (a.dtype == BF16)
-      hipLaunchKernelGGL(head_dh_kernel<bf16_t>, dim3(a.N), dim3(tc), 0, s, a.dlogits, a.fcw, (bf16_t*)a.dh, a.HW, a.C, a.classes);
+      DDG_LAUNCH(head_dh_kernel<bf16_t>, dim3(a.N), dim3(tc), 0, s, a.dlogits, a.fcw, (bf16_t*)a.dh, a.HW, a.C, a.classes);
     else
-      hipLaunchKernelGGL(head_dh_kernel<float>, dim3(a.N), dim3(tc), 0, s, a.dlogits, a.fcw, (float*)a.dh, a.HW, a.C, a.classes);
+      DDG_LAUNCH(head_dh_kernel<float>, dim3(a.N), dim3(tc), 0, s, a.dlogits, a.fcw, (float*)a.dh, a.HW, a.C, a.classes);
   }
   return hipGetLastError();
 }
@@ -421,7 +421,7 @@ __global__ void sgd_kernel(float* __restrict__ w, float* __restrict__ v, const f
 __global__ void set_scalar_kernel(float* dst, float v) { *dst = v; }
 
 hipError_t set_scalar_launch(float* dst, float v, hipStream_t s) {
-  hipLaunchKernelGGL(set_scalar_kernel, dim3(1), dim3(1), 0, s, dst, v);
+  DDG_LAUNCH(set_scalar_kernel, dim3(1), dim3(1), 0, s, dst, v);
   return hipGetLastError();
 }
 
@@ -430,7 +430,7 @@ hipError_t sgd_launch(float* w, float* v, const float* g, size_t n, float lr, co
   int grid = (int)((n + 255) / 256);
   if (grid > 2048) grid = 2048;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL(sgd_kernel, dim3(grid), dim3(256), 0, s, w, v, g, n, lr, lr_dev, mu, wd);
+  DDG_LAUNCH(sgd_kernel, dim3(grid), dim3(256), 0, s, w, v, g, n, lr, lr_dev, mu, wd);
   return hipGetLastError();
 }
 
@@ -448,7 +448,7 @@ hipError_t copy_launch(const void* src, void* dst, size_t bytes, hipStream_t s) 
   int grid = (int)((nvec + 255) / 256);
   if (grid > 2048) grid = 2048;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, nvec,
+  DDG_LAUNCH(copy_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, nvec,
                      (const unsigned char*)src, (unsigned char*)dst, nvec * 16, bytes);
   return hipGetLastError();
 }
@@ -463,8 +463,8 @@ hipError_t to_f32_launch(const void* src, float* dst, size_t elems, int dtype, h
   int grid = (int)((elems + 255) / 256);
   if (grid > 2048) grid = 2048;
   if (grid < 1) grid = 1;
-  if (dtype == BF16) hipLaunchKernelGGL(to_f32_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)src, dst, elems);
-  else hipLaunchKernelGGL(to_f32_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)src, dst, elems);
+  if (dtype == BF16) DDG_LAUNCH(to_f32_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)src, dst, elems);
+  else DDG_LAUNCH(to_f32_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)src, dst, elems);
   return hipGetLastError();
 }
 

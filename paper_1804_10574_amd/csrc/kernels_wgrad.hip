@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_all_kernel(const WredDesc* _
 
 hipError_t wgrad_reduce_all_launch(const WredDesc* dev_descs, int n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(wgrad_reduce_all_kernel, dim3(48, n), dim3(256), 0, s, dev_descs);
+  DDG_LAUNCH(wgrad_reduce_all_kernel, dim3(48, n), dim3(256), 0, s, dev_descs);
   return hipGetLastError();
 }
 
@@ -160,14 +160,14 @@ size_t wgrad_partial_elems(const WgradArgs& a) { return (size_t)a.msplit * a.Cou
 
 hipError_t wgrad_launch(const WgradArgs& a, hipStream_t s) {
   dim3 grid(a.msplit, a.Cout / 16, a.jgroups), block(256);
-  if (a.dtype == BF16) hipLaunchKernelGGL(wgrad_mfma_kernel<bf16_t>, grid, block, 0, s, a);
-  else hipLaunchKernelGGL(wgrad_mfma_kernel<float>, grid, block, 0, s, a);
+  if (a.dtype == BF16) DDG_LAUNCH(wgrad_mfma_kernel<bf16_t>, grid, block, 0, s, a);
+  else DDG_LAUNCH(wgrad_mfma_kernel<float>, grid, block, 0, s, a);
   return hipGetLastError();
 }
 
 hipError_t wgrad_reduce_launch(const WgradArgs& a, hipStream_t s) {
   const int total = a.Cout * a.JB * 16;
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((total + 15) / 16), dim3(256), 0, s, a);
+  DDG_LAUNCH(wgrad_reduce_kernel, dim3((total + 15) / 16), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -289,7 +289,7 @@ static hipError_t wgrad_tiled_launch_t(const WgradTiledArgs& a, int grid_x, hipS
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((wgrad_tiled_kernel<CIN, COUT, W>), dim3(grid_x, Cfg::OT), dim3(256), lds, s, a);
+  DDG_LAUNCH((wgrad_tiled_kernel<CIN, COUT, W>), dim3(grid_x, Cfg::OT), dim3(256), lds, s, a);
   return hipGetLastError();
 }
 

@@ -78,7 +78,8 @@ def load_library():
         "ddg_profile_kinds": (C.c_int, []),
         "ddg_profile_kind_name": (C.c_char_p, [C.c_int]),
         "ddg_profile_enable": (st, [vp, C.c_int]),
-        "ddg_profile_read": (st, [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double)]),
+        "ddg_profile_read": (st, [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double),
+                                  C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "ddg_profile_reset": (st, [vp]),
         "ddg_last_error": (C.c_char_p, []),
         "ddg_version": (C.c_char_p, []),
@@ -222,12 +223,12 @@ class Module:
         _check(self._lib.ddg_profile_reset(self._h))
 
     def profile_read(self):
-        """-> {kind name: (launches, total_ms)}"""
+        """-> {kind name: (launches, total_ms, algorithmic bytes, algorithmic flops)}"""
         out = {}
         for i, name in enumerate(profile_kinds()):
-            n, ms = C.c_long(), C.c_double()
-            _check(self._lib.ddg_profile_read(self._h, i, C.byref(n), C.byref(ms)))
-            out[name] = (n.value, ms.value)
+            n, ms, nb, fl = C.c_long(), C.c_double(), C.c_double(), C.c_double()
+            _check(self._lib.ddg_profile_read(self._h, i, C.byref(n), C.byref(ms), C.byref(nb), C.byref(fl)))
+            out[name] = (n.value, ms.value, nb.value, fl.value)
         return out
 
 
