@@ -24,7 +24,24 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def build_pipeline(wl, serial=False, one_stream_per_module=False):
+# profile kind -> the HIP kernel it times (as rocprofv3 names it)
+HIP_KERNEL_OF = {
+    "conv_fprop.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 1>",
+    "conv_fprop.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 1>",
+    "conv_fprop.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 1>",
+    "conv_dgrad.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 2> (and <16, 32, 0>)",
+    "conv_dgrad.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 2> (and <32, 16, 0>)",
+    "conv_dgrad.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 2> (and <64, 8, 0>)",
+    "conv_wgrad.tiled_c16_w32": "ddg::wgrad_tiled_kernel<16, 16, 32>",
+    "conv_wgrad.tiled_c32_w16": "ddg::wgrad_tiled_kernel<32, 32, 16>",
+    "conv_wgrad.tiled_c64_w8": "ddg::wgrad_tiled_kernel<64, 64, 8>",
+    "conv_fprop.generic": "ddg::conv_mfma_kernel<T, MB, NB, false>",
+    "conv_dgrad.generic": "ddg::conv_mfma_kernel<T, MB, NB, true>",
+    "conv_wgrad.generic": "ddg::wgrad_mfma_kernel<T>",
+}
+
+
+def build_pipeline(wl, serial=False, forward_streams=False):
     import torch
     import numpy as np
     import workloads as wk
@@ -39,7 +56,7 @@ def build_pipeline(wl, serial=False, one_stream_per_module=False):
                                wl.num_classes if m.blocks[-1].kind == wk.BLOCK_HEAD else 0,
                                ddg.DDG_BF16 if wl.dtype == "bf16" else ddg.DDG_F32,
                                wl.momentum, wl.weight_decay, wl.bn_eps,
-                               forward_stream=None if (serial or one_stream_per_module) else fstreams[m.k - 1].cuda_stream))
+                               forward_stream=fstreams[m.k - 1].cuda_stream if (forward_streams and not serial) else None))
     pipe = ddg.Pipeline(descs, None if serial else [s.cuda_stream for s in streams])
     for m in wl.modules:
         pipe.module(m.k).set_params(wk.init_module_params(wl, m).astype(np.float32))
@@ -79,8 +96,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="all modules on one stream")
-    ap.add_argument("--one-stream-per-module", action="store_true",
-                    help="forward and delayed backward of a module share one stream")
+    ap.add_argument("--forward-streams", action="store_true",
+                    help="give each module's forward pass a stream of its own (2K-1 streams; "
+                         "slower than K streams on this GPU, kept for comparison)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (modules are concurrent streams on one "
@@ -95,7 +113,7 @@ def main():
     wl = wk.get_workload(args.workload)
     if wl.single_module:
         raise SystemExit("bench.py times full pipelines; single-module workloads are parity cases")
-    pipe, streams = build_pipeline(wl, args.serial, args.one_stream_per_module)
+    pipe, streams = build_pipeline(wl, args.serial, args.forward_streams)
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     # a few distinct minibatches, resident in HBM before the timed region
     nbuf = 4
@@ -127,7 +145,7 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "network": wl.notes, "K": wl.K, "global_batch": wl.batch,
-                   "image": "3x32x32", "classes": wl.num_classes, "streams": 1 if args.serial else (wl.K if args.one_stream_per_module else 2 * wl.K - 1),
+                   "image": "3x32x32", "classes": wl.num_classes, "streams": 1 if args.serial else (2 * wl.K - 1 if args.forward_streams else wl.K),
                    "parallelism": "K modules as HIP streams on one GPU"},
         "final_loss": final_loss,
     }
@@ -147,17 +165,23 @@ def main():
                 a = fam.setdefault(name, [0, 0.0, 0.0, 0.0])
                 a[0] += n; a[1] += tms; a[2] += nbytes; a[3] += flops
             m.profile_enable(False)
-        kernels = {}
-        for name, (n, tms, nbytes, flops) in fam.items():
-            if n == 0:
-                continue
+        def entry(n, tms, nbytes, flops):
             e = {"launches_per_step": n / psteps, "avg_us": tms / n * 1e3, "ms_per_step": tms / psteps}
             if nbytes > 0 and tms > 0:
                 e["algorithmic_MB_per_launch"] = nbytes / n / 1e6
                 e["GBps"] = nbytes / 1e9 / (tms / 1e3)
             if flops > 0 and tms > 0:
                 e["TFLOPs"] = flops / 1e12 / (tms / 1e3)
-            kernels[name] = e
+            return e
+
+        # the library books one kind per kernel ("family.instance"); families are their sums
+        kernels = {name: entry(*v) for name, v in fam.items() if v[0]}
+        famsum = {}
+        for name, v in fam.items():
+            a = famsum.setdefault(name.split(".")[0], [0, 0.0, 0.0, 0.0])
+            for i in range(4):
+                a[i] += v[i]
+        families = {name: entry(*v) for name, v in famsum.items() if v[0]}
         dom = max((k for k in kernels if "GBps" in kernels[k]), key=lambda k: kernels[k]["ms_per_step"])
         d = kernels[dom]
         n, tms, nbytes, flops = fam[dom]
@@ -168,8 +192,17 @@ def main():
         else:
             roof = {"bound": "hbm", "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s"}
         roof["frac"] = roof["achieved"] / roof["peak"]
+        # measured HBM bytes per launch of this kernel: from the committed counter summary of the
+        # same workload (two rocprofv3 --pmc passes, calibrated by the library's copy kernel)
         roof["traffic"] = None
+        tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                             f"hbm_traffic_{wl.name}_{wl.dtype}.txt")
+        if os.path.exists(tpath):
+            from paper_1804_10574_amd.profile_summary import read_traffic_table
+            roof["traffic"] = read_traffic_table(tpath).get(dom)
+            roof["traffic_source"] = os.path.relpath(tpath, os.path.dirname(os.path.abspath(__file__)))
         roof["kernel"] = dom
+        roof["hip_kernel"] = HIP_KERNEL_OF.get(dom, dom)
         roof["avg_launch_us"] = d["avg_us"]
         roof["launches_per_step"] = d["launches_per_step"]
         roof["algorithmic_bytes_per_launch"] = nbytes / n
@@ -178,13 +211,14 @@ def main():
             roof["mfma_frac"] = d["TFLOPs"] / MFMA_PEAK_TFLOPS[wl.dtype]
         out["roofline"] = roof
         out["kernels"] = kernels
-        convs = [k for k in ("conv_fprop", "conv_dgrad", "conv_wgrad") if k in kernels]
-        conv_ms = sum(fam[k][1] for k in convs)
-        out["conv_mfma_util"] = sum(fam[k][3] for k in convs) / 1e12 / (conv_ms / 1e3) / MFMA_PEAK_TFLOPS[wl.dtype] if conv_ms else None
-        out["conv_hbm_frac"] = sum(fam[k][2] for k in convs) / 1e9 / (conv_ms / 1e3) / HBM_PEAK_GBS if conv_ms else None
-        bn = [k for k in ("bn_apply", "bn_bwd_reduce", "bn_bwd_apply") if k in kernels]
-        bn_ms = sum(fam[k][1] for k in bn)
-        out["bn_hbm_frac"] = sum(fam[k][2] for k in bn) / 1e9 / (bn_ms / 1e3) / HBM_PEAK_GBS if bn_ms else None
+        out["families"] = families
+        convs = [k for k in ("conv_fprop", "conv_dgrad", "conv_wgrad") if k in families]
+        conv_ms = sum(famsum[k][1] for k in convs)
+        out["conv_mfma_util"] = sum(famsum[k][3] for k in convs) / 1e12 / (conv_ms / 1e3) / MFMA_PEAK_TFLOPS[wl.dtype] if conv_ms else None
+        out["conv_hbm_frac"] = sum(famsum[k][2] for k in convs) / 1e9 / (conv_ms / 1e3) / HBM_PEAK_GBS if conv_ms else None
+        bn = [k for k in ("bn_apply", "bn_bwd_reduce", "bn_bwd_apply") if k in families]
+        bn_ms = sum(famsum[k][1] for k in bn)
+        out["bn_hbm_frac"] = sum(famsum[k][2] for k in bn) / 1e9 / (bn_ms / 1e3) / HBM_PEAK_GBS if bn_ms else None
         out["algorithmic_GFLOP_per_step"] = sum(v[3] for v in fam.values()) / psteps / 1e9
         out["algorithmic_GB_per_step"] = sum(v[2] for v in fam.values()) / psteps / 1e9
 

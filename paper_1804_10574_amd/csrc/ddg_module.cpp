@@ -29,12 +29,20 @@ static ddg_status fail(ddg_status st, const char* fmt, ...) {
   return st;
 }
 
+// One kind per kernel (the three convolution passes: the generic kernel, then one kind per
+// instance of the LDS-tiled kernel, in the order 16, 32, 64 channels); "family.instance" names.
 enum ProfKind {
-  PK_CONV_FPROP = 0, PK_CONV_DGRAD, PK_CONV_WGRAD, PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
+  PK_CONV_FPROP = 0, PK_CONV_FPROP_T16, PK_CONV_FPROP_T32, PK_CONV_FPROP_T64,
+  PK_CONV_DGRAD, PK_CONV_DGRAD_T16, PK_CONV_DGRAD_T32, PK_CONV_DGRAD_T64,
+  PK_CONV_WGRAD, PK_CONV_WGRAD_T16, PK_CONV_WGRAD_T32, PK_CONV_WGRAD_T64,
+  PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
   PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_COUNT
 };
 static const char* kProfNames[PK_COUNT] = {
-  "conv_fprop", "conv_dgrad", "conv_wgrad", "wgrad_reduce", "bn_finalize", "bn_apply",
+  "conv_fprop.generic", "conv_fprop.tiled_c16_w32", "conv_fprop.tiled_c32_w16", "conv_fprop.tiled_c64_w8",
+  "conv_dgrad.generic", "conv_dgrad.tiled_c16_w32", "conv_dgrad.tiled_c32_w16", "conv_dgrad.tiled_c64_w8",
+  "conv_wgrad.generic", "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c32_w16", "conv_wgrad.tiled_c64_w8",
+  "wgrad_reduce", "bn_finalize", "bn_apply",
   "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy"};
 
 struct Unit {  // convolution + batch normalisation
@@ -59,6 +67,7 @@ struct Unit {  // convolution + batch normalisation
   float* bstat = nullptr;       // partial rows of the BN-backward sums [brows][2][cout]
   int frows = 0;                // rows written by the last forward conv
   bool small_c() const { return cout <= 64; }   // consumers finalise the rows themselves
+  int tiled_instance() const { return cin == 16 ? 1 : cin == 32 ? 2 : 3; }   // offset of a tiled kernel's profile kind
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
   size_t in_elems() const { return (size_t)N * H * W * cin; }
 };
@@ -436,7 +445,7 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src) {
     BnRows ir{};
     const bool from_rows = src && src->small_c();
     if (from_rows) ir = fwd_rows(m, *src);
-    Launch L(m, PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
+    Launch L(m, PK_CONV_FPROP + u.tiled_instance(), (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
     DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? src->scale : nullptr, (src && !from_rows) ? src->shift : nullptr,
                               from_rows ? &ir : nullptr, u.wpack_f, u.z, st, nullptr, nullptr, u.N, u.H, u.W,
                               u.cin, u.tiled_grid, m->stream));
@@ -552,7 +561,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     f.dy = dy; f.mask = mask; f.mscale = mscale; f.mshift = mshift; f.z = u.z; f.coef = nullptr; f.rows = &br;
     f.dz_out = dz_buf;
     // reads x, dy, z (and the mask tensor if it is a different one), writes dz and dW
-    Launch L(m, PK_CONV_WGRAD, (u.in_elems() + (mask && mask != u.z ? 4.0 : 3.0) * E) * m->esz + wbytes(m, u) * 4.0 / m->esz,
+    Launch L(m, PK_CONV_WGRAD + u.tiled_instance(), (u.in_elems() + (mask && mask != u.z ? 4.0 : 3.0) * E) * m->esz + wbytes(m, u) * 4.0 / m->esz,
              conv_flops(u));
     DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, nullptr, &f, u.wg_partial, u.N, u.H, u.W, u.cin,
                                u.wg_tiled_rows, m->stream));
@@ -578,7 +587,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     const bool fuse_below = u.tiled_grid > 0 && below && below->u;
     double extra = (add_g ? (add_mask ? 2.0 : 1.0) : 0.0);
     if (fuse_below) extra += (below->mask == below->u->z) ? 1.0 : 2.0;
-    Launch L(m, PK_CONV_DGRAD, (E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u), conv_flops(u));
+    Launch L(m, PK_CONV_DGRAD + (u.tiled_grid > 0 ? u.tiled_instance() : 0), (E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u), conv_flops(u));
     if (u.tiled_grid > 0) {
       ConvStat st{};
       if (below && below->u) {

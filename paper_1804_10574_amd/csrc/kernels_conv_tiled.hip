@@ -47,7 +47,9 @@ struct ConvTiledCfg {
   static constexpr int COB = C / 16;
 };
 
-template <int C, int W>
+// MODE is the epilogue's statistics mode, fixed at compile time: 0 none, 1 sum / sum of squares
+// of the stored output (forward), 2 the BN-backward sums of the layer below (input gradient).
+template <int C, int W, int MODE>
 __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   using Cfg = ConvTiledCfg<C, W>;
   constexpr int TH = Cfg::TH, WC = Cfg::WC, PIX = Cfg::PIX, CH = Cfg::CH, NCHUNK = Cfg::NCHUNK;
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   float bmu[4], bis[4], bms[4], bmh[4];
   const bf16_t* st_mask = reinterpret_cast<const bf16_t*>(a.st.mask);
   const bf16_t* st_z = reinterpret_cast<const bf16_t*>(a.st.z);
-  if (a.st.mode == 2) {
+  if (MODE == 2) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int c = cb * 16 + lg * 4 + j;
@@ -204,10 +206,10 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) v[j] = Store<bf16_t>::round(v[j]);
       Store<bf16_t>::store4(a.out + idx, v[0], v[1], v[2], v[3]);
-      if (a.st.mode == 1) {
+      if (MODE == 1) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) { ssum[j] += v[j]; ssq[j] += v[j] * v[j]; }
-      } else if (a.st.mode == 2) {
+      } else if (MODE == 2) {
         float mk[4], zz[4];
         Store<bf16_t>::load4(st_mask + idx, mk);
         if (st_z == st_mask) {
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
     }
   }
 
-  if (a.st.mode != 0) {
+  if (MODE != 0) {
     // channel cb*16 + lg*4 + j: sum over the 16 pixel lanes, then over the PG waves of this cb
     __shared__ float red[4][2][16];
 #pragma unroll
@@ -264,7 +266,9 @@ int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, i
 template <int C, int W>
 static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStream_t s) {
   using Cfg = ConvTiledCfg<C, W>;
-  DDG_LAUNCH((conv3x3_tiled_kernel<C, W>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+  if (a.st.mode == 1) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 1>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+  else if (a.st.mode == 2) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 2>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+  else DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 0>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
   return hipGetLastError();
 }
 
