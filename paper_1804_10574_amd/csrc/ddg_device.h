@@ -14,12 +14,16 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// round-to-nearest-even; NaN stays NaN
+// fp32 -> bf16, round-to-nearest-even, NaN stays NaN: gfx950 converts a pair in one
+// instruction (v_cvt_pk_bf16_f32), which the compiler selects for these vector conversions.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+  return __builtin_bit_cast(uint16_t, (__bf16)f);
 }
 
 template <typename T> struct Store;
@@ -32,6 +36,9 @@ template <> struct Store<float> {
   __device__ static __forceinline__ float round(float v) { return v; }
   __device__ static __forceinline__ void load_vec(const float* p, float (&o)[4]) {
     float4 v = *reinterpret_cast<const float4*>(p);
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  }
+  __device__ static __forceinline__ void unpack_vec(const float4& v, float (&o)[4]) {
     o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
   }
   __device__ static __forceinline__ void store_vec(float* p, const float (&o)[4]) {
@@ -49,6 +56,12 @@ template <> struct Store<bf16_t> {
   __device__ static __forceinline__ float load1(const bf16_t* p) { return bf16_to_f32(p->v); }
   __device__ static __forceinline__ void store1(bf16_t* p, float v) { p->v = f32_to_bf16(v); }
   __device__ static __forceinline__ float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
+  __device__ static __forceinline__ void unpack_vec(const uint4& v, float (&o)[8]) {
+    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+    o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
+    o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
   __device__ static __forceinline__ void load_vec(const bf16_t* p, float (&o)[8]) {
     uint4 v = *reinterpret_cast<const uint4*>(p);
     o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
@@ -56,9 +69,7 @@ template <> struct Store<bf16_t> {
     o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
     o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
   }
-  __device__ static __forceinline__ uint32_t pack2(float lo, float hi) {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-  }
+  __device__ static __forceinline__ uint32_t pack2(float lo, float hi) { return f32x2_to_bf16x2(lo, hi); }
   __device__ static __forceinline__ void store_vec(bf16_t* p, const float (&o)[8]) {
     uint4 v;
     v.x = pack2(o[0], o[1]); v.y = pack2(o[2], o[3]); v.z = pack2(o[4], o[5]); v.w = pack2(o[6], o[7]);

@@ -94,7 +94,8 @@ hipError_t wgrad_reduce_launch(const WgradArgs& a, hipStream_t s);
 struct PackDesc { const float* W; void* wpack; int Cout, Cin, R, mode, log2cp, ksteps, OCB; unsigned total; };
 struct WredDesc { const float* partial; float* dW; int rows, Cout, Cin, R, log2cp, Jp; };
 hipError_t pack_all_launch(const PackDesc* dev_descs, int n, int dtype, hipStream_t s);
-hipError_t wgrad_reduce_all_launch(const WredDesc* dev_descs, int n, hipStream_t s);
+// max_outputs: the largest Cout*Jp among the n layers (sizes the grid)
+hipError_t wgrad_reduce_all_launch(const WredDesc* dev_descs, int n, int max_outputs, hipStream_t s);
 
 // LDS-tiled bf16 weight gradient for 3x3/stride-1 layers with 16/32/64 channels. Returns 0 rows
 // when the shape is not covered. x may be the saved conv output the activation derives from:

@@ -66,7 +66,8 @@ struct Unit {  // convolution + batch normalisation
   float* fstat = nullptr;       // partial rows of the forward statistics [frows][2][cout]
   float* bstat = nullptr;       // partial rows of the BN-backward sums [brows][2][cout]
   int frows = 0;                // rows written by the last forward conv
-  bool small_c() const { return cout <= 64; }   // consumers finalise the rows themselves
+  // consumers finalise the partial rows themselves (their reduction is built for these widths)
+  bool small_c() const { return cout == 16 || cout == 32 || cout == 64; }
   int tiled_instance() const { return cin == 16 ? 1 : cin == 32 ? 2 : 3; }   // offset of a tiled kernel's profile kind
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
   size_t in_elems() const { return (size_t)N * H * W * cin; }
@@ -109,7 +110,7 @@ struct ddg_module {
   void *Ga = nullptr, *Gb = nullptr, *D1 = nullptr, *D2 = nullptr, *D3 = nullptr;
   float* ws_stat = nullptr; size_t ws_stat_elems = 0;
   PackDesc* pack_descs = nullptr; int n_pack = 0;     // device tables for the whole-module kernels
-  WredDesc* wred_descs = nullptr; int n_wred = 0;
+  WredDesc* wred_descs = nullptr; int n_wred = 0; int wred_max = 0;   // wred_max: largest Cout*Jp
   std::vector<void*> allocs;
   size_t bytes = 0;
   // state
@@ -393,6 +394,7 @@ ddg_status build_plan(ddg_module* m) {
       w.partial = u.wg_partial; w.dW = m->grad + u.ow; w.rows = u.wg.msplit; w.Cout = u.cout; w.Cin = u.cin;
       w.R = u.R; w.log2cp = u.wg.log2cp; w.Jp = u.wg.JB * 16;
       wd.push_back(w);
+      if (w.Cout * w.Jp > m->wred_max) m->wred_max = w.Cout * w.Jp;
     }
   m->n_pack = (int)pd.size(); m->n_wred = (int)wd.size();
   if (!d.dry_run && m->n_pack) {
@@ -893,7 +895,7 @@ ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, con
   DDG_OKAY(run_backward(m, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out));
   // every layer's weight-gradient partials -> g (one launch for the module, fixed order)
   Launch L(m, PK_WGRAD_REDUCE, (double)m->nparams * 4.0);
-  DDG_TRY(wgrad_reduce_all_launch(m->wred_descs, m->n_wred, m->stream));
+  DDG_TRY(wgrad_reduce_all_launch(m->wred_descs, m->n_wred, m->wred_max, m->stream));
   return DDG_OK;
 }
 

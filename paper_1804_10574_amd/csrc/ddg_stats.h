@@ -12,37 +12,49 @@ namespace ddg {
 
 constexpr int STATS_CMAX = 64;
 
-// 256 threads. f(c, t1, t2) runs once per channel (in one thread) with the two column sums.
-// A row is 2*C floats; a thread owns one 16-byte column group and every nsl-th row, keeps 16
-// loads in flight, and adds its rows in order; the row slices are then combined in order.
-template <typename F>
-__device__ __forceinline__ void reduce_stat_rows(const float* __restrict__ partial, int rows, int C, F f) {
+// 256 threads, C a compile-time constant in {16, 32, 64}. f(c, t1, t2) runs once per channel (in
+// one thread) with the two column sums. A row is 2*C floats; a thread owns one 16-byte column
+// group and every NSL-th row, keeps 16 loads in flight and adds its rows in order (fp32, like
+// the rows themselves). The NSL row slices of a column are then combined in a fixed order in
+// fp64 in two short steps (four values per thread, then 256/(2C) per column), all unrolled.
+template <int C, typename F>
+__device__ __forceinline__ void reduce_stat_rows(const float* __restrict__ partial, int rows, F f) {
+  static_assert(C == 16 || C == 32 || C == 64, "channel count");
+  constexpr int NCOL4 = C / 2;            // float4 groups per row (2*C/4)
+  constexpr int NSL = 256 / NCOL4;        // row slices: 32, 16, 8
+  constexpr int G = 256 / (2 * C);        // second-step groups per column: 8, 4, 2 (NSL == 4*G)
   __shared__ float4 sh[256];
+  __shared__ double sh2[256];
   const int tid = threadIdx.x;
-  const int ncol4 = C / 2;               // float4 groups per row (2*C/4)
-  const int nsl = 256 / ncol4;           // row slices
-  const int c4 = tid % ncol4, slice = tid / ncol4;
+  const int c4 = tid % NCOL4, slice = tid / NCOL4;
   const float4* __restrict__ p4 = reinterpret_cast<const float4*>(partial);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int r0 = slice; r0 < rows; r0 += nsl * 16) {
+  for (int r0 = slice; r0 < rows; r0 += NSL * 16) {
     float4 v[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      const int rr = r0 + u * nsl;
-      v[u] = rr < rows ? p4[(size_t)rr * ncol4 + c4] : make_float4(0.f, 0.f, 0.f, 0.f);
+      const int rr = r0 + u * NSL;
+      v[u] = rr < rows ? p4[(size_t)rr * NCOL4 + c4] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
     for (int u = 0; u < 16; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
   }
   sh[tid] = acc;
   __syncthreads();
-  if (tid < C) {
+  {
+    // thread (column col of 2C, group g): slices g*4 .. g*4+3
     const float* shf = reinterpret_cast<const float*>(sh);
+    const int col = tid % (2 * C), g = tid / (2 * C);
+    double t = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) t += (double)shf[((g * 4 + k) * NCOL4) * 4 + col];
+    sh2[g * (2 * C) + col] = t;
+  }
+  __syncthreads();
+  if (tid < C) {
     double t1 = 0.0, t2 = 0.0;
-    for (int k = 0; k < nsl; ++k) {
-      t1 += (double)shf[(k * ncol4) * 4 + tid];        // columns 0..C-1: first sum
-      t2 += (double)shf[(k * ncol4) * 4 + C + tid];    // columns C..2C-1: second sum
-    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) { t1 += sh2[g * (2 * C) + tid]; t2 += sh2[g * (2 * C) + C + tid]; }
     f(tid, t1, t2);
   }
   __syncthreads();
@@ -50,8 +62,9 @@ __device__ __forceinline__ void reduce_stat_rows(const float* __restrict__ parti
 
 // Forward statistics -> scale = gamma*invstd, shift = beta - mean*scale in LDS (s_scale, s_shift);
 // workgroup 0 (write != 0) also stores mean, invstd, scale, shift.
-__device__ __forceinline__ void bn_fwd_from_rows(const BnRows& p, int C, float* s_scale, float* s_shift, bool write) {
-  reduce_stat_rows(p.partial, p.rows, C, [&](int c, double t1, double t2) {
+template <int C>
+__device__ __forceinline__ void bn_fwd_from_rows(const BnRows& p, float* s_scale, float* s_shift, bool write) {
+  reduce_stat_rows<C>(p.partial, p.rows, [&](int c, double t1, double t2) {
     const double mu = t1 / (double)p.count;
     double var = t2 / (double)p.count - mu * mu;
     if (var < 0.0) var = 0.0;
@@ -65,13 +78,26 @@ __device__ __forceinline__ void bn_fwd_from_rows(const BnRows& p, int C, float* 
 
 // Backward sums (sum g, sum g*xhat) -> coefficients of dz = A*g + B*z + C0 in LDS (s_coef[3][C]);
 // workgroup 0 also stores dgamma, dbeta.
-__device__ __forceinline__ void bn_bwd_from_rows(const BnBwdRows& p, int C, float* s_coef, bool write) {
-  reduce_stat_rows(p.partial, p.rows, C, [&](int c, double db, double dg) {
+template <int C>
+__device__ __forceinline__ void bn_bwd_from_rows(const BnBwdRows& p, float* s_coef, bool write) {
+  reduce_stat_rows<C>(p.partial, p.rows, [&](int c, double db, double dg) {
     const double g = p.gamma[c], is = p.invstd[c], mu = p.mean[c], m = p.count;
     const double A = g * is, B = -g * is * is * dg / m, C0 = -g * is * db / m - B * mu;
     s_coef[c] = (float)A; s_coef[C + c] = (float)B; s_coef[2 * C + c] = (float)C0;
     if (write) { p.dgamma[c] = (float)dg; p.dbeta[c] = (float)db; }
   });
+}
+
+// Run-time channel count (16, 32 or 64; the host checks): one of the three instances.
+__device__ __forceinline__ void bn_fwd_from_rows_rt(const BnRows& p, int C, float* s_scale, float* s_shift, bool write) {
+  if (C == 16) bn_fwd_from_rows<16>(p, s_scale, s_shift, write);
+  else if (C == 32) bn_fwd_from_rows<32>(p, s_scale, s_shift, write);
+  else bn_fwd_from_rows<64>(p, s_scale, s_shift, write);
+}
+__device__ __forceinline__ void bn_bwd_from_rows_rt(const BnBwdRows& p, int C, float* s_coef, bool write) {
+  if (C == 16) bn_bwd_from_rows<16>(p, s_coef, write);
+  else if (C == 32) bn_bwd_from_rows<32>(p, s_coef, write);
+  else bn_bwd_from_rows<64>(p, s_coef, write);
 }
 
 }  // namespace ddg

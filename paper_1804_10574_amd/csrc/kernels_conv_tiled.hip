@@ -49,53 +49,121 @@ struct ConvTiledCfg {
 
 // MODE is the epilogue's statistics mode, fixed at compile time: 0 none, 1 sum / sum of squares
 // of the stored output (forward), 2 the BN-backward sums of the layer below (input gradient).
+//
+// Instruction count matters as much as bytes here (a wave64 VALU instruction occupies its SIMD
+// for four cycles, and these kernels run a few microseconds): the staging map of a thread is
+// computed once, LDS fragment addresses are one per-lane register per k-step plus an
+// instruction immediate per pixel block, fragment reads are unconditional 16-byte reads, the
+// tensors the epilogue needs are requested before the MFMA phase, and fp32 -> bf16 uses the
+// packed hardware conversion.
 template <int C, int W, int MODE>
 __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   using Cfg = ConvTiledCfg<C, W>;
   constexpr int TH = Cfg::TH, WC = Cfg::WC, PIX = Cfg::PIX, CH = Cfg::CH, NCHUNK = Cfg::NCHUNK;
   constexpr int PT = Cfg::PER_THREAD, KSTEPS = Cfg::KSTEPS, PG = Cfg::PG, COB = Cfg::COB;
+  constexpr bool RAGGED_K = (9 * C) % 32 != 0;   // the last k-step runs past tap 8 for some lanes
   extern __shared__ __align__(16) unsigned char tile[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
   const int pgrp = wave % PG, cb = wave / PG;
+  const int tiles_per_img = a.H / TH;
 
-  // this wave's weights: KSTEPS fragments of its output-channel block
+  // ---- staging map (the same for every tile): chunk v = tid + i*256 -> halo pixel, 8 channels
+  const int my_ch = tid % CH;
+  int goff[PT];      // element offset of the chunk relative to the tile's first pixel (row r0, column 0)
+  int srow[PT];      // halo row 0..9 of the chunk; -1: no chunk, or a pad column (stays zero)
+  int loff[PT];      // LDS byte offset
+#pragma unroll
+  for (int i = 0; i < PT; ++i) {
+    const int v = tid + i * 256;
+    const int px = v / CH;
+    const int rr = px / WC, cc = px - rr * WC;
+    const bool col_ok = v < NCHUNK && cc >= 1 && cc <= W;
+    srow[i] = col_ok ? rr : -1;
+    goff[i] = ((rr - 1) * W + (cc - 1)) * C + my_ch * 8;
+    loff[i] = v < NCHUNK ? px * PIX + my_ch * 16 : -1;
+  }
+  uint4 stage[PT];
+  unsigned inimg = 0;   // bit i: chunk i of the tile in flight lies inside the image
+  auto issue_loads = [&](int t) {
+    const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
+    const bf16_t* base = a.in + ((size_t)(n * a.H + r0) * W) * C;
+    inimg = 0;
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      stage[i] = make_uint4(0, 0, 0, 0);
+      const int ih = r0 - 1 + srow[i];
+      if (srow[i] >= 0 && ih >= 0 && ih < a.H) {
+        inimg |= 1u << i;
+        stage[i] = *reinterpret_cast<const uint4*>(base + goff[i]);
+      }
+    }
+  };
+  int t = blockIdx.x;
+  if (t < a.tiles) issue_loads(t);
+
+  // ---- this wave's weights: KSTEPS fragments of its output-channel block
   uint4 wf[KSTEPS];
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks)
     wf[ks] = *reinterpret_cast<const uint4*>(a.wpack + ((size_t)(ks * COB + cb) * 64 + lane) * 8);
 
-  // staging: chunk v -> (pixel of the halo tile, 8-channel chunk); a thread's channel chunk is
-  // the same for all its chunks because 256 % CH == 0
-  const int my_ch = tid % CH;
-  const bool xform = a.scale != nullptr || a.in_rows.partial != nullptr;
-  float tsc[8], tsh[8];
-
-  // per-lane LDS byte offsets of the 4 pixel-blocks (tap 0,0; channel 0)
-  int pbase[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int pt = (pgrp * 4 + i) * 16 + l16;     // pixel inside the 8 x W tile
-    pbase[i] = ((pt / W) * WC + (pt % W)) * PIX;
-  }
-  // per-k-step tap offset of this lane's 8-channel chunk
-  int koff[KSTEPS];
-  bool kval[KSTEPS];
+  // ---- LDS fragment addresses: lane part + k-step part in a register, pixel block as immediate
+  // pixel of block i, lane l16: pt = (pgrp*4 + i)*16 + l16; its row/column split is additive in i
+  const int ptl = pgrp * 64 + l16;
+  const int lane_base = ((ptl / W) * WC + (ptl % W)) * PIX;
+  int kaddr[KSTEPS];
+  bool klast_ok = true;
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks) {
     const int kidx = (ks * 4 + lg) * 8;
     const int tap = kidx / C, c0 = kidx % C;
-    kval[ks] = tap < 9;
-    const int t = kval[ks] ? tap : 0;
-    koff[ks] = ((t / 3) * WC + (t % 3)) * PIX + c0 * 2;
+    const bool ok = tap < 9;
+    if (ks == KSTEPS - 1) klast_ok = ok;
+    const int tp = ok ? tap : 0;
+    kaddr[ks] = lane_base + ((tp / 3) * WC + (tp % 3)) * PIX + c0 * 2;
   }
+
+  // ---- per-channel transform of the input (while the first tile's loads are in flight)
+  const bool xform = a.scale != nullptr || a.in_rows.partial != nullptr;
+  float tsc[8], tsh[8];
+  if (a.in_rows.partial) {
+    __shared__ float s_sc[C], s_sh[C];
+    bn_fwd_from_rows<C>(a.in_rows, s_sc, s_sh, blockIdx.x == 0);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { tsc[j] = s_sc[my_ch * 8 + j]; tsh[j] = s_sh[my_ch * 8 + j]; }
+  } else if (a.scale) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { tsc[j] = a.scale[my_ch * 8 + j]; tsh[j] = a.shift[my_ch * 8 + j]; }
+  }
+  auto write_stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      if (loff[i] >= 0) {
+        uint4 q = stage[i];
+        if (xform && ((inimg >> i) & 1u)) {
+          float f[8];
+          Store<bf16_t>::unpack_vec(q, f);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float v = f[j] * tsc[j] + tsh[j];
+            f[j] = v > 0.f ? v : 0.f;
+          }
+          q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
+          q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
+        }
+        *reinterpret_cast<uint4*>(tile + loff[i]) = q;
+      }
+    }
+  };
 
   float ssum[4] = {0.f, 0.f, 0.f, 0.f}, ssq[4] = {0.f, 0.f, 0.f, 0.f};
   // mode 2: per-channel constants of the BN below, for this lane's 4 channels
   float bmu[4], bis[4], bms[4], bmh[4];
   const bf16_t* st_mask = reinterpret_cast<const bf16_t*>(a.st.mask);
   const bf16_t* st_z = reinterpret_cast<const bf16_t*>(a.st.z);
+  const bool two_tensors = MODE == 2 && st_z != st_mask;
   if (MODE == 2) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -104,66 +172,9 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
       bms[j] = a.st.mscale ? a.st.mscale[c] : 1.f; bmh[j] = a.st.mscale ? a.st.mshift[c] : 0.f;
     }
   }
-  const int tiles_per_img = a.H / TH;
+  // output element offset of (block 0, this lane) inside a tile; block i adds i*16*C
+  const int out_lane = ptl * C + cb * 16 + lg * 4;
 
-  uint4 stage[PT];
-  bool inimg[PT];
-  auto issue_loads = [&](int t) {
-    const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
-#pragma unroll
-    for (int i = 0; i < PT; ++i) {
-      const int v = tid + i * 256;
-      stage[i] = make_uint4(0, 0, 0, 0);
-      inimg[i] = false;
-      if (v < NCHUNK) {
-        const int px = v / CH;
-        const int rr = px / WC, cc = px % WC;
-        const int ih = r0 - 1 + rr, iw = cc - 1;
-        if (ih >= 0 && ih < a.H && iw >= 0 && iw < W) {
-          inimg[i] = true;
-          stage[i] = *reinterpret_cast<const uint4*>(a.in + ((size_t)(n * a.H + ih) * W + iw) * C + my_ch * 8);
-        }
-      }
-    }
-  };
-  auto write_stage = [&]() {
-#pragma unroll
-    for (int i = 0; i < PT; ++i) {
-      const int v = tid + i * 256;
-      if (v < NCHUNK) {
-        uint4 q = stage[i];
-        if (xform && inimg[i]) {
-          float f[8];
-          f[0] = __uint_as_float(q.x << 16); f[1] = __uint_as_float(q.x & 0xffff0000u);
-          f[2] = __uint_as_float(q.y << 16); f[3] = __uint_as_float(q.y & 0xffff0000u);
-          f[4] = __uint_as_float(q.z << 16); f[5] = __uint_as_float(q.z & 0xffff0000u);
-          f[6] = __uint_as_float(q.w << 16); f[7] = __uint_as_float(q.w & 0xffff0000u);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float t = f[j] * tsc[j] + tsh[j];
-            f[j] = t > 0.f ? t : 0.f;
-          }
-          q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
-          q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
-        }
-        const int px = v / CH;
-        *reinterpret_cast<uint4*>(tile + px * PIX + my_ch * 16) = q;
-      }
-    }
-  };
-
-  int t = blockIdx.x;
-  if (t < a.tiles) issue_loads(t);
-  // per-channel transform of the input; while the first tile's loads are in flight
-  if (a.in_rows.partial) {
-    __shared__ float s_sc[C], s_sh[C];
-    bn_fwd_from_rows(a.in_rows, C, s_sc, s_sh, blockIdx.x == 0);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { tsc[j] = s_sc[my_ch * 8 + j]; tsh[j] = s_sh[my_ch * 8 + j]; }
-  } else if (a.scale) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { tsc[j] = a.scale[my_ch * 8 + j]; tsh[j] = a.shift[my_ch * 8 + j]; }
-  }
   for (; t < a.tiles; t += gridDim.x) {
     __syncthreads();            // the previous tile has been consumed
     write_stage();
@@ -171,58 +182,77 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
     const int tn = t + gridDim.x;
     if (tn < a.tiles) issue_loads(tn);   // in flight during the MFMA phase
 
+    // what the epilogue reads, requested now
+    const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
+    const size_t obase = ((size_t)(n * a.H + r0) * W) * C + out_lane;
+    uint2 eg[4], em[4], ek[4], ez[4];
+    if (a.add_g) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        eg[i] = *reinterpret_cast<const uint2*>(a.add_g + obase + i * 16 * C);
+        if (a.add_mask) em[i] = *reinterpret_cast<const uint2*>(a.add_mask + obase + i * 16 * C);
+      }
+    }
+    if (MODE == 2) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ek[i] = *reinterpret_cast<const uint2*>(st_mask + obase + i * 16 * C);
+        if (two_tensors) ez[i] = *reinterpret_cast<const uint2*>(st_z + obase + i * 16 * C);
+      }
+    }
+
     f32x4_t acc[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
+      const unsigned char* kp = tile + kaddr[ks];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        uint4 af = make_uint4(0, 0, 0, 0);
-        if (kval[ks]) af = *reinterpret_cast<const uint4*>(tile + pbase[i] + koff[ks]);
+        constexpr int PT0 = 0;  // (silences unused warnings on some shapes)
+        (void)PT0;
+        const int blk = (((i * 16) / W) * WC + (i * 16) % W) * PIX;   // constant after unrolling
+        uint4 af = *reinterpret_cast<const uint4*>(kp + blk);
+        if (RAGGED_K && ks == KSTEPS - 1 && !klast_ok) af = make_uint4(0, 0, 0, 0);
         acc[i] = Mma<bf16_t>::mma(wf[ks], af, acc[i]);
       }
     }
 
     // epilogue: lane = pixel l16 of block i, channels cb*16 + lg*4 .. +3
-    const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
+    auto lo = [](uint32_t u) { return __uint_as_float(u << 16); };
+    auto hi = [](uint32_t u) { return __uint_as_float(u & 0xffff0000u); };
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int pt = (pgrp * 4 + i) * 16 + l16;
-      const size_t idx = ((size_t)(n * a.H + r0) * W + pt) * C + cb * 16 + lg * 4;
       float v[4] = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
       if (a.add_g) {
-        float g[4];
-        Store<bf16_t>::load4(a.add_g + idx, g);
+        float g[4] = {lo(eg[i].x), hi(eg[i].x), lo(eg[i].y), hi(eg[i].y)};
         if (a.add_mask) {
-          float mk[4];
-          Store<bf16_t>::load4(a.add_mask + idx, mk);
+          const float mk[4] = {lo(em[i].x), hi(em[i].x), lo(em[i].y), hi(em[i].y)};
 #pragma unroll
           for (int j = 0; j < 4; ++j) g[j] = (mk[j] > 0.f) ? g[j] : 0.f;
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] += g[j];
       }
+      uint2 o;
+      o.x = Store<bf16_t>::pack2(v[0], v[1]); o.y = Store<bf16_t>::pack2(v[2], v[3]);
+      *reinterpret_cast<uint2*>(a.out + obase + i * 16 * C) = o;
+      if (MODE != 0) {
+        const float r[4] = {lo(o.x), hi(o.x), lo(o.y), hi(o.y)};   // the values as stored
+        if (MODE == 1) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = Store<bf16_t>::round(v[j]);
-      Store<bf16_t>::store4(a.out + idx, v[0], v[1], v[2], v[3]);
-      if (MODE == 1) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { ssum[j] += v[j]; ssq[j] += v[j] * v[j]; }
-      } else if (MODE == 2) {
-        float mk[4], zz[4];
-        Store<bf16_t>::load4(st_mask + idx, mk);
-        if (st_z == st_mask) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) zz[j] = mk[j];
+          for (int j = 0; j < 4; ++j) { ssum[j] += r[j]; ssq[j] += r[j] * r[j]; }
         } else {
-          Store<bf16_t>::load4(st_z + idx, zz);
-        }
+          const float mk[4] = {lo(ek[i].x), hi(ek[i].x), lo(ek[i].y), hi(ek[i].y)};
+          float zz[4];
+          if (two_tensors) { zz[0] = lo(ez[i].x); zz[1] = hi(ez[i].x); zz[2] = lo(ez[i].y); zz[3] = hi(ez[i].y); }
+          else { zz[0] = mk[0]; zz[1] = mk[1]; zz[2] = mk[2]; zz[3] = mk[3]; }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float g = (mk[j] * bms[j] + bmh[j]) > 0.f ? v[j] : 0.f;
-          ssum[j] += g;
-          ssq[j] += g * ((zz[j] - bmu[j]) * bis[j]);
+          for (int j = 0; j < 4; ++j) {
+            const float g = (mk[j] * bms[j] + bmh[j]) > 0.f ? r[j] : 0.f;
+            ssum[j] += g;
+            ssq[j] += g * ((zz[j] - bmu[j]) * bis[j]);
+          }
         }
       }
     }

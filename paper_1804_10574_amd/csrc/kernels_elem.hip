@@ -71,8 +71,8 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ z, 
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int c0 = (int)((i * V) % C);
   __shared__ float s_sc[STATS_CMAX], s_sh[STATS_CMAX], s_rs[STATS_CMAX], s_rh[STATS_CMAX];
-  if (zrows.partial) { bn_fwd_from_rows(zrows, C, s_sc, s_sh, blockIdx.x == 0); scale = s_sc; shift = s_sh; }
-  if (rrows.partial) { bn_fwd_from_rows(rrows, C, s_rs, s_rh, blockIdx.x == 0); rscale = s_rs; rshift = s_rh; }
+  if (zrows.partial) { bn_fwd_from_rows_rt(zrows, C, s_sc, s_sh, blockIdx.x == 0); scale = s_sc; shift = s_sh; }
+  if (rrows.partial) { bn_fwd_from_rows_rt(rrows, C, s_rs, s_rh, blockIdx.x == 0); rscale = s_rs; rshift = s_rh; }
   float sc[V], sh[V], rs[V], rh[V];
 #pragma unroll
   for (int j = 0; j < V; ++j) {
@@ -111,21 +111,99 @@ static int elem_grid(size_t nvec, int C, int V, int max_blocks) {
   return (int)blocks;
 }
 
+// Same operation for the common case 256*V % C == 0 (a thread's channels are the same for all
+// its vectors). A workgroup owns 256*U consecutive vectors; every thread issues all its loads
+// first, the per-channel vectors are derived from the partial rows while those are in flight,
+// and nothing loops: with U = 4 a thread keeps 128 bytes in flight, which is what it takes to
+// approach the memory system's bandwidth with two workgroups per compute unit.
+template <typename T, int U>
+__global__ __launch_bounds__(256) void bn_apply_chunk_kernel(const T* __restrict__ z, const float* __restrict__ scale,
+                                                             const float* __restrict__ shift, BnRows zrows,
+                                                             const T* __restrict__ res,
+                                                             const float* __restrict__ rscale,
+                                                             const float* __restrict__ rshift, BnRows rrows,
+                                                             T* __restrict__ y, size_t nvec, int C, int relu) {
+  constexpr int V = Store<T>::VEC;
+  typedef typename Store<T>::vec_t vec_t;
+  const size_t base = (size_t)blockIdx.x * (256 * U) + threadIdx.x;
+  const int c0 = (int)((threadIdx.x * V) % C);
+  vec_t zq[U], rq[U];
+#pragma unroll
+  for (int j = 0; j < U; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i < nvec) {
+      zq[j] = *reinterpret_cast<const vec_t*>(z + i * V);
+      if (res) rq[j] = *reinterpret_cast<const vec_t*>(res + i * V);
+    }
+  }
+  __shared__ float s_sc[STATS_CMAX], s_sh[STATS_CMAX], s_rs[STATS_CMAX], s_rh[STATS_CMAX];
+  if (zrows.partial) { bn_fwd_from_rows_rt(zrows, C, s_sc, s_sh, blockIdx.x == 0); scale = s_sc; shift = s_sh; }
+  if (rrows.partial) { bn_fwd_from_rows_rt(rrows, C, s_rs, s_rh, blockIdx.x == 0); rscale = s_rs; rshift = s_rh; }
+  float sc[V], sh[V], rs[V], rh[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    sc[j] = scale[c0 + j]; sh[j] = shift[c0 + j];
+    rs[j] = rscale ? rscale[c0 + j] : 1.f;
+    rh[j] = rshift ? rshift[c0 + j] : 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < U; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i >= nvec) continue;
+    float v[V];
+    Store<T>::unpack_vec(zq[j], v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) v[e] = v[e] * sc[e] + sh[e];
+    if (res) {
+      float r[V];
+      Store<T>::unpack_vec(rq[j], r);
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[e] += r[e] * rs[e] + rh[e];
+    }
+    if (relu) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+    }
+    Store<T>::store_vec(y + i * V, v);
+  }
+}
+
+template <typename T>
+static void bn_apply_dispatch(const T* z, const float* scale, const float* shift, const BnRows& zr, const T* res,
+                              const float* rscale, const float* rshift, const BnRows& rr, T* y, size_t nvec, int C,
+                              int relu, bool rows, hipStream_t s) {
+  constexpr int V = Store<T>::VEC;
+  if ((256 * V) % C != 0) {
+    // a thread's channels change from vector to vector: grid-stride kernel
+    const int maxb = rows ? 512 : 2048;
+    DDG_LAUNCH(bn_apply_kernel<T>, dim3(elem_grid(nvec, C, V, maxb)), dim3(256), 0, s, z, scale, shift, zr, res, rscale,
+               rshift, rr, y, nvec, C, relu);
+    return;
+  }
+  // 4 vectors per thread once that still leaves two workgroups per compute unit
+  if (nvec >= (size_t)512 * 1024) {
+    DDG_LAUNCH((bn_apply_chunk_kernel<T, 4>), dim3((unsigned)((nvec + 1023) / 1024)), dim3(256), 0, s, z, scale, shift, zr,
+               res, rscale, rshift, rr, y, nvec, C, relu);
+  } else if (nvec >= (size_t)512 * 512) {
+    DDG_LAUNCH((bn_apply_chunk_kernel<T, 2>), dim3((unsigned)((nvec + 511) / 512)), dim3(256), 0, s, z, scale, shift, zr,
+               res, rscale, rshift, rr, y, nvec, C, relu);
+  } else {
+    DDG_LAUNCH((bn_apply_chunk_kernel<T, 1>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s, z, scale, shift, zr,
+               res, rscale, rshift, rr, y, nvec, C, relu);
+  }
+}
+
 hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const BnRows* zrows,
                            const void* res, const float* rscale, const float* rshift, const BnRows* rrows,
                            void* y, size_t elems, int C, int relu, int dtype, hipStream_t s) {
   const BnRows zr = zrows ? *zrows : BnRows{}, rr = rrows ? *rrows : BnRows{};
-  // every workgroup re-derives the per-channel vectors from the rows: keep the grid moderate
-  const int maxb = (zrows || rrows) ? 512 : 2048;
-  if (dtype == BF16) {
-    const size_t nvec = elems / 8;
-    DDG_LAUNCH(bn_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, maxb)), dim3(256), 0, s,
-                       (const bf16_t*)z, scale, shift, zr, (const bf16_t*)res, rscale, rshift, rr, (bf16_t*)y, nvec, C, relu);
-  } else {
-    const size_t nvec = elems / 4;
-    DDG_LAUNCH(bn_apply_kernel<float>, dim3(elem_grid(nvec, C, 4, maxb)), dim3(256), 0, s,
-                       (const float*)z, scale, shift, zr, (const float*)res, rscale, rshift, rr, (float*)y, nvec, C, relu);
-  }
+  const bool rows = zrows || rrows;
+  if (dtype == BF16)
+    bn_apply_dispatch<bf16_t>((const bf16_t*)z, scale, shift, zr, (const bf16_t*)res, rscale, rshift, rr, (bf16_t*)y,
+                              elems / 8, C, relu, rows, s);
+  else
+    bn_apply_dispatch<float>((const float*)z, scale, shift, zr, (const float*)res, rscale, rshift, rr, (float*)y,
+                             elems / 4, C, relu, rows, s);
   return hipGetLastError();
 }
 
@@ -273,7 +351,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int c0 = (int)((i * V) % C);
   __shared__ float s_coef[3 * STATS_CMAX];
-  if (rows.partial) { bn_bwd_from_rows(rows, C, s_coef, blockIdx.x == 0); coef = s_coef; }
+  if (rows.partial) { bn_bwd_from_rows_rt(rows, C, s_coef, blockIdx.x == 0); coef = s_coef; }
   float A[V], B[V], C0[V], ms[V], mh[V];
 #pragma unroll
   for (int j = 0; j < V; ++j) {
@@ -316,91 +394,149 @@ hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const float* ms
 // ---------------------------------------------------------------------------------
 // Head. Small: N x C x classes is a few hundred thousand operations.
 // ---------------------------------------------------------------------------------
+// Per sample (one workgroup of 256 threads): global average pool, logits, stable softmax, loss,
+// dlogits = (p - onehot)/N, and dh = dlogits * fcw / HW broadcast over the pixels. Every sum
+// runs in a fixed order. Dynamic LDS: 2*C + 2*classes + 256 floats.
 template <typename T>
-__global__ void head_pool_kernel(const T* __restrict__ h, float* __restrict__ pooled, int HW, int C) {
-  const int n = blockIdx.x;
-  for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    float s = 0.f;
-    for (int i = 0; i < HW; ++i) s += Store<T>::load1(h + ((size_t)n * HW + i) * C + c);
-    pooled[(size_t)n * C + c] = s / (float)HW;
+__global__ __launch_bounds__(256) void head_sample_kernel(const T* __restrict__ h, const float* __restrict__ fcw,
+                                                          const float* __restrict__ fcb,
+                                                          const int32_t* __restrict__ labels,
+                                                          float* __restrict__ pooled, float* __restrict__ dlogits,
+                                                          float* __restrict__ loss_n, T* __restrict__ dh, int N,
+                                                          int HW, int C, int classes) {
+  extern __shared__ float sm[];
+  float* s_pool = sm;               // [C]
+  float* s_dh = sm + C;             // [C]
+  float* s_lg = sm + 2 * C;         // [classes]
+  float* s_dl = s_lg + classes;     // [classes]
+  float* s_red = s_dl + classes;    // [256]
+  const int n = blockIdx.x, tid = threadIdx.x;
+  // pool: thread (channel lane cl, pixel class g); pixel classes are added in order afterwards
+  const int cpt = C < 256 ? C : 256, groups = 256 / cpt;
+  const int cl = tid % cpt, g = tid / cpt;
+  for (int c0 = 0; c0 < C; c0 += cpt) {
+    const int c = c0 + cl;
+    float a = 0.f;
+    if (g < groups && c < C) {
+      const T* p = h + (size_t)n * HW * C + c;
+#pragma unroll 8
+      for (int i = g; i < HW; i += groups) a += Store<T>::load1(p + (size_t)i * C);
+    }
+    s_red[tid] = a;
+    __syncthreads();
+    if (g == 0 && c < C) {
+      float t = 0.f;
+      for (int q = 0; q < groups; ++q) t += s_red[q * cpt + cl];
+      t /= (float)HW;
+      s_pool[c] = t;
+      pooled[(size_t)n * C + c] = t;
+    }
+    __syncthreads();
   }
-}
-
-// one workgroup per sample: logits, stable softmax, per-sample loss, dlogits = (p - onehot)/N
-__global__ void head_loss_kernel(const float* __restrict__ pooled, const float* __restrict__ fcw,
-                                 const float* __restrict__ fcb, const int32_t* __restrict__ labels,
-                                 float* __restrict__ dlogits, float* __restrict__ loss_n, int N, int C,
-                                 int classes) {
-  extern __shared__ float lg[];  // classes floats
-  const int n = blockIdx.x;
-  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
+  // logits
+  for (int j = tid; j < classes; j += 256) {
     float a = fcb[j];
-    for (int c = 0; c < C; ++c) a += fcw[(size_t)j * C + c] * pooled[(size_t)n * C + c];
-    lg[j] = a;
+    const float* w = fcw + (size_t)j * C;
+#pragma unroll 8
+    for (int c = 0; c < C; ++c) a += w[c] * s_pool[c];
+    s_lg[j] = a;
   }
   __syncthreads();
-  float mx = lg[0];
-  for (int j = 1; j < classes; ++j) mx = lg[j] > mx ? lg[j] : mx;
+  float mx = s_lg[0];
+  for (int j = 1; j < classes; ++j) mx = s_lg[j] > mx ? s_lg[j] : mx;
+  for (int j = tid; j < classes; j += 256) s_dl[j] = expf(s_lg[j] - mx);
+  __syncthreads();
   float den = 0.f;
-  for (int j = 0; j < classes; ++j) den += expf(lg[j] - mx);
+  for (int j = 0; j < classes; ++j) den += s_dl[j];
   const int y = labels[n];
-  for (int j = threadIdx.x; j < classes; j += blockDim.x) {
-    const float p = expf(lg[j] - mx) / den;
-    dlogits[(size_t)n * classes + j] = (p - (j == y ? 1.f : 0.f)) / (float)N;
+  __syncthreads();
+  for (int j = tid; j < classes; j += 256) {
+    const float d = (s_dl[j] / den - (j == y ? 1.f : 0.f)) / (float)N;
+    s_dl[j] = d;
+    dlogits[(size_t)n * classes + j] = d;
   }
-  if (threadIdx.x == 0) loss_n[n] = -(lg[y] - mx - logf(den));
+  if (tid == 0) loss_n[n] = -(s_lg[y] - mx - logf(den));
+  if (!dh) return;
+  __syncthreads();
+  for (int c = tid; c < C; c += 256) {
+    float a = 0.f;
+#pragma unroll 4
+    for (int j = 0; j < classes; ++j) a += s_dl[j] * fcw[(size_t)j * C + c];
+    s_dh[c] = Store<T>::round(a / (float)HW);
+  }
+  __syncthreads();
+  // broadcast over the pixels, 4 channels per store
+  const int c4n = C / 4;
+  for (int e = tid; e < HW * c4n; e += 256) {
+    const int i = e / c4n, c = (e - i * c4n) * 4;
+    Store<T>::store4(dh + ((size_t)n * HW + i) * C + c, s_dh[c], s_dh[c + 1], s_dh[c + 2], s_dh[c + 3]);
+  }
 }
 
-// one workgroup per class: dfcw[j][:], dfcb[j]; workgroup 0 also writes the mean loss
-__global__ void head_wgrad_kernel(const float* __restrict__ pooled, const float* __restrict__ dlogits,
-                                  const float* __restrict__ loss_n, float* __restrict__ dfcw,
-                                  float* __restrict__ dfcb, float* loss_out, int N, int C, int classes) {
-  const int j = blockIdx.x;
-  for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    float s = 0.f;
-    for (int n = 0; n < N; ++n) s += dlogits[(size_t)n * classes + j] * pooled[(size_t)n * C + c];
-    dfcw[(size_t)j * C + c] = s;
+// One workgroup per class j: dfcw[j][:] = sum_n dlogits[n][j] * pooled[n][:], dfcb[j]; thread
+// (channel lane, sample class g) adds samples g, g+groups, ... in order, then the classes are
+// added in order. Workgroup 0 also writes the mean loss.
+__global__ __launch_bounds__(256) void head_wgrad_kernel(const float* __restrict__ pooled,
+                                                         const float* __restrict__ dlogits,
+                                                         const float* __restrict__ loss_n, float* __restrict__ dfcw,
+                                                         float* __restrict__ dfcb, float* loss_out, int N, int C,
+                                                         int classes) {
+  __shared__ float s_red[256];
+  const int j = blockIdx.x, tid = threadIdx.x;
+  const int cpt = C < 256 ? C : 256, groups = 256 / cpt;
+  const int cl = tid % cpt, g = tid / cpt;
+  for (int c0 = 0; c0 < C; c0 += cpt) {
+    const int c = c0 + cl;
+    float a = 0.f;
+    if (g < groups && c < C) {
+#pragma unroll 8
+      for (int n = g; n < N; n += groups) a += dlogits[(size_t)n * classes + j] * pooled[(size_t)n * C + c];
+    }
+    s_red[tid] = a;
+    __syncthreads();
+    if (g == 0 && c < C) {
+      float t = 0.f;
+      for (int q = 0; q < groups; ++q) t += s_red[q * cpt + cl];
+      dfcw[(size_t)j * C + c] = t;
+    }
+    __syncthreads();
   }
-  if (threadIdx.x == 0) {
-    float s = 0.f;
-    for (int n = 0; n < N; ++n) s += dlogits[(size_t)n * classes + j];
-    dfcb[j] = s;
-    if (j == 0 && loss_out) {
-      float l = 0.f;
-      for (int n = 0; n < N; ++n) l += loss_n[n];
-      *loss_out = l / (float)N;
+  // bias gradient (and the mean loss): 256 partial sums over samples, added in order
+  float a = 0.f, l = 0.f;
+  for (int n = tid; n < N; n += 256) {
+    a += dlogits[(size_t)n * classes + j];
+    if (j == 0) l += loss_n[n];
+  }
+  s_red[tid] = a;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+    for (int q = 0; q < 256; ++q) t += s_red[q];
+    dfcb[j] = t;
+  }
+  if (j == 0 && loss_out) {
+    __syncthreads();
+    s_red[tid] = l;
+    __syncthreads();
+    if (tid == 0) {
+      float t = 0.f;
+      for (int q = 0; q < 256; ++q) t += s_red[q];
+      *loss_out = t / (float)N;
     }
   }
 }
 
-template <typename T>
-__global__ void head_dh_kernel(const float* __restrict__ dlogits, const float* __restrict__ fcw,
-                               T* __restrict__ dh, int HW, int C, int classes) {
-  const int n = blockIdx.x;
-  for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    float s = 0.f;
-    for (int j = 0; j < classes; ++j) s += dlogits[(size_t)n * classes + j] * fcw[(size_t)j * C + c];
-    s /= (float)HW;
-    for (int i = 0; i < HW; ++i) Store<T>::store1(dh + ((size_t)n * HW + i) * C + c, s);
-  }
-}
-
 hipError_t head_launch(const HeadArgs& a, hipStream_t s) {
-  const int tc = a.C < 64 ? 64 : (a.C > 256 ? 256 : a.C);
+  if (a.C % 4 != 0) return hipErrorInvalidValue;
+  const size_t lds = (size_t)(2 * a.C + 2 * a.classes + 256) * sizeof(float);
   if (a.dtype == BF16)
-    DDG_LAUNCH(head_pool_kernel<bf16_t>, dim3(a.N), dim3(tc), 0, s, (const bf16_t*)a.h, a.pooled, a.HW, a.C);
+    DDG_LAUNCH(head_sample_kernel<bf16_t>, dim3(a.N), dim3(256), lds, s, (const bf16_t*)a.h, a.fcw, a.fcb, a.labels,
+               a.pooled, a.dlogits, a.loss_n, (bf16_t*)a.dh, a.N, a.HW, a.C, a.classes);
   else
-    DDG_LAUNCH(head_pool_kernel<float>, dim3(a.N), dim3(tc), 0, s, (const float*)a.h, a.pooled, a.HW, a.C);
-  DDG_LAUNCH(head_loss_kernel, dim3(a.N), dim3(128), a.classes * sizeof(float), s, a.pooled, a.fcw,
-                     a.fcb, a.labels, a.dlogits, a.loss_n, a.N, a.C, a.classes);
-  DDG_LAUNCH(head_wgrad_kernel, dim3(a.classes), dim3(tc), 0, s, a.pooled, a.dlogits, a.loss_n, a.dfcw,
-                     a.dfcb, a.loss_out, a.N, a.C, a.classes);
-  if (a.dh) {
-    if (a.dtype == BF16)
-      DDG_LAUNCH(head_dh_kernel<bf16_t>, dim3(a.N), dim3(tc), 0, s, a.dlogits, a.fcw, (bf16_t*)a.dh, a.HW, a.C, a.classes);
-    else
-      DDG_LAUNCH(head_dh_kernel<float>, dim3(a.N), dim3(tc), 0, s, a.dlogits, a.fcw, (float*)a.dh, a.HW, a.C, a.classes);
-  }
+    DDG_LAUNCH(head_sample_kernel<float>, dim3(a.N), dim3(256), lds, s, (const float*)a.h, a.fcw, a.fcb, a.labels,
+               a.pooled, a.dlogits, a.loss_n, (float*)a.dh, a.N, a.HW, a.C, a.classes);
+  DDG_LAUNCH(head_wgrad_kernel, dim3(a.classes), dim3(256), 0, s, a.pooled, a.dlogits, a.loss_n, a.dfcw, a.dfcb,
+             a.loss_out, a.N, a.C, a.classes);
   return hipGetLastError();
 }
 

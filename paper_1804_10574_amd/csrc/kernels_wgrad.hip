@@ -104,37 +104,54 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs a) {
   }
 }
 
-// All layers of a module: blockIdx.y picks the layer, 16 threads share one output.
+// All layers of a module in one launch: blockIdx.y picks the layer, a workgroup covers 64 groups
+// of 4 consecutive outputs. Thread (column group, row class rc) adds the rows rc, rc+4, ... in
+// increasing order with 8 independent 16-byte loads in flight (a wave reads 1 KiB of one row);
+// the four row classes are then added in a fixed order.
 __global__ __launch_bounds__(256) void wgrad_reduce_all_kernel(const WredDesc* __restrict__ descs) {
   const WredDesc d = descs[blockIdx.y];
-  const int total = d.Cout * d.Jp;
-  __shared__ float red[16][17];
-  const int sub = threadIdx.x & 15, loc = threadIdx.x >> 4;
-  for (int base = blockIdx.x * 16; base < total; base += gridDim.x * 16) {
-    const int e = base + loc;
-    float s = 0.f;
-    if (e < total)
-      for (int sp = sub; sp < d.rows; sp += 16) s += d.partial[(size_t)sp * total + e];
-    __syncthreads();
-    red[loc][sub] = s;
-    __syncthreads();
-    if (sub == 0 && e < total) {
-      float t = 0.f;
+  const int total4 = d.Cout * d.Jp / 4;
+  if ((int)blockIdx.x * 64 >= total4) return;
+  const int cl = threadIdx.x & 63, rc = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + cl;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (col < total4) {
+    const float4* __restrict__ p = reinterpret_cast<const float4*>(d.partial) + col;
+    for (int r0 = rc; r0 < d.rows; r0 += 32) {
+      float4 v[8];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) t += red[loc][i];
+      for (int u = 0; u < 8; ++u) {
+        const int r = r0 + 4 * u;
+        v[u] = r < d.rows ? p[(size_t)r * total4] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+  }
+  __shared__ float4 red[4][64];
+  red[rc][cl] = s;
+  __syncthreads();
+  if (rc == 0 && col < total4) {
+    const float4 a0 = red[0][cl], a1 = red[1][cl], a2 = red[2][cl], a3 = red[3][cl];
+    const float t[4] = {((a0.x + a1.x) + a2.x) + a3.x, ((a0.y + a1.y) + a2.y) + a3.y,
+                        ((a0.z + a1.z) + a2.z) + a3.z, ((a0.w + a1.w) + a2.w) + a3.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = col * 4 + i;
       const int co = e / d.Jp, j = e - co * d.Jp;
       const int tap = j >> d.log2cp, ci = j & ((1 << d.log2cp) - 1);
       if (tap < d.R * d.R && ci < d.Cin) {
         const int r = tap / d.R, sx = tap % d.R;
-        d.dW[(((size_t)co * d.Cin + ci) * d.R + r) * d.R + sx] = t;
+        d.dW[(((size_t)co * d.Cin + ci) * d.R + r) * d.R + sx] = t[i];
       }
     }
   }
 }
 
-hipError_t wgrad_reduce_all_launch(const WredDesc* dev_descs, int n, hipStream_t s) {
+hipError_t wgrad_reduce_all_launch(const WredDesc* dev_descs, int n, int max_outputs, hipStream_t s) {
   if (n <= 0) return hipSuccess;
-  DDG_LAUNCH(wgrad_reduce_all_kernel, dim3(48, n), dim3(256), 0, s, dev_descs);
+  const int gx = (max_outputs / 4 + 63) / 64;
+  DDG_LAUNCH(wgrad_reduce_all_kernel, dim3(gx > 0 ? gx : 1, n), dim3(256), 0, s, dev_descs);
   return hipGetLastError();
 }
 

@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void wgrad_tiled_kernel(WgradTiledArgs a) {
     __shared__ float s_coef[3 * COUT];
     const float* coef = a.coef;
     if (a.rows.partial) {
-      bn_bwd_from_rows(a.rows, COUT, s_coef, blockIdx.x == 0 && blockIdx.y == 0);
+      bn_bwd_from_rows<COUT>(a.rows, s_coef, blockIdx.x == 0 && blockIdx.y == 0);
       coef = s_coef;
     }
 #pragma unroll
