@@ -3,13 +3,18 @@
 //
 //   dW[co][tap][ci] = sum over pixels m of dz[m][co] * a[pix(m,tap)][ci]
 //
-// The contraction index is the pixel, which is the slow index of both NHWC operands, while
-// an MFMA lane wants 8 consecutive contraction values. So both operands are transposed once
-// on their way into LDS ([channel][row][column] planes, written with 2-byte stores); after
-// that every fragment is one aligned 16-byte LDS read. The three horizontal taps of a row
-// are made from the aligned 8-column chunk plus its two neighbour columns with register
-// shifts, so each staged element is read from LDS three times (once per vertical tap) and
-// not nine. The activation a can be produced on the fly from the saved conv output:
+// The contraction index is the pixel, which is the slow index of both NHWC operands, while an
+// MFMA lane wants 8 consecutive contraction values of one channel. gfx950 can transpose on the
+// way out of LDS (ds_read_b64_tr_b16: in every block of 16 lanes, lane s supplies the address
+// of 4 consecutive 16-bit values, and lane i receives value i%4 of lanes i/4, i/4+4, i/4+8,
+// i/4+12). So both operands are staged exactly as they lie in memory, [pixel][channel] with
+// 16-byte writes; lane s of a block points at channels 4*(s%4).. of pixel P + s/4, lane i gets
+// channel i of pixels P..P+3, and two such reads make one 8-pixel fragment. A tap is a shifted
+// pixel address into the halo tile: the im2col matrix never exists and nothing is shifted in
+// registers. The pixel stride in LDS is 32 or 96 bytes modulo 128, which spreads the four
+// pixels of a 16-lane block over all banks.
+//
+// The activation a can be produced on the fly from the saved conv output:
 // a = relu(z*scale + shift) is applied while staging (scale == nullptr: use x as stored).
 //
 // The error gradient dz can likewise be formed while staging: with dy given, the kernel applies
@@ -18,8 +23,8 @@
 // writes it out once for the input-gradient kernel that follows: no separate apply pass.
 //
 // A workgroup walks over tiles of 8 image rows, keeps its accumulators in registers across
-// tiles, and writes one partial tile at the end; wgrad_reduce_kernel adds the partials in a
-// fixed order (deterministic).
+// tiles (the next tile's global loads are in flight meanwhile), and writes one partial tile at
+// the end; wgrad_reduce_all_kernel adds the partials in a fixed order (deterministic).
 #include "ddg_device.h"
 #include "ddg_kernels.h"
 #include "ddg_stats.h"
@@ -44,7 +49,7 @@ template <int CIN, int COUT, int W>
 struct WgradTiledCfg {
   static constexpr int TH = 8;
   static constexpr int ROWS = TH + 2;
-  static constexpr int WP = W + 16;                       // 8 pad columns left and right
+  static constexpr int WC = W + 2;                        // one pad column left and right
   static constexpr int CIB_ALL = CIN / 16;
   static constexpr int CIB = (CIN == 64) ? 1 : CIB_ALL;   // ci-blocks per workgroup
   static constexpr int OT = CIB_ALL / CIB;                // grid.y
@@ -52,76 +57,85 @@ struct WgradTiledCfg {
   static constexpr int COB = COUT / 16;
   static constexpr int KSPLIT = 4 / COB;                  // waves sharing one co-block
   static constexpr int KSTEPS = TH * W / 32;
-  static constexpr int round8odd(int v) { return ((v + 7) / 8) % 2 == 1 ? ((v + 7) / 8) * 8 : ((v + 7) / 8 + 1) * 8; }
-  static constexpr int PSX = round8odd(ROWS * WP);        // plane stride of x^T (elements)
-  static constexpr int PSZ = round8odd(TH * W);           // plane stride of dz^T
-  static constexpr int LDS_X = CINW * PSX;
-  static constexpr int LDS_Z = COUT * PSZ;
+  static constexpr int KPW = KSTEPS / KSPLIT;             // k-steps per wave and tile
+  // bytes per staged pixel: at least 2*channels, and 32 or 96 modulo 128
+  static constexpr int lds_pix(int ch) { return ch == 16 ? 32 : (ch == 32 ? 96 : 160); }
+  static constexpr int PIXX = lds_pix(CINW);
+  static constexpr int PIXZ = lds_pix(COUT);
+  static constexpr int LDS_X = ROWS * WC * PIXX;          // bytes
+  static constexpr int LDS_Z = TH * W * PIXZ;
+  static constexpr int RED = (KSPLIT - 1) * COB * 9 * CIB * 4 * 64 * 4;   // bytes, cross-wave sum
+  static constexpr int LDS = (LDS_X + LDS_Z) > RED ? (LDS_X + LDS_Z) : RED;
 };
+
+typedef short tr4_t __attribute__((ext_vector_type(4)));
+// 8-pixel fragment of one channel per lane: two transposing reads 4 pixels apart
+__device__ __forceinline__ uint4 lds_frag_tr(const unsigned char* p, int half_stride) {
+  typedef tr4_t __attribute__((address_space(3))) * lds_ptr_t;
+  const tr4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+  const tr4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + half_stride));
+  const uint2 l = __builtin_bit_cast(uint2, lo), h = __builtin_bit_cast(uint2, hi);
+  return make_uint4(l.x, l.y, h.x, h.y);
+}
 
 template <int CIN, int COUT, int W>
 __global__ __launch_bounds__(256) void wgrad_tiled_kernel(WgradTiledArgs a) {
   using Cfg = WgradTiledCfg<CIN, COUT, W>;
-  constexpr int TH = Cfg::TH, ROWS = Cfg::ROWS, WP = Cfg::WP, CIB = Cfg::CIB, CINW = Cfg::CINW;
-  constexpr int COB = Cfg::COB, KSPLIT = Cfg::KSPLIT, KSTEPS = Cfg::KSTEPS, PSX = Cfg::PSX, PSZ = Cfg::PSZ;
+  constexpr int TH = Cfg::TH, ROWS = Cfg::ROWS, WC = Cfg::WC, CIB = Cfg::CIB, CINW = Cfg::CINW;
+  constexpr int COB = Cfg::COB, KSPLIT = Cfg::KSPLIT, KPW = Cfg::KPW, PIXX = Cfg::PIXX, PIXZ = Cfg::PIXZ;
   extern __shared__ __align__(16) unsigned char smem[];
-  uint16_t* xT = reinterpret_cast<uint16_t*>(smem);
-  uint16_t* zT = xT + Cfg::LDS_X;
+  unsigned char* xt = smem;                 // [ROWS][WC] pixels x CINW channels
+  unsigned char* zt = smem + Cfg::LDS_X;    // [TH*W] pixels x COUT channels
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
   const int cb = wave % COB, kpart = wave / COB;
   const int ci0 = blockIdx.y * CINW;   // first staged input channel
-
-  // pad columns (image columns -1 and W) stay zero for the whole kernel
-  for (int i = tid; i < CINW * ROWS; i += 256) {
-    const int c = i / ROWS, rr = i - c * ROWS;
-    xT[c * PSX + rr * WP + 7] = 0;
-    xT[c * PSX + rr * WP + W + 8] = 0;
-  }
-
-  f32x4_t acc[9][CIB];
-#pragma unroll
-  for (int t = 0; t < 9; ++t)
-#pragma unroll
-    for (int b = 0; b < CIB; ++b) acc[t][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
   const int tiles_per_img = a.H / TH;
+
+  // ---- staging maps (the same for every tile)
   constexpr int XCH = CINW / 8;                 // 16-byte chunks per staged pixel of x
-  constexpr int XVEC = ROWS * W * XCH;
+  constexpr int XVEC = ROWS * WC * XCH;
   constexpr int XPT = (XVEC + 255) / 256;
   constexpr int ZCH = COUT / 8;
   constexpr int ZVEC = TH * W * ZCH;            // 512 for all three shapes
   constexpr int ZPT = ZVEC / 256;
   static_assert(ZVEC % 256 == 0 && 256 % XCH == 0 && 256 % ZCH == 0, "staging layout");
   const int xch = tid % XCH, zch = tid % ZCH;   // this thread's channel chunks (fixed)
+  int xgoff[XPT], xrow[XPT], xloff[XPT];
+#pragma unroll
+  for (int i = 0; i < XPT; ++i) {
+    const int v = tid + i * 256;
+    const int px = v / XCH;
+    const int rr = px / WC, cc = px - rr * WC;
+    const bool col_ok = v < XVEC && cc >= 1 && cc <= W;
+    xrow[i] = col_ok ? rr : -1;                                   // -1: nothing to load (pad column: zero)
+    xgoff[i] = ((rr - 1) * W + (cc - 1)) * CIN + ci0 + xch * 8;   // relative to the tile's first pixel
+    xloff[i] = v < XVEC ? px * PIXX + xch * 16 : -1;
+  }
   const bool fuse = a.dy != nullptr;
   const bool two_masks = fuse && a.mask && a.mask != a.zc;
 
   // registers that hold the next tile while the current one is contracted
   uint4 xs[XPT], ds[ZPT], zs[ZPT], ms[ZPT];
-  bool xin[XPT];
+  unsigned xin = 0;
   auto issue = [&](int tile) {
     const int n = tile / tiles_per_img, r0 = (tile - n * tiles_per_img) * TH;
+    const bf16_t* xb = a.x + ((size_t)(n * a.H + r0) * W) * CIN;
+    xin = 0;
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-      const int v = tid + i * 256;
       xs[i] = make_uint4(0, 0, 0, 0);
-      xin[i] = false;
-      if (v < XVEC) {
-        const int px = v / XCH;
-        const int col = px % W, rr = px / W;
-        const int ih = r0 - 1 + rr;
-        if (ih >= 0 && ih < a.H) {
-          xin[i] = true;
-          xs[i] = *reinterpret_cast<const uint4*>(a.x + ((size_t)(n * a.H + ih) * W + col) * CIN + ci0 + xch * 8);
-        }
+      const int ih = r0 - 1 + xrow[i];
+      if (xrow[i] >= 0 && ih >= 0 && ih < a.H) {
+        xin |= 1u << i;
+        xs[i] = *reinterpret_cast<const uint4*>(xb + xgoff[i]);
       }
     }
+    const size_t zb = ((size_t)(n * a.H + r0) * W) * COUT + (size_t)tid * 8;   // chunk v at zb + i*2048
 #pragma unroll
     for (int i = 0; i < ZPT; ++i) {
-      const int px = (tid + i * 256) / ZCH;
-      const size_t gi = ((size_t)(n * a.H + r0) * W + px) * COUT + zch * 8;
+      const size_t gi = zb + (size_t)i * 2048;
       if (fuse) {
         ds[i] = *reinterpret_cast<const uint4*>(a.dy + gi);
         zs[i] = *reinterpret_cast<const uint4*>(a.zc + gi);
@@ -134,6 +148,18 @@ __global__ __launch_bounds__(256) void wgrad_tiled_kernel(WgradTiledArgs a) {
 
   int tile = blockIdx.x;
   if (tile < a.tiles) issue(tile);
+
+  // ---- fragment addresses: lane and k-step part in a register, tap / ci-block / half as immediates
+  // k-step q of this wave covers pixels p = (kpart + q*KSPLIT)*32 + lg*8 .. +7 of the tile
+  const int sub = l16 >> 2, chq = (l16 & 3) * 8;     // pixel within a group of 4; byte offset of 4 channels
+  int zaddr[KPW], xaddr[KPW];
+#pragma unroll
+  for (int q = 0; q < KPW; ++q) {
+    const int p = (kpart + q * KSPLIT) * 32 + lg * 8;
+    const int row = p / W, col = p % W;
+    zaddr[q] = Cfg::LDS_X + (p + sub) * PIXZ + cb * 32 + chq;
+    xaddr[q] = (row * WC + col + sub) * PIXX + chq;
+  }
 
   // per-channel constants of this thread's chunks (derived while the first loads are in flight)
   float tsc[8], tsh[8];
@@ -157,131 +183,126 @@ __global__ __launch_bounds__(256) void wgrad_tiled_kernel(WgradTiledArgs a) {
     }
   }
 
-  auto unpack = [](const uint4& q, float (&f)[8]) {
-    f[0] = __uint_as_float(q.x << 16); f[1] = __uint_as_float(q.x & 0xffff0000u);
-    f[2] = __uint_as_float(q.y << 16); f[3] = __uint_as_float(q.y & 0xffff0000u);
-    f[4] = __uint_as_float(q.z << 16); f[5] = __uint_as_float(q.z & 0xffff0000u);
-    f[6] = __uint_as_float(q.w << 16); f[7] = __uint_as_float(q.w & 0xffff0000u);
-  };
   auto pack = [](const float (&f)[8]) {
     uint4 q;
     q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
     q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
     return q;
   };
-  auto scatter = [](uint16_t* d, int stride, const uint4& q) {   // 8 channels -> 8 planes
-    d[0 * stride] = (uint16_t)(q.x & 0xffff); d[1 * stride] = (uint16_t)(q.x >> 16);
-    d[2 * stride] = (uint16_t)(q.y & 0xffff); d[3 * stride] = (uint16_t)(q.y >> 16);
-    d[4 * stride] = (uint16_t)(q.z & 0xffff); d[5 * stride] = (uint16_t)(q.z >> 16);
-    d[6 * stride] = (uint16_t)(q.w & 0xffff); d[7 * stride] = (uint16_t)(q.w >> 16);
-  };
-  // transform the held registers and write them transposed into LDS
+  // transform the held registers and write them into LDS as they lie in memory
   auto stage = [&](int tile) {
     const int n = tile / tiles_per_img, r0 = (tile - n * tiles_per_img) * TH;
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
-      const int v = tid + i * 256;
-      if (v < XVEC) {
+      if (xloff[i] >= 0) {
         uint4 q = xs[i];
-        if (a.scale && xin[i]) {
+        if (a.scale && ((xin >> i) & 1u)) {
           float f[8];
-          unpack(q, f);
+          Store<bf16_t>::unpack_vec(q, f);
 #pragma unroll
           for (int j = 0; j < 8; ++j) { const float t = f[j] * tsc[j] + tsh[j]; f[j] = t > 0.f ? t : 0.f; }
           q = pack(f);
         }
-        const int px = v / XCH;
-        scatter(xT + (xch * 8) * PSX + (px / W) * WP + (px % W) + 8, PSX, q);
+        *reinterpret_cast<uint4*>(xt + xloff[i]) = q;
       }
     }
+    const size_t zb = ((size_t)(n * a.H + r0) * W) * COUT + (size_t)tid * 8;
 #pragma unroll
     for (int i = 0; i < ZPT; ++i) {
-      const int px = (tid + i * 256) / ZCH;
       uint4 q = ds[i];
       if (fuse) {
         float g[8], zz[8];
-        unpack(ds[i], g);
-        unpack(zs[i], zz);
+        Store<bf16_t>::unpack_vec(ds[i], g);
+        Store<bf16_t>::unpack_vec(zs[i], zz);
         if (a.mask) {
           float mk[8];
-          unpack(two_masks ? ms[i] : zs[i], mk);
+          Store<bf16_t>::unpack_vec(two_masks ? ms[i] : zs[i], mk);
 #pragma unroll
           for (int j = 0; j < 8; ++j) g[j] = (mk[j] * cms[j] + cmh[j]) > 0.f ? g[j] : 0.f;
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) g[j] = cA[j] * g[j] + (cB[j] * zz[j] + cC[j]);
         q = pack(g);
-        if (blockIdx.y == 0)
-          *reinterpret_cast<uint4*>(a.dz_out + ((size_t)(n * a.H + r0) * W + px) * COUT + zch * 8) = q;
+        if (blockIdx.y == 0) *reinterpret_cast<uint4*>(a.dz_out + zb + (size_t)i * 2048) = q;
       }
-      scatter(zT + (zch * 8) * PSZ + px, PSZ, q);
+      const int px = (tid + i * 256) / ZCH;
+      *reinterpret_cast<uint4*>(zt + px * PIXZ + zch * 16) = q;
     }
   };
+
+  f32x4_t acc[9][CIB];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int b = 0; b < CIB; ++b) acc[t][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   for (; tile < a.tiles; tile += gridDim.x) {
     __syncthreads();          // the previous tile has been contracted
     stage(tile);
     __syncthreads();
     if (tile + (int)gridDim.x < a.tiles) issue(tile + gridDim.x);   // in flight during the MFMA phase
-    // ---- contraction over the tile's pixels ----
-    for (int ks = kpart; ks < KSTEPS; ks += KSPLIT) {
-      const int px = ks * 32 + lg * 8;           // first of this lane's 8 pixels
-      const int row = px / W, col = px % W;
-      const uint4 zf = *reinterpret_cast<const uint4*>(zT + (cb * 16 + l16) * PSZ + px);
+    // ---- contraction over this wave's pixels of the tile ----
 #pragma unroll
-      for (int b = 0; b < CIB; ++b) {
-        const uint16_t* plane = xT + (b * 16 + l16) * PSX;
+    for (int q = 0; q < KPW; ++q) {
+      const uint4 zf = lds_frag_tr(smem + zaddr[q], 4 * PIXZ);
+      const unsigned char* xp = xt + xaddr[q];
 #pragma unroll
-        for (int r = 0; r < 3; ++r) {
-          const uint16_t* rowp = plane + (row + r) * WP + col + 8;
-          const uint4 m = *reinterpret_cast<const uint4*>(rowp);
-          const uint32_t left = rowp[-1], right = rowp[8];
-          uint4 s0, s2;
-          s0.x = (m.x << 16) | left;
-          s0.y = __builtin_amdgcn_alignbit(m.y, m.x, 16);
-          s0.z = __builtin_amdgcn_alignbit(m.z, m.y, 16);
-          s0.w = __builtin_amdgcn_alignbit(m.w, m.z, 16);
-          s2.x = __builtin_amdgcn_alignbit(m.y, m.x, 16);
-          s2.y = __builtin_amdgcn_alignbit(m.z, m.y, 16);
-          s2.z = __builtin_amdgcn_alignbit(m.w, m.z, 16);
-          s2.w = (m.w >> 16) | (right << 16);
-          acc[r * 3 + 0][b] = Mma<bf16_t>::mma(zf, s0, acc[r * 3 + 0][b]);
-          acc[r * 3 + 1][b] = Mma<bf16_t>::mma(zf, m, acc[r * 3 + 1][b]);
-          acc[r * 3 + 2][b] = Mma<bf16_t>::mma(zf, s2, acc[r * 3 + 2][b]);
-        }
-      }
+      for (int b = 0; b < CIB; ++b)
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+          for (int sx = 0; sx < 3; ++sx) {
+            const uint4 xf = lds_frag_tr(xp + (r * WC + sx) * PIXX + b * 32, 4 * PIXX);
+            acc[r * 3 + sx][b] = Mma<bf16_t>::mma(zf, xf, acc[r * 3 + sx][b]);
+          }
     }
   }
 
-  // ---- combine the waves that share a co-block (fixed order), write the partial tile ----
-  __syncthreads();
-  float* red = reinterpret_cast<float*>(smem);   // [KSPLIT][COB][9*CIB][16 co][17]
-  constexpr int FR = 9 * CIB;
-#pragma unroll
-  for (int t = 0; t < 9; ++t)
-#pragma unroll
-    for (int b = 0; b < CIB; ++b)
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        red[(((kpart * COB + cb) * FR + t * CIB + b) * 16 + lg * 4 + i) * 17 + l16] = acc[t][b][i];
-  __syncthreads();
+  // ---- add the waves that share a co-block in a fixed order; the first of them writes the
+  // partial tile: lane (l16, lg) holds ci = b*16 + l16, co = cb*16 + lg*4 + i of tap t ----
   constexpr int J = 9 * CIN;
-  for (int e = tid; e < COB * FR * 256; e += 256) {
-    const int ci_l = e & 15, co_l = (e >> 4) & 15, f = (e >> 8) % FR, cbb = (e >> 8) / FR;
-    float s = 0.f;
+  if (KSPLIT > 1) {
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem);   // [KSPLIT-1][COB][9*CIB*4][64 lanes]
+    constexpr int SLOTS = 9 * CIB * 4;
+    if (kpart > 0) {
+      float* w = red + (size_t)((kpart - 1) * COB + cb) * SLOTS * 64 + lane;
 #pragma unroll
-    for (int kp = 0; kp < KSPLIT; ++kp) s += red[(((kp * COB + cbb) * FR + f) * 16 + co_l) * 17 + ci_l];
-    const int t = f / CIB, b = f % CIB;
-    a.partial[((size_t)blockIdx.x * COUT + cbb * 16 + co_l) * J + t * CIN + ci0 + b * 16 + ci_l] = s;
+      for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int b = 0; b < CIB; ++b)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) w[((t * CIB + b) * 4 + i) * 64] = acc[t][b][i];
+    }
+    __syncthreads();
+    if (kpart == 0) {
+#pragma unroll
+      for (int kp = 1; kp < KSPLIT; ++kp) {
+        const float* w = red + (size_t)((kp - 1) * COB + cb) * SLOTS * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+          for (int b = 0; b < CIB; ++b)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[t][b][i] += w[((t * CIB + b) * 4 + i) * 64];
+      }
+    }
+  }
+  if (kpart == 0) {
+    float* dst = a.partial + ((size_t)blockIdx.x * COUT + cb * 16 + lg * 4) * J + ci0 + l16;
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+      for (int b = 0; b < CIB; ++b)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dst[(size_t)i * J + t * CIN + b * 16] = acc[t][b][i];
   }
 }
 
 template <int CIN, int COUT, int W>
 static hipError_t wgrad_tiled_launch_t(const WgradTiledArgs& a, int grid_x, hipStream_t s) {
   using Cfg = WgradTiledCfg<CIN, COUT, W>;
-  size_t lds = (size_t)(Cfg::LDS_X + Cfg::LDS_Z) * 2;
-  const size_t red = (size_t)Cfg::KSPLIT * Cfg::COB * 9 * Cfg::CIB * 16 * 17 * 4;
-  if (red > lds) lds = red;
+  const size_t lds = (size_t)Cfg::LDS;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_tiled_kernel<CIN, COUT, W>),
