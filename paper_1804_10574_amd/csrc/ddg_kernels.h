@@ -127,6 +127,7 @@ struct ConvStat {
   const void* mask; const float* mscale; const float* mshift;
   const void* z; const float* zmean; const float* zinvstd;
 };
+int conv_tiled_max_grid();   // no launch uses more workgroups (= partial statistics rows) than this
 int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
 // in_rows (optional): scale/shift are not final yet; the kernel derives them from these rows.
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,

@@ -306,8 +306,11 @@ ddg_status build_plan(ddg_module* m) {
       { void* sp = nullptr;
         DDG_OKAY(dev_alloc(m, &sp, st_e * sizeof(float)));
         u.fstat = (float*)sp;
-        // backward rows come from bn_bwd_reduce (<= 256 rows) or from a tiled input-gradient kernel (<= 512)
-        DDG_OKAY(dev_alloc(m, &sp, (size_t)512 * 2 * u.cout * sizeof(float)));
+        // backward rows come from bn_bwd_reduce (its own grid) or from the tiled input-gradient
+        // kernel of the layer above (at most conv_tiled_max_grid() workgroups)
+        int brows = bn_bwd_grid(u.out_elems(), u.cout, dt);
+        if (conv_tiled_max_grid() > brows) brows = conv_tiled_max_grid();
+        DDG_OKAY(dev_alloc(m, &sp, (size_t)brows * 2 * u.cout * sizeof(float)));
         u.bstat = (float*)sp; }
       // input gradient
       if (u.has_dgrad) {

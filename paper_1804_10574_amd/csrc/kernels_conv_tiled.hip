@@ -283,13 +283,23 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   }
 }
 
+// Upper bound of the grid (and so of the partial statistics rows a launch writes); the
+// DDG_TUNE_CONV_GRID environment variable overrides the default within [64, 2048].
+int conv_tiled_max_grid() {
+  int cap = 256;   // one workgroup per compute unit: fewer statistics rows for the consumers to add up
+  if (const char* e = getenv("DDG_TUNE_CONV_GRID")) {
+    const int v = atoi(e);
+    if (v >= 64 && v <= 2048) cap = v;
+  }
+  return cap;
+}
+
 int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype) {
   if (dtype != BF16 || R != 3 || stride != 1 || Cin != Cout) return 0;
   if (!((Cin == 16 && W == 32) || (Cin == 32 && W == 16) || (Cin == 64 && W == 8))) return 0;
   if (H % 8 != 0) return 0;
   const int tiles = N * (H / 8);
-  int cap = 512;
-  if (const char* e = getenv("DDG_TUNE_CONV_GRID")) cap = atoi(e) > 0 ? atoi(e) : cap;
+  const int cap = conv_tiled_max_grid();
   return tiles < cap ? tiles : cap;
 }
 

@@ -322,7 +322,10 @@ int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, 
   if (H % 8 != 0) return 0;
   const int tiles = N * (H / 8);
   int want = (Cin == 16) ? 256 : (Cin == 32 ? 128 : 32);
-  if (const char* e = getenv("DDG_TUNE_WGRAD_ROWS")) want = atoi(e) > 0 ? atoi(e) : want;
+  if (const char* e = getenv("DDG_TUNE_WGRAD_ROWS")) {   // override within [8, 1024]
+    const int v = atoi(e);
+    if (v >= 8 && v <= 1024) want = v;
+  }
   if (want > tiles) want = tiles;
   return want;
 }
