@@ -130,9 +130,12 @@ struct ConvStat {
 int conv_tiled_max_grid();   // no launch uses more workgroups (= partial statistics rows) than this
 int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
 // in_rows (optional): scale/shift are not final yet; the kernel derives them from these rows.
+// res (optional, forward with statistics only): the conv input is relu(in*scale+shift + res),
+// the output of the residual block before; y_out (optional) receives that input tensor.
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
                              const void* wpack, void* out, const ConvStat& st, const void* add_g,
-                             const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s);
+                             const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
+                             const void* res = nullptr, void* y_out = nullptr);
 
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
 // shift=beta-mean*scale.

@@ -441,8 +441,12 @@ BnRows fwd_rows(ddg_module* m, Unit& u) {
 // conv of one unit: in -> u.z plus partial rows of its batch statistics. For cout <= 64 the
 // consumer of the BN output derives mean/invstd/scale/shift from the rows (and stores them);
 // wider layers get a finalise launch here. `src`, if given, is the unit whose BN + ReLU
-// produces this conv's input from `in` while loading (LDS-tiled kernel only).
-ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src) {
+// produces this conv's input from `in` while loading (LDS-tiled kernel only). With `res` the
+// input is the output of the residual block before, relu(bn(in) + res), which the kernel also
+// stores to y_store: that block's separate normalise-add-ReLU pass is absorbed.
+ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const void* res = nullptr,
+                        void* y_store = nullptr) {
+  if (res && !(u.tiled_grid > 0 && src)) return fail(DDG_ERR_STATE, "internal: residual input needs the tiled kernel");
   if (u.tiled_grid > 0) {
     u.frows = u.tiled_grid;
     ConvStat st{};
@@ -450,10 +454,11 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src) {
     BnRows ir{};
     const bool from_rows = src && src->small_c();
     if (from_rows) ir = fwd_rows(m, *src);
-    Launch L(m, PK_CONV_FPROP + u.tiled_instance(), (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
+    Launch L(m, PK_CONV_FPROP + u.tiled_instance(),
+             ((res ? 3.0 : 1.0) * u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
     DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? src->scale : nullptr, (src && !from_rows) ? src->shift : nullptr,
                               from_rows ? &ir : nullptr, u.wpack_f, u.z, st, nullptr, nullptr, u.N, u.H, u.W,
-                              u.cin, u.tiled_grid, m->stream));
+                              u.cin, u.tiled_grid, m->stream, res, y_store));
   } else {
     if (src) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
     ConvArgs a = u.fprop;
@@ -491,14 +496,26 @@ ddg_status apply_bn(ddg_module* m, Unit& u, const void* res, Unit* ru, void* y) 
 ddg_status run_forward(ddg_module* m, std::vector<Blk>& blocks, const void* in, void* final_out) {
   const void* x = in;
   const int nres = (int)blocks.size() - (m->d.num_classes > 0 ? 1 : 0);
+  // An identity block followed by another identity block of the same shape does not run its
+  // own normalise-add-ReLU pass: the next block's first conv forms y = relu(bn(z) + x) while
+  // loading and stores it (`pend` carries what that conv needs).
+  static const bool no_defer = getenv("DDG_NO_DEFER") && getenv("DDG_NO_DEFER")[0] == '1';
+  struct { Unit* u = nullptr; const void* res = nullptr; void* y = nullptr; } pend;
   for (int bi = 0; bi < nres; ++bi) {
     Blk& b = blocks[bi];
     void* yout = (bi == nres - 1 && final_out) ? final_out : b.y;
     const void* cur = x;
     Unit* src = nullptr;   // pending relu(bn(.)) of `cur`
+    const void* res_in = nullptr;
+    void* y_store = nullptr;
+    if (pend.u) {
+      cur = pend.u->z; src = pend.u; res_in = pend.res; y_store = pend.y;
+      x = pend.y;          // materialised by this block's first conv
+      pend.u = nullptr;
+    }
     for (int i = 0; i < b.nmain; ++i) {
       Unit& u = b.u[i];
-      DDG_OKAY(unit_forward(m, u, cur, src));
+      DDG_OKAY(unit_forward(m, u, cur, src, i == 0 ? res_in : nullptr, i == 0 ? y_store : nullptr));
       src = nullptr;
       if (i + 1 < b.nmain) {
         if (b.act[i]) {
@@ -517,7 +534,14 @@ ddg_status run_forward(ddg_module* m, std::vector<Blk>& blocks, const void* in, 
       DDG_OKAY(unit_forward(m, up, x, nullptr));
       DDG_OKAY(apply_bn(m, ul, nullptr, &up, yout));
     } else {
-      DDG_OKAY(apply_bn(m, ul, x, nullptr, yout));
+      bool defer = false;
+      if (!no_defer && bi + 1 < nres && b.kind == DDG_BLOCK_BASIC && ul.tiled_grid > 0) {
+        const Blk& nb = blocks[bi + 1];
+        defer = nb.kind == DDG_BLOCK_BASIC && !nb.proj && nb.u[0].tiled_grid > 0 && nb.u[0].cin == ul.cout &&
+                nb.u[0].H == ul.P && nb.u[0].W == ul.Q;
+      }
+      if (defer) { pend.u = &ul; pend.res = x; pend.y = yout; }
+      else DDG_OKAY(apply_bn(m, ul, x, nullptr, yout));
     }
     x = yout;
   }

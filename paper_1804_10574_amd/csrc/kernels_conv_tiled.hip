@@ -22,6 +22,8 @@ namespace ddg {
 
 struct ConvTiledArgs {
   const bf16_t* in;        // [N,H,W,C]
+  const bf16_t* res;       // optional (RES kernels): input = relu(in*scale+shift + res), same layout
+  bf16_t* y_out;           // optional (RES kernels): that input is also stored here (tile rows only)
   const float* scale;      // optional input transform relu(in*scale+shift)
   const float* shift;
   BnRows in_rows;          // in_rows.partial != null: scale/shift come from these partial rows
@@ -56,7 +58,9 @@ struct ConvTiledCfg {
 // instruction immediate per pixel block, fragment reads are unconditional 16-byte reads, the
 // tensors the epilogue needs are requested before the MFMA phase, and fp32 -> bf16 uses the
 // packed hardware conversion.
-template <int C, int W, int MODE>
+// RES: the input is the output of the residual block before, y = relu(in*scale+shift + res),
+// formed while staging and written to y_out by the workgroup that owns the rows.
+template <int C, int W, int MODE, bool RES = false>
 __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   using Cfg = ConvTiledCfg<C, W>;
   constexpr int TH = Cfg::TH, WC = Cfg::WC, PIX = Cfg::PIX, CH = Cfg::CH, NCHUNK = Cfg::NCHUNK;
@@ -84,11 +88,13 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
     goff[i] = ((rr - 1) * W + (cc - 1)) * C + my_ch * 8;
     loff[i] = v < NCHUNK ? px * PIX + my_ch * 16 : -1;
   }
-  uint4 stage[PT];
+  uint4 stage[PT], stage2[RES ? PT : 1];
   unsigned inimg = 0;   // bit i: chunk i of the tile in flight lies inside the image
+  size_t tile_base = 0; // element offset of the staged tile's first pixel
   auto issue_loads = [&](int t) {
     const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
-    const bf16_t* base = a.in + ((size_t)(n * a.H + r0) * W) * C;
+    const size_t tb = ((size_t)(n * a.H + r0) * W) * C;
+    tile_base = tb;
     inimg = 0;
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
@@ -96,7 +102,8 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
       const int ih = r0 - 1 + srow[i];
       if (srow[i] >= 0 && ih >= 0 && ih < a.H) {
         inimg |= 1u << i;
-        stage[i] = *reinterpret_cast<const uint4*>(base + goff[i]);
+        stage[i] = *reinterpret_cast<const uint4*>(a.in + tb + goff[i]);
+        if (RES) stage2[i] = *reinterpret_cast<const uint4*>(a.res + tb + goff[i]);
       }
     }
   };
@@ -138,6 +145,7 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
     for (int j = 0; j < 8; ++j) { tsc[j] = a.scale[my_ch * 8 + j]; tsh[j] = a.shift[my_ch * 8 + j]; }
   }
   auto write_stage = [&]() {
+    const size_t stage_base = tile_base;   // of the tile held in the registers
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       if (loff[i] >= 0) {
@@ -145,13 +153,22 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
         if (xform && ((inimg >> i) & 1u)) {
           float f[8];
           Store<bf16_t>::unpack_vec(q, f);
+          if (RES) {
+            float r[8];
+            Store<bf16_t>::unpack_vec(stage2[i], r);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float v = f[j] * tsc[j] + tsh[j];
-            f[j] = v > 0.f ? v : 0.f;
+            for (int j = 0; j < 8; ++j) f[j] = f[j] * tsc[j] + tsh[j] + r[j];
+          } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) f[j] = f[j] * tsc[j] + tsh[j];
           }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) f[j] = f[j] > 0.f ? f[j] : 0.f;
           q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
           q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
+          // the tile's own rows (halo rows 1..8) are this workgroup's to store
+          if (RES && a.y_out && srow[i] >= 1 && srow[i] <= TH)
+            *reinterpret_cast<uint4*>(a.y_out + stage_base + goff[i]) = q;
         }
         *reinterpret_cast<uint4*>(tile + loff[i]) = q;
       }
@@ -283,15 +300,26 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   }
 }
 
-// Upper bound of the grid (and so of the partial statistics rows a launch writes); the
-// DDG_TUNE_CONV_GRID environment variable overrides the default within [64, 2048].
-int conv_tiled_max_grid() {
-  int cap = 256;   // one workgroup per compute unit: fewer statistics rows for the consumers to add up
-  if (const char* e = getenv("DDG_TUNE_CONV_GRID")) {
+// Workgroups per launch for a layer with C channels (and so the number of partial statistics
+// rows the launch writes). Every workgroup loads its wave's weights and adds up the rows of the
+// layer before, so on the small feature maps fewer, longer-running workgroups mean less L2
+// traffic. DDG_TUNE_CONV_GRID_C16/_C32/_C64 override the defaults within [32, 2048].
+static int conv_tiled_cap(int C) {
+  int cap = C == 64 ? 128 : 256;
+  const char* name = C == 16 ? "DDG_TUNE_CONV_GRID_C16" : (C == 32 ? "DDG_TUNE_CONV_GRID_C32" : "DDG_TUNE_CONV_GRID_C64");
+  if (const char* e = getenv(name)) {
     const int v = atoi(e);
-    if (v >= 64 && v <= 2048) cap = v;
+    if (v >= 32 && v <= 2048) cap = v;
   }
   return cap;
+}
+
+// No launch uses more workgroups than this (sizes row buffers).
+int conv_tiled_max_grid() {
+  int m = conv_tiled_cap(16);
+  if (conv_tiled_cap(32) > m) m = conv_tiled_cap(32);
+  if (conv_tiled_cap(64) > m) m = conv_tiled_cap(64);
+  return m;
 }
 
 int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype) {
@@ -299,14 +327,17 @@ int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, i
   if (!((Cin == 16 && W == 32) || (Cin == 32 && W == 16) || (Cin == 64 && W == 8))) return 0;
   if (H % 8 != 0) return 0;
   const int tiles = N * (H / 8);
-  const int cap = conv_tiled_max_grid();
+  const int cap = conv_tiled_cap(Cin);
   return tiles < cap ? tiles : cap;
 }
 
 template <int C, int W>
 static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStream_t s) {
   using Cfg = ConvTiledCfg<C, W>;
-  if (a.st.mode == 1) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 1>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+  if (a.res) {
+    if (a.st.mode != 1 || !(a.scale || a.in_rows.partial)) return hipErrorInvalidValue;
+    DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 1, true>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+  } else if (a.st.mode == 1) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 1>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
   else if (a.st.mode == 2) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 2>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
   else DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 0>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
   return hipGetLastError();
@@ -314,9 +345,11 @@ static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStrea
 
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
                              const void* wpack, void* out, const ConvStat& st, const void* add_g,
-                             const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s) {
+                             const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
+                             const void* res, void* y_out) {
   ConvTiledArgs a;
   a.in = (const bf16_t*)in; a.scale = scale; a.shift = shift; a.wpack = (const bf16_t*)wpack;
+  a.res = (const bf16_t*)res; a.y_out = (bf16_t*)y_out;
   if (in_rows) a.in_rows = *in_rows; else a.in_rows = BnRows{};
   a.out = (bf16_t*)out; a.st = st; a.add_g = (const bf16_t*)add_g;
   a.add_mask = (const bf16_t*)add_mask; a.N = N; a.H = H; a.tiles = N * (H / 8);
