@@ -112,6 +112,7 @@ hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* sh
                               const WgradFuse* fuse, float* partial, int N, int H, int W, int C, int rows,
                               hipStream_t s);
 
+
 // LDS-tiled 3x3/stride-1 convolution for 16/32/64 channels (bf16). Returns the grid (= number of
 // statistics rows), 0 if the shape is not covered. scale/shift: optional relu(in*scale+shift)
 // applied while staging. The same kernel computes the input gradient from an operand packed
@@ -136,6 +137,7 @@ hipError_t conv_tiled_launch(const void* in, const float* scale, const float* sh
                              const void* wpack, void* out, const ConvStat& st, const void* add_g,
                              const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
                              const void* res = nullptr, void* y_out = nullptr);
+
 
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
 // shift=beta-mean*scale.

@@ -49,6 +49,12 @@ struct ConvTiledCfg {
   static constexpr int COB = C / 16;
 };
 
+// Waves per SIMD the register allocation aims for (more co-resident workgroups when several
+// streams run): the largest value each variant reaches without spilling.
+constexpr int conv_tiled_waves(int C, int MODE, bool RES) {
+  return C == 64 ? (RES ? 1 : 2) : ((C == 32 && (RES || MODE == 2)) ? 2 : 3);
+}
+
 // MODE is the epilogue's statistics mode, fixed at compile time: 0 none, 1 sum / sum of squares
 // of the stored output (forward), 2 the BN-backward sums of the layer below (input gradient).
 //
@@ -61,7 +67,7 @@ struct ConvTiledCfg {
 // RES: the input is the output of the residual block before, y = relu(in*scale+shift + res),
 // formed while staging and written to y_out by the workgroup that owns the rows.
 template <int C, int W, int MODE, bool RES = false>
-__global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_waves(C, MODE, RES)))) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   using Cfg = ConvTiledCfg<C, W>;
   constexpr int TH = Cfg::TH, WC = Cfg::WC, PIX = Cfg::PIX, CH = Cfg::CH, NCHUNK = Cfg::NCHUNK;
   constexpr int PT = Cfg::PER_THREAD, KSTEPS = Cfg::KSTEPS, PG = Cfg::PG, COB = Cfg::COB;
@@ -76,7 +82,7 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   // ---- staging map (the same for every tile): chunk v = tid + i*256 -> halo pixel, 8 channels
   const int my_ch = tid % CH;
   int goff[PT];      // element offset of the chunk relative to the tile's first pixel (row r0, column 0)
-  int srow[PT];      // halo row 0..9 of the chunk; -1: no chunk, or a pad column (stays zero)
+  unsigned srows = 0;  // 4 bits per chunk: halo row 0..9 of the chunk + 1; 0: no chunk, or a pad column (stays zero)
   int loff[PT];      // LDS byte offset
 #pragma unroll
   for (int i = 0; i < PT; ++i) {
@@ -84,23 +90,24 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
     const int px = v / CH;
     const int rr = px / WC, cc = px - rr * WC;
     const bool col_ok = v < NCHUNK && cc >= 1 && cc <= W;
-    srow[i] = col_ok ? rr : -1;
+    srows |= (col_ok ? (unsigned)(rr + 1) : 0u) << (4 * i);
     goff[i] = ((rr - 1) * W + (cc - 1)) * C + my_ch * 8;
     loff[i] = v < NCHUNK ? px * PIX + my_ch * 16 : -1;
   }
   uint4 stage[PT], stage2[RES ? PT : 1];
   unsigned inimg = 0;   // bit i: chunk i of the tile in flight lies inside the image
-  size_t tile_base = 0; // element offset of the staged tile's first pixel
+  unsigned tile_base = 0;   // element offset of the staged tile's first pixel (the host checks 32 bits suffice)
   auto issue_loads = [&](int t) {
     const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
-    const size_t tb = ((size_t)(n * a.H + r0) * W) * C;
+    const unsigned tb = (unsigned)((n * a.H + r0) * W) * C;
     tile_base = tb;
     inimg = 0;
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       stage[i] = make_uint4(0, 0, 0, 0);
-      const int ih = r0 - 1 + srow[i];
-      if (srow[i] >= 0 && ih >= 0 && ih < a.H) {
+      const int sr = (int)((srows >> (4 * i)) & 15u) - 1;   // halo row, -1: nothing to load
+      const int ih = r0 - 1 + sr;
+      if (sr >= 0 && ih >= 0 && ih < a.H) {
         inimg |= 1u << i;
         stage[i] = *reinterpret_cast<const uint4*>(a.in + tb + goff[i]);
         if (RES) stage2[i] = *reinterpret_cast<const uint4*>(a.res + tb + goff[i]);
@@ -132,26 +139,28 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
     kaddr[ks] = lane_base + ((tp / 3) * WC + (tp % 3)) * PIX + c0 * 2;
   }
 
-  // ---- per-channel transform of the input (while the first tile's loads are in flight)
+  // ---- per-channel transform of the input (while the first tile's loads are in flight); the
+  // vectors stay in LDS and a thread reads its 8 channels when it stages (registers are scarce)
   const bool xform = a.scale != nullptr || a.in_rows.partial != nullptr;
-  float tsc[8], tsh[8];
+  __shared__ __align__(16) float s_sc[C], s_sh[C];
   if (a.in_rows.partial) {
-    __shared__ float s_sc[C], s_sh[C];
     bn_fwd_from_rows<C>(a.in_rows, s_sc, s_sh, blockIdx.x == 0);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { tsc[j] = s_sc[my_ch * 8 + j]; tsh[j] = s_sh[my_ch * 8 + j]; }
   } else if (a.scale) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { tsc[j] = a.scale[my_ch * 8 + j]; tsh[j] = a.shift[my_ch * 8 + j]; }
+    if (tid < C) { s_sc[tid] = a.scale[tid]; s_sh[tid] = a.shift[tid]; }
+    __syncthreads();
   }
   auto write_stage = [&]() {
-    const size_t stage_base = tile_base;   // of the tile held in the registers
+    const unsigned stage_base = tile_base;   // of the tile held in the registers
 #pragma unroll
     for (int i = 0; i < PT; ++i) {
       if (loff[i] >= 0) {
         uint4 q = stage[i];
         if (xform && ((inimg >> i) & 1u)) {
-          float f[8];
+          float f[8], tsc[8], tsh[8];
+          *reinterpret_cast<float4*>(&tsc[0]) = *reinterpret_cast<const float4*>(&s_sc[my_ch * 8]);
+          *reinterpret_cast<float4*>(&tsc[4]) = *reinterpret_cast<const float4*>(&s_sc[my_ch * 8 + 4]);
+          *reinterpret_cast<float4*>(&tsh[0]) = *reinterpret_cast<const float4*>(&s_sh[my_ch * 8]);
+          *reinterpret_cast<float4*>(&tsh[4]) = *reinterpret_cast<const float4*>(&s_sh[my_ch * 8 + 4]);
           Store<bf16_t>::unpack_vec(q, f);
           if (RES) {
             float r[8];
@@ -167,7 +176,8 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
           q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
           q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
           // the tile's own rows (halo rows 1..8) are this workgroup's to store
-          if (RES && a.y_out && srow[i] >= 1 && srow[i] <= TH)
+          const unsigned sr1 = (srows >> (4 * i)) & 15u;   // halo row + 1
+          if (RES && a.y_out && sr1 >= 2 && sr1 <= TH + 1)
             *reinterpret_cast<uint4*>(a.y_out + stage_base + goff[i]) = q;
         }
         *reinterpret_cast<uint4*>(tile + loff[i]) = q;
@@ -176,18 +186,19 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
   };
 
   float ssum[4] = {0.f, 0.f, 0.f, 0.f}, ssq[4] = {0.f, 0.f, 0.f, 0.f};
-  // mode 2: per-channel constants of the BN below, for this lane's 4 channels
-  float bmu[4], bis[4], bms[4], bmh[4];
+  // mode 2: per-channel constants of the BN below (mean, invstd, mask scale, mask shift) in LDS;
+  // a lane reads those of its 4 channels in the epilogue
+  __shared__ __align__(16) float s_below[MODE == 2 ? 4 * C : 4];
   const bf16_t* st_mask = reinterpret_cast<const bf16_t*>(a.st.mask);
   const bf16_t* st_z = reinterpret_cast<const bf16_t*>(a.st.z);
   const bool two_tensors = MODE == 2 && st_z != st_mask;
   if (MODE == 2) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = cb * 16 + lg * 4 + j;
-      bmu[j] = a.st.zmean[c]; bis[j] = a.st.zinvstd[c];
-      bms[j] = a.st.mscale ? a.st.mscale[c] : 1.f; bmh[j] = a.st.mscale ? a.st.mshift[c] : 0.f;
+    if (tid < C) {
+      s_below[tid] = a.st.zmean[tid]; s_below[C + tid] = a.st.zinvstd[tid];
+      s_below[2 * C + tid] = a.st.mscale ? a.st.mscale[tid] : 1.f;
+      s_below[3 * C + tid] = a.st.mscale ? a.st.mshift[tid] : 0.f;
     }
+    // (made visible by the barriers of the tile loop before any epilogue runs)
   }
   // output element offset of (block 0, this lane) inside a tile; block i adds i*16*C
   const int out_lane = ptl * C + cb * 16 + lg * 4;
@@ -201,7 +212,7 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
 
     // what the epilogue reads, requested now
     const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
-    const size_t obase = ((size_t)(n * a.H + r0) * W) * C + out_lane;
+    const unsigned obase = (unsigned)((n * a.H + r0) * W) * C + out_lane;
     uint2 eg[4], em[4], ek[4], ez[4];
     if (a.add_g) {
 #pragma unroll
@@ -261,6 +272,13 @@ __global__ __launch_bounds__(256) void conv3x3_tiled_kernel(ConvTiledArgs a) {
           for (int j = 0; j < 4; ++j) { ssum[j] += r[j]; ssq[j] += r[j] * r[j]; }
         } else {
           const float mk[4] = {lo(ek[i].x), hi(ek[i].x), lo(ek[i].y), hi(ek[i].y)};
+          const int cq = cb * 16 + lg * 4;
+          const float4 bmu4 = *reinterpret_cast<const float4*>(&s_below[cq]);
+          const float4 bis4 = *reinterpret_cast<const float4*>(&s_below[C + cq]);
+          const float4 bms4 = *reinterpret_cast<const float4*>(&s_below[2 * C + cq]);
+          const float4 bmh4 = *reinterpret_cast<const float4*>(&s_below[3 * C + cq]);
+          const float bmu[4] = {bmu4.x, bmu4.y, bmu4.z, bmu4.w}, bis[4] = {bis4.x, bis4.y, bis4.z, bis4.w};
+          const float bms[4] = {bms4.x, bms4.y, bms4.z, bms4.w}, bmh[4] = {bmh4.x, bmh4.y, bmh4.z, bmh4.w};
           float zz[4];
           if (two_tensors) { zz[0] = lo(ez[i].x); zz[1] = hi(ez[i].x); zz[2] = lo(ez[i].y); zz[3] = hi(ez[i].y); }
           else { zz[0] = mk[0]; zz[1] = mk[1]; zz[2] = mk[2]; zz[3] = mk[3]; }
@@ -353,6 +371,7 @@ hipError_t conv_tiled_launch(const void* in, const float* scale, const float* sh
   if (in_rows) a.in_rows = *in_rows; else a.in_rows = BnRows{};
   a.out = (bf16_t*)out; a.st = st; a.add_g = (const bf16_t*)add_g;
   a.add_mask = (const bf16_t*)add_mask; a.N = N; a.H = H; a.tiles = N * (H / 8);
+  if ((size_t)N * H * W * C >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside
   if (C == 16 && W == 32) return conv_tiled_launch_t<16, 32>(a, grid, s);
   if (C == 32 && W == 16) return conv_tiled_launch_t<32, 16>(a, grid, s);
   if (C == 64 && W == 8) return conv_tiled_launch_t<64, 8>(a, grid, s);

@@ -326,6 +326,11 @@ int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, 
     const int v = atoi(e);
     if (v >= 8 && v <= 1024) want = v;
   }
+  const char* name = Cin == 16 ? "DDG_TUNE_WGRAD_ROWS_C16" : (Cin == 32 ? "DDG_TUNE_WGRAD_ROWS_C32" : "DDG_TUNE_WGRAD_ROWS_C64");
+  if (const char* e = getenv(name)) {                    // per-shape override within [8, 256]
+    const int v = atoi(e);
+    if (v >= 8 && v <= 256) want = v;
+  }
   if (want > tiles) want = tiles;
   return want;
 }
