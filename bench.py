@@ -26,12 +26,13 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 # profile kind -> the HIP kernel it times (as rocprofv3 names it)
 HIP_KERNEL_OF = {
-    "conv_fprop.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 1>",
-    "conv_fprop.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 1>",
-    "conv_fprop.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 1>",
-    "conv_dgrad.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 2> (and <16, 32, 0>)",
-    "conv_dgrad.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 2> (and <32, 16, 0>)",
-    "conv_dgrad.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 2> (and <64, 8, 0>)",
+    "conv_fprop.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 1, false|true>",
+    "conv_fprop.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 1, false|true>",
+    "conv_fprop.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 1, false|true>",
+    "conv_dgrad.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 2|0, false>",
+    "conv_dgrad.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 2|0, false>",
+    "conv_dgrad.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 2|0, false>",
+    "bn_apply": "ddg::bn_apply_chunk_kernel<bf16_t, U>",
     "conv_wgrad.tiled_c16_w32": "ddg::wgrad_tiled_kernel<16, 16, 32>",
     "conv_wgrad.tiled_c32_w16": "ddg::wgrad_tiled_kernel<32, 32, 16>",
     "conv_wgrad.tiled_c64_w8": "ddg::wgrad_tiled_kernel<64, 64, 8>",
@@ -89,8 +90,8 @@ def cpu_baseline(wl_name, sample_batch, timed_steps=1):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet110_k4")
     ap.add_argument("--cpu-sample-batch", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")

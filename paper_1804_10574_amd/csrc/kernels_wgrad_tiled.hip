@@ -79,7 +79,7 @@ __device__ __forceinline__ uint4 lds_frag_tr(const unsigned char* p, int half_st
 }
 
 template <int CIN, int COUT, int W>
-__global__ __launch_bounds__(256) void wgrad_tiled_kernel(WgradTiledArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CIN == 32 ? 2 : 3))) void wgrad_tiled_kernel(WgradTiledArgs a) {
   using Cfg = WgradTiledCfg<CIN, COUT, W>;
   constexpr int TH = Cfg::TH, ROWS = Cfg::ROWS, WC = Cfg::WC, CIB = Cfg::CIB, CINW = Cfg::CINW;
   constexpr int COB = Cfg::COB, KSPLIT = Cfg::KSPLIT, KPW = Cfg::KPW, PIXX = Cfg::PIXX, PIXZ = Cfg::PIXZ;

@@ -24,7 +24,7 @@ import sys
 
 def kind_of(kernel_name: str) -> str:
     n = kernel_name.split("(")[0].replace("void ", "").replace("ddg::", "").strip()
-    m = re.match(r"conv3x3_tiled_kernel<(\d+), (\d+), (\d+)>", n)
+    m = re.match(r"conv3x3_tiled_kernel<(\d+), (\d+), (\d+)", n)
     if m:
         fam = "conv_fprop" if m.group(3) == "1" else "conv_dgrad"
         return f"{fam}.tiled_c{m.group(1)}_w{m.group(2)}"
@@ -37,6 +37,7 @@ def kind_of(kernel_name: str) -> str:
     table = [("wgrad_mfma_kernel", "conv_wgrad.generic"), ("wgrad_reduce", "wgrad_reduce"),
              ("bn_bwd_apply_kernel", "bn_bwd_apply"), ("bn_bwd_reduce_kernel", "bn_bwd_reduce"),
              ("bn_bwd_finalize", "bn_bwd_finalize"), ("bn_apply_kernel", "bn_apply"),
+             ("bn_apply_chunk_kernel", "bn_apply"),
              ("bn_finalize", "bn_finalize"), ("head_", "head"), ("sgd_kernel", "sgd"),
              ("pack_", "pack_weights"), ("copy_kernel", "copy")]
     for prefix, kind in table:
@@ -55,10 +56,18 @@ def stats(path: str, steps: float, out=sys.stdout):
     print(f"kernel time per pipeline iteration: {total / 1e6 / steps:.3f} ms "
           f"({sum(int(r['Calls']) for r in rows) / steps:.0f} launches)", file=out)
     print(f"{'kernel':<44} {'kind':<26} {'calls/it':>8} {'avg us':>8} {'ms/it':>7} {'share':>6}", file=out)
+    kinds = collections.defaultdict(lambda: [0, 0.0])
     for r in rows:
         t = float(r["TotalDurationNs"])
+        k = kinds[kind_of(r["Name"])]
+        k[0] += int(r["Calls"]); k[1] += t
         print(f"{short(r['Name'])[:44]:<44} {kind_of(r['Name']):<26} {int(r['Calls']) / steps:8.1f} "
               f"{float(r['AverageNs']) / 1e3:8.2f} {t / 1e6 / steps:7.3f} {100 * t / total:5.1f}%", file=out)
+    print("", file=out)
+    print("per kind (the unit bench.py's `kernels` and `roofline` use):", file=out)
+    print(f"{'kind':<28} {'calls/it':>8} {'avg us':>8} {'ms/it':>7}", file=out)
+    for name, (n, t) in sorted(kinds.items(), key=lambda kv: -kv[1][1]):
+        print(f"{name:<28} {n / steps:8.1f} {t / n / 1e3:8.2f} {t / 1e6 / steps:7.3f}", file=out)
 
 
 def _per_kernel(path: str, counter: str):
