@@ -49,7 +49,8 @@ def build_pipeline(wl, serial=False, forward_streams=False):
     import paper_1804_10574_amd as ddg
     from paper_1804_10574_amd.ddg import make_desc
     streams = [torch.cuda.Stream() for _ in range(wl.K)]
-    fstreams = [torch.cuda.Stream() for _ in range(wl.K)]   # forward passes on streams of their own
+    # optional: forward passes on streams of their own
+    fstreams = [torch.cuda.Stream() for _ in range(wl.K)] if (forward_streams and not serial) else None
     descs = []
     for m in wl.modules:
         descs.append(make_desc(wl.K, m.k, wl.batch, (m.in_c, m.in_h, m.in_w),
@@ -57,7 +58,7 @@ def build_pipeline(wl, serial=False, forward_streams=False):
                                wl.num_classes if m.blocks[-1].kind == wk.BLOCK_HEAD else 0,
                                ddg.DDG_BF16 if wl.dtype == "bf16" else ddg.DDG_F32,
                                wl.momentum, wl.weight_decay, wl.bn_eps,
-                               forward_stream=fstreams[m.k - 1].cuda_stream if (forward_streams and not serial) else None))
+                               forward_stream=fstreams[m.k - 1].cuda_stream if fstreams else None))
     pipe = ddg.Pipeline(descs, None if serial else [s.cuda_stream for s in streams])
     for m in wl.modules:
         pipe.module(m.k).set_params(wk.init_module_params(wl, m).astype(np.float32))

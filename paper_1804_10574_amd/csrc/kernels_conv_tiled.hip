@@ -237,8 +237,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
       const unsigned char* kp = tile + kaddr[ks];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        constexpr int PT0 = 0;  // (silences unused warnings on some shapes)
-        (void)PT0;
         const int blk = (((i * 16) / W) * WC + (i * 16) % W) * PIX;   // constant after unrolling
         uint4 af = *reinterpret_cast<const uint4*>(kp + blk);
         if (RAGGED_K && ks == KSTEPS - 1 && !klast_ok) af = make_uint4(0, 0, 0, 0);
