@@ -133,10 +133,15 @@ int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, i
 // in_rows (optional): scale/shift are not final yet; the kernel derives them from these rows.
 // res (optional, forward with statistics only): the conv input is relu(in*scale+shift + res),
 // the output of the residual block before; y_out (optional) receives that input tensor.
+// groups > 1 (forward only): N counts the images of `groups` minibatches laid end to end, each
+// with its own batch-norm statistics; grid workgroups are split evenly over the groups, the
+// statistics rows (st.partial, in_rows->partial) are [group][grid/groups][2][C], and the
+// per-channel vectors of group g lie g*vec_stride floats after those of group 0.
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
                              const void* wpack, void* out, const ConvStat& st, const void* add_g,
                              const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
-                             const void* res = nullptr, void* y_out = nullptr);
+                             const void* res = nullptr, void* y_out = nullptr, int groups = 1,
+                             int vec_stride = 0);
 
 
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,

@@ -63,14 +63,19 @@ struct Unit {  // convolution + batch normalisation
   int wg_tiled_rows = 0;   // > 0: the LDS-tiled bf16 weight-gradient kernel covers this layer
   int tiled_grid = 0;      // > 0: the LDS-tiled conv kernel covers this layer (forward and dgrad)
   float* wg_partial = nullptr;  // this layer's weight-gradient partial tiles (kept until the update)
-  float* fstat = nullptr;       // partial rows of the forward statistics [frows][2][cout]
+  float* fstat = nullptr;       // partial rows of the forward statistics [group][fcap][2][cout]
   float* bstat = nullptr;       // partial rows of the BN-backward sums [brows][2][cout]
-  int frows = 0;                // rows written by the last forward conv
+  int fcap = 0;                 // rows reserved per group in fstat
+  int frows = 0;                // rows written by the last forward conv (per group)
   // consumers finalise the partial rows themselves (their reduction is built for these widths)
   bool small_c() const { return cout == 16 || cout == 32 || cout == 64; }
   int tiled_instance() const { return cin == 16 ? 1 : cin == 32 ? 2 : 3; }   // offset of a tiled kernel's profile kind
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
   size_t in_elems() const { return (size_t)N * H * W * cin; }
+  // Group g of the forward buffers. Group 0 is the tape the backward pass reads; a module that
+  // runs the forward pass of the current minibatch together with the re-forward of the delayed
+  // one keeps a second group right behind the first (conv output, statistics rows, vectors).
+  int vec_stride() const { return 7 * cout; }   // floats from a group's mean to the next group's
 };
 
 struct Blk {
@@ -102,6 +107,7 @@ struct ddg_module {
   hipEvent_t ev_fwd[2] = {nullptr, nullptr};   // forward(t) done, by parity of t
   hipEvent_t ev_upd = nullptr;                 // last update (or parameter load) done
   int delay = 0, nslots = 1;
+  int groups = 1;                  // forward buffer groups (2: paired forward, see run_forward_pair)
   int out_c = 0, out_h = 0, out_w = 0;
   size_t nparams = 0, in_elems = 0, out_elems = 0, max_act = 0;
   size_t esz = 4;
@@ -255,6 +261,10 @@ ddg_status build_plan(ddg_module* m) {
   size_t off = 0;
   int c = d.in_c, h = d.in_h, w = d.in_w;
   const int N = d.batch;
+  // A module with a delay runs forward(t) and the re-forward of iteration t-K+k in the same
+  // launches (same weights, two minibatches): second group of forward buffers.
+  static const bool no_pair = getenv("DDG_NO_PAIR") && getenv("DDG_NO_PAIR")[0] == '1';
+  m->groups = (d.K - d.k > 0 && !m->two_streams && !no_pair) ? 2 : 1;
   m->in_elems = (size_t)N * h * w * c;
   m->max_act = m->in_elems;
   for (int i = 0; i < d.num_blocks; ++i) {
@@ -300,11 +310,12 @@ ddg_status build_plan(ddg_module* m) {
       DDG_OKAY(dev_alloc(m, &u.wpack_f, ne * m->esz));
       conv_plan(f);
       u.tiled_grid = conv_tiled_grid(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
-      if (u.tiled_grid > f.grid_x) f.grid_x = u.tiled_grid;   // sizes the statistics workspace
+      if (u.tiled_grid > 0) f.grid_x = u.tiled_grid;   // the generic kernel never runs this layer
+      u.fcap = f.grid_x;
       size_t st_e = (size_t)f.grid_x * 2 * u.cout;
       if (st_e > m->ws_stat_elems) m->ws_stat_elems = st_e;
       { void* sp = nullptr;
-        DDG_OKAY(dev_alloc(m, &sp, st_e * sizeof(float)));
+        DDG_OKAY(dev_alloc(m, &sp, m->groups * st_e * sizeof(float)));
         u.fstat = (float*)sp;
         // backward rows come from bn_bwd_reduce (its own grid) or from the tiled input-gradient
         // kernel of the layer above (at most conv_tiled_max_grid() workgroups)
@@ -336,9 +347,9 @@ ddg_status build_plan(ddg_module* m) {
       st_e = (size_t)bg * 2 * u.cout;
       if (st_e > m->ws_stat_elems) m->ws_stat_elems = st_e;
       // saved tensors and per-channel vectors
-      DDG_OKAY(dev_alloc(m, &u.z, u.out_elems() * m->esz));
+      DDG_OKAY(dev_alloc(m, &u.z, m->groups * u.out_elems() * m->esz));
       void* pc = nullptr;
-      DDG_OKAY(dev_alloc(m, &pc, (size_t)7 * u.cout * sizeof(float)));
+      DDG_OKAY(dev_alloc(m, &pc, (size_t)7 * m->groups * u.cout * sizeof(float)));
       u.mean = (float*)pc; u.invstd = u.mean + u.cout; u.scale = u.invstd + u.cout;
       u.shift = u.scale + u.cout; u.coef = u.shift + u.cout;
     }
@@ -346,11 +357,11 @@ ddg_status build_plan(ddg_module* m) {
       // the activation between two units is materialised only if the consumer cannot derive
       // it from the producer's conv output while loading
       void* a = nullptr;
-      if (b.u[ui + 1].tiled_grid == 0) DDG_OKAY(dev_alloc(m, &a, b.u[ui].out_elems() * m->esz));
+      if (b.u[ui + 1].tiled_grid == 0) DDG_OKAY(dev_alloc(m, &a, m->groups * b.u[ui].out_elems() * m->esz));
       b.act.push_back(a);
     }
     b.y_elems = b.u[b.nmain - 1].out_elems();
-    DDG_OKAY(dev_alloc(m, &b.y, b.y_elems * m->esz));
+    DDG_OKAY(dev_alloc(m, &b.y, m->groups * b.y_elems * m->esz));
     c = bd.cout; h = out_dim(h, bd.stride); w = out_dim(w, bd.stride);
     m->blocks.push_back(b);
   }
@@ -428,66 +439,159 @@ ddg_status pack_all(ddg_module* m) {
 double conv_flops(const Unit& u) { return 2.0 * u.N * u.P * u.Q * (double)u.cout * u.cin * u.R * u.R; }
 double wbytes(const ddg_module* m, const Unit& u) { return (double)u.cout * u.cin * u.R * u.R * m->esz; }
 
-// The forward statistics of u as partial rows for a consuming kernel.
-BnRows fwd_rows(ddg_module* m, Unit& u) {
+// Pointer to group g of a forward buffer whose groups are `bytes` apart.
+static inline const void* grp(const void* p, size_t bytes, int g) { return p ? (const char*)p + (size_t)g * bytes : nullptr; }
+static inline void* grp(void* p, size_t bytes, int g) { return p ? (char*)p + (size_t)g * bytes : nullptr; }
+
+// The forward statistics of u (group g) as partial rows for a consuming kernel.
+BnRows fwd_rows(ddg_module* m, Unit& u, int g = 0) {
   BnRows r{};
-  r.partial = u.fstat; r.rows = u.frows;
+  r.partial = u.fstat + (size_t)g * u.fcap * 2 * u.cout; r.rows = u.frows;
   r.gamma = m->theta + u.og; r.beta = m->theta + u.ob;
   r.count = (float)((size_t)u.N * u.P * u.Q); r.eps = m->d.bn_eps;
-  r.mean = u.mean; r.invstd = u.invstd; r.scale = u.scale; r.shift = u.shift;
+  const int vo = g * u.vec_stride();
+  r.mean = u.mean + vo; r.invstd = u.invstd + vo; r.scale = u.scale + vo; r.shift = u.shift + vo;
   return r;
 }
 
-// conv of one unit: in -> u.z plus partial rows of its batch statistics. For cout <= 64 the
-// consumer of the BN output derives mean/invstd/scale/shift from the rows (and stores them);
-// wider layers get a finalise launch here. `src`, if given, is the unit whose BN + ReLU
+// conv of one unit: in -> u.z plus partial rows of its batch statistics. For 16/32/64 channels
+// the consumer of the BN output derives mean/invstd/scale/shift from the rows (and stores
+// them); wider layers get a finalise launch here. `src`, if given, is the unit whose BN + ReLU
 // produces this conv's input from `in` while loading (LDS-tiled kernel only). With `res` the
 // input is the output of the residual block before, relu(bn(in) + res), which the kernel also
 // stores to y_store: that block's separate normalise-add-ReLU pass is absorbed.
+// Groups: the launch covers G minibatches starting with group g (G = 2 needs g = 0 and the
+// tiled kernel); in, res and y_store point at group g, whose successors follow contiguously.
 ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const void* res = nullptr,
-                        void* y_store = nullptr) {
+                        void* y_store = nullptr, int G = 1, int g = 0) {
   if (res && !(u.tiled_grid > 0 && src)) return fail(DDG_ERR_STATE, "internal: residual input needs the tiled kernel");
+  if (G > 1 && !(u.tiled_grid > 0 && g == 0 && G <= m->groups)) return fail(DDG_ERR_STATE, "internal: grouped launch needs the tiled kernel");
+  void* z = grp(u.z, u.out_elems() * m->esz, g);
+  float* fstat = u.fstat + (size_t)g * u.fcap * 2 * u.cout;
+  const int vo = g * u.vec_stride();
   if (u.tiled_grid > 0) {
     u.frows = u.tiled_grid;
     ConvStat st{};
-    st.mode = 1; st.partial = u.fstat;
+    st.mode = 1; st.partial = fstat;
     BnRows ir{};
     const bool from_rows = src && src->small_c();
-    if (from_rows) ir = fwd_rows(m, *src);
+    if (from_rows) ir = fwd_rows(m, *src, g);
+    const int svo = src ? g * src->vec_stride() : 0;
     Launch L(m, PK_CONV_FPROP + u.tiled_instance(),
-             ((res ? 3.0 : 1.0) * u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
-    DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? src->scale : nullptr, (src && !from_rows) ? src->shift : nullptr,
-                              from_rows ? &ir : nullptr, u.wpack_f, u.z, st, nullptr, nullptr, u.N, u.H, u.W,
-                              u.cin, u.tiled_grid, m->stream, res, y_store));
+             G * (((res ? 3.0 : 1.0) * u.in_elems() + u.out_elems()) * (double)m->esz) + wbytes(m, u), G * conv_flops(u));
+    DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? src->scale + svo : nullptr, (src && !from_rows) ? src->shift + svo : nullptr,
+                              from_rows ? &ir : nullptr, u.wpack_f, z, st, nullptr, nullptr, G * u.N, u.H, u.W,
+                              u.cin, G * u.tiled_grid, m->stream, res, y_store, G, src ? src->vec_stride() : 0));
   } else {
     if (src) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
     ConvArgs a = u.fprop;
     conv_plan(a);
     u.frows = a.grid_x;
-    a.in = in; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = u.fstat; a.add_g = nullptr; a.add_mask = nullptr;
+    a.in = in; a.wpack = u.wpack_f; a.out = z; a.stat_partial = fstat; a.add_g = nullptr; a.add_mask = nullptr;
     Launch L(m, PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
     DDG_TRY(conv_launch(a, m->stream));
   }
   if (!u.small_c()) {
     Launch L(m, PK_BN_FINALIZE);
-    DDG_TRY(bn_finalize_launch(u.fstat, u.frows, u.cout, m->theta + u.og, m->theta + u.ob,
-                               (float)((size_t)u.N * u.P * u.Q), m->d.bn_eps, u.mean, u.invstd, u.scale,
-                               u.shift, m->stream));
+    DDG_TRY(bn_finalize_launch(fstat, u.frows, u.cout, m->theta + u.og, m->theta + u.ob,
+                               (float)((size_t)u.N * u.P * u.Q), m->d.bn_eps, u.mean + vo, u.invstd + vo, u.scale + vo,
+                               u.shift + vo, m->stream));
   }
   return DDG_OK;
 }
 
-// y = relu(bn(u.z) [+ shortcut]); the shortcut is `res` itself or, with ru, bn(ru->z) of a
-// projection unit.
-ddg_status apply_bn(ddg_module* m, Unit& u, const void* res, Unit* ru, void* y) {
+// y = relu(bn(u.z) [+ shortcut]) for group g; the shortcut is `res` itself or, with ru, bn(ru->z)
+// of a projection unit. res and y point at group g.
+ddg_status apply_bn(ddg_module* m, Unit& u, const void* res, Unit* ru, void* y, int g = 0) {
   BnRows zr{}, rr{};
   const bool zrows = u.small_c(), rrows = ru && ru->small_c();
-  if (zrows) zr = fwd_rows(m, u);
-  if (rrows) rr = fwd_rows(m, *ru);
+  if (zrows) zr = fwd_rows(m, u, g);
+  if (rrows) rr = fwd_rows(m, *ru, g);
+  const int vo = g * u.vec_stride(), rvo = ru ? g * ru->vec_stride() : 0;
   Launch L(m, PK_BN_APPLY, ((res || ru) ? 3.0 : 2.0) * u.out_elems() * m->esz);
-  DDG_TRY(bn_apply_launch(u.z, u.scale, u.shift, zrows ? &zr : nullptr, ru ? ru->z : res,
-                          ru ? ru->scale : nullptr, ru ? ru->shift : nullptr, rrows ? &rr : nullptr, y,
-                          u.out_elems(), u.cout, 1, m->d.compute, m->stream));
+  DDG_TRY(bn_apply_launch(grp(u.z, u.out_elems() * m->esz, g), u.scale + vo, u.shift + vo, zrows ? &zr : nullptr,
+                          ru ? grp(ru->z, ru->out_elems() * m->esz, g) : res, ru ? ru->scale + rvo : nullptr,
+                          ru ? ru->shift + rvo : nullptr, rrows ? &rr : nullptr, y, u.out_elems(), u.cout, 1,
+                          m->d.compute, m->stream));
+  return DDG_OK;
+}
+
+// One block, one group, nothing deferred: x -> y.
+ddg_status block_forward(ddg_module* m, Blk& b, const void* x, void* y, int g) {
+  const void* cur = x;
+  Unit* src = nullptr;   // pending relu(bn(.)) of `cur`
+  for (int i = 0; i < b.nmain; ++i) {
+    Unit& u = b.u[i];
+    DDG_OKAY(unit_forward(m, u, cur, src, nullptr, nullptr, 1, g));
+    src = nullptr;
+    if (i + 1 < b.nmain) {
+      if (b.act[i]) {
+        void* act = grp(b.act[i], u.out_elems() * m->esz, g);
+        DDG_OKAY(apply_bn(m, u, nullptr, nullptr, act, g));
+        cur = act;
+      } else {
+        cur = grp(u.z, u.out_elems() * m->esz, g); src = &u;   // the next conv applies BN + ReLU while loading
+      }
+    }
+  }
+  Unit& ul = b.u[b.nmain - 1];
+  if (b.kind == DDG_BLOCK_STEM) return apply_bn(m, ul, nullptr, nullptr, y, g);
+  if (b.proj) {
+    Unit& up = b.u[b.nmain];
+    DDG_OKAY(unit_forward(m, up, x, nullptr, nullptr, nullptr, 1, g));
+    return apply_bn(m, ul, nullptr, &up, y, g);
+  }
+  return apply_bn(m, ul, x, nullptr, y, g);
+}
+
+// An identity block of the LDS-tiled shapes, whose convs can take two groups in one launch and
+// whose first conv can absorb the normalise-add-ReLU of the block before.
+static bool tiled_identity_block(const Blk& b) {
+  return b.kind == DDG_BLOCK_BASIC && !b.proj && b.nmain == 2 && b.u[0].tiled_grid > 0 && b.u[1].tiled_grid > 0 &&
+         b.u[0].cin == b.u[0].cout;
+}
+
+// Paired forward: the stored minibatch in0 goes through group 0 (the tape the backward pass
+// reads), the current minibatch in1 through group 1 (only its last block output, out1, is
+// kept). Both use the same weights, so wherever a block is of the tiled identity kind and its
+// input lies in the module's own two-group buffers, one launch serves both minibatches (each
+// with its own batch statistics); other blocks run once per group.
+ddg_status run_forward_pair(ddg_module* m, std::vector<Blk>& blocks, const void* in0, const void* in1, void* out1) {
+  const int nres = (int)blocks.size() - (m->d.num_classes > 0 ? 1 : 0);
+  static const bool no_defer = getenv("DDG_NO_DEFER") && getenv("DDG_NO_DEFER")[0] == '1';
+  const void* x0 = in0; const void* x1 = in1;
+  struct { Unit* u = nullptr; const void* res = nullptr; void* y = nullptr; } pend;   // group-0 pointers
+  for (int bi = 0; bi < nres; ++bi) {
+    Blk& b = blocks[bi];
+    const bool last = bi == nres - 1;
+    void* y0 = b.y;
+    void* y1 = last ? out1 : grp(b.y, b.y_elems * m->esz, 1);
+    // both groups' inputs are contiguous from the second block on
+    const bool both = bi >= 1 && tiled_identity_block(b);
+    if (!both) {
+      if (pend.u) return fail(DDG_ERR_STATE, "internal: deferred block output without a consumer");
+      DDG_OKAY(block_forward(m, b, x0, y0, 0));
+      DDG_OKAY(block_forward(m, b, x1, y1, 1));
+    } else {
+      Unit& u0 = b.u[0]; Unit& u1 = b.u[1];
+      if (pend.u) {
+        DDG_OKAY(unit_forward(m, u0, pend.u->z, pend.u, pend.res, pend.y, 2, 0));
+        x0 = pend.y; x1 = grp(pend.y, b.y_elems * m->esz, 1);   // materialised by that launch (same shape as this block's)
+        pend.u = nullptr;
+      } else {
+        DDG_OKAY(unit_forward(m, u0, x0, nullptr, nullptr, nullptr, 2, 0));
+      }
+      DDG_OKAY(unit_forward(m, u1, u0.z, &u0, nullptr, nullptr, 2, 0));
+      const bool defer = !no_defer && !last && bi + 1 < nres && tiled_identity_block(blocks[bi + 1]) &&
+                         blocks[bi + 1].u[0].cin == u1.cout && blocks[bi + 1].u[0].H == u1.P && blocks[bi + 1].u[0].W == u1.Q;
+      if (defer) { pend.u = &u1; pend.res = x0; pend.y = y0; }
+      else {
+        DDG_OKAY(apply_bn(m, u1, x0, nullptr, y0, 0));
+        DDG_OKAY(apply_bn(m, u1, x1, nullptr, y1, 1));
+      }
+    }
+    x0 = y0; x1 = y1;
+  }
   return DDG_OK;
 }
 
@@ -872,7 +976,9 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   if (((uintptr_t)h_in & 15) || ((uintptr_t)h_out & 15)) return fail(DDG_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
   m->phase = 1;
   if (m->d.dry_run) return DDG_OK;
-  if (m->skip) { m->tape_is_current = (m->delay == 0); return DDG_OK; }
+  // paired: this call also re-forwards the minibatch of iteration t - delay (same weights)
+  const bool paired = m->groups == 2 && t >= m->delay;
+  if (m->skip) { m->tape_is_current = (m->delay == 0) || paired; return DDG_OK; }
   m->stream = m->fstream;
   const bool self_sync = m->two_streams && !m->external_sync;
   // the forward stream needs the weights of update(t-1) and the ring slot that backward(t-1) read
@@ -881,7 +987,10 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   { Launch L(m, PK_COPY, 2.0 * m->in_elems * m->esz); DDG_TRY(copy_launch(h_in, slot, m->in_elems * m->esz, m->stream)); }
   // A module with delay > 0 re-forwards before its backward, so this pass need not keep a
   // tape and writes straight to h_out; the last module keeps the tape for its own backward.
-  if (m->delay > 0) {
+  if (paired) {
+    DDG_OKAY(run_forward_pair(m, m->blocks, m->ring[(t - m->delay) % m->nslots], slot, h_out));
+    m->tape_is_current = true;    // group 0 holds the tape of iteration t - delay
+  } else if (m->delay > 0) {
     DDG_OKAY(run_forward(m, m->two_streams ? m->fblocks : m->blocks, slot, h_out));
     m->tape_is_current = false;
     if (self_sync) DDG_TRY(hipEventRecord(m->ev_fwd[t & 1], m->fstream));

@@ -32,8 +32,15 @@ struct ConvTiledArgs {
   ConvStat st;             // epilogue statistics: partial rows [grid][2][C]
   const bf16_t* add_g;     // optional epilogue term, same layout as out
   const bf16_t* add_mask;  // add_g counts only where add_mask > 0
-  int N, H;
+  int N, H;                // N counts the images of all groups
   int tiles;               // N * H/8
+  // groups > 1: the batch is `groups` independent minibatches laid end to end (batch-norm
+  // statistics are per minibatch). A workgroup works on one group only: workgroups
+  // [g*grid/groups, (g+1)*grid/groups) take group g, write that group's statistics rows
+  // (rows are indexed by workgroup), and use that group's input transform: in_rows.partial and
+  // st.partial advance by rows*2*C per group, the per-channel vectors by vec_stride floats.
+  int groups;
+  int vec_stride;
 };
 
 template <int C, int W>
@@ -78,6 +85,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
   const int l16 = lane & 15, lg = lane >> 4;
   const int pgrp = wave % PG, cb = wave / PG;
   const int tiles_per_img = a.H / TH;
+  // this workgroup's group, its index among the group's workgroups, the group's tile range
+  const int g1 = gridDim.x / a.groups;
+  const int grp = blockIdx.x / g1, bl = blockIdx.x - grp * g1;
+  const int tiles_g = a.tiles / a.groups, t_end = (grp + 1) * tiles_g;
 
   // ---- staging map (the same for every tile): chunk v = tid + i*256 -> halo pixel, 8 channels
   const int my_ch = tid % CH;
@@ -114,8 +125,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
       }
     }
   };
-  int t = blockIdx.x;
-  if (t < a.tiles) issue_loads(t);
+  int t = grp * tiles_g + bl;
+  if (t < t_end) issue_loads(t);
 
   // ---- this wave's weights: KSTEPS fragments of its output-channel block
   uint4 wf[KSTEPS];
@@ -144,9 +155,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
   const bool xform = a.scale != nullptr || a.in_rows.partial != nullptr;
   __shared__ __align__(16) float s_sc[C], s_sh[C];
   if (a.in_rows.partial) {
-    bn_fwd_from_rows<C>(a.in_rows, s_sc, s_sh, blockIdx.x == 0);
+    BnRows r = a.in_rows;
+    r.partial += (size_t)grp * r.rows * 2 * C;
+    const int vo = grp * a.vec_stride;
+    r.mean += vo; r.invstd += vo; r.scale += vo; r.shift += vo;
+    bn_fwd_from_rows<C>(r, s_sc, s_sh, bl == 0);
   } else if (a.scale) {
-    if (tid < C) { s_sc[tid] = a.scale[tid]; s_sh[tid] = a.shift[tid]; }
+    const int vo = grp * a.vec_stride;
+    if (tid < C) { s_sc[tid] = a.scale[vo + tid]; s_sh[tid] = a.shift[vo + tid]; }
     __syncthreads();
   }
   auto write_stage = [&]() {
@@ -203,12 +219,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
   // output element offset of (block 0, this lane) inside a tile; block i adds i*16*C
   const int out_lane = ptl * C + cb * 16 + lg * 4;
 
-  for (; t < a.tiles; t += gridDim.x) {
+  for (; t < t_end; t += g1) {
     __syncthreads();            // the previous tile has been consumed
     write_stage();
     __syncthreads();
-    const int tn = t + gridDim.x;
-    if (tn < a.tiles) issue_loads(tn);   // in flight during the MFMA phase
+    const int tn = t + g1;
+    if (tn < t_end) issue_loads(tn);   // in flight during the MFMA phase
 
     // what the epilogue reads, requested now
     const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
@@ -362,8 +378,11 @@ static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStrea
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
                              const void* wpack, void* out, const ConvStat& st, const void* add_g,
                              const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
-                             const void* res, void* y_out) {
+                             const void* res, void* y_out, int groups, int vec_stride) {
+  if (groups < 1 || N % groups != 0 || grid % groups != 0) return hipErrorInvalidValue;
+  if (groups > 1 && (st.mode != 1 || add_g)) return hipErrorInvalidValue;   // forward only
   ConvTiledArgs a;
+  a.groups = groups; a.vec_stride = vec_stride;
   a.in = (const bf16_t*)in; a.scale = scale; a.shift = shift; a.wpack = (const bf16_t*)wpack;
   a.res = (const bf16_t*)res; a.y_out = (bf16_t*)y_out;
   if (in_rows) a.in_rows = *in_rows; else a.in_rows = BnRows{};
