@@ -21,7 +21,9 @@ struct ddg_pipeline {
   std::vector<ddg_module*> mods;
   std::vector<hipStream_t> streams;     // [k] backward / update stream of module k
   std::vector<hipStream_t> fstreams;    // [k] forward stream (== streams[k] unless the module has its own)
-  std::vector<void*> h;                 // h[k], k = 1..K-1 (index k)
+  std::vector<void*> h;                 // h[k], k = 1..K-1 (index k), for even iterations
+  std::vector<void*> h_odd;             // the same for odd iterations: the producer of iteration t+1
+                                        // need not wait for the consumer of iteration t
   std::vector<void*> mail[2];           // mail[slot][k]: df/dh_k, k = 1..K-1
   std::vector<long> mail_iter[2];       // iteration the slot content belongs to
   std::vector<size_t> h_elems;
@@ -75,6 +77,7 @@ ddg_status ddg_pipeline_destroy(ddg_pipeline* p) {
     for (hipStream_t s : p->streams) (void)hipStreamSynchronize(s);
     for (hipStream_t s : p->fstreams) if (s) (void)hipStreamSynchronize(s);
     for (size_t k = 0; k < p->h.size(); ++k) if (p->h[k]) (void)hipFree(p->h[k]);
+    for (size_t k = 0; k < p->h_odd.size(); ++k) if (p->h_odd[k]) (void)hipFree(p->h_odd[k]);
     for (int sl = 0; sl < 2; ++sl) {
       for (void* q : p->mail[sl]) if (q) (void)hipFree(q);
       for (hipEvent_t e : p->bwd_done[sl]) if (e) (void)hipEventDestroy(e);
@@ -102,6 +105,7 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
   p->mods.assign(K + 1, nullptr);
   p->streams.assign(K + 1, nullptr);
   p->h.assign(K + 1, nullptr);
+  p->h_odd.assign(K + 1, nullptr);
   p->h_elems.assign(K + 1, 0);
   p->dtype.assign(K + 1, 0);
   p->fstreams.assign(K + 1, nullptr);
@@ -139,7 +143,8 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
     for (int k = 1; k <= K; ++k) {
       const size_t bytes = p->h_elems[k] * ddg::dtype_size(p->dtype[k]);
       if (k < K) {
-        if (hipMalloc(&p->h[k], bytes) != hipSuccess || hipMalloc(&p->mail[0][k], bytes) != hipSuccess ||
+        if (hipMalloc(&p->h[k], bytes) != hipSuccess || hipMalloc(&p->h_odd[k], bytes) != hipSuccess ||
+            hipMalloc(&p->mail[0][k], bytes) != hipSuccess ||
             hipMalloc(&p->mail[1][k], bytes) != hipSuccess) { ddg_pipeline_destroy(p); return DDG_ERR_OOM; }
       }
       if (hipEventCreateWithFlags(&p->fwd_done[0][k], hipEventDisableTiming) != hipSuccess ||
@@ -169,7 +174,7 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
   }
   else {
     // dry run: nothing is dereferenced; hand the modules a non-null, aligned placeholder
-    for (int k = 1; k < K; ++k) { p->h[k] = (void*)4096; p->mail[0][k] = (void*)4096; p->mail[1][k] = (void*)4096; }
+    for (int k = 1; k < K; ++k) { p->h[k] = (void*)4096; p->h_odd[k] = (void*)4096; p->mail[0][k] = (void*)4096; p->mail[1][k] = (void*)4096; }
   }
   *out = p;
   return DDG_OK;
@@ -230,14 +235,16 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
     hipStream_t fs = p->dry ? nullptr : p->fstreams[k];
     if (!p->dry) {
       if (k > 1) DDG_P(hipStreamWaitEvent(fs, p->fwd_done[cur][k - 1], 0));
-      // h[k] is still being read by module k+1's forward of the previous iteration
-      if (k < K && t > 0) DDG_P(hipStreamWaitEvent(fs, p->fwd_done[prev][k + 1], 0));
+      // this iteration's h[k] buffer was last read by module k+1's forward two iterations ago
+      // (the event of this parity still carries that record: module k+1 re-records it later)
+      if (k < K && t > 1) DDG_P(hipStreamWaitEvent(fs, p->fwd_done[cur][k + 1], 0));
       // a forward stream of its own: the weights of update(t-1), and the ring slot that
       // backward(t-1) read, come from the module's other stream
       if (fs != p->streams[k] && t > 0) DDG_P(hipStreamWaitEvent(fs, p->bwd_done[prev][k], 0));
     }
     ddg_status st = run(k, fs, p->gfwd[k], [&]() {
-      return ddg_forward(p->mods[k], t, k == 1 ? x_in : p->h[k - 1], k < K ? p->h[k] : nullptr); });
+      std::vector<void*>& hb = cur ? p->h_odd : p->h;
+      return ddg_forward(p->mods[k], t, k == 1 ? x_in : hb[k - 1], k < K ? hb[k] : nullptr); });
     if (st != DDG_OK) return st;
     if (!p->dry) DDG_P(hipEventRecord(p->fwd_done[cur][k], fs));
   }
@@ -296,7 +303,8 @@ static ddg_status fetch_f32(ddg_pipeline* p, const void* dev, size_t elems, int 
 ddg_status ddg_pipeline_get_h(ddg_pipeline* p, int k, float* host_dst) {
   if (!p || !host_dst || k < 1 || k >= p->K) return DDG_ERR_INVALID_ARG;
   if (p->dry) return DDG_OK;
-  return fetch_f32(p, p->h[k], p->h_elems[k], p->dtype[k], host_dst);
+  // the buffer written during the last completed iteration
+  return fetch_f32(p, ((p->t - 1) & 1) ? p->h_odd[k] : p->h[k], p->h_elems[k], p->dtype[k], host_dst);
 }
 
 ddg_status ddg_pipeline_get_delta(ddg_pipeline* p, int k, float* host_dst, long* iteration) {
