@@ -90,7 +90,7 @@ SMOOTH_KINDS = ("loss", "h", "params", "velocity")
 
 
 def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_forced=True,
-                        loose=0.25, deriv_tol=None, say=None):
+                        loose=0.25, deriv_tol=None, say=None, forward_streams=False):
     """Run `steps` DDG iterations on the HIP pipeline and on the float64 oracle with the same
     seeded inputs and compare per tensor (relative L2 error).
 
@@ -111,7 +111,7 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
     """
     K = wl.K
     st = [torch.cuda.Stream() for _ in range(K)] if streams else None
-    fst = [torch.cuda.Stream() for _ in range(K)] if streams else None   # forward streams of their own
+    fst = [torch.cuda.Stream() for _ in range(K)] if (streams and forward_streams) else None
     pipe = ddg.Pipeline(descs_for(wl, fstreams=[s.cuda_stream for s in fst] if fst else None),
                         [s.cuda_stream for s in st] if st else None)
     mods = {k: pipe.module(k) for k in range(1, K + 1)}

@@ -56,9 +56,11 @@ def test_projection_stride2_ragged_sizes(H, dtype):
     assert not report, "\n".join(report)
 
 
+@pytest.mark.parametrize("forward_streams", [False, True], ids=["k_streams", "forward_streams"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_k4_schedule(H, dtype):
-    """K=4: delays 3,2,1,0; all mailboxes and rings in use."""
+def test_k4_schedule(H, dtype, forward_streams):
+    """K=4: delays 3,2,1,0; all mailboxes and rings in use. With one stream per module the
+    forward pass is paired with the re-forward; with a forward stream per module it is not."""
     wl = custom_cifar(2, [2, 4, 6], batch=8, num_classes=10, hw=16, dtype=dtype, name="k4")
     wl.lr = 0.05
     _say(f"case k4 {dtype} steps=14")
@@ -67,7 +69,7 @@ def test_k4_schedule(H, dtype):
     # forward quantities stay within 2e-2, gradient-like ones are held to 0.2 (see harness).
     report, stats = H.run_pipeline_parity(wl, 14, TOL[dtype], say=_say,
                                           deriv_tol=0.2 if dtype == "bf16" else None,
-                                          loose=0.6 if dtype == "bf16" else 0.25)
+                                          loose=0.6 if dtype == "bf16" else 0.25, forward_streams=forward_streams)
     assert not report, "\n".join(report)
 
 
