@@ -373,6 +373,8 @@ struct Module {
   bool has_head = false;
   std::vector<Block<T>> blocks;
   std::vector<T> theta, vel, grad;
+  std::vector<T> mom2;             // Adam-DDG: second moment (vel holds the first moment)
+  long nupd = 0;                   // Adam-DDG: updates executed so far
   bool has_grad = false;
   struct Entry { std::vector<T> u; std::vector<T> theta; long t; };
   std::deque<Entry> fifo;          // module inputs waiting for their delayed gradient
@@ -389,6 +391,8 @@ template <class T>
 struct Net {
   int K = 1, k_first = 1;
   T momentum = T(0), wd = T(0), eps = T(1e-5);
+  int adam = 0;                    // 0: momentum SGD (Algorithm 1), 1: Adam (Algorithm 2)
+  T beta1 = T(0.9), beta2 = T(0.999), adam_eps = T(1e-8);
   int stale_jacobian = 0;
   int store_bf16 = 0;
   long t = 0;
@@ -436,7 +440,7 @@ void build_module(Module<T>& m, const int* desc, int nblocks) {
     m.blocks.push_back(b);
   }
   m.out_c = c; m.out_h = h; m.out_w = w;
-  m.theta.assign(off, T(0)); m.vel.assign(off, T(0)); m.grad.assign(off, T(0));
+  m.theta.assign(off, T(0)); m.vel.assign(off, T(0)); m.grad.assign(off, T(0)); m.mom2.assign(off, T(0));
 }
 
 // Forward of one module (Eq. 3 for every layer of G(k)), taping intermediates.
@@ -556,10 +560,32 @@ int ddg_backward_delayed(Net<T>& net, int k, long t, const T* delta_in, const in
   return 1;
 }
 
+// Adam with delayed gradients on module k (Algorithm 2), steps in the paper's order: first
+// moment, second moment, both bias corrections, weight update. The exponent of the bias
+// corrections is the number of updates this module has executed (its warm-up iterations
+// execute none, so its moments are untouched until then). wd adds wd*w to the gradient.
+template <class T>
+void ddg_update_adam(Net<T>& net, int k, T lr) {
+  auto& m = net.mod(k);
+  if (!m.has_grad) return;
+  m.nupd += 1;
+  const T b1 = net.beta1, b2 = net.beta2;
+  const T c1 = T(1) - std::pow(b1, (T)m.nupd), c2 = T(1) - std::pow(b2, (T)m.nupd);
+  for (size_t i = 0; i < m.theta.size(); ++i) {
+    const T g = m.grad[i] + net.wd * m.theta[i];
+    m.vel[i] = b1 * m.vel[i] + (T(1) - b1) * g;
+    m.mom2[i] = b2 * m.mom2[i] + (T(1) - b2) * g * g;
+    const T mhat = m.vel[i] / c1;
+    const T vhat = m.mom2[i] / c2;
+    m.theta[i] = m.theta[i] - lr * mhat / (std::sqrt(vhat) + net.adam_eps);
+  }
+}
+
 // Momentum SGD on module k: v <- mu*v + (g + wd*w); w <- w - lr*v. Skipped while the
-// module has no gradient yet.
+// module has no gradient yet. (With net.adam set, the Adam update above instead.)
 template <class T>
 void ddg_update(Net<T>& net, int k, T lr) {
+  if (net.adam) { ddg_update_adam(net, k, lr); return; }
   auto& m = net.mod(k);
   if (!m.has_grad) return;
   for (size_t i = 0; i < m.theta.size(); ++i) {
@@ -722,6 +748,14 @@ Net<T>* net_create(int K, int k_first, int nmods, const int* nblocks, const int*
                                  T* delta_out, T* loss_out) {                                    \
     return ddg_backward_delayed<T>(*(Net<T>*)p, k, t, delta_in, labels, delta_out, loss_out); }  \
   void orc_update_##SFX(void* p, int k, double lr) { ddg_update<T>(*(Net<T>*)p, k, T(lr)); }     \
+  void orc_set_adam_##SFX(void* p, int on, double b1, double b2, double eps) {                    \
+    auto& n = *(Net<T>*)p; n.adam = on; n.beta1 = T(b1); n.beta2 = T(b2); n.adam_eps = T(eps); }  \
+  void orc_set_moment2_##SFX(void* p, int k, const T* v) {                                       \
+    auto& m = ((Net<T>*)p)->mod(k); std::copy(v, v + m.mom2.size(), m.mom2.begin()); }           \
+  void orc_get_moment2_##SFX(void* p, int k, T* v) {                                             \
+    auto& m = ((Net<T>*)p)->mod(k); std::copy(m.mom2.begin(), m.mom2.end(), v); }                \
+  long orc_get_updates_##SFX(void* p, int k) { return ((Net<T>*)p)->mod(k).nupd; }               \
+  void orc_set_updates_##SFX(void* p, int k, long n) { ((Net<T>*)p)->mod(k).nupd = n; }          \
   double orc_ddg_step_##SFX(void* p, const T* x, const int* labels, double lr) {                 \
     return (double)ddg_step<T>(*(Net<T>*)p, x, labels, T(lr)); }                                 \
   double orc_bp_step_##SFX(void* p, const T* x, const int* labels, double lr, int do_update) {   \

@@ -34,7 +34,7 @@ def lib():
         _lib = C.CDLL(build())
         for sfx in ("f64", "f32"):
             getattr(_lib, f"orc_create_{sfx}").restype = C.c_void_p
-            for n in ("param_count", "in_size", "out_size", "get_delta", "fifo_depth", "time"):
+            for n in ("param_count", "in_size", "out_size", "get_delta", "fifo_depth", "time", "get_updates"):
                 getattr(_lib, f"orc_{n}_{sfx}").restype = C.c_long
             for n in ("head", "ddg_step", "bp_step"):
                 getattr(_lib, f"orc_{n}_{sfx}").restype = C.c_double
@@ -264,6 +264,24 @@ class OracleNet:
 
     def update(self, k, lr):
         self.ty.fn("update")(self._h, k, C.c_double(lr))
+
+    # Adam with delayed gradients (Algorithm 2) instead of momentum SGD
+    def set_adam(self, on=True, beta1=0.9, beta2=0.999, eps=1e-8):
+        self.ty.fn("set_adam")(self._h, int(on), C.c_double(beta1), C.c_double(beta2), C.c_double(eps))
+
+    def get_moment2(self, k):
+        return self._get("get_moment2", k)[0]
+
+    def set_moment2(self, k, v):
+        v = self.ty.arr(v)
+        assert v.size == self.param_count(k)
+        self.ty.fn("set_moment2")(self._h, k, _p(v))
+
+    def get_updates(self, k) -> int:
+        return int(self.ty.fn("get_updates")(self._h, k))
+
+    def set_updates(self, k, n):
+        self.ty.fn("set_updates")(self._h, k, C.c_long(n))
 
     # drivers
     def ddg_step(self, x, labels, lr):
