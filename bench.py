@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--cpu-sample-batch", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
+                    help="momentum SGD (Algorithm 1, the headline configuration) or Adam (Algorithm 2, "
+                         "beta1 0.9, beta2 0.999, eps 1e-8)")
     ap.add_argument("--serial", action="store_true", help="all modules on one stream")
     ap.add_argument("--forward-streams", action="store_true",
                     help="give each module's forward pass a stream of its own (2K-1 streams; "
@@ -116,6 +119,9 @@ def main():
     if wl.single_module:
         raise SystemExit("bench.py times full pipelines; single-module workloads are parity cases")
     pipe, streams = build_pipeline(wl, args.serial, args.forward_streams)
+    if args.optimizer == "adam":
+        import paper_1804_10574_amd as ddg
+        pipe.set_optimizer(ddg.DDG_OPT_ADAM, 0.9, 0.999, 1e-8)
     tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     # a few distinct minibatches, resident in HBM before the timed region
     nbuf = 4
@@ -148,7 +154,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "network": wl.notes, "K": wl.K, "global_batch": wl.batch,
                    "image": "3x32x32", "classes": wl.num_classes, "streams": 1 if args.serial else (2 * wl.K - 1 if args.forward_streams else wl.K),
-                   "parallelism": "K modules as HIP streams on one GPU"},
+                   "optimizer": args.optimizer, "parallelism": "K modules as HIP streams on one GPU"},
         "final_loss": final_loss,
     }
 

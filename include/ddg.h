@@ -141,6 +141,23 @@ ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, con
  * (s < 0). Must follow ddg_backward_delayed(t). */
 ddg_status ddg_update(ddg_module* m, long t, float lr);
 
+/* Algorithm 2 (Adam with delayed gradients) in place of momentum SGD: with kind = DDG_OPT_ADAM,
+ * ddg_update applies, to the delayed gradient g (plus wd*w),
+ *   m <- b1*m + (1-b1)*g;  v <- b2*v + (1-b2)*g^2;
+ *   w <- w - lr * (m/(1-b1^n)) / (sqrt(v/(1-b2^n)) + eps),
+ * where n counts the updates this module has executed (its warm-up iterations execute none).
+ * The first moment lives in the velocity buffer (ddg_set_velocity / ddg_get_velocity), the
+ * second in a buffer of its own; both start at zero, n at 0. Switching the kind keeps the
+ * buffers as they are. Paper's constants: b1 = 0.9, b2 = 0.999, eps = 1e-8. */
+enum { DDG_OPT_SGD = 0, DDG_OPT_ADAM = 1 };
+ddg_status ddg_set_optimizer(ddg_module* m, int kind, float beta1, float beta2, float eps);
+/* Second-moment buffer in / out (fp32, ddg_param_count values; same conventions as the velocity
+ * calls) and the executed-update count n (resuming a run). */
+ddg_status ddg_set_moment2(ddg_module* m, const float* src, int is_device);
+ddg_status ddg_get_moment2(ddg_module* m, float* host_dst);
+ddg_status ddg_set_update_count(ddg_module* m, long n);
+long ddg_get_update_count(const ddg_module* m);
+
 /* Wait for the module's stream. */
 ddg_status ddg_module_sync(ddg_module* m);
 
@@ -165,6 +182,8 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
  * once every module computes a gradient (iteration >= K); on = 0 enqueues every kernel
  * individually instead (same results). Also off when the environment has DDG_NO_GRAPH=1. */
 ddg_status ddg_pipeline_set_graphs(ddg_pipeline* p, int on);
+/* ddg_set_optimizer on every module of the pipeline. */
+ddg_status ddg_pipeline_set_optimizer(ddg_pipeline* p, int kind, float beta1, float beta2, float eps);
 /* Copy module k's latest forward output / the error gradient last delivered to module k
  * (mailbox) to host memory as fp32 NHWC; synchronises. *iteration receives the iteration the
  * mailbox content belongs to (-1: none yet). */

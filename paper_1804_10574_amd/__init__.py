@@ -5,7 +5,7 @@ include/ddg.h; this package only marshals arguments. Importing it never falls
 back to a CPU implementation: if the library is missing, loading raises.
 """
 from .ddg import (DDGError, Module, Pipeline, BlockDesc, ModuleDesc, load_library, library_path,
-                  DDG_F32, DDG_BF16, profile_kinds, version)
+                  DDG_F32, DDG_BF16, DDG_OPT_SGD, DDG_OPT_ADAM, profile_kinds, version)
 
 __all__ = ["DDGError", "Module", "Pipeline", "BlockDesc", "ModuleDesc", "load_library",
-           "library_path", "DDG_F32", "DDG_BF16", "profile_kinds", "version"]
+           "library_path", "DDG_F32", "DDG_BF16", "DDG_OPT_SGD", "DDG_OPT_ADAM", "profile_kinds", "version"]

@@ -184,6 +184,13 @@ hipError_t head_launch(const HeadArgs& a, hipStream_t s);
 hipError_t sgd_launch(float* w, float* v, const float* g, size_t n, float lr, const float* lr_dev,
                       float mu, float wd, hipStream_t s);
 hipError_t set_scalar_launch(float* dst, float v, hipStream_t s);
+// Adam (Algorithm 2). pw[0], pw[1] hold beta1^n, beta2^n in device memory: adam_advance_launch
+// multiplies them by beta1, beta2 (one more executed update), adam_launch then applies
+// m <- b1 m + (1-b1) g', v <- b2 v + (1-b2) g'^2, w <- w - lr (m/(1-pw0)) / (sqrt(v/(1-pw1)) + eps)
+// with g' = g + wd*w. Device-resident so that a captured graph replays correctly.
+hipError_t adam_advance_launch(double* pw, float b1, float b2, hipStream_t s);
+hipError_t adam_launch(float* w, float* m1, float* m2, const float* g, size_t n, float lr, const float* lr_dev,
+                       float b1, float b2, float eps, float wd, const double* pw, hipStream_t s);
 hipError_t copy_launch(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t to_f32_launch(const void* src, float* dst, size_t elems, int dtype, hipStream_t s);
 

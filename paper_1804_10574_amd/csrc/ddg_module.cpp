@@ -8,6 +8,7 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -36,14 +37,14 @@ enum ProfKind {
   PK_CONV_DGRAD, PK_CONV_DGRAD_T16, PK_CONV_DGRAD_T32, PK_CONV_DGRAD_T64,
   PK_CONV_WGRAD, PK_CONV_WGRAD_T16, PK_CONV_WGRAD_T32, PK_CONV_WGRAD_T64,
   PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
-  PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_COUNT
+  PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_COUNT
 };
 static const char* kProfNames[PK_COUNT] = {
   "conv_fprop.generic", "conv_fprop.tiled_c16_w32", "conv_fprop.tiled_c32_w16", "conv_fprop.tiled_c64_w8",
   "conv_dgrad.generic", "conv_dgrad.tiled_c16_w32", "conv_dgrad.tiled_c32_w16", "conv_dgrad.tiled_c64_w8",
   "conv_wgrad.generic", "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c32_w16", "conv_wgrad.tiled_c64_w8",
   "wgrad_reduce", "bn_finalize", "bn_apply",
-  "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy"};
+  "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam"};
 
 struct Unit {  // convolution + batch normalisation
   int cin = 0, cout = 0, R = 0, stride = 1, pad = 0;
@@ -112,6 +113,12 @@ struct ddg_module {
   size_t nparams = 0, in_elems = 0, out_elems = 0, max_act = 0;
   size_t esz = 4;
   float *theta = nullptr, *vel = nullptr, *grad = nullptr;
+  // optimizer: momentum SGD, or Adam (Algorithm 2) with the first moment in vel
+  int opt = DDG_OPT_SGD;
+  float beta1 = 0.9f, beta2 = 0.999f, adam_eps = 1e-8f;
+  float* mom2 = nullptr;           // Adam: second moment
+  double* adam_pw = nullptr;       // Adam: beta1^n, beta2^n (device)
+  long nupd = 0;                   // Adam: updates executed so far (n)
   std::vector<void*> ring;
   void *Ga = nullptr, *Gb = nullptr, *D1 = nullptr, *D2 = nullptr, *D3 = nullptr;
   float* ws_stat = nullptr; size_t ws_stat_elems = 0;
@@ -375,8 +382,10 @@ ddg_status build_plan(ddg_module* m) {
     hb.pooled = (float*)p; hb.dlogits = hb.pooled + (size_t)N * hb.C; hb.loss_n = hb.dlogits + (size_t)N * d.num_classes;
   }
   void* p = nullptr;
-  DDG_OKAY(dev_alloc(m, &p, 3 * m->nparams * sizeof(float)));
+  DDG_OKAY(dev_alloc(m, &p, 4 * m->nparams * sizeof(float) + 2 * sizeof(double)));
   m->theta = (float*)p; m->vel = m->theta + m->nparams; m->grad = m->vel + m->nparams;
+  m->mom2 = m->grad + m->nparams;
+  m->adam_pw = (double*)((char*)p + ((4 * m->nparams * sizeof(float) + 7) & ~(size_t)7));
   m->delay = d.K - d.k;
   m->nslots = m->delay + 1;
   m->ring.resize(m->nslots, nullptr);
@@ -421,7 +430,11 @@ ddg_status build_plan(ddg_module* m) {
       return fail(DDG_ERR_DEVICE, "copying the layer tables failed");
   }
   if (!d.dry_run) {
-    hipError_t e = hipMemsetAsync(m->theta, 0, 3 * m->nparams * sizeof(float), m->stream);
+    hipError_t e = hipMemsetAsync(m->theta, 0, 4 * m->nparams * sizeof(float), m->stream);
+    if (e == hipSuccess) {
+      const double one[2] = {1.0, 1.0};   // beta^0
+      e = hipMemcpy(m->adam_pw, one, sizeof one, hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) return fail(DDG_ERR_DEVICE, "hipMemsetAsync: %s", hipGetErrorString(e));
   }
   return DDG_OK;
@@ -950,6 +963,47 @@ ddg_status ddg_set_velocity(ddg_module* m, const float* src, int is_device) {
   return DDG_OK;
 }
 
+ddg_status ddg_set_moment2(ddg_module* m, const float* src, int is_device) {
+  DDG_OKAY(check_handle(m));
+  if (!src) return fail(DDG_ERR_INVALID_ARG, "src is null");
+  if (m->d.dry_run) return DDG_OK;
+  m->stream = m->bstream;
+  if (is_device) {
+    Launch L(m, PK_COPY);
+    DDG_TRY(copy_launch(src, m->mom2, m->nparams * sizeof(float), m->stream));
+  } else {
+    DDG_TRY(hipStreamSynchronize(m->bstream));
+    DDG_TRY(hipMemcpy(m->mom2, src, m->nparams * sizeof(float), hipMemcpyHostToDevice));
+  }
+  return DDG_OK;
+}
+
+ddg_status ddg_set_optimizer(ddg_module* m, int kind, float beta1, float beta2, float eps) {
+  DDG_OKAY(check_handle(m));
+  if (kind != DDG_OPT_SGD && kind != DDG_OPT_ADAM) return fail(DDG_ERR_INVALID_ARG, "unknown optimizer kind %d", kind);
+  if (kind == DDG_OPT_ADAM && !(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f && eps >= 0.f))
+    return fail(DDG_ERR_INVALID_ARG, "Adam needs 0 <= beta1, beta2 < 1 and eps >= 0");
+  if (m->phase != 0) return fail(DDG_ERR_STATE, "the optimizer can only change between iterations");
+  const bool betas_changed = kind == DDG_OPT_ADAM && (beta1 != m->beta1 || beta2 != m->beta2);
+  m->opt = kind;
+  if (kind == DDG_OPT_ADAM) { m->beta1 = beta1; m->beta2 = beta2; m->adam_eps = eps; }
+  if (betas_changed) return ddg_set_update_count(m, m->nupd);   // beta^n for the new betas
+  return DDG_OK;
+}
+
+ddg_status ddg_set_update_count(ddg_module* m, long n) {
+  DDG_OKAY(check_handle(m));
+  if (n < 0) return fail(DDG_ERR_INVALID_ARG, "update count must be >= 0");
+  m->nupd = n;
+  if (m->d.dry_run) return DDG_OK;
+  DDG_OKAY(sync_streams(m));
+  const double pw[2] = {std::pow((double)m->beta1, (double)n), std::pow((double)m->beta2, (double)n)};
+  DDG_TRY(hipMemcpy(m->adam_pw, pw, sizeof pw, hipMemcpyHostToDevice));
+  return DDG_OK;
+}
+
+long ddg_get_update_count(const ddg_module* m) { return m ? m->nupd : 0; }
+
 static ddg_status get_vec(ddg_module* m, const float* dev, float* host_dst) {
   DDG_OKAY(check_handle(m));
   if (!host_dst) return fail(DDG_ERR_INVALID_ARG, "host_dst is null");
@@ -960,6 +1014,7 @@ static ddg_status get_vec(ddg_module* m, const float* dev, float* host_dst) {
 }
 ddg_status ddg_get_params(ddg_module* m, float* host_dst) { return get_vec(m, m ? m->theta : nullptr, host_dst); }
 ddg_status ddg_get_velocity(ddg_module* m, float* host_dst) { return get_vec(m, m ? m->vel : nullptr, host_dst); }
+ddg_status ddg_get_moment2(ddg_module* m, float* host_dst) { return get_vec(m, m ? m->mom2 : nullptr, host_dst); }
 ddg_status ddg_get_grad(ddg_module* m, float* host_dst, int* valid) {
   DDG_OKAY(get_vec(m, m ? m->grad : nullptr, host_dst));
   if (valid) *valid = m->has_grad ? 1 : 0;
@@ -1040,13 +1095,21 @@ ddg_status ddg_update(ddg_module* m, long t, float lr) {
   if (m->phase != 2 || t != m->t_next) return fail(DDG_ERR_STATE, "ddg_update(t=%ld) must follow ddg_backward_delayed(t=%ld)", t, m->t_next);
   m->phase = 0;
   m->t_next = t + 1;
+  if (m->has_grad && m->opt == DDG_OPT_ADAM) m->nupd += 1;   // also while a captured graph does the work
   if (!m->has_grad || m->d.dry_run || m->skip) return DDG_OK;
   m->stream = m->bstream;
   const bool self_sync = m->two_streams && !m->external_sync;
   // the forward pass of this iteration must have finished reading the weights
   if (self_sync) DDG_TRY(hipStreamWaitEvent(m->bstream, m->ev_fwd[t & 1], 0));
-  { Launch L(m, PK_SGD, (double)m->nparams * 20.0);
-    DDG_TRY(sgd_launch(m->theta, m->vel, m->grad, m->nparams, lr, m->lr_dev, m->d.momentum, m->d.weight_decay, m->stream)); }
+  if (m->opt == DDG_OPT_ADAM) {
+    { Launch L(m, PK_ADAM); DDG_TRY(adam_advance_launch(m->adam_pw, m->beta1, m->beta2, m->stream)); }
+    Launch L(m, PK_ADAM, (double)m->nparams * 28.0);   // w, m, v read and written, g read
+    DDG_TRY(adam_launch(m->theta, m->vel, m->mom2, m->grad, m->nparams, lr, m->lr_dev, m->beta1, m->beta2,
+                        m->adam_eps, m->d.weight_decay, m->adam_pw, m->stream));
+  } else {
+    Launch L(m, PK_SGD, (double)m->nparams * 20.0);
+    DDG_TRY(sgd_launch(m->theta, m->vel, m->grad, m->nparams, lr, m->lr_dev, m->d.momentum, m->d.weight_decay, m->stream));
+  }
   DDG_OKAY(pack_all(m));
   if (self_sync) DDG_TRY(hipEventRecord(m->ev_upd, m->bstream));
   return DDG_OK;

@@ -188,6 +188,20 @@ ddg_status ddg_pipeline_set_graphs(ddg_pipeline* p, int on) {
   return DDG_OK;
 }
 
+ddg_status ddg_pipeline_set_optimizer(ddg_pipeline* p, int kind, float beta1, float beta2, float eps) {
+  if (!p) return DDG_ERR_INVALID_ARG;
+  for (int k = 1; k <= p->K; ++k) {
+    const ddg_status st = ddg_set_optimizer(p->mods[k], kind, beta1, beta2, eps);
+    if (st != DDG_OK) return st;
+  }
+  // graphs captured with the other update kernel must not be replayed
+  for (int k = 1; k <= p->K; ++k) {
+    for (auto& kv : p->gupd[k]) if (kv.second) (void)hipGraphExecDestroy(kv.second);
+    p->gupd[k].clear();
+  }
+  return DDG_OK;
+}
+
 ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labels, float lr, float* loss_out) {
   if (!p || !x || !labels) return DDG_ERR_INVALID_ARG;
   const int K = p->K;

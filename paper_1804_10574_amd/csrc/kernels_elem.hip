@@ -554,6 +554,37 @@ __global__ void sgd_kernel(float* __restrict__ w, float* __restrict__ v, const f
   }
 }
 
+__global__ void adam_advance_kernel(double* pw, double b1, double b2) { pw[0] *= b1; pw[1] *= b2; }
+
+hipError_t adam_advance_launch(double* pw, float b1, float b2, hipStream_t s) {
+  DDG_LAUNCH(adam_advance_kernel, dim3(1), dim3(1), 0, s, pw, (double)b1, (double)b2);
+  return hipGetLastError();
+}
+
+__global__ void adam_kernel(float* __restrict__ w, float* __restrict__ m1, float* __restrict__ m2,
+                            const float* __restrict__ g, size_t n, float lr, const float* __restrict__ lr_dev,
+                            float b1, float b2, float eps, float wd, const double* __restrict__ pw) {
+  if (lr_dev) lr = *lr_dev;
+  const float c1 = (float)(1.0 - pw[0]), c2 = (float)(1.0 - pw[1]);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    const float wi = w[i];
+    const float gi = g[i] + wd * wi;
+    const float mi = b1 * m1[i] + (1.f - b1) * gi;
+    const float vi = b2 * m2[i] + (1.f - b2) * gi * gi;
+    m1[i] = mi; m2[i] = vi;
+    w[i] = wi - lr * (mi / c1) / (sqrtf(vi / c2) + eps);
+  }
+}
+
+hipError_t adam_launch(float* w, float* m1, float* m2, const float* g, size_t n, float lr, const float* lr_dev,
+                       float b1, float b2, float eps, float wd, const double* pw, hipStream_t s) {
+  int grid = (int)((n + 255) / 256);
+  if (grid > 2048) grid = 2048;
+  if (grid < 1) grid = 1;
+  DDG_LAUNCH(adam_kernel, dim3(grid), dim3(256), 0, s, w, m1, m2, g, n, lr, lr_dev, b1, b2, eps, wd, pw);
+  return hipGetLastError();
+}
+
 __global__ void set_scalar_kernel(float* dst, float v) { *dst = v; }
 
 hipError_t set_scalar_launch(float* dst, float v, hipStream_t s) {

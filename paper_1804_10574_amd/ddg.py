@@ -8,6 +8,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 DDG_F32, DDG_BF16 = 0, 1
+DDG_OPT_SGD, DDG_OPT_ADAM = 0, 1
 _STATUS = {0: "DDG_OK", 1: "DDG_ERR_INVALID_ARG", 2: "DDG_ERR_SHAPE", 3: "DDG_ERR_STATE",
            4: "DDG_ERR_OOM", 5: "DDG_ERR_DEVICE"}
 
@@ -66,6 +67,12 @@ def load_library():
         "ddg_forward": (st, [vp, C.c_long, vp, vp]),
         "ddg_backward_delayed": (st, [vp, C.c_long, vp, vp, vp, vp, C.POINTER(C.c_int)]),
         "ddg_update": (st, [vp, C.c_long, C.c_float]),
+        "ddg_set_optimizer": (st, [vp, C.c_int, C.c_float, C.c_float, C.c_float]),
+        "ddg_set_moment2": (st, [vp, vp, C.c_int]),
+        "ddg_get_moment2": (st, [vp, vp]),
+        "ddg_set_update_count": (st, [vp, C.c_long]),
+        "ddg_get_update_count": (C.c_long, [vp]),
+        "ddg_pipeline_set_optimizer": (st, [vp, C.c_int, C.c_float, C.c_float, C.c_float]),
         "ddg_module_sync": (st, [vp]),
         "ddg_pipeline_create": (st, [C.POINTER(ModuleDesc), C.c_int, C.POINTER(vp), C.POINTER(vp)]),
         "ddg_pipeline_destroy": (st, [vp]),
@@ -94,6 +101,8 @@ def load_library():
 EXPORTS = ["ddg_module_create", "ddg_module_destroy", "ddg_param_count", "ddg_out_shape",
            "ddg_device_bytes", "ddg_set_params", "ddg_set_velocity", "ddg_get_params", "ddg_get_velocity", "ddg_get_grad",
            "ddg_forward", "ddg_backward_delayed", "ddg_update", "ddg_module_sync",
+           "ddg_set_optimizer", "ddg_set_moment2", "ddg_get_moment2", "ddg_set_update_count", "ddg_get_update_count",
+           "ddg_pipeline_set_optimizer",
            "ddg_pipeline_create", "ddg_pipeline_destroy", "ddg_pipeline_module", "ddg_pipeline_step",
            "ddg_pipeline_set_graphs", "ddg_pipeline_get_h", "ddg_pipeline_get_delta", "ddg_pipeline_sync", "ddg_profile_kinds",
            "ddg_profile_kind_name", "ddg_profile_enable", "ddg_profile_read", "ddg_profile_reset",
@@ -180,6 +189,26 @@ class Module:
             src = np.ascontiguousarray(src, np.float32)
             assert src.size == self.param_count()
         _check(self._lib.ddg_set_velocity(self._h, _ptr(src), 1 if is_device else 0))
+
+    def set_optimizer(self, kind, beta1=0.9, beta2=0.999, eps=1e-8):
+        _check(self._lib.ddg_set_optimizer(self._h, kind, beta1, beta2, eps))
+
+    def set_moment2(self, src, is_device=False):
+        if not is_device:
+            src = np.ascontiguousarray(src, np.float32)
+            assert src.size == self.param_count()
+        _check(self._lib.ddg_set_moment2(self._h, _ptr(src), 1 if is_device else 0))
+
+    def get_moment2(self):
+        out, st = self._get(self._lib.ddg_get_moment2)
+        _check(st)
+        return out
+
+    def set_update_count(self, n):
+        _check(self._lib.ddg_set_update_count(self._h, n))
+
+    def get_update_count(self) -> int:
+        return int(self._lib.ddg_get_update_count(self._h))
 
     def _get(self, fn):
         out = np.empty(self.param_count(), np.float32)
@@ -268,6 +297,9 @@ class Pipeline:
 
     def set_graphs(self, on: bool):
         _check(self._lib.ddg_pipeline_set_graphs(self._h, 1 if on else 0))
+
+    def set_optimizer(self, kind, beta1=0.9, beta2=0.999, eps=1e-8):
+        _check(self._lib.ddg_pipeline_set_optimizer(self._h, kind, beta1, beta2, eps))
 
     def sync(self):
         _check(self._lib.ddg_pipeline_sync(self._h))

@@ -90,7 +90,7 @@ SMOOTH_KINDS = ("loss", "h", "params", "velocity")
 
 
 def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_forced=True,
-                        loose=0.25, deriv_tol=None, say=None, forward_streams=False):
+                        loose=0.25, deriv_tol=None, say=None, forward_streams=False, adam=None):
     """Run `steps` DDG iterations on the HIP pipeline and on the float64 oracle with the same
     seeded inputs and compare per tensor (relative L2 error).
 
@@ -117,6 +117,9 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
     mods = {k: pipe.module(k) for k in range(1, K + 1)}
     oracle = orc.OracleNet.from_workload(wl, dtype="f64")
     init_both(wl, mods, oracle, perturb_bn)
+    if adam:   # (beta1, beta2, eps): Algorithm 2 instead of momentum SGD, on both sides
+        oracle.set_adam(True, *adam)
+        pipe.set_optimizer(ddg.DDG_OPT_ADAM, *adam)
     errs = {k: [] for k in ("loss", "h", "params", "velocity", "grad", "delta")}
     report = []
     loss_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
@@ -130,6 +133,9 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
             for m in wl.modules:
                 mods[m.k].set_params(oracle.get_params(m.k).astype(np.float32))
                 mods[m.k].set_velocity(oracle.get_velocity(m.k).astype(np.float32))
+                if adam:
+                    mods[m.k].set_moment2(oracle.get_moment2(m.k).astype(np.float32))
+                    mods[m.k].set_update_count(oracle.get_updates(m.k))
         torch.cuda.synchronize()
         pipe.step(xd, yd, wl.lr, loss_dev)
         pipe.sync()
@@ -143,8 +149,11 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
                 continue
             if g is None:
                 continue
+            if adam and mods[m.k].get_update_count() != oracle.get_updates(m.k):
+                report.append(f"t={t} module {m.k}: update count {mods[m.k].get_update_count()} vs {oracle.get_updates(m.k)}")
+            extra = (("velocity", mods[m.k].get_moment2(), oracle.get_moment2(m.k)),) if adam else ()
             for kind, a, b in (("grad", g, r), ("params", mods[m.k].get_params(), oracle.get_params(m.k)),
-                               ("velocity", mods[m.k].get_velocity(), oracle.get_velocity(m.k))):
+                               ("velocity", mods[m.k].get_velocity(), oracle.get_velocity(m.k))) + extra:
                 for (name, av), (_, bv) in zip(split_params(wl, m, a), split_params(wl, m, b)):
                     if np.linalg.norm(bv) < 1e-9 and np.linalg.norm(av) < 1e-6:
                         continue

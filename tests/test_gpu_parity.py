@@ -262,6 +262,34 @@ def test_single_block_module(H, which, dtype):
     assert not fails, "\n".join(fails)
 
 
+# ---- Adam with delayed gradients (Algorithm 2) ---------------------------------------------
+
+ADAM = (0.9, 0.999, 1e-8)
+
+
+def test_adam_tiny_k2_free_running(H):
+    """Algorithm 2 on the tiny K=2 network, fp32, five iterations without teacher forcing:
+    moments, update counts (warm-up executes none) and weights against the oracle."""
+    wl = wk.get_workload("tiny_k2")
+    wl.lr = 1e-3
+    _say("case adam tiny_k2 steps=5 free-running")
+    report, stats = H.run_pipeline_parity(wl, 5, 1e-4, teacher_forced=False, say=_say, adam=ADAM)
+    assert not report, "\n".join(report)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_adam_k4_schedule(H, dtype):
+    """Algorithm 2 with K=4 (delays 3,2,1,0), 14 iterations, replayed as graphs from iteration K
+    on: the bias-correction state lives on the device and advances with every replay."""
+    wl = custom_cifar(2, [2, 4, 6], batch=8, num_classes=10, hw=16, dtype=dtype, name="k4_adam")
+    wl.lr = 1e-3
+    _say(f"case adam k4 {dtype} steps=14")
+    report, stats = H.run_pipeline_parity(wl, 14, TOL[dtype], say=_say, adam=ADAM,
+                                          deriv_tol=0.2 if dtype == "bf16" else None,
+                                          loose=0.6 if dtype == "bf16" else 0.25)
+    assert not report, "\n".join(report)
+
+
 # ---- the benchmark's network shapes -------------------------------------------------------
 
 def test_cifar_shaped_pipeline_bf16(H):
