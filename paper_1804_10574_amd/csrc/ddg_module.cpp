@@ -228,7 +228,6 @@ ddg_status validate(const ddg_module_desc* d) {
       if (i != d->num_blocks - 1) return fail(DDG_ERR_SHAPE, "the head must be the last block");
       if (d->num_classes < 2) return fail(DDG_ERR_SHAPE, "a head needs num_classes >= 2");
       if (d->k != d->K) return fail(DDG_ERR_SHAPE, "only the last module (k == K) may end in the head");
-      if (d->num_blocks < 2) return fail(DDG_ERR_SHAPE, "a module cannot consist of the head alone");
       continue;
     }
     if (b.stride != 1 && b.stride != 2) return fail(DDG_ERR_SHAPE, "block %d: stride must be 1 or 2", i);
@@ -764,9 +763,11 @@ ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const i
   if (head) {
     Blk& hb = m->blocks.back();
     HeadArgs a{};
-    a.h = m->blocks[nres - 1].y; a.fcw = m->theta + hb.ofcw; a.fcb = m->theta + hb.ofcb; a.labels = labels;
+    // a module that is the head alone (a split point after the last conv layer) reads its
+    // stored input and hands the gradient straight to delta_out
+    a.h = nres > 0 ? m->blocks[nres - 1].y : in; a.fcw = m->theta + hb.ofcw; a.fcb = m->theta + hb.ofcb; a.labels = labels;
     a.pooled = hb.pooled; a.dlogits = hb.dlogits; a.loss_n = hb.loss_n; a.loss_out = loss_out;
-    a.dfcw = m->grad + hb.ofcw; a.dfcb = m->grad + hb.ofcb; a.dh = m->Ga;
+    a.dfcw = m->grad + hb.ofcw; a.dfcb = m->grad + hb.ofcb; a.dh = nres > 0 ? m->Ga : delta_out;
     a.N = m->d.batch; a.HW = hb.HW; a.C = hb.C; a.classes = m->d.num_classes; a.dtype = dt;
     Launch L(m, PK_HEAD);
     DDG_TRY(head_launch(a, m->stream));

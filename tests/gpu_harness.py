@@ -90,7 +90,7 @@ SMOOTH_KINDS = ("loss", "h", "params", "velocity")
 
 
 def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_forced=True,
-                        loose=0.25, deriv_tol=None, say=None, forward_streams=False, adam=None):
+                        loose=0.25, deriv_tol=None, say=None, forward_streams=False, adam=None, lr_of=None):
     """Run `steps` DDG iterations on the HIP pipeline and on the float64 oracle with the same
     seeded inputs and compare per tensor (relative L2 error).
 
@@ -124,6 +124,7 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
     report = []
     loss_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
     for t in range(steps):
+        lr = lr_of(t) if lr_of else wl.lr       # the step-size schedule is the caller's
         x, y = wk.minibatch(wl, t)
         xd = to_dev_nhwc(x, wl)
         yd = torch.from_numpy(y).to("cuda")
@@ -137,9 +138,9 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
                     mods[m.k].set_moment2(oracle.get_moment2(m.k).astype(np.float32))
                     mods[m.k].set_update_count(oracle.get_updates(m.k))
         torch.cuda.synchronize()
-        pipe.step(xd, yd, wl.lr, loss_dev)
+        pipe.step(xd, yd, lr, loss_dev)
         pipe.sync()
-        ref_loss = oracle.ddg_step(x, y, wl.lr)
+        ref_loss = oracle.ddg_step(x, y, lr)
         got_loss = float(loss_dev.cpu()[0])
         errs["loss"].append((abs(got_loss - ref_loss) / max(abs(ref_loss), 1e-12), f"t={t} loss"))
         for m in wl.modules:

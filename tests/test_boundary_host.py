@@ -102,12 +102,19 @@ def test_create_rejects_bad_block_lists():
         ([(S, 3, 0, 24, 1, 0)], {}),                                    # cout not a power of two
         ([(S, 3, 0, 16, 3, 0)], {}),                                    # stride 3
         ([(S, 3, 0, 16, 1, 0), (H, 16, 0, 10, 1, 0)], dict(classes=10)),  # head but k != K
-        ([(H, 16, 0, 10, 1, 0)], dict(k=2, classes=10, in_c=16)),       # head alone
         ([(S, 3, 0, 16, 1, 0)], dict(classes=10)),                      # classes without head
     ]:
         with pytest.raises(ddg.DDGError) as e:
             ddg.Module(mk(blocks, **kw))
         assert e.value.status == 2, (blocks, str(e.value))
+
+
+def test_a_module_may_be_the_head_alone():
+    """A split point after the last conv layer leaves only the classifier in the last module."""
+    H = wk.BLOCK_HEAD
+    m = ddg.Module(make_desc(2, 2, 4, (16, 8, 8), [(H, 16, 0, 10, 1, 0)], 10, 0, 0.9, 0.0, 1e-5, dry_run=True))
+    assert m.param_count() == 16 * 10 + 10
+    m.close()
 
 
 def test_dry_run_pipeline_schedule():

@@ -290,6 +290,64 @@ def test_adam_k4_schedule(H, dtype):
     assert not report, "\n".join(report)
 
 
+# ---- ResNet-8 (Table 2) with the split points of Section 5.1 --------------------------------
+
+@pytest.mark.parametrize("layer", [1, 3, 5, 7])
+def test_resnet8_one_split_point_adam(H, layer):
+    """One split point after layer 1, 3, 5 or 7, Adam with step size 1e-3 (Section 5.1), fp32."""
+    wl = wk.resnet8((layer,), batch=16)
+    _say(f"case resnet8 split after layer {layer}, adam, steps=6")
+    report, stats = H.run_pipeline_parity(wl, 6, 1e-4, say=_say, adam=ADAM)
+    assert not report, "\n".join(report)
+
+
+def test_resnet8_four_split_points_sgd_with_decay_and_schedule(H):
+    """K=5 (split after layers 1, 3, 5, 7), momentum SGD with weight decay 5e-4 and a step size
+    divided by 10 part-way (Section 5.2's recipe): the step size reaches the replayed update
+    graphs through device memory."""
+    wl = wk.resnet8((1, 3, 5, 7), batch=16, weight_decay=5e-4, lr=0.01)
+    _say("case resnet8 K=5 sgd wd=5e-4 lr 0.01 -> 0.001 at t=9, steps=14")
+    report, stats = H.run_pipeline_parity(wl, 14, 1e-4, say=_say, lr_of=lambda t: 0.01 if t < 9 else 0.001)
+    assert not report, "\n".join(report)
+
+
+def test_delayed_gradients_train_like_backpropagation(H):
+    """Shape of the paper's convergence figures on synthetic data: ResNet-8, Adam 1e-3, a fixed
+    set of four minibatches of 64 images revisited for 160 iterations, K = 1 (backpropagation),
+    2, 3 and 5 modules. Every K must bring the training loss far below its start, and the
+    delayed-gradient runs must end close to the K=1 run."""
+    import torch
+    import paper_1804_10574_amd as ddg
+    finals = {}
+    for splits in ((), (3,), (1, 5), (1, 3, 5, 7)):
+        wl = wk.resnet8(splits, batch=64) if splits else custom_cifar(1, [], batch=64, num_classes=10, hw=32, name="resnet8_k1")
+        st = [torch.cuda.Stream() for _ in range(wl.K)]
+        pipe = ddg.Pipeline(H.descs_for(wl), [s.cuda_stream for s in st])
+        for m in wl.modules:
+            pipe.module(m.k).set_params(wk.init_module_params(wl, m, perturb_bn=False).astype(np.float32))
+        pipe.set_optimizer(ddg.DDG_OPT_ADAM, *ADAM)
+        data = []
+        for i in range(4):
+            x, y = wk.minibatch(wl, i)
+            data.append((H.to_dev_nhwc(x, wl), torch.from_numpy(y).to("cuda")))
+        losses = torch.zeros(160, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        for t in range(160):
+            xd, yd = data[t % 4]
+            pipe.step(xd, yd, 1e-3, losses[t:t + 1])
+        pipe.sync()
+        l = losses.cpu().numpy()
+        pipe.close()
+        first = float(l[wl.K - 1:wl.K + 3].mean())      # first losses that are reported
+        last = float(l[-8:].mean())
+        finals[wl.K] = last
+        _say(f"K={wl.K}: loss {first:.3f} -> {last:.3f}")
+        assert np.all(np.isfinite(l))
+        assert last < 0.5 * first, (wl.K, first, last)
+    for K, last in finals.items():
+        assert last < finals[1] + 0.35, finals
+
+
 # ---- the benchmark's network shapes -------------------------------------------------------
 
 def test_cifar_shaped_pipeline_bf16(H):

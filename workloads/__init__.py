@@ -7,7 +7,7 @@ rule) and imports neither the oracle nor the HIP library.
 """
 from .configs import (BLOCK_STEM, BLOCK_BASIC, BLOCK_BOTTLENECK, BLOCK_HEAD,
                       Block, ModuleSpec, Workload, get_workload, WORKLOADS,
-                      block_param_shapes, module_param_count)
+                      block_param_shapes, module_param_count, resnet8)
 from .rng import normal, uniform_int
 from .init import init_module_params, minibatch, synthetic_delta
 
@@ -15,5 +15,5 @@ __all__ = [
     "BLOCK_STEM", "BLOCK_BASIC", "BLOCK_BOTTLENECK", "BLOCK_HEAD", "Block",
     "ModuleSpec", "Workload", "get_workload", "WORKLOADS", "block_param_shapes",
     "module_param_count", "normal", "uniform_int", "init_module_params",
-    "minibatch", "synthetic_delta",
+    "minibatch", "synthetic_delta", "resnet8",
 ]

@@ -196,12 +196,32 @@ def _bottleneck_slice(nblocks: int = 23, batch: int = 32, c: int = 1024, mid: in
                     single_module=2)
 
 
+def resnet8(split_layers=(3,), batch: int = 128, dtype: str = "f32", weight_decay: float = 0.0,
+            lr: float = 1e-3) -> Workload:
+    """ResNet-8 (Table 2: units 1-1-1, channels 16-16-32-64): stem = layer 1, three basic blocks
+    = layers 2-3, 4-5, 6-7, classifier = layer 8. A split point "at layer l" (Section 5.1 uses
+    1, 3, 5, 7, and 2 to 4 of them at once) cuts the network after layer l. Batch 128 and step
+    size 1e-3 are Section 5.1's (Adam); synthetic CIFAR-10-shaped inputs."""
+    for l in split_layers:
+        if l not in (1, 3, 5, 7):
+            raise ValueError("ResNet-8 split points lie after layers 1, 3, 5 or 7")
+    blocks = cifar_resnet_blocks(1, 10)
+    cuts = sorted((l + 1) // 2 for l in split_layers)
+    mods = _split(blocks, cuts, 3, 32, 32)
+    name = "resnet8_k%d_l%s" % (len(cuts) + 1, "".join(str(l) for l in sorted(split_layers)))
+    return Workload(name, len(cuts) + 1, batch, 10, mods, dtype, lr, 0.9, weight_decay, 1e-5, 8,
+                    notes="ResNet-8, split after layer(s) " + ",".join(str(l) for l in sorted(split_layers)))
+
+
 WORKLOADS = {
     "tiny_k2": _tiny,
     "resnet20_k2": _resnet20,
     "resnet56_k3": _resnet56,
     "resnet110_k4": _resnet110,
     "r101_stage3_k4m2": _bottleneck_slice,
+    # Section 5.1's network, one split point in the middle / four split points
+    "resnet8_k2": lambda: resnet8((3,)),
+    "resnet8_k5": lambda: resnet8((1, 3, 5, 7)),
 }
 
 
