@@ -42,7 +42,7 @@ HIP_KERNEL_OF = {
 }
 
 
-def build_pipeline(wl, serial=False, forward_streams=False):
+def build_pipeline(wl, serial=False, forward_streams=False, stale_jacobian=False):
     import torch
     import numpy as np
     import workloads as wk
@@ -58,7 +58,8 @@ def build_pipeline(wl, serial=False, forward_streams=False):
                                wl.num_classes if m.blocks[-1].kind == wk.BLOCK_HEAD else 0,
                                ddg.DDG_BF16 if wl.dtype == "bf16" else ddg.DDG_F32,
                                wl.momentum, wl.weight_decay, wl.bn_eps,
-                               forward_stream=fstreams[m.k - 1].cuda_stream if fstreams else None))
+                               forward_stream=fstreams[m.k - 1].cuda_stream if fstreams else None,
+                               stale_jacobian=stale_jacobian))
     pipe = ddg.Pipeline(descs, None if serial else [s.cuda_stream for s in streams])
     for m in wl.modules:
         pipe.module(m.k).set_params(wk.init_module_params(wl, m).astype(np.float32))
@@ -100,6 +101,9 @@ def main():
     ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
                     help="momentum SGD (Algorithm 1, the headline configuration) or Adam (Algorithm 2, "
                          "beta1 0.9, beta2 0.999, eps 1e-8)")
+    ap.add_argument("--stale-jacobian", action="store_true",
+                    help="Eq. 6-7 read literally (tapes and weight snapshots per ring slot, no re-forward); "
+                         "not the headline configuration")
     ap.add_argument("--serial", action="store_true", help="all modules on one stream")
     ap.add_argument("--forward-streams", action="store_true",
                     help="give each module's forward pass a stream of its own (2K-1 streams; "
@@ -118,7 +122,7 @@ def main():
     wl = wk.get_workload(args.workload)
     if wl.single_module:
         raise SystemExit("bench.py times full pipelines; single-module workloads are parity cases")
-    pipe, streams = build_pipeline(wl, args.serial, args.forward_streams)
+    pipe, streams = build_pipeline(wl, args.serial, args.forward_streams, args.stale_jacobian)
     if args.optimizer == "adam":
         import paper_1804_10574_amd as ddg
         pipe.set_optimizer(ddg.DDG_OPT_ADAM, 0.9, 0.999, 1e-8)
@@ -154,7 +158,9 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "network": wl.notes, "K": wl.K, "global_batch": wl.batch,
                    "image": "3x32x32", "classes": wl.num_classes, "streams": 1 if args.serial else (2 * wl.K - 1 if args.forward_streams else wl.K),
-                   "optimizer": args.optimizer, "parallelism": "K modules as HIP streams on one GPU"},
+                   "optimizer": args.optimizer,
+                   "gradient": "stale Jacobian (Eq. 6-7 as printed)" if args.stale_jacobian else "re-forward with current weights",
+                   "parallelism": "K modules as HIP streams on one GPU"},
         "final_loss": final_loss,
     }
 

@@ -88,6 +88,14 @@ typedef struct {
                                   weights; the update waits for both). 0: everything on `stream` */
   int dry_run;                 /* != 0: no device memory, no launches; only the argument and
                                   state checks run (lets host logic be tested without a GPU) */
+  int stale_jacobian;          /* != 0: Eq. 6-7 read literally. ddg_forward(t) keeps every saved
+                                  activation of iteration t and a snapshot of the weights it used
+                                  (K-k+1 of each), and ddg_backward_delayed(t) back-propagates the
+                                  delayed error gradient through the activations and weights of
+                                  iteration t-K+k: no re-forward, (K-k+1) times the activation
+                                  memory. 0 (default): only the module input is kept and it is
+                                  re-forwarded with the current weights. forward_stream is
+                                  ignored in this mode. */
 } ddg_module_desc;
 
 /* Section 3: create module G(k). Allocates weights, velocity, gradients, the input ring of

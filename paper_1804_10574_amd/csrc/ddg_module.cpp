@@ -51,7 +51,8 @@ struct Unit {  // convolution + batch normalisation
   int N = 0, H = 0, W = 0, P = 0, Q = 0;
   size_t ow = 0, og = 0, ob = 0;
   void* wpack_f = nullptr;
-  void* wpack_d = nullptr;
+  void* wpack_d = nullptr;      // input-gradient operand (stale-Jacobian mode: one per ring slot)
+  size_t wpack_d_bytes = 0;
   void* z = nullptr;
   float* mean = nullptr;   // mean, invstd, scale, shift, coef[3C] in one allocation
   float* invstd = nullptr;
@@ -108,7 +109,13 @@ struct ddg_module {
   hipEvent_t ev_fwd[2] = {nullptr, nullptr};   // forward(t) done, by parity of t
   hipEvent_t ev_upd = nullptr;                 // last update (or parameter load) done
   int delay = 0, nslots = 1;
-  int groups = 1;                  // forward buffer groups (2: paired forward, see run_forward_pair)
+  int groups = 1;                  // forward buffer groups (2: paired forward, see run_forward_pair;
+                                   // K-k+1 in stale-Jacobian mode: one tape per ring slot)
+  bool stale = false;              // Eq. 6-7 literally: tapes and weight snapshots per ring slot
+  float* theta_snap = nullptr;     // stale: [nslots][nparams] weights as of each kept forward
+  const float* theta_bwd = nullptr;   // the weights the backward pass reads (theta, or a snapshot)
+  std::vector<PackDesc*> pack_descs_d;   // stale: per-slot tables of the input-gradient operands
+  int n_pack_d = 0;
   int out_c = 0, out_h = 0, out_w = 0;
   size_t nparams = 0, in_elems = 0, out_elems = 0, max_act = 0;
   size_t esz = 4;
@@ -270,7 +277,8 @@ ddg_status build_plan(ddg_module* m) {
   // A module with a delay runs forward(t) and the re-forward of iteration t-K+k in the same
   // launches (same weights, two minibatches): second group of forward buffers.
   static const bool no_pair = getenv("DDG_NO_PAIR") && getenv("DDG_NO_PAIR")[0] == '1';
-  m->groups = (d.K - d.k > 0 && !m->two_streams && !no_pair) ? 2 : 1;
+  m->stale = d.stale_jacobian != 0 && d.K - d.k > 0;
+  m->groups = m->stale ? (d.K - d.k + 1) : ((d.K - d.k > 0 && !m->two_streams && !no_pair) ? 2 : 1);
   m->in_elems = (size_t)N * h * w * c;
   m->max_act = m->in_elems;
   for (int i = 0; i < d.num_blocks; ++i) {
@@ -318,6 +326,7 @@ ddg_status build_plan(ddg_module* m) {
       u.tiled_grid = conv_tiled_grid(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
       if (u.tiled_grid > 0) f.grid_x = u.tiled_grid;   // the generic kernel never runs this layer
       u.fcap = f.grid_x;
+      u.frows = u.fcap;    // what the forward conv of this layer writes (the same every time)
       size_t st_e = (size_t)f.grid_x * 2 * u.cout;
       if (st_e > m->ws_stat_elems) m->ws_stat_elems = st_e;
       { void* sp = nullptr;
@@ -336,7 +345,8 @@ ddg_status build_plan(ddg_module* m) {
         g.R = u.R; g.stride = u.stride; g.pad = u.pad; g.ntaps = u.R * u.R;
         g.M = N * u.H * u.W; g.dgrad = 1; g.dtype = dt;
         ne = conv_wpack_elems(u.cout, u.cin, u.R, dt, &g.log2cp, &g.ksteps);
-        DDG_OKAY(dev_alloc(m, &u.wpack_d, ne * m->esz));
+        u.wpack_d_bytes = (ne * m->esz + 255) & ~(size_t)255;
+        DDG_OKAY(dev_alloc(m, &u.wpack_d, (m->stale ? (size_t)(d.K - d.k + 1) : 1) * u.wpack_d_bytes));
         conv_plan(g);
       }
       // weight gradient
@@ -397,7 +407,10 @@ ddg_status build_plan(ddg_module* m) {
   DDG_OKAY(dev_alloc(m, &p, m->ws_stat_elems * sizeof(float)));
   m->ws_stat = (float*)p;
   // device tables: one entry per packed operand / per layer
+  // (stale-Jacobian mode: the input-gradient operands are packed per ring slot when a forward
+  // pass is kept, from tables of their own; the main table then holds the forward operands only)
   std::vector<PackDesc> pd;
+  std::vector<std::vector<PackDesc>> pdd(m->stale ? m->nslots : 0);
   std::vector<WredDesc> wd;
   for (Blk& b : m->blocks)
     for (Unit& u : b.u) {
@@ -410,7 +423,11 @@ ddg_status build_plan(ddg_module* m) {
         d.Cout = u.cout; d.Cin = u.cin; d.R = u.R; d.mode = md;
         d.total = (unsigned)conv_wpack_elems(kc, nc, u.R, dt, &d.log2cp, &d.ksteps);
         d.OCB = nc / 16;
-        pd.push_back(d);
+        if (mode == 1 && m->stale) {
+          for (int j = 0; j < m->nslots; ++j) { d.wpack = (char*)u.wpack_d + (size_t)j * u.wpack_d_bytes; pdd[j].push_back(d); }
+        } else {
+          pd.push_back(d);
+        }
       }
       WredDesc w{};
       w.partial = u.wg_partial; w.dW = m->grad + u.ow; w.rows = u.wg.msplit; w.Cout = u.cout; w.Cin = u.cin;
@@ -427,7 +444,20 @@ ddg_status build_plan(ddg_module* m) {
     if (hipMemcpy(m->pack_descs, pd.data(), pd.size() * sizeof(PackDesc), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(m->wred_descs, wd.data(), wd.size() * sizeof(WredDesc), hipMemcpyHostToDevice) != hipSuccess)
       return fail(DDG_ERR_DEVICE, "copying the layer tables failed");
+    for (size_t j = 0; j < pdd.size(); ++j) {
+      m->n_pack_d = (int)pdd[j].size();
+      if (!m->n_pack_d) break;
+      DDG_OKAY(dev_alloc(m, &p, pdd[j].size() * sizeof(PackDesc)));
+      m->pack_descs_d.push_back((PackDesc*)p);
+      if (hipMemcpy(p, pdd[j].data(), pdd[j].size() * sizeof(PackDesc), hipMemcpyHostToDevice) != hipSuccess)
+        return fail(DDG_ERR_DEVICE, "copying the layer tables failed");
+    }
   }
+  if (m->stale && !d.dry_run) {
+    DDG_OKAY(dev_alloc(m, &p, (size_t)m->nslots * m->nparams * sizeof(float)));
+    m->theta_snap = (float*)p;
+  }
+  m->theta_bwd = m->theta;
   if (!d.dry_run) {
     hipError_t e = hipMemsetAsync(m->theta, 0, 4 * m->nparams * sizeof(float), m->stream);
     if (e == hipSuccess) {
@@ -695,7 +725,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     DDG_TRY(bn_bwd_reduce_launch(dy, mask, mscale, mshift, u.z, u.mean, u.invstd, u.bstat, E, u.cout, dt, m->stream));
   }
   BnBwdRows br{};
-  br.partial = u.bstat; br.rows = stats_rows; br.gamma = m->theta + u.og; br.mean = u.mean; br.invstd = u.invstd;
+  br.partial = u.bstat; br.rows = stats_rows; br.gamma = m->theta_bwd + u.og; br.mean = u.mean; br.invstd = u.invstd;
   br.count = (float)((size_t)u.N * u.P * u.Q); br.dgamma = m->grad + u.og; br.dbeta = m->grad + u.ob;
   WgradArgs w = u.wg;
   w.x = x_in; w.dz = dz_buf; w.partial = u.wg_partial; w.dW = m->grad + u.ow;
@@ -717,7 +747,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
       DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, nullptr, &br, dz_buf, E, u.cout, dt, m->stream));
     } else {
       { Launch L(m, PK_BN_BWD_FINALIZE);
-        DDG_TRY(bn_bwd_finalize_launch(u.bstat, stats_rows, u.cout, m->theta + u.og, u.mean, u.invstd,
+        DDG_TRY(bn_bwd_finalize_launch(u.bstat, stats_rows, u.cout, m->theta_bwd + u.og, u.mean, u.invstd,
                                        (float)((size_t)u.N * u.P * u.Q), m->grad + u.og, m->grad + u.ob, u.coef, m->stream)); }
       Launch L(m, PK_BN_BWD_APPLY, (mask && mask != u.z ? 4.0 : 3.0) * E * m->esz);
       DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
@@ -753,19 +783,20 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
   return DDG_OK;
 }
 
-// Backward through the tape. dtop: gradient at the module output (null with a head).
-ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const int32_t* labels,
-                        void* delta_out, float* loss_out) {
+// Backward through the tape held in `blocks` (the module's own, or a ring slot's view of them).
+// dtop: gradient at the module output (null with a head).
+ddg_status run_backward(ddg_module* m, std::vector<Blk>& blocks, const void* in, const void* dtop,
+                        const int32_t* labels, void* delta_out, float* loss_out) {
   const int dt = m->d.compute;
   const bool head = m->d.num_classes > 0;
-  const int nres = (int)m->blocks.size() - (head ? 1 : 0);
+  const int nres = (int)blocks.size() - (head ? 1 : 0);
   const void* dy = dtop;
   if (head) {
-    Blk& hb = m->blocks.back();
+    Blk& hb = blocks.back();
     HeadArgs a{};
     // a module that is the head alone (a split point after the last conv layer) reads its
     // stored input and hands the gradient straight to delta_out
-    a.h = nres > 0 ? m->blocks[nres - 1].y : in; a.fcw = m->theta + hb.ofcw; a.fcb = m->theta + hb.ofcb; a.labels = labels;
+    a.h = nres > 0 ? blocks[nres - 1].y : in; a.fcw = m->theta + hb.ofcw; a.fcb = m->theta + hb.ofcb; a.labels = labels;
     a.pooled = hb.pooled; a.dlogits = hb.dlogits; a.loss_n = hb.loss_n; a.loss_out = loss_out;
     a.dfcw = m->grad + hb.ofcw; a.dfcb = m->grad + hb.ofcb; a.dh = nres > 0 ? m->Ga : delta_out;
     a.N = m->d.batch; a.HW = hb.HW; a.C = hb.C; a.classes = m->d.num_classes; a.dtype = dt;
@@ -776,8 +807,8 @@ ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const i
   void* gnext = (dy == m->Ga) ? m->Gb : m->Ga;  // where this block's input gradient goes
   int top_rows = 0;   // > 0: the BN sums of this block's last unit are already in the workspace
   for (int bi = nres - 1; bi >= 0; --bi) {
-    Blk& b = m->blocks[bi];
-    const void* x = (bi == 0) ? in : m->blocks[bi - 1].y;
+    Blk& b = blocks[bi];
+    const void* x = (bi == 0) ? in : blocks[bi - 1].y;
     const bool want_dx = (bi > 0) || (m->d.k > 1);
     void* dx_dst = nullptr;
     if (want_dx) dx_dst = (bi == 0) ? delta_out : gnext;
@@ -785,7 +816,7 @@ ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const i
     // block below (its ReLU mask is that block's output)
     BelowBn below_blk;
     if (bi > 0) {
-      Blk& pb = m->blocks[bi - 1];
+      Blk& pb = blocks[bi - 1];
       below_blk.u = &pb.u[pb.nmain - 1];
       below_blk.mask = pb.y;
     }
@@ -833,6 +864,27 @@ ddg_status run_backward(ddg_module* m, const void* in, const void* dtop, const i
     if (bi > 0) { dy = gnext; gnext = (gnext == m->Ga) ? m->Gb : m->Ga; }
   }
   return DDG_OK;
+}
+
+// The module's blocks with every forward buffer (conv outputs, statistics rows, per-channel
+// vectors, activations, block outputs) and the input-gradient operand moved to group / ring
+// slot g: what a kept forward pass of that slot wrote, and what its backward pass reads.
+std::vector<Blk> group_view(ddg_module* m, int g) {
+  std::vector<Blk> v = m->blocks;
+  for (Blk& b : v) {
+    if (b.kind == DDG_BLOCK_HEAD) continue;
+    for (size_t i = 0; i < b.u.size(); ++i) {
+      Unit& u = b.u[i];
+      u.z = grp(u.z, u.out_elems() * m->esz, g);
+      u.fstat += (size_t)g * u.fcap * 2 * u.cout;
+      const int vo = g * u.vec_stride();
+      u.mean += vo; u.invstd += vo; u.scale += vo; u.shift += vo; u.coef += vo;
+      if (u.wpack_d) u.wpack_d = (char*)u.wpack_d + (size_t)g * u.wpack_d_bytes;
+    }
+    for (size_t i = 0; i < b.act.size(); ++i) b.act[i] = grp(b.act[i], b.u[i].out_elems() * m->esz, g);
+    b.y = grp(b.y, b.y_elems * m->esz, g);
+  }
+  return v;
 }
 
 // Second set of forward buffers: same plan and packed weights, own conv outputs, statistics
@@ -892,7 +944,7 @@ ddg_status ddg_module_create(const ddg_module_desc* desc, ddg_module** out) {
   m->bstream = (hipStream_t)desc->stream;
   m->fstream = m->bstream;
   m->stream = m->bstream;
-  m->two_streams = desc->forward_stream && desc->forward_stream != desc->stream && (desc->K - desc->k) > 0 &&
+  m->two_streams = !desc->stale_jacobian && desc->forward_stream && desc->forward_stream != desc->stream && (desc->K - desc->k) > 0 &&
                    !desc->dry_run;
   if (m->two_streams) m->fstream = (hipStream_t)desc->forward_stream;
   ddg_status st = build_plan(m);
@@ -1033,7 +1085,7 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   m->phase = 1;
   if (m->d.dry_run) return DDG_OK;
   // paired: this call also re-forwards the minibatch of iteration t - delay (same weights)
-  const bool paired = m->groups == 2 && t >= m->delay;
+  const bool paired = !m->stale && m->groups == 2 && t >= m->delay;
   if (m->skip) { m->tape_is_current = (m->delay == 0) || paired; return DDG_OK; }
   m->stream = m->fstream;
   const bool self_sync = m->two_streams && !m->external_sync;
@@ -1043,7 +1095,19 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   { Launch L(m, PK_COPY, 2.0 * m->in_elems * m->esz); DDG_TRY(copy_launch(h_in, slot, m->in_elems * m->esz, m->stream)); }
   // A module with delay > 0 re-forwards before its backward, so this pass need not keep a
   // tape and writes straight to h_out; the last module keeps the tape for its own backward.
-  if (paired) {
+  if (m->stale) {
+    // keep this pass: its tape, the weights it used and their input-gradient operands
+    const int g = (int)(t % m->nslots);
+    std::vector<Blk> tape = group_view(m, g);
+    { Launch L(m, PK_COPY, 2.0 * m->nparams * sizeof(float));
+      DDG_TRY(copy_launch(m->theta, m->theta_snap + (size_t)g * m->nparams, m->nparams * sizeof(float), m->stream)); }
+    if (m->n_pack_d) { Launch L(m, PK_PACK); DDG_TRY(pack_all_launch(m->pack_descs_d[g], m->n_pack_d, m->d.compute, m->stream)); }
+    DDG_OKAY(run_forward(m, tape, slot, nullptr));
+    m->tape_is_current = false;
+    const Blk& lb = tape[tape.size() - 1];
+    Launch L(m, PK_COPY, 2.0 * m->out_elems * m->esz);
+    DDG_TRY(copy_launch(lb.y, h_out, m->out_elems * m->esz, m->stream));
+  } else if (paired) {
     DDG_OKAY(run_forward_pair(m, m->blocks, m->ring[(t - m->delay) % m->nslots], slot, h_out));
     m->tape_is_current = true;    // group 0 holds the tape of iteration t - delay
   } else if (m->delay > 0) {
@@ -1082,9 +1146,19 @@ ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, con
   // the stored input of iteration s <= t-1 was written by the forward stream
   if (m->two_streams && !m->external_sync && t > 0) DDG_TRY(hipStreamWaitEvent(m->bstream, m->ev_fwd[(t - 1) & 1], 0));
   void* slot = m->ring[s % m->nslots];
-  if (!m->tape_is_current) DDG_OKAY(run_forward(m, m->blocks, slot, nullptr));
+  if (!m->tape_is_current && !m->stale) DDG_OKAY(run_forward(m, m->blocks, slot, nullptr));
   m->tape_is_current = false;
-  DDG_OKAY(run_backward(m, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out));
+  if (m->stale) {
+    // the tape and the weights of iteration s (Eq. 6-7 as printed)
+    const int g = (int)(s % m->nslots);
+    std::vector<Blk> tape = group_view(m, g);
+    m->theta_bwd = m->theta_snap + (size_t)g * m->nparams;
+    const ddg_status st = run_backward(m, tape, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out);
+    m->theta_bwd = m->theta;
+    DDG_OKAY(st);
+  } else {
+    DDG_OKAY(run_backward(m, m->blocks, slot, delta_in, labels, m->d.k > 1 ? delta_out : nullptr, loss_out));
+  }
   // every layer's weight-gradient partials -> g (one launch for the module, fixed order)
   Launch L(m, PK_WGRAD_REDUCE, (double)m->nparams * 4.0);
   DDG_TRY(wgrad_reduce_all_launch(m->wred_descs, m->n_wred, m->wred_max, m->stream));

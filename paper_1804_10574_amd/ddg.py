@@ -35,7 +35,8 @@ class ModuleDesc(C.Structure):
                 ("in_h", C.c_int), ("in_w", C.c_int), ("num_blocks", C.c_int),
                 ("blocks", C.POINTER(BlockDesc)), ("num_classes", C.c_int), ("compute", C.c_int),
                 ("momentum", C.c_float), ("weight_decay", C.c_float), ("bn_eps", C.c_float),
-                ("stream", C.c_void_p), ("forward_stream", C.c_void_p), ("dry_run", C.c_int)]
+                ("stream", C.c_void_p), ("forward_stream", C.c_void_p), ("dry_run", C.c_int),
+                ("stale_jacobian", C.c_int)]
 
 
 _lib = None
@@ -135,10 +136,11 @@ def _ptr(t) -> Optional[int]:
 
 
 def make_desc(K, k, batch, in_chw, blocks: Sequence[Sequence[int]], num_classes, compute, momentum,
-              weight_decay, bn_eps, stream=None, dry_run=False, forward_stream=None):
+              weight_decay, bn_eps, stream=None, dry_run=False, forward_stream=None, stale_jacobian=False):
     arr = (BlockDesc * len(blocks))(*[BlockDesc(*b) for b in blocks])
     d = ModuleDesc(K, k, batch, in_chw[0], in_chw[1], in_chw[2], len(blocks), arr, num_classes,
-                   compute, momentum, weight_decay, bn_eps, stream, forward_stream, 1 if dry_run else 0)
+                   compute, momentum, weight_decay, bn_eps, stream, forward_stream, 1 if dry_run else 0,
+                   1 if stale_jacobian else 0)
     d._keep = arr
     return d
 

@@ -34,7 +34,7 @@ def nhwc_np_to_nchw(a):
     return np.asarray(a, np.float64).transpose(0, 3, 1, 2)
 
 
-def descs_for(wl, streams=None, dry_run=False, batch=None, fstreams=None):
+def descs_for(wl, streams=None, dry_run=False, batch=None, fstreams=None, stale_jacobian=False):
     out = []
     for i, m in enumerate(wl.modules):
         out.append(make_desc(wl.K, m.k, batch or wl.batch, (m.in_c, m.in_h, m.in_w),
@@ -42,7 +42,8 @@ def descs_for(wl, streams=None, dry_run=False, batch=None, fstreams=None):
                              wl.num_classes if m.blocks[-1].kind == wk.BLOCK_HEAD else 0,
                              compute_enum(wl), wl.momentum, wl.weight_decay, wl.bn_eps,
                              stream=(streams[i] if streams else None), dry_run=dry_run,
-                             forward_stream=(fstreams[i] if fstreams else None)))
+                             forward_stream=(fstreams[i] if fstreams else None),
+                             stale_jacobian=stale_jacobian))
     return out
 
 
@@ -90,7 +91,8 @@ SMOOTH_KINDS = ("loss", "h", "params", "velocity")
 
 
 def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_forced=True,
-                        loose=0.25, deriv_tol=None, say=None, forward_streams=False, adam=None, lr_of=None):
+                        loose=0.25, deriv_tol=None, say=None, forward_streams=False, adam=None, lr_of=None,
+                        stale_jacobian=False):
     """Run `steps` DDG iterations on the HIP pipeline and on the float64 oracle with the same
     seeded inputs and compare per tensor (relative L2 error).
 
@@ -112,10 +114,11 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
     K = wl.K
     st = [torch.cuda.Stream() for _ in range(K)] if streams else None
     fst = [torch.cuda.Stream() for _ in range(K)] if (streams and forward_streams) else None
-    pipe = ddg.Pipeline(descs_for(wl, fstreams=[s.cuda_stream for s in fst] if fst else None),
+    pipe = ddg.Pipeline(descs_for(wl, fstreams=[s.cuda_stream for s in fst] if fst else None,
+                                  stale_jacobian=stale_jacobian),
                         [s.cuda_stream for s in st] if st else None)
     mods = {k: pipe.module(k) for k in range(1, K + 1)}
-    oracle = orc.OracleNet.from_workload(wl, dtype="f64")
+    oracle = orc.OracleNet.from_workload(wl, dtype="f64", stale_jacobian=stale_jacobian)
     init_both(wl, mods, oracle, perturb_bn)
     if adam:   # (beta1, beta2, eps): Algorithm 2 instead of momentum SGD, on both sides
         oracle.set_adam(True, *adam)

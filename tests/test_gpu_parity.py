@@ -290,6 +290,30 @@ def test_adam_k4_schedule(H, dtype):
     assert not report, "\n".join(report)
 
 
+# ---- Eq. 6-7 read literally: tapes and weight snapshots instead of the re-forward -------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stale_jacobian_k4(H, dtype):
+    """K=4 in stale-Jacobian mode against the oracle's stale-Jacobian mode, 14 iterations with
+    graph replay from iteration K on. The weights change every iteration, so a backward pass
+    that read the current weights, or the tape of the wrong ring slot, would not match."""
+    wl = custom_cifar(2, [2, 4, 6], batch=8, num_classes=10, hw=16, dtype=dtype, name="k4_stale")
+    wl.lr = 0.05
+    _say(f"case stale-jacobian k4 {dtype} steps=14")
+    report, stats = H.run_pipeline_parity(wl, 14, TOL[dtype], say=_say, stale_jacobian=True,
+                                          deriv_tol=0.2 if dtype == "bf16" else None,
+                                          loose=0.6 if dtype == "bf16" else 0.25)
+    assert not report, "\n".join(report)
+
+
+def test_stale_jacobian_cifar_shapes_bf16(H):
+    """The LDS-tiled kernels on ring-slot views of the buffers: 32x32 inputs, K=3."""
+    wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="bf16", name="cifar_k3_stale")
+    _say("case stale-jacobian cifar_k3 bf16 steps=8")
+    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=0.2, loose=0.6, stale_jacobian=True)
+    assert not report, "\n".join(report)
+
+
 # ---- ResNet-8 (Table 2) with the split points of Section 5.1 --------------------------------
 
 @pytest.mark.parametrize("layer", [1, 3, 5, 7])
