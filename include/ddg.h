@@ -15,7 +15,18 @@
  * The paper does not say how a module obtains its inner activations of
  * iteration s. This library keeps the module INPUT of the last K-k iterations
  * in a ring of device buffers and re-runs the module's forward on the stored
- * input with the module's current weights before back-propagating.
+ * input with the module's current weights before back-propagating (for a module
+ * with a delay, ddg_forward(t) does this in the same launches as the forward pass
+ * on minibatch t: same weights, two minibatches, separate batch statistics).
+ * ddg_module_desc.stale_jacobian selects the literal reading of Eq. 6-7 instead.
+ *
+ * Environment (read when a module or pipeline is created; all optional)
+ *   DDG_NO_GRAPH=1   the pipeline enqueues every kernel instead of replaying graphs
+ *   DDG_NO_PAIR=1    forward(t) and the re-forward run as separate passes
+ *   DDG_NO_DEFER=1   every residual block runs its own normalise-add-ReLU pass
+ *   DDG_TUNE_CONV_GRID_C16/_C32/_C64, DDG_TUNE_WGRAD_ROWS[_C16/_C32/_C64]
+ *                    workgroup counts of the LDS-tiled kernels (clamped to safe ranges)
+ * None of them changes a result beyond the order of floating-point sums.
  *
  * Conventions for every call
  *   - All tensor pointers are DEVICE pointers unless the argument says "host".
