@@ -26,12 +26,15 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 # profile kind -> the HIP kernel it times (as rocprofv3 names it)
 HIP_KERNEL_OF = {
-    "conv_fprop.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 1, false|true>",
-    "conv_fprop.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 1, false|true>",
-    "conv_fprop.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 1, false|true>",
-    "conv_dgrad.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 2|0, false>",
-    "conv_dgrad.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 2|0, false>",
-    "conv_dgrad.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 2|0, false>",
+    "conv_fprop.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 1, XF>",
+    "conv_fprop.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 1, XF>",
+    "conv_fprop.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 1, XF>",
+    "conv_dgrad.tiled_c16_w32": "ddg::conv3x3_tiled_kernel<16, 32, 2|0, XF>",
+    "conv_dgrad.tiled_c32_w16": "ddg::conv3x3_tiled_kernel<32, 16, 2|0, XF>",
+    "conv_dgrad.tiled_c64_w8": "ddg::conv3x3_tiled_kernel<64, 8, 2|0, XF>",
+    "conv_bwd_pair.tiled_c16_w32": "ddg::bwd_pair_kernel<16, 32, 2|0, XF>",
+    "conv_bwd_pair.tiled_c32_w16": "ddg::bwd_pair_kernel<32, 16, 2|0, XF>",
+    "conv_bwd_pair.tiled_c64_w8": "ddg::bwd_pair_kernel<64, 8, 2|0, XF>",
     "bn_apply": "ddg::bn_apply_chunk_kernel<bf16_t, U>",
     "conv_wgrad.tiled_c16_w32": "ddg::wgrad_tiled_kernel<16, 16, 32>",
     "conv_wgrad.tiled_c32_w16": "ddg::wgrad_tiled_kernel<32, 32, 16>",
@@ -226,7 +229,7 @@ def main():
         out["roofline"] = roof
         out["kernels"] = kernels
         out["families"] = families
-        convs = [k for k in ("conv_fprop", "conv_dgrad", "conv_wgrad") if k in families]
+        convs = [k for k in ("conv_fprop", "conv_dgrad", "conv_wgrad", "conv_bwd_pair") if k in families]
         conv_ms = sum(famsum[k][1] for k in convs)
         out["conv_mfma_util"] = sum(famsum[k][3] for k in convs) / 1e12 / (conv_ms / 1e3) / MFMA_PEAK_TFLOPS[wl.dtype] if conv_ms else None
         out["conv_hbm_frac"] = sum(famsum[k][2] for k in convs) / 1e9 / (conv_ms / 1e3) / HBM_PEAK_GBS if conv_ms else None

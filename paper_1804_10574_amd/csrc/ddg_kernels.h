@@ -107,6 +107,9 @@ struct WgradFuse {
   const void* dy; const void* mask; const float* mscale; const float* mshift;
   const void* z; const float* coef; const BnBwdRows* rows; void* dz_out;
 };
+struct WgradPair {
+  const void* x; const float* scale; const float* shift; const void* dz; float* partial; int rows;
+};
 int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
 hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* shift, const void* dz,
                               const WgradFuse* fuse, float* partial, int N, int H, int W, int C, int rows,
@@ -137,11 +140,17 @@ int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, i
 // with its own batch-norm statistics; grid workgroups are split evenly over the groups, the
 // statistics rows (st.partial, in_rows->partial) are [group][grid/groups][2][C], and the
 // per-channel vectors of group g lie g*vec_stride floats after those of group 0.
+// apply (optional, input gradient only): `in` is apply->dy, the gradient after a batch norm's
+// ReLU; the kernel forms dz = BN-backward(dy) from apply->rows while staging (as the fused
+// weight-gradient kernel does), convolves dz, and stores it to apply->dz_out.
+// pair (optional, with apply): the launch also carries the plain weight gradient of another
+// layer of the same shape (input x, or relu(x*scale+shift); error gradient dz; `rows` partial
+// tiles as wgrad_tiled_rows() says), on workgroups of its own.
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
                              const void* wpack, void* out, const ConvStat& st, const void* add_g,
                              const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
                              const void* res = nullptr, void* y_out = nullptr, int groups = 1,
-                             int vec_stride = 0);
+                             int vec_stride = 0, const WgradFuse* apply = nullptr, const WgradPair* pair = nullptr);
 
 
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,

@@ -36,13 +36,16 @@ enum ProfKind {
   PK_CONV_FPROP = 0, PK_CONV_FPROP_T16, PK_CONV_FPROP_T32, PK_CONV_FPROP_T64,
   PK_CONV_DGRAD, PK_CONV_DGRAD_T16, PK_CONV_DGRAD_T32, PK_CONV_DGRAD_T64,
   PK_CONV_WGRAD, PK_CONV_WGRAD_T16, PK_CONV_WGRAD_T32, PK_CONV_WGRAD_T64,
-  PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
+  // a launch that carries an input-gradient kernel and the weight gradient of the unit above
+  PK_BWD_PAIR_T16, PK_BWD_PAIR_T32, PK_BWD_PAIR_T64, PK_BWD_PAIR = PK_BWD_PAIR_T16 - 1,
+  PK_WGRAD_REDUCE = PK_BWD_PAIR_T64 + 1, PK_BN_FINALIZE, PK_BN_APPLY,
   PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_COUNT
 };
 static const char* kProfNames[PK_COUNT] = {
   "conv_fprop.generic", "conv_fprop.tiled_c16_w32", "conv_fprop.tiled_c32_w16", "conv_fprop.tiled_c64_w8",
   "conv_dgrad.generic", "conv_dgrad.tiled_c16_w32", "conv_dgrad.tiled_c32_w16", "conv_dgrad.tiled_c64_w8",
   "conv_wgrad.generic", "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c32_w16", "conv_wgrad.tiled_c64_w8",
+  "conv_bwd_pair.tiled_c16_w32", "conv_bwd_pair.tiled_c32_w16", "conv_bwd_pair.tiled_c64_w8",
   "wgrad_reduce", "bn_finalize", "bn_apply",
   "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam"};
 
@@ -128,6 +131,14 @@ struct ddg_module {
   long nupd = 0;                   // Adam: updates executed so far (n)
   std::vector<void*> ring;
   void *Ga = nullptr, *Gb = nullptr, *D1 = nullptr, *D2 = nullptr, *D3 = nullptr;
+  // dz buffers: units alternate between D1 and D1b, so that the weight gradient of a unit can
+  // run one launch late, beside the input-gradient kernel of the unit below
+  void* D1b = nullptr; int dz_flip = 0;
+  struct PendingWgrad {
+    bool on = false; const Unit* u = nullptr;
+    const void* x = nullptr; const float* xsc = nullptr; const float* xsh = nullptr; const void* dz = nullptr;
+  } pend_w;
+  bool defer_wgrad = true;         // DDG_NO_BWD_PAIR=1 switches the deferred weight gradient off
   float* ws_stat = nullptr; size_t ws_stat_elems = 0;
   PackDesc* pack_descs = nullptr; int n_pack = 0;     // device tables for the whole-module kernels
   WredDesc* wred_descs = nullptr; int n_wred = 0; int wred_max = 0;   // wred_max: largest Cout*Jp
@@ -402,6 +413,8 @@ ddg_status build_plan(ddg_module* m) {
   DDG_OKAY(dev_alloc(m, &m->Ga, m->max_act * m->esz));
   DDG_OKAY(dev_alloc(m, &m->Gb, m->max_act * m->esz));
   DDG_OKAY(dev_alloc(m, &m->D1, m->max_act * m->esz));
+  DDG_OKAY(dev_alloc(m, &m->D1b, m->max_act * m->esz));
+  if (const char* e = getenv("DDG_NO_BWD_PAIR")) m->defer_wgrad = !(e[0] == '1');
   DDG_OKAY(dev_alloc(m, &m->D2, m->max_act * m->esz));
   DDG_OKAY(dev_alloc(m, &m->D3, m->max_act * m->esz));
   DDG_OKAY(dev_alloc(m, &p, m->ws_stat_elems * sizeof(float)));
@@ -702,6 +715,19 @@ struct BelowBn {
   const float* mshift = nullptr;
 };
 
+// Launches the weight gradient a unit left for later (plain: its dz is in memory by now).
+ddg_status flush_pending_wgrad(ddg_module* m) {
+  if (!m->pend_w.on) return DDG_OK;
+  const ddg_module::PendingWgrad w = m->pend_w;
+  m->pend_w.on = false;
+  const Unit& u = *w.u;
+  Launch L(m, PK_CONV_WGRAD + u.tiled_instance(), (u.in_elems() + (double)u.out_elems()) * m->esz + wbytes(m, u) * 4.0 / m->esz,
+           conv_flops(u));
+  DDG_TRY(wgrad_tiled_launch(w.x, w.xsc, w.xsh, w.dz, nullptr, u.wg_partial, u.N, u.H, u.W, u.cin, u.wg_tiled_rows,
+                             m->stream));
+  return DDG_OK;
+}
+
 // BN backward + weight gradient (+ input gradient) of one unit.
 //   dy: gradient w.r.t. the ReLU output that follows this unit's BN; the ReLU was active where
 //       mask > 0 (or mask*mscale+mshift > 0); mask == null: no ReLU in between
@@ -719,6 +745,8 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
   const int dt = m->d.compute;
   const size_t E = u.out_elems();
   if (below_rows) *below_rows = 0;
+  dz_buf = m->dz_flip ? m->D1b : m->D1;   // not the buffer a pending weight gradient reads
+  m->dz_flip ^= 1;
   if (stats_rows <= 0) {
     stats_rows = bn_bwd_grid(E, u.cout, dt);
     Launch L(m, PK_BN_BWD_REDUCE, (mask && mask != u.z ? 3.0 : 2.0) * E * m->esz);
@@ -727,6 +755,49 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
   BnBwdRows br{};
   br.partial = u.bstat; br.rows = stats_rows; br.gamma = m->theta_bwd + u.og; br.mean = u.mean; br.invstd = u.invstd;
   br.count = (float)((size_t)u.N * u.P * u.Q); br.dgamma = m->grad + u.og; br.dbeta = m->grad + u.ob;
+  if (m->defer_wgrad && u.wg_tiled_rows > 0 && u.tiled_grid > 0 && dx && dx != dy) {   // (a halo kernel cannot work in place)
+    // The input-gradient kernel forms dz = BN-backward(dy) while staging (coefficients from the
+    // rows), stores it, convolves it, and forms the sums of the unit below in its epilogue. The
+    // weight gradient of this unit then needs nothing but dz and the input: it runs one launch
+    // late, in the same launch as the next unit's input-gradient kernel.
+    WgradFuse f{};
+    f.dy = dy; f.mask = mask; f.mscale = mscale; f.mshift = mshift; f.z = u.z; f.coef = nullptr; f.rows = &br;
+    f.dz_out = dz_buf;
+    ConvStat st{};
+    double extra = (add_g ? (add_mask ? 2.0 : 1.0) : 0.0);
+    if (below && below->u) {
+      st.mode = 2; st.partial = below->u->bstat;
+      st.mask = below->mask; st.mscale = below->mscale; st.mshift = below->mshift;
+      st.z = below->u->z; st.zmean = below->u->mean; st.zinvstd = below->u->invstd;
+      if (below_rows) *below_rows = u.tiled_grid;
+      extra += (below->mask == below->u->z) ? 1.0 : 2.0;
+    }
+    // a pending weight gradient of the same shape rides in this launch
+    const ddg_module::PendingWgrad pw = m->pend_w;
+    const bool ride = pw.on && pw.u->cin == u.cin && pw.u->W == u.W && pw.u->H == u.H && pw.u->N == u.N;
+    if (!ride) DDG_OKAY(flush_pending_wgrad(m));
+    {
+      // reads dy, z (and the mask tensor if it is a different one) and the weights, writes dz and
+      // dx; plus the shortcut term and what the sums of the unit below read; plus, for a weight
+      // gradient that rides along, its input and dz read and its partial tiles written
+      double bytes = ((mask && mask != u.z ? 4.0 : 3.0) * E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u);
+      double flops = conv_flops(u);
+      WgradPair wp{};
+      if (ride) {
+        wp.x = pw.x; wp.scale = pw.xsc; wp.shift = pw.xsh; wp.dz = pw.dz; wp.partial = pw.u->wg_partial; wp.rows = pw.u->wg_tiled_rows;
+        bytes += (pw.u->in_elems() + (double)pw.u->out_elems()) * m->esz + wbytes(m, *pw.u) * 4.0 / m->esz;
+        flops += conv_flops(*pw.u);
+        m->pend_w.on = false;
+      }
+      Launch L(m, (ride ? PK_BWD_PAIR : PK_CONV_DGRAD) + u.tiled_instance(), bytes, flops);
+      DDG_TRY(conv_tiled_launch(dy, nullptr, nullptr, nullptr, u.wpack_d, dx, st, add_g, add_mask, u.N, u.H, u.W,
+                                u.cin, u.tiled_grid, m->stream, nullptr, nullptr, 1, 0, &f, ride ? &wp : nullptr));
+    }
+    m->pend_w.on = true; m->pend_w.u = &u; m->pend_w.x = x_in; m->pend_w.xsc = x_scale; m->pend_w.xsh = x_shift;
+    m->pend_w.dz = dz_buf;
+    return DDG_OK;
+  }
+  DDG_OKAY(flush_pending_wgrad(m));
   WgradArgs w = u.wg;
   w.x = x_in; w.dz = dz_buf; w.partial = u.wg_partial; w.dW = m->grad + u.ow;
   if (u.wg_tiled_rows > 0) {
@@ -863,7 +934,7 @@ ddg_status run_backward(ddg_module* m, std::vector<Blk>& blocks, const void* in,
     top_rows = next_top_rows;
     if (bi > 0) { dy = gnext; gnext = (gnext == m->Ga) ? m->Gb : m->Ga; }
   }
-  return DDG_OK;
+  return flush_pending_wgrad(m);
 }
 
 // The module's blocks with every forward buffer (conv outputs, statistics rows, per-channel

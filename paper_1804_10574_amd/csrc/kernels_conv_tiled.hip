@@ -16,6 +16,7 @@
 #include "ddg_device.h"
 #include "ddg_kernels.h"
 #include "ddg_stats.h"
+#include "ddg_wgrad_tiled.h"
 #include <cstdlib>
 
 namespace ddg {
@@ -32,6 +33,12 @@ struct ConvTiledArgs {
   ConvStat st;             // epilogue statistics: partial rows [grid][2][C]
   const bf16_t* add_g;     // optional epilogue term, same layout as out
   const bf16_t* add_mask;  // add_g counts only where add_mask > 0
+  // XF_APPLY kernels: `in` is dy, the gradient w.r.t. the ReLU output after a batch norm, and the
+  // convolved tensor is dz = A*g + B*bz + C0 with g = dy where bmask*bmscale+bmshift > 0 (bmask
+  // null: g = dy); A, B, C0 derive from the partial rows `brows` of that BN's backward sums.
+  // dz is formed while staging and also stored to dz_out (tile rows only).
+  const bf16_t* bz; const bf16_t* bmask; const float* bmscale; const float* bmshift;
+  BnBwdRows brows; bf16_t* dz_out;
   int N, H;                // N counts the images of all groups
   int tiles;               // N * H/8
   // groups > 1: the batch is `groups` independent minibatches laid end to end (batch-norm
@@ -58,8 +65,14 @@ struct ConvTiledCfg {
 
 // Waves per SIMD the register allocation aims for (more co-resident workgroups when several
 // streams run): the largest value each variant reaches without spilling.
-constexpr int conv_tiled_waves(int C, int MODE, bool RES) {
-  return C == 64 ? (RES ? 1 : 2) : ((C == 32 && (RES || MODE == 2)) ? 2 : 3);
+// What staging does to the loaded input: nothing or relu(in*scale+shift) (decided at run time),
+// the residual-block output relu(in*scale+shift + res), or the batch-norm backward formula
+// (XF_APPLY: the ReLU mask is the BN's own conv output bz; XF_APPLY_MASK: a separate tensor).
+enum { XF_PLAIN = 0, XF_RES = 1, XF_APPLY = 2, XF_APPLY_MASK = 3 };
+
+constexpr int conv_tiled_waves(int C, int MODE, int XF) {
+  return C == 64 ? (XF != XF_PLAIN ? 1 : 2)
+                 : (((C == 32 && (XF != XF_PLAIN || MODE == 2)) || (C == 16 && XF >= XF_APPLY && MODE == 2)) ? 2 : 3);
 }
 
 // MODE is the epilogue's statistics mode, fixed at compile time: 0 none, 1 sum / sum of squares
@@ -73,21 +86,22 @@ constexpr int conv_tiled_waves(int C, int MODE, bool RES) {
 // packed hardware conversion.
 // RES: the input is the output of the residual block before, y = relu(in*scale+shift + res),
 // formed while staging and written to y_out by the workgroup that owns the rows.
-template <int C, int W, int MODE, bool RES = false>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_waves(C, MODE, RES)))) void conv3x3_tiled_kernel(ConvTiledArgs a) {
+// bidx of gdim: this workgroup's index in the launch (or in the part of a launch this work has).
+template <int C, int W, int MODE, int XF>
+__device__ __forceinline__ void conv3x3_tiled_body(const ConvTiledArgs& a, unsigned char* tile, int bidx, int gdim) {
   using Cfg = ConvTiledCfg<C, W>;
+  constexpr bool RES = XF == XF_RES, APPLY = XF == XF_APPLY || XF == XF_APPLY_MASK;
   constexpr int TH = Cfg::TH, WC = Cfg::WC, PIX = Cfg::PIX, CH = Cfg::CH, NCHUNK = Cfg::NCHUNK;
   constexpr int PT = Cfg::PER_THREAD, KSTEPS = Cfg::KSTEPS, PG = Cfg::PG, COB = Cfg::COB;
   constexpr bool RAGGED_K = (9 * C) % 32 != 0;   // the last k-step runs past tap 8 for some lanes
-  extern __shared__ __align__(16) unsigned char tile[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
   const int pgrp = wave % PG, cb = wave / PG;
   const int tiles_per_img = a.H / TH;
   // this workgroup's group, its index among the group's workgroups, the group's tile range
-  const int g1 = gridDim.x / a.groups;
-  const int grp = blockIdx.x / g1, bl = blockIdx.x - grp * g1;
+  const int g1 = gdim / a.groups;
+  const int grp = bidx / g1, bl = bidx - grp * g1;
   const int tiles_g = a.tiles / a.groups, t_end = (grp + 1) * tiles_g;
 
   // ---- staging map (the same for every tile): chunk v = tid + i*256 -> halo pixel, 8 channels
@@ -105,7 +119,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
     goff[i] = ((rr - 1) * W + (cc - 1)) * C + my_ch * 8;
     loff[i] = v < NCHUNK ? px * PIX + my_ch * 16 : -1;
   }
-  uint4 stage[PT], stage2[RES ? PT : 1];
+  uint4 stage[PT], stage2[(RES || APPLY) ? PT : 1], stage3[XF == XF_APPLY_MASK ? PT : 1];
   unsigned inimg = 0;   // bit i: chunk i of the tile in flight lies inside the image
   unsigned tile_base = 0;   // element offset of the staged tile's first pixel (the host checks 32 bits suffice)
   auto issue_loads = [&](int t) {
@@ -122,6 +136,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
         inimg |= 1u << i;
         stage[i] = *reinterpret_cast<const uint4*>(a.in + tb + goff[i]);
         if (RES) stage2[i] = *reinterpret_cast<const uint4*>(a.res + tb + goff[i]);
+        if (APPLY) stage2[i] = *reinterpret_cast<const uint4*>(a.bz + tb + goff[i]);
+        if (XF == XF_APPLY_MASK) stage3[i] = *reinterpret_cast<const uint4*>(a.bmask + tb + goff[i]);
       }
     }
   };
@@ -152,9 +168,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
 
   // ---- per-channel transform of the input (while the first tile's loads are in flight); the
   // vectors stay in LDS and a thread reads its 8 channels when it stages (registers are scarce)
-  const bool xform = a.scale != nullptr || a.in_rows.partial != nullptr;
-  __shared__ __align__(16) float s_sc[C], s_sh[C];
-  if (a.in_rows.partial) {
+  const bool xform = !APPLY && (a.scale != nullptr || a.in_rows.partial != nullptr);
+  __shared__ __align__(16) float s_sc[APPLY ? 4 : C], s_sh[APPLY ? 4 : C];
+  // XF_APPLY: A, B, C0 of the formula, then the mask's scale and shift
+  __shared__ __align__(16) float s_coef[APPLY ? 5 * C : 4];
+  if (APPLY) {
+    if (tid < C) {
+      s_coef[3 * C + tid] = a.bmscale ? a.bmscale[tid] : 1.f;
+      s_coef[4 * C + tid] = a.bmscale ? a.bmshift[tid] : 0.f;
+    }
+    bn_bwd_from_rows<C>(a.brows, s_coef, bidx == 0);   // ends with a barrier
+  } else if (a.in_rows.partial) {
     BnRows r = a.in_rows;
     r.partial += (size_t)grp * r.rows * 2 * C;
     const int vo = grp * a.vec_stride;
@@ -171,6 +195,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
     for (int i = 0; i < PT; ++i) {
       if (loff[i] >= 0) {
         uint4 q = stage[i];
+        if (APPLY && ((inimg >> i) & 1u)) {
+          auto ld8 = [&](const float* p, float (&d)[8]) {
+            *reinterpret_cast<float4*>(&d[0]) = *reinterpret_cast<const float4*>(p + my_ch * 8);
+            *reinterpret_cast<float4*>(&d[4]) = *reinterpret_cast<const float4*>(p + my_ch * 8 + 4);
+          };
+          float g[8], zz[8], k0[8], k1[8];
+          Store<bf16_t>::unpack_vec(q, g);
+          Store<bf16_t>::unpack_vec(stage2[i], zz);
+          if (a.bmask) {
+            float mk[8];
+            Store<bf16_t>::unpack_vec(XF == XF_APPLY_MASK ? stage3[i] : stage2[i], mk);
+            ld8(&s_coef[3 * C], k0); ld8(&s_coef[4 * C], k1);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) g[j] = (mk[j] * k0[j] + k1[j]) > 0.f ? g[j] : 0.f;
+          }
+          ld8(&s_coef[C], k0); ld8(&s_coef[2 * C], k1);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) zz[j] = k0[j] * zz[j] + k1[j];
+          ld8(&s_coef[0], k0);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) g[j] = k0[j] * g[j] + zz[j];
+          q.x = Store<bf16_t>::pack2(g[0], g[1]); q.y = Store<bf16_t>::pack2(g[2], g[3]);
+          q.z = Store<bf16_t>::pack2(g[4], g[5]); q.w = Store<bf16_t>::pack2(g[6], g[7]);
+          const unsigned sr1 = (srows >> (4 * i)) & 15u;   // halo row + 1
+          if (sr1 >= 2 && sr1 <= TH + 1)
+            *reinterpret_cast<uint4*>(a.dz_out + stage_base + goff[i]) = q;
+        }
         if (xform && ((inimg >> i) & 1u)) {
           float f[8], tsc[8], tsh[8];
           *reinterpret_cast<float4*>(&tsc[0]) = *reinterpret_cast<const float4*>(&s_sc[my_ch * 8]);
@@ -327,8 +378,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
       float s = 0.f;
 #pragma unroll
       for (int g = 0; g < PG; ++g) s += red[cbb * PG + g][which][cl];
-      a.st.partial[((size_t)blockIdx.x * 2 + which) * C + c] = s;
+      a.st.partial[((size_t)bidx * 2 + which) * C + c] = s;
     }
+  }
+}
+
+template <int C, int W, int MODE, int XF = XF_PLAIN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_waves(C, MODE, XF)))) void conv3x3_tiled_kernel(ConvTiledArgs a) {
+  extern __shared__ __align__(16) unsigned char tile[];
+  conv3x3_tiled_body<C, W, MODE, XF>(a, tile, blockIdx.x, gridDim.x);
+}
+
+// Two independent pieces of backward work of one shape in one launch (a launch costs a few
+// microseconds of dispatch whatever it carries): the first conv_grid workgroups run the
+// input-gradient kernel of a unit (which forms its dz while staging), the others the plain weight
+// gradient of the unit above it, whose dz the launch before has stored.
+template <int C, int W, int MODE, int XF>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_waves(C, MODE, XF)))) void bwd_pair_kernel(ConvTiledArgs ca, WgradTiledArgs wa, int conv_grid, int wg_rows) {
+  extern __shared__ __align__(16) unsigned char tile[];
+  const int b = blockIdx.x;
+  if (b < conv_grid) {
+    conv3x3_tiled_body<C, W, MODE, XF>(ca, tile, b, conv_grid);
+  } else {
+    const int v = b - conv_grid;
+    wgrad_tiled_body<C, C, W, false>(wa, tile, v % wg_rows, v / wg_rows, wg_rows);
   }
 }
 
@@ -364,11 +437,39 @@ int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, i
 }
 
 template <int C, int W>
-static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStream_t s) {
+static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStream_t s, const WgradTiledArgs* wa, int wg_rows) {
   using Cfg = ConvTiledCfg<C, W>;
+  if (wa) {
+    using WCfg = WgradTiledCfg<C, C, W>;
+    if (!a.bz || a.st.mode == 1 || a.scale || a.in_rows.partial || !a.brows.partial || !a.dz_out || wg_rows < 1)
+      return hipErrorInvalidValue;
+    constexpr int lds = Cfg::TILE_BYTES > WCfg::LDS ? Cfg::TILE_BYTES : WCfg::LDS;
+    static_assert(lds <= 48 * 1024, "dynamic LDS within the default limit");
+    const bool own_mask = a.bmask && a.bmask != a.bz;
+    const dim3 g(grid + wg_rows * WCfg::OT);
+    if (a.st.mode == 2) {
+      if (own_mask) DDG_LAUNCH((bwd_pair_kernel<C, W, 2, XF_APPLY_MASK>), g, dim3(256), lds, s, a, *wa, grid, wg_rows);
+      else DDG_LAUNCH((bwd_pair_kernel<C, W, 2, XF_APPLY>), g, dim3(256), lds, s, a, *wa, grid, wg_rows);
+    } else {
+      if (own_mask) DDG_LAUNCH((bwd_pair_kernel<C, W, 0, XF_APPLY_MASK>), g, dim3(256), lds, s, a, *wa, grid, wg_rows);
+      else DDG_LAUNCH((bwd_pair_kernel<C, W, 0, XF_APPLY>), g, dim3(256), lds, s, a, *wa, grid, wg_rows);
+    }
+    return hipGetLastError();
+  }
   if (a.res) {
     if (a.st.mode != 1 || !(a.scale || a.in_rows.partial)) return hipErrorInvalidValue;
-    DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 1, true>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+    DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 1, XF_RES>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+  } else if (a.bz) {
+    // input-gradient kernel that applies the batch-norm backward formula to its input
+    if (a.st.mode == 1 || a.scale || a.in_rows.partial || !a.brows.partial || !a.dz_out) return hipErrorInvalidValue;
+    const bool own_mask = a.bmask && a.bmask != a.bz;
+    if (a.st.mode == 2) {
+      if (own_mask) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 2, XF_APPLY_MASK>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+      else DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 2, XF_APPLY>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+    } else {
+      if (own_mask) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 0, XF_APPLY_MASK>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+      else DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 0, XF_APPLY>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
+    }
   } else if (a.st.mode == 1) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 1>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
   else if (a.st.mode == 2) DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 2>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
   else DDG_LAUNCH((conv3x3_tiled_kernel<C, W, 0>), dim3(grid), dim3(256), Cfg::TILE_BYTES, s, a);
@@ -378,10 +479,17 @@ static hipError_t conv_tiled_launch_t(const ConvTiledArgs& a, int grid, hipStrea
 hipError_t conv_tiled_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
                              const void* wpack, void* out, const ConvStat& st, const void* add_g,
                              const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
-                             const void* res, void* y_out, int groups, int vec_stride) {
+                             const void* res, void* y_out, int groups, int vec_stride, const WgradFuse* apply,
+                             const WgradPair* pair) {
   if (groups < 1 || N % groups != 0 || grid % groups != 0) return hipErrorInvalidValue;
   if (groups > 1 && (st.mode != 1 || add_g)) return hipErrorInvalidValue;   // forward only
-  ConvTiledArgs a;
+  ConvTiledArgs a{};
+  if (apply) {
+    if (groups != 1 || res || !apply->rows) return hipErrorInvalidValue;
+    if (apply->dy != in) return hipErrorInvalidValue;   // the gradient is the conv input
+    a.bz = (const bf16_t*)apply->z; a.bmask = (const bf16_t*)apply->mask; a.bmscale = apply->mscale;
+    a.bmshift = apply->mshift; a.brows = *apply->rows; a.dz_out = (bf16_t*)apply->dz_out;
+  }
   a.groups = groups; a.vec_stride = vec_stride;
   a.in = (const bf16_t*)in; a.scale = scale; a.shift = shift; a.wpack = (const bf16_t*)wpack;
   a.res = (const bf16_t*)res; a.y_out = (bf16_t*)y_out;
@@ -389,9 +497,17 @@ hipError_t conv_tiled_launch(const void* in, const float* scale, const float* sh
   a.out = (bf16_t*)out; a.st = st; a.add_g = (const bf16_t*)add_g;
   a.add_mask = (const bf16_t*)add_mask; a.N = N; a.H = H; a.tiles = N * (H / 8);
   if ((size_t)N * H * W * C >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside
-  if (C == 16 && W == 32) return conv_tiled_launch_t<16, 32>(a, grid, s);
-  if (C == 32 && W == 16) return conv_tiled_launch_t<32, 16>(a, grid, s);
-  if (C == 64 && W == 8) return conv_tiled_launch_t<64, 8>(a, grid, s);
+  WgradTiledArgs wa{};
+  if (pair) {
+    if (!apply || pair->rows < 1 || pair->rows > N * (H / 8)) return hipErrorInvalidValue;
+    wa.x = (const bf16_t*)pair->x; wa.scale = pair->scale; wa.shift = pair->shift; wa.dz = (const bf16_t*)pair->dz;
+    wa.partial = pair->partial; wa.N = N; wa.H = H; wa.W = W; wa.tiles = N * (H / 8);
+  }
+  const WgradTiledArgs* wp = pair ? &wa : nullptr;
+  const int wr = pair ? pair->rows : 0;
+  if (C == 16 && W == 32) return conv_tiled_launch_t<16, 32>(a, grid, s, wp, wr);
+  if (C == 32 && W == 16) return conv_tiled_launch_t<32, 16>(a, grid, s, wp, wr);
+  if (C == 64 && W == 8) return conv_tiled_launch_t<64, 8>(a, grid, s, wp, wr);
   return hipErrorInvalidValue;
 }
 

@@ -28,6 +28,9 @@ def kind_of(kernel_name: str) -> str:
     if m:
         fam = "conv_fprop" if m.group(3) == "1" else "conv_dgrad"
         return f"{fam}.tiled_c{m.group(1)}_w{m.group(2)}"
+    m = re.match(r"bwd_pair_kernel<(\d+), (\d+), ", n)
+    if m:
+        return f"conv_bwd_pair.tiled_c{m.group(1)}_w{m.group(2)}"
     m = re.match(r"wgrad_tiled_kernel<(\d+), (\d+), (\d+)>", n)
     if m:
         return f"conv_wgrad.tiled_c{m.group(1)}_w{m.group(3)}"
