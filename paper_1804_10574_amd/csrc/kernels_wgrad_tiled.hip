@@ -58,7 +58,7 @@ int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, 
   if (!((Cin == 16 && W == 32) || (Cin == 32 && W == 16) || (Cin == 64 && W == 8))) return 0;
   if (H % 8 != 0) return 0;
   const int tiles = N * (H / 8);
-  int want = (Cin == 16) ? 256 : (Cin == 32 ? 128 : 32);
+  int want = (Cin == 16) ? 128 : (Cin == 32 ? 64 : 16);
   if (const char* e = getenv("DDG_TUNE_WGRAD_ROWS")) {   // override within [8, 1024]
     const int v = atoi(e);
     if (v >= 8 && v <= 1024) want = v;
