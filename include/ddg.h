@@ -24,6 +24,9 @@
  *   DDG_NO_GRAPH=1   the pipeline enqueues every kernel instead of replaying graphs
  *   DDG_NO_PAIR=1    forward(t) and the re-forward run as separate passes
  *   DDG_NO_DEFER=1   every residual block runs its own normalise-add-ReLU pass
+ *   DDG_NO_BWD_PAIR=1  the weight gradient of a layer runs in a launch of its own (with the
+ *                    batch-norm backward fused into it) instead of beside the next
+ *                    input-gradient kernel
  *   DDG_TUNE_CONV_GRID_C16/_C32/_C64, DDG_TUNE_WGRAD_ROWS[_C16/_C32/_C64]
  *                    workgroup counts of the LDS-tiled kernels (clamped to safe ranges)
  * None of them changes a result beyond the order of floating-point sums.

@@ -383,6 +383,17 @@ def test_cifar_shaped_pipeline_bf16(H):
     assert not report, "\n".join(report)
 
 
+def test_cifar_shaped_pipeline_bf16_unpaired_backward(H, monkeypatch):
+    """The same pipeline with the library's environment switch that launches every weight
+    gradient on its own (batch-norm backward fused into it) instead of beside the next
+    input-gradient kernel: the other backward path of the LDS-tiled layers."""
+    monkeypatch.setenv("DDG_NO_BWD_PAIR", "1")     # read when a module is created
+    wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="bf16", name="cifar_k3")
+    _say("case cifar_k3 bf16 steps=8, unpaired backward")
+    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=0.2, loose=0.6)
+    assert not report, "\n".join(report)
+
+
 def test_cifar_shaped_pipeline_f32(H):
     wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="f32", name="cifar_k3")
     _say("case cifar_k3 f32 steps=8")
