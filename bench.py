@@ -69,6 +69,83 @@ def build_pipeline(wl, serial=False, forward_streams=False, stale_jacobian=False
     return pipe, streams
 
 
+class SingleModule:
+    """One module on its own (the ImageNet-shaped bottleneck slice): its input and the delayed
+    error gradient are synthetic tensors resident in HBM; a step is ddg_forward +
+    ddg_backward_delayed + ddg_update. Presents the calls the timing loop uses on a pipeline."""
+
+    def __init__(self, wl, stale_jacobian=False, forward_stream=False):
+        import torch
+        import numpy as np
+        import workloads as wk
+        import paper_1804_10574_amd as ddg
+        from paper_1804_10574_amd.ddg import make_desc
+        m = wl.modules[0]
+        self.wl, self.m = wl, m
+        self.stream = torch.cuda.Stream()
+        self.fstream = torch.cuda.Stream() if forward_stream else None
+        tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        desc = make_desc(wl.K, m.k, wl.batch, (m.in_c, m.in_h, m.in_w), [b.as_tuple() for b in m.blocks], 0,
+                         ddg.DDG_BF16 if wl.dtype == "bf16" else ddg.DDG_F32, wl.momentum, wl.weight_decay,
+                         wl.bn_eps, stream=self.stream.cuda_stream, stale_jacobian=stale_jacobian,
+                         forward_stream=self.fstream.cuda_stream if self.fstream else None)
+        self.mod = ddg.Module(desc)
+        self.mod.set_params(wk.init_module_params(wl, m).astype(np.float32))
+        shape_in = (wl.batch, m.in_c, m.in_h, m.in_w)
+        def dev(a):
+            return torch.from_numpy(np.ascontiguousarray(a.transpose(0, 2, 3, 1))).to(torch.float32).cuda().to(tdt).contiguous()
+        self.h = [dev(wk.normal(wl.seed, 100 + i, int(np.prod(shape_in))).reshape(shape_in)) for i in range(4)]
+        self.delta = [dev(wk.synthetic_delta(wl, m, i)) for i in range(4)]
+        self.h_out = torch.empty((wl.batch, m.out_h, m.out_w, m.out_c), dtype=tdt, device="cuda")
+        self.d_out = torch.empty_like(self.h[0])
+        self.t = 0
+
+    def step(self, i):
+        self.mod.forward(self.t, self.h[i % 4], self.h_out)
+        self.mod.backward_delayed(self.t, delta_in=self.delta[i % 4], delta_out=self.d_out)
+        self.mod.update(self.t, self.wl.lr)
+        self.t += 1
+
+    def set_optimizer(self, *a):
+        self.mod.set_optimizer(*a)
+
+    def modules(self):
+        return [self.mod]
+
+    def sync(self):
+        self.mod.sync()
+
+    def close(self):
+        self.mod.close()
+
+
+def cpu_baseline_single(wl_name, sample_batch):
+    """The CPU oracle on the single-module workload at a reduced batch: K warm-up iterations
+    (fill the ring), then one steady-state forward + delayed backward + update."""
+    import numpy as np
+    import workloads as wk
+    from oracle import ddg_oracle as orc
+    wl = wk.get_workload(wl_name, batch=sample_batch)
+    m = wl.modules[0]
+    net = orc.OracleNet.from_workload(wl, dtype="f32", store_bf16=False)
+    net.set_params(m.k, wk.init_module_params(wl, m))
+    shape_in = (wl.batch, m.in_c, m.in_h, m.in_w)
+    h = wk.normal(wl.seed, 100, int(np.prod(shape_in))).reshape(shape_in)
+    delta = wk.synthetic_delta(wl, m, 0)
+    def one(t):
+        net.forward(m.k, t, h)
+        net.backward_delayed(m.k, t, delta, None, in_shape=shape_in)
+        net.update(m.k, wl.lr)
+    for t in range(wl.K):
+        one(t)
+    t0 = time.perf_counter()
+    one(wl.K)
+    dt = time.perf_counter() - t0
+    return {"value": sample_batch / dt, "unit": "images/sec", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{wl_name} at batch {sample_batch} (of {wk.get_workload(wl_name).batch}), "
+                      f"1 steady-state step after {wl.K} warm-up steps, fp32 oracle"}
+
+
 def cpu_baseline(wl_name, sample_batch, timed_steps=1):
     """The CPU oracle (fp32 instance, as it stands) on a bounded sample of the workload:
     the same network and module split at a reduced batch, K warm-up iterations to fill the
@@ -123,9 +200,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = wk.get_workload(args.workload)
-    if wl.single_module:
-        raise SystemExit("bench.py times full pipelines; single-module workloads are parity cases")
-    pipe, streams = build_pipeline(wl, args.serial, args.forward_streams, args.stale_jacobian)
+    single = SingleModule(wl, args.stale_jacobian, args.forward_streams) if wl.single_module else None
+    if single:
+        pipe = single
+    else:
+        pipe, streams = build_pipeline(wl, args.serial, args.forward_streams, args.stale_jacobian)
     if args.optimizer == "adam":
         import paper_1804_10574_amd as ddg
         pipe.set_optimizer(ddg.DDG_OPT_ADAM, 0.9, 0.999, 1e-8)
@@ -133,7 +212,7 @@ def main():
     # a few distinct minibatches, resident in HBM before the timed region
     nbuf = 4
     xs, ys = [], []
-    for i in range(nbuf):
+    for i in range(0 if single else nbuf):
         x, y = wk.minibatch(wl, i)
         xs.append(torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1))).to(torch.float32).cuda().to(tdt).contiguous())
         ys.append(torch.from_numpy(y).cuda())
@@ -141,7 +220,10 @@ def main():
     torch.cuda.synchronize()
 
     def step(i):
-        pipe.step(xs[i % nbuf], ys[i % nbuf], wl.lr, loss)
+        if single:
+            single.step(i)
+        else:
+            pipe.step(xs[i % nbuf], ys[i % nbuf], wl.lr, loss)
 
     it = 0
     for _ in range(wl.K + args.warmup):      # fill the delay rings, then warm up
@@ -160,16 +242,22 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "network": wl.notes, "K": wl.K, "global_batch": wl.batch,
-                   "image": "3x32x32", "classes": wl.num_classes, "streams": 1 if args.serial else (2 * wl.K - 1 if args.forward_streams else wl.K),
+                   "image": "3x32x32", "classes": wl.num_classes, "streams": (2 if args.forward_streams else 1) if (args.serial or single) else (2 * wl.K - 1 if args.forward_streams else wl.K),
                    "optimizer": args.optimizer,
                    "gradient": "stale Jacobian (Eq. 6-7 as printed)" if args.stale_jacobian else "re-forward with current weights",
                    "parallelism": "K modules as HIP streams on one GPU"},
         "final_loss": final_loss,
     }
+    if single:
+        m = wl.modules[0]
+        out["config"].update({"image": None, "classes": None, "module": f"k={m.k} of K={wl.K} (delay {wl.K - m.k})",
+                              "module_input": f"{m.in_c}x{m.in_h}x{m.in_w}",
+                              "parallelism": "one module, one HIP stream; synthetic input and delayed error gradient"})
+        out.pop("final_loss")
 
     if not args.no_roofline:
         # second pass with per-launch HIP events on each module's stream
-        mods = [pipe.module(k) for k in range(1, wl.K + 1)]
+        mods = single.modules() if single else [pipe.module(k) for k in range(1, wl.K + 1)]
         for m in mods:
             m.profile_reset(); m.profile_enable(True)
         psteps = max(2, min(5, args.steps))
@@ -241,7 +329,8 @@ def main():
 
     pipe.close()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl.name, args.cpu_sample_batch)
+        out["cpu_baseline"] = (cpu_baseline_single(wl.name, min(args.cpu_sample_batch, 2)) if single
+                               else cpu_baseline(wl.name, args.cpu_sample_batch))
     print(json.dumps(out))
 
 

@@ -153,6 +153,24 @@ hipError_t conv_tiled_launch(const void* in, const float* scale, const float* sh
                              int vec_stride = 0, const WgradFuse* apply = nullptr, const WgradPair* pair = nullptr);
 
 
+// GEMM-class kernel for wide bf16 layers (1x1 / 3x3, stride 1, contraction channels a power of
+// two >= 64, output channels a multiple of 128): forward, or input gradient with an operand
+// packed with mirrored taps. in [N*H*W][IC], out [N*H*W][OC], wpack as for conv_launch;
+// stat_partial (optional): [conv_wide_rows(M)][2][OC] sums / sums of squares of the stored
+// values; add_g / add_mask as in ConvArgs.
+bool conv_wide_ok(int IC, int OC, int R, int stride, int dtype);
+int conv_wide_rows(int M);
+hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* add_g,
+                            const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s);
+
+// Weight gradient of the same wide layers (Cin a power of two >= 128, Cout a multiple of 128):
+// partial tiles [splits][Cout][R*R*Cin] over `splits` slices of the pixels, to be added by
+// wgrad_reduce_all_launch. x [N*H*W][Cin], dz [N*H*W][Cout].
+bool wgrad_wide_ok(int Cin, int Cout, int R, int stride, int dtype);
+int wgrad_wide_splits(int M, int Cin, int Cout, int R);
+hipError_t wgrad_wide_launch(const void* x, const void* dz, float* partial, int N, int H, int W, int Cin, int Cout,
+                             int R, int splits, hipStream_t s);
+
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
 // shift=beta-mean*scale.
 hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,

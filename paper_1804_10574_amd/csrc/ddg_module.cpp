@@ -38,7 +38,9 @@ enum ProfKind {
   PK_CONV_WGRAD, PK_CONV_WGRAD_T16, PK_CONV_WGRAD_T32, PK_CONV_WGRAD_T64,
   // a launch that carries an input-gradient kernel and the weight gradient of the unit above
   PK_BWD_PAIR_T16, PK_BWD_PAIR_T32, PK_BWD_PAIR_T64, PK_BWD_PAIR = PK_BWD_PAIR_T16 - 1,
-  PK_WGRAD_REDUCE = PK_BWD_PAIR_T64 + 1, PK_BN_FINALIZE, PK_BN_APPLY,
+  // the GEMM-class kernels of the wide layers
+  PK_CONV_FPROP_WIDE = PK_BWD_PAIR_T64 + 1, PK_CONV_DGRAD_WIDE, PK_CONV_WGRAD_WIDE,
+  PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
   PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_COUNT
 };
 static const char* kProfNames[PK_COUNT] = {
@@ -46,6 +48,7 @@ static const char* kProfNames[PK_COUNT] = {
   "conv_dgrad.generic", "conv_dgrad.tiled_c16_w32", "conv_dgrad.tiled_c32_w16", "conv_dgrad.tiled_c64_w8",
   "conv_wgrad.generic", "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c32_w16", "conv_wgrad.tiled_c64_w8",
   "conv_bwd_pair.tiled_c16_w32", "conv_bwd_pair.tiled_c32_w16", "conv_bwd_pair.tiled_c64_w8",
+  "conv_fprop.wide", "conv_dgrad.wide", "conv_wgrad.wide",
   "wgrad_reduce", "bn_finalize", "bn_apply",
   "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam"};
 
@@ -73,6 +76,8 @@ struct Unit {  // convolution + batch normalisation
   int fcap = 0;                 // rows reserved per group in fstat
   int frows = 0;                // rows written by the last forward conv (per group)
   // consumers finalise the partial rows themselves (their reduction is built for these widths)
+  bool wide_f = false, wide_d = false;   // the GEMM-class kernel runs the forward conv / the input gradient
+  int wide_splits = 0;                   // > 0: the GEMM-class weight-gradient kernel, this many pixel slices
   bool small_c() const { return cout == 16 || cout == 32 || cout == 64; }
   int tiled_instance() const { return cin == 16 ? 1 : cin == 32 ? 2 : 3; }   // offset of a tiled kernel's profile kind
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
@@ -336,6 +341,9 @@ ddg_status build_plan(ddg_module* m) {
       conv_plan(f);
       u.tiled_grid = conv_tiled_grid(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
       if (u.tiled_grid > 0) f.grid_x = u.tiled_grid;   // the generic kernel never runs this layer
+      u.wide_f = conv_wide_ok(u.cin, u.cout, u.R, u.stride, dt) && !getenv("DDG_NO_WIDE");
+      u.wide_d = u.has_dgrad && conv_wide_ok(u.cout, u.cin, u.R, u.stride, dt) && !getenv("DDG_NO_WIDE");
+      if (u.wide_f) f.grid_x = conv_wide_rows(f.M);
       u.fcap = f.grid_x;
       u.frows = u.fcap;    // what the forward conv of this layer writes (the same every time)
       size_t st_e = (size_t)f.grid_x * 2 * u.cout;
@@ -367,6 +375,10 @@ ddg_status build_plan(ddg_module* m) {
       wgrad_plan(wgd);
       u.wg_tiled_rows = wgrad_tiled_rows(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
       if (u.wg_tiled_rows > 0) wgd.msplit = u.wg_tiled_rows;  // the reduce kernel sums this many rows
+      if (wgrad_wide_ok(u.cin, u.cout, u.R, u.stride, dt) && !getenv("DDG_NO_WIDE")) {
+        u.wide_splits = wgrad_wide_splits(wgd.M, u.cin, u.cout, u.R);
+        wgd.msplit = u.wide_splits;
+      }
       { void* wp = nullptr;
         DDG_OKAY(dev_alloc(m, &wp, wgrad_partial_elems(wgd) * sizeof(float)));
         u.wg_partial = (float*)wp; }
@@ -430,7 +442,7 @@ ddg_status build_plan(ddg_module* m) {
       for (int mode = 0; mode < 2; ++mode) {
         if (mode == 1 && !u.has_dgrad) continue;
         PackDesc d{};
-        const int md = mode == 0 ? 0 : (u.tiled_grid > 0 ? 2 : 1);
+        const int md = mode == 0 ? 0 : ((u.tiled_grid > 0 || u.wide_d) ? 2 : 1);
         const int kc = md ? u.cout : u.cin, nc = md ? u.cin : u.cout;
         d.W = m->theta + u.ow; d.wpack = mode == 0 ? u.wpack_f : u.wpack_d;
         d.Cout = u.cout; d.Cin = u.cin; d.R = u.R; d.mode = md;
@@ -539,12 +551,18 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
                               u.cin, G * u.tiled_grid, m->stream, res, y_store, G, src ? src->vec_stride() : 0));
   } else {
     if (src) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
-    ConvArgs a = u.fprop;
-    conv_plan(a);
-    u.frows = a.grid_x;
-    a.in = in; a.wpack = u.wpack_f; a.out = z; a.stat_partial = fstat; a.add_g = nullptr; a.add_mask = nullptr;
-    Launch L(m, PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
-    DDG_TRY(conv_launch(a, m->stream));
+    if (u.wide_f) {
+      u.frows = conv_wide_rows(u.N * u.P * u.Q);
+      Launch L(m, PK_CONV_FPROP_WIDE, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
+      DDG_TRY(conv_wide_launch(in, u.wpack_f, z, fstat, nullptr, nullptr, u.N, u.H, u.W, u.cin, u.cout, u.R, m->stream));
+    } else {
+      ConvArgs a = u.fprop;
+      conv_plan(a);
+      u.frows = a.grid_x;
+      a.in = in; a.wpack = u.wpack_f; a.out = z; a.stat_partial = fstat; a.add_g = nullptr; a.add_mask = nullptr;
+      Launch L(m, PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
+      DDG_TRY(conv_launch(a, m->stream));
+    }
   }
   if (!u.small_c()) {
     Launch L(m, PK_BN_FINALIZE);
@@ -824,8 +842,11 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
       DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
     }
     if (x_scale) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
-    Launch L(m, PK_CONV_WGRAD, (u.in_elems() + E) * (double)m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
-    DDG_TRY(wgrad_launch(w, m->stream));
+    Launch L(m, u.wide_splits > 0 ? PK_CONV_WGRAD_WIDE : PK_CONV_WGRAD, (u.in_elems() + E) * (double)m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
+    if (u.wide_splits > 0)
+      DDG_TRY(wgrad_wide_launch(x_in, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.cout, u.R, u.wide_splits, m->stream));
+    else
+      DDG_TRY(wgrad_launch(w, m->stream));
   }
   if (dx) {
     // reads dz and the weights, writes dx; plus the shortcut term (and its mask), plus the mask
@@ -833,8 +854,11 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     const bool fuse_below = u.tiled_grid > 0 && below && below->u;
     double extra = (add_g ? (add_mask ? 2.0 : 1.0) : 0.0);
     if (fuse_below) extra += (below->mask == below->u->z) ? 1.0 : 2.0;
-    Launch L(m, PK_CONV_DGRAD + (u.tiled_grid > 0 ? u.tiled_instance() : 0), (E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u), conv_flops(u));
-    if (u.tiled_grid > 0) {
+    Launch L(m, u.tiled_grid > 0 ? PK_CONV_DGRAD + u.tiled_instance() : (u.wide_d ? PK_CONV_DGRAD_WIDE : PK_CONV_DGRAD),
+             (E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u), conv_flops(u));
+    if (u.tiled_grid == 0 && u.wide_d) {
+      DDG_TRY(conv_wide_launch(dz_buf, u.wpack_d, dx, nullptr, add_g, add_mask, u.N, u.P, u.Q, u.cout, u.cin, u.R, m->stream));
+    } else if (u.tiled_grid > 0) {
       ConvStat st{};
       if (below && below->u) {
         st.mode = 2; st.partial = below->u->bstat;

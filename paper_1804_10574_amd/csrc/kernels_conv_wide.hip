@@ -1,0 +1,261 @@
+// Convolution (forward and input-gradient) for wide bf16 layers: 1x1 and 3x3, stride 1,
+// contraction channels a power of two >= 64, output channels a multiple of 128 (the bottleneck
+// stage of an ImageNet-shaped ResNet: 1024 -> 256 -> 256 -> 1024 at 14x14). These layers are
+// matrix-core bound, so this is a GEMM-class kernel: a workgroup owns a 64-pixel x 128-channel
+// output tile and walks over the contraction in chunks of 64 channels of one tap.
+//
+//   pixel operand:  64 rows x 64 channels per chunk, staged in LDS (row stride 144 bytes, so
+//                   the 16 rows of a fragment read fall into distinct bank groups); a 3x3 tap
+//                   is a shifted pixel row, out-of-image rows are zero: no im2col matrix.
+//   weight operand: the packed operand of the generic kernel is already fragment-ordered
+//                   ([k-step][16-channel block][lane][8]), so a chunk's 128 channels x 64 k is
+//                   16 fragments of 1 KiB that are copied to LDS as they lie (fragment reads are
+//                   lane-contiguous, conflict-free).
+//   Both go through registers into one of two LDS buffers; the global loads of a chunk are
+//   issued four chunks ahead (four named register sets), one barrier per chunk.
+//
+// Eight waves: 2 (pixels) x 2 (channels) x 2 (the two 32-channel k-steps of a chunk). A wave
+// owns 32 pixels x 64 channels = 8 accumulator tiles of mfma_f32_16x16x32_bf16 (weights as
+// rows, so a lane holds 4 consecutive channels of one pixel) for its half of the contraction;
+// two waves per SIMD let one wave's LDS and global traffic run under the other's MFMAs. The epilogue passes the tile through LDS so that stores (and the optional masked
+// shortcut-gradient term) are 16-byte accesses along the channels, and accumulates the
+// batch-norm statistics of the stored values (one partial row per 64-pixel tile).
+#include "ddg_device.h"
+#include "ddg_kernels.h"
+#include <cstdlib>
+
+namespace ddg {
+
+struct ConvWideArgs {
+  const bf16_t* in;        // [M][IC]
+  const bf16_t* wpack;     // [k-step][OC/16][64][8], k = tap*IC + channel
+  bf16_t* out;             // [M][OC]
+  float* stat_partial;     // [gridDim.x][2][OC] or null
+  const bf16_t* add_g;     // optional: out += add_g (where add_mask > 0, if given)
+  const bf16_t* add_mask;
+  int M, H, W, HW, IC, OC, R;
+};
+
+namespace wide {
+constexpr int BM = 64, BN = 128, BK = 64;
+constexpr int PROW = BK * 2 + 16;                 // bytes per staged pixel row
+constexpr int P_BYTES = BM * PROW;                // 9216
+constexpr int W_BYTES = (BN / 16) * (BK / 32) * 1024;   // 16 fragments
+constexpr int BUF = P_BYTES + W_BYTES;            // 25600
+constexpr int LDS = 2 * BUF;
+}
+
+// Registers that hold a thread's share of one chunk on its way from global memory to LDS.
+struct WideChunk { uint4 p0, w0, w1; bool ok; };
+
+template <bool STATS>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void conv_wide_kernel(ConvWideArgs a) {
+  using namespace wide;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, lg = lane >> 4;
+  const int wm = wave & 1, wn = (wave >> 1) & 1, kg = wave >> 2;   // pixel half, channel half, k-step of a chunk
+  const int m0 = blockIdx.x * BM;
+  const int OCB = a.OC >> 4;
+  const int cb0 = blockIdx.y * (BN / 16);
+  const int cpt = a.IC / BK;                      // chunks per tap
+  const int nchunks = a.R * a.R * cpt;
+
+  // ---- staging map of the pixel operand: row tid/8, 16-byte chunk tid%8
+  const int pc = tid & 7, prow = tid >> 3;
+  const int mA = m0 + prow;
+  const bool vA = mA < a.M;
+  const int remA = (vA ? mA : 0) % a.HW;
+  const int hA = remA / a.W, wA = remA - hA * a.W;
+  const int baseA = (vA ? mA : 0) * a.IC + pc * 8;
+  const bf16_t* wsrc = a.wpack + ((size_t)cb0 * 64) * 8 + tid * 8;
+  const size_t wstep = (size_t)OCB * 64 * 8;      // elements per k-step of the packed operand
+
+  // Chunk kc: 64 channels of one tap. The loads of a chunk are issued four chunks before it is
+  // needed (the memory latency is several times the time a chunk takes to contract). Nothing
+  // here is conditional, so that the compiler can count the loads in flight and wait only for
+  // the oldest: a row outside the image loads its own pixel instead and is zeroed when it is
+  // written to LDS; a chunk index past the end repeats the last chunk (never used).
+  auto issue = [&](WideChunk& r, int kc_want) __attribute__((always_inline)) {
+    const int kc = kc_want < nchunks ? kc_want : nchunks - 1;
+    const int tap = kc / cpt, c0 = (kc - tap * cpt) * BK;
+    int dr = 0, ds = 0;
+    if (a.R == 3) { dr = tap / 3 - 1; ds = tap - (tap / 3) * 3 - 1; }
+    const int sh = (dr * a.W + ds) * a.IC;
+    r.ok = vA && hA + dr >= 0 && hA + dr < a.H && wA + ds >= 0 && wA + ds < a.W;
+    r.p0 = *reinterpret_cast<const uint4*>(a.in + baseA + c0 + (r.ok ? sh : 0));
+    // 16-byte unit tid of the 8 fragments of each of the chunk's two k-steps
+    const bf16_t* wa = wsrc + (size_t)(kc * 2) * wstep;
+    r.w0 = *reinterpret_cast<const uint4*>(wa);
+    r.w1 = *reinterpret_cast<const uint4*>(wa + wstep);
+  };
+  auto stash = [&](const WideChunk& r, int buf) __attribute__((always_inline)) {
+    unsigned char* P = smem + buf * BUF;
+    unsigned char* Wt = P + P_BYTES;
+    *reinterpret_cast<uint4*>(P + prow * PROW + pc * 16) = r.ok ? r.p0 : make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(Wt + tid * 16) = r.w0;
+    *reinterpret_cast<uint4*>(Wt + (tid + 512) * 16) = r.w1;
+  };
+
+  f32x4_t acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  // this wave's k-step of every chunk: waves 0-3 take the first 32 channels, waves 4-7 the rest
+  const int poff = (wm * 32 + l16) * PROW + lg * 16 + kg * 64;             // + i*16*PROW
+  const int woff = P_BYTES + ((kg * 8 + wn * 4) * 64 + lane) * 16;         // + j*1024
+  auto contract = [&](int buf) __attribute__((always_inline)) {
+    const unsigned char* B = smem + buf * BUF;
+    uint4 pf[2], wf[4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) pf[i] = *reinterpret_cast<const uint4*>(B + poff + i * 16 * PROW);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wf[j] = *reinterpret_cast<const uint4*>(B + woff + j * 1024);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = Mma<bf16_t>::mma(wf[j], pf[i], acc[i][j]);
+  };
+
+  // Register set c % 2 carries chunk c. At the top of iteration c: LDS buffer c % 2 holds chunk c,
+  // the sets hold chunks c+1 and c+2 (requested, maybe arrived). The loop body is written out
+  // twice so that every set is a named variable.
+  WideChunk r0, r1;
+  issue(r0, 0);
+  stash(r0, 0);
+  issue(r1, 1);
+  issue(r0, 2);
+  __syncthreads();
+  // one iteration: move chunk c+1 from its registers to the other LDS buffer (free since the
+  // barrier that ended iteration c-1), request chunk c+3 into the registers just freed, contract
+  // chunk c
+#define DDG_WIDE_STEP(c, rnext)                         \
+  {                                                     \
+    if ((c) + 1 < nchunks) stash(rnext, ((c) + 1) & 1); \
+    issue(rnext, (c) + 3);                              \
+    contract((c) & 1);                                  \
+    __syncthreads();                                    \
+  }
+  for (int kc = 0; kc < nchunks; kc += 2) {
+    DDG_WIDE_STEP(kc, r1)
+    if (kc + 1 >= nchunks) break;
+    DDG_WIDE_STEP(kc + 1, r0)
+  }
+#undef DDG_WIDE_STEP
+
+  // ---- epilogue. The accumulators (lane = pixel wm*32 + i*16 + l16, channels (wn*4 + j)*16 +
+  // lg*4 .. +3) go through LDS as fp32 [64 pixels][128 channels]: the two wave groups add their
+  // halves of the contraction there (first group, then second: a fixed order), and memory then
+  // sees 16-byte accesses, 256 contiguous bytes per pixel: thread = pixels (tid>>4) + 32*q,
+  // channels (tid&15)*8 .. +7
+  constexpr int OROW = BN * 4 + 16;               // bytes per pixel row of the fp32 tile
+  static_assert(BM * OROW <= LDS, "output tile fits the operand buffers");
+  if (kg == 0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<f32x4_t*>(smem + (wm * 32 + i * 16 + l16) * OROW + ((wn * 4 + j) * 16 + lg * 4) * 4) = acc[i][j];
+  }
+  __syncthreads();
+  if (kg == 1) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        f32x4_t* p = reinterpret_cast<f32x4_t*>(smem + (wm * 32 + i * 16 + l16) * OROW + ((wn * 4 + j) * 16 + lg * 4) * 4);
+        *p = *p + acc[i][j];
+      }
+  }
+  __syncthreads();
+  const int oc = tid & 15, orow = tid >> 4;       // orow 0..31
+  float ssum[8], ssq[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { ssum[e] = 0.f; ssq[e] = 0.f; }
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int row = orow + 32 * q, m = m0 + row;
+    if (m < a.M) {
+      float v[8];
+      *reinterpret_cast<float4*>(&v[0]) = *reinterpret_cast<const float4*>(smem + row * OROW + oc * 32);
+      *reinterpret_cast<float4*>(&v[4]) = *reinterpret_cast<const float4*>(smem + row * OROW + oc * 32 + 16);
+      const size_t idx = (size_t)m * a.OC + cb0 * 16 + oc * 8;
+      if (a.add_g) {
+        float g[8];
+        Store<bf16_t>::unpack_vec(*reinterpret_cast<const uint4*>(a.add_g + idx), g);
+        if (a.add_mask) {
+          float mk[8];
+          Store<bf16_t>::unpack_vec(*reinterpret_cast<const uint4*>(a.add_mask + idx), mk);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) g[e] = mk[e] > 0.f ? g[e] : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += g[e];
+      }
+      uint4 o;
+      o.x = Store<bf16_t>::pack2(v[0], v[1]); o.y = Store<bf16_t>::pack2(v[2], v[3]);
+      o.z = Store<bf16_t>::pack2(v[4], v[5]); o.w = Store<bf16_t>::pack2(v[6], v[7]);
+      *reinterpret_cast<uint4*>(a.out + idx) = o;
+      if (STATS) {
+        float r[8];
+        Store<bf16_t>::unpack_vec(o, r);            // the values as stored
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { ssum[e] += r[e]; ssq[e] += r[e] * r[e]; }
+      }
+    }
+  }
+  if (STATS) {
+    // per channel: the 32 row classes in a fixed order
+    __syncthreads();                               // the fp32 tile has been read
+    float* red = reinterpret_cast<float*>(smem);   // [32 row classes][2][128]
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      red[(orow * 2 + 0) * BN + oc * 8 + e] = ssum[e];
+      red[(orow * 2 + 1) * BN + oc * 8 + e] = ssq[e];
+    }
+    __syncthreads();
+    if (tid < 2 * BN) {
+      const int which = tid / BN, c = tid % BN;
+      float s = 0.f;
+#pragma unroll
+      for (int r = 0; r < 32; ++r) s += red[(r * 2 + which) * BN + c];
+      a.stat_partial[((size_t)blockIdx.x * 2 + which) * a.OC + cb0 * 16 + c] = s;
+    }
+  }
+}
+
+// Shapes the kernel covers (the module code asks before it plans a layer).
+bool conv_wide_ok(int IC, int OC, int R, int stride, int dtype) {
+  if (dtype != BF16 || stride != 1 || (R != 1 && R != 3)) return false;
+  if (IC < 64 || (IC & (IC - 1)) != 0) return false;      // power of two: k = tap*IC + channel in the packed operand
+  return OC % wide::BN == 0;
+}
+int conv_wide_rows(int M) { return (M + wide::BM - 1) / wide::BM; }
+
+hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* add_g,
+                            const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s) {
+  if (!conv_wide_ok(IC, OC, R, 1, BF16)) return hipErrorInvalidValue;
+  const size_t M = (size_t)N * H * W;
+  if (M * (size_t)(IC > OC ? IC : OC) >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside
+  ConvWideArgs a{};
+  a.in = (const bf16_t*)in; a.wpack = (const bf16_t*)wpack; a.out = (bf16_t*)out; a.stat_partial = stat_partial;
+  a.add_g = (const bf16_t*)add_g; a.add_mask = (const bf16_t*)add_mask;
+  a.M = (int)M; a.H = H; a.W = W; a.HW = H * W; a.IC = IC; a.OC = OC; a.R = R;
+  const dim3 grid(conv_wide_rows((int)M), OC / wide::BN);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wide_kernel<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wide_kernel<false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  if (stat_partial) DDG_LAUNCH(conv_wide_kernel<true>, grid, dim3(512), wide::LDS, s, a);
+  else DDG_LAUNCH(conv_wide_kernel<false>, grid, dim3(512), wide::LDS, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace ddg

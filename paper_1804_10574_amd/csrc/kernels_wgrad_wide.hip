@@ -1,0 +1,188 @@
+// Weight gradient of wide bf16 layers (1x1 and 3x3, stride 1; input and output channels
+// multiples of 128): the companion of conv_wide_kernel.
+//
+//   dW[co][tap][ci] = sum over pixels p of dz[p][co] * x[pix(p, tap)][ci]
+//
+// A GEMM whose contraction index, the pixel, is the slow index of both NHWC operands. A
+// workgroup owns a 128 (co) x 128 (ci) tile of one tap and a slice of the pixels; it stages
+// 64 pixels of both operands per step exactly as they lie in memory ([pixel][128 channels],
+// row stride 288 bytes) and takes MFMA fragments out of LDS with the transposing read of
+// gfx950 (ds_read_b64_tr_b16: a lane ends up with 8 consecutive pixels of one channel). A tap
+// is a shifted pixel row with zeros outside the image. Global loads of the next 64 pixels are
+// in flight while the current ones are contracted (double-buffered through registers).
+//
+// Four waves as 2 (co) x 2 (ci), 64 x 64 each = 16 accumulator tiles of
+// mfma_f32_16x16x32_bf16. The pixel slices (split-K) give the launch enough workgroups; each
+// writes an fp32 partial tile [split][co][tap*Cin + ci], which wgrad_reduce_all_kernel adds in
+// a fixed order (deterministic).
+#include "ddg_device.h"
+#include "ddg_kernels.h"
+#include <cstdlib>
+
+namespace ddg {
+
+struct WgradWideArgs {
+  const bf16_t* x;       // [M][Cin]
+  const bf16_t* dz;      // [M][Cout]
+  float* partial;        // [splits][Cout][J], J = taps*Cin
+  int M, H, W, HW, Cin, Cout, R, J;
+  int steps_per_split;   // 64-pixel steps per split
+  int nsteps;            // ceil(M/64)
+  int cit, taps;         // Cin/128, R*R: blockIdx.x = (cot*taps + tap)*cit + ci tile
+};
+
+namespace wgw {
+constexpr int BP = 64;                     // pixels per step
+constexpr int ROW = 256 + 32;              // bytes per staged pixel (128 channels), 32 modulo 128
+constexpr int OPB = BP * ROW;              // one operand, one buffer: 18432
+constexpr int BUF = 2 * OPB;
+constexpr int LDS = 2 * BUF;               // 73728
+}
+
+typedef short wtr4_t __attribute__((ext_vector_type(4)));
+// 8-pixel fragment of one channel per lane: two transposing reads 4 pixels apart
+__device__ __forceinline__ uint4 wide_frag_tr(const unsigned char* p) {
+  typedef wtr4_t __attribute__((address_space(3))) * lds_ptr_t;
+  const wtr4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+  const wtr4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * wgw::ROW));
+  const uint2 l = __builtin_bit_cast(uint2, lo), h = __builtin_bit_cast(uint2, hi);
+  return make_uint4(l.x, l.y, h.x, h.y);
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void wgrad_wide_kernel(WgradWideArgs a) {
+  using namespace wgw;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, lg = lane >> 4;
+  const int wa = wave & 1, wb = wave >> 1;           // co half, ci half
+  const int cit = blockIdx.x % a.cit;
+  const int tap = (blockIdx.x / a.cit) % a.taps;
+  const int cot = blockIdx.x / (a.cit * a.taps);
+  const int co0 = cot * 128, ci0 = cit * 128;
+  int dr = 0, ds = 0;
+  if (a.R == 3) { dr = tap / 3 - 1; ds = tap - (tap / 3) * 3 - 1; }
+  const int s0 = blockIdx.y * a.steps_per_split;
+  const int s1 = (s0 + a.steps_per_split < a.nsteps) ? s0 + a.steps_per_split : a.nsteps;
+
+  // staging map: 16-byte unit tid + q*256 of a 64 x 128 tile = pixel (tid>>4) + 16*q, chunk tid&15
+  const int ch = tid & 15, prow = tid >> 4;
+  const int xshift = (dr * a.W + ds) * a.Cin;
+  uint4 z0, z1, z2, z3, x0, x1, x2, x3;   // (named: arrays here are not promoted to registers)
+  auto ldz = [&](int m) __attribute__((always_inline)) {
+    return m < a.M ? *reinterpret_cast<const uint4*>(a.dz + (size_t)m * a.Cout + co0 + ch * 8) : make_uint4(0, 0, 0, 0);
+  };
+  auto ldx = [&](int m) __attribute__((always_inline)) {
+    if (m >= a.M) return make_uint4(0, 0, 0, 0);
+    const int rem = m % a.HW;
+    const int h = rem / a.W + dr, w = rem % a.W + ds;
+    if (h < 0 || h >= a.H || w < 0 || w >= a.W) return make_uint4(0, 0, 0, 0);
+    return *reinterpret_cast<const uint4*>(a.x + (size_t)m * a.Cin + xshift + ci0 + ch * 8);
+  };
+  auto issue = [&](int step) __attribute__((always_inline)) {
+    const int m = step * BP + prow;
+    z0 = ldz(m); z1 = ldz(m + 16); z2 = ldz(m + 32); z3 = ldz(m + 48);
+    x0 = ldx(m); x1 = ldx(m + 16); x2 = ldx(m + 32); x3 = ldx(m + 48);
+  };
+  auto stash = [&](int buf) __attribute__((always_inline)) {
+    unsigned char* Z = smem + buf * BUF + prow * ROW + ch * 16;
+    unsigned char* X = Z + OPB;
+    *reinterpret_cast<uint4*>(Z) = z0; *reinterpret_cast<uint4*>(Z + 16 * ROW) = z1;
+    *reinterpret_cast<uint4*>(Z + 32 * ROW) = z2; *reinterpret_cast<uint4*>(Z + 48 * ROW) = z3;
+    *reinterpret_cast<uint4*>(X) = x0; *reinterpret_cast<uint4*>(X + 16 * ROW) = x1;
+    *reinterpret_cast<uint4*>(X + 32 * ROW) = x2; *reinterpret_cast<uint4*>(X + 48 * ROW) = x3;
+  };
+
+  f32x4_t acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  // fragment address of (k-step 0, channel block 0): lane s of a 16-lane block points at
+  // channels 4*(s%4).. of pixel lg*8 + s/4; the second read is 4 pixels further
+  const int frag = (lg * 8 + (l16 >> 2)) * ROW + (l16 & 3) * 8;
+  const int zoff = frag + wa * 128;            // + i*32 (channel block) + ks*32*ROW
+  const int xoff = OPB + frag + wb * 128;
+
+  if (s0 < s1) {
+    issue(s0);
+    stash(0);
+  }
+  __syncthreads();
+  for (int s = s0; s < s1; ++s) {
+    const bool more = s + 1 < s1;
+    if (more) issue(s + 1);
+    const unsigned char* B = smem + ((s - s0) & 1) * BUF;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      uint4 zf[4], xf[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) zf[i] = wide_frag_tr(B + zoff + i * 32 + ks * 32 * ROW);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) xf[j] = wide_frag_tr(B + xoff + j * 32 + ks * 32 * ROW);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = Mma<bf16_t>::mma(zf[i], xf[j], acc[i][j]);
+    }
+    if (more) stash((s + 1 - s0) & 1);
+    __syncthreads();
+  }
+
+  // lane (l16, lg) of tile (i, j) holds co = co0 + (wa*4 + i)*16 + lg*4 + e, ci = ci0 + (wb*4 + j)*16 + l16
+  float* dst = a.partial + ((size_t)blockIdx.y * a.Cout + co0 + wa * 64 + lg * 4) * a.J + (size_t)tap * a.Cin + ci0 + wb * 64 + l16;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dst[(size_t)(i * 16 + e) * a.J + j * 16] = acc[i][j][e];
+}
+
+bool wgrad_wide_ok(int Cin, int Cout, int R, int stride, int dtype) {
+  if (dtype != BF16 || stride != 1 || (R != 1 && R != 3)) return false;
+  if (Cin < 128 || (Cin & (Cin - 1)) != 0) return false;   // power of two: the partial tile's column is tap*Cin + ci
+  return Cout % 128 == 0;
+}
+
+// Number of pixel slices (= partial tiles per output element) for a layer: enough workgroups to
+// fill the GPU (about two per compute unit), at least 2 steps of 64 pixels each.
+// DDG_TUNE_WGRAD_WIDE_WGS overrides the target workgroup count within [64, 2048].
+int wgrad_wide_splits(int M, int Cin, int Cout, int R) {
+  int target = 512;
+  if (const char* e = getenv("DDG_TUNE_WGRAD_WIDE_WGS")) {
+    const int v = atoi(e);
+    if (v >= 64 && v <= 2048) target = v;
+  }
+  const int tiles = (Cout / 128) * (Cin / 128) * R * R;
+  const int nsteps = (M + wgw::BP - 1) / wgw::BP;
+  int splits = (target + tiles - 1) / tiles;
+  if (splits > nsteps / 2) splits = nsteps / 2;
+  if (splits < 1) splits = 1;
+  const int sps = (nsteps + splits - 1) / splits;
+  return (nsteps + sps - 1) / sps;     // no empty slice
+}
+
+hipError_t wgrad_wide_launch(const void* x, const void* dz, float* partial, int N, int H, int W, int Cin, int Cout,
+                             int R, int splits, hipStream_t s) {
+  if (!wgrad_wide_ok(Cin, Cout, R, 1, BF16) || splits < 1) return hipErrorInvalidValue;
+  WgradWideArgs a{};
+  a.x = (const bf16_t*)x; a.dz = (const bf16_t*)dz; a.partial = partial;
+  a.M = N * H * W; a.H = H; a.W = W; a.HW = H * W; a.Cin = Cin; a.Cout = Cout; a.R = R; a.J = R * R * Cin;
+  a.nsteps = (a.M + wgw::BP - 1) / wgw::BP;
+  a.steps_per_split = (a.nsteps + splits - 1) / splits;
+  if ((size_t)(splits - 1) * a.steps_per_split >= (size_t)a.nsteps) return hipErrorInvalidValue;   // an empty slice
+  a.cit = Cin / 128; a.taps = R * R;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_wide_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, wgw::LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const dim3 grid((Cout / 128) * a.taps * a.cit, splits);
+  DDG_LAUNCH(wgrad_wide_kernel, grid, dim3(256), wgw::LDS, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace ddg
