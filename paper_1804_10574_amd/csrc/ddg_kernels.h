@@ -160,16 +160,20 @@ hipError_t conv_tiled_launch(const void* in, const float* scale, const float* sh
 // values; add_g / add_mask as in ConvArgs.
 bool conv_wide_ok(int IC, int OC, int R, int stride, int dtype);
 int conv_wide_rows(int M);
+// scale/shift (optional, forward only): the conv input is relu(in*scale + shift) per input
+// channel, applied while staging.
 hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* add_g,
-                            const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s);
+                            const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s,
+                            const float* scale = nullptr, const float* shift = nullptr);
 
 // Weight gradient of the same wide layers (Cin a power of two >= 128, Cout a multiple of 128):
 // partial tiles [splits][Cout][R*R*Cin] over `splits` slices of the pixels, to be added by
 // wgrad_reduce_all_launch. x [N*H*W][Cin], dz [N*H*W][Cout].
 bool wgrad_wide_ok(int Cin, int Cout, int R, int stride, int dtype);
 int wgrad_wide_splits(int M, int Cin, int Cout, int R);
+// scale/shift (optional): x is relu(x*scale + shift) per input channel, applied while staging.
 hipError_t wgrad_wide_launch(const void* x, const void* dz, float* partial, int N, int H, int W, int Cin, int Cout,
-                             int R, int splits, hipStream_t s);
+                             int R, int splits, hipStream_t s, const float* scale = nullptr, const float* shift = nullptr);
 
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
 // shift=beta-mean*scale.

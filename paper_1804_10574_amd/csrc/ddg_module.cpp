@@ -396,7 +396,11 @@ ddg_status build_plan(ddg_module* m) {
       // the activation between two units is materialised only if the consumer cannot derive
       // it from the producer's conv output while loading
       void* a = nullptr;
-      if (b.u[ui + 1].tiled_grid == 0) DDG_OKAY(dev_alloc(m, &a, m->groups * b.u[ui].out_elems() * m->esz));
+      const Unit& cons = b.u[ui + 1];
+      // the consumer's forward conv and weight gradient both transform while staging (the wide
+      // kernels read final scale/shift vectors, which a producer with more than 64 channels has)
+      const bool on_load = cons.tiled_grid > 0 || (cons.wide_f && cons.wide_splits > 0 && !b.u[ui].small_c());
+      if (!on_load) DDG_OKAY(dev_alloc(m, &a, m->groups * b.u[ui].out_elems() * m->esz));
       b.act.push_back(a);
     }
     b.y_elems = b.u[b.nmain - 1].out_elems();
@@ -550,11 +554,13 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
                               from_rows ? &ir : nullptr, u.wpack_f, z, st, nullptr, nullptr, G * u.N, u.H, u.W,
                               u.cin, G * u.tiled_grid, m->stream, res, y_store, G, src ? src->vec_stride() : 0));
   } else {
-    if (src) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
+    if (src && !u.wide_f) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
     if (u.wide_f) {
       u.frows = conv_wide_rows(u.N * u.P * u.Q);
+      const int svo = src ? g * src->vec_stride() : 0;   // (a wide producer's vectors are final: it ran its finalise launch)
       Launch L(m, PK_CONV_FPROP_WIDE, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
-      DDG_TRY(conv_wide_launch(in, u.wpack_f, z, fstat, nullptr, nullptr, u.N, u.H, u.W, u.cin, u.cout, u.R, m->stream));
+      DDG_TRY(conv_wide_launch(in, u.wpack_f, z, fstat, nullptr, nullptr, u.N, u.H, u.W, u.cin, u.cout, u.R, m->stream,
+                               src ? src->scale + svo : nullptr, src ? src->shift + svo : nullptr));
     } else {
       ConvArgs a = u.fprop;
       conv_plan(a);
@@ -841,10 +847,11 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
       Launch L(m, PK_BN_BWD_APPLY, (mask && mask != u.z ? 4.0 : 3.0) * E * m->esz);
       DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
     }
-    if (x_scale) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
+    if (x_scale && u.wide_splits == 0) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
     Launch L(m, u.wide_splits > 0 ? PK_CONV_WGRAD_WIDE : PK_CONV_WGRAD, (u.in_elems() + E) * (double)m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
     if (u.wide_splits > 0)
-      DDG_TRY(wgrad_wide_launch(x_in, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.cout, u.R, u.wide_splits, m->stream));
+      DDG_TRY(wgrad_wide_launch(x_in, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.cout, u.R, u.wide_splits, m->stream,
+                                x_scale, x_shift));
     else
       DDG_TRY(wgrad_launch(w, m->stream));
   }

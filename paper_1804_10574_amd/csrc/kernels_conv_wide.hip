@@ -33,6 +33,8 @@ struct ConvWideArgs {
   float* stat_partial;     // [gridDim.x][2][OC] or null
   const bf16_t* add_g;     // optional: out += add_g (where add_mask > 0, if given)
   const bf16_t* add_mask;
+  const float* scale;      // optional (XFORM kernels): the conv input is relu(in*scale + shift), per input channel
+  const float* shift;
   int M, H, W, HW, IC, OC, R;
 };
 
@@ -48,7 +50,9 @@ constexpr int LDS = 2 * BUF;
 // Registers that hold a thread's share of one chunk on its way from global memory to LDS.
 struct WideChunk { uint4 p0, w0, w1; bool ok; };
 
-template <bool STATS>
+// XFORM: the input is turned into the activation it stands for, relu(in*scale + shift) (batch
+// norm + ReLU of the layer before), while it is written to LDS; zero padding comes after that.
+template <bool STATS, bool XFORM>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void conv_wide_kernel(ConvWideArgs a) {
   using namespace wide;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -58,7 +62,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   const int m0 = blockIdx.x * BM;
   const int OCB = a.OC >> 4;
   const int cb0 = blockIdx.y * (BN / 16);
-  const int cpt = a.IC / BK;                      // chunks per tap
+  const int cpt = a.IC / BK;                      // chunks per tap (a power of two)
+  const int l2cpt = 31 - __clz(cpt);
   const int nchunks = a.R * a.R * cpt;
 
   // ---- staging map of the pixel operand: row tid/8, 16-byte chunk tid%8
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   // written to LDS; a chunk index past the end repeats the last chunk (never used).
   auto issue = [&](WideChunk& r, int kc_want) __attribute__((always_inline)) {
     const int kc = kc_want < nchunks ? kc_want : nchunks - 1;
-    const int tap = kc / cpt, c0 = (kc - tap * cpt) * BK;
+    const int tap = kc >> l2cpt, c0 = (kc & (cpt - 1)) * BK;
     int dr = 0, ds = 0;
     if (a.R == 3) { dr = tap / 3 - 1; ds = tap - (tap / 3) * 3 - 1; }
     const int sh = (dr * a.W + ds) * a.IC;
@@ -89,10 +94,30 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
     r.w0 = *reinterpret_cast<const uint4*>(wa);
     r.w1 = *reinterpret_cast<const uint4*>(wa + wstep);
   };
-  auto stash = [&](const WideChunk& r, int buf) __attribute__((always_inline)) {
+  // XFORM: scale and shift of all input channels, after the operand buffers
+  float* tab = reinterpret_cast<float*>(smem + LDS);
+  if (XFORM) {
+    for (int c = tid; c < a.IC; c += 512) { tab[c] = a.scale[c]; tab[a.IC + c] = a.shift[c]; }
+    __syncthreads();
+  }
+  auto stash = [&](const WideChunk& r, int buf, int kc) __attribute__((always_inline)) {
     unsigned char* P = smem + buf * BUF;
     unsigned char* Wt = P + P_BYTES;
-    *reinterpret_cast<uint4*>(P + prow * PROW + pc * 16) = r.ok ? r.p0 : make_uint4(0, 0, 0, 0);
+    uint4 q = r.p0;
+    if (XFORM) {
+      const int c = (kc & (cpt - 1)) * BK + pc * 8;     // this thread's 8 input channels of chunk kc
+      float f[8], sc[8], sh[8];
+      *reinterpret_cast<float4*>(&sc[0]) = *reinterpret_cast<const float4*>(&tab[c]);
+      *reinterpret_cast<float4*>(&sc[4]) = *reinterpret_cast<const float4*>(&tab[c + 4]);
+      *reinterpret_cast<float4*>(&sh[0]) = *reinterpret_cast<const float4*>(&tab[a.IC + c]);
+      *reinterpret_cast<float4*>(&sh[4]) = *reinterpret_cast<const float4*>(&tab[a.IC + c + 4]);
+      Store<bf16_t>::unpack_vec(q, f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float t = f[e] * sc[e] + sh[e]; f[e] = t > 0.f ? t : 0.f; }
+      q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
+      q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
+    }
+    *reinterpret_cast<uint4*>(P + prow * PROW + pc * 16) = r.ok ? q : make_uint4(0, 0, 0, 0);
     *reinterpret_cast<uint4*>(Wt + tid * 16) = r.w0;
     *reinterpret_cast<uint4*>(Wt + (tid + 512) * 16) = r.w1;
   };
@@ -123,7 +148,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   // twice so that every set is a named variable.
   WideChunk r0, r1;
   issue(r0, 0);
-  stash(r0, 0);
+  stash(r0, 0, 0);
   issue(r1, 1);
   issue(r0, 2);
   __syncthreads();
@@ -132,7 +157,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   // chunk c
 #define DDG_WIDE_STEP(c, rnext)                         \
   {                                                     \
-    if ((c) + 1 < nchunks) stash(rnext, ((c) + 1) & 1); \
+    if ((c) + 1 < nchunks) stash(rnext, ((c) + 1) & 1, (c) + 1); \
     issue(rnext, (c) + 3);                              \
     contract((c) & 1);                                  \
     __syncthreads();                                    \
@@ -234,27 +259,38 @@ bool conv_wide_ok(int IC, int OC, int R, int stride, int dtype) {
 int conv_wide_rows(int M) { return (M + wide::BM - 1) / wide::BM; }
 
 hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* add_g,
-                            const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s) {
+                            const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s,
+                            const float* scale, const float* shift) {
   if (!conv_wide_ok(IC, OC, R, 1, BF16)) return hipErrorInvalidValue;
   const size_t M = (size_t)N * H * W;
   if (M * (size_t)(IC > OC ? IC : OC) >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside
   ConvWideArgs a{};
   a.in = (const bf16_t*)in; a.wpack = (const bf16_t*)wpack; a.out = (bf16_t*)out; a.stat_partial = stat_partial;
-  a.add_g = (const bf16_t*)add_g; a.add_mask = (const bf16_t*)add_mask;
+  a.add_g = (const bf16_t*)add_g; a.add_mask = (const bf16_t*)add_mask; a.scale = scale; a.shift = shift;
   a.M = (int)M; a.H = H; a.W = W; a.HW = H * W; a.IC = IC; a.OC = OC; a.R = R;
   const dim3 grid(conv_wide_rows((int)M), OC / wide::BN);
+  const bool xf = scale != nullptr;
+  if (xf && (add_g || IC > 2048)) return hipErrorInvalidValue;   // forward only; the table lives in LDS
+  const int lds = wide::LDS + (xf ? 2 * IC * (int)sizeof(float) : 0);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wide_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_wide_kernel<false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS);
-    if (e != hipSuccess) return e;
+    const void* fns[4] = {reinterpret_cast<const void*>(&conv_wide_kernel<true, false>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<false, false>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<true, true>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<false, true>)};
+    for (const void* f : fns) {
+      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS + 2 * 2048 * (int)sizeof(float));
+      if (e != hipSuccess) return e;
+    }
     attr_set = true;
   }
-  if (stat_partial) DDG_LAUNCH(conv_wide_kernel<true>, grid, dim3(512), wide::LDS, s, a);
-  else DDG_LAUNCH(conv_wide_kernel<false>, grid, dim3(512), wide::LDS, s, a);
+  if (stat_partial) {
+    if (xf) DDG_LAUNCH((conv_wide_kernel<true, true>), grid, dim3(512), lds, s, a);
+    else DDG_LAUNCH((conv_wide_kernel<true, false>), grid, dim3(512), lds, s, a);
+  } else {
+    if (xf) DDG_LAUNCH((conv_wide_kernel<false, true>), grid, dim3(512), lds, s, a);
+    else DDG_LAUNCH((conv_wide_kernel<false, false>), grid, dim3(512), lds, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -374,11 +374,92 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const T* __restrict__
   }
 }
 
+// The same operation without a loop, for final coefficients and 256*V % C == 0 (a thread's
+// channels are the same for all its vectors): a workgroup owns 256*U consecutive vectors, a
+// thread requests all its tensor data first and its per-channel constants (16-byte loads) while
+// that is in flight.
+template <typename T, int U>
+__global__ __launch_bounds__(256) void bn_bwd_apply_chunk_kernel(const T* __restrict__ dy, const T* __restrict__ mask,
+                                                                 const float* __restrict__ mscale,
+                                                                 const float* __restrict__ mshift,
+                                                                 const T* __restrict__ z, const float* __restrict__ coef,
+                                                                 T* __restrict__ dz, size_t nvec, int C) {
+  constexpr int V = Store<T>::VEC;
+  typedef typename Store<T>::vec_t vec_t;
+  const size_t base = (size_t)blockIdx.x * (256 * U) + threadIdx.x;
+  const int c0 = (int)((threadIdx.x * V) % C);
+  vec_t gq[U], zq[U], mq[U];
+#pragma unroll
+  for (int j = 0; j < U; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i < nvec) {
+      gq[j] = *reinterpret_cast<const vec_t*>(dy + i * V);
+      zq[j] = *reinterpret_cast<const vec_t*>(z + i * V);
+      if (mask && mask != z) mq[j] = *reinterpret_cast<const vec_t*>(mask + i * V);
+    }
+  }
+  float A[V], B[V], C0[V], ms[V], mh[V];
+#pragma unroll
+  for (int j = 0; j < V; j += 4) {
+    *reinterpret_cast<float4*>(&A[j]) = *reinterpret_cast<const float4*>(coef + c0 + j);
+    *reinterpret_cast<float4*>(&B[j]) = *reinterpret_cast<const float4*>(coef + C + c0 + j);
+    *reinterpret_cast<float4*>(&C0[j]) = *reinterpret_cast<const float4*>(coef + 2 * C + c0 + j);
+    if (mscale) {
+      *reinterpret_cast<float4*>(&ms[j]) = *reinterpret_cast<const float4*>(mscale + c0 + j);
+      *reinterpret_cast<float4*>(&mh[j]) = *reinterpret_cast<const float4*>(mshift + c0 + j);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { ms[j + e] = 1.f; mh[j + e] = 0.f; }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < U; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i >= nvec) continue;
+    float g[V], zz[V];
+    Store<T>::unpack_vec(gq[j], g);
+    Store<T>::unpack_vec(zq[j], zz);
+    if (mask) {
+      float mk[V];
+      Store<T>::unpack_vec(mask != z ? mq[j] : zq[j], mk);
+#pragma unroll
+      for (int e = 0; e < V; ++e) g[e] = (mk[e] * ms[e] + mh[e]) > 0.f ? g[e] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) g[e] = A[e] * g[e] + (B[e] * zz[e] + C0[e]);
+    Store<T>::store_vec(dz + i * V, g);
+  }
+}
+
+template <typename T>
+static bool bn_bwd_apply_chunked(const T* dy, const T* mask, const float* mscale, const float* mshift, const T* z,
+                                 const float* coef, T* dz, size_t nvec, int C, hipStream_t s) {
+  constexpr int V = Store<T>::VEC;
+  // final coefficients, a thread's channels fixed, 16-byte aligned per-channel vectors
+  if (!coef || (256 * V) % C != 0 || C % 4 != 0) return false;
+  if (((uintptr_t)coef | (uintptr_t)mscale | (uintptr_t)mshift) & 15u) return false;
+  if (nvec >= (size_t)512 * 1024)
+    DDG_LAUNCH((bn_bwd_apply_chunk_kernel<T, 2>), dim3((unsigned)((nvec + 511) / 512)), dim3(256), 0, s, dy, mask, mscale,
+               mshift, z, coef, dz, nvec, C);
+  else
+    DDG_LAUNCH((bn_bwd_apply_chunk_kernel<T, 1>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s, dy, mask, mscale,
+               mshift, z, coef, dz, nvec, C);
+  return true;
+}
+
 hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const float* mscale, const float* mshift,
                                const void* z, const float* coef, const BnBwdRows* rows, void* dz, size_t elems,
                                int C, int dtype, hipStream_t s) {
   const BnBwdRows br = rows ? *rows : BnBwdRows{};
   const int maxb = rows ? 512 : 2048;
+  if (!rows) {
+    const bool done = dtype == BF16
+        ? bn_bwd_apply_chunked<bf16_t>((const bf16_t*)dy, (const bf16_t*)mask, mscale, mshift, (const bf16_t*)z, coef,
+                                       (bf16_t*)dz, elems / 8, C, s)
+        : bn_bwd_apply_chunked<float>((const float*)dy, (const float*)mask, mscale, mshift, (const float*)z, coef,
+                                      (float*)dz, elems / 4, C, s);
+    if (done) return hipGetLastError();
+  }
   if (dtype == BF16) {
     const size_t nvec = elems / 8;
     DDG_LAUNCH(bn_bwd_apply_kernel<bf16_t>, dim3(elem_grid(nvec, C, 8, maxb)), dim3(256), 0, s,

@@ -24,6 +24,8 @@ namespace ddg {
 struct WgradWideArgs {
   const bf16_t* x;       // [M][Cin]
   const bf16_t* dz;      // [M][Cout]
+  const float* scale;    // optional per-channel transform of x: relu(x*scale+shift)
+  const float* shift;
   float* partial;        // [splits][Cout][J], J = taps*Cin
   int M, H, W, HW, Cin, Cout, R, J;
   int steps_per_split;   // 64-pixel steps per split
@@ -71,21 +73,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void w
   auto ldz = [&](int m) __attribute__((always_inline)) {
     return m < a.M ? *reinterpret_cast<const uint4*>(a.dz + (size_t)m * a.Cout + co0 + ch * 8) : make_uint4(0, 0, 0, 0);
   };
-  auto ldx = [&](int m) __attribute__((always_inline)) {
-    if (m >= a.M) return make_uint4(0, 0, 0, 0);
-    const int rem = m % a.HW;
-    const int h = rem / a.W + dr, w = rem % a.W + ds;
-    if (h < 0 || h >= a.H || w < 0 || w >= a.W) return make_uint4(0, 0, 0, 0);
-    return *reinterpret_cast<const uint4*>(a.x + (size_t)m * a.Cin + xshift + ci0 + ch * 8);
+  // small non-negative integers divide exactly through fp32 (the host checks M < 2^22)
+  const float inv_hw = 1.0f / (float)a.HW, inv_w = 1.0f / (float)a.W;
+  unsigned xin = 0;      // bit q: row q of the step in the registers lies inside the image for this tap
+  auto ldx = [&](int m, int q) __attribute__((always_inline)) {
+    const int n = (int)(((float)m + 0.5f) * inv_hw);
+    const int rem = m - n * a.HW;
+    const int hh = (int)(((float)rem + 0.5f) * inv_w);
+    const int h = hh + dr, w = rem - hh * a.W + ds;
+    const bool in = m < a.M && h >= 0 && h < a.H && w >= 0 && w < a.W;
+    xin |= (in ? 1u : 0u) << q;
+    return in ? *reinterpret_cast<const uint4*>(a.x + (size_t)m * a.Cin + xshift + ci0 + ch * 8) : make_uint4(0, 0, 0, 0);
   };
   auto issue = [&](int step) __attribute__((always_inline)) {
     const int m = step * BP + prow;
     z0 = ldz(m); z1 = ldz(m + 16); z2 = ldz(m + 32); z3 = ldz(m + 48);
-    x0 = ldx(m); x1 = ldx(m + 16); x2 = ldx(m + 32); x3 = ldx(m + 48);
+    xin = 0;
+    x0 = ldx(m, 0); x1 = ldx(m + 16, 1); x2 = ldx(m + 32, 2); x3 = ldx(m + 48, 3);
+  };
+  // per-channel constants of this thread's 8 input channels (the same in every step)
+  float tsc[8], tsh[8];
+  const bool xform = a.scale != nullptr;
+  if (xform) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { tsc[e] = a.scale[ci0 + ch * 8 + e]; tsh[e] = a.shift[ci0 + ch * 8 + e]; }
+  }
+  // a pixel outside the image or past the end stays zero: the transform applies to loaded rows only
+  auto act = [&](uint4 q, bool in) __attribute__((always_inline)) {
+    float f[8];
+    Store<bf16_t>::unpack_vec(q, f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { const float t = f[e] * tsc[e] + tsh[e]; f[e] = (in && t > 0.f) ? t : 0.f; }
+    uint4 o;
+    o.x = Store<bf16_t>::pack2(f[0], f[1]); o.y = Store<bf16_t>::pack2(f[2], f[3]);
+    o.z = Store<bf16_t>::pack2(f[4], f[5]); o.w = Store<bf16_t>::pack2(f[6], f[7]);
+    return o;
   };
   auto stash = [&](int buf) __attribute__((always_inline)) {
     unsigned char* Z = smem + buf * BUF + prow * ROW + ch * 16;
     unsigned char* X = Z + OPB;
+    if (xform) {
+      x0 = act(x0, xin & 1u); x1 = act(x1, xin & 2u); x2 = act(x2, xin & 4u); x3 = act(x3, xin & 8u);
+    }
     *reinterpret_cast<uint4*>(Z) = z0; *reinterpret_cast<uint4*>(Z + 16 * ROW) = z1;
     *reinterpret_cast<uint4*>(Z + 32 * ROW) = z2; *reinterpret_cast<uint4*>(Z + 48 * ROW) = z3;
     *reinterpret_cast<uint4*>(X) = x0; *reinterpret_cast<uint4*>(X + 16 * ROW) = x1;
@@ -164,10 +193,11 @@ int wgrad_wide_splits(int M, int Cin, int Cout, int R) {
 }
 
 hipError_t wgrad_wide_launch(const void* x, const void* dz, float* partial, int N, int H, int W, int Cin, int Cout,
-                             int R, int splits, hipStream_t s) {
+                             int R, int splits, hipStream_t s, const float* scale, const float* shift) {
   if (!wgrad_wide_ok(Cin, Cout, R, 1, BF16) || splits < 1) return hipErrorInvalidValue;
+  if ((size_t)N * H * W >= ((size_t)1 << 22)) return hipErrorInvalidValue;   // pixel indices divide through fp32 inside
   WgradWideArgs a{};
-  a.x = (const bf16_t*)x; a.dz = (const bf16_t*)dz; a.partial = partial;
+  a.x = (const bf16_t*)x; a.dz = (const bf16_t*)dz; a.partial = partial; a.scale = scale; a.shift = shift;
   a.M = N * H * W; a.H = H; a.W = W; a.HW = H * W; a.Cin = Cin; a.Cout = Cout; a.R = R; a.J = R * R * Cin;
   a.nsteps = (a.M + wgw::BP - 1) / wgw::BP;
   a.steps_per_split = (a.nsteps + splits - 1) / splits;
