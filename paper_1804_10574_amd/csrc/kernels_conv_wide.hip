@@ -41,14 +41,15 @@ struct ConvWideArgs {
 namespace wide {
 constexpr int BM = 64, BN = 128, BK = 64;
 constexpr int PROW = BK * 2 + 16;                 // bytes per staged pixel row
-constexpr int P_BYTES = BM * PROW;                // 9216
-constexpr int W_BYTES = (BN / 16) * (BK / 32) * 1024;   // 16 fragments
-constexpr int BUF = P_BYTES + W_BYTES;            // 25600
-constexpr int LDS = 2 * BUF;
+constexpr int P_BYTES = BM * PROW;                // 9216: one pixel buffer
+constexpr int OROW = BN * 4 + 16;                 // bytes per pixel row of the epilogue's fp32 tile
+constexpr int LDS = BM * OROW;                    // 33792 >= the two pixel buffers and the statistics scratch
 }
 
-// Registers that hold a thread's share of one chunk on its way from global memory to LDS.
-struct WideChunk { uint4 p0, w0, w1; bool ok; };
+// Registers that carry a thread's share of a chunk's pixel operand to LDS, and a wave's weight
+// fragments of a chunk (used from the registers).
+struct WidePix { uint4 p; bool ok; };
+struct WideWts { uint4 w0, w1; };
 
 // XFORM: the input is turned into the activation it stands for, relu(in*scale + shift) (batch
 // norm + ReLU of the layer before), while it is written to LDS; zero padding comes after that.
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
-  const int wm = wave & 1, wn = (wave >> 1) & 1, kg = wave >> 2;   // pixel half, channel half, k-step of a chunk
+  const int wn = wave & 3, kg = wave >> 2;        // 32-channel group; k-step of a chunk
   const int m0 = blockIdx.x * BM;
   const int OCB = a.OC >> 4;
   const int cb0 = blockIdx.y * (BN / 16);
@@ -73,37 +74,39 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   const int remA = (vA ? mA : 0) % a.HW;
   const int hA = remA / a.W, wA = remA - hA * a.W;
   const int baseA = (vA ? mA : 0) * a.IC + pc * 8;
-  const bf16_t* wsrc = a.wpack + ((size_t)cb0 * 64) * 8 + tid * 8;
+  // this wave's weight fragments of k-step 0: channel blocks cb0 + wn*2, +1; k-step ks adds ks*wstep
+  const bf16_t* wsrc = a.wpack + ((size_t)(cb0 + wn * 2) * 64 + lane) * 8;
   const size_t wstep = (size_t)OCB * 64 * 8;      // elements per k-step of the packed operand
 
-  // Chunk kc: 64 channels of one tap. The loads of a chunk are issued four chunks before it is
-  // needed (the memory latency is several times the time a chunk takes to contract). Nothing
-  // here is conditional, so that the compiler can count the loads in flight and wait only for
-  // the oldest: a row outside the image loads its own pixel instead and is zeroed when it is
-  // written to LDS; a chunk index past the end repeats the last chunk (never used).
-  auto issue = [&](WideChunk& r, int kc_want) __attribute__((always_inline)) {
+  // Chunk kc: 64 channels of one tap. Loads are issued two to three chunks before they are needed (the
+  // memory latency is several times the time a chunk takes to contract). Nothing here is
+  // conditional, so that the compiler can count the loads in flight and wait only for the
+  // oldest: a row outside the image loads its own pixel instead and is zeroed when it is written
+  // to LDS; a chunk index past the end repeats the last chunk (never used).
+  auto issue_pix = [&](WidePix& r, int kc_want) __attribute__((always_inline)) {
     const int kc = kc_want < nchunks ? kc_want : nchunks - 1;
     const int tap = kc >> l2cpt, c0 = (kc & (cpt - 1)) * BK;
     int dr = 0, ds = 0;
     if (a.R == 3) { dr = tap / 3 - 1; ds = tap - (tap / 3) * 3 - 1; }
     const int sh = (dr * a.W + ds) * a.IC;
     r.ok = vA && hA + dr >= 0 && hA + dr < a.H && wA + ds >= 0 && wA + ds < a.W;
-    r.p0 = *reinterpret_cast<const uint4*>(a.in + baseA + c0 + (r.ok ? sh : 0));
-    // 16-byte unit tid of the 8 fragments of each of the chunk's two k-steps
-    const bf16_t* wa = wsrc + (size_t)(kc * 2) * wstep;
-    r.w0 = *reinterpret_cast<const uint4*>(wa);
-    r.w1 = *reinterpret_cast<const uint4*>(wa + wstep);
+    r.p = *reinterpret_cast<const uint4*>(a.in + baseA + c0 + (r.ok ? sh : 0));
   };
-  // XFORM: scale and shift of all input channels, after the operand buffers
+  auto issue_wts = [&](WideWts& r, int kc_want) __attribute__((always_inline)) {
+    const int kc = kc_want < nchunks ? kc_want : nchunks - 1;
+    const bf16_t* wa = wsrc + (size_t)(kc * 2 + kg) * wstep;
+    r.w0 = *reinterpret_cast<const uint4*>(wa);
+    r.w1 = *reinterpret_cast<const uint4*>(wa + 64 * 8);
+  };
+  // XFORM: scale and shift of all input channels, after the pixel buffers
   float* tab = reinterpret_cast<float*>(smem + LDS);
   if (XFORM) {
     for (int c = tid; c < a.IC; c += 512) { tab[c] = a.scale[c]; tab[a.IC + c] = a.shift[c]; }
     __syncthreads();
   }
-  auto stash = [&](const WideChunk& r, int buf, int kc) __attribute__((always_inline)) {
-    unsigned char* P = smem + buf * BUF;
-    unsigned char* Wt = P + P_BYTES;
-    uint4 q = r.p0;
+  auto stash = [&](const WidePix& r, int buf, int kc) __attribute__((always_inline)) {
+    unsigned char* P = smem + buf * P_BYTES;
+    uint4 q = r.p;
     if (XFORM) {
       const int c = (kc & (cpt - 1)) * BK + pc * 8;     // this thread's 8 input channels of chunk kc
       float f[8], sc[8], sh[8];
@@ -118,78 +121,76 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
       q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
     }
     *reinterpret_cast<uint4*>(P + prow * PROW + pc * 16) = r.ok ? q : make_uint4(0, 0, 0, 0);
-    *reinterpret_cast<uint4*>(Wt + tid * 16) = r.w0;
-    *reinterpret_cast<uint4*>(Wt + (tid + 512) * 16) = r.w1;
   };
 
-  f32x4_t acc[2][4];
+  f32x4_t acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   // this wave's k-step of every chunk: waves 0-3 take the first 32 channels, waves 4-7 the rest
-  const int poff = (wm * 32 + l16) * PROW + lg * 16 + kg * 64;             // + i*16*PROW
-  const int woff = P_BYTES + ((kg * 8 + wn * 4) * 64 + lane) * 16;         // + j*1024
-  auto contract = [&](int buf) __attribute__((always_inline)) {
-    const unsigned char* B = smem + buf * BUF;
-    uint4 pf[2], wf[4];
+  const int poff = l16 * PROW + lg * 16 + kg * 64;             // + i*16*PROW
+  auto contract = [&](int buf, const WideWts& w) __attribute__((always_inline)) {
+    const unsigned char* B = smem + buf * P_BYTES;
+    uint4 pf[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) pf[i] = *reinterpret_cast<const uint4*>(B + poff + i * 16 * PROW);
+    for (int i = 0; i < 4; ++i) pf[i] = *reinterpret_cast<const uint4*>(B + poff + i * 16 * PROW);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) wf[j] = *reinterpret_cast<const uint4*>(B + woff + j * 1024);
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = Mma<bf16_t>::mma(wf[j], pf[i], acc[i][j]);
+    for (int i = 0; i < 4; ++i) {
+      acc[i][0] = Mma<bf16_t>::mma(w.w0, pf[i], acc[i][0]);
+      acc[i][1] = Mma<bf16_t>::mma(w.w1, pf[i], acc[i][1]);
+    }
   };
 
-  // Register set c % 2 carries chunk c. At the top of iteration c: LDS buffer c % 2 holds chunk c,
-  // the sets hold chunks c+1 and c+2 (requested, maybe arrived). The loop body is written out
-  // twice so that every set is a named variable.
-  WideChunk r0, r1;
-  issue(r0, 0);
-  stash(r0, 0, 0);
-  issue(r1, 1);
-  issue(r0, 2);
+  // Pixel set c % 2 and weight set c % 2 carry chunk c. At the top of iteration c: LDS buffer
+  // c % 2 holds the pixels of chunk c, the pixel sets hold chunks c+1 and c+2, the weight sets
+  // chunks c and c+1. The loop body is written out twice so that every set is a named variable.
+  WidePix p0, p1;
+  WideWts w0, w1;
+  issue_pix(p0, 0);
+  issue_wts(w0, 0);
+  stash(p0, 0, 0);
+  issue_pix(p1, 1); issue_wts(w1, 1);
+  issue_pix(p0, 2);
   __syncthreads();
-  // one iteration: move chunk c+1 from its registers to the other LDS buffer (free since the
-  // barrier that ended iteration c-1), request chunk c+3 into the registers just freed, contract
-  // chunk c
-#define DDG_WIDE_STEP(c, rnext)                         \
-  {                                                     \
-    if ((c) + 1 < nchunks) stash(rnext, ((c) + 1) & 1, (c) + 1); \
-    issue(rnext, (c) + 3);                              \
-    contract((c) & 1);                                  \
-    __syncthreads();                                    \
+  // one iteration: move the pixels of chunk c+1 from their registers to the other LDS buffer
+  // (free since the barrier that ended iteration c-1) and request chunk c+4 into those
+  // registers; contract chunk c with its weights and request the weights of chunk c+2
+#define DDG_WIDE_STEP(c, pnext, wcur)                               \
+  {                                                                 \
+    if ((c) + 1 < nchunks) stash(pnext, ((c) + 1) & 1, (c) + 1);    \
+    issue_pix(pnext, (c) + 3);                                      \
+    contract((c) & 1, wcur);                                        \
+    issue_wts(wcur, (c) + 2);                                       \
+    __syncthreads();                                                \
   }
   for (int kc = 0; kc < nchunks; kc += 2) {
-    DDG_WIDE_STEP(kc, r1)
+    DDG_WIDE_STEP(kc, p1, w0)
     if (kc + 1 >= nchunks) break;
-    DDG_WIDE_STEP(kc + 1, r0)
+    DDG_WIDE_STEP(kc + 1, p0, w1)
   }
 #undef DDG_WIDE_STEP
 
-  // ---- epilogue. The accumulators (lane = pixel wm*32 + i*16 + l16, channels (wn*4 + j)*16 +
+  // ---- epilogue. The accumulators (lane = pixel i*16 + l16, channels (wn*2 + j)*16 +
   // lg*4 .. +3) go through LDS as fp32 [64 pixels][128 channels]: the two wave groups add their
   // halves of the contraction there (first group, then second: a fixed order), and memory then
   // sees 16-byte accesses, 256 contiguous bytes per pixel: thread = pixels (tid>>4) + 32*q,
   // channels (tid&15)*8 .. +7
-  constexpr int OROW = BN * 4 + 16;               // bytes per pixel row of the fp32 tile
-  static_assert(BM * OROW <= LDS, "output tile fits the operand buffers");
+  static_assert(2 * P_BYTES <= LDS && 32 * 2 * BN * 4 <= LDS, "pixel buffers and statistics scratch fit");
   if (kg == 0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        *reinterpret_cast<f32x4_t*>(smem + (wm * 32 + i * 16 + l16) * OROW + ((wn * 4 + j) * 16 + lg * 4) * 4) = acc[i][j];
+      for (int j = 0; j < 2; ++j)
+        *reinterpret_cast<f32x4_t*>(smem + (i * 16 + l16) * OROW + ((wn * 2 + j) * 16 + lg * 4) * 4) = acc[i][j];
   }
   __syncthreads();
   if (kg == 1) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        f32x4_t* p = reinterpret_cast<f32x4_t*>(smem + (wm * 32 + i * 16 + l16) * OROW + ((wn * 4 + j) * 16 + lg * 4) * 4);
+      for (int j = 0; j < 2; ++j) {
+        f32x4_t* p = reinterpret_cast<f32x4_t*>(smem + (i * 16 + l16) * OROW + ((wn * 2 + j) * 16 + lg * 4) * 4);
         *p = *p + acc[i][j];
       }
   }
