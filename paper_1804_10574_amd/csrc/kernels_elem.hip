@@ -227,20 +227,38 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const T* __restrict_
     mu[j] = mean[c0 + j]; is[j] = invstd[c0 + j]; s1[j] = 0.f; s2[j] = 0.f;
     ms[j] = mscale ? mscale[c0 + j] : 1.f; mh[j] = mscale ? mshift[c0 + j] : 0.f;
   }
-  for (; i < nvec; i += stride) {
-    float g[V], zz[V];
-    Store<T>::load_vec(dy + i * V, g);
-    Store<T>::load_vec(z + i * V, zz);
-    if (mask) {
-      float mk[V];
-      Store<T>::load_vec(mask + i * V, mk);
+  // four vectors per trip, all requested before any is used (the sums keep their order)
+  typedef typename Store<T>::vec_t vec_t;
+  constexpr int U = 4;
+  const bool own_mask = mask && mask != z;
+  for (; i < nvec; i += U * stride) {
+    vec_t gq[U], zq[U], mq[U];
 #pragma unroll
-      for (int j = 0; j < V; ++j) g[j] = (mk[j] * ms[j] + mh[j]) > 0.f ? g[j] : 0.f;
+    for (int u = 0; u < U; ++u) {
+      const size_t iu = i + u * stride;
+      if (iu < nvec) {
+        gq[u] = *reinterpret_cast<const vec_t*>(dy + iu * V);
+        zq[u] = *reinterpret_cast<const vec_t*>(z + iu * V);
+        if (own_mask) mq[u] = *reinterpret_cast<const vec_t*>(mask + iu * V);
+      }
     }
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-      s1[j] += g[j];
-      s2[j] += g[j] * ((zz[j] - mu[j]) * is[j]);
+    for (int u = 0; u < U; ++u) {
+      if (i + u * stride >= nvec) continue;
+      float g[V], zz[V];
+      Store<T>::unpack_vec(gq[u], g);
+      Store<T>::unpack_vec(zq[u], zz);
+      if (mask) {
+        float mk[V];
+        Store<T>::unpack_vec(own_mask ? mq[u] : zq[u], mk);
+#pragma unroll
+        for (int j = 0; j < V; ++j) g[j] = (mk[j] * ms[j] + mh[j]) > 0.f ? g[j] : 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < V; ++j) {
+        s1[j] += g[j];
+        s2[j] += g[j] * ((zz[j] - mu[j]) * is[j]);
+      }
     }
   }
   // threads with equal (threadIdx.x*V) % C hold the same channels; combine in thread order
