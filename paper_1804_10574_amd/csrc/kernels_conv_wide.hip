@@ -39,23 +39,30 @@ struct ConvWideArgs {
 };
 
 namespace wide {
-constexpr int BM = 64, BN = 128, BK = 64;
-constexpr int PROW = BK * 2 + 16;                 // bytes per staged pixel row
-constexpr int P_BYTES = BM * PROW;                // 9216: one pixel buffer
+constexpr int BM = 64, BN = 128;
 constexpr int OROW = BN * 4 + 16;                 // bytes per pixel row of the epilogue's fp32 tile
-constexpr int LDS = BM * OROW;                    // 33792 >= the two pixel buffers and the statistics scratch
+constexpr int prow_bytes(int BK) { return BK * 2 + 16; }          // bytes per staged pixel row
+constexpr int pix_bytes(int BK) { return BM * prow_bytes(BK); }   // one pixel buffer
+// dynamic LDS: the two pixel buffers, later reused by the epilogue's fp32 tile and statistics scratch
+constexpr int lds_bytes(int BK) { return 2 * pix_bytes(BK) > BM * OROW ? 2 * pix_bytes(BK) : BM * OROW; }
 }
 
 // Registers that carry a thread's share of a chunk's pixel operand to LDS, and a wave's weight
 // fragments of a chunk (used from the registers).
-struct WidePix { uint4 p; bool ok; };
-struct WideWts { uint4 w0, w1; };
+struct WidePix { uint4 p, q; bool ok, okq; };       // q: second row of the thread (BK = 128)
+struct WideWts { uint4 w0, w1, w2, w3; };           // w2, w3: second k-step of the wave (BK = 128)
 
 // XFORM: the input is turned into the activation it stands for, relu(in*scale + shift) (batch
 // norm + ReLU of the layer before), while it is written to LDS; zero padding comes after that.
-template <bool STATS, bool XFORM>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void conv_wide_kernel(ConvWideArgs a) {
+// BK: contraction channels per chunk (one barrier each). 128 halves the number of barriers; 64
+// keeps the kernel at 128 registers, two workgroups per compute unit (launches with many tiles).
+template <bool STATS, bool XFORM, int BK>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 4 : 2))) void conv_wide_kernel(ConvWideArgs a) {
   using namespace wide;
+  constexpr int PROW = prow_bytes(BK), P_BYTES = pix_bytes(BK), LDS = lds_bytes(BK);
+  constexpr int UPR = BK / 8;                     // 16-byte units per staged pixel row
+  constexpr bool TWO = BK == 128;                 // two rows per thread, two k-steps per wave
+  constexpr int KSW = BK / 64;                    // k-steps per wave and chunk
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
@@ -67,13 +74,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   const int l2cpt = 31 - __clz(cpt);
   const int nchunks = a.R * a.R * cpt;
 
-  // ---- staging map of the pixel operand: row tid/8, 16-byte chunk tid%8
-  const int pc = tid & 7, prow = tid >> 3;
-  const int mA = m0 + prow;
-  const bool vA = mA < a.M;
-  const int remA = (vA ? mA : 0) % a.HW;
-  const int hA = remA / a.W, wA = remA - hA * a.W;
-  const int baseA = (vA ? mA : 0) * a.IC + pc * 8;
+  // ---- staging map of the pixel operand: row tid/UPR (and 32 rows further for BK = 128),
+  // 16-byte unit tid%UPR
+  const int pc = tid % UPR, prow = tid / UPR;
+  const int mA = m0 + prow, mB = mA + 32;
+  const bool vA = mA < a.M, vB = TWO && mB < a.M;
+  const int remA = (vA ? mA : 0) % a.HW, remB = (vB ? mB : 0) % a.HW;
+  const int hA = remA / a.W, wA = remA - hA * a.W, hB = remB / a.W, wB = remB - hB * a.W;
+  const int baseA = (vA ? mA : 0) * a.IC + pc * 8, baseB = (vB ? mB : 0) * a.IC + pc * 8;
   // this wave's weight fragments of k-step 0: channel blocks cb0 + wn*2, +1; k-step ks adds ks*wstep
   const bf16_t* wsrc = a.wpack + ((size_t)(cb0 + wn * 2) * 64 + lane) * 8;
   const size_t wstep = (size_t)OCB * 64 * 8;      // elements per k-step of the packed operand
@@ -91,12 +99,20 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
     const int sh = (dr * a.W + ds) * a.IC;
     r.ok = vA && hA + dr >= 0 && hA + dr < a.H && wA + ds >= 0 && wA + ds < a.W;
     r.p = *reinterpret_cast<const uint4*>(a.in + baseA + c0 + (r.ok ? sh : 0));
+    if (TWO) {
+      r.okq = vB && hB + dr >= 0 && hB + dr < a.H && wB + ds >= 0 && wB + ds < a.W;
+      r.q = *reinterpret_cast<const uint4*>(a.in + baseB + c0 + (r.okq ? sh : 0));
+    }
   };
   auto issue_wts = [&](WideWts& r, int kc_want) __attribute__((always_inline)) {
     const int kc = kc_want < nchunks ? kc_want : nchunks - 1;
-    const bf16_t* wa = wsrc + (size_t)(kc * 2 + kg) * wstep;
+    const bf16_t* wa = wsrc + (size_t)((kc * 2 + kg) * KSW) * wstep;
     r.w0 = *reinterpret_cast<const uint4*>(wa);
     r.w1 = *reinterpret_cast<const uint4*>(wa + 64 * 8);
+    if (TWO) {
+      r.w2 = *reinterpret_cast<const uint4*>(wa + wstep);
+      r.w3 = *reinterpret_cast<const uint4*>(wa + wstep + 64 * 8);
+    }
   };
   // XFORM: scale and shift of all input channels, after the pixel buffers
   float* tab = reinterpret_cast<float*>(smem + LDS);
@@ -106,21 +122,29 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   }
   auto stash = [&](const WidePix& r, int buf, int kc) __attribute__((always_inline)) {
     unsigned char* P = smem + buf * P_BYTES;
-    uint4 q = r.p;
+    uint4 q = r.p, q2 = r.q;
     if (XFORM) {
       const int c = (kc & (cpt - 1)) * BK + pc * 8;     // this thread's 8 input channels of chunk kc
-      float f[8], sc[8], sh[8];
+      float sc[8], sh[8];
       *reinterpret_cast<float4*>(&sc[0]) = *reinterpret_cast<const float4*>(&tab[c]);
       *reinterpret_cast<float4*>(&sc[4]) = *reinterpret_cast<const float4*>(&tab[c + 4]);
       *reinterpret_cast<float4*>(&sh[0]) = *reinterpret_cast<const float4*>(&tab[a.IC + c]);
       *reinterpret_cast<float4*>(&sh[4]) = *reinterpret_cast<const float4*>(&tab[a.IC + c + 4]);
-      Store<bf16_t>::unpack_vec(q, f);
+      auto act = [&](uint4 v) __attribute__((always_inline)) {
+        float f[8];
+        Store<bf16_t>::unpack_vec(v, f);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { const float t = f[e] * sc[e] + sh[e]; f[e] = t > 0.f ? t : 0.f; }
-      q.x = Store<bf16_t>::pack2(f[0], f[1]); q.y = Store<bf16_t>::pack2(f[2], f[3]);
-      q.z = Store<bf16_t>::pack2(f[4], f[5]); q.w = Store<bf16_t>::pack2(f[6], f[7]);
+        for (int e = 0; e < 8; ++e) { const float t = f[e] * sc[e] + sh[e]; f[e] = t > 0.f ? t : 0.f; }
+        uint4 o;
+        o.x = Store<bf16_t>::pack2(f[0], f[1]); o.y = Store<bf16_t>::pack2(f[2], f[3]);
+        o.z = Store<bf16_t>::pack2(f[4], f[5]); o.w = Store<bf16_t>::pack2(f[6], f[7]);
+        return o;
+      };
+      q = act(q);
+      if (TWO) q2 = act(q2);
     }
     *reinterpret_cast<uint4*>(P + prow * PROW + pc * 16) = r.ok ? q : make_uint4(0, 0, 0, 0);
+    if (TWO) *reinterpret_cast<uint4*>(P + (prow + 32) * PROW + pc * 16) = r.okq ? q2 : make_uint4(0, 0, 0, 0);
   };
 
   f32x4_t acc[4][2];
@@ -128,17 +152,28 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  // this wave's k-step of every chunk: waves 0-3 take the first 32 channels, waves 4-7 the rest
-  const int poff = l16 * PROW + lg * 16 + kg * 64;             // + i*16*PROW
+  // this wave's k-steps of every chunk: waves 0-3 take the first half of its channels, waves 4-7 the rest
+  const int poff = l16 * PROW + lg * 16 + kg * BK;             // + i*16*PROW (+ 64 for the second k-step)
   auto contract = [&](int buf, const WideWts& w) __attribute__((always_inline)) {
     const unsigned char* B = smem + buf * P_BYTES;
-    uint4 pf[4];
+    uint4 pf[4], pg[TWO ? 4 : 1];
 #pragma unroll
     for (int i = 0; i < 4; ++i) pf[i] = *reinterpret_cast<const uint4*>(B + poff + i * 16 * PROW);
+    if (TWO) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pg[i] = *reinterpret_cast<const uint4*>(B + poff + i * 16 * PROW + 64);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       acc[i][0] = Mma<bf16_t>::mma(w.w0, pf[i], acc[i][0]);
       acc[i][1] = Mma<bf16_t>::mma(w.w1, pf[i], acc[i][1]);
+    }
+    if (TWO) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[i][0] = Mma<bf16_t>::mma(w.w2, pg[i], acc[i][0]);
+        acc[i][1] = Mma<bf16_t>::mma(w.w3, pg[i], acc[i][1]);
+      }
     }
   };
 
@@ -176,7 +211,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   // halves of the contraction there (first group, then second: a fixed order), and memory then
   // sees 16-byte accesses, 256 contiguous bytes per pixel: thread = pixels (tid>>4) + 32*q,
   // channels (tid&15)*8 .. +7
-  static_assert(2 * P_BYTES <= LDS && 32 * 2 * BN * 4 <= LDS, "pixel buffers and statistics scratch fit");
+  static_assert(2 * P_BYTES <= LDS && BM * OROW <= LDS && 32 * 2 * BN * 4 <= LDS, "pixel buffers, fp32 tile and statistics scratch fit");
   if (kg == 0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -251,6 +286,32 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void c
   }
 }
 
+template <int BK>
+static hipError_t conv_wide_dispatch(const ConvWideArgs& a, dim3 grid, bool stats, bool xf, int IC, hipStream_t s) {
+  const int tab_max = 2 * 2048 * (int)sizeof(float);
+  const int lds = wide::lds_bytes(BK) + (xf ? 2 * IC * (int)sizeof(float) : 0);
+  static bool attr_set = false;
+  if (!attr_set) {
+    const void* fns[4] = {reinterpret_cast<const void*>(&conv_wide_kernel<true, false, BK>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<false, false, BK>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<true, true, BK>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<false, true, BK>)};
+    for (const void* f : fns) {
+      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, wide::lds_bytes(BK) + tab_max);
+      if (e != hipSuccess) return e;
+    }
+    attr_set = true;
+  }
+  if (stats) {
+    if (xf) DDG_LAUNCH((conv_wide_kernel<true, true, BK>), grid, dim3(512), lds, s, a);
+    else DDG_LAUNCH((conv_wide_kernel<true, false, BK>), grid, dim3(512), lds, s, a);
+  } else {
+    if (xf) DDG_LAUNCH((conv_wide_kernel<false, true, BK>), grid, dim3(512), lds, s, a);
+    else DDG_LAUNCH((conv_wide_kernel<false, false, BK>), grid, dim3(512), lds, s, a);
+  }
+  return hipGetLastError();
+}
+
 // Shapes the kernel covers (the module code asks before it plans a layer).
 bool conv_wide_ok(int IC, int OC, int R, int stride, int dtype) {
   if (dtype != BF16 || stride != 1 || (R != 1 && R != 3)) return false;
@@ -272,27 +333,10 @@ hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float*
   const dim3 grid(conv_wide_rows((int)M), OC / wide::BN);
   const bool xf = scale != nullptr;
   if (xf && (add_g || IC > 2048)) return hipErrorInvalidValue;   // forward only; the table lives in LDS
-  const int lds = wide::LDS + (xf ? 2 * IC * (int)sizeof(float) : 0);
-  static bool attr_set = false;
-  if (!attr_set) {
-    const void* fns[4] = {reinterpret_cast<const void*>(&conv_wide_kernel<true, false>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<false, false>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<true, true>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<false, true>)};
-    for (const void* f : fns) {
-      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, wide::LDS + 2 * 2048 * (int)sizeof(float));
-      if (e != hipSuccess) return e;
-    }
-    attr_set = true;
-  }
-  if (stat_partial) {
-    if (xf) DDG_LAUNCH((conv_wide_kernel<true, true>), grid, dim3(512), lds, s, a);
-    else DDG_LAUNCH((conv_wide_kernel<true, false>), grid, dim3(512), lds, s, a);
-  } else {
-    if (xf) DDG_LAUNCH((conv_wide_kernel<false, true>), grid, dim3(512), lds, s, a);
-    else DDG_LAUNCH((conv_wide_kernel<false, false>), grid, dim3(512), lds, s, a);
-  }
-  return hipGetLastError();
+  // few tiles (one workgroup per compute unit at most): the long chunk; else two workgroups per unit
+  const bool long_chunk = IC >= 128 && grid.x * grid.y <= 256;
+  return long_chunk ? conv_wide_dispatch<128>(a, grid, stat_partial != nullptr, xf, IC, s)
+                    : conv_wide_dispatch<64>(a, grid, stat_partial != nullptr, xf, IC, s);
 }
 
 }  // namespace ddg
