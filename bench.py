@@ -39,6 +39,9 @@ HIP_KERNEL_OF = {
     "conv_wgrad.tiled_c16_w32": "ddg::wgrad_tiled_kernel<16, 16, 32>",
     "conv_wgrad.tiled_c32_w16": "ddg::wgrad_tiled_kernel<32, 32, 16>",
     "conv_wgrad.tiled_c64_w8": "ddg::wgrad_tiled_kernel<64, 64, 8>",
+    "conv_fprop.wide": "ddg::conv_wide_kernel<true, XFORM, BK>",
+    "conv_dgrad.wide": "ddg::conv_wide_kernel<false, false, BK>",
+    "conv_wgrad.wide": "ddg::wgrad_wide_kernel",
     "conv_fprop.generic": "ddg::conv_mfma_kernel<T, MB, NB, false>",
     "conv_dgrad.generic": "ddg::conv_mfma_kernel<T, MB, NB, true>",
     "conv_wgrad.generic": "ddg::wgrad_mfma_kernel<T>",

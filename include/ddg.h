@@ -27,7 +27,8 @@
  *   DDG_NO_BWD_PAIR=1  the weight gradient of a layer runs in a launch of its own (with the
  *                    batch-norm backward fused into it) instead of beside the next
  *                    input-gradient kernel
- *   DDG_TUNE_CONV_GRID_C16/_C32/_C64, DDG_TUNE_WGRAD_ROWS[_C16/_C32/_C64]
+ *   DDG_NO_WIDE=1    wide bf16 layers (>= 128 channels, stride 1) run the generic kernels
+ *   DDG_TUNE_CONV_GRID_C16/_C32/_C64, DDG_TUNE_WGRAD_ROWS[_C16/_C32/_C64], DDG_TUNE_WGRAD_WIDE_WGS
  *                    workgroup counts of the LDS-tiled kernels (clamped to safe ranges)
  * None of them changes a result beyond the order of floating-point sums.
  *

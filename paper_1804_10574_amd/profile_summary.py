@@ -34,11 +34,16 @@ def kind_of(kernel_name: str) -> str:
     m = re.match(r"wgrad_tiled_kernel<(\d+), (\d+), (\d+)>", n)
     if m:
         return f"conv_wgrad.tiled_c{m.group(1)}_w{m.group(3)}"
+    m = re.match(r"conv_wide_kernel<(true|false), ", n)
+    if m:   # with statistics: the forward conv; without: the input gradient
+        return "conv_fprop.wide" if m.group(1) == "true" else "conv_dgrad.wide"
+    if n.startswith("wgrad_wide_kernel"):
+        return "conv_wgrad.wide"
     m = re.match(r"conv_mfma_kernel<.*(true|false)>", n)
     if m:
         return "conv_dgrad.generic" if m.group(1) == "true" else "conv_fprop.generic"
     table = [("wgrad_mfma_kernel", "conv_wgrad.generic"), ("wgrad_reduce", "wgrad_reduce"),
-             ("bn_bwd_apply_kernel", "bn_bwd_apply"), ("bn_bwd_reduce_kernel", "bn_bwd_reduce"),
+             ("bn_bwd_apply_kernel", "bn_bwd_apply"), ("bn_bwd_apply_chunk_kernel", "bn_bwd_apply"), ("bn_bwd_reduce_kernel", "bn_bwd_reduce"),
              ("bn_bwd_finalize", "bn_bwd_finalize"), ("bn_apply_kernel", "bn_apply"),
              ("bn_apply_chunk_kernel", "bn_apply"),
              ("bn_finalize", "bn_finalize"), ("head_", "head"), ("sgd_kernel", "sgd"),
