@@ -427,14 +427,17 @@ def test_deep_workloads_bf16_envelope(H, name, batch, steps):
     assert not report, "\n".join(report)
 
 
-def test_wide_bottleneck_module_bf16(H):
+@pytest.mark.parametrize("nblocks,batch", [(2, 2), (1, 12)], ids=["two_blocks_batch2", "one_block_batch12"])
+def test_wide_bottleneck_module_bf16(H, nblocks, batch):
     """The ImageNet-shaped slice at reduced size: bottleneck blocks 1024 -> 256 -> 256 -> 1024 at
-    14x14 (the wide-layer kernels and their finalise launches), module k=2 of K=4, synthetic
-    error gradient, bf16."""
+    14x14 (the GEMM-class kernels of the wide layers and their finalise launches), module k=2 of
+    K=4, synthetic error gradient, bf16. Batch 2: 392 pixels, a ragged last 64-pixel tile and
+    few tiles per launch (the 128-channel chunks); batch 12: 2352 pixels, the 1024-channel
+    outputs have more than 256 tiles (the 64-channel chunks, as at the full size)."""
     import torch
     import paper_1804_10574_amd as ddg
     from oracle import ddg_oracle as orc
-    wl = custom_bottleneck(2, batch=2, c=1024, mid=256, hw=14)
+    wl = custom_bottleneck(nblocks, batch=batch, c=1024, mid=256, hw=14)
     wl.dtype = "bf16"
     m = wl.modules[0]
     mod = ddg.Module(H.descs_for(wl)[0])
