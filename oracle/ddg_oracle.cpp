@@ -24,6 +24,15 @@
 // input and back-propagates through that snapshot: this realises Eq. 6-7/8-9
 // literally and exists to pin the delay bookkeeping against plain backprop.
 //
+// Evaluation. The paper reports test error (Section 5) and leaves batch normalisation at test
+// time to its citations. Reading taken: every BN layer keeps running estimates of mean and
+// variance, r <- (1-rho)*r + rho*(batch statistic) with rho = 0.1, the variance estimate
+// unbiased (batch variance * m/(m-1)), starting from mean 0 and variance 1; they are updated by
+// the forward pass on the current minibatch (ddg_forward, and the forward of plain
+// backpropagation), never by the re-forward of a stored input, which would count that
+// minibatch twice. The evaluation forward normalises with the running estimates and leaves
+// all training state (tape, queue, estimates) untouched.
+//
 // Storage precision. The paper does not state a number format. The benchmark this oracle
 // serves fixes bf16 convolution operands with fp32 accumulation for some workloads; with
 // `store_bf16` every tensor that such an implementation keeps in memory between layers
@@ -186,7 +195,7 @@ void conv_bwd_weight(const T* x, const T* dy, T* dw, int N, int Ci, int H, int W
 // ---------------------------------------------------------------------------
 template <class T>
 void bn_fwd(const T* x, const T* gamma, const T* beta, T eps, T* y, T* mean, T* invstd, int N,
-            int C, int HW) {
+            int C, int HW, T* var = nullptr) {
   const T m = T(N) * T(HW);
 #pragma omp parallel for schedule(static)
   for (int c = 0; c < C; ++c) {
@@ -204,10 +213,27 @@ void bn_fwd(const T* x, const T* gamma, const T* beta, T eps, T* y, T* mean, T* 
     const T is = T(1) / std::sqrt(v / m + eps);
     mean[c] = mu;
     invstd[c] = is;
+    if (var) var[c] = v / m;   // biased batch variance
     for (int n = 0; n < N; ++n) {
       const T* xp = x + ((size_t)n * C + c) * HW;
       T* yp = y + ((size_t)n * C + c) * HW;
       for (int i = 0; i < HW; ++i) yp[i] = gamma[c] * ((xp[i] - mu) * is) + beta[c];
+    }
+  }
+}
+
+// Batch normalisation at evaluation time: fixed per-channel estimates instead of batch
+// statistics, y = gamma*(x - rmean)/sqrt(rvar + eps) + beta.
+template <class T>
+void bn_eval(const T* x, const T* gamma, const T* beta, const T* rmean, const T* rvar, T eps, T* y,
+             int N, int C, int HW) {
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    const T is = T(1) / std::sqrt(rvar[c] + eps);
+    for (int n = 0; n < N; ++n) {
+      const T* xp = x + ((size_t)n * C + c) * HW;
+      T* yp = y + ((size_t)n * C + c) * HW;
+      for (int i = 0; i < HW; ++i) yp[i] = gamma[c] * ((xp[i] - rmean[c]) * is) + beta[c];
     }
   }
 }
@@ -310,9 +336,12 @@ struct Unit {  // convolution followed by batch normalisation
   size_t ow = 0, og = 0, ob = 0;  // offsets of W, gamma, beta in the module's parameter vector
   int N = 0, H = 0, W = 0, P = 0, Q = 0;
   std::vector<T> x, z, mean, invstd;  // tape: conv input, conv output, batch statistics
+  std::vector<T> rmean, rvar;         // running estimates for evaluation (start: 0 and 1)
 
   std::vector<T> wop;  // conv weights as the convolution sees them (rounded if store_bf16)
-  std::vector<T> forward(const T* th, const std::vector<T>& in, int N_, int H_, int W_, T eps, bool rb) {
+  // rho > 0: this pass is on the current minibatch and moves the running estimates
+  std::vector<T> forward(const T* th, const std::vector<T>& in, int N_, int H_, int W_, T eps, bool rb,
+                         T rho = T(0)) {
     N = N_; H = H_; W = W_;
     P = out_dim(H, R, st, pad); Q = out_dim(W, R, st, pad);
     x = in;
@@ -322,8 +351,29 @@ struct Unit {  // convolution followed by batch normalisation
     conv_fwd(x.data(), wop.data(), z.data(), N, ci, H, W, co, R, st, pad);
     round_store(z, rb);
     mean.assign(co, T(0)); invstd.assign(co, T(0));
-    std::vector<T> y(z.size());
-    bn_fwd(z.data(), th + og, th + ob, eps, y.data(), mean.data(), invstd.data(), N, co, P * Q);
+    std::vector<T> y(z.size()), var(co);
+    bn_fwd(z.data(), th + og, th + ob, eps, y.data(), mean.data(), invstd.data(), N, co, P * Q, var.data());
+    if (rho > T(0)) {
+      const T m = T(N) * T(P * Q);
+      for (int c = 0; c < co; ++c) {
+        rmean[c] = (T(1) - rho) * rmean[c] + rho * mean[c];
+        rvar[c] = (T(1) - rho) * rvar[c] + rho * (var[c] * m / (m - T(1)));
+      }
+    }
+    return y;
+  }
+  // Evaluation: same conv, normalisation by the running estimates; nothing is taped.
+  std::vector<T> forward_eval(const T* th, const std::vector<T>& in, int N_, int H_, int W_, T eps, bool rb,
+                              int* P_out, int* Q_out) const {
+    const int Pe = out_dim(H_, R, st, pad), Qe = out_dim(W_, R, st, pad);
+    std::vector<T> w(th + ow, th + ow + (size_t)co * ci * R * R);
+    round_store(w, rb);
+    std::vector<T> ze((size_t)N_ * co * Pe * Qe, T(0));
+    conv_fwd(in.data(), w.data(), ze.data(), N_, ci, H_, W_, co, R, st, pad);
+    round_store(ze, rb);
+    std::vector<T> y(ze.size());
+    bn_eval(ze.data(), th + og, th + ob, rmean.data(), rvar.data(), eps, y.data(), N_, co, Pe * Qe);
+    *P_out = Pe; *Q_out = Qe;
     return y;
   }
   // dy: gradient w.r.t. the BN output. Fills this unit's parameter gradients. The returned
@@ -395,6 +445,7 @@ struct Net {
   T beta1 = T(0.9), beta2 = T(0.999), adam_eps = T(1e-8);
   int stale_jacobian = 0;
   int store_bf16 = 0;
+  T bn_rho = T(0.1);               // weight of the newest batch statistic in the running estimates
   long t = 0;
   std::vector<Module<T>> mods;
   Module<T>& mod(int k) { return mods[k - k_first]; }
@@ -407,6 +458,7 @@ void add_unit(Block<T>& b, size_t& off, int ci, int co, int R, int st) {
   u.ow = off; off += (size_t)co * ci * R * R;
   u.og = off; off += co;
   u.ob = off; off += co;
+  u.rmean.assign(co, T(0)); u.rvar.assign(co, T(1));
   b.u.push_back(u);
 }
 
@@ -445,7 +497,8 @@ void build_module(Module<T>& m, const int* desc, int nblocks) {
 
 // Forward of one module (Eq. 3 for every layer of G(k)), taping intermediates.
 template <class T>
-std::vector<T> module_forward(Module<T>& m, const T* th, const std::vector<T>& in, T eps, bool rb) {
+std::vector<T> module_forward(Module<T>& m, const T* th, const std::vector<T>& in, T eps, bool rb,
+                              T rho = T(0)) {
   std::vector<T> cur = in;
   int h = m.in_h, w = m.in_w;
   for (auto& b : m.blocks) {
@@ -455,7 +508,7 @@ std::vector<T> module_forward(Module<T>& m, const T* th, const std::vector<T>& i
     std::vector<T> a = cur;
     for (int i = 0; i < b.nmain; ++i) {
       const int hh = (i == 0) ? h : b.u[i - 1].P, ww = (i == 0) ? w : b.u[i - 1].Q;
-      a = b.u[i].forward(th, a, m.N, hh, ww, eps, rb);
+      a = b.u[i].forward(th, a, m.N, hh, ww, eps, rb, rho);
       if (i + 1 < b.nmain || b.kind == KIND_STEM) {
         relu_inplace(a);
         round_store(a, rb);
@@ -463,13 +516,55 @@ std::vector<T> module_forward(Module<T>& m, const T* th, const std::vector<T>& i
       }
     }
     if (b.kind != KIND_STEM) {
-      std::vector<T> sc = (b.projection) ? b.u[b.nmain].forward(th, cur, m.N, h, w, eps, rb) : cur;
+      std::vector<T> sc = (b.projection) ? b.u[b.nmain].forward(th, cur, m.N, h, w, eps, rb, rho) : cur;
       for (size_t i = 0; i < a.size(); ++i) a[i] = a[i] + sc[i];
       relu_inplace(a);
       round_store(a, rb);
     }
     b.y = a;
     h = b.u[b.nmain - 1].P; w = b.u[b.nmain - 1].Q;
+    cur = a;
+  }
+  return cur;
+}
+
+// Evaluation forward of one module: the same layers with every BN normalising by its running
+// estimates. Touches no training state. With a head: the mean loss is returned through
+// loss_out (labels given) and the logits through logits_out; the returned tensor is the input
+// of the head.
+template <class T>
+std::vector<T> module_forward_eval(const Module<T>& m, const std::vector<T>& in, T eps, bool rb,
+                                   const int* labels, T* loss_out, T* logits_out) {
+  const T* th = m.theta.data();
+  std::vector<T> cur = in;
+  int h = m.in_h, w = m.in_w;
+  for (const auto& b : m.blocks) {
+    if (b.kind == KIND_HEAD) {
+      std::vector<int> zero_labels;
+      if (!labels) { zero_labels.assign(m.N, 0); labels = zero_labels.data(); }
+      const T loss = head_fwd_bwd<T>(cur.data(), th + b.ofcw, th + b.ofcb, labels, m.N, b.cin, h * w, m.classes,
+                                     nullptr, nullptr, nullptr, logits_out);
+      if (loss_out) *loss_out = loss;
+      continue;
+    }
+    std::vector<T> a = cur;
+    int hh = h, ww = w, P = h, Q = w;
+    for (int i = 0; i < b.nmain; ++i) {
+      a = b.u[i].forward_eval(th, a, m.N, hh, ww, eps, rb, &P, &Q);
+      hh = P; ww = Q;
+      if (i + 1 < b.nmain || b.kind == KIND_STEM) {
+        relu_inplace(a);
+        round_store(a, rb);
+      }
+    }
+    if (b.kind != KIND_STEM) {
+      int Ps, Qs;
+      std::vector<T> sc = (b.projection) ? b.u[b.nmain].forward_eval(th, cur, m.N, h, w, eps, rb, &Ps, &Qs) : cur;
+      for (size_t i = 0; i < a.size(); ++i) a[i] = a[i] + sc[i];
+      relu_inplace(a);
+      round_store(a, rb);
+    }
+    h = P; w = Q;
     cur = a;
   }
   return cur;
@@ -530,8 +625,19 @@ void ddg_forward(Net<T>& net, int k, long t, const T* h_in, T* h_out) {
   if (net.stale_jacobian) e.theta = m.theta;
   round_store(e.u, net.store_bf16 != 0);
   m.fifo.push_back(e);
-  m.h_out = module_forward(m, m.theta.data(), m.fifo.back().u, net.eps, net.store_bf16 != 0);
+  m.h_out = module_forward(m, m.theta.data(), m.fifo.back().u, net.eps, net.store_bf16 != 0, net.bn_rho);
   if (h_out) std::copy(m.h_out.begin(), m.h_out.end(), h_out);
+}
+
+// Evaluation forward of module k on h_in (running estimates, no training state touched).
+template <class T>
+void ddg_forward_eval(const Net<T>& net, int k, const T* h_in, T* h_out, const int* labels, T* loss_out,
+                      T* logits_out) {
+  const auto& m = net.mods[k - net.k_first];
+  std::vector<T> in(h_in, h_in + m.in_size());
+  round_store(in, net.store_bf16 != 0);
+  const std::vector<T> out = module_forward_eval(m, in, net.eps, net.store_bf16 != 0, labels, loss_out, logits_out);
+  if (h_out && !m.has_head) std::copy(out.begin(), out.end(), h_out);
 }
 
 // Returns 1 if a gradient was computed (s = t-K+k >= 0), else 0 (Eq. 8: zero gradient).
@@ -643,7 +749,7 @@ T bp_step(Net<T>& net, const T* x, const int* labels, T lr, int do_update) {
   round_store(h, net.store_bf16 != 0);  // the network input is a stored tensor too
   for (int k = 1; k <= K; ++k) {
     auto& m = net.mod(k);
-    m.h_out = module_forward(m, m.theta.data(), h, net.eps, net.store_bf16 != 0);
+    m.h_out = module_forward(m, m.theta.data(), h, net.eps, net.store_bf16 != 0, net.bn_rho);
     h = m.h_out;
   }
   std::vector<T> d;
@@ -754,6 +860,22 @@ Net<T>* net_create(int K, int k_first, int nmods, const int* nblocks, const int*
     auto& m = ((Net<T>*)p)->mod(k); std::copy(v, v + m.mom2.size(), m.mom2.begin()); }           \
   void orc_get_moment2_##SFX(void* p, int k, T* v) {                                             \
     auto& m = ((Net<T>*)p)->mod(k); std::copy(m.mom2.begin(), m.mom2.end(), v); }                \
+  void orc_forward_eval_##SFX(void* p, int k, const T* h_in, T* h_out, const int* labels,        \
+                              T* loss_out, T* logits_out) {                                      \
+    ddg_forward_eval<T>(*(Net<T>*)p, k, h_in, h_out, labels, loss_out, logits_out); }            \
+  void orc_set_bn_momentum_##SFX(void* p, double rho) { ((Net<T>*)p)->bn_rho = T(rho); }         \
+  long orc_running_count_##SFX(void* p, int k) {                                                 \
+    long n = 0;                                                                                  \
+    for (auto& b : ((Net<T>*)p)->mod(k).blocks) for (auto& u : b.u) n += 2 * u.co;               \
+    return n; }                                                                                  \
+  /* per conv unit in parameter order: running mean[C], then running variance[C] */             \
+  void orc_get_running_##SFX(void* p, int k, T* v) {                                             \
+    for (auto& b : ((Net<T>*)p)->mod(k).blocks) for (auto& u : b.u) {                            \
+      v = std::copy(u.rmean.begin(), u.rmean.end(), v); v = std::copy(u.rvar.begin(), u.rvar.end(), v); } } \
+  void orc_set_running_##SFX(void* p, int k, const T* v) {                                       \
+    for (auto& b : ((Net<T>*)p)->mod(k).blocks) for (auto& u : b.u) {                            \
+      std::copy(v, v + u.co, u.rmean.begin()); v += u.co;                                        \
+      std::copy(v, v + u.co, u.rvar.begin()); v += u.co; } }                                     \
   long orc_get_updates_##SFX(void* p, int k) { return ((Net<T>*)p)->mod(k).nupd; }               \
   void orc_set_updates_##SFX(void* p, int k, long n) { ((Net<T>*)p)->mod(k).nupd = n; }          \
   double orc_ddg_step_##SFX(void* p, const T* x, const int* labels, double lr) {                 \

@@ -34,7 +34,7 @@ def lib():
         _lib = C.CDLL(build())
         for sfx in ("f64", "f32"):
             getattr(_lib, f"orc_create_{sfx}").restype = C.c_void_p
-            for n in ("param_count", "in_size", "out_size", "get_delta", "fifo_depth", "time", "get_updates"):
+            for n in ("param_count", "in_size", "out_size", "get_delta", "fifo_depth", "time", "get_updates", "running_count"):
                 getattr(_lib, f"orc_{n}_{sfx}").restype = C.c_long
             for n in ("head", "ddg_step", "bp_step"):
                 getattr(_lib, f"orc_{n}_{sfx}").restype = C.c_double
@@ -157,6 +157,8 @@ class OracleNet:
         self.ty = _Typed(dtype)
         self.K, self.k_first, self.nmods = K, k_first, len(modules)
         self.batch = batch
+        self.num_classes = num_classes
+        self._has_head = [any(b[0] == 3 for b in m) for m in modules]   # block kind 3: the classifier
         nblocks = np.array([len(m) for m in modules], np.int32)
         desc = np.array([v for m in modules for b in m for v in b], np.int32)
         self._h = C.c_void_p(self.ty.fn("create")(
@@ -264,6 +266,38 @@ class OracleNet:
 
     def update(self, k, lr):
         self.ty.fn("update")(self._h, k, C.c_double(lr))
+
+    # evaluation: running BN estimates (per conv unit in parameter order: mean[C], variance[C])
+    def set_bn_momentum(self, rho):
+        self.ty.fn("set_bn_momentum")(self._h, C.c_double(rho))
+
+    def running_count(self, k):
+        return int(self.ty.fn("running_count")(self._h, k))
+
+    def get_running(self, k):
+        v = np.empty(self.running_count(k), self.ty.np)
+        self.ty.fn("get_running")(self._h, k, _p(v))
+        return v
+
+    def set_running(self, k, v):
+        v = self.ty.arr(v)
+        assert v.size == self.running_count(k)
+        self.ty.fn("set_running")(self._h, k, _p(v))
+
+    def forward_eval(self, k, h_in, labels=None):
+        """Evaluation forward of module k. Without a head: the module output. With a head:
+        (mean loss or None without labels, logits[N, classes])."""
+        h_in = self.ty.arr(h_in)
+        assert h_in.size == self.in_size(k)
+        if not self._has_head[k - self.k_first]:
+            out = np.empty(self.out_shape(k), self.ty.np)
+            self.ty.fn("forward_eval")(self._h, k, _p(h_in), _p(out), None, None, None)
+            return out
+        lab = np.ascontiguousarray(labels, np.int32) if labels is not None else None
+        loss = np.zeros(1, self.ty.np)
+        logits = np.empty((self.batch, self.num_classes), self.ty.np)
+        self.ty.fn("forward_eval")(self._h, k, _p(h_in), None, _p(lab), _p(loss), _p(logits))
+        return (float(loss[0]) if labels is not None else None), logits
 
     # Adam with delayed gradients (Algorithm 2) instead of momentum SGD
     def set_adam(self, on=True, beta1=0.9, beta2=0.999, eps=1e-8):
