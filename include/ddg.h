@@ -181,6 +181,30 @@ ddg_status ddg_get_moment2(ddg_module* m, float* host_dst);
 ddg_status ddg_set_update_count(ddg_module* m, long n);
 long ddg_get_update_count(const ddg_module* m);
 
+/* Evaluation (the paper reports test error, Section 5; batch normalisation at test time is
+ * left to its citations). Every BN layer keeps running estimates of mean and variance,
+ *   r <- (1-rho)*r + rho*(batch statistic),  variance unbiased (batch variance * m/(m-1)),
+ * starting from mean 0 / variance 1, moved by ddg_forward's pass on minibatch t only (never
+ * by the re-forward of a stored input). rho defaults to 0.1; it can be changed before the
+ * first iteration (0 switches the estimates off). The estimates are a flat fp32 vector of
+ * ddg_running_count values: per conv unit in parameter order, mean[C] then variance[C]; get /
+ * set use host pointers and synchronise. */
+ddg_status ddg_set_bn_momentum(ddg_module* m, float rho);
+size_t ddg_running_count(const ddg_module* m);
+ddg_status ddg_get_running(ddg_module* m, float* host_dst);
+ddg_status ddg_set_running(ddg_module* m, const float* host_src);
+/* Evaluation forward of the module on h_in [batch,in_h,in_w,in_c]: the same layers with every
+ * BN normalising by its running estimates, current weights. Without a head the output goes to
+ * h_out [batch,out_h,out_w,out_c]. With a head h_out is ignored; logits_out (device fp32
+ * [batch][classes], may be NULL) receives the logits and loss_out (device float, may be NULL;
+ * needs labels, device int32 [batch]) the mean cross-entropy. Allowed between iterations only
+ * (after ddg_update, before the next ddg_forward); it overwrites the module's forward buffers
+ * and nothing else: weights, estimates, the input ring and the gradient mailbox are
+ * untouched. Not available in stale-Jacobian mode (DDG_ERR_STATE), where every set of forward
+ * buffers holds a tape that a later backward pass needs. Enqueues on the module's stream. */
+ddg_status ddg_forward_eval(ddg_module* m, const void* h_in, void* h_out, const int32_t* labels,
+                            float* loss_out, float* logits_out);
+
 /* Wait for the module's stream. */
 ddg_status ddg_module_sync(ddg_module* m);
 
@@ -207,6 +231,13 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
 ddg_status ddg_pipeline_set_graphs(ddg_pipeline* p, int on);
 /* ddg_set_optimizer on every module of the pipeline. */
 ddg_status ddg_pipeline_set_optimizer(ddg_pipeline* p, int kind, float beta1, float beta2, float eps);
+/* Evaluation forward of the whole network (ddg_forward_eval of module 1..K in turn) on x
+ * [batch,in_h,in_w,in_c]; labels / loss_out / logits_out as for ddg_forward_eval of the head
+ * module. Between iterations only; synchronises. */
+ddg_status ddg_pipeline_forward_eval(ddg_pipeline* p, const void* x, const int32_t* labels, float* loss_out,
+                                     float* logits_out);
+/* ddg_set_bn_momentum on every module (before the first iteration). */
+ddg_status ddg_pipeline_set_bn_momentum(ddg_pipeline* p, float rho);
 /* Copy module k's latest forward output / the error gradient last delivered to module k
  * (mailbox) to host memory as fp32 NHWC; synchronises. *iteration receives the iteration the
  * mailbox content belongs to (-1: none yet). */

@@ -207,8 +207,21 @@ struct HeadArgs {
   float* pooled; float* dlogits; float* loss_n; float* loss_out;
   float* dfcw; float* dfcb; void* dh;
   int N, HW, C, classes, dtype;
+  float* logits_out;     // optional [N][classes]
 };
+// dfcw == nullptr: evaluation (no gradients; dh must be null too).
 hipError_t head_launch(const HeadArgs& a, hipStream_t s);
+
+// Running batch-norm estimates and evaluation vectors, all layers of a module per launch.
+struct RunDesc {
+  const float* mean; const float* invstd;      // batch statistics of the forward pass that just ran
+  const float* gamma; const float* beta;
+  float* rmean; float* rvar;                   // running estimates
+  float* escale; float* eshift;                // what the evaluation forward normalises with
+  int C; float count, eps;
+};
+hipError_t running_update_launch(const RunDesc* dev_descs, int n, int max_c, float rho, hipStream_t s);
+hipError_t eval_vectors_launch(const RunDesc* dev_descs, int n, int max_c, hipStream_t s);
 
 // lr_dev != nullptr: the step size is read from device memory (lets a captured graph be replayed
 // with a different step size).

@@ -41,7 +41,7 @@ enum ProfKind {
   // the GEMM-class kernels of the wide layers
   PK_CONV_FPROP_WIDE = PK_BWD_PAIR_T64 + 1, PK_CONV_DGRAD_WIDE, PK_CONV_WGRAD_WIDE,
   PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
-  PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_COUNT
+  PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_BN_RUNNING, PK_COUNT
 };
 static const char* kProfNames[PK_COUNT] = {
   "conv_fprop.generic", "conv_fprop.tiled_c16_w32", "conv_fprop.tiled_c32_w16", "conv_fprop.tiled_c64_w8",
@@ -50,7 +50,7 @@ static const char* kProfNames[PK_COUNT] = {
   "conv_bwd_pair.tiled_c16_w32", "conv_bwd_pair.tiled_c32_w16", "conv_bwd_pair.tiled_c64_w8",
   "conv_fprop.wide", "conv_dgrad.wide", "conv_wgrad.wide",
   "wgrad_reduce", "bn_finalize", "bn_apply",
-  "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam"};
+  "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam", "bn_running"};
 
 struct Unit {  // convolution + batch normalisation
   int cin = 0, cout = 0, R = 0, stride = 1, pad = 0;
@@ -76,6 +76,8 @@ struct Unit {  // convolution + batch normalisation
   int fcap = 0;                 // rows reserved per group in fstat
   int frows = 0;                // rows written by the last forward conv (per group)
   // consumers finalise the partial rows themselves (their reduction is built for these widths)
+  float *rmean = nullptr, *rvar = nullptr;     // running estimates for evaluation
+  float *escale = nullptr, *eshift = nullptr;  // evaluation-time scale and shift derived from them
   bool wide_f = false, wide_d = false;   // the GEMM-class kernel runs the forward conv / the input gradient
   int wide_splits = 0;                   // > 0: the GEMM-class weight-gradient kernel, this many pixel slices
   bool small_c() const { return cout == 16 || cout == 32 || cout == 64; }
@@ -144,6 +146,16 @@ struct ddg_module {
     const void* x = nullptr; const float* xsc = nullptr; const float* xsh = nullptr; const void* dz = nullptr;
   } pend_w;
   bool defer_wgrad = true;         // DDG_NO_BWD_PAIR=1 switches the deferred weight gradient off
+  // Evaluation: running batch-norm estimates, flat per conv unit in parameter order (mean[C],
+  // variance[C]), followed in the same allocation by the evaluation scale/shift vectors; one
+  // table of layer descriptors per group of forward buffers (the statistics the estimates
+  // follow are those of the group that held the current minibatch), plus one for the forward
+  // stream's own buffers.
+  float* running = nullptr; size_t nrunning = 0;
+  float bn_rho = 0.1f;
+  std::vector<RunDesc*> run_descs; RunDesc* run_descs_f = nullptr; int n_run = 0, run_max_c = 0;
+  int32_t* zero_labels = nullptr;  // head modules: labels for an evaluation without labels
+  bool eval_mode = false;          // the forward helpers normalise with the evaluation vectors
   float* ws_stat = nullptr; size_t ws_stat_elems = 0;
   PackDesc* pack_descs = nullptr; int n_pack = 0;     // device tables for the whole-module kernels
   WredDesc* wred_descs = nullptr; int n_wred = 0; int wred_max = 0;   // wred_max: largest Cout*Jp
@@ -545,12 +557,14 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
     ConvStat st{};
     st.mode = 1; st.partial = fstat;
     BnRows ir{};
-    const bool from_rows = src && src->small_c();
+    const bool from_rows = src && src->small_c() && !m->eval_mode;
     if (from_rows) ir = fwd_rows(m, *src, g);
     const int svo = src ? g * src->vec_stride() : 0;
+    const float* ssc = !src ? nullptr : (m->eval_mode ? src->escale : src->scale + svo);
+    const float* ssh = !src ? nullptr : (m->eval_mode ? src->eshift : src->shift + svo);
     Launch L(m, PK_CONV_FPROP + u.tiled_instance(),
              G * (((res ? 3.0 : 1.0) * u.in_elems() + u.out_elems()) * (double)m->esz) + wbytes(m, u), G * conv_flops(u));
-    DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? src->scale + svo : nullptr, (src && !from_rows) ? src->shift + svo : nullptr,
+    DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? ssc : nullptr, (src && !from_rows) ? ssh : nullptr,
                               from_rows ? &ir : nullptr, u.wpack_f, z, st, nullptr, nullptr, G * u.N, u.H, u.W,
                               u.cin, G * u.tiled_grid, m->stream, res, y_store, G, src ? src->vec_stride() : 0));
   } else {
@@ -560,7 +574,8 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
       const int svo = src ? g * src->vec_stride() : 0;   // (a wide producer's vectors are final: it ran its finalise launch)
       Launch L(m, PK_CONV_FPROP_WIDE, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
       DDG_TRY(conv_wide_launch(in, u.wpack_f, z, fstat, nullptr, nullptr, u.N, u.H, u.W, u.cin, u.cout, u.R, m->stream,
-                               src ? src->scale + svo : nullptr, src ? src->shift + svo : nullptr));
+                               !src ? nullptr : (m->eval_mode ? src->escale : src->scale + svo),
+                               !src ? nullptr : (m->eval_mode ? src->eshift : src->shift + svo)));
     } else {
       ConvArgs a = u.fprop;
       conv_plan(a);
@@ -570,7 +585,7 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
       DDG_TRY(conv_launch(a, m->stream));
     }
   }
-  if (!u.small_c()) {
+  if (!u.small_c() && !m->eval_mode) {   // (evaluation normalises with the running estimates)
     Launch L(m, PK_BN_FINALIZE);
     DDG_TRY(bn_finalize_launch(fstat, u.frows, u.cout, m->theta + u.og, m->theta + u.ob,
                                (float)((size_t)u.N * u.P * u.Q), m->d.bn_eps, u.mean + vo, u.invstd + vo, u.scale + vo,
@@ -583,14 +598,16 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
 // of a projection unit. res and y point at group g.
 ddg_status apply_bn(ddg_module* m, Unit& u, const void* res, Unit* ru, void* y, int g = 0) {
   BnRows zr{}, rr{};
-  const bool zrows = u.small_c(), rrows = ru && ru->small_c();
+  const bool zrows = u.small_c() && !m->eval_mode, rrows = ru && ru->small_c() && !m->eval_mode;
   if (zrows) zr = fwd_rows(m, u, g);
   if (rrows) rr = fwd_rows(m, *ru, g);
   const int vo = g * u.vec_stride(), rvo = ru ? g * ru->vec_stride() : 0;
   Launch L(m, PK_BN_APPLY, ((res || ru) ? 3.0 : 2.0) * u.out_elems() * m->esz);
-  DDG_TRY(bn_apply_launch(grp(u.z, u.out_elems() * m->esz, g), u.scale + vo, u.shift + vo, zrows ? &zr : nullptr,
-                          ru ? grp(ru->z, ru->out_elems() * m->esz, g) : res, ru ? ru->scale + rvo : nullptr,
-                          ru ? ru->shift + rvo : nullptr, rrows ? &rr : nullptr, y, u.out_elems(), u.cout, 1,
+  const bool ev = m->eval_mode;
+  DDG_TRY(bn_apply_launch(grp(u.z, u.out_elems() * m->esz, g), ev ? u.escale : u.scale + vo, ev ? u.eshift : u.shift + vo,
+                          zrows ? &zr : nullptr,
+                          ru ? grp(ru->z, ru->out_elems() * m->esz, g) : res, !ru ? nullptr : (ev ? ru->escale : ru->scale + rvo),
+                          !ru ? nullptr : (ev ? ru->eshift : ru->shift + rvo), rrows ? &rr : nullptr, y, u.out_elems(), u.cout, 1,
                           m->d.compute, m->stream));
   return DDG_OK;
 }
@@ -1014,6 +1031,64 @@ ddg_status build_forward_shadow(ddg_module* m) {
   return DDG_OK;
 }
 
+// Running batch-norm estimates (start: mean 0, variance 1), the evaluation vectors, and the
+// per-group tables of layer descriptors for the kernels that maintain them.
+ddg_status build_running_tables(ddg_module* m) {
+  size_t sum_c = 0;
+  for (const Blk& b : m->blocks) for (const Unit& u : b.u) { sum_c += u.cout; ++m->n_run; if (u.cout > m->run_max_c) m->run_max_c = u.cout; }
+  m->nrunning = 2 * sum_c;
+  if (m->d.dry_run || m->n_run == 0) return DDG_OK;
+  void* p = nullptr;
+  DDG_OKAY(dev_alloc(m, &p, 4 * sum_c * sizeof(float)));
+  m->running = (float*)p;
+  std::vector<float> init(4 * sum_c, 0.f);
+  size_t off = 0;
+  auto assign = [&](std::vector<Blk>& blocks) {
+    size_t o = 0;
+    for (Blk& b : blocks) for (Unit& u : b.u) {
+      u.rmean = m->running + o; u.rvar = u.rmean + u.cout;
+      u.escale = m->running + 2 * sum_c + o; u.eshift = u.escale + u.cout;
+      o += 2 * (size_t)u.cout;
+    }
+  };
+  assign(m->blocks);
+  if (m->two_streams) assign(m->fblocks);
+  for (const Blk& b : m->blocks) for (const Unit& u : b.u) {
+    for (int c = 0; c < u.cout; ++c) init[off + u.cout + c] = 1.f;
+    off += 2 * (size_t)u.cout;
+  }
+  if (hipMemcpy(m->running, init.data(), init.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
+    return fail(DDG_ERR_DEVICE, "initialising the running estimates failed");
+  auto table = [&](const std::vector<Blk>& blocks, RunDesc** out) -> ddg_status {
+    std::vector<RunDesc> t;
+    for (const Blk& b : blocks) for (const Unit& u : b.u) {
+      RunDesc r{};
+      r.mean = u.mean; r.invstd = u.invstd; r.gamma = m->theta + u.og; r.beta = m->theta + u.ob;
+      r.rmean = u.rmean; r.rvar = u.rvar; r.escale = u.escale; r.eshift = u.eshift;
+      r.C = u.cout; r.count = (float)((size_t)u.N * u.P * u.Q); r.eps = m->d.bn_eps;
+      t.push_back(r);
+    }
+    void* q = nullptr;
+    DDG_OKAY(dev_alloc(m, &q, t.size() * sizeof(RunDesc)));
+    if (hipMemcpy(q, t.data(), t.size() * sizeof(RunDesc), hipMemcpyHostToDevice) != hipSuccess)
+      return fail(DDG_ERR_DEVICE, "copying the layer tables failed");
+    *out = (RunDesc*)q;
+    return DDG_OK;
+  };
+  for (int g = 0; g < m->groups; ++g) {
+    RunDesc* t = nullptr;
+    DDG_OKAY(table(group_view(m, g), &t));
+    m->run_descs.push_back(t);
+  }
+  if (m->two_streams) DDG_OKAY(table(m->fblocks, &m->run_descs_f));
+  if (m->d.num_classes > 0) {
+    DDG_OKAY(dev_alloc(m, &p, (size_t)m->d.batch * sizeof(int32_t)));
+    m->zero_labels = (int32_t*)p;
+    if (hipMemset(p, 0, (size_t)m->d.batch * sizeof(int32_t)) != hipSuccess) return fail(DDG_ERR_DEVICE, "hipMemset failed");
+  }
+  return DDG_OK;
+}
+
 ddg_status sync_streams(ddg_module* m) {
   DDG_TRY(hipStreamSynchronize(m->bstream));
   if (m->two_streams) DDG_TRY(hipStreamSynchronize(m->fstream));
@@ -1051,6 +1126,7 @@ ddg_status ddg_module_create(const ddg_module_desc* desc, ddg_module** out) {
   if (m->two_streams) m->fstream = (hipStream_t)desc->forward_stream;
   ddg_status st = build_plan(m);
   if (st == DDG_OK && m->two_streams) st = build_forward_shadow(m);
+  if (st == DDG_OK) st = build_running_tables(m);
   if (st != DDG_OK) {
     for (void* p : m->allocs) (void)hipFree(p);
     delete m;
@@ -1197,9 +1273,12 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   { Launch L(m, PK_COPY, 2.0 * m->in_elems * m->esz); DDG_TRY(copy_launch(h_in, slot, m->in_elems * m->esz, m->stream)); }
   // A module with delay > 0 re-forwards before its backward, so this pass need not keep a
   // tape and writes straight to h_out; the last module keeps the tape for its own backward.
+  // the running estimates follow the batch statistics of this pass on minibatch t
+  const RunDesc* run_table = nullptr;
   if (m->stale) {
     // keep this pass: its tape, the weights it used and their input-gradient operands
     const int g = (int)(t % m->nslots);
+    if (m->n_run) run_table = m->run_descs[g];
     std::vector<Blk> tape = group_view(m, g);
     { Launch L(m, PK_COPY, 2.0 * m->nparams * sizeof(float));
       DDG_TRY(copy_launch(m->theta, m->theta_snap + (size_t)g * m->nparams, m->nparams * sizeof(float), m->stream)); }
@@ -1212,10 +1291,11 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
   } else if (paired) {
     DDG_OKAY(run_forward_pair(m, m->blocks, m->ring[(t - m->delay) % m->nslots], slot, h_out));
     m->tape_is_current = true;    // group 0 holds the tape of iteration t - delay
+    if (m->n_run) run_table = m->run_descs[1];   // group 1 held minibatch t
   } else if (m->delay > 0) {
     DDG_OKAY(run_forward(m, m->two_streams ? m->fblocks : m->blocks, slot, h_out));
     m->tape_is_current = false;
-    if (self_sync) DDG_TRY(hipEventRecord(m->ev_fwd[t & 1], m->fstream));
+    if (m->n_run) run_table = m->two_streams ? m->run_descs_f : m->run_descs[0];
   } else {
     DDG_OKAY(run_forward(m, m->blocks, slot, nullptr));
     m->tape_is_current = true;
@@ -1223,6 +1303,73 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
       Launch L(m, PK_COPY);
       DDG_TRY(copy_launch(m->blocks[m->blocks.size() - (head ? 2 : 1)].y, h_out, m->out_elems * m->esz, m->stream));
     }
+    if (m->n_run) run_table = m->run_descs[0];
+  }
+  if (run_table && m->bn_rho > 0.f) {
+    Launch L(m, PK_BN_RUNNING);
+    DDG_TRY(running_update_launch(run_table, m->n_run, m->run_max_c, m->bn_rho, m->stream));
+  }
+  if (m->delay > 0 && !m->stale && !paired && self_sync) DDG_TRY(hipEventRecord(m->ev_fwd[t & 1], m->fstream));
+  return DDG_OK;
+}
+
+ddg_status ddg_set_bn_momentum(ddg_module* m, float rho) {
+  DDG_OKAY(check_handle(m));
+  if (!(rho >= 0.f && rho <= 1.f)) return fail(DDG_ERR_INVALID_ARG, "the weight of the newest batch statistic must lie in [0, 1]");
+  if (m->t_next != 0) return fail(DDG_ERR_STATE, "the weight can only be set before the first iteration");
+  m->bn_rho = rho;
+  return DDG_OK;
+}
+
+size_t ddg_running_count(const ddg_module* m) { return m ? m->nrunning : 0; }
+
+ddg_status ddg_get_running(ddg_module* m, float* host_dst) {
+  DDG_OKAY(check_handle(m));
+  if (!host_dst) return fail(DDG_ERR_INVALID_ARG, "destination is null");
+  if (m->d.dry_run || m->nrunning == 0) return DDG_OK;
+  DDG_OKAY(sync_streams(m));
+  DDG_TRY(hipMemcpy(host_dst, m->running, m->nrunning * sizeof(float), hipMemcpyDeviceToHost));
+  return DDG_OK;
+}
+
+ddg_status ddg_set_running(ddg_module* m, const float* host_src) {
+  DDG_OKAY(check_handle(m));
+  if (!host_src) return fail(DDG_ERR_INVALID_ARG, "source is null");
+  if (m->d.dry_run || m->nrunning == 0) return DDG_OK;
+  DDG_OKAY(sync_streams(m));
+  DDG_TRY(hipMemcpy(m->running, host_src, m->nrunning * sizeof(float), hipMemcpyHostToDevice));
+  return DDG_OK;
+}
+
+ddg_status ddg_forward_eval(ddg_module* m, const void* h_in, void* h_out, const int32_t* labels, float* loss_out,
+                            float* logits_out) {
+  DDG_OKAY(check_handle(m));
+  const bool head = m->d.num_classes > 0;
+  if (!h_in) return fail(DDG_ERR_INVALID_ARG, "h_in is null");
+  if (!head && !h_out) return fail(DDG_ERR_INVALID_ARG, "h_out is null");
+  if (head && loss_out && !labels) return fail(DDG_ERR_INVALID_ARG, "the loss needs labels");
+  if (((uintptr_t)h_in & 15) || ((uintptr_t)h_out & 15)) return fail(DDG_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+  if (m->phase != 0) return fail(DDG_ERR_STATE, "evaluation runs between iterations (after ddg_update, before the next ddg_forward)");
+  if (m->stale) return fail(DDG_ERR_STATE, "no evaluation forward in stale-Jacobian mode: every set of forward buffers holds a kept tape");
+  if (m->d.dry_run) return DDG_OK;
+  m->stream = m->bstream;
+  if (m->n_run) DDG_TRY(eval_vectors_launch(m->run_descs[0], m->n_run, m->run_max_c, m->stream));
+  const int nres = (int)m->blocks.size() - (head ? 1 : 0);
+  m->eval_mode = true;
+  ddg_status st = DDG_OK;
+  if (nres > 0) st = run_forward(m, m->blocks, h_in, head ? nullptr : h_out);
+  m->eval_mode = false;
+  m->tape_is_current = false;     // the forward buffers of group 0 now hold this pass
+  DDG_OKAY(st);
+  if (head) {
+    Blk& hb = m->blocks.back();
+    HeadArgs a{};
+    a.h = nres > 0 ? m->blocks[nres - 1].y : h_in; a.fcw = m->theta + hb.ofcw; a.fcb = m->theta + hb.ofcb;
+    a.labels = labels ? labels : m->zero_labels;
+    a.pooled = hb.pooled; a.dlogits = hb.dlogits; a.loss_n = hb.loss_n; a.loss_out = loss_out;
+    a.dfcw = nullptr; a.dfcb = nullptr; a.dh = nullptr; a.logits_out = logits_out;
+    a.N = m->d.batch; a.HW = hb.HW; a.C = hb.C; a.classes = m->d.num_classes; a.dtype = m->d.compute;
+    DDG_TRY(head_launch(a, m->stream));
   }
   return DDG_OK;
 }

@@ -202,6 +202,37 @@ ddg_status ddg_pipeline_set_optimizer(ddg_pipeline* p, int kind, float beta1, fl
   return DDG_OK;
 }
 
+ddg_status ddg_pipeline_set_bn_momentum(ddg_pipeline* p, float rho) {
+  if (!p) return DDG_ERR_INVALID_ARG;
+  for (int k = 1; k <= p->K; ++k) {
+    const ddg_status st = ddg_set_bn_momentum(p->mods[k], rho);
+    if (st != DDG_OK) return st;
+  }
+  return DDG_OK;
+}
+
+// Evaluation of the whole network between iterations. Module k writes into the buffer that
+// iteration p->t will overwrite anyway (the one ddg_pipeline_get_h does not read); modules run
+// one after the other, each waited for.
+ddg_status ddg_pipeline_forward_eval(ddg_pipeline* p, const void* x, const int32_t* labels, float* loss_out,
+                                     float* logits_out) {
+  if (!p || !x) return DDG_ERR_INVALID_ARG;
+  if (p->dry) return DDG_OK;
+  ddg_status st = ddg_pipeline_sync(p);
+  if (st != DDG_OK) return st;
+  const void* in = x;
+  for (int k = 1; k <= p->K; ++k) {
+    void* out = (k < p->K) ? ((p->t & 1) ? p->h_odd[k] : p->h[k]) : nullptr;
+    st = ddg_forward_eval(p->mods[k], in, out, k == p->K ? labels : nullptr, k == p->K ? loss_out : nullptr,
+                          k == p->K ? logits_out : nullptr);
+    if (st != DDG_OK) return st;
+    st = ddg_module_sync(p->mods[k]);
+    if (st != DDG_OK) return st;
+    in = out;
+  }
+  return DDG_OK;
+}
+
 ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labels, float lr, float* loss_out) {
   if (!p || !x || !labels) return DDG_ERR_INVALID_ARG;
   const int K = p->K;

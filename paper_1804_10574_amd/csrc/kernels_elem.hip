@@ -491,6 +491,53 @@ hipError_t bn_bwd_apply_launch(const void* dy, const void* mask, const float* ms
 }
 
 // ---------------------------------------------------------------------------------
+// Running batch-norm estimates (for evaluation) of all layers of a module in one launch:
+//   rmean <- (1-rho)*rmean + rho*mean,  rvar <- (1-rho)*rvar + rho*var*m/(m-1)
+// with the batch statistics of the forward pass that just ran (var = 1/invstd^2 - eps), and
+// the per-channel vectors the evaluation forward normalises with:
+//   escale = gamma/sqrt(rvar + eps),  eshift = beta - rmean*escale.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void running_update_kernel(const RunDesc* __restrict__ descs, float rho) {
+  const RunDesc d = descs[blockIdx.y];
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= d.C) return;
+  const float is = d.invstd[c];
+  const float var = 1.f / (is * is) - d.eps;
+  d.rmean[c] = (1.f - rho) * d.rmean[c] + rho * d.mean[c];
+  d.rvar[c] = (1.f - rho) * d.rvar[c] + rho * (var * d.count / (d.count - 1.f));
+}
+
+__global__ __launch_bounds__(256) void eval_vectors_kernel(const RunDesc* __restrict__ descs) {
+  const RunDesc d = descs[blockIdx.y];
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= d.C) return;
+  const float sc = d.gamma[c] / sqrtf(d.rvar[c] + d.eps);
+  d.escale[c] = sc;
+  d.eshift[c] = d.beta[c] - d.rmean[c] * sc;
+}
+
+hipError_t running_update_launch(const RunDesc* dev_descs, int n, int max_c, float rho, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  DDG_LAUNCH(running_update_kernel, dim3((max_c + 255) / 256, n), dim3(256), 0, s, dev_descs, rho);
+  return hipGetLastError();
+}
+
+hipError_t eval_vectors_launch(const RunDesc* dev_descs, int n, int max_c, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  DDG_LAUNCH(eval_vectors_kernel, dim3((max_c + 255) / 256, n), dim3(256), 0, s, dev_descs);
+  return hipGetLastError();
+}
+
+// mean of the per-sample losses, added in order (evaluation; training gets it from head_wgrad_kernel)
+__global__ void loss_mean_kernel(const float* __restrict__ loss_n, int N, float* __restrict__ out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    float l = 0.f;
+    for (int n = 0; n < N; ++n) l += loss_n[n];
+    *out = l / (float)N;
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // Head. Small: N x C x classes is a few hundred thousand operations.
 // ---------------------------------------------------------------------------------
 // Per sample (one workgroup of 256 threads): global average pool, logits, stable softmax, loss,
@@ -502,7 +549,7 @@ __global__ __launch_bounds__(256) void head_sample_kernel(const T* __restrict__ 
                                                           const int32_t* __restrict__ labels,
                                                           float* __restrict__ pooled, float* __restrict__ dlogits,
                                                           float* __restrict__ loss_n, T* __restrict__ dh, int N,
-                                                          int HW, int C, int classes) {
+                                                          int HW, int C, int classes, float* __restrict__ logits_out) {
   extern __shared__ float sm[];
   float* s_pool = sm;               // [C]
   float* s_dh = sm + C;             // [C]
@@ -539,6 +586,7 @@ __global__ __launch_bounds__(256) void head_sample_kernel(const T* __restrict__ 
 #pragma unroll 8
     for (int c = 0; c < C; ++c) a += w[c] * s_pool[c];
     s_lg[j] = a;
+    if (logits_out) logits_out[(size_t)n * classes + j] = a;
   }
   __syncthreads();
   float mx = s_lg[0];
@@ -630,10 +678,14 @@ hipError_t head_launch(const HeadArgs& a, hipStream_t s) {
   const size_t lds = (size_t)(2 * a.C + 2 * a.classes + 256) * sizeof(float);
   if (a.dtype == BF16)
     DDG_LAUNCH(head_sample_kernel<bf16_t>, dim3(a.N), dim3(256), lds, s, (const bf16_t*)a.h, a.fcw, a.fcb, a.labels,
-               a.pooled, a.dlogits, a.loss_n, (bf16_t*)a.dh, a.N, a.HW, a.C, a.classes);
+               a.pooled, a.dlogits, a.loss_n, (bf16_t*)a.dh, a.N, a.HW, a.C, a.classes, a.logits_out);
   else
     DDG_LAUNCH(head_sample_kernel<float>, dim3(a.N), dim3(256), lds, s, (const float*)a.h, a.fcw, a.fcb, a.labels,
-               a.pooled, a.dlogits, a.loss_n, (float*)a.dh, a.N, a.HW, a.C, a.classes);
+               a.pooled, a.dlogits, a.loss_n, (float*)a.dh, a.N, a.HW, a.C, a.classes, a.logits_out);
+  if (!a.dfcw) {   // evaluation: no gradients; the mean loss if asked for
+    if (a.loss_out) DDG_LAUNCH(loss_mean_kernel, dim3(1), dim3(64), 0, s, a.loss_n, a.N, a.loss_out);
+    return hipGetLastError();
+  }
   DDG_LAUNCH(head_wgrad_kernel, dim3(a.classes), dim3(256), 0, s, a.pooled, a.dlogits, a.loss_n, a.dfcw, a.dfcb,
              a.loss_out, a.N, a.C, a.classes);
   return hipGetLastError();

@@ -74,6 +74,13 @@ def load_library():
         "ddg_set_update_count": (st, [vp, C.c_long]),
         "ddg_get_update_count": (C.c_long, [vp]),
         "ddg_pipeline_set_optimizer": (st, [vp, C.c_int, C.c_float, C.c_float, C.c_float]),
+        "ddg_set_bn_momentum": (st, [vp, C.c_float]),
+        "ddg_running_count": (C.c_size_t, [vp]),
+        "ddg_get_running": (st, [vp, vp]),
+        "ddg_set_running": (st, [vp, vp]),
+        "ddg_forward_eval": (st, [vp, vp, vp, vp, vp, vp]),
+        "ddg_pipeline_forward_eval": (st, [vp, vp, vp, vp, vp]),
+        "ddg_pipeline_set_bn_momentum": (st, [vp, C.c_float]),
         "ddg_module_sync": (st, [vp]),
         "ddg_pipeline_create": (st, [C.POINTER(ModuleDesc), C.c_int, C.POINTER(vp), C.POINTER(vp)]),
         "ddg_pipeline_destroy": (st, [vp]),
@@ -104,6 +111,8 @@ EXPORTS = ["ddg_module_create", "ddg_module_destroy", "ddg_param_count", "ddg_ou
            "ddg_forward", "ddg_backward_delayed", "ddg_update", "ddg_module_sync",
            "ddg_set_optimizer", "ddg_set_moment2", "ddg_get_moment2", "ddg_set_update_count", "ddg_get_update_count",
            "ddg_pipeline_set_optimizer",
+           "ddg_set_bn_momentum", "ddg_running_count", "ddg_get_running", "ddg_set_running", "ddg_forward_eval",
+           "ddg_pipeline_forward_eval", "ddg_pipeline_set_bn_momentum",
            "ddg_pipeline_create", "ddg_pipeline_destroy", "ddg_pipeline_module", "ddg_pipeline_step",
            "ddg_pipeline_set_graphs", "ddg_pipeline_get_h", "ddg_pipeline_get_delta", "ddg_pipeline_sync", "ddg_profile_kinds",
            "ddg_profile_kind_name", "ddg_profile_enable", "ddg_profile_read", "ddg_profile_reset",
@@ -216,6 +225,27 @@ class Module:
         out = np.empty(self.param_count(), np.float32)
         return out, fn(self._h, _ptr(out))
 
+    # evaluation: running BN estimates (per conv unit in parameter order: mean[C], variance[C])
+    def set_bn_momentum(self, rho):
+        _check(self._lib.ddg_set_bn_momentum(self._h, rho))
+
+    def running_count(self) -> int:
+        return int(self._lib.ddg_running_count(self._h))
+
+    def get_running(self):
+        out = np.empty(self.running_count(), np.float32)
+        _check(self._lib.ddg_get_running(self._h, _ptr(out)))
+        return out
+
+    def set_running(self, src):
+        src = np.ascontiguousarray(src, np.float32)
+        assert src.size == self.running_count()
+        _check(self._lib.ddg_set_running(self._h, _ptr(src)))
+
+    def forward_eval(self, h_in, h_out=None, labels=None, loss_out=None, logits_out=None):
+        _check(self._lib.ddg_forward_eval(self._h, _ptr(h_in), _ptr(h_out), _ptr(labels), _ptr(loss_out),
+                                          _ptr(logits_out)))
+
     def get_params(self):
         out = np.empty(self.param_count(), np.float32)
         _check(self._lib.ddg_get_params(self._h, _ptr(out)))
@@ -302,6 +332,12 @@ class Pipeline:
 
     def set_optimizer(self, kind, beta1=0.9, beta2=0.999, eps=1e-8):
         _check(self._lib.ddg_pipeline_set_optimizer(self._h, kind, beta1, beta2, eps))
+
+    def set_bn_momentum(self, rho):
+        _check(self._lib.ddg_pipeline_set_bn_momentum(self._h, rho))
+
+    def forward_eval(self, x, labels=None, loss_out=None, logits_out=None):
+        _check(self._lib.ddg_pipeline_forward_eval(self._h, _ptr(x), _ptr(labels), _ptr(loss_out), _ptr(logits_out)))
 
     def sync(self):
         _check(self._lib.ddg_pipeline_sync(self._h))

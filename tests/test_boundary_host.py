@@ -61,6 +61,45 @@ def test_dry_run_state_machine():
     assert e.value.status == 1
 
 
+def test_evaluation_calls_follow_the_state_machine():
+    """ddg_forward_eval runs between iterations only, needs labels for a loss, and is refused in
+    stale-Jacobian mode; the running estimates count two values per BN channel; the weight of
+    the newest batch statistic can only be set before the first iteration."""
+    wl = wk.get_workload("tiny_k2")
+    d = descs_for(wl, dry_run=True)
+    m = ddg.Module(d[0])
+    channels = sum(co for b in wl.modules[0].blocks for _, _, co, _, _ in wk.configs.conv_units(b))
+    assert m.running_count() == 2 * channels
+    fake = 4096
+    m.set_bn_momentum(0.2)
+    with pytest.raises(ddg.DDGError) as e:
+        m.set_bn_momentum(1.5)
+    assert e.value.status == 1
+    m.forward_eval(fake, fake)                 # before iteration 0: allowed
+    with pytest.raises(ddg.DDGError) as e:
+        m.forward_eval(fake, None)             # a module without a head needs h_out
+    assert e.value.status == 1
+    m.forward(0, fake, fake)
+    with pytest.raises(ddg.DDGError) as e:
+        m.forward_eval(fake, fake)             # in the middle of iteration 0
+    assert e.value.status == 3
+    m.backward_delayed(0, delta_in=fake)
+    m.update(0, 0.1)
+    m.forward_eval(fake, fake)
+    with pytest.raises(ddg.DDGError) as e:
+        m.set_bn_momentum(0.1)                 # the run has begun
+    assert e.value.status == 3
+    head = ddg.Module(d[1])
+    with pytest.raises(ddg.DDGError) as e:
+        head.forward_eval(fake, None, labels=None, loss_out=fake)
+    assert e.value.status == 1
+    head.forward_eval(fake, None, labels=fake, loss_out=fake, logits_out=fake)
+    stale = ddg.Module(descs_for(wl, dry_run=True, stale_jacobian=True)[0])
+    with pytest.raises(ddg.DDGError) as e:
+        stale.forward_eval(fake, fake)
+    assert e.value.status == 3
+
+
 def test_head_module_argument_rules():
     wl = wk.get_workload("tiny_k2")
     d = descs_for(wl, dry_run=True)
