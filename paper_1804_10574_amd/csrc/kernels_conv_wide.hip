@@ -1,25 +1,29 @@
 // Convolution (forward and input-gradient) for wide bf16 layers: 1x1 and 3x3, stride 1,
 // contraction channels a power of two >= 64, output channels a multiple of 128 (the bottleneck
-// stage of an ImageNet-shaped ResNet: 1024 -> 256 -> 256 -> 1024 at 14x14). These layers are
-// matrix-core bound, so this is a GEMM-class kernel: a workgroup owns a 64-pixel x 128-channel
-// output tile and walks over the contraction in chunks of 64 channels of one tap.
+// stage of an ImageNet-shaped ResNet: 1024 -> 256 -> 256 -> 1024 at 14x14). By arithmetic
+// intensity these layers are matrix-core bound, so this is a GEMM-class kernel: a workgroup
+// owns a 64-pixel x 128-channel output tile and walks over the contraction in chunks of 64 or
+// 128 channels of one tap, one barrier per chunk.
 //
-//   pixel operand:  64 rows x 64 channels per chunk, staged in LDS (row stride 144 bytes, so
-//                   the 16 rows of a fragment read fall into distinct bank groups); a 3x3 tap
-//                   is a shifted pixel row, out-of-image rows are zero: no im2col matrix.
+//   pixel operand:  64 rows x one chunk of channels, through registers into one of two LDS
+//                   buffers (rows padded by 16 bytes, so the 16 rows of a fragment read fall
+//                   into distinct bank groups); a 3x3 tap is a shifted pixel row, out-of-image
+//                   rows are zero: no im2col matrix.
 //   weight operand: the packed operand of the generic kernel is already fragment-ordered
-//                   ([k-step][16-channel block][lane][8]), so a chunk's 128 channels x 64 k is
-//                   16 fragments of 1 KiB that are copied to LDS as they lie (fragment reads are
-//                   lane-contiguous, conflict-free).
-//   Both go through registers into one of two LDS buffers; the global loads of a chunk are
-//   issued four chunks ahead (four named register sets), one barrier per chunk.
+//                   ([k-step][16-channel block][lane][8]), so a wave loads the fragments it
+//                   multiplies with straight from global memory into registers, 1 KiB
+//                   contiguous per load; weights never touch LDS and no two waves of a
+//                   workgroup load the same fragment.
+//   Loads are requested two chunks ahead (named register sets, loop body written out twice)
+//   and none of them is conditional, so the compiler's wait counts leave the newest in flight.
 //
-// Eight waves: 2 (pixels) x 2 (channels) x 2 (the two 32-channel k-steps of a chunk). A wave
-// owns 32 pixels x 64 channels = 8 accumulator tiles of mfma_f32_16x16x32_bf16 (weights as
-// rows, so a lane holds 4 consecutive channels of one pixel) for its half of the contraction;
-// two waves per SIMD let one wave's LDS and global traffic run under the other's MFMAs. The epilogue passes the tile through LDS so that stores (and the optional masked
-// shortcut-gradient term) are 16-byte accesses along the channels, and accumulates the
-// batch-norm statistics of the stored values (one partial row per 64-pixel tile).
+// Eight waves: 4 (32 channels each) x 2 (halves of a chunk's k-steps). A wave owns all 64
+// pixels x 32 channels = 8 accumulator tiles of mfma_f32_16x16x32_bf16 (weights as rows, so a
+// lane holds 4 consecutive channels of one pixel) for its half of the contraction; two waves
+// per SIMD let one wave's LDS and global traffic run under the other's MFMAs. The two halves
+// meet in an fp32 LDS tile, from which stores (and the optional masked shortcut-gradient term)
+// are 16-byte accesses along the channels; the batch-norm statistics of the stored values go
+// to one partial row per 64-pixel tile.
 #include "ddg_device.h"
 #include "ddg_kernels.h"
 #include <cstdlib>
