@@ -547,17 +547,20 @@ def test_deep_workloads_bf16_envelope(H, name, batch, steps):
     assert not report, "\n".join(report)
 
 
-@pytest.mark.parametrize("nblocks,batch", [(2, 2), (1, 12)], ids=["two_blocks_batch2", "one_block_batch12"])
-def test_wide_bottleneck_module_bf16(H, nblocks, batch):
+@pytest.mark.parametrize("nblocks,batch,c,mid,hw", [(2, 2, 1024, 256, 14), (1, 12, 1024, 256, 14), (2, 4, 256, 64, 7)],
+                         ids=["two_blocks_batch2", "one_block_batch12", "c256_mid64_7x7"])
+def test_wide_bottleneck_module_bf16(H, nblocks, batch, c, mid, hw):
     """The ImageNet-shaped slice at reduced size: bottleneck blocks 1024 -> 256 -> 256 -> 1024 at
     14x14 (the GEMM-class kernels of the wide layers and their finalise launches), module k=2 of
     K=4, synthetic error gradient, bf16. Batch 2: 392 pixels, a ragged last 64-pixel tile and
     few tiles per launch (the 128-channel chunks); batch 12: 2352 pixels, the 1024-channel
-    outputs have more than 256 tiles (the 64-channel chunks, as at the full size)."""
+    outputs have more than 256 tiles (the 64-channel chunks, as at the full size). The 256-64-64-256
+    block at 7x7: only the last 1x1 conv (64 -> 256) is wide, forward only, with a contraction of a
+    single 64-channel chunk and a materialised input; the rest runs the generic kernels."""
     import torch
     import paper_1804_10574_amd as ddg
     from oracle import ddg_oracle as orc
-    wl = custom_bottleneck(nblocks, batch=batch, c=1024, mid=256, hw=14)
+    wl = custom_bottleneck(nblocks, batch=batch, c=c, mid=mid, hw=hw)
     wl.dtype = "bf16"
     m = wl.modules[0]
     mod = ddg.Module(H.descs_for(wl)[0])
