@@ -36,9 +36,10 @@ HIP_KERNEL_OF = {
     "conv_bwd_pair.tiled_c32_w16": "ddg::bwd_pair_kernel<32, 16, 2|0, XF>",
     "conv_bwd_pair.tiled_c64_w8": "ddg::bwd_pair_kernel<64, 8, 2|0, XF>",
     "bn_apply": "ddg::bn_apply_chunk_kernel<bf16_t, U>",
-    "conv_wgrad.tiled_c16_w32": "ddg::wgrad_tiled_kernel<16, 16, 32>",
-    "conv_wgrad.tiled_c32_w16": "ddg::wgrad_tiled_kernel<32, 32, 16>",
-    "conv_wgrad.tiled_c64_w8": "ddg::wgrad_tiled_kernel<64, 64, 8>",
+    "conv_wgrad.tiled_c16_w32": "ddg::wgrad_tiled_kernel<16, 16, 32, 1, 3>",
+    "conv_wgrad.tiled_c32_w16": "ddg::wgrad_tiled_kernel<32, 32, 16, 1, 3>",
+    "conv_wgrad.tiled_c64_w8": "ddg::wgrad_tiled_kernel<64, 64, 8, 1, 3>",
+    "conv_wgrad.tiled_stride2": "ddg::wgrad_tiled_kernel<Cin, 2*Cin, W, 2, R>",
     "conv_fprop.wide": "ddg::conv_wide_kernel<true, XFORM, BK>",
     "conv_dgrad.wide": "ddg::conv_wide_kernel<false, false, BK>",
     "conv_wgrad.wide": "ddg::wgrad_wide_kernel",

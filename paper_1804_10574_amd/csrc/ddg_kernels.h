@@ -111,9 +111,11 @@ struct WgradPair {
   const void* x; const float* scale; const float* shift; const void* dz; float* partial; int rows;
 };
 int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
+// H, W, C: height, width, channels of the conv INPUT. Cout (0: = C), R, stride select the
+// stride-2 variants (3x3 and 1x1, Cout = 2*C) that wgrad_tiled_rows also covers.
 hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* shift, const void* dz,
                               const WgradFuse* fuse, float* partial, int N, int H, int W, int C, int rows,
-                              hipStream_t s);
+                              hipStream_t s, int Cout = 0, int R = 3, int stride = 1);
 
 
 // LDS-tiled 3x3/stride-1 convolution for 16/32/64 channels (bf16). Returns the grid (= number of

@@ -40,6 +40,7 @@ enum ProfKind {
   PK_BWD_PAIR_T16, PK_BWD_PAIR_T32, PK_BWD_PAIR_T64, PK_BWD_PAIR = PK_BWD_PAIR_T16 - 1,
   // the GEMM-class kernels of the wide layers
   PK_CONV_FPROP_WIDE = PK_BWD_PAIR_T64 + 1, PK_CONV_DGRAD_WIDE, PK_CONV_WGRAD_WIDE,
+  PK_CONV_WGRAD_S2,   // the LDS-tiled weight gradient of the stride-2 layers between stages
   PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
   PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_BN_RUNNING, PK_COUNT
 };
@@ -48,7 +49,7 @@ static const char* kProfNames[PK_COUNT] = {
   "conv_dgrad.generic", "conv_dgrad.tiled_c16_w32", "conv_dgrad.tiled_c32_w16", "conv_dgrad.tiled_c64_w8",
   "conv_wgrad.generic", "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c32_w16", "conv_wgrad.tiled_c64_w8",
   "conv_bwd_pair.tiled_c16_w32", "conv_bwd_pair.tiled_c32_w16", "conv_bwd_pair.tiled_c64_w8",
-  "conv_fprop.wide", "conv_dgrad.wide", "conv_wgrad.wide",
+  "conv_fprop.wide", "conv_dgrad.wide", "conv_wgrad.wide", "conv_wgrad.tiled_stride2",
   "wgrad_reduce", "bn_finalize", "bn_apply",
   "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam", "bn_running"};
 
@@ -848,10 +849,10 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     f.dy = dy; f.mask = mask; f.mscale = mscale; f.mshift = mshift; f.z = u.z; f.coef = nullptr; f.rows = &br;
     f.dz_out = dz_buf;
     // reads x, dy, z (and the mask tensor if it is a different one), writes dz and dW
-    Launch L(m, PK_CONV_WGRAD + u.tiled_instance(), (u.in_elems() + (mask && mask != u.z ? 4.0 : 3.0) * E) * m->esz + wbytes(m, u) * 4.0 / m->esz,
-             conv_flops(u));
+    Launch L(m, u.stride == 2 ? PK_CONV_WGRAD_S2 : PK_CONV_WGRAD + u.tiled_instance(),
+             (u.in_elems() + (mask && mask != u.z ? 4.0 : 3.0) * E) * m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
     DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, nullptr, &f, u.wg_partial, u.N, u.H, u.W, u.cin,
-                               u.wg_tiled_rows, m->stream));
+                               u.wg_tiled_rows, m->stream, u.cout, u.R, u.stride));
   } else {
     if (u.small_c()) {
       // the apply kernel derives dgamma, dbeta and its coefficients from the rows

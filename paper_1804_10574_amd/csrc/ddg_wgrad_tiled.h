@@ -7,24 +7,30 @@
 
 namespace ddg {
 
+// W, a.H: width and height of the conv OUTPUT (= of the input for stride 1; the input of a
+// stride-2 layer is 2H x 2W).
 struct WgradTiledArgs {
-  const bf16_t* x;       // [N,H,W,CIN] conv input, or the conv output it is derived from
+  const bf16_t* x;       // [N,H*S,W*S,CIN] conv input, or the conv output it is derived from
   const float* scale;    // optional per-channel transform of x: relu(x*scale+shift)
   const float* shift;
   const bf16_t* dz;      // [N,H,W,COUT] (ignored when dy is given)
   // optional: form dz = A*g + B*zc + C0 with g = dy where mask*mscale+mshift > 0 (mask null: g = dy)
   const bf16_t* dy; const bf16_t* mask; const float* mscale; const float* mshift;
   const bf16_t* zc; const float* coef; BnBwdRows rows; bf16_t* dz_out;
-  float* partial;        // [grid.x][COUT][9*CIN]
+  float* partial;        // [grid.x][COUT][R*R*CIN]
   int N, H, W;
   int tiles;             // N * H/8
 };
 
-template <int CIN, int COUT, int W>
+// S: stride (1 or 2), R: kernel size (3 with pad 1, or 1 with pad 0)
+template <int CIN, int COUT, int W, int S = 1, int R = 3>
 struct WgradTiledCfg {
   static constexpr int TH = 8;
-  static constexpr int ROWS = TH + 2;
-  static constexpr int WC = W + 2;                        // one pad column left and right
+  static constexpr int PAD = R / 2;
+  static constexpr int ROWS = (TH - 1) * S + R;           // input rows a tile of TH output rows reads
+  static constexpr int WC = (W - 1) * S + R;              // input columns (pad columns included)
+  static constexpr int WI = W * S;                        // input width
+  static constexpr int TAPS = R * R;
   static constexpr int CIB_ALL = CIN / 16;
   static constexpr int CIB = (CIN == 64) ? 1 : CIB_ALL;   // ci-blocks per workgroup
   static constexpr int OT = CIB_ALL / CIB;                // grid.y
@@ -39,7 +45,7 @@ struct WgradTiledCfg {
   static constexpr int PIXZ = lds_pix(COUT);
   static constexpr int LDS_X = ROWS * WC * PIXX;          // bytes
   static constexpr int LDS_Z = TH * W * PIXZ;
-  static constexpr int RED = (KSPLIT - 1) * COB * 9 * CIB * 4 * 64 * 4;   // bytes, cross-wave sum
+  static constexpr int RED = (KSPLIT - 1) * COB * TAPS * CIB * 4 * 64 * 4;   // bytes, cross-wave sum
   static constexpr int LDS = (LDS_X + LDS_Z) > RED ? (LDS_X + LDS_Z) : RED;
 };
 
@@ -56,10 +62,11 @@ __device__ __forceinline__ uint4 lds_frag_tr(const unsigned char* p, int half_st
 // The kernel body. bx of gx: this workgroup's index among those that walk over the tiles (one
 // partial tile each); by: which slice of the input channels it stages (0 .. Cfg::OT-1).
 // FUSE = false leaves the path that forms dz out of the code (a.dy is ignored).
-template <int CIN, int COUT, int W, bool FUSE = true>
+template <int CIN, int COUT, int W, bool FUSE = true, int S = 1, int R = 3>
 __device__ __forceinline__ void wgrad_tiled_body(const WgradTiledArgs& a, unsigned char* smem, int bx, int by, int gx) {
-  using Cfg = WgradTiledCfg<CIN, COUT, W>;
+  using Cfg = WgradTiledCfg<CIN, COUT, W, S, R>;
   constexpr int TH = Cfg::TH, ROWS = Cfg::ROWS, WC = Cfg::WC, CIB = Cfg::CIB, CINW = Cfg::CINW;
+  constexpr int PAD = Cfg::PAD, WI = Cfg::WI, TAPS = Cfg::TAPS;
   constexpr int COB = Cfg::COB, KSPLIT = Cfg::KSPLIT, KPW = Cfg::KPW, PIXX = Cfg::PIXX, PIXZ = Cfg::PIXZ;
   unsigned char* xt = smem;                 // [ROWS][WC] pixels x CINW channels
   unsigned char* zt = smem + Cfg::LDS_X;    // [TH*W] pixels x COUT channels
@@ -85,9 +92,9 @@ __device__ __forceinline__ void wgrad_tiled_body(const WgradTiledArgs& a, unsign
     const int v = tid + i * 256;
     const int px = v / XCH;
     const int rr = px / WC, cc = px - rr * WC;
-    const bool col_ok = v < XVEC && cc >= 1 && cc <= W;
+    const bool col_ok = v < XVEC && cc >= PAD && cc - PAD < WI;
     xrow[i] = col_ok ? rr : -1;                                   // -1: nothing to load (pad column: zero)
-    xgoff[i] = ((rr - 1) * W + (cc - 1)) * CIN + ci0 + xch * 8;   // relative to the tile's first pixel
+    xgoff[i] = ((rr - PAD) * WI + (cc - PAD)) * CIN + ci0 + xch * 8;   // relative to the tile's first input pixel
     xloff[i] = v < XVEC ? px * PIXX + xch * 16 : -1;
   }
   const bool fuse = FUSE && a.dy != nullptr;
@@ -98,13 +105,13 @@ __device__ __forceinline__ void wgrad_tiled_body(const WgradTiledArgs& a, unsign
   unsigned xin = 0;
   auto issue = [&](int tile) {
     const int n = tile / tiles_per_img, r0 = (tile - n * tiles_per_img) * TH;
-    const bf16_t* xb = a.x + ((size_t)(n * a.H + r0) * W) * CIN;
+    const bf16_t* xb = a.x + ((size_t)(n * a.H * S + r0 * S) * WI) * CIN;
     xin = 0;
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
       xs[i] = make_uint4(0, 0, 0, 0);
-      const int ih = r0 - 1 + xrow[i];
-      if (xrow[i] >= 0 && ih >= 0 && ih < a.H) {
+      const int ih = r0 * S - PAD + xrow[i];
+      if (xrow[i] >= 0 && ih >= 0 && ih < a.H * S) {
         xin |= 1u << i;
         xs[i] = *reinterpret_cast<const uint4*>(xb + xgoff[i]);
       }
@@ -135,7 +142,7 @@ __device__ __forceinline__ void wgrad_tiled_body(const WgradTiledArgs& a, unsign
     const int p = (kpart + q * KSPLIT) * 32 + lg * 8;
     const int row = p / W, col = p % W;
     zaddr[q] = Cfg::LDS_X + (p + sub) * PIXZ + cb * 32 + chq;
-    xaddr[q] = (row * WC + col + sub) * PIXX + chq;
+    xaddr[q] = (row * S * WC + (col + sub) * S) * PIXX + chq;
   }
 
   // per-channel constants of this thread's chunks (derived while the first loads are in flight)
@@ -207,9 +214,9 @@ __device__ __forceinline__ void wgrad_tiled_body(const WgradTiledArgs& a, unsign
     }
   };
 
-  f32x4_t acc[9][CIB];
+  f32x4_t acc[TAPS][CIB];
 #pragma unroll
-  for (int t = 0; t < 9; ++t)
+  for (int t = 0; t < TAPS; ++t)
 #pragma unroll
     for (int b = 0; b < CIB; ++b) acc[t][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
@@ -226,26 +233,26 @@ __device__ __forceinline__ void wgrad_tiled_body(const WgradTiledArgs& a, unsign
 #pragma unroll
       for (int b = 0; b < CIB; ++b)
 #pragma unroll
-        for (int r = 0; r < 3; ++r)
+        for (int r = 0; r < R; ++r)
 #pragma unroll
-          for (int sx = 0; sx < 3; ++sx) {
-            const uint4 xf = lds_frag_tr(xp + (r * WC + sx) * PIXX + b * 32, 4 * PIXX);
-            acc[r * 3 + sx][b] = Mma<bf16_t>::mma(zf, xf, acc[r * 3 + sx][b]);
+          for (int sx = 0; sx < R; ++sx) {
+            const uint4 xf = lds_frag_tr(xp + (r * WC + sx) * PIXX + b * 32, 4 * S * PIXX);
+            acc[r * R + sx][b] = Mma<bf16_t>::mma(zf, xf, acc[r * R + sx][b]);
           }
     }
   }
 
   // ---- add the waves that share a co-block in a fixed order; the first of them writes the
   // partial tile: lane (l16, lg) holds ci = b*16 + l16, co = cb*16 + lg*4 + i of tap t ----
-  constexpr int J = 9 * CIN;
+  constexpr int J = TAPS * CIN;
   if (KSPLIT > 1) {
     __syncthreads();
     float* red = reinterpret_cast<float*>(smem);   // [KSPLIT-1][COB][9*CIB*4][64 lanes]
-    constexpr int SLOTS = 9 * CIB * 4;
+    constexpr int SLOTS = TAPS * CIB * 4;
     if (kpart > 0) {
       float* w = red + (size_t)((kpart - 1) * COB + cb) * SLOTS * 64 + lane;
 #pragma unroll
-      for (int t = 0; t < 9; ++t)
+      for (int t = 0; t < TAPS; ++t)
 #pragma unroll
         for (int b = 0; b < CIB; ++b)
 #pragma unroll
@@ -257,7 +264,7 @@ __device__ __forceinline__ void wgrad_tiled_body(const WgradTiledArgs& a, unsign
       for (int kp = 1; kp < KSPLIT; ++kp) {
         const float* w = red + (size_t)((kp - 1) * COB + cb) * SLOTS * 64 + lane;
 #pragma unroll
-        for (int t = 0; t < 9; ++t)
+        for (int t = 0; t < TAPS; ++t)
 #pragma unroll
           for (int b = 0; b < CIB; ++b)
 #pragma unroll
@@ -268,7 +275,7 @@ __device__ __forceinline__ void wgrad_tiled_body(const WgradTiledArgs& a, unsign
   if (kpart == 0) {
     float* dst = a.partial + ((size_t)bx * COUT + cb * 16 + lg * 4) * J + ci0 + l16;
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
+    for (int t = 0; t < TAPS; ++t)
 #pragma unroll
       for (int b = 0; b < CIB; ++b)
 #pragma unroll

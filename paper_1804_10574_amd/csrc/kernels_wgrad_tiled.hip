@@ -30,30 +30,42 @@
 
 namespace ddg {
 
-template <int CIN, int COUT, int W>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CIN == 32 ? 2 : 3))) void wgrad_tiled_kernel(WgradTiledArgs a) {
+template <int CIN, int COUT, int W, int S = 1, int R = 3>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((CIN == 32 || S == 2) ? 2 : 3))) void wgrad_tiled_kernel(WgradTiledArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  wgrad_tiled_body<CIN, COUT, W>(a, smem, blockIdx.x, blockIdx.y, gridDim.x);
+  wgrad_tiled_body<CIN, COUT, W, true, S, R>(a, smem, blockIdx.x, blockIdx.y, gridDim.x);
 }
 
-template <int CIN, int COUT, int W>
+template <int CIN, int COUT, int W, int S = 1, int R = 3>
 static hipError_t wgrad_tiled_launch_t(const WgradTiledArgs& a, int grid_x, hipStream_t s) {
-  using Cfg = WgradTiledCfg<CIN, COUT, W>;
+  using Cfg = WgradTiledCfg<CIN, COUT, W, S, R>;
   const size_t lds = (size_t)Cfg::LDS;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_tiled_kernel<CIN, COUT, W>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wgrad_tiled_kernel<CIN, COUT, W, S, R>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  DDG_LAUNCH((wgrad_tiled_kernel<CIN, COUT, W>), dim3(grid_x, Cfg::OT), dim3(256), lds, s, a);
+  DDG_LAUNCH((wgrad_tiled_kernel<CIN, COUT, W, S, R>), dim3(grid_x, Cfg::OT), dim3(256), lds, s, a);
   return hipGetLastError();
+}
+
+// The layers between two stages: 3x3 stride 2 and the 1x1 stride-2 projection, Cout = 2*Cin,
+// from 32x32 (16 channels) or 16x16 (32 channels) inputs.
+static bool wgrad_tiled_stride2(int H, int W, int Cin, int Cout, int R, int stride) {
+  return stride == 2 && (R == 3 || R == 1) && Cout == 2 * Cin && ((Cin == 16 && W == 32) || (Cin == 32 && W == 16)) &&
+         H % 16 == 0;
 }
 
 // Returns the number of partial rows (grid.x) the tiled kernel will use for this shape, or 0
 // if the shape is not covered (then the generic kernel is used).
 int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype) {
+  if (dtype == BF16 && wgrad_tiled_stride2(H, W, Cin, Cout, R, stride)) {
+    const int tiles = N * (H / 2 / 8);
+    const int want = 64;
+    return want < tiles ? want : tiles;
+  }
   if (dtype != BF16 || R != 3 || stride != 1 || Cin != Cout) return 0;
   if (!((Cin == 16 && W == 32) || (Cin == 32 && W == 16) || (Cin == 64 && W == 8))) return 0;
   if (H % 8 != 0) return 0;
@@ -74,7 +86,8 @@ int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, 
 
 hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* shift, const void* dz,
                               const WgradFuse* fuse, float* partial, int N, int H, int W, int C, int rows,
-                              hipStream_t s) {
+                              hipStream_t s, int Cout, int R, int stride) {
+  if (Cout == 0) Cout = C;
   WgradTiledArgs a{};
   a.x = (const bf16_t*)x; a.scale = scale; a.shift = shift; a.dz = (const bf16_t*)dz; a.partial = partial;
   if (fuse) {
@@ -82,6 +95,16 @@ hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* sh
     a.zc = (const bf16_t*)fuse->z; a.coef = fuse->coef; a.dz_out = (bf16_t*)fuse->dz_out;
     if (fuse->rows) a.rows = *fuse->rows;
   }
+  if (wgrad_tiled_stride2(H, W, C, Cout, R, stride)) {
+    a.N = N; a.H = H / 2; a.W = W / 2; a.tiles = N * (a.H / 8);     // output geometry
+    if (rows < 1 || rows > a.tiles) return hipErrorInvalidValue;
+    if (C == 16 && R == 3) return wgrad_tiled_launch_t<16, 32, 16, 2, 3>(a, rows, s);
+    if (C == 16 && R == 1) return wgrad_tiled_launch_t<16, 32, 16, 2, 1>(a, rows, s);
+    if (C == 32 && R == 3) return wgrad_tiled_launch_t<32, 64, 8, 2, 3>(a, rows, s);
+    if (C == 32 && R == 1) return wgrad_tiled_launch_t<32, 64, 8, 2, 1>(a, rows, s);
+    return hipErrorInvalidValue;
+  }
+  if (Cout != C || R != 3 || stride != 1) return hipErrorInvalidValue;
   a.N = N; a.H = H; a.W = W; a.tiles = N * (H / 8);
   if (C == 16 && W == 32) return wgrad_tiled_launch_t<16, 16, 32>(a, rows, s);
   if (C == 32 && W == 16) return wgrad_tiled_launch_t<32, 32, 16>(a, rows, s);

@@ -31,9 +31,9 @@ def kind_of(kernel_name: str) -> str:
     m = re.match(r"bwd_pair_kernel<(\d+), (\d+), ", n)
     if m:
         return f"conv_bwd_pair.tiled_c{m.group(1)}_w{m.group(2)}"
-    m = re.match(r"wgrad_tiled_kernel<(\d+), (\d+), (\d+)>", n)
-    if m:
-        return f"conv_wgrad.tiled_c{m.group(1)}_w{m.group(3)}"
+    m = re.match(r"wgrad_tiled_kernel<(\d+), (\d+), (\d+), (\d+), (\d+)>", n)
+    if m:   # <Cin, Cout, output width, stride, kernel size>
+        return "conv_wgrad.tiled_stride2" if m.group(4) == "2" else f"conv_wgrad.tiled_c{m.group(1)}_w{m.group(3)}"
     m = re.match(r"conv_wide_kernel<(true|false), ", n)
     if m:   # with statistics: the forward conv; without: the input gradient
         return "conv_fprop.wide" if m.group(1) == "true" else "conv_dgrad.wide"
