@@ -51,6 +51,9 @@ struct ConvArgs {
   const void* wpack;        // packed operand, see pack_weights
   void* out;
   float* stat_partial;      // fprop only: [grid_x][2][OC] per-workgroup sum / sum of squares, or null
+  // optional second minibatch in the same launch (forward; same weights, its own tensors and
+  // statistics rows): in_b non-null doubles the grid
+  const void* in_b; void* out_b; float* stat_partial_b;
   const void* add_g;        // optional: out += add_g (masked where add_mask <= 0), same layout as out
   const void* add_mask;
   int N, IH, IW, IC, OH, OW, OC;
@@ -164,9 +167,12 @@ bool conv_wide_ok(int IC, int OC, int R, int stride, int dtype);
 int conv_wide_rows(int M);
 // scale/shift (optional, forward only): the conv input is relu(in*scale + shift) per input
 // channel, applied while staging.
+// second (optional, forward only): a second minibatch in the same launch, same weights.
+struct ConvWideSecond { const void* in; void* out; float* stat_partial; const float* scale; const float* shift; };
 hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* add_g,
                             const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s,
-                            const float* scale = nullptr, const float* shift = nullptr);
+                            const float* scale = nullptr, const float* shift = nullptr,
+                            const ConvWideSecond* second = nullptr);
 
 // Weight gradient of the same wide layers (Cin a power of two >= 128, Cout a multiple of 128):
 // partial tiles [splits][Cout][R*R*Cin] over `splits` slices of the pixels, to be added by
@@ -179,14 +185,25 @@ hipError_t wgrad_wide_launch(const void* x, const void* dz, float* partial, int 
 
 // Batch-norm statistics from per-workgroup partial sums -> mean, invstd, scale=gamma*invstd,
 // shift=beta-mean*scale.
+// partial_b (optional): a second set of rows finalised by the same launch into mean_b[0..C),
+// invstd = mean_b + C, scale = mean_b + 2C, shift = mean_b + 3C.
 hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                               const float* beta, float count, float eps, float* mean, float* invstd,
-                              float* scale, float* shift, hipStream_t s);
+                              float* scale, float* shift, hipStream_t s, const float* partial_b = nullptr,
+                              float* mean_b = nullptr);
 // y = [relu](z*scale+shift [+ res*rscale+rshift | + res]); zrows / rrows (optional, C <= 64):
 // derive scale/shift (rscale/rshift) from partial rows instead of reading final vectors.
 hipError_t bn_apply_launch(const void* z, const float* scale, const float* shift, const BnRows* zrows,
                            const void* res, const float* rscale, const float* rshift, const BnRows* rrows,
                            void* y, size_t elems, int C, int relu, int dtype, hipStream_t s);
+// The same for two minibatches of the same layer in one launch (same shapes; every pointer of
+// its own). Needs 256*V % C == 0 (V = 8 for bf16, 4 for fp32); false: not covered, nothing launched.
+struct BnApplySet {
+  const void* z; const float* scale; const float* shift; BnRows zrows;
+  const void* res; const float* rscale; const float* rshift; BnRows rrows; void* y;
+};
+bool bn_apply_pair_launch(const BnApplySet& a, const BnApplySet& b, size_t elems, int C, int relu, int dtype,
+                          hipStream_t s, hipError_t* err);
 // g = dy where the ReLU that follows was active, else 0: active means mask > 0, or
 // mask*mscale+mshift > 0 when mscale is given (the mask tensor is then the conv output the
 // activation derives from); mask == nullptr: g = dy. partial[grid][2][C] = (sum g, sum g*xhat)

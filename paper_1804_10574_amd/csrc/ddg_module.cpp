@@ -641,6 +641,100 @@ ddg_status block_forward(ddg_module* m, Blk& b, const void* x, void* y, int g) {
   return apply_bn(m, ul, x, nullptr, y, g);
 }
 
+// The same conv for the two minibatches of a paired forward pass (groups 0 and 1) in one launch
+// where the kernel can: the tiled kernel when the two inputs lie one group apart, the generic
+// and the GEMM-class kernels always (they take a second set of pointers).
+ddg_status unit_forward_two(ddg_module* m, Unit& u, const void* in0, const void* in1, Unit* src) {
+  if (u.tiled_grid > 0) {
+    if ((const char*)in1 == (const char*)in0 + u.in_elems() * m->esz) return unit_forward(m, u, in0, src, nullptr, nullptr, 2, 0);
+    DDG_OKAY(unit_forward(m, u, in0, src, nullptr, nullptr, 1, 0));
+    return unit_forward(m, u, in1, src, nullptr, nullptr, 1, 1);
+  }
+  if (src && !u.wide_f) return fail(DDG_ERR_STATE, "internal: generic conv needs a materialised input");
+  void* z1 = grp(u.z, u.out_elems() * m->esz, 1);
+  float* fstat1 = u.fstat + (size_t)u.fcap * 2 * u.cout;
+  const double bytes = 2.0 * ((u.in_elems() + u.out_elems()) * (double)m->esz) + wbytes(m, u);
+  if (u.wide_f) {
+    u.frows = conv_wide_rows(u.N * u.P * u.Q);
+    const int sv = src ? src->vec_stride() : 0;
+    ConvWideSecond sec{in1, z1, fstat1, src ? src->scale + sv : nullptr, src ? src->shift + sv : nullptr};
+    Launch L(m, PK_CONV_FPROP_WIDE, bytes, 2.0 * conv_flops(u));
+    DDG_TRY(conv_wide_launch(in0, u.wpack_f, u.z, u.fstat, nullptr, nullptr, u.N, u.H, u.W, u.cin, u.cout, u.R, m->stream,
+                             src ? src->scale : nullptr, src ? src->shift : nullptr, &sec));
+  } else {
+    ConvArgs a = u.fprop;
+    conv_plan(a);
+    u.frows = a.grid_x;
+    a.in = in0; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = u.fstat; a.add_g = nullptr; a.add_mask = nullptr;
+    a.in_b = in1; a.out_b = z1; a.stat_partial_b = fstat1;
+    Launch L(m, PK_CONV_FPROP, bytes, 2.0 * conv_flops(u));
+    DDG_TRY(conv_launch(a, m->stream));
+  }
+  if (!u.small_c()) {
+    Launch L(m, PK_BN_FINALIZE);
+    DDG_TRY(bn_finalize_launch(u.fstat, u.frows, u.cout, m->theta + u.og, m->theta + u.ob,
+                               (float)((size_t)u.N * u.P * u.Q), m->d.bn_eps, u.mean, u.invstd, u.scale, u.shift, m->stream,
+                               fstat1, u.mean + u.vec_stride()));
+  }
+  return DDG_OK;
+}
+
+// y = relu(bn(u.z) [+ shortcut]) for both groups in one launch (see apply_bn).
+ddg_status apply_bn_two(ddg_module* m, Unit& u, const void* res0, const void* res1, Unit* ru, void* y0, void* y1) {
+  const int V = m->d.compute == DDG_BF16 ? 8 : 4;
+  if ((256 * V) % u.cout != 0) {   // not covered by the two-set kernel
+    DDG_OKAY(apply_bn(m, u, res0, ru, y0, 0));
+    return apply_bn(m, u, res1, ru, y1, 1);
+  }
+  BnApplySet st[2];
+  const bool zrows = u.small_c(), rrows = ru && ru->small_c();
+  for (int g = 0; g < 2; ++g) {
+    BnApplySet& q = st[g];
+    q = BnApplySet{};
+    const int vo = g * u.vec_stride(), rvo = ru ? g * ru->vec_stride() : 0;
+    q.z = grp(u.z, u.out_elems() * m->esz, g); q.scale = u.scale + vo; q.shift = u.shift + vo;
+    if (zrows) q.zrows = fwd_rows(m, u, g);
+    q.res = ru ? grp(ru->z, ru->out_elems() * m->esz, g) : (g ? res1 : res0);
+    q.rscale = ru ? ru->scale + rvo : nullptr; q.rshift = ru ? ru->shift + rvo : nullptr;
+    if (rrows) q.rrows = fwd_rows(m, *ru, g);
+    q.y = g ? y1 : y0;
+  }
+  Launch L(m, PK_BN_APPLY, 2.0 * ((res0 || ru) ? 3.0 : 2.0) * u.out_elems() * m->esz);
+  hipError_t e = hipSuccess;
+  if (!bn_apply_pair_launch(st[0], st[1], u.out_elems(), u.cout, 1, m->d.compute, m->stream, &e))
+    return fail(DDG_ERR_STATE, "internal: two-set normalisation not covered");
+  DDG_TRY(e);
+  return DDG_OK;
+}
+
+// One block for both groups of a paired forward pass, nothing deferred: (x0, x1) -> (y0, y1).
+ddg_status block_forward_two(ddg_module* m, Blk& b, const void* x0, const void* x1, void* y0, void* y1) {
+  const void* c0 = x0; const void* c1 = x1;
+  Unit* src = nullptr;   // pending relu(bn(.)) of the current tensors
+  for (int i = 0; i < b.nmain; ++i) {
+    Unit& u = b.u[i];
+    DDG_OKAY(unit_forward_two(m, u, c0, c1, src));
+    src = nullptr;
+    if (i + 1 < b.nmain) {
+      if (b.act[i]) {
+        void* a0 = b.act[i]; void* a1 = grp(b.act[i], u.out_elems() * m->esz, 1);
+        DDG_OKAY(apply_bn_two(m, u, nullptr, nullptr, nullptr, a0, a1));
+        c0 = a0; c1 = a1;
+      } else {
+        c0 = u.z; c1 = grp(u.z, u.out_elems() * m->esz, 1); src = &u;
+      }
+    }
+  }
+  Unit& ul = b.u[b.nmain - 1];
+  if (b.kind == DDG_BLOCK_STEM) return apply_bn_two(m, ul, nullptr, nullptr, nullptr, y0, y1);
+  if (b.proj) {
+    Unit& up = b.u[b.nmain];
+    DDG_OKAY(unit_forward_two(m, up, x0, x1, nullptr));
+    return apply_bn_two(m, ul, nullptr, nullptr, &up, y0, y1);
+  }
+  return apply_bn_two(m, ul, x0, x1, nullptr, y0, y1);
+}
+
 // An identity block of the LDS-tiled shapes, whose convs can take two groups in one launch and
 // whose first conv can absorb the normalise-add-ReLU of the block before.
 static bool tiled_identity_block(const Blk& b) {
@@ -667,8 +761,7 @@ ddg_status run_forward_pair(ddg_module* m, std::vector<Blk>& blocks, const void*
     const bool both = bi >= 1 && tiled_identity_block(b);
     if (!both) {
       if (pend.u) return fail(DDG_ERR_STATE, "internal: deferred block output without a consumer");
-      DDG_OKAY(block_forward(m, b, x0, y0, 0));
-      DDG_OKAY(block_forward(m, b, x1, y1, 1));
+      DDG_OKAY(block_forward_two(m, b, x0, x1, y0, y1));
     } else {
       Unit& u0 = b.u[0]; Unit& u1 = b.u[1];
       if (pend.u) {
@@ -682,10 +775,7 @@ ddg_status run_forward_pair(ddg_module* m, std::vector<Blk>& blocks, const void*
       const bool defer = !no_defer && !last && bi + 1 < nres && tiled_identity_block(blocks[bi + 1]) &&
                          blocks[bi + 1].u[0].cin == u1.cout && blocks[bi + 1].u[0].H == u1.P && blocks[bi + 1].u[0].W == u1.Q;
       if (defer) { pend.u = &u1; pend.res = x0; pend.y = y0; }
-      else {
-        DDG_OKAY(apply_bn(m, u1, x0, nullptr, y0, 0));
-        DDG_OKAY(apply_bn(m, u1, x1, nullptr, y1, 1));
-      }
+      else DDG_OKAY(apply_bn_two(m, u1, x0, x1, nullptr, y0, y1));
     }
     x0 = y0; x1 = y1;
   }

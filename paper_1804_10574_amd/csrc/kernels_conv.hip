@@ -26,9 +26,11 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
   const int l16 = lane & 15, lg = lane >> 4;
   const int cb0 = blockIdx.y * NB;
   const int OCB = a.OC >> 4;
-  const T* __restrict__ in = reinterpret_cast<const T*>(a.in);
+  // blockIdx.z = 1: the second minibatch of a two-group launch (same weights, own tensors)
+  const T* __restrict__ in = reinterpret_cast<const T*>(blockIdx.z ? a.in_b : a.in);
   const T* __restrict__ wp = reinterpret_cast<const T*>(a.wpack);
-  T* __restrict__ out = reinterpret_cast<T*>(a.out);
+  T* __restrict__ out = reinterpret_cast<T*>(blockIdx.z ? a.out_b : a.out);
+  float* __restrict__ stat_partial = blockIdx.z ? a.stat_partial_b : a.stat_partial;
   const T* __restrict__ addg = reinterpret_cast<const T*>(a.add_g);
   const T* __restrict__ addm = reinterpret_cast<const T*>(a.add_mask);
   const int tiles = (a.M + 16 * MB - 1) / (16 * MB);
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
     }
   }
 
-  if (a.stat_partial) {
+  if (stat_partial) {
     __shared__ float red[4][2][NB * 16];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
     if (threadIdx.x < 2 * NB * 16) {
       const int which = threadIdx.x / (NB * 16), c = threadIdx.x % (NB * 16);
       const float t = ((red[0][which][c] + red[1][which][c]) + red[2][which][c]) + red[3][which][c];
-      a.stat_partial[((size_t)blockIdx.x * 2 + which) * a.OC + cb0 * 16 + c] = t;
+      stat_partial[((size_t)blockIdx.x * 2 + which) * a.OC + cb0 * 16 + c] = t;
     }
   }
 }
@@ -199,7 +201,7 @@ void conv_plan(ConvArgs& a) {
 
 template <typename T>
 static hipError_t conv_dispatch(const ConvArgs& a, hipStream_t s) {
-  dim3 grid(a.grid_x, (a.OC / 16) / a.nb), block(256);
+  dim3 grid(a.grid_x, (a.OC / 16) / a.nb, a.in_b ? 2 : 1), block(256);
 #define DDG_CONV_CASE(MB_, NB_)                                                          \
   if (a.mb == MB_ && a.nb == NB_) {                                                      \
     if (a.dgrad) DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, true>), grid, block, 0, s, a);  \

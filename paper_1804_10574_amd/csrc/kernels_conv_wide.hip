@@ -39,6 +39,8 @@ struct ConvWideArgs {
   const bf16_t* add_mask;
   const float* scale;      // optional (XFORM kernels): the conv input is relu(in*scale + shift), per input channel
   const float* shift;
+  // optional second minibatch (blockIdx.z = 1; forward only): same weights, its own tensors
+  const bf16_t* in_b; bf16_t* out_b; float* stat_partial_b; const float* scale_b; const float* shift_b;
   int M, H, W, HW, IC, OC, R;
 };
 
@@ -71,6 +73,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
   const int wn = wave & 3, kg = wave >> 2;        // 32-channel group; k-step of a chunk
+  const bool second = blockIdx.z != 0;
+  const bf16_t* __restrict__ g_in = second ? a.in_b : a.in;
+  bf16_t* __restrict__ g_out = second ? a.out_b : a.out;
+  float* __restrict__ g_stat = second ? a.stat_partial_b : a.stat_partial;
+  const float* __restrict__ g_scale = second ? a.scale_b : a.scale;
+  const float* __restrict__ g_shift = second ? a.shift_b : a.shift;
   const int m0 = blockIdx.x * BM;
   const int OCB = a.OC >> 4;
   const int cb0 = blockIdx.y * (BN / 16);
@@ -102,10 +110,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
     if (a.R == 3) { dr = tap / 3 - 1; ds = tap - (tap / 3) * 3 - 1; }
     const int sh = (dr * a.W + ds) * a.IC;
     r.ok = vA && hA + dr >= 0 && hA + dr < a.H && wA + ds >= 0 && wA + ds < a.W;
-    r.p = *reinterpret_cast<const uint4*>(a.in + baseA + c0 + (r.ok ? sh : 0));
+    r.p = *reinterpret_cast<const uint4*>(g_in + baseA + c0 + (r.ok ? sh : 0));
     if (TWO) {
       r.okq = vB && hB + dr >= 0 && hB + dr < a.H && wB + ds >= 0 && wB + ds < a.W;
-      r.q = *reinterpret_cast<const uint4*>(a.in + baseB + c0 + (r.okq ? sh : 0));
+      r.q = *reinterpret_cast<const uint4*>(g_in + baseB + c0 + (r.okq ? sh : 0));
     }
   };
   auto issue_wts = [&](WideWts& r, int kc_want) __attribute__((always_inline)) {
@@ -121,7 +129,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
   // XFORM: scale and shift of all input channels, after the pixel buffers
   float* tab = reinterpret_cast<float*>(smem + LDS);
   if (XFORM) {
-    for (int c = tid; c < a.IC; c += 512) { tab[c] = a.scale[c]; tab[a.IC + c] = a.shift[c]; }
+    for (int c = tid; c < a.IC; c += 512) { tab[c] = g_scale[c]; tab[a.IC + c] = g_shift[c]; }
     __syncthreads();
   }
   auto stash = [&](const WidePix& r, int buf, int kc) __attribute__((always_inline)) {
@@ -261,7 +269,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
       uint4 o;
       o.x = Store<bf16_t>::pack2(v[0], v[1]); o.y = Store<bf16_t>::pack2(v[2], v[3]);
       o.z = Store<bf16_t>::pack2(v[4], v[5]); o.w = Store<bf16_t>::pack2(v[6], v[7]);
-      *reinterpret_cast<uint4*>(a.out + idx) = o;
+      *reinterpret_cast<uint4*>(g_out + idx) = o;
       if (STATS) {
         float r[8];
         Store<bf16_t>::unpack_vec(o, r);            // the values as stored
@@ -285,7 +293,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
       float s = 0.f;
 #pragma unroll
       for (int r = 0; r < 32; ++r) s += red[(r * 2 + which) * BN + c];
-      a.stat_partial[((size_t)blockIdx.x * 2 + which) * a.OC + cb0 * 16 + c] = s;
+      g_stat[((size_t)blockIdx.x * 2 + which) * a.OC + cb0 * 16 + c] = s;
     }
   }
 }
@@ -326,19 +334,25 @@ int conv_wide_rows(int M) { return (M + wide::BM - 1) / wide::BM; }
 
 hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* add_g,
                             const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s,
-                            const float* scale, const float* shift) {
+                            const float* scale, const float* shift, const ConvWideSecond* second) {
   if (!conv_wide_ok(IC, OC, R, 1, BF16)) return hipErrorInvalidValue;
   const size_t M = (size_t)N * H * W;
   if (M * (size_t)(IC > OC ? IC : OC) >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside
   ConvWideArgs a{};
   a.in = (const bf16_t*)in; a.wpack = (const bf16_t*)wpack; a.out = (bf16_t*)out; a.stat_partial = stat_partial;
   a.add_g = (const bf16_t*)add_g; a.add_mask = (const bf16_t*)add_mask; a.scale = scale; a.shift = shift;
+  if (second) {
+    if (add_g || (scale != nullptr) != (second->scale != nullptr) || (stat_partial != nullptr) != (second->stat_partial != nullptr))
+      return hipErrorInvalidValue;
+    a.in_b = (const bf16_t*)second->in; a.out_b = (bf16_t*)second->out; a.stat_partial_b = second->stat_partial;
+    a.scale_b = second->scale; a.shift_b = second->shift;
+  }
   a.M = (int)M; a.H = H; a.W = W; a.HW = H * W; a.IC = IC; a.OC = OC; a.R = R;
-  const dim3 grid(conv_wide_rows((int)M), OC / wide::BN);
+  const dim3 grid(conv_wide_rows((int)M), OC / wide::BN, second ? 2 : 1);
   const bool xf = scale != nullptr;
   if (xf && (add_g || IC > 2048)) return hipErrorInvalidValue;   // forward only; the table lives in LDS
   // few tiles (one workgroup per compute unit at most): the long chunk; else two workgroups per unit
-  const bool long_chunk = IC >= 128 && grid.x * grid.y <= 256;
+  const bool long_chunk = IC >= 128 && grid.x * grid.y * grid.z <= 256;
   return long_chunk ? conv_wide_dispatch<128>(a, grid, stat_partial != nullptr, xf, IC, s)
                     : conv_wide_dispatch<64>(a, grid, stat_partial != nullptr, xf, IC, s);
 }

@@ -20,7 +20,11 @@ __global__ __launch_bounds__(1024) void bn_finalize_kernel(const float* __restri
                                                           int C, const float* __restrict__ gamma,
                                                           const float* __restrict__ beta, float count,
                                                           float eps, float* mean, float* invstd,
-                                                          float* scale, float* shift) {
+                                                          float* scale, float* shift,
+                                                          const float* __restrict__ partial_b, float* mean_b) {
+  if (blockIdx.y) {   // the second set of rows and vectors
+    partial = partial_b; mean = mean_b; invstd = mean_b + C; scale = mean_b + 2 * C; shift = mean_b + 3 * C;
+  }
   __shared__ double r1[64][17], r2[64][17];
   const int cl = threadIdx.x & 15, slice = threadIdx.x >> 4;
   const int c = blockIdx.x * 16 + cl;
@@ -50,9 +54,9 @@ __global__ __launch_bounds__(1024) void bn_finalize_kernel(const float* __restri
 
 hipError_t bn_finalize_launch(const float* partial, int rows, int C, const float* gamma,
                               const float* beta, float count, float eps, float* mean, float* invstd,
-                              float* scale, float* shift, hipStream_t s) {
-  DDG_LAUNCH(bn_finalize_kernel, dim3((C + 15) / 16), dim3(1024), 0, s, partial, rows, C, gamma,
-                     beta, count, eps, mean, invstd, scale, shift);
+                              float* scale, float* shift, hipStream_t s, const float* partial_b, float* mean_b) {
+  DDG_LAUNCH(bn_finalize_kernel, dim3((C + 15) / 16, partial_b ? 2 : 1), dim3(1024), 0, s, partial, rows, C, gamma,
+                     beta, count, eps, mean, invstd, scale, shift, partial_b, mean_b);
   return hipGetLastError();
 }
 
@@ -166,6 +170,80 @@ __global__ __launch_bounds__(256) void bn_apply_chunk_kernel(const T* __restrict
     }
     Store<T>::store_vec(y + i * V, v);
   }
+}
+
+// Two minibatches of one layer per launch: blockIdx.y selects the set of pointers.
+template <typename T, int U>
+__global__ __launch_bounds__(256) void bn_apply_pair_kernel(BnApplySet s0, BnApplySet s1, size_t nvec, int C, int relu) {
+  constexpr int V = Store<T>::VEC;
+  typedef typename Store<T>::vec_t vec_t;
+  const BnApplySet& q = blockIdx.y ? s1 : s0;
+  const T* z = reinterpret_cast<const T*>(q.z);
+  const T* res = reinterpret_cast<const T*>(q.res);
+  T* y = reinterpret_cast<T*>(q.y);
+  const float *scale = q.scale, *shift = q.shift, *rscale = q.rscale, *rshift = q.rshift;
+  const size_t base = (size_t)blockIdx.x * (256 * U) + threadIdx.x;
+  const int c0 = (int)((threadIdx.x * V) % C);
+  vec_t zq[U], rq[U];
+#pragma unroll
+  for (int j = 0; j < U; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i < nvec) {
+      zq[j] = *reinterpret_cast<const vec_t*>(z + i * V);
+      if (res) rq[j] = *reinterpret_cast<const vec_t*>(res + i * V);
+    }
+  }
+  __shared__ float s_sc[STATS_CMAX], s_sh[STATS_CMAX], s_rs[STATS_CMAX], s_rh[STATS_CMAX];
+  if (q.zrows.partial) { bn_fwd_from_rows_rt(q.zrows, C, s_sc, s_sh, blockIdx.x == 0); scale = s_sc; shift = s_sh; }
+  if (q.rrows.partial) { bn_fwd_from_rows_rt(q.rrows, C, s_rs, s_rh, blockIdx.x == 0); rscale = s_rs; rshift = s_rh; }
+  float sc[V], sh[V], rs[V], rh[V];
+#pragma unroll
+  for (int j = 0; j < V; ++j) {
+    sc[j] = scale[c0 + j]; sh[j] = shift[c0 + j];
+    rs[j] = rscale ? rscale[c0 + j] : 1.f;
+    rh[j] = rshift ? rshift[c0 + j] : 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < U; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i >= nvec) continue;
+    float v[V];
+    Store<T>::unpack_vec(zq[j], v);
+#pragma unroll
+    for (int e = 0; e < V; ++e) v[e] = v[e] * sc[e] + sh[e];
+    if (res) {
+      float r[V];
+      Store<T>::unpack_vec(rq[j], r);
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[e] += r[e] * rs[e] + rh[e];
+    }
+    if (relu) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+    }
+    Store<T>::store_vec(y + i * V, v);
+  }
+}
+
+template <typename T>
+static void bn_apply_pair_dispatch(const BnApplySet& a, const BnApplySet& b, size_t nvec, int C, int relu, hipStream_t s) {
+  if (nvec >= (size_t)512 * 1024)
+    DDG_LAUNCH((bn_apply_pair_kernel<T, 4>), dim3((unsigned)((nvec + 1023) / 1024), 2), dim3(256), 0, s, a, b, nvec, C, relu);
+  else if (nvec >= (size_t)512 * 512)
+    DDG_LAUNCH((bn_apply_pair_kernel<T, 2>), dim3((unsigned)((nvec + 511) / 512), 2), dim3(256), 0, s, a, b, nvec, C, relu);
+  else
+    DDG_LAUNCH((bn_apply_pair_kernel<T, 1>), dim3((unsigned)((nvec + 255) / 256), 2), dim3(256), 0, s, a, b, nvec, C, relu);
+}
+
+bool bn_apply_pair_launch(const BnApplySet& a, const BnApplySet& b, size_t elems, int C, int relu, int dtype,
+                          hipStream_t s, hipError_t* err) {
+  const int V = dtype == BF16 ? 8 : 4;
+  if ((256 * V) % C != 0) return false;
+  // the same kind of work in both sets (the kernel decides per set, the shapes must agree)
+  if (dtype == BF16) bn_apply_pair_dispatch<bf16_t>(a, b, elems / 8, C, relu, s);
+  else bn_apply_pair_dispatch<float>(a, b, elems / 4, C, relu, s);
+  *err = hipGetLastError();
+  return true;
 }
 
 template <typename T>
