@@ -168,11 +168,13 @@ int conv_wide_rows(int M);
 // scale/shift (optional, forward only): the conv input is relu(in*scale + shift) per input
 // channel, applied while staging.
 // second (optional, forward only): a second minibatch in the same launch, same weights.
+// below (optional, input gradient only; mode 2): the epilogue forms the BN-backward sums of the
+// layer below into below->partial, conv_wide_rows(M) rows (see ConvStat).
 struct ConvWideSecond { const void* in; void* out; float* stat_partial; const float* scale; const float* shift; };
 hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* add_g,
                             const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s,
                             const float* scale = nullptr, const float* shift = nullptr,
-                            const ConvWideSecond* second = nullptr);
+                            const ConvWideSecond* second = nullptr, const ConvStat* below = nullptr);
 
 // Weight gradient of the same wide layers (Cin a power of two >= 128, Cout a multiple of 128):
 // partial tiles [splits][Cout][R*R*Cin] over `splits` slices of the pixels, to be added by

@@ -368,6 +368,8 @@ ddg_status build_plan(ddg_module* m) {
         // kernel of the layer above (at most conv_tiled_max_grid() workgroups)
         int brows = bn_bwd_grid(u.out_elems(), u.cout, dt);
         if (conv_tiled_max_grid() > brows) brows = conv_tiled_max_grid();
+        // (or from the GEMM-class input-gradient kernel above: one row per 64 pixels)
+        if (u.cout % 128 == 0 && conv_wide_rows(N * u.P * u.Q) > brows) brows = conv_wide_rows(N * u.P * u.Q);
         DDG_OKAY(dev_alloc(m, &sp, (size_t)brows * 2 * u.cout * sizeof(float)));
         u.bstat = (float*)sp; }
       // input gradient
@@ -966,13 +968,23 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
   if (dx) {
     // reads dz and the weights, writes dx; plus the shortcut term (and its mask), plus the mask
     // and conv output of the layer below when its BN-backward sums are formed here
-    const bool fuse_below = u.tiled_grid > 0 && below && below->u;
+    const bool wide_below = u.tiled_grid == 0 && u.wide_d && below && below->u && below->u->cout == u.cin &&
+                            m->d.compute == DDG_BF16 && !getenv("DDG_NO_WIDE_BELOW");
+    const bool fuse_below = (u.tiled_grid > 0 && below && below->u) || wide_below;
     double extra = (add_g ? (add_mask ? 2.0 : 1.0) : 0.0);
     if (fuse_below) extra += (below->mask == below->u->z) ? 1.0 : 2.0;
     Launch L(m, u.tiled_grid > 0 ? PK_CONV_DGRAD + u.tiled_instance() : (u.wide_d ? PK_CONV_DGRAD_WIDE : PK_CONV_DGRAD),
              (E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u), conv_flops(u));
     if (u.tiled_grid == 0 && u.wide_d) {
-      DDG_TRY(conv_wide_launch(dz_buf, u.wpack_d, dx, nullptr, add_g, add_mask, u.N, u.P, u.Q, u.cout, u.cin, u.R, m->stream));
+      ConvStat st{};
+      if (wide_below) {
+        st.mode = 2; st.partial = below->u->bstat;
+        st.mask = below->mask; st.mscale = below->mscale; st.mshift = below->mshift;
+        st.z = below->u->z; st.zmean = below->u->mean; st.zinvstd = below->u->invstd;
+        if (below_rows) *below_rows = conv_wide_rows(u.N * u.H * u.W);
+      }
+      DDG_TRY(conv_wide_launch(dz_buf, u.wpack_d, dx, nullptr, add_g, add_mask, u.N, u.P, u.Q, u.cout, u.cin, u.R, m->stream,
+                               nullptr, nullptr, nullptr, wide_below ? &st : nullptr));
     } else if (u.tiled_grid > 0) {
       ConvStat st{};
       if (below && below->u) {

@@ -39,6 +39,12 @@ struct ConvWideArgs {
   const bf16_t* add_mask;
   const float* scale;      // optional (XFORM kernels): the conv input is relu(in*scale + shift), per input channel
   const float* shift;
+  // STATS = 2 (input gradient): the outputs are an error gradient v; with the ReLU mask of the
+  // layer below applied, g = (bmask*bmscale + bmshift > 0) ? v : 0 (bmask null: g = v), the rows
+  // hold sum g and sum g*xhat of that layer's BN (xhat = (bz - bmean)*binvstd): its
+  // bn_bwd_reduce pass comes for free. stat_partial receives the rows.
+  const bf16_t* bmask; const float* bmscale; const float* bmshift;
+  const bf16_t* bz; const float* bmean; const float* binvstd;
   // optional second minibatch (blockIdx.z = 1; forward only): same weights, its own tensors
   const bf16_t* in_b; bf16_t* out_b; float* stat_partial_b; const float* scale_b; const float* shift_b;
   int M, H, W, HW, IC, OC, R;
@@ -62,7 +68,9 @@ struct WideWts { uint4 w0, w1, w2, w3; };           // w2, w3: second k-step of 
 // norm + ReLU of the layer before), while it is written to LDS; zero padding comes after that.
 // BK: contraction channels per chunk (one barrier each). 128 halves the number of barriers; 64
 // keeps the kernel at 128 registers, two workgroups per compute unit (launches with many tiles).
-template <bool STATS, bool XFORM, int BK>
+// STATS: 0 none, 1 sum / sum of squares of the stored outputs (forward), 2 the BN-backward sums of
+// the layer below (input gradient).
+template <int STATS, bool XFORM, int BK>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 4 : 2))) void conv_wide_kernel(ConvWideArgs a) {
   using namespace wide;
   constexpr int PROW = prow_bytes(BK), P_BYTES = pix_bytes(BK), LDS = lds_bytes(BK);
@@ -246,6 +254,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
   float ssum[8], ssq[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { ssum[e] = 0.f; ssq[e] = 0.f; }
+  float bmu[8], bis[8], bms[8], bmh[8];           // STATS = 2: constants of the BN below, this thread's 8 channels
+  if (STATS == 2) {
+    const int c = cb0 * 16 + oc * 8;
+    auto ld8 = [&](const float* p, float (&d)[8], float dflt) __attribute__((always_inline)) {
+      float4 lo = make_float4(dflt, dflt, dflt, dflt), hi = lo;
+      if (p) { lo = *reinterpret_cast<const float4*>(p + c); hi = *reinterpret_cast<const float4*>(p + c + 4); }
+      d[0] = lo.x; d[1] = lo.y; d[2] = lo.z; d[3] = lo.w; d[4] = hi.x; d[5] = hi.y; d[6] = hi.z; d[7] = hi.w;
+    };
+    ld8(a.bmean, bmu, 0.f); ld8(a.binvstd, bis, 1.f);
+    ld8(a.bmscale, bms, 1.f); ld8(a.bmscale ? a.bmshift : nullptr, bmh, 0.f);
+  }
 #pragma unroll
   for (int q = 0; q < 2; ++q) {
     const int row = orow + 32 * q, m = m0 + row;
@@ -270,11 +289,26 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
       o.x = Store<bf16_t>::pack2(v[0], v[1]); o.y = Store<bf16_t>::pack2(v[2], v[3]);
       o.z = Store<bf16_t>::pack2(v[4], v[5]); o.w = Store<bf16_t>::pack2(v[6], v[7]);
       *reinterpret_cast<uint4*>(g_out + idx) = o;
-      if (STATS) {
+      if (STATS == 1) {
         float r[8];
         Store<bf16_t>::unpack_vec(o, r);            // the values as stored
 #pragma unroll
         for (int e = 0; e < 8; ++e) { ssum[e] += r[e]; ssq[e] += r[e] * r[e]; }
+      }
+      if (STATS == 2) {
+        float r[8], zz[8], mk[8];
+        Store<bf16_t>::unpack_vec(o, r);            // the gradient as stored
+        const uint4 zq = *reinterpret_cast<const uint4*>(a.bz + idx);
+        Store<bf16_t>::unpack_vec(zq, zz);
+        uint4 mq = zq;
+        if (a.bmask && a.bmask != a.bz) mq = *reinterpret_cast<const uint4*>(a.bmask + idx);
+        Store<bf16_t>::unpack_vec(mq, mk);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float g = (!a.bmask || mk[e] * bms[e] + bmh[e] > 0.f) ? r[e] : 0.f;
+          ssum[e] += g;
+          ssq[e] += g * ((zz[e] - bmu[e]) * bis[e]);
+        }
       }
     }
   }
@@ -299,27 +333,31 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
 }
 
 template <int BK>
-static hipError_t conv_wide_dispatch(const ConvWideArgs& a, dim3 grid, bool stats, bool xf, int IC, hipStream_t s) {
+static hipError_t conv_wide_dispatch(const ConvWideArgs& a, dim3 grid, int stats, bool xf, int IC, hipStream_t s) {
   const int tab_max = 2 * 2048 * (int)sizeof(float);
   const int lds = wide::lds_bytes(BK) + (xf ? 2 * IC * (int)sizeof(float) : 0);
   static bool attr_set = false;
   if (!attr_set) {
-    const void* fns[4] = {reinterpret_cast<const void*>(&conv_wide_kernel<true, false, BK>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<false, false, BK>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<true, true, BK>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<false, true, BK>)};
+    const void* fns[5] = {reinterpret_cast<const void*>(&conv_wide_kernel<1, false, BK>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<0, false, BK>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<1, true, BK>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<0, true, BK>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<2, false, BK>)};
     for (const void* f : fns) {
       hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, wide::lds_bytes(BK) + tab_max);
       if (e != hipSuccess) return e;
     }
     attr_set = true;
   }
-  if (stats) {
-    if (xf) DDG_LAUNCH((conv_wide_kernel<true, true, BK>), grid, dim3(512), lds, s, a);
-    else DDG_LAUNCH((conv_wide_kernel<true, false, BK>), grid, dim3(512), lds, s, a);
+  if (stats == 2) {
+    if (xf) return hipErrorInvalidValue;
+    DDG_LAUNCH((conv_wide_kernel<2, false, BK>), grid, dim3(512), lds, s, a);
+  } else if (stats == 1) {
+    if (xf) DDG_LAUNCH((conv_wide_kernel<1, true, BK>), grid, dim3(512), lds, s, a);
+    else DDG_LAUNCH((conv_wide_kernel<1, false, BK>), grid, dim3(512), lds, s, a);
   } else {
-    if (xf) DDG_LAUNCH((conv_wide_kernel<false, true, BK>), grid, dim3(512), lds, s, a);
-    else DDG_LAUNCH((conv_wide_kernel<false, false, BK>), grid, dim3(512), lds, s, a);
+    if (xf) DDG_LAUNCH((conv_wide_kernel<0, true, BK>), grid, dim3(512), lds, s, a);
+    else DDG_LAUNCH((conv_wide_kernel<0, false, BK>), grid, dim3(512), lds, s, a);
   }
   return hipGetLastError();
 }
@@ -334,7 +372,7 @@ int conv_wide_rows(int M) { return (M + wide::BM - 1) / wide::BM; }
 
 hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* add_g,
                             const void* add_mask, int N, int H, int W, int IC, int OC, int R, hipStream_t s,
-                            const float* scale, const float* shift, const ConvWideSecond* second) {
+                            const float* scale, const float* shift, const ConvWideSecond* second, const ConvStat* below) {
   if (!conv_wide_ok(IC, OC, R, 1, BF16)) return hipErrorInvalidValue;
   const size_t M = (size_t)N * H * W;
   if (M * (size_t)(IC > OC ? IC : OC) >= ((size_t)1 << 31)) return hipErrorInvalidValue;   // 32-bit element offsets inside
@@ -347,14 +385,21 @@ hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float*
     a.in_b = (const bf16_t*)second->in; a.out_b = (bf16_t*)second->out; a.stat_partial_b = second->stat_partial;
     a.scale_b = second->scale; a.shift_b = second->shift;
   }
+  int stats = stat_partial ? 1 : 0;
+  if (below) {   // the BN-backward sums of the layer below, from the gradient this launch produces
+    if (below->mode != 2 || stat_partial || second || scale || !below->partial || !below->z || !below->zmean || !below->zinvstd)
+      return hipErrorInvalidValue;
+    a.stat_partial = below->partial; a.bmask = (const bf16_t*)below->mask; a.bmscale = below->mscale; a.bmshift = below->mshift;
+    a.bz = (const bf16_t*)below->z; a.bmean = below->zmean; a.binvstd = below->zinvstd;
+    stats = 2;
+  }
   a.M = (int)M; a.H = H; a.W = W; a.HW = H * W; a.IC = IC; a.OC = OC; a.R = R;
   const dim3 grid(conv_wide_rows((int)M), OC / wide::BN, second ? 2 : 1);
   const bool xf = scale != nullptr;
   if (xf && (add_g || IC > 2048)) return hipErrorInvalidValue;   // forward only; the table lives in LDS
   // few tiles (one workgroup per compute unit at most): the long chunk; else two workgroups per unit
   const bool long_chunk = IC >= 128 && grid.x * grid.y * grid.z <= 256;
-  return long_chunk ? conv_wide_dispatch<128>(a, grid, stat_partial != nullptr, xf, IC, s)
-                    : conv_wide_dispatch<64>(a, grid, stat_partial != nullptr, xf, IC, s);
+  return long_chunk ? conv_wide_dispatch<128>(a, grid, stats, xf, IC, s) : conv_wide_dispatch<64>(a, grid, stats, xf, IC, s);
 }
 
 }  // namespace ddg
