@@ -96,7 +96,8 @@ hipError_t wgrad_reduce_launch(const WgradArgs& a, hipStream_t s);
 // partials in a fixed order.
 struct PackDesc { const float* W; void* wpack; int Cout, Cin, R, mode, log2cp, ksteps, OCB; unsigned total; };
 struct WredDesc { const float* partial; float* dW; int rows, Cout, Cin, R, log2cp, Jp; };
-hipError_t pack_all_launch(const PackDesc* dev_descs, int n, int dtype, hipStream_t s);
+// max_total: the largest `total` among the n operands (sizes the grid)
+hipError_t pack_all_launch(const PackDesc* dev_descs, int n, int dtype, hipStream_t s, unsigned max_total = 0);
 // max_outputs: the largest Cout*Jp among the n layers (sizes the grid)
 hipError_t wgrad_reduce_all_launch(const WredDesc* dev_descs, int n, int max_outputs, hipStream_t s);
 

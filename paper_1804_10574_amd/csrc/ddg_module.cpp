@@ -159,6 +159,7 @@ struct ddg_module {
   bool eval_mode = false;          // the forward helpers normalise with the evaluation vectors
   float* ws_stat = nullptr; size_t ws_stat_elems = 0;
   PackDesc* pack_descs = nullptr; int n_pack = 0;     // device tables for the whole-module kernels
+  unsigned pack_max = 0;                              // largest packed operand (elements)
   WredDesc* wred_descs = nullptr; int n_wred = 0; int wred_max = 0;   // wred_max: largest Cout*Jp
   std::vector<void*> allocs;
   size_t bytes = 0;
@@ -467,6 +468,7 @@ ddg_status build_plan(ddg_module* m) {
         d.Cout = u.cout; d.Cin = u.cin; d.R = u.R; d.mode = md;
         d.total = (unsigned)conv_wpack_elems(kc, nc, u.R, dt, &d.log2cp, &d.ksteps);
         d.OCB = nc / 16;
+        if (d.total > m->pack_max) m->pack_max = d.total;
         if (mode == 1 && m->stale) {
           for (int j = 0; j < m->nslots; ++j) { d.wpack = (char*)u.wpack_d + (size_t)j * u.wpack_d_bytes; pdd[j].push_back(d); }
         } else {
@@ -517,7 +519,7 @@ ddg_status build_plan(ddg_module* m) {
 
 ddg_status pack_all(ddg_module* m) {
   Launch L(m, PK_PACK);
-  DDG_TRY(pack_all_launch(m->pack_descs, m->n_pack, m->d.compute, m->stream));
+  DDG_TRY(pack_all_launch(m->pack_descs, m->n_pack, m->d.compute, m->stream, m->pack_max));
   return DDG_OK;
 }
 
@@ -1385,7 +1387,7 @@ ddg_status ddg_forward(ddg_module* m, long t, const void* h_in, void* h_out) {
     std::vector<Blk> tape = group_view(m, g);
     { Launch L(m, PK_COPY, 2.0 * m->nparams * sizeof(float));
       DDG_TRY(copy_launch(m->theta, m->theta_snap + (size_t)g * m->nparams, m->nparams * sizeof(float), m->stream)); }
-    if (m->n_pack_d) { Launch L(m, PK_PACK); DDG_TRY(pack_all_launch(m->pack_descs_d[g], m->n_pack_d, m->d.compute, m->stream)); }
+    if (m->n_pack_d) { Launch L(m, PK_PACK); DDG_TRY(pack_all_launch(m->pack_descs_d[g], m->n_pack_d, m->d.compute, m->stream, m->pack_max)); }
     DDG_OKAY(run_forward(m, tape, slot, nullptr));
     m->tape_is_current = false;
     const Blk& lb = tape[tape.size() - 1];

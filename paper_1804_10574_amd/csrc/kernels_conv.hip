@@ -272,10 +272,13 @@ __global__ void pack_all_kernel(const PackDesc* __restrict__ descs) {
   }
 }
 
-hipError_t pack_all_launch(const PackDesc* dev_descs, int n, int dtype, hipStream_t s) {
+hipError_t pack_all_launch(const PackDesc* dev_descs, int n, int dtype, hipStream_t s, unsigned max_total) {
   if (n <= 0) return hipSuccess;
-  if (dtype == BF16) DDG_LAUNCH(pack_all_kernel<bf16_t>, dim3(16, n), dim3(256), 0, s, dev_descs);
-  else DDG_LAUNCH(pack_all_kernel<float>, dim3(16, n), dim3(256), 0, s, dev_descs);
+  // workgroups per operand: about 16 elements per thread of the largest one, between 16 and 128
+  unsigned bx = max_total / 4096;
+  bx = bx < 16 ? 16 : (bx > 128 ? 128 : bx);
+  if (dtype == BF16) DDG_LAUNCH(pack_all_kernel<bf16_t>, dim3(bx, n), dim3(256), 0, s, dev_descs);
+  else DDG_LAUNCH(pack_all_kernel<float>, dim3(bx, n), dim3(256), 0, s, dev_descs);
   return hipGetLastError();
 }
 
