@@ -70,7 +70,11 @@ struct WideWts { uint4 w0, w1, w2, w3; };           // w2, w3: second k-step of 
 // keeps the kernel at 128 registers, two workgroups per compute unit (launches with many tiles).
 // STATS: 0 none, 1 sum / sum of squares of the stored outputs (forward), 2 the BN-backward sums of
 // the layer below (input gradient).
-template <int STATS, bool XFORM, int BK>
+// R: kernel size (1 or 3), a template parameter because the loop is instruction-issue bound: a
+// chunk is only 8-16 MFMAs per wave, so every address or predicate instruction per chunk counts
+// (tap validity is a 9-bit mask computed once, wave-uniform values live in scalar registers,
+// addresses are a uniform pointer plus a 32-bit lane offset).
+template <int STATS, bool XFORM, int BK, int R>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 4 : 2))) void conv_wide_kernel(ConvWideArgs a) {
   using namespace wide;
   constexpr int PROW = prow_bytes(BK), P_BYTES = pix_bytes(BK), LDS = lds_bytes(BK);
@@ -78,7 +82,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
   constexpr bool TWO = BK == 128;                 // two rows per thread, two k-steps per wave
   constexpr int KSW = BK / 64;                    // k-steps per wave and chunk
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: scalar registers
   const int l16 = lane & 15, lg = lane >> 4;
   const int wn = wave & 3, kg = wave >> 2;        // 32-channel group; k-step of a chunk
   const bool second = blockIdx.z != 0;
@@ -92,7 +97,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
   const int cb0 = blockIdx.y * (BN / 16);
   const int cpt = a.IC / BK;                      // chunks per tap (a power of two)
   const int l2cpt = 31 - __clz(cpt);
-  const int nchunks = a.R * a.R * cpt;
+  const int nchunks = R * R * cpt;
 
   // ---- staging map of the pixel operand: row tid/UPR (and 32 rows further for BK = 128),
   // 16-byte unit tid%UPR
@@ -102,8 +107,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
   const int remA = (vA ? mA : 0) % a.HW, remB = (vB ? mB : 0) % a.HW;
   const int hA = remA / a.W, wA = remA - hA * a.W, hB = remB / a.W, wB = remB - hB * a.W;
   const int baseA = (vA ? mA : 0) * a.IC + pc * 8, baseB = (vB ? mB : 0) * a.IC + pc * 8;
-  // this wave's weight fragments of k-step 0: channel blocks cb0 + wn*2, +1; k-step ks adds ks*wstep
-  const bf16_t* wsrc = a.wpack + ((size_t)(cb0 + wn * 2) * 64 + lane) * 8;
+  // bit t: tap t of this thread's row lies inside the image (R = 1: the row itself is valid)
+  unsigned tapsA = 0, tapsB = 0;
+#pragma unroll
+  for (int t = 0; t < R * R; ++t) {
+    const int dr = R == 3 ? t / 3 - 1 : 0, ds = R == 3 ? t % 3 - 1 : 0;
+    tapsA |= (vA && hA + dr >= 0 && hA + dr < a.H && wA + ds >= 0 && wA + ds < a.W ? 1u : 0u) << t;
+    tapsB |= (vB && hB + dr >= 0 && hB + dr < a.H && wB + ds >= 0 && wB + ds < a.W ? 1u : 0u) << t;
+  }
+  // this wave's weight fragments of k-step 0: channel blocks cb0 + wn*2, +1 (uniform pointer, lane
+  // offset); k-step ks adds ks*wstep
+  const bf16_t* wsrc = a.wpack + (size_t)(cb0 + wn * 2) * 64 * 8;
+  const int wlane = lane * 8;
   const size_t wstep = (size_t)OCB * 64 * 8;      // elements per k-step of the packed operand
 
   // Chunk kc: 64 channels of one tap. Loads are issued two to three chunks before they are needed (the
@@ -113,25 +128,25 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
   // to LDS; a chunk index past the end repeats the last chunk (never used).
   auto issue_pix = [&](WidePix& r, int kc_want) __attribute__((always_inline)) {
     const int kc = kc_want < nchunks ? kc_want : nchunks - 1;
-    const int tap = kc >> l2cpt, c0 = (kc & (cpt - 1)) * BK;
-    int dr = 0, ds = 0;
-    if (a.R == 3) { dr = tap / 3 - 1; ds = tap - (tap / 3) * 3 - 1; }
-    const int sh = (dr * a.W + ds) * a.IC;
-    r.ok = vA && hA + dr >= 0 && hA + dr < a.H && wA + ds >= 0 && wA + ds < a.W;
-    r.p = *reinterpret_cast<const uint4*>(g_in + baseA + c0 + (r.ok ? sh : 0));
+    const int tap = R == 3 ? kc >> l2cpt : 0, c0 = (kc & (cpt - 1)) * BK;
+    int sh = 0;
+    if (R == 3) { const int dr = tap / 3 - 1, ds = tap - (tap / 3) * 3 - 1; sh = (dr * a.W + ds) * a.IC; }
+    const bf16_t* src = g_in + c0;                 // uniform
+    r.ok = (tapsA >> tap) & 1u;
+    r.p = *reinterpret_cast<const uint4*>(src + (baseA + (r.ok ? sh : 0)));
     if (TWO) {
-      r.okq = vB && hB + dr >= 0 && hB + dr < a.H && wB + ds >= 0 && wB + ds < a.W;
-      r.q = *reinterpret_cast<const uint4*>(g_in + baseB + c0 + (r.okq ? sh : 0));
+      r.okq = (tapsB >> tap) & 1u;
+      r.q = *reinterpret_cast<const uint4*>(src + (baseB + (r.okq ? sh : 0)));
     }
   };
   auto issue_wts = [&](WideWts& r, int kc_want) __attribute__((always_inline)) {
     const int kc = kc_want < nchunks ? kc_want : nchunks - 1;
-    const bf16_t* wa = wsrc + (size_t)((kc * 2 + kg) * KSW) * wstep;
-    r.w0 = *reinterpret_cast<const uint4*>(wa);
-    r.w1 = *reinterpret_cast<const uint4*>(wa + 64 * 8);
+    const bf16_t* wa = wsrc + (size_t)((kc * 2 + kg) * KSW) * wstep;   // uniform
+    r.w0 = *reinterpret_cast<const uint4*>(wa + wlane);
+    r.w1 = *reinterpret_cast<const uint4*>(wa + 64 * 8 + wlane);
     if (TWO) {
-      r.w2 = *reinterpret_cast<const uint4*>(wa + wstep);
-      r.w3 = *reinterpret_cast<const uint4*>(wa + wstep + 64 * 8);
+      r.w2 = *reinterpret_cast<const uint4*>(wa + wstep + wlane);
+      r.w3 = *reinterpret_cast<const uint4*>(wa + wstep + 64 * 8 + wlane);
     }
   };
   // XFORM: scale and shift of all input channels, after the pixel buffers
@@ -332,17 +347,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
   }
 }
 
-template <int BK>
+template <int BK, int R>
 static hipError_t conv_wide_dispatch(const ConvWideArgs& a, dim3 grid, int stats, bool xf, int IC, hipStream_t s) {
   const int tab_max = 2 * 2048 * (int)sizeof(float);
   const int lds = wide::lds_bytes(BK) + (xf ? 2 * IC * (int)sizeof(float) : 0);
   static bool attr_set = false;
   if (!attr_set) {
-    const void* fns[5] = {reinterpret_cast<const void*>(&conv_wide_kernel<1, false, BK>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<0, false, BK>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<1, true, BK>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<0, true, BK>),
-                          reinterpret_cast<const void*>(&conv_wide_kernel<2, false, BK>)};
+    const void* fns[5] = {reinterpret_cast<const void*>(&conv_wide_kernel<1, false, BK, R>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<0, false, BK, R>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<1, true, BK, R>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<0, true, BK, R>),
+                          reinterpret_cast<const void*>(&conv_wide_kernel<2, false, BK, R>)};
     for (const void* f : fns) {
       hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, wide::lds_bytes(BK) + tab_max);
       if (e != hipSuccess) return e;
@@ -351,13 +366,13 @@ static hipError_t conv_wide_dispatch(const ConvWideArgs& a, dim3 grid, int stats
   }
   if (stats == 2) {
     if (xf) return hipErrorInvalidValue;
-    DDG_LAUNCH((conv_wide_kernel<2, false, BK>), grid, dim3(512), lds, s, a);
+    DDG_LAUNCH((conv_wide_kernel<2, false, BK, R>), grid, dim3(512), lds, s, a);
   } else if (stats == 1) {
-    if (xf) DDG_LAUNCH((conv_wide_kernel<1, true, BK>), grid, dim3(512), lds, s, a);
-    else DDG_LAUNCH((conv_wide_kernel<1, false, BK>), grid, dim3(512), lds, s, a);
+    if (xf) DDG_LAUNCH((conv_wide_kernel<1, true, BK, R>), grid, dim3(512), lds, s, a);
+    else DDG_LAUNCH((conv_wide_kernel<1, false, BK, R>), grid, dim3(512), lds, s, a);
   } else {
-    if (xf) DDG_LAUNCH((conv_wide_kernel<0, true, BK>), grid, dim3(512), lds, s, a);
-    else DDG_LAUNCH((conv_wide_kernel<0, false, BK>), grid, dim3(512), lds, s, a);
+    if (xf) DDG_LAUNCH((conv_wide_kernel<0, true, BK, R>), grid, dim3(512), lds, s, a);
+    else DDG_LAUNCH((conv_wide_kernel<0, false, BK, R>), grid, dim3(512), lds, s, a);
   }
   return hipGetLastError();
 }
@@ -399,7 +414,9 @@ hipError_t conv_wide_launch(const void* in, const void* wpack, void* out, float*
   if (xf && (add_g || IC > 2048)) return hipErrorInvalidValue;   // forward only; the table lives in LDS
   // few tiles (one workgroup per compute unit at most): the long chunk; else two workgroups per unit
   const bool long_chunk = IC >= 128 && grid.x * grid.y * grid.z <= 256;
-  return long_chunk ? conv_wide_dispatch<128>(a, grid, stats, xf, IC, s) : conv_wide_dispatch<64>(a, grid, stats, xf, IC, s);
+  if (R == 3)
+    return long_chunk ? conv_wide_dispatch<128, 3>(a, grid, stats, xf, IC, s) : conv_wide_dispatch<64, 3>(a, grid, stats, xf, IC, s);
+  return long_chunk ? conv_wide_dispatch<128, 1>(a, grid, stats, xf, IC, s) : conv_wide_dispatch<64, 1>(a, grid, stats, xf, IC, s);
 }
 
 }  // namespace ddg
