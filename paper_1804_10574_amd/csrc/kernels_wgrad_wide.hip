@@ -28,9 +28,10 @@ struct WgradWideArgs {
   const float* shift;
   float* partial;        // [splits][Cout][J], J = taps*Cin
   int M, H, W, HW, Cin, Cout, R, J;
-  int steps_per_split;   // 64-pixel steps per split
+  int nsplits;           // pixel slices: slice i covers 64-pixel steps [i*nsteps/nsplits, (i+1)*nsteps/nsplits)
   int nsteps;            // ceil(M/64)
-  int cit, taps;         // Cin/128, R*R: blockIdx.x = (cot*taps + tap)*cit + ci tile
+  int cit, taps;         // Cin/128, R*R: tile index = (cot*taps + tap)*cit + ci tile
+  int by_xcd;            // 1: workgroups are renumbered so that a pixel slice stays on one XCD
 };
 
 namespace wgw {
@@ -57,14 +58,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void w
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
   const int wa = wave & 1, wb = wave >> 1;           // co half, ci half
-  const int cit = blockIdx.x % a.cit;
-  const int tap = (blockIdx.x / a.cit) % a.taps;
-  const int cot = blockIdx.x / (a.cit * a.taps);
+  // Workgroups go to the 8 XCDs round-robin in launch order. All tiles of one pixel slice read
+  // the same rows of x and dz, so the (slice, tile) pairs are numbered slice-major and XCD j is
+  // given the j-th eighth of that sequence: the rows of a slice then come from memory once into
+  // one XCD's L2 (two at a boundary) and every other tile finds them there.
+  int tile = blockIdx.x, split = blockIdx.y;
+  if (a.by_xcd) {
+    const int T = gridDim.x * gridDim.y, L = blockIdx.x + gridDim.x * blockIdx.y;
+    const int xcd = L & 7, q = T >> 3, r = T & 7;
+    const int V = xcd * q + (xcd < r ? xcd : r) + (L >> 3);   // XCD j holds q (+1 if j < r) workgroups
+    split = V / (int)gridDim.x;
+    tile = V - split * (int)gridDim.x;
+  }
+  const int cit = tile % a.cit;
+  const int tap = (tile / a.cit) % a.taps;
+  const int cot = tile / (a.cit * a.taps);
   const int co0 = cot * 128, ci0 = cit * 128;
   int dr = 0, ds = 0;
   if (a.R == 3) { dr = tap / 3 - 1; ds = tap - (tap / 3) * 3 - 1; }
-  const int s0 = blockIdx.y * a.steps_per_split;
-  const int s1 = (s0 + a.steps_per_split < a.nsteps) ? s0 + a.steps_per_split : a.nsteps;
+  const int s0 = split * a.nsteps / a.nsplits;
+  const int s1 = (split + 1) * a.nsteps / a.nsplits;
 
   // staging map: 16-byte unit tid + q*256 of a 64 x 128 tile = pixel (tid>>4) + 16*q, chunk tid&15
   const int ch = tid & 15, prow = tid >> 4;
@@ -159,7 +172,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void w
   }
 
   // lane (l16, lg) of tile (i, j) holds co = co0 + (wa*4 + i)*16 + lg*4 + e, ci = ci0 + (wb*4 + j)*16 + l16
-  float* dst = a.partial + ((size_t)blockIdx.y * a.Cout + co0 + wa * 64 + lg * 4) * a.J + (size_t)tap * a.Cin + ci0 + wb * 64 + l16;
+  float* dst = a.partial + ((size_t)split * a.Cout + co0 + wa * 64 + lg * 4) * a.J + (size_t)tap * a.Cin + ci0 + wb * 64 + l16;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -185,11 +198,9 @@ int wgrad_wide_splits(int M, int Cin, int Cout, int R) {
   }
   const int tiles = (Cout / 128) * (Cin / 128) * R * R;
   const int nsteps = (M + wgw::BP - 1) / wgw::BP;
-  int splits = (target + tiles - 1) / tiles;
+  int splits = target / tiles;      // never more workgroups than the target: one past what fits at once costs a whole extra round
   if (splits > nsteps / 2) splits = nsteps / 2;
-  if (splits < 1) splits = 1;
-  const int sps = (nsteps + splits - 1) / splits;
-  return (nsteps + sps - 1) / sps;     // no empty slice
+  return splits < 1 ? 1 : splits;
 }
 
 hipError_t wgrad_wide_launch(const void* x, const void* dz, float* partial, int N, int H, int W, int Cin, int Cout,
@@ -200,8 +211,9 @@ hipError_t wgrad_wide_launch(const void* x, const void* dz, float* partial, int 
   a.x = (const bf16_t*)x; a.dz = (const bf16_t*)dz; a.partial = partial; a.scale = scale; a.shift = shift;
   a.M = N * H * W; a.H = H; a.W = W; a.HW = H * W; a.Cin = Cin; a.Cout = Cout; a.R = R; a.J = R * R * Cin;
   a.nsteps = (a.M + wgw::BP - 1) / wgw::BP;
-  a.steps_per_split = (a.nsteps + splits - 1) / splits;
-  if ((size_t)(splits - 1) * a.steps_per_split >= (size_t)a.nsteps) return hipErrorInvalidValue;   // an empty slice
+  if (splits > a.nsteps) return hipErrorInvalidValue;   // an empty slice
+  a.nsplits = splits;
+  a.by_xcd = getenv("DDG_NO_WGRAD_XCD") ? 0 : 1;
   a.cit = Cin / 128; a.taps = R * R;
   static bool attr_set = false;
   if (!attr_set) {
