@@ -40,8 +40,8 @@ HIP_KERNEL_OF = {
     "conv_wgrad.tiled_c32_w16": "ddg::wgrad_tiled_kernel<32, 32, 16, 1, 3>",
     "conv_wgrad.tiled_c64_w8": "ddg::wgrad_tiled_kernel<64, 64, 8, 1, 3>",
     "conv_wgrad.tiled_stride2": "ddg::wgrad_tiled_kernel<Cin, 2*Cin, W, 2, R>",
-    "conv_fprop.wide": "ddg::conv_wide_kernel<true, XFORM, BK>",
-    "conv_dgrad.wide": "ddg::conv_wide_kernel<false, false, BK>",
+    "conv_fprop.wide": "ddg::conv_wide_kernel<1, XFORM, BK, R>",
+    "conv_dgrad.wide": "ddg::conv_wide_kernel<0|2, false, BK, R>",
     "conv_wgrad.wide": "ddg::wgrad_wide_kernel",
     "conv_fprop.generic": "ddg::conv_mfma_kernel<T, MB, NB, false>",
     "conv_dgrad.generic": "ddg::conv_mfma_kernel<T, MB, NB, true>",

@@ -34,9 +34,9 @@ def kind_of(kernel_name: str) -> str:
     m = re.match(r"wgrad_tiled_kernel<(\d+), (\d+), (\d+), (\d+), (\d+)>", n)
     if m:   # <Cin, Cout, output width, stride, kernel size>
         return "conv_wgrad.tiled_stride2" if m.group(4) == "2" else f"conv_wgrad.tiled_c{m.group(1)}_w{m.group(3)}"
-    m = re.match(r"conv_wide_kernel<(true|false), ", n)
-    if m:   # with statistics: the forward conv; without: the input gradient
-        return "conv_fprop.wide" if m.group(1) == "true" else "conv_dgrad.wide"
+    m = re.match(r"conv_wide_kernel<(\d+), ", n)
+    if m:   # <STATS, ...>: 1 = forward statistics (the forward conv); 0 / 2 = the input gradient
+        return "conv_fprop.wide" if m.group(1) == "1" else "conv_dgrad.wide"
     if n.startswith("wgrad_wide_kernel"):
         return "conv_wgrad.wide"
     m = re.match(r"conv_mfma_kernel<.*(true|false)>", n)
@@ -45,7 +45,8 @@ def kind_of(kernel_name: str) -> str:
     table = [("wgrad_mfma_kernel", "conv_wgrad.generic"), ("wgrad_reduce", "wgrad_reduce"),
              ("bn_bwd_apply_kernel", "bn_bwd_apply"), ("bn_bwd_apply_chunk_kernel", "bn_bwd_apply"), ("bn_bwd_reduce_kernel", "bn_bwd_reduce"),
              ("bn_bwd_finalize", "bn_bwd_finalize"), ("bn_apply_kernel", "bn_apply"),
-             ("bn_apply_chunk_kernel", "bn_apply"),
+             ("bn_apply_chunk_kernel", "bn_apply"), ("bn_apply_pair_kernel", "bn_apply"),
+             ("running_update_kernel", "bn_running"), ("eval_vectors_kernel", "bn_running"),
              ("bn_finalize", "bn_finalize"), ("head_", "head"), ("sgd_kernel", "sgd"),
              ("pack_", "pack_weights"), ("copy_kernel", "copy")]
     for prefix, kind in table:
