@@ -130,7 +130,10 @@ hipError_t wgrad_tiled_launch(const void* x, const float* scale, const float* sh
 //   mode 1: sum / sum of squares of the stored outputs (batch-norm forward of this conv)
 //   mode 2: the outputs are an error gradient v; with the ReLU mask of the layer below applied,
 //           g = (mask*mscale+mshift > 0) ? v : 0, the rows hold sum g and sum g*xhat of that
-//           layer's BN (xhat = (z - zmean)*zinvstd): its bn_bwd_reduce pass comes for free
+//           layer's BN (xhat = (z - zmean)*zinvstd): its bn_bwd_reduce pass comes for free.
+//           The stored output is g, not v: the mask is applied once, where the gradient is
+//           produced, and its readers (BN backward of that layer, the shortcut term of the
+//           block below) take it as already masked.
 struct ConvStat {
   int mode;
   float* partial;

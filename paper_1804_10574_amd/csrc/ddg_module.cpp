@@ -873,7 +873,8 @@ ddg_status flush_pending_wgrad(ddg_module* m) {
 //   dx: where the input gradient goes (null: not needed); add_g/add_mask: optional term added
 //       to dx in the same kernel
 //   below: if given and the input-gradient kernel supports it, that kernel also forms the
-//       BN-backward sums of the unit below from dx; *below_done reports whether it did
+//       BN-backward sums of the unit below from dx and stores dx multiplied by that unit's ReLU
+//       mask; *below_rows > 0 reports that it did (the readers of dx then pass mask = null)
 ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mask, const float* mscale,
                          const float* mshift, int stats_rows, const void* x_in, const float* x_scale,
                          const float* x_shift, void* dz_buf, void* dx, const void* add_g, const void* add_mask,
@@ -1030,6 +1031,8 @@ ddg_status run_backward(ddg_module* m, std::vector<Blk>& blocks, const void* in,
   }
   void* gnext = (dy == m->Ga) ? m->Gb : m->Ga;  // where this block's input gradient goes
   int top_rows = 0;   // > 0: the BN sums of this block's last unit are already in the workspace
+  // DDG_NO_PREMASK=1 (timing experiments): readers apply the ReLU mask again (same result, the old traffic)
+  static const bool premasked = !(getenv("DDG_NO_PREMASK") && getenv("DDG_NO_PREMASK")[0] == '1');
   for (int bi = nres - 1; bi >= 0; --bi) {
     Blk& b = blocks[bi];
     const void* x = (bi == 0) ? in : blocks[bi - 1].y;
@@ -1045,21 +1048,24 @@ ddg_status run_backward(ddg_module* m, std::vector<Blk>& blocks, const void* in,
       below_blk.mask = pb.y;
     }
     int next_top_rows = 0;
+    // the ReLU mask of this block's output: already applied to dy by the kernel that produced
+    // it, if that kernel also formed the sums (top_rows > 0)
+    const void* ymask = (top_rows > 0 && premasked) ? nullptr : b.y;
     if (b.kind == DDG_BLOCK_STEM) {
-      DDG_OKAY(unit_backward(m, b.u[0], dy, b.y, nullptr, nullptr, top_rows, x, nullptr, nullptr, m->D1,
+      DDG_OKAY(unit_backward(m, b.u[0], dy, ymask, nullptr, nullptr, top_rows, x, nullptr, nullptr, m->D1,
                              dx_dst, nullptr, nullptr, bi > 0 ? &below_blk : nullptr, &next_top_rows));
     } else {
       // shortcut term of the input gradient
       const void* add_g = nullptr; const void* add_mask = nullptr;
       if (b.proj) {
         Unit& up = b.u[b.nmain];
-        DDG_OKAY(unit_backward(m, up, dy, b.y, nullptr, nullptr, 0, x, nullptr, nullptr, m->D1,
+        DDG_OKAY(unit_backward(m, up, dy, ymask, nullptr, nullptr, 0, x, nullptr, nullptr, m->D1,
                                want_dx ? m->D3 : nullptr, nullptr, nullptr, nullptr, nullptr));
         if (want_dx) add_g = m->D3;
       } else if (want_dx) {
-        add_g = dy; add_mask = b.y;
+        add_g = dy; add_mask = ymask;
       }
-      const void* d = dy; const void* mask = b.y;
+      const void* d = dy; const void* mask = ymask;
       const float *msc = nullptr, *msh = nullptr;
       int stats_rows = top_rows;
       for (int i = b.nmain - 1; i >= 0; --i) {
@@ -1080,8 +1086,12 @@ ddg_status run_backward(ddg_module* m, std::vector<Blk>& blocks, const void* in,
         DDG_OKAY(unit_backward(m, u, d, mask, msc, msh, stats_rows, uin, xsc, xsh, m->D1, udx,
                                i == 0 ? add_g : nullptr, i == 0 ? add_mask : nullptr,
                                (udx && below.u) ? &below : nullptr, &done));
-        if (i > 0) { d = m->D2; mask = uin; msc = xsc; msh = xsh; stats_rows = done; }
-        else next_top_rows = done;
+        if (i > 0) {
+          d = m->D2; mask = uin; msc = xsc; msh = xsh; stats_rows = done;
+          if (done > 0 && premasked) { mask = nullptr; msc = nullptr; msh = nullptr; }   // D2 is masked already
+        } else {
+          next_top_rows = done;
+        }
       }
     }
     top_rows = next_top_rows;

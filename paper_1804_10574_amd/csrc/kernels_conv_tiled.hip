@@ -329,6 +329,27 @@ __device__ __forceinline__ void conv3x3_tiled_body(const ConvTiledArgs& a, unsig
       }
       uint2 o;
       o.x = Store<bf16_t>::pack2(v[0], v[1]); o.y = Store<bf16_t>::pack2(v[2], v[3]);
+      float bmu[4], bis[4], zz[4];
+      if (MODE == 2) {
+        // the gradient leaves this kernel already multiplied by the ReLU mask of the layer below
+        // (every reader of it applies that mask first, so it is applied once, here)
+        const float mk[4] = {lo(ek[i].x), hi(ek[i].x), lo(ek[i].y), hi(ek[i].y)};
+        const int cq = cb * 16 + lg * 4;
+        const float4 bmu4 = *reinterpret_cast<const float4*>(&s_below[cq]);
+        const float4 bis4 = *reinterpret_cast<const float4*>(&s_below[C + cq]);
+        const float4 bms4 = *reinterpret_cast<const float4*>(&s_below[2 * C + cq]);
+        const float4 bmh4 = *reinterpret_cast<const float4*>(&s_below[3 * C + cq]);
+        bmu[0] = bmu4.x; bmu[1] = bmu4.y; bmu[2] = bmu4.z; bmu[3] = bmu4.w;
+        bis[0] = bis4.x; bis[1] = bis4.y; bis[2] = bis4.z; bis[3] = bis4.w;
+        const float bms[4] = {bms4.x, bms4.y, bms4.z, bms4.w}, bmh[4] = {bmh4.x, bmh4.y, bmh4.z, bmh4.w};
+        if (two_tensors) { zz[0] = lo(ez[i].x); zz[1] = hi(ez[i].x); zz[2] = lo(ez[i].y); zz[3] = hi(ez[i].y); }
+        else { zz[0] = mk[0]; zz[1] = mk[1]; zz[2] = mk[2]; zz[3] = mk[3]; }
+        const uint32_t k0 = (mk[0] * bms[0] + bmh[0]) > 0.f ? 0x0000ffffu : 0u;
+        const uint32_t k1 = (mk[1] * bms[1] + bmh[1]) > 0.f ? 0xffff0000u : 0u;
+        const uint32_t k2 = (mk[2] * bms[2] + bmh[2]) > 0.f ? 0x0000ffffu : 0u;
+        const uint32_t k3 = (mk[3] * bms[3] + bmh[3]) > 0.f ? 0xffff0000u : 0u;
+        o.x &= k0 | k1; o.y &= k2 | k3;
+      }
       *reinterpret_cast<uint2*>(a.out + obase + i * 16 * C) = o;
       if (MODE != 0) {
         const float r[4] = {lo(o.x), hi(o.x), lo(o.y), hi(o.y)};   // the values as stored
@@ -336,22 +357,10 @@ __device__ __forceinline__ void conv3x3_tiled_body(const ConvTiledArgs& a, unsig
 #pragma unroll
           for (int j = 0; j < 4; ++j) { ssum[j] += r[j]; ssq[j] += r[j] * r[j]; }
         } else {
-          const float mk[4] = {lo(ek[i].x), hi(ek[i].x), lo(ek[i].y), hi(ek[i].y)};
-          const int cq = cb * 16 + lg * 4;
-          const float4 bmu4 = *reinterpret_cast<const float4*>(&s_below[cq]);
-          const float4 bis4 = *reinterpret_cast<const float4*>(&s_below[C + cq]);
-          const float4 bms4 = *reinterpret_cast<const float4*>(&s_below[2 * C + cq]);
-          const float4 bmh4 = *reinterpret_cast<const float4*>(&s_below[3 * C + cq]);
-          const float bmu[4] = {bmu4.x, bmu4.y, bmu4.z, bmu4.w}, bis[4] = {bis4.x, bis4.y, bis4.z, bis4.w};
-          const float bms[4] = {bms4.x, bms4.y, bms4.z, bms4.w}, bmh[4] = {bmh4.x, bmh4.y, bmh4.z, bmh4.w};
-          float zz[4];
-          if (two_tensors) { zz[0] = lo(ez[i].x); zz[1] = hi(ez[i].x); zz[2] = lo(ez[i].y); zz[3] = hi(ez[i].y); }
-          else { zz[0] = mk[0]; zz[1] = mk[1]; zz[2] = mk[2]; zz[3] = mk[3]; }
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float g = (mk[j] * bms[j] + bmh[j]) > 0.f ? r[j] : 0.f;
-            ssum[j] += g;
-            ssq[j] += g * ((zz[j] - bmu[j]) * bis[j]);
+            ssum[j] += r[j];
+            ssq[j] += r[j] * ((zz[j] - bmu[j]) * bis[j]);
           }
         }
       }

@@ -42,7 +42,8 @@ struct ConvWideArgs {
   // STATS = 2 (input gradient): the outputs are an error gradient v; with the ReLU mask of the
   // layer below applied, g = (bmask*bmscale + bmshift > 0) ? v : 0 (bmask null: g = v), the rows
   // hold sum g and sum g*xhat of that layer's BN (xhat = (bz - bmean)*binvstd): its
-  // bn_bwd_reduce pass comes for free. stat_partial receives the rows.
+  // bn_bwd_reduce pass comes for free. stat_partial receives the rows, and the stored output is
+  // g (the mask is applied here, once; readers take the gradient as already masked).
   const bf16_t* bmask; const float* bmscale; const float* bmshift;
   const bf16_t* bz; const float* bmean; const float* binvstd;
   // optional second minibatch (blockIdx.z = 1; forward only): same weights, its own tensors
@@ -303,7 +304,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
       uint4 o;
       o.x = Store<bf16_t>::pack2(v[0], v[1]); o.y = Store<bf16_t>::pack2(v[2], v[3]);
       o.z = Store<bf16_t>::pack2(v[4], v[5]); o.w = Store<bf16_t>::pack2(v[6], v[7]);
-      *reinterpret_cast<uint4*>(g_out + idx) = o;
+      if (STATS != 2) *reinterpret_cast<uint4*>(g_out + idx) = o;
       if (STATS == 1) {
         float r[8];
         Store<bf16_t>::unpack_vec(o, r);            // the values as stored
@@ -311,8 +312,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
         for (int e = 0; e < 8; ++e) { ssum[e] += r[e]; ssq[e] += r[e] * r[e]; }
       }
       if (STATS == 2) {
+        // the gradient leaves this kernel already multiplied by the ReLU mask of the layer below
+        // (every reader of it applies that mask first, so it is applied once, here)
         float r[8], zz[8], mk[8];
-        Store<bf16_t>::unpack_vec(o, r);            // the gradient as stored
+        Store<bf16_t>::unpack_vec(o, r);
         const uint4 zq = *reinterpret_cast<const uint4*>(a.bz + idx);
         Store<bf16_t>::unpack_vec(zq, zz);
         uint4 mq = zq;
@@ -321,9 +324,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(BK == 64 ? 
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const float g = (!a.bmask || mk[e] * bms[e] + bmh[e] > 0.f) ? r[e] : 0.f;
+          r[e] = g;
           ssum[e] += g;
           ssq[e] += g * ((zz[e] - bmu[e]) * bis[e]);
         }
+        o.x = Store<bf16_t>::pack2(r[0], r[1]); o.y = Store<bf16_t>::pack2(r[2], r[3]);   // (exact: bf16 values or zeros)
+        o.z = Store<bf16_t>::pack2(r[4], r[5]); o.w = Store<bf16_t>::pack2(r[6], r[7]);
+        *reinterpret_cast<uint4*>(g_out + idx) = o;
       }
     }
   }
