@@ -28,6 +28,11 @@
  *                    batch-norm backward fused into it) instead of beside the next
  *                    input-gradient kernel
  *   DDG_NO_WIDE=1    wide bf16 layers (>= 128 channels, stride 1) run the generic kernels
+ *   DDG_NO_WIDE_BELOW=1  the input-gradient kernel of a wide layer leaves the batch-norm
+ *                    backward sums of the layer below to a reduction pass
+ *   DDG_NO_WGRAD_XCD=1  the wide weight-gradient kernel keeps the launch order of its workgroups
+ *   DDG_NO_PREMASK=1 readers of an error gradient that was stored already multiplied by a
+ *                    ReLU mask load the mask tensor and apply it again (same values)
  *   DDG_TUNE_CONV_GRID_C16/_C32/_C64, DDG_TUNE_WGRAD_ROWS[_C16/_C32/_C64], DDG_TUNE_WGRAD_WIDE_WGS
  *                    workgroup counts of the LDS-tiled kernels (clamped to safe ranges)
  * None of them changes a result beyond the order of floating-point sums.
