@@ -1,4 +1,5 @@
-"""Builds the HIP library (gfx950) in-tree: paper_1804_10574_amd/libddg.so."""
+"""Builds the HIP library (gfx950) in-tree: paper_1804_10574_amd/libddg.so, and the stand-alone
+measuring tool paper_1804_10574_amd/ddg_peaks (attained HBM bandwidth and MFMA rates)."""
 from __future__ import annotations
 
 import concurrent.futures as cf
@@ -10,6 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libddg.so")
+PEAKS = os.path.join(HERE, "ddg_peaks")
 
 SOURCES = ["kernels_conv.hip", "kernels_conv_tiled.hip", "kernels_conv_wide.hip", "kernels_wgrad.hip", "kernels_wgrad_tiled.hip", "kernels_wgrad_wide.hip", "kernels_elem.hip", "ddg_module.cpp", "ddg_pipeline.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -37,6 +39,10 @@ def build_library(verbose: bool = True) -> str:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.check_call(cmd)
+    r = subprocess.run([HIPCC] + FLAGS + [os.path.join(CSRC, "peaks_main.hip"), "-o", PEAKS], capture_output=True, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("hipcc failed on peaks_main.hip")
     if verbose:
         print("built", LIB)
     return LIB

@@ -118,6 +118,26 @@ def traffic(fetch_csv: str, write_csv: str, out=sys.stdout):
         print(f"{kind} | {' + '.join(sorted(names))} | {n} | {fs / n:.1f} | {ws / n:.1f} | {b:.0f}", file=out)
 
 
+def mfma(util_csv: str, flops_csv: str, out=sys.stdout):
+    """Matrix-core evidence per kernel kind from two counter passes: MfmaUtil (MFMA-busy cycles
+    over elapsed cycles times SIMDs, in %) and MfmaFlopsBF16 (flops the MFMA instructions
+    executed, zero padding included)."""
+    u_agg, _ = _per_kernel(util_csv, "MfmaUtil")
+    f_agg, _ = _per_kernel(flops_csv, "MfmaFlopsBF16")
+    print("kind | kernel | dispatches | MfmaUtil % (mean over dispatches) | executed bf16 MFMA GFLOP/dispatch", file=out)
+    kinds = collections.defaultdict(lambda: [0, 0.0, 0, 0.0, []])
+    for name, (n, us) in u_agg.items():
+        k = kinds[kind_of(name)]
+        k[0] += n; k[1] += us; k[4].append(name)
+    for name, (n, fs) in f_agg.items():
+        k = kinds[kind_of(name)]
+        k[2] += n; k[3] += fs
+    for kind, (n, us, nf, fs, names) in sorted(kinds.items(), key=lambda kv: -kv[1][3]):
+        if fs <= 0.0:
+            continue                                  # no matrix-core work in this kind
+        print(f"{kind} | {' + '.join(sorted(names))} | {n} | {us / max(n, 1):.2f} | {fs / max(nf, 1) / 1e9:.3f}", file=out)
+
+
 def read_traffic_table(path: str) -> dict:
     """kind -> calibrated bytes per dispatch, from a summary written by `traffic`."""
     table = {}
@@ -133,11 +153,14 @@ def main():
     sub = ap.add_subparsers(dest="cmd", required=True)
     s = sub.add_parser("stats"); s.add_argument("csv"); s.add_argument("--steps", type=float, required=True)
     t = sub.add_parser("traffic"); t.add_argument("fetch_csv"); t.add_argument("write_csv")
+    f = sub.add_parser("mfma"); f.add_argument("util_csv"); f.add_argument("flops_csv")
     a = ap.parse_args()
     if a.cmd == "stats":
         stats(a.csv, a.steps)
-    else:
+    elif a.cmd == "traffic":
         traffic(a.fetch_csv, a.write_csv)
+    else:
+        mfma(a.util_csv, a.flops_csv)
 
 
 if __name__ == "__main__":
