@@ -11,10 +11,13 @@
 // is a shifted pixel row with zeros outside the image. Global loads of the next 64 pixels are
 // in flight while the current ones are contracted (double-buffered through registers).
 //
-// Four waves as 2 (co) x 2 (ci), 64 x 64 each = 16 accumulator tiles of
-// mfma_f32_16x16x32_bf16. The pixel slices (split-K) give the launch enough workgroups; each
-// writes an fp32 partial tile [split][co][tap*Cin + ci], which wgrad_reduce_all_kernel adds in
-// a fixed order (deterministic).
+// Eight waves as 2 (pixel halves of a step) x 2 (co) x 2 (ci), 64 x 64 each = 16 accumulator
+// tiles of mfma_f32_16x16x32_bf16; the two pixel halves meet in LDS at the end, so a workgroup
+// writes one tile for twice the matrix work in flight. The pixel slices (split-K) give the
+// launch enough workgroups; each writes an fp32 partial tile [split][co][tap*Cin + ci], which
+// wgrad_reduce_all_kernel adds in a fixed order (deterministic). The partial tiles are what
+// this kernel costs in memory traffic (64 KB per workgroup, written here and read by the
+// reduction), hence one workgroup of eight waves per compute unit rather than two of four.
 #include "ddg_device.h"
 #include "ddg_kernels.h"
 #include <cstdlib>
@@ -52,12 +55,14 @@ __device__ __forceinline__ uint4 wide_frag_tr(const unsigned char* p) {
   return make_uint4(l.x, l.y, h.x, h.y);
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void wgrad_wide_kernel(WgradWideArgs a) {
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void wgrad_wide_kernel(WgradWideArgs a) {
   using namespace wgw;
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, lg = lane >> 4;
-  const int wa = wave & 1, wb = wave >> 1;           // co half, ci half
+  const int wa = wave & 1, wb = (wave >> 1) & 1;     // co half, ci half
+  const int kg = wave >> 2;                          // pixels 32*kg .. 32*kg + 31 of every step
   // Workgroups go to the 8 XCDs round-robin in launch order. All tiles of one pixel slice read
   // the same rows of x and dz, so the (slice, tile) pairs are numbered slice-major and XCD j is
   // given the j-th eighth of that sequence: the rows of a slice then come from memory once into
@@ -79,10 +84,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void w
   const int s0 = split * a.nsteps / a.nsplits;
   const int s1 = (split + 1) * a.nsteps / a.nsplits;
 
-  // staging map: 16-byte unit tid + q*256 of a 64 x 128 tile = pixel (tid>>4) + 16*q, chunk tid&15
+  // staging map: 16-byte unit tid + q*512 of a 64 x 128 tile = pixel (tid>>4) + 32*q, chunk tid&15
   const int ch = tid & 15, prow = tid >> 4;
   const int xshift = (dr * a.W + ds) * a.Cin;
-  uint4 z0, z1, z2, z3, x0, x1, x2, x3;   // (named: arrays here are not promoted to registers)
+  uint4 z0, z1, x0, x1;   // (named: arrays here are not promoted to registers)
   auto ldz = [&](int m) __attribute__((always_inline)) {
     return m < a.M ? *reinterpret_cast<const uint4*>(a.dz + (size_t)m * a.Cout + co0 + ch * 8) : make_uint4(0, 0, 0, 0);
   };
@@ -100,9 +105,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void w
   };
   auto issue = [&](int step) __attribute__((always_inline)) {
     const int m = step * BP + prow;
-    z0 = ldz(m); z1 = ldz(m + 16); z2 = ldz(m + 32); z3 = ldz(m + 48);
+    z0 = ldz(m); z1 = ldz(m + 32);
     xin = 0;
-    x0 = ldx(m, 0); x1 = ldx(m + 16, 1); x2 = ldx(m + 32, 2); x3 = ldx(m + 48, 3);
+    x0 = ldx(m, 0); x1 = ldx(m + 32, 1);
   };
   // per-channel constants of this thread's 8 input channels (the same in every step)
   float tsc[8], tsh[8];
@@ -125,13 +130,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void w
   auto stash = [&](int buf) __attribute__((always_inline)) {
     unsigned char* Z = smem + buf * BUF + prow * ROW + ch * 16;
     unsigned char* X = Z + OPB;
-    if (xform) {
-      x0 = act(x0, xin & 1u); x1 = act(x1, xin & 2u); x2 = act(x2, xin & 4u); x3 = act(x3, xin & 8u);
-    }
-    *reinterpret_cast<uint4*>(Z) = z0; *reinterpret_cast<uint4*>(Z + 16 * ROW) = z1;
-    *reinterpret_cast<uint4*>(Z + 32 * ROW) = z2; *reinterpret_cast<uint4*>(Z + 48 * ROW) = z3;
-    *reinterpret_cast<uint4*>(X) = x0; *reinterpret_cast<uint4*>(X + 16 * ROW) = x1;
-    *reinterpret_cast<uint4*>(X + 32 * ROW) = x2; *reinterpret_cast<uint4*>(X + 48 * ROW) = x3;
+    if (xform) { x0 = act(x0, xin & 1u); x1 = act(x1, xin & 2u); }
+    *reinterpret_cast<uint4*>(Z) = z0; *reinterpret_cast<uint4*>(Z + 32 * ROW) = z1;
+    *reinterpret_cast<uint4*>(X) = x0; *reinterpret_cast<uint4*>(X + 32 * ROW) = x1;
   };
 
   f32x4_t acc[4][4];
@@ -143,42 +144,52 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void w
   // fragment address of (k-step 0, channel block 0): lane s of a 16-lane block points at
   // channels 4*(s%4).. of pixel lg*8 + s/4; the second read is 4 pixels further
   const int frag = (lg * 8 + (l16 >> 2)) * ROW + (l16 & 3) * 8;
-  const int zoff = frag + wa * 128;            // + i*32 (channel block) + ks*32*ROW
-  const int xoff = OPB + frag + wb * 128;
+  const int zoff = frag + wa * 128 + kg * 32 * ROW;   // + i*32 (channel block)
+  const int xoff = OPB + frag + wb * 128 + kg * 32 * ROW;
 
-  if (s0 < s1) {
-    issue(s0);
-    stash(0);
-  }
+  issue(s0);          // (the host gives every slice at least one step)
+  stash(0);
   __syncthreads();
   for (int s = s0; s < s1; ++s) {
     const bool more = s + 1 < s1;
     if (more) issue(s + 1);
     const unsigned char* B = smem + ((s - s0) & 1) * BUF;
+    uint4 zf[4], xf[4];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      uint4 zf[4], xf[4];
+    for (int i = 0; i < 4; ++i) zf[i] = wide_frag_tr(B + zoff + i * 32);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) zf[i] = wide_frag_tr(B + zoff + i * 32 + ks * 32 * ROW);
+    for (int j = 0; j < 4; ++j) xf[j] = wide_frag_tr(B + xoff + j * 32);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) xf[j] = wide_frag_tr(B + xoff + j * 32 + ks * 32 * ROW);
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = Mma<bf16_t>::mma(zf[i], xf[j], acc[i][j]);
-    }
+      for (int j = 0; j < 4; ++j) acc[i][j] = Mma<bf16_t>::mma(zf[i], xf[j], acc[i][j]);
     if (more) stash((s + 1 - s0) & 1);
     __syncthreads();
   }
 
-  // lane (l16, lg) of tile (i, j) holds co = co0 + (wa*4 + i)*16 + lg*4 + e, ci = ci0 + (wb*4 + j)*16 + l16
-  float* dst = a.partial + ((size_t)split * a.Cout + co0 + wa * 64 + lg * 4) * a.J + (size_t)tap * a.Cin + ci0 + wb * 64 + l16;
+  // the two pixel halves meet: waves 4-7 hand their accumulators over through LDS (the staging
+  // buffers are free after the loop's last barrier), [wave & 3][register][lane], 64 KB
+  float* ex = reinterpret_cast<float*>(smem) + (wave & 3) * 64 * 64 + lane;
+  if (kg == 1) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) dst[(size_t)(i * 16 + e) * a.J + j * 16] = acc[i][j][e];
+        for (int e = 0; e < 4; ++e) ex[((i * 4 + j) * 4 + e) * 64] = acc[i][j][e];
+  }
+  __syncthreads();
+  if (kg == 0) {
+    // lane (l16, lg) of tile (i, j) holds co = co0 + (wa*4 + i)*16 + lg*4 + e, ci = ci0 + (wb*4 + j)*16 + l16
+    float* dst = a.partial + ((size_t)split * a.Cout + co0 + wa * 64 + lg * 4) * a.J + (size_t)tap * a.Cin + ci0 + wb * 64 + l16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          dst[(size_t)(i * 16 + e) * a.J + j * 16] = acc[i][j][e] + ex[((i * 4 + j) * 4 + e) * 64];
+  }
 }
 
 bool wgrad_wide_ok(int Cin, int Cout, int R, int stride, int dtype) {
@@ -188,10 +199,10 @@ bool wgrad_wide_ok(int Cin, int Cout, int R, int stride, int dtype) {
 }
 
 // Number of pixel slices (= partial tiles per output element) for a layer: enough workgroups to
-// fill the GPU (about two per compute unit), at least 2 steps of 64 pixels each.
+// fill the GPU (one of eight waves per compute unit), at least 2 steps of 64 pixels each.
 // DDG_TUNE_WGRAD_WIDE_WGS overrides the target workgroup count within [64, 2048].
 int wgrad_wide_splits(int M, int Cin, int Cout, int R) {
-  int target = 512;
+  int target = 256;
   if (const char* e = getenv("DDG_TUNE_WGRAD_WIDE_WGS")) {
     const int v = atoi(e);
     if (v >= 64 && v <= 2048) target = v;
@@ -223,7 +234,7 @@ hipError_t wgrad_wide_launch(const void* x, const void* dz, float* partial, int 
     attr_set = true;
   }
   const dim3 grid((Cout / 128) * a.taps * a.cit, splits);
-  DDG_LAUNCH(wgrad_wide_kernel, grid, dim3(256), wgw::LDS, s, a);
+  DDG_LAUNCH(wgrad_wide_kernel, grid, dim3(512), wgw::LDS, s, a);
   return hipGetLastError();
 }
 
