@@ -597,6 +597,77 @@ def test_wide_bottleneck_module_bf16(H, nblocks, batch, c, mid, hw):
     assert np.median(deriv) <= 0.1 and max(deriv) <= 0.25
 
 
+def test_full_size_bottleneck_module_bf16(H):
+    """The ImageNet-shaped module exactly as `bench.py --workload r101_stage3_k4m2` runs it: 23
+    bottleneck blocks 1024-256-256-1024 at 14x14, batch 32 (6272 pixels per layer: 98 pixel
+    tiles, the 16 / 7 pixel slices of the weight-gradient kernel), k = 2 of K = 4, bf16: two
+    warm-up iterations (forward only) and the first one with a delayed backward pass and an
+    update. The oracle affords this size in fp32 arithmetic (five orders of magnitude finer
+    than the storage type, three times faster than fp64).
+
+    69 layers deep, bf16 storage rounding moves ANY implementation away from the unrounded
+    result by about 0.4 % per block (8-9 % for the module output), and two correct bf16
+    implementations away from each other by almost as much, so a fixed tolerance between the
+    two says nothing at this depth. Criterion, as for the deep CIFAR networks: the HIP path
+    must be as close to the unrounded result as the oracle in its bf16-storage mode is (at
+    most 1.25 times its distance plus the bf16 tolerance), for the module output of every
+    iteration, the error gradient passed down, and the weight gradient (all of it, and the
+    first and the last block alone). Through 23 blocks the gradients of both bf16 runs lie
+    0.76 away from the unrounded ones (0.40 for the last block) and within 0.5 % of each
+    other's distance; a zero or an unrelated gradient would lie at 1.0 or 1.4 and fail."""
+    import torch
+    import paper_1804_10574_amd as ddg
+    from oracle import ddg_oracle as orc
+    wl = wk.get_workload("r101_stage3_k4m2")
+    m = wl.modules[0]
+    mod = ddg.Module(H.descs_for(wl)[0])
+    rounded = orc.OracleNet.from_workload(wl, dtype="f32", store_bf16=True)
+    exact = orc.OracleNet.from_workload(wl, dtype="f32", store_bf16=False)
+    H.init_both(wl, {m.k: mod}, rounded)
+    exact.set_params(m.k, rounded.get_params(m.k))
+    shape_in = (wl.batch, m.in_c, m.in_h, m.in_w)
+    tol, factor = 2e-2, 1.25
+    bad = []
+
+    def check(what, got, rnd, ex):
+        a, b = H.rel_err(got, ex), H.rel_err(rnd, ex)
+        _say(f"full-size bottleneck module {what}: from the unrounded result HIP {a:.3e}, bf16-mode oracle {b:.3e}; "
+             f"HIP from the bf16-mode oracle {H.rel_err(got, rnd):.3e}")
+        if not a <= factor * b + tol:
+            bad.append(f"{what}: {a:.3e} vs {b:.3e}")
+
+    for t in range(3):
+        _say(f"case full-size bottleneck module t={t}")
+        h_in = wk.normal(7, 300 + t, int(np.prod(shape_in))).reshape(shape_in)
+        delta = wk.synthetic_delta(wl, m, t)
+        hd, dd = H.to_dev_nhwc(h_in, wl), H.to_dev_nhwc(delta, wl)
+        h_in, delta = H.from_dev_nhwc(hd), H.from_dev_nhwc(dd)
+        h_out = torch.empty((wl.batch, m.out_h, m.out_w, m.out_c), dtype=H.tdtype(wl), device="cuda")
+        d_out = torch.zeros_like(hd)
+        torch.cuda.synchronize()
+        mod.forward(t, hd, h_out)
+        did = mod.backward_delayed(t, delta_in=dd, delta_out=d_out)
+        mod.update(t, wl.lr)
+        mod.sync()
+        check(f"h t={t}", H.from_dev_nhwc(h_out), rounded.forward(m.k, t, h_in), exact.forward(m.k, t, h_in))
+        r_did, r_dout, _ = rounded.backward_delayed(m.k, t, delta, None, in_shape=shape_in)
+        e_did, e_dout, _ = exact.backward_delayed(m.k, t, delta, None, in_shape=shape_in)
+        assert did == bool(r_did) == bool(e_did) == (t >= 2)
+        if did:
+            g, rg, eg = mod.get_grad(), rounded.get_grad(m.k), exact.get_grad(m.k)
+            assert np.all(np.isfinite(g))
+            per = len(g) // len(m.blocks)
+            assert per * len(m.blocks) == len(g)
+            check("delta_out", H.from_dev_nhwc(d_out), r_dout, e_dout)
+            check("dW", g, rg, eg)
+            check("dW of the first block", g[:per], rg[:per], eg[:per])
+            check("dW of the last block", g[-per:], rg[-per:], eg[-per:])
+        rounded.update(m.k, wl.lr)
+        exact.update(m.k, wl.lr)
+    mod.close()
+    assert not bad, "; ".join(bad)
+
+
 def test_full_size_bench_configuration(H):
     """ResNet-110 / K=4 / batch 256 / bf16 exactly as bench.py runs it (K streams, graph replay).
     The oracle cannot run this size in test time, so:
