@@ -93,13 +93,20 @@ template <> struct Store<bf16_t> {
 template <typename T> struct Mma;
 
 template <> struct Mma<float> {
-  static constexpr int KV = 1;      // k-values per lane
-  static constexpr int KSTEP = 4;   // k per instruction
-  typedef float frag_t;
-  __device__ static __forceinline__ frag_t zero() { return 0.f; }
-  __device__ static __forceinline__ frag_t load(const float* p) { return *p; }
+  // Four instructions of k = 4 per fragment: a lane holds 4 consecutive k-values (one 16-byte
+  // load) and instruction j contracts element j of every lane, i.e. the k-values
+  // {(l/16)*4 + j}. Any assignment of k-values to instructions is as good as another as long
+  // as both operands use the same one, and this one makes every gather a 16-byte access.
+  static constexpr int KV = 4;      // k-values per lane
+  static constexpr int KSTEP = 16;  // k per fragment
+  typedef float4 frag_t;
+  __device__ static __forceinline__ frag_t zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+  __device__ static __forceinline__ frag_t load(const float* p) { return *reinterpret_cast<const float4*>(p); }
   __device__ static __forceinline__ f32x4_t mma(frag_t x, frag_t y, f32x4_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x4f32(x, y, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.x, y.x, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.y, y.y, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(x.z, y.z, c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(x.w, y.w, c, 0, 0, 0);
   }
 };
 

@@ -26,7 +26,7 @@ extern thread_local ProfEvents g_prof_events;
 
 enum DType { F32 = 0, BF16 = 1 };
 inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
-inline int mma_kv(int dt) { return dt == BF16 ? 8 : 1; }
+inline int mma_kv(int dt) { return dt == BF16 ? 8 : 4; }
 
 // Partial rows of a batch-norm reduction that the consuming kernel finalises itself
 // (partial == nullptr: the per-channel vectors are already final).

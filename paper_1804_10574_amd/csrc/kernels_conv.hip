@@ -5,8 +5,8 @@
 // MB pixel-blocks x NB channel-blocks of 16x16 accumulators; a lane's accumulator
 // registers are 4 consecutive channels of one pixel, so the result is stored NHWC
 // with one 8/16-byte store per lane. Activation fragments are gathered straight
-// from the NHWC tensor (one 16-byte load of 8 bf16 channels of one tap, or one
-// float), which makes the im2col matrix implicit; zero padding, stride and the
+// from the NHWC tensor (one 16-byte load of 8 bf16 or 4 fp32 channels of one tap),
+// which makes the im2col matrix implicit; zero padding, stride and the
 // divisibility test of the input-gradient are folded into the gather predicate.
 //
 // The forward variant also accumulates per-channel sum and sum of squares of the
@@ -102,6 +102,9 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) e[j] = (c0 + j < a.IC) ? (uint32_t)reinterpret_cast<const uint16_t*>(p)[j] : 0u;
             af = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+          } else {
+            const float* pf = reinterpret_cast<const float*>(p);
+            af = make_float4(pf[0], c0 + 1 < a.IC ? pf[1] : 0.f, c0 + 2 < a.IC ? pf[2] : 0.f, c0 + 3 < a.IC ? pf[3] : 0.f);
           }
         }
 #pragma unroll
