@@ -45,7 +45,7 @@ HIP_KERNEL_OF = {
     "conv_wgrad.wide": "ddg::wgrad_wide_kernel",
     "conv_fprop.generic": "ddg::conv_mfma_kernel<T, MB, NB, false>",
     "conv_dgrad.generic": "ddg::conv_mfma_kernel<T, MB, NB, true>",
-    "conv_wgrad.generic": "ddg::wgrad_mfma_kernel<T>",
+    "conv_wgrad.generic": "ddg::wgrad_mfma_vec_kernel<T> / wgrad_mfma_kernel<T>",
 }
 
 

@@ -83,8 +83,9 @@ struct WgradArgs {
   int log2cp, J, JB;        // J = ntaps*CP columns, JB = ceil(J/16)
   int M;                    // N*P*Q
   int msplit, steps;        // splits over M, 4-pixel steps per wave
-  int jgroups;              // column-block groups of up to 9
+  int jgroups;              // column-block groups of up to 9 (vec: groups of 192 columns)
   int dtype;
+  int vec;                  // 1: input channels a multiple of 4, the kernel with 4-channel gathers
 };
 void wgrad_plan(WgradArgs& a);
 size_t wgrad_partial_elems(const WgradArgs& a);

@@ -42,7 +42,7 @@ def kind_of(kernel_name: str) -> str:
     m = re.match(r"conv_mfma_kernel<.*(true|false)>", n)
     if m:
         return "conv_dgrad.generic" if m.group(1) == "true" else "conv_fprop.generic"
-    table = [("wgrad_mfma_kernel", "conv_wgrad.generic"), ("wgrad_reduce", "wgrad_reduce"),
+    table = [("wgrad_mfma_kernel", "conv_wgrad.generic"), ("wgrad_mfma_vec_kernel", "conv_wgrad.generic"), ("wgrad_reduce", "wgrad_reduce"),
              ("bn_bwd_apply_kernel", "bn_bwd_apply"), ("bn_bwd_apply_chunk_kernel", "bn_bwd_apply"), ("bn_bwd_reduce_kernel", "bn_bwd_reduce"),
              ("bn_bwd_finalize", "bn_bwd_finalize"), ("bn_apply_kernel", "bn_apply"),
              ("bn_apply_chunk_kernel", "bn_apply"), ("bn_apply_pair_kernel", "bn_apply"),
