@@ -43,8 +43,8 @@ HIP_KERNEL_OF = {
     "conv_fprop.wide": "ddg::conv_wide_kernel<1, XFORM, BK, R>",
     "conv_dgrad.wide": "ddg::conv_wide_kernel<0|2, false, BK, R>",
     "conv_wgrad.wide": "ddg::wgrad_wide_kernel",
-    "conv_fprop.generic": "ddg::conv_mfma_kernel<T, MB, NB, false>",
-    "conv_dgrad.generic": "ddg::conv_mfma_kernel<T, MB, NB, true>",
+    "conv_fprop.generic": "ddg::conv_mfma_kernel<T, MB, NB, false, VEC>",
+    "conv_dgrad.generic": "ddg::conv_mfma_kernel<T, MB, NB, true, VEC>",
     "conv_wgrad.generic": "ddg::wgrad_mfma_vec_kernel<T> / wgrad_mfma_kernel<T>",
 }
 

@@ -17,7 +17,15 @@
 
 namespace ddg {
 
-template <typename T, int MB, int NB, bool DGRAD>
+// Keeps a loaded fragment alive at the point of its use whatever the predicate says: without it
+// the compiler moves the load back under the predicate, which makes it a branch, and every
+// branch around a load ends in a wait for all loads in flight.
+__device__ __forceinline__ void keep_frag(uint4& f) { asm volatile("" : "+v"(f.x), "+v"(f.y), "+v"(f.z), "+v"(f.w)); }
+__device__ __forceinline__ void keep_frag(float4& f) { asm volatile("" : "+v"(f.x), "+v"(f.y), "+v"(f.z), "+v"(f.w)); }
+
+// VEC: the contraction channel count is a multiple of the fragment width (every layer but a
+// 3-channel stem): gathers are whole fragments and none of them is conditional.
+template <typename T, int MB, int NB, bool DGRAD, bool VEC>
 __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
   using M_ = Mma<T>;
   using S_ = Store<T>;
@@ -37,7 +45,6 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
   const int ohow = a.OH * a.OW;
   const int cpmask = (1 << a.log2cp) - 1;
   const int sshift = a.stride - 1;  // stride is 1 or 2
-  const bool vec_ok = (a.IC % KV) == 0;
 
   float ssum[NB][4], ssq[NB][4];
 #pragma unroll
@@ -67,6 +74,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) acc[i][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+#pragma unroll 2
     for (int ks = 0; ks < a.ksteps; ++ks) {
       const int kidx = (ks * 4 + lg) * KV;
       const int tap = kidx >> a.log2cp;
@@ -78,6 +86,8 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
         wf[nb] = M_::load(wp + ((size_t)(ks * OCB + cb0 + nb) * 64 + lane) * KV);
+      typename M_::frag_t ld[MB];
+      bool okv[MB];
 #pragma unroll
       for (int i = 0; i < MB; ++i) {
         int ih, iw;
@@ -91,21 +101,34 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
           ih = ph[i] + r; iw = pw[i] + s;
           ok = ok && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
         }
-        typename M_::frag_t af = M_::zero();
-        if (ok) {
-          const T* p = in + ((size_t)(pn[i] * a.IH + ih) * a.IW + iw) * a.IC + c0;
-          if (vec_ok) {
-            af = M_::load(p);
-          } else if constexpr (KV == 8) {
-            // contraction channels not a multiple of 8 (3-channel images): element gather
-            uint32_t e[8];
+        okv[i] = ok;
+        if (VEC) {
+          // a padded or masked position reads the tensor's first elements instead (dropped below)
+          const size_t off = ok ? ((size_t)(pn[i] * a.IH + ih) * a.IW + iw) * a.IC + c0 : (size_t)0;
+          ld[i] = M_::load(in + off);
+        } else {
+          ld[i] = M_::zero();
+          if (ok) {
+            const T* p = in + ((size_t)(pn[i] * a.IH + ih) * a.IW + iw) * a.IC + c0;
+            if constexpr (KV == 8) {
+              // contraction channels not a multiple of 8 (3-channel images): element gather
+              uint32_t e[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) e[j] = (c0 + j < a.IC) ? (uint32_t)reinterpret_cast<const uint16_t*>(p)[j] : 0u;
-            af = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
-          } else {
-            const float* pf = reinterpret_cast<const float*>(p);
-            af = make_float4(pf[0], c0 + 1 < a.IC ? pf[1] : 0.f, c0 + 2 < a.IC ? pf[2] : 0.f, c0 + 3 < a.IC ? pf[3] : 0.f);
+              for (int j = 0; j < 8; ++j) e[j] = (c0 + j < a.IC) ? (uint32_t)reinterpret_cast<const uint16_t*>(p)[j] : 0u;
+              ld[i] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+            } else {
+              const float* pf = reinterpret_cast<const float*>(p);
+              ld[i] = make_float4(pf[0], c0 + 1 < a.IC ? pf[1] : 0.f, c0 + 2 < a.IC ? pf[2] : 0.f, c0 + 3 < a.IC ? pf[3] : 0.f);
+            }
           }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        typename M_::frag_t af = ld[i];
+        if (VEC) {
+          keep_frag(af);
+          if (!okv[i]) af = M_::zero();
         }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[i][nb] = M_::mma(wf[nb], af, acc[i][nb]);
@@ -193,6 +216,12 @@ void conv_plan(ConvArgs& a) {
   if (ocb % 4 == 0) { a.nb = 4; a.mb = 2; }
   else if (ocb % 2 == 0) { a.nb = 2; a.mb = 2; }
   else { a.nb = 1; a.mb = 4; }
+  if (a.dtype != BF16) {
+    // fp32 matrix instructions are 16 times slower per flop than bf16 ones: a wave's tile is
+    // what bounds the launch, so tiles shrink until there are about two per SIMD
+    a.nb = 1; a.mb = 4;
+    while (a.mb > 1 && (long)((a.M + 16 * a.mb - 1) / (16 * a.mb)) * ocb < 2048) a.mb /= 2;
+  }
   const int gy = ocb / a.nb;
   const int tiles = (a.M + 16 * a.mb - 1) / (16 * a.mb);
   int gx = (tiles + 3) / 4;
@@ -205,13 +234,21 @@ void conv_plan(ConvArgs& a) {
 template <typename T>
 static hipError_t conv_dispatch(const ConvArgs& a, hipStream_t s) {
   dim3 grid(a.grid_x, (a.OC / 16) / a.nb, a.in_b ? 2 : 1), block(256);
-#define DDG_CONV_CASE(MB_, NB_)                                                          \
-  if (a.mb == MB_ && a.nb == NB_) {                                                      \
-    if (a.dgrad) DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, true>), grid, block, 0, s, a);  \
-    else DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, false>), grid, block, 0, s, a);         \
-    return hipGetLastError();                                                            \
+  const bool vec = a.IC % Mma<T>::KV == 0;
+#define DDG_CONV_CASE(MB_, NB_)                                                                   \
+  if (a.mb == MB_ && a.nb == NB_) {                                                               \
+    if (vec) {                                                                                    \
+      if (a.dgrad) DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, true, true>), grid, block, 0, s, a);   \
+      else DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, false, true>), grid, block, 0, s, a);          \
+    } else {                                                                                      \
+      if (a.dgrad) DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, true, false>), grid, block, 0, s, a);  \
+      else DDG_LAUNCH((conv_mfma_kernel<T, MB_, NB_, false, false>), grid, block, 0, s, a);         \
+    }                                                                                             \
+    return hipGetLastError();                                                                     \
   }
   DDG_CONV_CASE(4, 1)
+  DDG_CONV_CASE(2, 1)
+  DDG_CONV_CASE(1, 1)
   DDG_CONV_CASE(2, 2)
   DDG_CONV_CASE(2, 4)
 #undef DDG_CONV_CASE

@@ -8,6 +8,7 @@
 // kernel adds the partials in a fixed order (no atomics: results are reproducible).
 #include "ddg_device.h"
 #include "ddg_kernels.h"
+#include <cstdlib>
 
 namespace ddg {
 
@@ -42,14 +43,18 @@ __global__ __launch_bounds__(256) void wgrad_mfma_kernel(WgradArgs a) {
   for (int b = 0; b < WG_NJ; ++b) acc[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int pq = a.P * a.Q;
+  const bool fdiv = a.M < (1 << 22);
+  const float inv_pq = 1.0f / (float)pq, inv_q = 1.0f / (float)a.Q;
   long m0 = ((long)blockIdx.x * 4 + wave) * (long)a.steps * 4;
   for (int st = 0; st < a.steps; ++st) {
     const long m = m0 + (long)st * 4 + lg;
     const bool mv = m < a.M;
     const int mm = mv ? (int)m : 0;
-    const int n = mm / pq;
+    // (small non-negative integers divide exactly through fp32; an integer division costs as
+    // much as the step's matrix instructions)
+    const int n = fdiv ? (int)(((float)mm + 0.5f) * inv_pq) : mm / pq;
     const int rem = mm - n * pq;
-    const int p = rem / a.Q;
+    const int p = fdiv ? (int)(((float)rem + 0.5f) * inv_q) : rem / a.Q;
     const int q = rem - p * a.Q;
     const float dv = mv ? S_::load1(dz + (size_t)mm * a.Cout + cob * 16 + l16) : 0.f;
     const int ihb = p * a.stride, iwb = q * a.stride;
@@ -116,26 +121,56 @@ __global__ __launch_bounds__(256) void wgrad_mfma_vec_kernel(WgradArgs a) {
     for (int e = 0; e < 4; ++e) acc[g][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int pq = a.P * a.Q;
+  const bool fdiv = a.M < (1 << 22);
+  const float inv_pq = 1.0f / (float)pq, inv_q = 1.0f / (float)a.Q;
   long m0 = ((long)blockIdx.x * 4 + wave) * (long)a.steps * 4;
-  for (int st = 0; st < a.steps; ++st) {
+  // Nothing in the loop is conditional (a masked position loads element 0 and contributes a
+  // zero), and the loads of step st+1 are requested before the matrix instructions of step st.
+  struct StepRegs { float dv; float xq[WGV_NG][4]; unsigned ok; };   // ok bit g: group g valid, bit 31: pixel valid
+  auto issue = [&](StepRegs& r, int st) __attribute__((always_inline)) {
     const long m = m0 + (long)st * 4 + lg;
-    const bool mv = m < a.M;
+    const bool mv = st < a.steps && m < a.M;
     const int mm = mv ? (int)m : 0;
-    const int n = mm / pq;
+    // (small non-negative integers divide exactly through fp32; an integer division costs as
+    // much as the step's matrix instructions)
+    const int n = fdiv ? (int)(((float)mm + 0.5f) * inv_pq) : mm / pq;
     const int rem = mm - n * pq;
-    const int p = rem / a.Q;
+    const int p = fdiv ? (int)(((float)rem + 0.5f) * inv_q) : rem / a.Q;
     const int q = rem - p * a.Q;
-    const float dv = mv ? S_::load1(dz + (size_t)mm * a.Cout + cob * 16 + l16) : 0.f;
+    r.dv = S_::load1(dz + (size_t)mm * a.Cout + cob * 16 + l16);
     const int ihb = p * a.stride, iwb = q * a.stride;
+    unsigned okb = mv ? 0x80000000u : 0u;
 #pragma unroll
     for (int g = 0; g < WGV_NG; ++g) {
       const int ih = ihb + jr[g], iw = iwb + js[g];
       const bool ok = mv && jv[g] && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-      float xq[4] = {0.f, 0.f, 0.f, 0.f};
-      if (ok) S_::load4(x + ((size_t)(n * a.H + ih) * a.W + iw) * a.Cin + jc[g], xq);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[g][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, xq[e], acc[g][e], 0, 0, 0);
+      const size_t off = ok ? ((size_t)(n * a.H + ih) * a.W + iw) * a.Cin + jc[g] : (size_t)0;
+      S_::load4(x + off, r.xq[g]);
+      okb |= (ok ? 1u : 0u) << g;
     }
+    r.ok = okb;
+  };
+  auto contract = [&](StepRegs& r) __attribute__((always_inline)) {
+    // (the empty statements keep the loads where they are: left to itself the compiler moves a
+    // load under its predicate, and a branch around a load ends in a wait for every load in flight)
+    asm volatile("" : "+v"(r.dv));
+    const float dv = (r.ok >> 31) ? r.dv : 0.f;
+#pragma unroll
+    for (int g = 0; g < WGV_NG; ++g) {
+      asm volatile("" : "+v"(r.xq[g][0]), "+v"(r.xq[g][1]), "+v"(r.xq[g][2]), "+v"(r.xq[g][3]));
+      const bool ok = (r.ok >> g) & 1u;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        acc[g][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, ok ? r.xq[g][e] : 0.f, acc[g][e], 0, 0, 0);
+    }
+  };
+  StepRegs ra, rb;     // two sets, used in turn (a step past the end is masked: it adds zeros)
+  issue(ra, 0);
+  for (int st = 0; st < a.steps; st += 2) {
+    issue(rb, st + 1);
+    contract(ra);
+    issue(ra, st + 2);
+    contract(rb);
   }
 
   // sum the four waves in a fixed order, then write the partial tile (columns back in order)
@@ -243,7 +278,11 @@ void wgrad_plan(WgradArgs& a) {
   a.vec = (a.Cin % 4 == 0) ? 1 : 0;       // the kernel with 4-channel gathers
   a.jgroups = a.vec ? (a.JB * 16 + 64 * WGV_NG - 1) / (64 * WGV_NG) : (a.JB + WG_NJ - 1) / WG_NJ;
   const int tiles = (a.Cout / 16) * a.jgroups;
-  int want = 1024 / tiles;               // workgroups over the pixel range
+  int want = 512 / tiles;                // workgroups over the pixel range (two per compute unit; more only add partial tiles)
+  if (const char* e = getenv("DDG_TUNE_WGRAD_GENERIC_WGS")) {   // timing experiments, within [64, 4096]
+    const int v = atoi(e);
+    if (v >= 64 && v <= 4096) want = v / tiles;
+  }
   if (want < 1) want = 1;
   const long quads = ((long)a.M + 3) / 4;  // 4-pixel steps in total
   long steps = (quads + (long)want * 4 - 1) / ((long)want * 4);

@@ -39,8 +39,8 @@ def kind_of(kernel_name: str) -> str:
         return "conv_fprop.wide" if m.group(1) == "1" else "conv_dgrad.wide"
     if n.startswith("wgrad_wide_kernel"):
         return "conv_wgrad.wide"
-    m = re.match(r"conv_mfma_kernel<.*(true|false)>", n)
-    if m:
+    m = re.match(r"conv_mfma_kernel<\w+, \d+, \d+, (true|false)", n)
+    if m:   # <T, MB, NB, DGRAD, VEC>
         return "conv_dgrad.generic" if m.group(1) == "true" else "conv_fprop.generic"
     table = [("wgrad_mfma_kernel", "conv_wgrad.generic"), ("wgrad_mfma_vec_kernel", "conv_wgrad.generic"), ("wgrad_reduce", "wgrad_reduce"),
              ("bn_bwd_apply_kernel", "bn_bwd_apply"), ("bn_bwd_apply_chunk_kernel", "bn_bwd_apply"), ("bn_bwd_reduce_kernel", "bn_bwd_reduce"),
