@@ -180,7 +180,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet110_k4")
     ap.add_argument("--cpu-sample-batch", type=int, default=32,
-                    help="batch of the oracle's timed sample (K warm-up + 3 timed iterations; about 10 s of CPU work)")
+                    help="batch of the oracle's timed sample (K warm-up + 8 timed iterations; about 10 s of CPU work)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
@@ -335,7 +335,7 @@ def main():
     pipe.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = (cpu_baseline_single(wl.name, min(args.cpu_sample_batch, 2)) if single
-                               else cpu_baseline(wl.name, args.cpu_sample_batch, timed_steps=3))
+                               else cpu_baseline(wl.name, args.cpu_sample_batch, timed_steps=8))
     print(json.dumps(out))
 
 
