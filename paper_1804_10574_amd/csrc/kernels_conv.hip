@@ -74,7 +74,6 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) acc[i][nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-#pragma unroll 2
     for (int ks = 0; ks < a.ksteps; ++ks) {
       const int kidx = (ks * 4 + lg) * KV;
       const int tap = kidx >> a.log2cp;
@@ -104,7 +103,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(ConvArgs a) {
         okv[i] = ok;
         if (VEC) {
           // a padded or masked position reads the tensor's first elements instead (dropped below)
-          const size_t off = ok ? ((size_t)(pn[i] * a.IH + ih) * a.IW + iw) * a.IC + c0 : (size_t)0;
+          const unsigned off = ok ? (unsigned)((pn[i] * a.IH + ih) * a.IW + iw) * (unsigned)a.IC + (unsigned)c0 : 0u;   // (32 bits: the host checks)
           ld[i] = M_::load(in + off);
         } else {
           ld[i] = M_::zero();
@@ -256,6 +255,8 @@ static hipError_t conv_dispatch(const ConvArgs& a, hipStream_t s) {
 }
 
 hipError_t conv_launch(const ConvArgs& a, hipStream_t s) {
+  // the gathers form 32-bit element offsets
+  if ((size_t)a.N * a.IH * a.IW * a.IC >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   return a.dtype == BF16 ? conv_dispatch<bf16_t>(a, s) : conv_dispatch<float>(a, s);
 }
 

@@ -137,14 +137,14 @@ __global__ __launch_bounds__(256) void wgrad_mfma_vec_kernel(WgradArgs a) {
     const int rem = mm - n * pq;
     const int p = fdiv ? (int)(((float)rem + 0.5f) * inv_q) : rem / a.Q;
     const int q = rem - p * a.Q;
-    r.dv = S_::load1(dz + (size_t)mm * a.Cout + cob * 16 + l16);
+    r.dv = S_::load1(dz + ((unsigned)mm * (unsigned)a.Cout + (unsigned)(cob * 16 + l16)));
     const int ihb = p * a.stride, iwb = q * a.stride;
     unsigned okb = mv ? 0x80000000u : 0u;
 #pragma unroll
     for (int g = 0; g < WGV_NG; ++g) {
       const int ih = ihb + jr[g], iw = iwb + js[g];
       const bool ok = mv && jv[g] && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-      const size_t off = ok ? ((size_t)(n * a.H + ih) * a.W + iw) * a.Cin + jc[g] : (size_t)0;
+      const unsigned off = ok ? (unsigned)((n * a.H + ih) * a.W + iw) * (unsigned)a.Cin + (unsigned)jc[g] : 0u;   // (32 bits: the host checks)
       S_::load4(x + off, r.xq[g]);
       okb |= (ok ? 1u : 0u) << g;
     }
@@ -298,6 +298,8 @@ hipError_t wgrad_launch(const WgradArgs& a, hipStream_t s) {
   dim3 grid(a.msplit, a.Cout / 16, a.jgroups), block(256);
   if (a.vec) {
     if (a.Cin % 4 != 0) return hipErrorInvalidValue;
+    // 32-bit element offsets inside
+    if ((size_t)a.N * a.H * a.W * a.Cin >= ((size_t)1 << 32) || (size_t)a.M * a.Cout >= ((size_t)1 << 32)) return hipErrorInvalidValue;
     if (a.dtype == BF16) DDG_LAUNCH(wgrad_mfma_vec_kernel<bf16_t>, grid, block, 0, s, a);
     else DDG_LAUNCH(wgrad_mfma_vec_kernel<float>, grid, block, 0, s, a);
     return hipGetLastError();
