@@ -147,6 +147,8 @@ struct ddg_module {
     const void* x = nullptr; const float* xsc = nullptr; const float* xsh = nullptr; const void* dz = nullptr;
   } pend_w;
   bool defer_wgrad = true;         // DDG_NO_BWD_PAIR=1 switches the deferred weight gradient off
+  bool no_defer = false;           // DDG_NO_DEFER=1: every residual block runs its own normalise-add-ReLU pass
+  bool premasked = true;           // DDG_NO_PREMASK=1: readers of a stored masked gradient apply the mask again
   // Evaluation: running batch-norm estimates, flat per conv unit in parameter order (mean[C],
   // variance[C]), followed in the same allocation by the evaluation scale/shift vectors; one
   // table of layer descriptors per group of forward buffers (the statistics the estimates
@@ -306,7 +308,10 @@ ddg_status build_plan(ddg_module* m) {
   const int N = d.batch;
   // A module with a delay runs forward(t) and the re-forward of iteration t-K+k in the same
   // launches (same weights, two minibatches): second group of forward buffers.
-  static const bool no_pair = getenv("DDG_NO_PAIR") && getenv("DDG_NO_PAIR")[0] == '1';
+  auto env_on = [](const char* name) { const char* e = getenv(name); return e && e[0] == '1'; };
+  const bool no_pair = env_on("DDG_NO_PAIR");
+  m->no_defer = env_on("DDG_NO_DEFER");
+  m->premasked = !env_on("DDG_NO_PREMASK");
   m->stale = d.stale_jacobian != 0 && d.K - d.k > 0;
   m->groups = m->stale ? (d.K - d.k + 1) : ((d.K - d.k > 0 && !m->two_streams && !no_pair) ? 2 : 1);
   m->in_elems = (size_t)N * h * w * c;
@@ -753,7 +758,7 @@ static bool tiled_identity_block(const Blk& b) {
 // with its own batch statistics); other blocks run once per group.
 ddg_status run_forward_pair(ddg_module* m, std::vector<Blk>& blocks, const void* in0, const void* in1, void* out1) {
   const int nres = (int)blocks.size() - (m->d.num_classes > 0 ? 1 : 0);
-  static const bool no_defer = getenv("DDG_NO_DEFER") && getenv("DDG_NO_DEFER")[0] == '1';
+  const bool no_defer = m->no_defer;
   const void* x0 = in0; const void* x1 = in1;
   struct { Unit* u = nullptr; const void* res = nullptr; void* y = nullptr; } pend;   // group-0 pointers
   for (int bi = 0; bi < nres; ++bi) {
@@ -794,7 +799,7 @@ ddg_status run_forward(ddg_module* m, std::vector<Blk>& blocks, const void* in, 
   // An identity block followed by another identity block of the same shape does not run its
   // own normalise-add-ReLU pass: the next block's first conv forms y = relu(bn(z) + x) while
   // loading and stores it (`pend` carries what that conv needs).
-  static const bool no_defer = getenv("DDG_NO_DEFER") && getenv("DDG_NO_DEFER")[0] == '1';
+  const bool no_defer = m->no_defer;
   struct { Unit* u = nullptr; const void* res = nullptr; void* y = nullptr; } pend;
   for (int bi = 0; bi < nres; ++bi) {
     Blk& b = blocks[bi];
@@ -1032,7 +1037,7 @@ ddg_status run_backward(ddg_module* m, std::vector<Blk>& blocks, const void* in,
   void* gnext = (dy == m->Ga) ? m->Gb : m->Ga;  // where this block's input gradient goes
   int top_rows = 0;   // > 0: the BN sums of this block's last unit are already in the workspace
   // DDG_NO_PREMASK=1 (timing experiments): readers apply the ReLU mask again (same result, the old traffic)
-  static const bool premasked = !(getenv("DDG_NO_PREMASK") && getenv("DDG_NO_PREMASK")[0] == '1');
+  const bool premasked = m->premasked;
   for (int bi = nres - 1; bi >= 0; --bi) {
     Blk& b = blocks[bi];
     const void* x = (bi == 0) ? in : blocks[bi - 1].y;

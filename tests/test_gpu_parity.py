@@ -514,6 +514,20 @@ def test_cifar_shaped_pipeline_bf16_unpaired_backward(H, monkeypatch):
     assert not report, "\n".join(report)
 
 
+@pytest.mark.parametrize("switch", ["DDG_NO_PAIR", "DDG_NO_DEFER", "DDG_NO_PREMASK", "DDG_NO_GRAPH"])
+def test_cifar_shaped_pipeline_bf16_other_launch_plans(H, monkeypatch, switch):
+    """The same pipeline under each of the library's other environment switches (read when a
+    module or pipeline is created): forward(t) and the re-forward as separate passes; a
+    normalise-add-ReLU pass per residual block instead of the fold into the next conv; readers
+    of a stored masked gradient applying the mask again; kernels enqueued instead of replayed
+    as graphs. Each is a different plan of launches for the same arithmetic."""
+    monkeypatch.setenv(switch, "1")
+    wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="bf16", name="cifar_k3")
+    _say(f"case cifar_k3 bf16 steps=8, {switch}=1")
+    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=0.2, loose=0.6)
+    assert not report, "\n".join(report)
+
+
 def test_cifar_shaped_pipeline_f32(H):
     wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="f32", name="cifar_k3")
     _say("case cifar_k3 f32 steps=8")
