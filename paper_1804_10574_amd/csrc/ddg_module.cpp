@@ -149,6 +149,7 @@ struct ddg_module {
   bool defer_wgrad = true;         // DDG_NO_BWD_PAIR=1 switches the deferred weight gradient off
   bool no_defer = false;           // DDG_NO_DEFER=1: every residual block runs its own normalise-add-ReLU pass
   bool premasked = true;           // DDG_NO_PREMASK=1: readers of a stored masked gradient apply the mask again
+  bool wide_below = true;          // DDG_NO_WIDE_BELOW=1: wide input-gradient kernels leave the sums of the layer below to a reduction pass
   // Evaluation: running batch-norm estimates, flat per conv unit in parameter order (mean[C],
   // variance[C]), followed in the same allocation by the evaluation scale/shift vectors; one
   // table of layer descriptors per group of forward buffers (the statistics the estimates
@@ -312,6 +313,7 @@ ddg_status build_plan(ddg_module* m) {
   const bool no_pair = env_on("DDG_NO_PAIR");
   m->no_defer = env_on("DDG_NO_DEFER");
   m->premasked = !env_on("DDG_NO_PREMASK");
+  m->wide_below = getenv("DDG_NO_WIDE_BELOW") == nullptr;
   m->stale = d.stale_jacobian != 0 && d.K - d.k > 0;
   m->groups = m->stale ? (d.K - d.k + 1) : ((d.K - d.k > 0 && !m->two_streams && !no_pair) ? 2 : 1);
   m->in_elems = (size_t)N * h * w * c;
@@ -977,7 +979,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     // reads dz and the weights, writes dx; plus the shortcut term (and its mask), plus the mask
     // and conv output of the layer below when its BN-backward sums are formed here
     const bool wide_below = u.tiled_grid == 0 && u.wide_d && below && below->u && below->u->cout == u.cin &&
-                            m->d.compute == DDG_BF16 && !getenv("DDG_NO_WIDE_BELOW");
+                            m->d.compute == DDG_BF16 && m->wide_below;
     const bool fuse_below = (u.tiled_grid > 0 && below && below->u) || wide_below;
     double extra = (add_g ? (add_mask ? 2.0 : 1.0) : 0.0);
     if (fuse_below) extra += (below->mask == below->u->z) ? 1.0 : 2.0;
