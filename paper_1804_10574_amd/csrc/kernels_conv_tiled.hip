@@ -419,7 +419,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(conv_tiled_
 // layer before, so on the small feature maps fewer, longer-running workgroups mean less L2
 // traffic. DDG_TUNE_CONV_GRID_C16/_C32/_C64 override the defaults within [32, 2048].
 static int conv_tiled_cap(int C) {
-  int cap = C == 16 ? 256 : 128;
+  int cap = C == 16 ? 256 : (C == 32 ? 128 : 96);   // (measured: c64 flat between 64 and 96, worse at 48 and at 128+)
   const char* name = C == 16 ? "DDG_TUNE_CONV_GRID_C16" : (C == 32 ? "DDG_TUNE_CONV_GRID_C32" : "DDG_TUNE_CONV_GRID_C64");
   if (const char* e = getenv(name)) {
     const int v = atoi(e);
