@@ -36,10 +36,19 @@ __global__ __launch_bounds__(1024) void bn_finalize_kernel(const float* __restri
     }
   r1[slice][cl] = s1; r2[slice][cl] = s2;
   __syncthreads();
+  // the 64 slices in two short steps (8 x 8, each in a fixed order) instead of one chain of 64
+  double p1 = 0.0, p2 = 0.0;
+  if (slice < 8) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { p1 += r1[slice * 8 + i][cl]; p2 += r2[slice * 8 + i][cl]; }
+  }
+  __syncthreads();
+  if (slice < 8) { r1[slice][cl] = p1; r2[slice][cl] = p2; }
+  __syncthreads();
   if (slice == 0 && c < C) {
     double t1 = 0.0, t2 = 0.0;
 #pragma unroll
-    for (int i = 0; i < 64; ++i) { t1 += r1[i][cl]; t2 += r2[i][cl]; }
+    for (int i = 0; i < 8; ++i) { t1 += r1[i][cl]; t2 += r2[i][cl]; }
     const double mu = t1 / (double)count;
     double var = t2 / (double)count - mu * mu;
     if (var < 0.0) var = 0.0;
@@ -412,10 +421,18 @@ __global__ __launch_bounds__(1024) void bn_bwd_finalize_kernel(const float* __re
     }
   r1[slice][cl] = s1; r2[slice][cl] = s2;
   __syncthreads();
+  double p1 = 0.0, p2 = 0.0;   // two short steps, as in bn_finalize_kernel
+  if (slice < 8) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { p1 += r1[slice * 8 + i][cl]; p2 += r2[slice * 8 + i][cl]; }
+  }
+  __syncthreads();
+  if (slice < 8) { r1[slice][cl] = p1; r2[slice][cl] = p2; }
+  __syncthreads();
   if (slice == 0 && c < C) {
     double db = 0.0, dg = 0.0;
 #pragma unroll
-    for (int i = 0; i < 64; ++i) { db += r1[i][cl]; dg += r2[i][cl]; }
+    for (int i = 0; i < 8; ++i) { db += r1[i][cl]; dg += r2[i][cl]; }
     dbeta[c] = (float)db;
     dgamma[c] = (float)dg;
     const double g = gamma[c], is = invstd[c], mu = mean[c], m = count;
