@@ -690,14 +690,17 @@ __global__ __launch_bounds__(256) void head_sample_kernel(const T* __restrict__ 
   __syncthreads();
   float den = 0.f;
   for (int j = 0; j < classes; ++j) den += s_dl[j];
+  // a label outside [0, classes) has no class to point at: that sample's loss (and with it the
+  // mean loss) is NaN, so the caller sees it, and nothing outside the logits is read
   const int y = labels[n];
+  const bool y_ok = (unsigned)y < (unsigned)classes;
   __syncthreads();
   for (int j = tid; j < classes; j += 256) {
     const float d = (s_dl[j] / den - (j == y ? 1.f : 0.f)) / (float)N;
     s_dl[j] = d;
     dlogits[(size_t)n * classes + j] = d;
   }
-  if (tid == 0) loss_n[n] = -(s_lg[y] - mx - logf(den));
+  if (tid == 0) loss_n[n] = y_ok ? -(s_lg[y] - mx - logf(den)) : __builtin_nanf("");
   if (!dh) return;
   __syncthreads();
   for (int c = tid; c < C; c += 256) {
