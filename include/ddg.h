@@ -211,6 +211,21 @@ ddg_status ddg_set_running(ddg_module* m, const float* host_src);
 ddg_status ddg_forward_eval(ddg_module* m, const void* h_in, void* h_out, const int32_t* labels,
                             float* loss_out, float* logits_out);
 
+/* For callers that cannot allocate device memory when they evaluate (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): ddg_forward_eval with every
+ * intermediate of the pass (conv outputs, statistics rows, activations, block outputs, the
+ * head's per-sample vectors) in a static device array that is part of the library, 64 MiB per
+ * GPU, held until the process ends, instead of the module's forward buffers. Same arguments,
+ * same results (the same kernels run). It calls no hipMalloc / hipFree and leaves the module's
+ * forward buffers alone, so it is also available in stale-Jacobian mode. A module whose pass
+ * needs more than the 64 MiB (two block outputs plus two blocks' worth of conv outputs; e.g.
+ * ResNet-110's first module up to batch 256 fits) is refused with DDG_ERR_SHAPE and a message
+ * that names both sizes. Every call on one GPU, from any module or thread, uses the same array:
+ * calls that overlap on one GPU (different streams, or threads) race, so keep them on one
+ * stream or order them yourself. Between iterations only, like ddg_forward_eval. */
+ddg_status ddg_forward_eval_static(ddg_module* m, const void* h_in, void* h_out, const int32_t* labels,
+                                   float* loss_out, float* logits_out);
+
 /* Wait for the module's stream. */
 ddg_status ddg_module_sync(ddg_module* m);
 

@@ -264,4 +264,10 @@ hipError_t adam_launch(float* w, float* m1, float* m2, const float* g, size_t n,
 hipError_t copy_launch(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t to_f32_launch(const void* src, float* dst, size_t elems, int dtype, hipStream_t s);
 
+// Static device scratch (ddg_scratch.hip): a file-scope __device__ array of this many bytes per
+// GPU. static_scratch returns its device address on the current device (looked up once per
+// device) and its size. Every caller on a GPU shares the one array.
+#define DDG_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+hipError_t static_scratch(void** ptr, size_t* bytes);
+
 }  // namespace ddg

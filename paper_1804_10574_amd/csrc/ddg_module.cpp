@@ -1463,8 +1463,34 @@ ddg_status ddg_set_running(ddg_module* m, const float* host_src) {
   return DDG_OK;
 }
 
-ddg_status ddg_forward_eval(ddg_module* m, const void* h_in, void* h_out, const int32_t* labels, float* loss_out,
-                            float* logits_out) {
+// The evaluation forward through `blocks` (the module's own forward buffers, or a view of them
+// whose buffers lie elsewhere); hs: the head's per-sample scratch.
+struct HeadScratch { float* pooled; float* dlogits; float* loss_n; };
+static ddg_status eval_forward(ddg_module* m, std::vector<Blk>& blocks, const HeadScratch& hs, const void* h_in,
+                               void* h_out, const int32_t* labels, float* loss_out, float* logits_out) {
+  const bool head = m->d.num_classes > 0;
+  m->stream = m->bstream;
+  if (m->n_run) DDG_TRY(eval_vectors_launch(m->run_descs[0], m->n_run, m->run_max_c, m->stream));
+  const int nres = (int)blocks.size() - (head ? 1 : 0);
+  m->eval_mode = true;
+  ddg_status st = DDG_OK;
+  if (nres > 0) st = run_forward(m, blocks, h_in, head ? nullptr : h_out);
+  m->eval_mode = false;
+  DDG_OKAY(st);
+  if (head) {
+    Blk& hb = blocks.back();
+    HeadArgs a{};
+    a.h = nres > 0 ? blocks[nres - 1].y : h_in; a.fcw = m->theta + hb.ofcw; a.fcb = m->theta + hb.ofcb;
+    a.labels = labels ? labels : m->zero_labels;
+    a.pooled = hs.pooled; a.dlogits = hs.dlogits; a.loss_n = hs.loss_n; a.loss_out = loss_out;
+    a.dfcw = nullptr; a.dfcb = nullptr; a.dh = nullptr; a.logits_out = logits_out;
+    a.N = m->d.batch; a.HW = hb.HW; a.C = hb.C; a.classes = m->d.num_classes; a.dtype = m->d.compute;
+    DDG_TRY(head_launch(a, m->stream));
+  }
+  return DDG_OK;
+}
+
+static ddg_status eval_args_ok(ddg_module* m, const void* h_in, void* h_out, const int32_t* labels, float* loss_out) {
   DDG_OKAY(check_handle(m));
   const bool head = m->d.num_classes > 0;
   if (!h_in) return fail(DDG_ERR_INVALID_ARG, "h_in is null");
@@ -1472,28 +1498,83 @@ ddg_status ddg_forward_eval(ddg_module* m, const void* h_in, void* h_out, const 
   if (head && loss_out && !labels) return fail(DDG_ERR_INVALID_ARG, "the loss needs labels");
   if (((uintptr_t)h_in & 15) || ((uintptr_t)h_out & 15)) return fail(DDG_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
   if (m->phase != 0) return fail(DDG_ERR_STATE, "evaluation runs between iterations (after ddg_update, before the next ddg_forward)");
+  return DDG_OK;
+}
+
+ddg_status ddg_forward_eval(ddg_module* m, const void* h_in, void* h_out, const int32_t* labels, float* loss_out,
+                            float* logits_out) {
+  DDG_OKAY(eval_args_ok(m, h_in, h_out, labels, loss_out));
   if (m->stale) return fail(DDG_ERR_STATE, "no evaluation forward in stale-Jacobian mode: every set of forward buffers holds a kept tape");
   if (m->d.dry_run) return DDG_OK;
-  m->stream = m->bstream;
-  if (m->n_run) DDG_TRY(eval_vectors_launch(m->run_descs[0], m->n_run, m->run_max_c, m->stream));
-  const int nres = (int)m->blocks.size() - (head ? 1 : 0);
-  m->eval_mode = true;
-  ddg_status st = DDG_OK;
-  if (nres > 0) st = run_forward(m, m->blocks, h_in, head ? nullptr : h_out);
-  m->eval_mode = false;
   m->tape_is_current = false;     // the forward buffers of group 0 now hold this pass
-  DDG_OKAY(st);
-  if (head) {
-    Blk& hb = m->blocks.back();
-    HeadArgs a{};
-    a.h = nres > 0 ? m->blocks[nres - 1].y : h_in; a.fcw = m->theta + hb.ofcw; a.fcb = m->theta + hb.ofcb;
-    a.labels = labels ? labels : m->zero_labels;
-    a.pooled = hb.pooled; a.dlogits = hb.dlogits; a.loss_n = hb.loss_n; a.loss_out = loss_out;
-    a.dfcw = nullptr; a.dfcb = nullptr; a.dh = nullptr; a.logits_out = logits_out;
-    a.N = m->d.batch; a.HW = hb.HW; a.C = hb.C; a.classes = m->d.num_classes; a.dtype = m->d.compute;
-    DDG_TRY(head_launch(a, m->stream));
+  HeadScratch hs{};
+  if (m->d.num_classes > 0) { const Blk& hb = m->blocks.back(); hs.pooled = hb.pooled; hs.dlogits = hb.dlogits; hs.loss_n = hb.loss_n; }
+  return eval_forward(m, m->blocks, hs, h_in, h_out, labels, loss_out, logits_out);
+}
+
+// Bytes of static scratch the evaluation forward of this module needs, and (base != null) a view
+// of the module's blocks whose forward buffers lie in it. Layout: two slots for block outputs
+// (block i writes slot i mod 2: the output of block i-1 is the last one read when block i+1's
+// first conv forms the output of block i), then two regions for the conv outputs, statistics
+// rows and activations of a block (block i uses region i mod 2: the last conv output of block i
+// is read while the first conv of block i+1 writes its own), then the head's per-sample vectors.
+static size_t static_eval_layout(const ddg_module* m, char* base, std::vector<Blk>* view, HeadScratch* hs) {
+  auto up = [](size_t b) { return (b + 255) & ~(size_t)255; };
+  size_t ymax = 0, zmax = 0;
+  for (const Blk& b : m->blocks) {
+    if (b.kind == DDG_BLOCK_HEAD) continue;
+    size_t zb = 0;
+    for (const Unit& u : b.u) zb += up(u.out_elems() * m->esz) + up((size_t)u.fcap * 2 * u.cout * sizeof(float));
+    for (size_t i = 0; i < b.act.size(); ++i) if (b.act[i]) zb += up(b.u[i].out_elems() * m->esz);
+    if (zb > zmax) zmax = zb;
+    if (up(b.y_elems * m->esz) > ymax) ymax = up(b.y_elems * m->esz);
   }
-  return DDG_OK;
+  size_t total = 2 * ymax + 2 * zmax;
+  const size_t head_off = total;
+  if (m->d.num_classes > 0) {
+    const Blk& hb = m->blocks.back();
+    total += up(((size_t)m->d.batch * hb.C + (size_t)m->d.batch * m->d.num_classes + m->d.batch) * sizeof(float));
+  }
+  if (!base) return total;
+  *view = m->blocks;
+  int bi = 0;
+  for (Blk& b : *view) {
+    if (b.kind == DDG_BLOCK_HEAD) continue;
+    b.y = base + (size_t)(bi & 1) * ymax;
+    char* p = base + 2 * ymax + (size_t)(bi & 1) * zmax;
+    for (Unit& u : b.u) {
+      u.z = p; p += up(u.out_elems() * m->esz);
+      u.fstat = (float*)p; p += up((size_t)u.fcap * 2 * u.cout * sizeof(float));
+    }
+    for (size_t i = 0; i < b.act.size(); ++i) if (b.act[i]) { b.act[i] = p; p += up(b.u[i].out_elems() * m->esz); }
+    ++bi;
+  }
+  if (m->d.num_classes > 0) {
+    const Blk& hb = m->blocks.back();
+    hs->pooled = (float*)(base + head_off);
+    hs->dlogits = hs->pooled + (size_t)m->d.batch * hb.C;
+    hs->loss_n = hs->dlogits + (size_t)m->d.batch * m->d.num_classes;
+  }
+  return total;
+}
+
+ddg_status ddg_forward_eval_static(ddg_module* m, const void* h_in, void* h_out, const int32_t* labels,
+                                   float* loss_out, float* logits_out) {
+  DDG_OKAY(eval_args_ok(m, h_in, h_out, labels, loss_out));
+  const size_t need = static_eval_layout(m, nullptr, nullptr, nullptr);
+  if (need > DDG_STATIC_SCRATCH_BYTES)
+    return fail(DDG_ERR_SHAPE, "this module's evaluation forward needs %zu bytes of scratch; the static scratch holds %zu",
+                need, (size_t)DDG_STATIC_SCRATCH_BYTES);
+  if (m->d.dry_run) return DDG_OK;
+  void* base = nullptr; size_t have = 0;
+  DDG_TRY(static_scratch(&base, &have));
+  std::vector<Blk> view;
+  HeadScratch hs{};
+  static_eval_layout(m, (char*)base, &view, &hs);
+  // every buffer in the scratch is written before it is read (conv outputs and statistics rows
+  // by the conv launches, block outputs by the launch that forms them, the head's vectors by the
+  // head kernel), so nothing of an earlier call's contents has to be cleared
+  return eval_forward(m, view, hs, h_in, h_out, labels, loss_out, logits_out);
 }
 
 ddg_status ddg_backward_delayed(ddg_module* m, long t, const void* delta_in, const int32_t* labels,

@@ -79,6 +79,7 @@ def load_library():
         "ddg_get_running": (st, [vp, vp]),
         "ddg_set_running": (st, [vp, vp]),
         "ddg_forward_eval": (st, [vp, vp, vp, vp, vp, vp]),
+        "ddg_forward_eval_static": (st, [vp, vp, vp, vp, vp, vp]),
         "ddg_pipeline_forward_eval": (st, [vp, vp, vp, vp, vp]),
         "ddg_pipeline_set_bn_momentum": (st, [vp, C.c_float]),
         "ddg_module_sync": (st, [vp]),
@@ -111,7 +112,7 @@ EXPORTS = ["ddg_module_create", "ddg_module_destroy", "ddg_param_count", "ddg_ou
            "ddg_forward", "ddg_backward_delayed", "ddg_update", "ddg_module_sync",
            "ddg_set_optimizer", "ddg_set_moment2", "ddg_get_moment2", "ddg_set_update_count", "ddg_get_update_count",
            "ddg_pipeline_set_optimizer",
-           "ddg_set_bn_momentum", "ddg_running_count", "ddg_get_running", "ddg_set_running", "ddg_forward_eval",
+           "ddg_set_bn_momentum", "ddg_running_count", "ddg_get_running", "ddg_set_running", "ddg_forward_eval", "ddg_forward_eval_static",
            "ddg_pipeline_forward_eval", "ddg_pipeline_set_bn_momentum",
            "ddg_pipeline_create", "ddg_pipeline_destroy", "ddg_pipeline_module", "ddg_pipeline_step",
            "ddg_pipeline_set_graphs", "ddg_pipeline_get_h", "ddg_pipeline_get_delta", "ddg_pipeline_sync", "ddg_profile_kinds",
@@ -245,6 +246,10 @@ class Module:
     def forward_eval(self, h_in, h_out=None, labels=None, loss_out=None, logits_out=None):
         _check(self._lib.ddg_forward_eval(self._h, _ptr(h_in), _ptr(h_out), _ptr(labels), _ptr(loss_out),
                                           _ptr(logits_out)))
+
+    def forward_eval_static(self, h_in, h_out=None, labels=None, loss_out=None, logits_out=None):
+        _check(self._lib.ddg_forward_eval_static(self._h, _ptr(h_in), _ptr(h_out), _ptr(labels), _ptr(loss_out),
+                                                 _ptr(logits_out)))
 
     def get_params(self):
         out = np.empty(self.param_count(), np.float32)

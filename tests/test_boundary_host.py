@@ -169,3 +169,25 @@ def test_dry_run_pipeline_schedule():
             assert it == (s if s >= 0 else -1), (t, k, it)
     for k in range(1, 5):
         assert p.module(k).param_count() == wk.module_param_count(wl.modules[k - 1], wl.num_classes)
+
+
+def test_static_scratch_evaluation_checks_its_size_on_the_host():
+    """ddg_forward_eval_static refuses, before any device work, a module whose evaluation pass
+    does not fit the 64 MiB static scratch, and runs the same argument and state checks as
+    ddg_forward_eval (dry-run modules: nothing is launched)."""
+    fake = 4096
+    wl = wk.get_workload("resnet110_k4")
+    m = ddg.Module(descs_for(wl, dry_run=True)[0])              # batch 256: 2 x 8 MiB outputs + 2 x 16 MiB convs
+    m.forward_eval_static(fake, fake)
+    with pytest.raises(ddg.DDGError) as e:
+        m.forward_eval_static(None, fake)
+    assert e.value.status == 1
+    m.forward(0, fake, fake)
+    with pytest.raises(ddg.DDGError) as e:                      # between iterations only
+        m.forward_eval_static(fake, fake)
+    assert e.value.status == 3
+    big = ddg.Module(descs_for(wl, dry_run=True, batch=512)[0])
+    with pytest.raises(ddg.DDGError) as e:
+        big.forward_eval_static(fake, fake)
+    assert e.value.status == 2 and "static scratch" in str(e.value)
+    big.forward_eval(fake, fake)                                # the allocating one has no such limit
