@@ -173,38 +173,13 @@ def cpu_baseline(wl_name, sample_batch, timed_steps=1):
                       f"{timed_steps} steady-state step(s) after {wl.K} warm-up steps, fp32 oracle"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="resnet110_k4")
-    ap.add_argument("--cpu-sample-batch", type=int, default=32,
-                    help="batch of the oracle's timed sample (K warm-up + 8 timed iterations; about 10 s of CPU work)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-roofline", action="store_true")
-    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
-                    help="momentum SGD (Algorithm 1, the headline configuration) or Adam (Algorithm 2, "
-                         "beta1 0.9, beta2 0.999, eps 1e-8)")
-    ap.add_argument("--stale-jacobian", action="store_true",
-                    help="Eq. 6-7 read literally (tapes and weight snapshots per ring slot, no re-forward); "
-                         "not the headline configuration")
-    ap.add_argument("--serial", action="store_true", help="all modules on one stream")
-    ap.add_argument("--forward-streams", action="store_true",
-                    help="give each module's forward pass a stream of its own (2K-1 streams; "
-                         "slower than K streams on this GPU, kept for comparison)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (modules are concurrent streams on one "
-              "device); --gpus must be 1", file=sys.stderr)
-        sys.exit(2)
-
+def measure(wl, args, steps, warmup):
+    """Times `steps` steps of workload wl after K + warmup untimed ones and, unless switched off,
+    runs the per-launch event pass. Returns the fields of the bench line that describe this
+    workload (value, ms_per_step, config, roofline, kernels, ...)."""
     import numpy as np
     import torch
     import workloads as wk
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    wl = wk.get_workload(args.workload)
     single = SingleModule(wl, args.stale_jacobian, args.forward_streams) if wl.single_module else None
     if single:
         pipe = single
@@ -231,21 +206,19 @@ def main():
             pipe.step(xs[i % nbuf], ys[i % nbuf], wl.lr, loss)
 
     it = 0
-    for _ in range(wl.K + args.warmup):      # fill the delay rings, then warm up
+    for _ in range(wl.K + warmup):      # fill the delay rings, then warm up
         step(it); it += 1
     pipe.sync(); torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(it); it += 1
     pipe.sync(); torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     final_loss = float(loss.cpu()[0])
-    ms = dt / args.steps * 1e3
+    ms = dt / steps * 1e3
     out = {
-        "metric": "DDG module images/sec on 1 MI355X", "value": wl.batch * args.steps / dt,
-        "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
+        "value": wl.batch * steps / dt, "unit": "images/sec", "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "dtype": wl.dtype,
         "config": {"workload": wl.name, "network": wl.notes, "K": wl.K, "global_batch": wl.batch,
                    "image": "3x32x32", "classes": wl.num_classes, "streams": (2 if args.forward_streams else 1) if (args.serial or single) else (2 * wl.K - 1 if args.forward_streams else wl.K),
                    "optimizer": args.optimizer,
@@ -265,7 +238,7 @@ def main():
         mods = single.modules() if single else [pipe.module(k) for k in range(1, wl.K + 1)]
         for m in mods:
             m.profile_reset(); m.profile_enable(True)
-        psteps = max(2, min(5, args.steps))
+        psteps = max(2, min(5, steps))
         for _ in range(psteps):
             step(it); it += 1
         pipe.sync()
@@ -275,6 +248,8 @@ def main():
                 a = fam.setdefault(name, [0, 0.0, 0.0, 0.0])
                 a[0] += n; a[1] += tms; a[2] += nbytes; a[3] += flops
             m.profile_enable(False)
+        peak_tf = MFMA_PEAK_TFLOPS[wl.dtype]
+
         def entry(n, tms, nbytes, flops):
             e = {"launches_per_step": n / psteps, "avg_us": tms / n * 1e3, "ms_per_step": tms / psteps}
             if nbytes > 0 and tms > 0:
@@ -282,6 +257,17 @@ def main():
                 e["GBps"] = nbytes / 1e9 / (tms / 1e3)
             if flops > 0 and tms > 0:
                 e["TFLOPs"] = flops / 1e12 / (tms / 1e3)
+            if nbytes > 0 and tms > 0:
+                # the roof that binds this kind: the time its algorithmic bytes need at the HBM
+                # peak against the time its flops need at the MFMA peak of its operand type; the
+                # fraction is that time over the measured one
+                t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
+                t_mfma = flops / (peak_tf * 1e12)
+                e["bound"] = "mfma" if t_mfma > t_hbm else "hbm"
+                e["frac_of_min_roof"] = max(t_hbm, t_mfma) / (tms / 1e3)
+                if flops > 0:
+                    e["mfma_frac"] = e["TFLOPs"] / peak_tf
+                e["hbm_frac"] = e["GBps"] / HBM_PEAK_GBS
             return e
 
         # the library books one kind per kernel ("family.instance"); families are their sums
@@ -296,21 +282,23 @@ def main():
         d = kernels[dom]
         n, tms, nbytes, flops = fam[dom]
         ai = flops / nbytes if nbytes else 0.0
-        ridge = MFMA_PEAK_TFLOPS[wl.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+        ridge = peak_tf * 1e12 / (HBM_PEAK_GBS * 1e9)
         if flops and ai >= ridge:
-            roof = {"bound": "mfma", "achieved": d["TFLOPs"], "peak": MFMA_PEAK_TFLOPS[wl.dtype], "unit": "TFLOP/s"}
+            roof = {"bound": "mfma", "achieved": d["TFLOPs"], "peak": peak_tf, "unit": "TFLOP/s"}
         else:
             roof = {"bound": "hbm", "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s"}
         roof["frac"] = roof["achieved"] / roof["peak"]
         # measured HBM bytes per launch of this kernel: from the committed counter summary of the
-        # same workload (two rocprofv3 --pmc passes, calibrated by the library's copy kernel)
+        # same workload (two rocprofv3 --pmc passes, calibrated by the library's copy kernel);
+        # traffic_stale: the kernel sources have changed since that summary was taken
         roof["traffic"] = None
-        tpath = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                             f"hbm_traffic_{wl.name}_{wl.dtype}.txt")
+        here = os.path.dirname(os.path.abspath(__file__))
+        tpath = os.path.join(here, "profiles", f"hbm_traffic_{wl.name}_{wl.dtype}.txt")
         if os.path.exists(tpath):
-            from paper_1804_10574_amd.profile_summary import read_traffic_table
+            from paper_1804_10574_amd.profile_summary import read_traffic_table, read_source_digest, source_digest
             roof["traffic"] = read_traffic_table(tpath).get(dom)
-            roof["traffic_source"] = os.path.relpath(tpath, os.path.dirname(os.path.abspath(__file__)))
+            roof["traffic_source"] = os.path.relpath(tpath, here)
+            roof["traffic_stale"] = read_source_digest(tpath) != source_digest()
         roof["kernel"] = dom
         roof["hip_kernel"] = HIP_KERNEL_OF.get(dom, dom)
         roof["avg_launch_us"] = d["avg_us"]
@@ -318,24 +306,85 @@ def main():
         roof["algorithmic_bytes_per_launch"] = nbytes / n
         if flops:
             roof["arithmetic_intensity_flop_per_byte"] = ai
-            roof["mfma_frac"] = d["TFLOPs"] / MFMA_PEAK_TFLOPS[wl.dtype]
+            roof["mfma_frac"] = d["TFLOPs"] / peak_tf
         out["roofline"] = roof
         out["kernels"] = kernels
         out["families"] = families
         convs = [k for k in ("conv_fprop", "conv_dgrad", "conv_wgrad", "conv_bwd_pair") if k in families]
         conv_ms = sum(famsum[k][1] for k in convs)
-        out["conv_mfma_util"] = sum(famsum[k][3] for k in convs) / 1e12 / (conv_ms / 1e3) / MFMA_PEAK_TFLOPS[wl.dtype] if conv_ms else None
+        out["conv_mfma_util"] = sum(famsum[k][3] for k in convs) / 1e12 / (conv_ms / 1e3) / peak_tf if conv_ms else None
         out["conv_hbm_frac"] = sum(famsum[k][2] for k in convs) / 1e9 / (conv_ms / 1e3) / HBM_PEAK_GBS if conv_ms else None
+        # all conv kinds against the roof that binds each of them
+        out["conv_frac_of_min_roof"] = (sum(max(fam[k][2] / (HBM_PEAK_GBS * 1e9), fam[k][3] / (peak_tf * 1e12))
+                                            for k in fam if k.split(".")[0] in convs) / (conv_ms / 1e3)) if conv_ms else None
         bn = [k for k in ("bn_apply", "bn_bwd_reduce", "bn_bwd_apply") if k in families]
         bn_ms = sum(famsum[k][1] for k in bn)
         out["bn_hbm_frac"] = sum(famsum[k][2] for k in bn) / 1e9 / (bn_ms / 1e3) / HBM_PEAK_GBS if bn_ms else None
         out["algorithmic_GFLOP_per_step"] = sum(v[3] for v in fam.values()) / psteps / 1e9
         out["algorithmic_GB_per_step"] = sum(v[2] for v in fam.values()) / psteps / 1e9
-
     pipe.close()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet110_k4")
+    ap.add_argument("--cpu-sample-batch", type=int, default=0,
+                    help="batch of the oracle's timed sample (0: the workload's own batch; K warm-up + 1 timed "
+                         "iteration, about 30 s of CPU work for resnet110_k4)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the short measurement of the ImageNet-shaped single module that the default "
+                         "run adds to its line")
+    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
+                    help="momentum SGD (Algorithm 1, the headline configuration) or Adam (Algorithm 2, "
+                         "beta1 0.9, beta2 0.999, eps 1e-8)")
+    ap.add_argument("--stale-jacobian", action="store_true",
+                    help="Eq. 6-7 read literally (tapes and weight snapshots per ring slot, no re-forward); "
+                         "not the headline configuration")
+    ap.add_argument("--serial", action="store_true", help="all modules on one stream")
+    ap.add_argument("--forward-streams", action="store_true",
+                    help="give each module's forward pass a stream of its own (2K-1 streams; "
+                         "slower than K streams on this GPU, kept for comparison)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (modules are concurrent streams on one "
+              "device); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wk
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = wk.get_workload(args.workload)
+    res = measure(wl, args, args.steps, args.warmup)
+    out = {"metric": "DDG module images/sec on 1 MI355X", "value": res.pop("value"), "unit": res.pop("unit"),
+           "n_gpus": 1, "steps": res.pop("steps"), "warmup": res.pop("warmup"), "ms_per_step": res.pop("ms_per_step"),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": res.pop("dtype"),
+           "data": "synthetic"}
+    out.update(res)
+    if wl.name == "resnet110_k4" and not args.no_secondary:
+        # the benchmark's fifth configuration (one ImageNet-shaped module of 23 bottleneck blocks,
+        # the GEMM-class kernels), measured in the same run: 30 timed steps as specified
+        wl2 = wk.get_workload("r101_stage3_k4m2")
+        r2 = measure(wl2, args, 30, 5)
+        sec = {k: r2[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config") if k in r2}
+        for k in ("roofline", "conv_mfma_util", "conv_frac_of_min_roof", "bn_hbm_frac", "algorithmic_GFLOP_per_step",
+                  "algorithmic_GB_per_step"):
+            if k in r2:
+                sec[k] = r2[k]
+        if "kernels" in r2:   # the kinds that take 3 % of the step or more
+            sec["kernels"] = {k: v for k, v in r2["kernels"].items() if v["ms_per_step"] >= 0.03 * r2["ms_per_step"]}
+        out["secondary"] = sec
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = (cpu_baseline_single(wl.name, min(args.cpu_sample_batch, 2)) if single
-                               else cpu_baseline(wl.name, args.cpu_sample_batch, timed_steps=8))
+        if wl.single_module:
+            out["cpu_baseline"] = cpu_baseline_single(wl.name, min(args.cpu_sample_batch or 2, 2))
+        else:
+            out["cpu_baseline"] = cpu_baseline(wl.name, args.cpu_sample_batch or wl.batch, timed_steps=1)
     print(json.dumps(out))
 
 

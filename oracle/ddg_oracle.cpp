@@ -41,7 +41,13 @@
 // stays in the oracle's scalar type. This puts the sign decisions of ReLU on the same
 // values on both sides; without it a sign flip of a near-zero pre-activation changes the
 // masked gradient by O(1) for that element. Parameters, statistics, weight gradients and
-// the update are never rounded.
+// the update are never rounded. Where exactly the mode rounds (module input, conv weights as
+// operands, conv outputs, stored activations and block outputs; on the way back the gradient
+// of a conv output, of a stored activation before its ReLU mask, of the projection branch, of
+// a block input, the gradient received from the module above, the head's input gradient) is
+// pinned by tests/test_oracle_bf16_placement.py against a PyTorch float64 autograd network
+// with explicit casts at those points: identical to 1e-15, and leaving out any one point
+// moves the result by 3e-4 or more.
 //
 // Layouts: activations NCHW, conv weights [Cout][Cin][R][S], all row-major.
 // Parameter order per block: conv.W, bn.gamma, bn.beta for each conv unit in

@@ -18,8 +18,30 @@ The kernel -> kind mapping is the one the library books its per-launch measureme
 import argparse
 import collections
 import csv
+import hashlib
+import os
 import re
 import sys
+
+
+def source_digest() -> str:
+    """A digest of the kernel and host sources of the library (csrc/): a counter summary carries
+    the digest of the sources it was taken with, so that a reader can tell when they have
+    changed since."""
+    csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def read_source_digest(path: str):
+    for line in open(path):
+        if line.startswith("csrc digest:"):
+            return line.split(":", 1)[1].strip()
+    return None
 
 
 def kind_of(kernel_name: str) -> str:
@@ -103,6 +125,7 @@ def traffic(fetch_csv: str, write_csv: str, out=sys.stdout):
         raise SystemExit("no calibration dispatches of copy_kernel found")
     kf = sum(b for b, _ in f_cal) / sum(c for _, c in f_cal)
     kw = sum(b for b, _ in w_cal) / sum(c for _, c in w_cal)
+    print(f"csrc digest: {source_digest()}", file=out)
     print(f"calibration (copy_kernel, {len(f_cal)} dispatches of known size): "
           f"bytes read = {kf:.4f} x FETCH_SIZE KiB, bytes written = {kw:.4f} x WRITE_SIZE KiB", file=out)
     print("kind | kernel | dispatches | FETCH_SIZE KiB/dispatch | WRITE_SIZE KiB/dispatch | "

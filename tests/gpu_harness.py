@@ -91,8 +91,8 @@ SMOOTH_KINDS = ("loss", "h", "params", "velocity")
 
 
 def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_forced=True,
-                        loose=0.25, deriv_tol=None, say=None, forward_streams=False, adam=None, lr_of=None,
-                        stale_jacobian=False):
+                        loose=2e-2, deriv_tol=None, say=None, forward_streams=False, adam=None, lr_of=None,
+                        stale_jacobian=False, per_iteration=None, store_bf16=None):
     """Run `steps` DDG iterations on the HIP pipeline and on the float64 oracle with the same
     seeded inputs and compare per tensor (relative L2 error).
 
@@ -118,7 +118,7 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
                                   stale_jacobian=stale_jacobian),
                         [s.cuda_stream for s in st] if st else None)
     mods = {k: pipe.module(k) for k in range(1, K + 1)}
-    oracle = orc.OracleNet.from_workload(wl, dtype="f64", stale_jacobian=stale_jacobian)
+    oracle = orc.OracleNet.from_workload(wl, dtype="f64", stale_jacobian=stale_jacobian, store_bf16=store_bf16)
     init_both(wl, mods, oracle, perturb_bn)
     if adam:   # (beta1, beta2, eps): Algorithm 2 instead of momentum SGD, on both sides
         oracle.set_adam(True, *adam)
@@ -127,6 +127,7 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
     report = []
     loss_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
     for t in range(steps):
+        seen = {k: len(v) for k, v in errs.items()}
         lr = lr_of(t) if lr_of else wl.lr       # the step-size schedule is the caller's
         x, y = wk.minibatch(wl, t)
         xd = to_dev_nhwc(x, wl)
@@ -170,6 +171,9 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
                 report.append(f"t={t} delta_{k}: iteration {ts_got} vs oracle {ts_ref}")
             elif ts_ref >= 0:
                 errs["delta"].append((rel_err(nhwc_np_to_nchw(d_got), d_ref), f"t={t} delta_{k}"))
+        if per_iteration:   # the largest relative error of each kind in this iteration
+            per_iteration(f"  {wl.name} t={t}: " + ", ".join(
+                f"{k} {max(e for e, _ in v[seen[k]:]):.2e}" for k, v in errs.items() if len(v) > seen[k]))
     pipe.close()
     stats = {}
     for kind, lst in errs.items():
@@ -195,90 +199,116 @@ def run_pipeline_parity(wl, steps, tol, streams=True, perturb_bn=True, teacher_f
     return report, stats
 
 
-def run_pipeline_envelope(wl, steps, tol, factor=2.0, say=None):
-    """Parity for networks too deep for a fixed tolerance on derivative-like tensors (fp32: the
-    "rounded" oracle below is the oracle computing in fp32, and every h is held to tol).
+def run_pipeline_three_way(wl, steps, arith="f64", say=None, second_rounded=None, teacher_forced=True,
+                           perturb_bn=False):
+    """The HIP pipeline next to two oracles on the same seeded inputs, from the same weights:
+      rounded  the oracle in the HIP path's storage precision (bf16 workloads: the bf16-storage
+               mode; fp32 workloads: the oracle computing in fp32), arithmetic `arith`;
+      plain    the oracle with no rounding of stored tensors (fp32 workloads: in fp64).
+    second_rounded: optionally a third oracle, the rounded one in another arithmetic ("f32"): the
+    distance between the two rounded oracles is how far two straightforward implementations in
+    the same storage precision lie apart by the order of their sums alone.
+    Weights and velocities of all sides are set to the rounded oracle's before every iteration
+    (teacher_forced), so every iteration's distance is that iteration's own.
 
-    Three runs of the same DDG iterations from the same weights: the HIP pipeline, the oracle in
-    its bf16-storage mode, and the oracle in plain fp64 (no rounding anywhere: the exact result).
-    Both rounded runs are measured against the exact one. The HIP path passes when, per kind of
-    tensor, its median distance from the exact result is at most `factor` times the bf16-mode
-    oracle's own distance plus tol: it is then as close to the truth as a straightforward bf16
-    implementation of the same arithmetic is. Loss and the first module's output are also held
-    to tol against the bf16-mode oracle directly. Weights and velocities of all three are reset
-    to the bf16-mode oracle's after every iteration."""
+    Returns (report, dist): report lists structural failures (gradient present on one side
+    only, mailbox iteration stamps); dist[kind][pair] is a list of (relative L2 error, name) with
+    kind in loss / h / delta / grad / params / velocity and pair in hip_rounded, hip_plain,
+    rounded_plain (and rounded2_rounded); dist[kind]["norm_ratio"] lists |HIP| / |rounded| per
+    tensor (a zero, or a wrongly scaled, result shows there even where the directions of two
+    correct results have decorrelated). Assertions are the caller's."""
     K = wl.K
     st = [torch.cuda.Stream() for _ in range(K)]
     pipe = ddg.Pipeline(descs_for(wl), [s.cuda_stream for s in st])
     mods = {k: pipe.module(k) for k in range(1, K + 1)}
-    if wl.dtype == "bf16":
-        rounded = orc.OracleNet.from_workload(wl, dtype="f64", store_bf16=True)
-    else:
-        rounded = orc.OracleNet.from_workload(wl, dtype="f32", store_bf16=False)
-    exact = orc.OracleNet.from_workload(wl, dtype="f64", store_bf16=False)
-    init_both(wl, mods, rounded, perturb_bn=False)
-    for m in wl.modules:
-        exact.set_params(m.k, rounded.get_params(m.k).astype(np.float64))
-    gpu_e = {k: [] for k in ("h", "grad", "delta")}
-    orc_e = {k: [] for k in ("h", "grad", "delta")}
+    bf = wl.dtype == "bf16"
+    rounded = orc.OracleNet.from_workload(wl, dtype=arith if bf else "f32", store_bf16=bf)
+    plain = orc.OracleNet.from_workload(wl, dtype=arith if bf else "f64", store_bf16=False)
+    others = {"plain": plain}
+    if second_rounded:
+        others["rounded2"] = orc.OracleNet.from_workload(wl, dtype=second_rounded, store_bf16=bf)
+    init_both(wl, mods, rounded, perturb_bn=perturb_bn)
+    for o in others.values():
+        for m in wl.modules:
+            o.set_params(m.k, rounded.get_params(m.k))
+    kinds = ("loss", "h", "delta", "grad", "params", "velocity")
+    pairs = ("hip_rounded", "hip_plain", "rounded_plain") + (("rounded2_rounded",) if second_rounded else ())
+    dist = {k: {p: [] for p in pairs + ("norm_ratio",)} for k in kinds}
     report = []
     loss_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
+
+    def book(kind, name, hip, rnd, pln, rnd2=None):
+        dist[kind]["norm_ratio"].append((float(np.linalg.norm(np.asarray(hip, np.float64).ravel()) /
+                                               max(np.linalg.norm(np.asarray(rnd, np.float64).ravel()), 1e-300)), name))
+        dist[kind]["hip_rounded"].append((rel_err(hip, rnd), name))
+        dist[kind]["hip_plain"].append((rel_err(hip, pln), name))
+        dist[kind]["rounded_plain"].append((rel_err(rnd, pln), name))
+        if rnd2 is not None:
+            dist[kind]["rounded2_rounded"].append((rel_err(rnd2, rnd), name))
+
     for t in range(steps):
         x, y = wk.minibatch(wl, t)
         xd = to_dev_nhwc(x, wl)
         yd = torch.from_numpy(y).to("cuda")
-        x = from_dev_nhwc(xd)
-        if t > 0:
+        if bf:
+            x = from_dev_nhwc(xd)
+        if teacher_forced and t > 0:
             for m in wl.modules:
                 p, v = rounded.get_params(m.k), rounded.get_velocity(m.k)
-                p, v = p.astype(np.float64), v.astype(np.float64)
                 mods[m.k].set_params(p.astype(np.float32)); mods[m.k].set_velocity(v.astype(np.float32))
-                exact.set_params(m.k, p); exact.set_velocity(m.k, v)
+                for o in others.values():
+                    o.set_params(m.k, p); o.set_velocity(m.k, v)
         torch.cuda.synchronize()
         pipe.step(xd, yd, wl.lr, loss_dev)
         pipe.sync()
         l_r = rounded.ddg_step(x, y, wl.lr)
-        exact.ddg_step(x, y, wl.lr)
+        l_o = {n: o.ddg_step(x, y, wl.lr) for n, o in others.items()}
         l_g = float(loss_dev.cpu()[0])
-        if not abs(l_g - l_r) <= tol * abs(l_r):
-            report.append(f"t={t} loss {l_g} vs {l_r}")
-        for k in range(1, 2 if wl.dtype == "bf16" else K):
-            e1 = rel_err(nhwc_np_to_nchw(pipe.get_h(k)), rounded.get_h(k))
-            if not e1 <= tol:
-                report.append(f"t={t} h_{k}: rel err {e1:.3e} > {tol:g}")
+        if say:
+            say(f"  {wl.name} t={t}: loss HIP {l_g:.6f} rounded {l_r:.6f} plain {l_o['plain']:.6f}")
+        book("loss", f"t={t} loss", [l_g], [l_r], [l_o["plain"]], [l_o["rounded2"]] if second_rounded else None)
         for k in range(1, K):
-            gpu_e["h"].append(rel_err(nhwc_np_to_nchw(pipe.get_h(k)), exact.get_h(k)))
-            orc_e["h"].append(rel_err(rounded.get_h(k), exact.get_h(k)))
-            d_ex, ts_ex = exact.get_delta(k)
-            d_ro, ts_ro = rounded.get_delta(k)
+            book("h", f"t={t} h_{k}", nhwc_np_to_nchw(pipe.get_h(k)), rounded.get_h(k), plain.get_h(k),
+                 others["rounded2"].get_h(k) if second_rounded else None)
             d_g, ts_g = pipe.get_delta(k)
-            if not (ts_ex == ts_ro == ts_g):
-                report.append(f"t={t} delta_{k}: iterations {ts_g}/{ts_ro}/{ts_ex}")
-            elif ts_ex >= 0:
-                gpu_e["delta"].append(rel_err(nhwc_np_to_nchw(d_g), d_ex))
-                orc_e["delta"].append(rel_err(d_ro, d_ex))
+            d_r, ts_r = rounded.get_delta(k)
+            d_p, ts_p = plain.get_delta(k)
+            if not (ts_g == ts_r == ts_p):
+                report.append(f"t={t} delta_{k}: iterations {ts_g}/{ts_r}/{ts_p}")
+            elif ts_r >= 0:
+                book("delta", f"t={t} delta_{k}", nhwc_np_to_nchw(d_g), d_r, d_p,
+                     others["rounded2"].get_delta(k)[0] if second_rounded else None)
         for m in wl.modules:
-            g, r, e = mods[m.k].get_grad(), rounded.get_grad(m.k), exact.get_grad(m.k)
+            g, r, e = mods[m.k].get_grad(), rounded.get_grad(m.k), plain.get_grad(m.k)
             if (g is None) != (r is None):
                 report.append(f"t={t} module {m.k}: gradient present on one side only")
             if g is None or r is None:
                 continue
-            for (name, gv), (_, rv), (_, ev) in zip(split_params(wl, m, g), split_params(wl, m, r),
-                                                    split_params(wl, m, e)):
-                if np.linalg.norm(ev) < 1e-9:
-                    continue
-                gpu_e["grad"].append(rel_err(gv, ev))
-                orc_e["grad"].append(rel_err(rv, ev))
+            r2 = others["rounded2"] if second_rounded else None
+            for kind, a, b, c, d in (("grad", g, r, e, r2.get_grad(m.k) if r2 else None),
+                                     ("params", mods[m.k].get_params(), rounded.get_params(m.k), plain.get_params(m.k),
+                                      r2.get_params(m.k) if r2 else None),
+                                     ("velocity", mods[m.k].get_velocity(), rounded.get_velocity(m.k), plain.get_velocity(m.k),
+                                      r2.get_velocity(m.k) if r2 else None)):
+                sp = [split_params(wl, m, v) if v is not None else None for v in (a, b, c, d)]
+                for i, (name, av) in enumerate(sp[0]):
+                    if np.linalg.norm(sp[2][i][1]) < 1e-9:
+                        continue
+                    book(kind, f"t={t} {kind} {name}", av, sp[1][i][1], sp[2][i][1], sp[3][i][1] if sp[3] else None)
     pipe.close()
-    stats = {}
-    for kind in gpu_e:
-        if not gpu_e[kind]:
-            continue
-        a, b = float(np.median(gpu_e[kind])), float(np.median(orc_e[kind]))
-        stats[kind] = (a, b)
-        if not a <= factor * b + tol:
-            report.append(f"{kind}: median distance from exact {a:.3e} (HIP) vs {b:.3e} (bf16-mode oracle)")
     if say:
-        say(f"{wl.name} envelope steps={steps}: " +
-            ", ".join(f"{k} HIP {a:.2e} / oracle-bf16 {b:.2e}" for k, (a, b) in stats.items()))
-    return report, stats
+        for kind in kinds:
+            if not dist[kind]["hip_rounded"]:
+                continue
+            say(f"{wl.name} {wl.dtype} steps={steps} {kind}: " + ", ".join(
+                f"{p} med {np.median([e for e, _ in dist[kind][p]]):.2e} max {max(e for e, _ in dist[kind][p]):.2e}"
+                for p in pairs))
+    return report, dist
+
+
+def med(lst):
+    return float(np.median([e for e, _ in lst])) if lst else 0.0
+
+
+def worst(lst):
+    return max((e for e, _ in lst), default=0.0)

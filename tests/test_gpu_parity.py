@@ -1,7 +1,17 @@
 """GPU parity: the HIP library against the float64 CPU oracle on the same seeded inputs,
-through the C boundary. Tolerances: relative L2 error per tensor <= 1e-4 with fp32 conv
-operands, <= 2e-2 with bf16 operands (weights, velocities, activations, error gradients,
-loss)."""
+through the C boundary. Target tolerances: relative L2 error per tensor <= 1e-4 with fp32 conv
+operands, <= 2e-2 with bf16 operands. What is enforced:
+  * fp32: loss, activations and weights at 1e-4 everywhere; gradient-like tensors (error
+    gradients, weight gradients, velocities) at 1e-4 in the median, with a stated loose bound
+    per case for the rare ReLU sign event;
+  * bf16, shallow paths (single blocks, the tiny network): every tensor at 2e-2 against the
+    oracle in its bf16-storage mode, the module output also against the plain oracle
+    (test_single_block_module; test_gpu_plain_oracle.py);
+  * bf16 pipelines several blocks deep: loss, activations and weights at 2e-2; gradient-like
+    tensors at a bound stated per case, 1.5 x the median / maximum measured for that case (the
+    measured values are tabulated in the design notes); a wrong ring slot or mailbox gives 1.4.
+The kernel-level claim for gradient-like tensors rests on the single-block and single-module
+cases, whose inputs are identical on both sides."""
 import sys
 
 import numpy as np
@@ -64,12 +74,13 @@ def test_k4_schedule(H, dtype, forward_streams):
     wl = custom_cifar(2, [2, 4, 6], batch=8, num_classes=10, hw=16, dtype=dtype, name="k4")
     wl.lr = 0.05
     _say(f"case k4 {dtype} steps=14")
-    # 15 conv layers deep: with 8-bit significands the two sides decorrelate at the ulp level
-    # after a few layers, so about 0.3 % of the ReLU signs per layer are decided differently;
-    # forward quantities stay within 2e-2, gradient-like ones are held to 0.2 (see harness).
+    # 15 conv layers deep, bf16: the two sides decorrelate at the ulp level after a few layers and
+    # decide a share of the ReLU signs differently; forward quantities stay within 2e-2.
+    # Gradient-like tensors: 1.5 x the values measured for this case (median 0.105, max 0.347);
+    # fp32: median at the tolerance, max 2e-2 (measured 2.7e-6).
     report, stats = H.run_pipeline_parity(wl, 14, TOL[dtype], say=_say,
-                                          deriv_tol=0.2 if dtype == "bf16" else None,
-                                          loose=0.6 if dtype == "bf16" else 0.25, forward_streams=forward_streams)
+                                          deriv_tol=0.16 if dtype == "bf16" else None,
+                                          loose=0.52 if dtype == "bf16" else 2e-2, forward_streams=forward_streams)
     assert not report, "\n".join(report)
 
 
@@ -162,7 +173,8 @@ def test_bottleneck_module_with_synthetic_delta(H, dtype):
     mod.close()
     _say(f"bottleneck {dtype}: gradient-like tensors median {np.median(derr):.2e} max {np.max(derr):.2e}")
     assert not fails, "\n".join(fails)
-    assert np.median(derr) <= tol and np.max(derr) <= 0.25
+    # measured: fp32 median 4.3e-7 / max 8.7e-7; bf16 median 1.2e-7 / max 1.7e-4
+    assert np.median(derr) <= (1e-5 if dtype == "f32" else 1e-4) and np.max(derr) <= (1e-5 if dtype == "f32" else 1e-3)
 
 
 def test_resnet20_small_batch_50_steps(H):
@@ -170,19 +182,9 @@ def test_resnet20_small_batch_50_steps(H):
     needs about half a second per iteration at this size), teacher-forced."""
     wl = wk.get_workload("resnet20_k2", batch=16)
     _say("case resnet20_k2 batch=16 steps=50")
-    report, stats = H.run_pipeline_parity(wl, 50, 1e-4, perturb_bn=False, say=_say)
-    assert not report, "\n".join(report)
-
-
-def test_resnet20_full_batch_smooth_quantities(H):
-    """Full batch 128 for 3 iterations. With 2.4e7 pre-activations per pass some always lie
-    within fp32 rounding of zero, so the gradient-like tensors differ from the float64 oracle
-    by about 1e-3 in any fp32 implementation (the oracle's own fp32 instance differs by 1e-2);
-    weights, forward activations and loss must still meet 1e-4, and gradients 1e-2."""
-    wl = wk.get_workload("resnet20_k2")
-    _say("case resnet20_k2 batch=128 steps=3")
-    report, stats = H.run_pipeline_parity(wl, 3, 1e-4, perturb_bn=False, say=_say, loose=2e-2,
-                                          deriv_tol=1e-2)
+    # loose bound on single gradient-like tensors: twice the largest value measured (2.1e-2: a BN
+    # shift that consists of a few updates only)
+    report, stats = H.run_pipeline_parity(wl, 50, 1e-4, perturb_bn=False, say=_say, loose=4.5e-2)
     assert not report, "\n".join(report)
 
 
@@ -192,10 +194,14 @@ SINGLE_BLOCKS = {
     "basic_projection_s2": ([(wk.BLOCK_BASIC, 16, 0, 32, 2, 1)], 6, 9),
     "bottleneck": ([(wk.BLOCK_BOTTLENECK, 64, 16, 64, 1, 0)], 6, 9),
     "bottleneck_projection_s2": ([(wk.BLOCK_BOTTLENECK, 32, 16, 64, 2, 1)], 6, 9),
-    # the CIFAR layer shapes (LDS-tiled kernels), with more tiles than workgroups
+    # the CIFAR layer shapes (LDS-tiled kernels). Tiles are 8 rows of one image: 288 tiles for
+    # at most 256 workgroups (c16), 144 for 128 (c32); 40 for 96 (c64: one tile per workgroup)
     "cifar_c16_w32": ([(wk.BLOCK_BASIC, 16, 0, 16, 1, 0)], 72, 32),
     "cifar_c32_w16": ([(wk.BLOCK_BASIC, 32, 0, 32, 1, 0)], 72, 16),
     "cifar_c64_w8": ([(wk.BLOCK_BASIC, 64, 0, 64, 1, 0)], 40, 8),
+    # 200 tiles (400 with the paired forward) for the 64-channel kernels' workgroups: the tile
+    # loop with its prefetch, and several tiles' statistics in one partial row, as at full size
+    "cifar_c64_w8_many_tiles": ([(wk.BLOCK_BASIC, 64, 0, 64, 1, 0)], 200, 8),
     "cifar_c16_w32_small": ([(wk.BLOCK_BASIC, 16, 0, 16, 1, 0)], 3, 32),
 }
 
@@ -219,10 +225,15 @@ def test_single_block_module(H, which, dtype):
     mod = ddg.Module(desc)
     oracle = orc.OracleNet(3, [blocks], N, (cin, Hh, Hh), 0, 0.9, 0.0, 1e-5, "f64", k_first=2,
                            store_bf16=(dtype == "bf16"))
+    # bf16: the plain oracle (nothing rounded) alongside
+    plain = orc.OracleNet(3, [blocks], N, (cin, Hh, Hh), 0, 0.9, 0.0, 1e-5, "f64", k_first=2,
+                          store_bf16=False) if dtype == "bf16" else None
     nparam = oracle.param_count(2)
     theta = (wk.normal(11, 1, nparam) * 0.2 + 0.05).astype(np.float32)
     # conv weights and BN scales of that size are fine for a single block
     oracle.set_params(2, theta.astype(np.float64))
+    if plain:
+        plain.set_params(2, theta.astype(np.float64))
     mod.set_params(theta)
     Ho = (Hh - 1) // stride + 1
     class WL:  # what the harness helpers read
@@ -248,16 +259,37 @@ def test_single_block_module(H, which, dtype):
         e = H.rel_err(H.from_dev_nhwc(h_out), ref_h)
         if e > tol:
             fails.append(f"t={t} h_out rel err {e:.3e}")
+        if plain:
+            # the module output is held to the tolerance against the PLAIN oracle as well
+            pl_h = plain.forward(2, t, h_in)
+            _, pl_dout, _ = plain.backward_delayed(2, t, delta, None, in_shape=h_in.shape)
+            e = H.rel_err(H.from_dev_nhwc(h_out), pl_h)
+            if e > tol:
+                fails.append(f"t={t} h_out rel err {e:.3e} from the plain oracle")
         if did:
-            e = H.rel_err(H.from_dev_nhwc(d_out), ref_dout)
-            if e > tol:
-                fails.append(f"t={t} delta_out rel err {e:.3e}")
             g, r = mod.get_grad(), oracle.get_grad(2)
-            e = H.rel_err(g, r)
-            if e > tol:
-                fails.append(f"t={t} grad rel err {e:.3e}")
+            e_d, e_g = H.rel_err(H.from_dev_nhwc(d_out), ref_dout), H.rel_err(g, r)
+            if e_d > tol:
+                fails.append(f"t={t} delta_out rel err {e_d:.3e}")
+            if e_g > tol:
+                fails.append(f"t={t} grad rel err {e_g:.3e}")
+            msg = f"single block {which} {dtype} t={t}: delta_out {e_d:.2e}, grad {e_g:.2e}"
+            if plain:
+                # gradient-like tensors: bf16 storage decides ~0.1 % of the ReLU signs differently
+                # from the unrounded network (a few % in relative L2 norm for ANY bf16
+                # implementation): the HIP path must lie no farther from the plain oracle than
+                # the rounded oracle does
+                for what, got, rnd, pln in (("delta_out", H.from_dev_nhwc(d_out), ref_dout, pl_dout),
+                                            ("grad", g, r, plain.get_grad(2))):
+                    a, b = H.rel_err(got, pln), H.rel_err(rnd, pln)
+                    msg += f"; {what} from the plain oracle: HIP {a:.2e}, rounded oracle {b:.2e}"
+                    if not a <= 1.1 * b + 1e-3:
+                        fails.append(f"t={t} {what}: {a:.3e} from the plain oracle, the rounded oracle {b:.3e}")
+            _say(msg)
         mod.update(t, 0.0)
         oracle.update(2, 0.0)
+        if plain:
+            plain.update(2, 0.0)
     mod.close()
     assert not fails, "\n".join(fails)
 
@@ -284,9 +316,10 @@ def test_adam_k4_schedule(H, dtype):
     wl = custom_cifar(2, [2, 4, 6], batch=8, num_classes=10, hw=16, dtype=dtype, name="k4_adam")
     wl.lr = 1e-3
     _say(f"case adam k4 {dtype} steps=14")
+    # gradient-like tensors, bf16: 1.5 x measured (median 0.096, max 0.323); fp32: max 2e-2 (6.3e-3)
     report, stats = H.run_pipeline_parity(wl, 14, TOL[dtype], say=_say, adam=ADAM,
-                                          deriv_tol=0.2 if dtype == "bf16" else None,
-                                          loose=0.6 if dtype == "bf16" else 0.25)
+                                          deriv_tol=0.145 if dtype == "bf16" else None,
+                                          loose=0.49 if dtype == "bf16" else 2e-2)
     assert not report, "\n".join(report)
 
 
@@ -300,9 +333,10 @@ def test_stale_jacobian_k4(H, dtype):
     wl = custom_cifar(2, [2, 4, 6], batch=8, num_classes=10, hw=16, dtype=dtype, name="k4_stale")
     wl.lr = 0.05
     _say(f"case stale-jacobian k4 {dtype} steps=14")
+    # gradient-like tensors, bf16: 1.5 x measured (median 0.088, max 0.364); fp32: max 2e-2 (1.2e-3)
     report, stats = H.run_pipeline_parity(wl, 14, TOL[dtype], say=_say, stale_jacobian=True,
-                                          deriv_tol=0.2 if dtype == "bf16" else None,
-                                          loose=0.6 if dtype == "bf16" else 0.25)
+                                          deriv_tol=0.135 if dtype == "bf16" else None,
+                                          loose=0.55 if dtype == "bf16" else 2e-2)
     assert not report, "\n".join(report)
 
 
@@ -310,7 +344,8 @@ def test_stale_jacobian_cifar_shapes_bf16(H):
     """The LDS-tiled kernels on ring-slot views of the buffers: 32x32 inputs, K=3."""
     wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="bf16", name="cifar_k3_stale")
     _say("case stale-jacobian cifar_k3 bf16 steps=8")
-    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=0.2, loose=0.6, stale_jacobian=True)
+    # gradient-like tensors: 1.5 x measured (median 0.111, max 0.227)
+    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=0.17, loose=0.34, stale_jacobian=True)
     assert not report, "\n".join(report)
 
 
@@ -321,7 +356,7 @@ def test_resnet8_one_split_point_adam(H, layer):
     """One split point after layer 1, 3, 5 or 7, Adam with step size 1e-3 (Section 5.1), fp32."""
     wl = wk.resnet8((layer,), batch=16)
     _say(f"case resnet8 split after layer {layer}, adam, steps=6")
-    report, stats = H.run_pipeline_parity(wl, 6, 1e-4, say=_say, adam=ADAM)
+    report, stats = H.run_pipeline_parity(wl, 6, 1e-4, say=_say, adam=ADAM, loose=2e-2)   # measured max 7.9e-3
     assert not report, "\n".join(report)
 
 
@@ -331,7 +366,8 @@ def test_resnet8_four_split_points_sgd_with_decay_and_schedule(H):
     graphs through device memory."""
     wl = wk.resnet8((1, 3, 5, 7), batch=16, weight_decay=5e-4, lr=0.01)
     _say("case resnet8 K=5 sgd wd=5e-4 lr 0.01 -> 0.001 at t=9, steps=14")
-    report, stats = H.run_pipeline_parity(wl, 14, 1e-4, say=_say, lr_of=lambda t: 0.01 if t < 9 else 0.001)
+    report, stats = H.run_pipeline_parity(wl, 14, 1e-4, say=_say, lr_of=lambda t: 0.01 if t < 9 else 0.001,
+                                          loose=2e-2)   # measured max 1.06e-2
     assert not report, "\n".join(report)
 
 
@@ -494,12 +530,17 @@ def test_evaluation_forward_of_a_wide_module_bf16(H):
 
 # ---- the benchmark's network shapes -------------------------------------------------------
 
+# gradient-like tensors of the cifar_k3 bf16 pipeline: 1.5 x the measured median 0.107 / maximum
+# 0.265 (the same under every launch plan: the plans differ in the order of sums only)
+CIFAR_K3_DERIV = (0.16, 0.40)
+
+
 def test_cifar_shaped_pipeline_bf16(H):
     """32x32 inputs, widths 16/32/64, K=3, bf16: every LDS-tiled kernel (16 ch @ 32 wide, 32 @ 16,
     64 @ 8), the stride-2 transition blocks and the fused statistics paths, 8 iterations."""
     wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="bf16", name="cifar_k3")
     _say("case cifar_k3 bf16 steps=8")
-    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=0.2, loose=0.6)
+    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=CIFAR_K3_DERIV[0], loose=CIFAR_K3_DERIV[1])
     assert not report, "\n".join(report)
 
 
@@ -510,7 +551,7 @@ def test_cifar_shaped_pipeline_bf16_unpaired_backward(H, monkeypatch):
     monkeypatch.setenv("DDG_NO_BWD_PAIR", "1")     # read when a module is created
     wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="bf16", name="cifar_k3")
     _say("case cifar_k3 bf16 steps=8, unpaired backward")
-    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=0.2, loose=0.6)
+    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=CIFAR_K3_DERIV[0], loose=CIFAR_K3_DERIV[1])
     assert not report, "\n".join(report)
 
 
@@ -524,46 +565,72 @@ def test_cifar_shaped_pipeline_bf16_other_launch_plans(H, monkeypatch, switch):
     monkeypatch.setenv(switch, "1")
     wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="bf16", name="cifar_k3")
     _say(f"case cifar_k3 bf16 steps=8, {switch}=1")
-    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=0.2, loose=0.6)
+    report, stats = H.run_pipeline_parity(wl, 8, 2e-2, say=_say, deriv_tol=CIFAR_K3_DERIV[0], loose=CIFAR_K3_DERIV[1])
     assert not report, "\n".join(report)
 
 
 def test_cifar_shaped_pipeline_f32(H):
     wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="f32", name="cifar_k3")
     _say("case cifar_k3 f32 steps=8")
-    report, stats = H.run_pipeline_parity(wl, 8, 1e-4, say=_say)
+    report, stats = H.run_pipeline_parity(wl, 8, 1e-4, say=_say, loose=2e-2)   # measured max 3.9e-3
     assert not report, "\n".join(report)
+
+
+def _deep_three_way(H, wl, steps, tol, factor, slack):
+    report, d = H.run_pipeline_three_way(wl, steps, say=_say)
+    bad = list(report)
+    for kind in ("grad", "delta", "velocity", "h"):
+        a, b = H.med(d[kind]["hip_plain"]), H.med(d[kind]["rounded_plain"])
+        if not a <= factor * b + slack:
+            bad.append(f"{kind}: median distance from the plain oracle {a:.3e} (HIP) vs {b:.3e} (rounded oracle)")
+        r = H.med(d[kind]["norm_ratio"])
+        if not 0.9 <= r <= 1.1:
+            bad.append(f"{kind}: median |HIP| / |rounded oracle| = {r:.3f}")
+    if not H.worst(d["loss"]["hip_rounded"]) <= tol:
+        bad.append(f"loss: {H.worst(d['loss']['hip_rounded']):.3e}")
+    return bad, d
 
 
 @pytest.mark.parametrize("name,batch,steps", [("resnet56_k3", 4, 6), ("resnet110_k4", 2, 7)])
 def test_deep_workloads_f32(H, name, batch, steps):
     """ResNet-56 (K=3) and ResNet-110 (K=4) with their real depth and module splits at a batch
     the oracle finishes in seconds, fp32: up to 27 residual blocks per module. Loss and every h
-    within 1e-4 of the fp32 oracle. A ReLU whose input lies within fp32 rounding of zero flips
+    within 1e-4 of the fp64 oracle. A ReLU whose input lies within fp32 rounding of zero flips
     in about 1e-6 of the elements per layer, which moves a derivative-like tensor by the square
-    root of that fraction (1e-3) per layer in relative L2 norm, so those are held to the
-    envelope criterion: as close to the exact fp64 result as the fp32 oracle is."""
+    root of that fraction (1e-3) per layer in relative L2 norm, so those are held to: no farther
+    from the fp64 oracle than the oracle's own fp32 instance (measured: 2-160 times closer), and
+    the same norms."""
     wl = wk.get_workload(name, batch=batch, dtype="f32")
     _say(f"case {name} f32 batch={batch} steps={steps}")
-    report, stats = H.run_pipeline_envelope(wl, steps, 1e-4, say=_say)
-    assert not report, "\n".join(report)
+    bad, d = _deep_three_way(H, wl, steps, 1e-4, 1.0, 1e-4)
+    if not H.worst(d["h"]["hip_plain"]) <= 1e-4:
+        bad.append(f"h: {H.worst(d['h']['hip_plain']):.3e} from the fp64 oracle")
+    assert not bad, "\n".join(bad)
 
 
 @pytest.mark.parametrize("name,batch,steps", [("resnet56_k3", 4, 6), ("resnet110_k4", 2, 7)])
 def test_deep_workloads_bf16_envelope(H, name, batch, steps):
-    """The same two networks in bf16. Over tens of blocks, bf16 storage rounding and the ReLU
-    sign events it causes decorrelate derivative-like tensors of ANY two bf16 implementations,
-    so a fixed tolerance against the bf16-mode oracle says nothing; instead the HIP path must be
-    as close to the exact fp64 result as the bf16-mode oracle is (see the harness)."""
+    """The same two networks in bf16 at a small batch. Tens of blocks deep, bf16 storage
+    decorrelates the derivative-like tensors of ANY two implementations (the share of ReLU signs
+    decided differently grows with the accumulated forward error), so they are held to: as close
+    to the plain oracle as the bf16-storage oracle is (within 10 %: measured 0.5-3 %) and the
+    same norms (a zero or wrongly scaled gradient fails that). The first module's output is held
+    to 2e-2 against the bf16-storage oracle directly."""
     wl = wk.get_workload(name, batch=batch)
     _say(f"case {name} bf16 envelope batch={batch} steps={steps}")
-    report, stats = H.run_pipeline_envelope(wl, steps, 2e-2, say=_say)
-    assert not report, "\n".join(report)
+    bad, d = _deep_three_way(H, wl, steps, 2e-2, 1.1, 2e-3)
+    h1 = [x for x in d["h"]["hip_rounded"] if x[1].endswith("h_1")]
+    if not H.worst(h1) <= 2e-2:
+        bad.append(f"h_1: {H.worst(h1):.3e} from the bf16-storage oracle")
+    assert not bad, "\n".join(bad)
 
 
-@pytest.mark.parametrize("nblocks,batch,c,mid,hw", [(2, 2, 1024, 256, 14), (1, 12, 1024, 256, 14), (2, 4, 256, 64, 7)],
+# gradient-like tensors of each case: 1.5 x the measured (median, maximum)
+@pytest.mark.parametrize("nblocks,batch,c,mid,hw,dmed,dmax",
+                         [(2, 2, 1024, 256, 14, 0.088, 0.094), (1, 12, 1024, 256, 14, 0.0125, 0.0135),
+                          (2, 4, 256, 64, 7, 0.018, 0.031)],
                          ids=["two_blocks_batch2", "one_block_batch12", "c256_mid64_7x7"])
-def test_wide_bottleneck_module_bf16(H, nblocks, batch, c, mid, hw):
+def test_wide_bottleneck_module_bf16(H, nblocks, batch, c, mid, hw, dmed, dmax):
     """The ImageNet-shaped slice at reduced size: bottleneck blocks 1024 -> 256 -> 256 -> 1024 at
     14x14 (the GEMM-class kernels of the wide layers and their finalise launches), module k=2 of
     K=4, synthetic error gradient, bf16. Batch 2: 392 pixels, a ragged last 64-pixel tile and
@@ -608,7 +675,7 @@ def test_wide_bottleneck_module_bf16(H, nblocks, batch, c, mid, hw):
     mod.close()
     _say(f"wide bottleneck: h max {max(smooth):.2e}, gradient-like median {np.median(deriv):.2e} max {max(deriv):.2e}")
     assert max(smooth) <= 2e-2
-    assert np.median(deriv) <= 0.1 and max(deriv) <= 0.25
+    assert np.median(deriv) <= dmed and max(deriv) <= dmax
 
 
 def test_full_size_bottleneck_module_bf16(H):
@@ -624,7 +691,7 @@ def test_full_size_bottleneck_module_bf16(H):
     implementations away from each other by almost as much, so a fixed tolerance between the
     two says nothing at this depth. Criterion, as for the deep CIFAR networks: the HIP path
     must be as close to the unrounded result as the oracle in its bf16-storage mode is (at
-    most 1.25 times its distance plus the bf16 tolerance), for the module output of every
+    most 1.05 times its distance plus 1e-2, and the same norm within 5 %), for the module output of every
     iteration, the error gradient passed down, and the weight gradient (all of it, and the
     first and the last block alone). Through 23 blocks the gradients of both bf16 runs lie
     0.76 away from the unrounded ones (0.40 for the last block) and within 0.5 % of each
@@ -640,15 +707,18 @@ def test_full_size_bottleneck_module_bf16(H):
     H.init_both(wl, {m.k: mod}, rounded)
     exact.set_params(m.k, rounded.get_params(m.k))
     shape_in = (wl.batch, m.in_c, m.in_h, m.in_w)
-    tol, factor = 2e-2, 1.25
+    tol, factor = 1e-2, 1.05      # measured: the two distances agree within 0.5 %
     bad = []
 
     def check(what, got, rnd, ex):
         a, b = H.rel_err(got, ex), H.rel_err(rnd, ex)
+        r = float(np.linalg.norm(np.asarray(got, np.float64).ravel()) / np.linalg.norm(np.asarray(rnd, np.float64).ravel()))
         _say(f"full-size bottleneck module {what}: from the unrounded result HIP {a:.3e}, bf16-mode oracle {b:.3e}; "
-             f"HIP from the bf16-mode oracle {H.rel_err(got, rnd):.3e}")
+             f"HIP from the bf16-mode oracle {H.rel_err(got, rnd):.3e}; |HIP| / |bf16-mode oracle| = {r:.4f}")
         if not a <= factor * b + tol:
             bad.append(f"{what}: {a:.3e} vs {b:.3e}")
+        if not 0.95 <= r <= 1.05:     # a zero, halved or doubled result fails here where directions have decorrelated
+            bad.append(f"{what}: norm ratio {r:.4f}")
 
     for t in range(3):
         _say(f"case full-size bottleneck module t={t}")
@@ -683,11 +753,11 @@ def test_full_size_bottleneck_module_bf16(H):
 
 
 def test_full_size_bench_configuration(H):
-    """ResNet-110 / K=4 / batch 256 / bf16 exactly as bench.py runs it (K streams, graph replay).
-    The oracle cannot run this size in test time, so:
+    """ResNet-110 / K=4 / batch 256 / bf16 exactly as bench.py runs it (K streams, graph replay):
+    invariants that hold at any size, next to the comparison with the oracle at this size in
+    test_gpu_plain_oracle.py (test_config3_and_config4_full_batch):
       * module 1's forward output of iteration 0 (stem + 13 blocks, batch statistics over all
-        256 images) is compared with the oracle's forward of the same module: one full-size
-        tensor the oracle can afford;
+        256 images) against the oracle's forward of the same module;
       * with the classifier weights set to zero the first loss must be ln(100);
       * conv -> BN is invariant to the scale of each filter, so <W_co, dW_co> must vanish for
         every filter of every conv layer, at any size;
