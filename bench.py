@@ -243,10 +243,14 @@ def measure(wl, args, steps, warmup):
             step(it); it += 1
         pipe.sync()
         fam = {}
+        per_module = []      # summed kernel time and launches of each module's stream, per step
         for m in mods:
+            tot_ms, tot_n = 0.0, 0
             for name, (n, tms, nbytes, flops) in m.profile_read().items():
                 a = fam.setdefault(name, [0, 0.0, 0.0, 0.0])
                 a[0] += n; a[1] += tms; a[2] += nbytes; a[3] += flops
+                tot_ms += tms; tot_n += n
+            per_module.append({"kernel_ms_per_step": tot_ms / psteps, "launches_per_step": tot_n / psteps})
             m.profile_enable(False)
         peak_tf = MFMA_PEAK_TFLOPS[wl.dtype]
 
@@ -308,6 +312,7 @@ def measure(wl, args, steps, warmup):
             roof["arithmetic_intensity_flop_per_byte"] = ai
             roof["mfma_frac"] = d["TFLOPs"] / peak_tf
         out["roofline"] = roof
+        out["per_module"] = per_module
         out["kernels"] = kernels
         out["families"] = families
         convs = [k for k in ("conv_fprop", "conv_dgrad", "conv_wgrad", "conv_bwd_pair") if k in families]

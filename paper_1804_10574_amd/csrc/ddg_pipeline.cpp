@@ -194,7 +194,12 @@ ddg_status ddg_pipeline_set_optimizer(ddg_pipeline* p, int kind, float beta1, fl
     const ddg_status st = ddg_set_optimizer(p->mods[k], kind, beta1, beta2, eps);
     if (st != DDG_OK) return st;
   }
-  // graphs captured with the other update kernel must not be replayed
+  // graphs captured with the other update kernel must not be replayed; a replay may still be
+  // running on the streams, so wait for them before the executables go
+  {
+    const ddg_status st = ddg_pipeline_sync(p);
+    if (st != DDG_OK) return st;
+  }
   for (int k = 1; k <= p->K; ++k) {
     for (auto& kv : p->gupd[k]) if (kv.second) (void)hipGraphExecDestroy(kv.second);
     p->gupd[k].clear();

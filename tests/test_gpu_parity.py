@@ -49,6 +49,42 @@ def test_tiny_k2_five_steps_free_running(H):
     assert not report, "\n".join(report)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_k1_is_backpropagation(H, dtype):
+    """The degenerate case K = 1 (Section 3.2: the method reduces to backpropagation): one module
+    with no delay, no ring depth, no mailbox, whose backward pass reuses the tape of its own
+    forward pass. Six free-running iterations against the oracle's PLAIN backpropagation + SGD
+    driver (not its DDG driver), fp32 at 1e-4 on every tensor; bf16 teacher-forced against the
+    DDG driver at 2e-2."""
+    import torch
+    import paper_1804_10574_amd as ddg
+    from oracle import ddg_oracle as orc
+    wl = custom_cifar(1, [], batch=8, num_classes=10, hw=16, dtype=dtype, name="k1")
+    wl.lr = 0.05
+    _say(f"case K=1 {dtype} steps=6")
+    if dtype == "bf16":
+        report, stats = H.run_pipeline_parity(wl, 6, 2e-2, say=_say, deriv_tol=0.1, loose=0.3)
+        assert not report, "\n".join(report)
+        return
+    pipe = ddg.Pipeline(H.descs_for(wl), [torch.cuda.Stream().cuda_stream])
+    mod = pipe.module(1)
+    oracle = orc.OracleNet.from_workload(wl, dtype="f64")
+    H.init_both(wl, {1: mod}, oracle)
+    loss_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
+    for t in range(6):
+        x, y = wk.minibatch(wl, t)
+        xd, yd = H.to_dev_nhwc(x, wl), torch.from_numpy(y).to("cuda")
+        pipe.step(xd, yd, wl.lr, loss_dev)
+        pipe.sync()
+        ref_loss = oracle.bp_step(x, y, wl.lr)              # plain backpropagation + momentum SGD
+        got = float(loss_dev.cpu()[0])
+        assert abs(got - ref_loss) <= 1e-4 * abs(ref_loss), (t, got, ref_loss)
+        assert H.rel_err(mod.get_grad(), oracle.get_grad(1)) <= 1e-4
+        assert H.rel_err(mod.get_params(), oracle.get_params(1)) <= 1e-4
+        assert H.rel_err(mod.get_velocity(), oracle.get_velocity(1)) <= 1e-4
+    pipe.close()
+
+
 def test_tiny_k2_bf16(H):
     wl = wk.get_workload("tiny_k2", dtype="bf16")
     _say("case tiny_k2 bf16 steps=5")
