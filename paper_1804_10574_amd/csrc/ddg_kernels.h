@@ -65,6 +65,8 @@ struct ConvArgs {
   int dtype;
   int grid_x;               // filled by conv_plan
   int mb, nb;               // tile shape chosen by conv_plan
+  int lds32;                // filled by conv_plan: the LDS-staged fp32 kernel runs this layer (an input
+                            // gradient then takes the operand packed with mirrored taps, mode 2)
 };
 void conv_plan(ConvArgs& a);                       // chooses tile shape and grid
 hipError_t conv_launch(const ConvArgs& a, hipStream_t s);
@@ -74,6 +76,15 @@ size_t conv_wpack_elems(int kchannels, int nchannels, int R, int dtype, int* log
 // with mirrored taps (for kernels that run the input-gradient as a plain 3x3 correlation).
 hipError_t pack_weights_launch(const float* W, void* wpack, int Cout, int Cin, int R, int dgrad,
                                int dtype, hipStream_t s);
+
+// LDS-staged fp32 3x3/stride-1 convolution for 16/32/64 channels on 32/16/8-wide maps (forward, or
+// input gradient with an operand packed with mirrored taps). conv_lds32_grid: workgroups (= partial
+// statistics rows) or 0 if the shape is not covered; DDG_NO_LDS32=1 in the environment switches
+// the kernel off (conv_plan then keeps the gather kernel).
+int conv_lds32_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
+hipError_t conv_lds32_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* in_b,
+                             void* out_b, float* stat_partial_b, const void* add_g, const void* add_mask, int N,
+                             int H, int W, int C, int grid, hipStream_t s);
 
 // Gradient w.r.t. the weights: dW[co][ci][r][s] = sum_{n,p,q} dz[n,p,q,co] * x[n,p*st+r-pad,q*st+s-pad,ci].
 // Two launches: per-split partial tiles, then a fixed-order sum into dW (deterministic).

@@ -41,6 +41,7 @@ enum ProfKind {
   // the GEMM-class kernels of the wide layers
   PK_CONV_FPROP_WIDE = PK_BWD_PAIR_T64 + 1, PK_CONV_DGRAD_WIDE, PK_CONV_WGRAD_WIDE,
   PK_CONV_WGRAD_S2,   // the LDS-tiled weight gradient of the stride-2 layers between stages
+  PK_CONV_FPROP_LDS32, PK_CONV_DGRAD_LDS32,   // the LDS-staged fp32 kernel
   PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
   PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_BN_RUNNING, PK_COUNT
 };
@@ -50,6 +51,7 @@ static const char* kProfNames[PK_COUNT] = {
   "conv_wgrad.generic", "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c32_w16", "conv_wgrad.tiled_c64_w8",
   "conv_bwd_pair.tiled_c16_w32", "conv_bwd_pair.tiled_c32_w16", "conv_bwd_pair.tiled_c64_w8",
   "conv_fprop.wide", "conv_dgrad.wide", "conv_wgrad.wide", "conv_wgrad.tiled_stride2",
+  "conv_fprop.lds_f32", "conv_dgrad.lds_f32",
   "wgrad_reduce", "bn_finalize", "bn_apply",
   "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam", "bn_running"};
 
@@ -469,7 +471,7 @@ ddg_status build_plan(ddg_module* m) {
       for (int mode = 0; mode < 2; ++mode) {
         if (mode == 1 && !u.has_dgrad) continue;
         PackDesc d{};
-        const int md = mode == 0 ? 0 : ((u.tiled_grid > 0 || u.wide_d) ? 2 : 1);
+        const int md = mode == 0 ? 0 : ((u.tiled_grid > 0 || u.wide_d || u.dgrad.lds32) ? 2 : 1);
         const int kc = md ? u.cout : u.cin, nc = md ? u.cin : u.cout;
         d.W = m->theta + u.ow; d.wpack = mode == 0 ? u.wpack_f : u.wpack_d;
         d.Cout = u.cout; d.Cin = u.cin; d.R = u.R; d.mode = md;
@@ -593,7 +595,7 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
       conv_plan(a);
       u.frows = a.grid_x;
       a.in = in; a.wpack = u.wpack_f; a.out = z; a.stat_partial = fstat; a.add_g = nullptr; a.add_mask = nullptr;
-      Launch L(m, PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
+      Launch L(m, a.lds32 ? PK_CONV_FPROP_LDS32 : PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
       DDG_TRY(conv_launch(a, m->stream));
     }
   }
@@ -678,7 +680,7 @@ ddg_status unit_forward_two(ddg_module* m, Unit& u, const void* in0, const void*
     u.frows = a.grid_x;
     a.in = in0; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = u.fstat; a.add_g = nullptr; a.add_mask = nullptr;
     a.in_b = in1; a.out_b = z1; a.stat_partial_b = fstat1;
-    Launch L(m, PK_CONV_FPROP, bytes, 2.0 * conv_flops(u));
+    Launch L(m, a.lds32 ? PK_CONV_FPROP_LDS32 : PK_CONV_FPROP, bytes, 2.0 * conv_flops(u));
     DDG_TRY(conv_launch(a, m->stream));
   }
   if (!u.small_c()) {
@@ -983,7 +985,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     const bool fuse_below = (u.tiled_grid > 0 && below && below->u) || wide_below;
     double extra = (add_g ? (add_mask ? 2.0 : 1.0) : 0.0);
     if (fuse_below) extra += (below->mask == below->u->z) ? 1.0 : 2.0;
-    Launch L(m, u.tiled_grid > 0 ? PK_CONV_DGRAD + u.tiled_instance() : (u.wide_d ? PK_CONV_DGRAD_WIDE : PK_CONV_DGRAD),
+    Launch L(m, u.tiled_grid > 0 ? PK_CONV_DGRAD + u.tiled_instance() : (u.wide_d ? PK_CONV_DGRAD_WIDE : (u.dgrad.lds32 ? PK_CONV_DGRAD_LDS32 : PK_CONV_DGRAD)),
              (E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u), conv_flops(u));
     if (u.tiled_grid == 0 && u.wide_d) {
       ConvStat st{};
