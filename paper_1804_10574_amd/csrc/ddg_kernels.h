@@ -67,6 +67,7 @@ struct ConvArgs {
   int mb, nb;               // tile shape chosen by conv_plan
   int lds32;                // filled by conv_plan: the LDS-staged fp32 kernel runs this layer (an input
                             // gradient then takes the operand packed with mirrored taps, mode 2)
+  int no_lds32;             // set by the caller before conv_plan: keep the gather kernel
 };
 void conv_plan(ConvArgs& a);                       // chooses tile shape and grid
 hipError_t conv_launch(const ConvArgs& a, hipStream_t s);
@@ -79,12 +80,17 @@ hipError_t pack_weights_launch(const float* W, void* wpack, int Cout, int Cin, i
 
 // LDS-staged fp32 3x3/stride-1 convolution for 16/32/64 channels on 32/16/8-wide maps (forward, or
 // input gradient with an operand packed with mirrored taps). conv_lds32_grid: workgroups (= partial
-// statistics rows) or 0 if the shape is not covered; DDG_NO_LDS32=1 in the environment switches
-// the kernel off (conv_plan then keeps the gather kernel).
+// statistics rows) or 0 if the shape is not covered.
 int conv_lds32_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
 hipError_t conv_lds32_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* in_b,
                              void* out_b, float* stat_partial_b, const void* add_g, const void* add_mask, int N,
                              int H, int W, int C, int grid, hipStream_t s);
+
+// LDS-staged fp32 weight gradient of the same layers: `rows` partial tiles [rows][C][9*C] (column
+// tap*C + ci), to be added by wgrad_reduce_all_launch. wgrad_lds32_rows: 0 if not covered.
+int wgrad_lds32_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
+hipError_t wgrad_lds32_launch(const void* x, const void* dz, float* partial, int N, int H, int W, int C, int rows,
+                              hipStream_t s);
 
 // Gradient w.r.t. the weights: dW[co][ci][r][s] = sum_{n,p,q} dz[n,p,q,co] * x[n,p*st+r-pad,q*st+s-pad,ci].
 // Two launches: per-split partial tiles, then a fixed-order sum into dW (deterministic).

@@ -41,7 +41,7 @@ enum ProfKind {
   // the GEMM-class kernels of the wide layers
   PK_CONV_FPROP_WIDE = PK_BWD_PAIR_T64 + 1, PK_CONV_DGRAD_WIDE, PK_CONV_WGRAD_WIDE,
   PK_CONV_WGRAD_S2,   // the LDS-tiled weight gradient of the stride-2 layers between stages
-  PK_CONV_FPROP_LDS32, PK_CONV_DGRAD_LDS32,   // the LDS-staged fp32 kernel
+  PK_CONV_FPROP_LDS32, PK_CONV_DGRAD_LDS32, PK_CONV_WGRAD_LDS32,   // the LDS-staged fp32 kernels
   PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
   PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_BN_RUNNING, PK_COUNT
 };
@@ -51,7 +51,7 @@ static const char* kProfNames[PK_COUNT] = {
   "conv_wgrad.generic", "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c32_w16", "conv_wgrad.tiled_c64_w8",
   "conv_bwd_pair.tiled_c16_w32", "conv_bwd_pair.tiled_c32_w16", "conv_bwd_pair.tiled_c64_w8",
   "conv_fprop.wide", "conv_dgrad.wide", "conv_wgrad.wide", "conv_wgrad.tiled_stride2",
-  "conv_fprop.lds_f32", "conv_dgrad.lds_f32",
+  "conv_fprop.lds_f32", "conv_dgrad.lds_f32", "conv_wgrad.lds_f32",
   "wgrad_reduce", "bn_finalize", "bn_apply",
   "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam", "bn_running"};
 
@@ -83,6 +83,7 @@ struct Unit {  // convolution + batch normalisation
   float *escale = nullptr, *eshift = nullptr;  // evaluation-time scale and shift derived from them
   bool wide_f = false, wide_d = false;   // the GEMM-class kernel runs the forward conv / the input gradient
   int wide_splits = 0;                   // > 0: the GEMM-class weight-gradient kernel, this many pixel slices
+  int wg_lds32_rows = 0;                 // > 0: the LDS-staged fp32 weight-gradient kernel, this many partial tiles
   bool small_c() const { return cout == 16 || cout == 32 || cout == 64; }
   int tiled_instance() const { return cin == 16 ? 1 : cin == 32 ? 2 : 3; }   // offset of a tiled kernel's profile kind
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
@@ -316,6 +317,7 @@ ddg_status build_plan(ddg_module* m) {
   m->no_defer = env_on("DDG_NO_DEFER");
   m->premasked = !env_on("DDG_NO_PREMASK");
   m->wide_below = getenv("DDG_NO_WIDE_BELOW") == nullptr;
+  const int no_lds32 = env_on("DDG_NO_LDS32") ? 1 : 0;
   m->stale = d.stale_jacobian != 0 && d.K - d.k > 0;
   m->groups = m->stale ? (d.K - d.k + 1) : ((d.K - d.k > 0 && !m->two_streams && !no_pair) ? 2 : 1);
   m->in_elems = (size_t)N * h * w * c;
@@ -358,7 +360,7 @@ ddg_status build_plan(ddg_module* m) {
       ConvArgs& f = u.fprop;
       f.N = N; f.IH = u.H; f.IW = u.W; f.IC = u.cin; f.OH = u.P; f.OW = u.Q; f.OC = u.cout;
       f.R = u.R; f.stride = u.stride; f.pad = u.pad; f.ntaps = u.R * u.R;
-      f.M = N * u.P * u.Q; f.dgrad = 0; f.dtype = dt;
+      f.M = N * u.P * u.Q; f.dgrad = 0; f.dtype = dt; f.no_lds32 = no_lds32;
       size_t ne = conv_wpack_elems(u.cin, u.cout, u.R, dt, &f.log2cp, &f.ksteps);
       DDG_OKAY(dev_alloc(m, &u.wpack_f, ne * m->esz));
       conv_plan(f);
@@ -387,7 +389,7 @@ ddg_status build_plan(ddg_module* m) {
         ConvArgs& g = u.dgrad;
         g.N = N; g.IH = u.P; g.IW = u.Q; g.IC = u.cout; g.OH = u.H; g.OW = u.W; g.OC = u.cin;
         g.R = u.R; g.stride = u.stride; g.pad = u.pad; g.ntaps = u.R * u.R;
-        g.M = N * u.H * u.W; g.dgrad = 1; g.dtype = dt;
+        g.M = N * u.H * u.W; g.dgrad = 1; g.dtype = dt; g.no_lds32 = no_lds32;
         ne = conv_wpack_elems(u.cout, u.cin, u.R, dt, &g.log2cp, &g.ksteps);
         u.wpack_d_bytes = (ne * m->esz + 255) & ~(size_t)255;
         DDG_OKAY(dev_alloc(m, &u.wpack_d, (m->stale ? (size_t)(d.K - d.k + 1) : 1) * u.wpack_d_bytes));
@@ -400,6 +402,8 @@ ddg_status build_plan(ddg_module* m) {
       wgrad_plan(wgd);
       u.wg_tiled_rows = wgrad_tiled_rows(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
       if (u.wg_tiled_rows > 0) wgd.msplit = u.wg_tiled_rows;  // the reduce kernel sums this many rows
+      u.wg_lds32_rows = no_lds32 ? 0 : wgrad_lds32_rows(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
+      if (u.wg_lds32_rows > 0) wgd.msplit = u.wg_lds32_rows;
       if (wgrad_wide_ok(u.cin, u.cout, u.R, u.stride, dt) && !getenv("DDG_NO_WIDE")) {
         u.wide_splits = wgrad_wide_splits(wgd.M, u.cin, u.cout, u.R);
         wgd.msplit = u.wide_splits;
@@ -970,10 +974,13 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
       DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
     }
     if (x_scale && u.wide_splits == 0) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
-    Launch L(m, u.wide_splits > 0 ? PK_CONV_WGRAD_WIDE : PK_CONV_WGRAD, (u.in_elems() + E) * (double)m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
+    Launch L(m, u.wide_splits > 0 ? PK_CONV_WGRAD_WIDE : (u.wg_lds32_rows > 0 ? PK_CONV_WGRAD_LDS32 : PK_CONV_WGRAD),
+             (u.in_elems() + E) * (double)m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
     if (u.wide_splits > 0)
       DDG_TRY(wgrad_wide_launch(x_in, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.cout, u.R, u.wide_splits, m->stream,
                                 x_scale, x_shift));
+    else if (u.wg_lds32_rows > 0)
+      DDG_TRY(wgrad_lds32_launch(x_in, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.wg_lds32_rows, m->stream));
     else
       DDG_TRY(wgrad_launch(w, m->stream));
   }

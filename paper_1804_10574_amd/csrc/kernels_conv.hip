@@ -214,8 +214,7 @@ size_t conv_wpack_elems(int kchannels, int nchannels, int R, int dtype, int* log
 void conv_plan(ConvArgs& a) {
   a.lds32 = 0;
   {
-    static const bool off = [] { const char* e = getenv("DDG_NO_LDS32"); return e && e[0] == '1'; }();
-    const int g = off ? 0 : conv_lds32_grid(a.N, a.IH, a.IW, a.IC, a.OC, a.R, a.stride, a.dtype);
+    const int g = a.no_lds32 ? 0 : conv_lds32_grid(a.N, a.IH, a.IW, a.IC, a.OC, a.R, a.stride, a.dtype);
     if (g > 0) { a.lds32 = 1; a.grid_x = g; a.mb = 4; a.nb = 1; return; }
   }
   const int ocb = a.OC / 16;

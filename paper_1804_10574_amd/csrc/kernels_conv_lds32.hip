@@ -20,6 +20,7 @@
 // row per workgroup, added in a fixed order.
 #include "ddg_device.h"
 #include "ddg_kernels.h"
+#include <cstdlib>
 
 namespace ddg {
 
@@ -231,6 +232,193 @@ hipError_t conv_lds32_launch(const void* in, const void* wpack, void* out, float
   if (C == 16 && W == 32) return conv_lds32_launch_t<16, 32>(a, grid, s);
   if (C == 32 && W == 16) return conv_lds32_launch_t<32, 16>(a, grid, s);
   if (C == 64 && W == 8) return conv_lds32_launch_t<64, 8>(a, grid, s);
+  return hipErrorInvalidValue;
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Weight gradient of the same layers: dW[co][tap][ci] = sum over pixels p of dz[p][co] * x[p + tap][ci].
+// The contraction runs over pixels, so with the fp32 matrix instruction (k = 4 pixels per
+// instruction, one element per lane and operand) no transposition is needed: a lane reads
+// dz[pixel lg][channel l16] and x[pixel lg + tap][channel l16] as they lie in the staged tiles.
+// A workgroup stages the halo tile of x and the tile of dz in LDS (every element is read from
+// memory once per tile instead of once per tap), keeps its share of the 16x16 accumulator blocks
+// of dW in registers across all its tiles, and writes one partial tile; the partial tiles are
+// added in a fixed order by the module's reduction launch (no atomics).
+//   16 channels:  9 blocks, every wave holds all of them and takes a quarter of the pixels (the
+//                 four waves' sums are added through LDS in a fixed order at the end);
+//   32 channels: 36 blocks, wave = (output-channel block, input-channel block), all 9 taps;
+//   64 channels: 144 blocks, wave = output-channel block, all input-channel blocks and taps;
+//                its tiles are 4 rows high so that a 128-image minibatch has 256 of them.
+// ---------------------------------------------------------------------------------------------
+struct WgradLds32Args {
+  const float* x;          // [N,H,W,C] conv input
+  const float* dz;         // [N,H,W,C] gradient w.r.t. the conv output
+  float* partial;          // [gridDim.x][C][9*C]
+  int N, H;
+  int tiles;               // N * H/TH
+};
+
+template <int C, int W>
+struct WgradLds32Cfg {
+  static constexpr int TH = C == 64 ? 4 : 8, ROWS = TH + 2, WC = W + 2;
+  static constexpr int PIX = C * 4 + 16;
+  static constexpr int X_BYTES = ROWS * WC * PIX, Z_BYTES = TH * W * PIX;
+  static constexpr int CH = C / 4;
+  static constexpr int NX = ROWS * WC * CH, NZ = TH * W * CH;           // 16-byte chunks per tile
+  static constexpr int PTX = (NX + 255) / 256, PTZ = (NZ + 255) / 256;
+  static constexpr int NCB = C / 16;                                    // channel blocks
+  static constexpr int NACC = C == 64 ? 36 : 9;                         // accumulator blocks per wave
+  static constexpr int KS = TH * W / 4;                                 // 4-pixel steps per tile
+  static constexpr int RED_BYTES = C == 16 ? 4 * 9 * 256 * 4 : 0;       // 16 channels: the four waves' blocks
+  static constexpr int LDS = (X_BYTES + Z_BYTES) > RED_BYTES ? (X_BYTES + Z_BYTES) : RED_BYTES;
+};
+
+template <int C, int W>
+__global__ __launch_bounds__(256) void wgrad3x3_lds_f32_kernel(WgradLds32Args a) {
+  using Cfg = WgradLds32Cfg<C, W>;
+  constexpr int TH = Cfg::TH, WC = Cfg::WC, PIX = Cfg::PIX, CH = Cfg::CH;
+  constexpr int PTX = Cfg::PTX, PTZ = Cfg::PTZ, NACC = Cfg::NACC, KS = Cfg::KS;
+  extern __shared__ __align__(16) unsigned char lds[];
+  unsigned char* xs = lds;
+  unsigned char* zs = lds + Cfg::X_BYTES;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, lg = lane >> 4;
+  const int tiles_per_img = a.H / TH;
+  // this wave's blocks: output-channel block cob; input-channel blocks cib0 .. cib0 + NCI - 1
+  constexpr int NCI = C == 64 ? 4 : 1;
+  const int cob = C == 16 ? 0 : (C == 32 ? wave >> 1 : wave);
+  const int cib0 = C == 32 ? (wave & 1) : 0;
+
+  // ---- staging maps (the same for every tile)
+  const int my_ch = tid % CH;
+  int xg[PTX], xl[PTX], xr[PTX];     // element offset from the tile's first pixel; LDS offset (-1: none); halo row (-1: stays zero)
+#pragma unroll
+  for (int i = 0; i < PTX; ++i) {
+    const int v = tid + i * 256;
+    const int px = v / CH;
+    const int rr = px / WC, cc = px - rr * WC;
+    const bool col_ok = v < Cfg::NX && cc >= 1 && cc <= W;
+    xr[i] = col_ok ? rr : -1;
+    xg[i] = ((rr - 1) * W + (cc - 1)) * C + my_ch * 4;
+    xl[i] = v < Cfg::NX ? px * PIX + my_ch * 16 : -1;
+  }
+  int zg[PTZ], zl[PTZ];
+#pragma unroll
+  for (int i = 0; i < PTZ; ++i) {
+    const int v = tid + i * 256;
+    const int px = v / CH;
+    zg[i] = px * C + my_ch * 4;
+    zl[i] = v < Cfg::NZ ? px * PIX + my_ch * 16 : -1;
+  }
+  float4 sx[PTX], sz[PTZ];
+  auto issue_loads = [&](int t) {
+    const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
+    const unsigned tb = (unsigned)((n * a.H + r0) * W) * C;   // (32 bits: the host checks)
+#pragma unroll
+    for (int i = 0; i < PTX; ++i) {
+      sx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      const int ih = r0 - 1 + xr[i];
+      if (xr[i] >= 0 && ih >= 0 && ih < a.H) sx[i] = *reinterpret_cast<const float4*>(a.x + tb + xg[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < PTZ; ++i) {
+      sz[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (zl[i] >= 0) sz[i] = *reinterpret_cast<const float4*>(a.dz + tb + zg[i]);
+    }
+  };
+  int t = blockIdx.x;
+  if (t < a.tiles) issue_loads(t);
+
+  f32x4_t acc[NACC];
+#pragma unroll
+  for (int b = 0; b < NACC; ++b) acc[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  for (; t < a.tiles; t += gridDim.x) {
+    __syncthreads();            // the previous tile has been consumed
+#pragma unroll
+    for (int i = 0; i < PTX; ++i)
+      if (xl[i] >= 0) *reinterpret_cast<float4*>(xs + xl[i]) = sx[i];
+#pragma unroll
+    for (int i = 0; i < PTZ; ++i)
+      if (zl[i] >= 0) *reinterpret_cast<float4*>(zs + zl[i]) = sz[i];
+    __syncthreads();
+    const int tn = t + gridDim.x;
+    if (tn < a.tiles) issue_loads(tn);   // in flight during the matrix phase
+
+    // 4-pixel steps: 16 channels: wave w takes steps w, w+4, ...; else every wave takes all
+    constexpr int S0 = C == 16 ? 4 : 1;
+    for (int s = (C == 16 ? wave : 0); s < KS; s += S0) {
+      const int p = s * 4 + lg;                      // this lane's pixel of the step
+      const int r = p / W, c = p % W;
+      const float dv = *reinterpret_cast<const float*>(zs + p * PIX + (cob * 16 + l16) * 4);
+      const unsigned char* xb = xs + (r * WC + c) * PIX + (cib0 * 16 + l16) * 4;
+#pragma unroll
+      for (int ci = 0; ci < NCI; ++ci)
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+          const float xv = *reinterpret_cast<const float*>(xb + ((tap / 3) * WC + tap % 3) * PIX + ci * 64);
+          acc[ci * 9 + tap] = __builtin_amdgcn_mfma_f32_16x16x4f32(dv, xv, acc[ci * 9 + tap], 0, 0, 0);
+        }
+    }
+  }
+
+  // ---- write the partial tile: block (cob, tap, cib): rows co = cob*16 + lg*4 + v, column
+  // tap*C + cib*16 + l16
+  constexpr int J = 9 * C;
+  float* dst = a.partial + (size_t)blockIdx.x * C * J;
+  if (C == 16) {
+    // the four waves hold sums over different pixels of the same 9 blocks: add them in order
+    __syncthreads();            // the tiles are no longer read
+    float* red = reinterpret_cast<float*>(lds);      // [wave][block][row][col]
+#pragma unroll
+    for (int b = 0; b < 9; ++b)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[((wave * 9 + b) * 16 + lg * 4 + v) * 16 + l16] = acc[b][v];
+    __syncthreads();
+    for (int e = tid; e < 9 * 256; e += 256) {
+      const int b = e >> 8, row = (e >> 4) & 15, col = e & 15;
+      const float s4 = ((red[((0 * 9 + b) * 16 + row) * 16 + col] + red[((1 * 9 + b) * 16 + row) * 16 + col]) +
+                        red[((2 * 9 + b) * 16 + row) * 16 + col]) + red[((3 * 9 + b) * 16 + row) * 16 + col];
+      dst[(size_t)row * J + b * 16 + col] = s4;
+    }
+  } else {
+#pragma unroll
+    for (int ci = 0; ci < NCI; ++ci)
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          dst[(size_t)(cob * 16 + lg * 4 + v) * J + tap * C + (cib0 + ci) * 16 + l16] = acc[ci * 9 + tap][v];
+  }
+}
+
+// Partial tiles (= workgroups) of the LDS-staged fp32 weight gradient, 0 if the shape is not covered.
+int wgrad_lds32_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype) {
+  if (conv_lds32_grid(N, H, W, Cin, Cout, R, stride, dtype) == 0) return 0;
+  const int tiles = N * (H / (Cin == 64 ? 4 : 8));
+  int cap = 128;     // (measured on ResNet-20: 128 and 256 give the same iteration time; fewer partial tiles to add)
+  if (const char* e = getenv("DDG_TUNE_WGRAD_LDS32_ROWS")) { const int v = atoi(e); if (v >= 16 && v <= 1024) cap = v; }
+  return tiles < cap ? tiles : cap;
+}
+
+template <int C, int W>
+static hipError_t wgrad_lds32_launch_t(const WgradLds32Args& a, int rows, hipStream_t s) {
+  using Cfg = WgradLds32Cfg<C, W>;
+  static_assert(Cfg::LDS <= 48 * 1024, "dynamic LDS within the default limit");
+  DDG_LAUNCH((wgrad3x3_lds_f32_kernel<C, W>), dim3(rows), dim3(256), Cfg::LDS, s, a);
+  return hipGetLastError();
+}
+
+hipError_t wgrad_lds32_launch(const void* x, const void* dz, float* partial, int N, int H, int W, int C, int rows,
+                              hipStream_t s) {
+  if (rows < 1 || rows != wgrad_lds32_rows(N, H, W, C, C, 3, 1, F32)) return hipErrorInvalidValue;
+  WgradLds32Args a{};
+  a.x = (const float*)x; a.dz = (const float*)dz; a.partial = partial; a.N = N; a.H = H;
+  a.tiles = N * (H / (C == 64 ? 4 : 8));
+  if (C == 16 && W == 32) return wgrad_lds32_launch_t<16, 32>(a, rows, s);
+  if (C == 32 && W == 16) return wgrad_lds32_launch_t<32, 16>(a, rows, s);
+  if (C == 64 && W == 8) return wgrad_lds32_launch_t<64, 8>(a, rows, s);
   return hipErrorInvalidValue;
 }
 

@@ -18,6 +18,35 @@ __global__ __launch_bounds__(256) void copy16(const uint4* __restrict__ src, uin
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Variants of the copy, to see whether the plain one undersells the memory system: four 16-byte
+// loads in flight per thread before the stores; the same with non-temporal accesses.
+template <bool NT>
+__global__ __launch_bounds__(256) void copy16x4(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x * 4 + threadIdx.x; i < n16; i += stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t j = i + (size_t)u * blockDim.x;
+      if (j < n16) {
+        if (NT) { const unsigned* p = reinterpret_cast<const unsigned*>(src + j);
+                  v[u] = make_uint4(__builtin_nontemporal_load(p), __builtin_nontemporal_load(p + 1), __builtin_nontemporal_load(p + 2), __builtin_nontemporal_load(p + 3)); }
+        else v[u] = src[j];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t j = i + (size_t)u * blockDim.x;
+      if (j < n16) {
+        if (NT) { unsigned* p = reinterpret_cast<unsigned*>(dst + j);
+                  __builtin_nontemporal_store(v[u].x, p); __builtin_nontemporal_store(v[u].y, p + 1);
+                  __builtin_nontemporal_store(v[u].z, p + 2); __builtin_nontemporal_store(v[u].w, p + 3); }
+        else dst[j] = v[u];
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void read16(const uint4* __restrict__ src, unsigned* __restrict__ sink, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   unsigned acc = 0;
@@ -109,6 +138,16 @@ int main() {
     const double tr = best_ms([&] { hipLaunchKernelGGL(read16, dim3(grid), dim3(256), 0, 0, src, sink, n16); }, 10);
     printf("copy %5zu MiB: %.3f ms, %.0f GB/s read+written = %.3f of 8 TB/s;  read only: %.3f ms, %.0f GB/s = %.3f\n", mib, tc,
            2.0 * bytes / tc / 1e6, 2.0 * bytes / tc / 1e6 / 8000.0, tr, (double)bytes / tr / 1e6, (double)bytes / tr / 1e6 / 8000.0);
+    // the same copy written three other ways (does the plain kernel undersell the memory system?)
+    for (int wgs : {4, 16}) {
+      const int g4 = cus * wgs;
+      const double t4 = best_ms([&] { hipLaunchKernelGGL(copy16x4<false>, dim3(g4), dim3(256), 0, 0, src, dst, n16); }, 10);
+      const double tn = best_ms([&] { hipLaunchKernelGGL(copy16x4<true>, dim3(g4), dim3(256), 0, 0, src, dst, n16); }, 10);
+      printf("      variants, %2d workgroups per compute unit: 4 loads in flight %.0f GB/s; non-temporal %.0f GB/s\n", wgs,
+             2.0 * bytes / t4 / 1e6, 2.0 * bytes / tn / 1e6);
+    }
+    const double tm = best_ms([&] { (void)hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, 0); }, 10);
+    printf("      the runtime's own device-to-device copy: %.0f GB/s\n", 2.0 * bytes / tm / 1e6);
     CK(hipFree(src)); CK(hipFree(dst)); CK(hipFree(sink));
   }
 

@@ -627,6 +627,16 @@ def _deep_three_way(H, wl, steps, tol, factor, slack):
     return bad, d
 
 
+def test_cifar_shaped_pipeline_f32_gather_kernels(H, monkeypatch):
+    """The same fp32 pipeline with the library's environment switch that keeps the gather kernels
+    for the 3x3 layers the LDS-staged fp32 kernels otherwise run (read when a module is created)."""
+    monkeypatch.setenv("DDG_NO_LDS32", "1")
+    wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="f32", name="cifar_k3")
+    _say("case cifar_k3 f32 steps=8, DDG_NO_LDS32=1")
+    report, stats = H.run_pipeline_parity(wl, 8, 1e-4, say=_say, loose=2e-2)
+    assert not report, "\n".join(report)
+
+
 @pytest.mark.parametrize("name,batch,steps", [("resnet56_k3", 4, 6), ("resnet110_k4", 2, 7)])
 def test_deep_workloads_f32(H, name, batch, steps):
     """ResNet-56 (K=3) and ResNet-110 (K=4) with their real depth and module splits at a batch
