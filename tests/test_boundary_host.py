@@ -148,6 +148,25 @@ def test_create_rejects_bad_block_lists():
         assert e.value.status == 2, (blocks, str(e.value))
 
 
+def test_maximum_sizes_are_checked_on_the_host():
+    """The kernels index pixels and elements with 32 bits: a module whose largest tensor would not
+    fit is refused when it is created (DDG_ERR_SHAPE), the largest one that fits is accepted
+    (dry run: nothing is allocated), and the smallest shapes (batch 1, one 8x8 image) plan too."""
+    S, B = wk.BLOCK_STEM, wk.BLOCK_BASIC
+    blocks = [(S, 3, 0, 16, 1, 0), (B, 16, 0, 16, 1, 0)]
+    def mk(batch, hw):
+        return make_desc(2, 1, batch, (3, hw, hw), blocks, 0, 1, 0.9, 0.0, 1e-5, dry_run=True)
+    # 16 channels x 32 x 32 x batch elements must stay below 2^31
+    limit = (2 ** 31 - 1) // (16 * 32 * 32)
+    ddg.Module(mk(limit, 32)).close()
+    with pytest.raises(ddg.DDGError) as e:
+        ddg.Module(mk(limit + 1, 32))
+    assert e.value.status == 2 and "32-bit" in str(e.value)
+    m = ddg.Module(mk(1, 8))
+    assert m.out_shape() == (16, 8, 8)
+    m.close()
+
+
 def test_a_module_may_be_the_head_alone():
     """A split point after the last conv layer leaves only the classifier in the last module."""
     H = wk.BLOCK_HEAD
