@@ -337,6 +337,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet110_k4")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="run the workload at another batch than the one it is specified with (0: as specified); "
+                         "for the step-time-against-batch fit, not a bench line: implies --no-secondary and --no-cpu-baseline")
     ap.add_argument("--cpu-sample-batch", type=int, default=0,
                     help="batch of the oracle's timed sample (0: the workload's own batch; K warm-up + 1 timed "
                          "iteration, about 30 s of CPU work for resnet110_k4)")
@@ -366,6 +369,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = wk.get_workload(args.workload)
+    if args.batch and args.batch != wl.batch:
+        wl = wk.get_workload(args.workload, batch=args.batch)
+        wl.name = f"{wl.name}@batch{args.batch}"     # named in config.workload: not the specified configuration
+        args.no_secondary = args.no_cpu_baseline = True
     res = measure(wl, args, args.steps, args.warmup)
     out = {"metric": "DDG module images/sec on 1 MI355X", "value": res.pop("value"), "unit": res.pop("unit"),
            "n_gpus": 1, "steps": res.pop("steps"), "warmup": res.pop("warmup"), "ms_per_step": res.pop("ms_per_step"),
