@@ -230,6 +230,23 @@ ddg_status ddg_forward_eval_static(ddg_module* m, const void* h_in, void* h_out,
 /* Wait for the module's stream. */
 ddg_status ddg_module_sync(ddg_module* m);
 
+/* Checkpoint of the delay ring (Section 3.1: a module keeps its inputs for K-k iterations, so a
+ * checkpoint of weights and velocity alone would have to replay the warm-up of Eq. 8). The ring
+ * has ddg_ring_slots() = K-k+1 slots of ddg_ring_slot_bytes() bytes each (the module input,
+ * [batch,in_h,in_w,in_c] in the compute type); slot i holds the input of the iteration t with
+ * t mod (K-k+1) == i. get copies a slot to host memory, set copies host memory into a slot; both
+ * synchronise. ddg_set_time makes t the next iteration the module expects (ddg_get_time reads
+ * it): with weights, velocity (second moment, update count, running estimates) and ring slots
+ * restored and the time set, a new module continues a run exactly where the checkpoint was taken.
+ * Between iterations only (DDG_ERR_STATE otherwise), t >= 0; not in stale-Jacobian mode, whose
+ * kept forward passes are not part of a checkpoint (DDG_ERR_STATE). */
+int ddg_ring_slots(const ddg_module* m);
+size_t ddg_ring_slot_bytes(const ddg_module* m);
+ddg_status ddg_get_ring_slot(ddg_module* m, int slot, void* host_dst);
+ddg_status ddg_set_ring_slot(ddg_module* m, int slot, const void* host_src);
+ddg_status ddg_set_time(ddg_module* m, long t);
+long ddg_get_time(const ddg_module* m);
+
 /* ---- K modules as concurrent streams (Algorithm 1, "for k = 1..K in parallel") -------------
  * The pipeline owns the K modules, the activations handed from module k to k+1 and the
  * double-buffered error-gradient mailboxes handed from k+1 to k, and orders the streams with
@@ -266,6 +283,19 @@ ddg_status ddg_pipeline_set_bn_momentum(ddg_pipeline* p, float rho);
 ddg_status ddg_pipeline_get_h(ddg_pipeline* p, int k, float* host_dst);
 ddg_status ddg_pipeline_get_delta(ddg_pipeline* p, int k, float* host_dst, long* iteration);
 ddg_status ddg_pipeline_sync(ddg_pipeline* p);
+/* Checkpoint of the pipeline's own state between two iterations (Fig. 2: the error gradient
+ * module k+1 computed in the last iteration is in flight to module k). ddg_pipeline_time: the
+ * next iteration. ddg_pipeline_get_mail: that gradient for edge k (1 <= k < K), raw, in module
+ * k's compute type (ddg_pipeline_mail_bytes(p, k) bytes), and the iteration it belongs to (-1:
+ * none, then nothing is copied); synchronises. To resume: create the pipeline, restore every
+ * module (weights, velocity, ring slots, ...; not their time), then ddg_pipeline_set_time(p, t)
+ * (sets the time of every module too), then ddg_pipeline_set_mail for every edge whose
+ * iteration was >= 0. The run then continues bit for bit as the checkpointed one would have. */
+long ddg_pipeline_time(const ddg_pipeline* p);
+ddg_status ddg_pipeline_set_time(ddg_pipeline* p, long t);
+size_t ddg_pipeline_mail_bytes(const ddg_pipeline* p, int k);
+ddg_status ddg_pipeline_get_mail(ddg_pipeline* p, int k, void* host_dst, long* iteration);
+ddg_status ddg_pipeline_set_mail(ddg_pipeline* p, int k, const void* host_src, long iteration);
 
 /* ---- measurement ----------------------------------------------------------------------------
  * Per-kernel-family timing with HIP events on the module's stream. While enabled, every launch

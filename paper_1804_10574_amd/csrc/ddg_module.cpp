@@ -1359,7 +1359,14 @@ ddg_status ddg_set_update_count(ddg_module* m, long n) {
   m->nupd = n;
   if (m->d.dry_run) return DDG_OK;
   DDG_OKAY(sync_streams(m));
-  const double pw[2] = {std::pow((double)m->beta1, (double)n), std::pow((double)m->beta2, (double)n)};
+  // beta^n as the update kernels form it, one multiplication per executed update, so that a
+  // restored count continues a run bit for bit (beyond 10^8 updates: the closed form)
+  double pw[2] = {1.0, 1.0};
+  if (n <= 100000000L) {
+    for (long i = 0; i < n; ++i) { pw[0] *= (double)m->beta1; pw[1] *= (double)m->beta2; }
+  } else {
+    pw[0] = std::pow((double)m->beta1, (double)n); pw[1] = std::pow((double)m->beta2, (double)n);
+  }
   DDG_TRY(hipMemcpy(m->adam_pw, pw, sizeof pw, hipMemcpyHostToDevice));
   return DDG_OK;
 }
@@ -1451,6 +1458,48 @@ ddg_status ddg_set_bn_momentum(ddg_module* m, float rho) {
   m->bn_rho = rho;
   return DDG_OK;
 }
+
+int ddg_ring_slots(const ddg_module* m) { return m ? m->nslots : 0; }
+size_t ddg_ring_slot_bytes(const ddg_module* m) { return m ? m->in_elems * m->esz : 0; }
+
+static ddg_status ring_slot_ok(ddg_module* m, int slot, const void* host) {
+  DDG_OKAY(check_handle(m));
+  if (!host) return fail(DDG_ERR_INVALID_ARG, "host buffer is null");
+  if (slot < 0 || slot >= m->nslots) return fail(DDG_ERR_INVALID_ARG, "ring slot %d outside [0, %d)", slot, m->nslots);
+  if (m->phase != 0) return fail(DDG_ERR_STATE, "the ring can only be read or written between iterations");
+  if (m->stale) return fail(DDG_ERR_STATE, "stale-Jacobian mode keeps forward passes that a checkpoint does not hold");
+  return DDG_OK;
+}
+
+ddg_status ddg_get_ring_slot(ddg_module* m, int slot, void* host_dst) {
+  DDG_OKAY(ring_slot_ok(m, slot, host_dst));
+  if (m->d.dry_run) return DDG_OK;
+  DDG_OKAY(sync_streams(m));
+  DDG_TRY(hipMemcpy(host_dst, m->ring[slot], m->in_elems * m->esz, hipMemcpyDeviceToHost));
+  return DDG_OK;
+}
+
+ddg_status ddg_set_ring_slot(ddg_module* m, int slot, const void* host_src) {
+  DDG_OKAY(ring_slot_ok(m, slot, host_src));
+  if (m->d.dry_run) return DDG_OK;
+  DDG_OKAY(sync_streams(m));
+  DDG_TRY(hipMemcpy(m->ring[slot], host_src, m->in_elems * m->esz, hipMemcpyHostToDevice));
+  return DDG_OK;
+}
+
+ddg_status ddg_set_time(ddg_module* m, long t) {
+  DDG_OKAY(check_handle(m));
+  if (t < 0) return fail(DDG_ERR_INVALID_ARG, "iteration must be >= 0");
+  if (m->phase != 0) return fail(DDG_ERR_STATE, "the time can only be set between iterations");
+  if (m->stale) return fail(DDG_ERR_STATE, "stale-Jacobian mode keeps forward passes that a checkpoint does not hold");
+  if (!m->d.dry_run) DDG_OKAY(sync_streams(m));
+  m->t_next = t;
+  m->tape_is_current = false;
+  m->has_grad = false;
+  return DDG_OK;
+}
+
+long ddg_get_time(const ddg_module* m) { return m ? m->t_next : -1; }
 
 size_t ddg_running_count(const ddg_module* m) { return m ? m->nrunning : 0; }
 

@@ -367,4 +367,49 @@ ddg_status ddg_pipeline_get_delta(ddg_pipeline* p, int k, float* host_dst, long*
   return fetch_f32(p, p->mail[slot][k], p->h_elems[k], p->dtype[k], host_dst);
 }
 
+long ddg_pipeline_time(const ddg_pipeline* p) { return p ? p->t : -1; }
+
+ddg_status ddg_pipeline_set_time(ddg_pipeline* p, long t) {
+  if (!p || t < 0) return DDG_ERR_INVALID_ARG;
+  ddg_status st = ddg_pipeline_sync(p);
+  if (st != DDG_OK) return st;
+  for (int k = 1; k <= p->K; ++k) {
+    st = ddg_set_time(p->mods[k], t);
+    if (st != DDG_OK) return st;
+  }
+  p->t = t;
+  for (int sl = 0; sl < 2; ++sl) for (int k = 1; k < p->K; ++k) p->mail_iter[sl][k] = -1;
+  return DDG_OK;
+}
+
+size_t ddg_pipeline_mail_bytes(const ddg_pipeline* p, int k) {
+  return (p && k >= 1 && k < p->K) ? p->h_elems[k] * ddg::dtype_size(p->dtype[k]) : 0;
+}
+
+ddg_status ddg_pipeline_get_mail(ddg_pipeline* p, int k, void* host_dst, long* iteration) {
+  if (!p || k < 1 || k >= p->K) return DDG_ERR_INVALID_ARG;
+  // the slot written during the last completed iteration is the one the next iteration reads
+  const int slot = (int)((p->t - 1) & 1);
+  const long it = (p->t > 0) ? p->mail_iter[slot][k] : -1;
+  if (iteration) *iteration = it;
+  if (it < 0 || !host_dst || p->dry) return DDG_OK;
+  const ddg_status st = ddg_pipeline_sync(p);
+  if (st != DDG_OK) return st;
+  return hipMemcpy(host_dst, p->mail[slot][k], ddg_pipeline_mail_bytes(p, k), hipMemcpyDeviceToHost) == hipSuccess
+             ? DDG_OK : DDG_ERR_DEVICE;
+}
+
+ddg_status ddg_pipeline_set_mail(ddg_pipeline* p, int k, const void* host_src, long iteration) {
+  if (!p || k < 1 || k >= p->K || !host_src || iteration < 0 || p->t < 1) return DDG_ERR_INVALID_ARG;
+  // module k reads it during iteration p->t as the gradient of iteration p->t - K + k
+  if (iteration != p->t - 1 - p->K + (k + 1)) return DDG_ERR_INVALID_ARG;
+  const int slot = (int)((p->t - 1) & 1);
+  p->mail_iter[slot][k] = iteration;
+  if (p->dry) return DDG_OK;
+  const ddg_status st = ddg_pipeline_sync(p);
+  if (st != DDG_OK) return st;
+  return hipMemcpy(p->mail[slot][k], host_src, ddg_pipeline_mail_bytes(p, k), hipMemcpyHostToDevice) == hipSuccess
+             ? DDG_OK : DDG_ERR_DEVICE;
+}
+
 }  // extern "C"

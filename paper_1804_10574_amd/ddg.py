@@ -83,6 +83,17 @@ def load_library():
         "ddg_pipeline_forward_eval": (st, [vp, vp, vp, vp, vp]),
         "ddg_pipeline_set_bn_momentum": (st, [vp, C.c_float]),
         "ddg_module_sync": (st, [vp]),
+        "ddg_ring_slots": (C.c_int, [vp]),
+        "ddg_ring_slot_bytes": (C.c_size_t, [vp]),
+        "ddg_get_ring_slot": (st, [vp, C.c_int, vp]),
+        "ddg_set_ring_slot": (st, [vp, C.c_int, vp]),
+        "ddg_set_time": (st, [vp, C.c_long]),
+        "ddg_get_time": (C.c_long, [vp]),
+        "ddg_pipeline_time": (C.c_long, [vp]),
+        "ddg_pipeline_set_time": (st, [vp, C.c_long]),
+        "ddg_pipeline_mail_bytes": (C.c_size_t, [vp, C.c_int]),
+        "ddg_pipeline_get_mail": (st, [vp, C.c_int, vp, C.POINTER(C.c_long)]),
+        "ddg_pipeline_set_mail": (st, [vp, C.c_int, vp, C.c_long]),
         "ddg_pipeline_create": (st, [C.POINTER(ModuleDesc), C.c_int, C.POINTER(vp), C.POINTER(vp)]),
         "ddg_pipeline_destroy": (st, [vp]),
         "ddg_pipeline_module": (vp, [vp, C.c_int]),
@@ -117,6 +128,9 @@ EXPORTS = ["ddg_module_create", "ddg_module_destroy", "ddg_param_count", "ddg_ou
            "ddg_pipeline_create", "ddg_pipeline_destroy", "ddg_pipeline_module", "ddg_pipeline_step",
            "ddg_pipeline_set_graphs", "ddg_pipeline_get_h", "ddg_pipeline_get_delta", "ddg_pipeline_sync", "ddg_profile_kinds",
            "ddg_profile_kind_name", "ddg_profile_enable", "ddg_profile_read", "ddg_profile_reset",
+           "ddg_ring_slots", "ddg_ring_slot_bytes", "ddg_get_ring_slot", "ddg_set_ring_slot", "ddg_set_time", "ddg_get_time",
+           "ddg_pipeline_time", "ddg_pipeline_set_time", "ddg_pipeline_mail_bytes", "ddg_pipeline_get_mail",
+           "ddg_pipeline_set_mail",
            "ddg_last_error", "ddg_version"]
 
 
@@ -282,6 +296,26 @@ class Module:
     def sync(self):
         _check(self._lib.ddg_module_sync(self._h))
 
+    # checkpoint of the delay ring: raw slots (bytes of the compute type) and the iteration counter
+    def ring_slots(self) -> int:
+        return int(self._lib.ddg_ring_slots(self._h))
+
+    def get_ring_slot(self, slot):
+        out = np.empty(int(self._lib.ddg_ring_slot_bytes(self._h)), np.uint8)
+        _check(self._lib.ddg_get_ring_slot(self._h, slot, _ptr(out)))
+        return out
+
+    def set_ring_slot(self, slot, src):
+        src = np.ascontiguousarray(src, np.uint8)
+        assert src.size == int(self._lib.ddg_ring_slot_bytes(self._h))
+        _check(self._lib.ddg_set_ring_slot(self._h, slot, _ptr(src)))
+
+    def set_time(self, t):
+        _check(self._lib.ddg_set_time(self._h, t))
+
+    def get_time(self) -> int:
+        return int(self._lib.ddg_get_time(self._h))
+
     def profile_enable(self, on=True):
         _check(self._lib.ddg_profile_enable(self._h, 1 if on else 0))
 
@@ -346,6 +380,25 @@ class Pipeline:
 
     def sync(self):
         _check(self._lib.ddg_pipeline_sync(self._h))
+
+    # checkpoint of the pipeline's own state: the iteration counter and the error gradients in flight
+    def time(self) -> int:
+        return int(self._lib.ddg_pipeline_time(self._h))
+
+    def set_time(self, t):
+        _check(self._lib.ddg_pipeline_set_time(self._h, t))
+
+    def get_mail(self, k):
+        """-> (raw bytes of the gradient in flight to module k, its iteration), or (None, -1)."""
+        out = np.empty(int(self._lib.ddg_pipeline_mail_bytes(self._h, k)), np.uint8)
+        it = C.c_long()
+        _check(self._lib.ddg_pipeline_get_mail(self._h, k, _ptr(out), C.byref(it)))
+        return (out, it.value) if it.value >= 0 else (None, -1)
+
+    def set_mail(self, k, src, iteration):
+        src = np.ascontiguousarray(src, np.uint8)
+        assert src.size == int(self._lib.ddg_pipeline_mail_bytes(self._h, k))
+        _check(self._lib.ddg_pipeline_set_mail(self._h, k, _ptr(src), iteration))
 
     def get_h(self, k):
         c, h, w = self.module(k).out_shape()

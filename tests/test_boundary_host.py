@@ -210,3 +210,59 @@ def test_static_scratch_evaluation_checks_its_size_on_the_host():
         big.forward_eval_static(fake, fake)
     assert e.value.status == 2 and "static scratch" in str(e.value)
     big.forward_eval(fake, fake)                                # the allocating one has no such limit
+
+
+def test_checkpoint_calls_follow_the_state_machine():
+    """The ring and the time of a module, and the time and the gradients in flight of a pipeline, can be
+    read and set between iterations only; slot indices and the iteration of a restored gradient
+    are checked; stale-Jacobian mode has no checkpoint (dry run: nothing is copied)."""
+    import numpy as np
+    wl = wk.get_workload("resnet110_k4")
+    d = descs_for(wl, dry_run=True)
+    m = ddg.Module(d[1])                                   # k = 2 of K = 4: delay 2, three slots
+    assert m.ring_slots() == 3 and m.get_time() == 0
+    nbytes = 256 * 32 * 32 * 16 * 2
+    assert m.get_ring_slot(0).size == nbytes
+    with pytest.raises(ddg.DDGError) as e:
+        m.get_ring_slot(3)
+    assert e.value.status == 1
+    fake = 4096
+    m.forward(0, fake, fake)
+    with pytest.raises(ddg.DDGError) as e:                 # in the middle of iteration 0
+        m.set_time(5)
+    assert e.value.status == 3
+    with pytest.raises(ddg.DDGError) as e:
+        m.set_ring_slot(0, np.zeros(nbytes, np.uint8))
+    assert e.value.status == 3
+    m.backward_delayed(0, delta_in=fake, delta_out=fake); m.update(0, 0.1)
+    m.set_time(7)
+    assert m.get_time() == 7
+    with pytest.raises(ddg.DDGError):
+        m.forward(1, fake, fake)
+    m.forward(7, fake, fake)                               # continues at the restored iteration
+    assert m.backward_delayed(7, delta_in=fake, delta_out=fake) is True    # 7 - 2 >= 0: a gradient is due
+    m.update(7, 0.1)
+    m.close()
+    ms = ddg.Module(descs_for(wl, dry_run=True, stale_jacobian=True)[1])
+    with pytest.raises(ddg.DDGError) as e:
+        ms.set_time(3)
+    assert e.value.status == 3
+    ms.close()
+
+    p = ddg.Pipeline(d)
+    assert p.time() == 0
+    assert p.get_mail(1) == (None, -1)
+    p.set_time(9)
+    assert p.time() == 9 and p.module(3).get_time() == 9
+    # the gradient in flight to module k at time t belongs to iteration t - K + k
+    with pytest.raises(ddg.DDGError) as e:
+        p.set_mail(2, np.zeros(256 * 16 * 16 * 32 * 2, np.uint8), 9 - 4 + 2 - 1)
+    assert e.value.status == 1
+    p.set_mail(2, np.zeros(256 * 16 * 16 * 32 * 2, np.uint8), 9 - 4 + 2)
+    _, it = p.get_mail(2)
+    assert it == 7
+    p.step(fake, fake, 0.01)
+    assert p.time() == 10
+    _, it = p.get_delta(1)
+    assert it == 9 - 4 + 2                                  # module 2 wrote, during iteration 9, the gradient of 9-K+k+1
+    p.close()
