@@ -34,6 +34,9 @@
  *   DDG_NO_PREMASK=1 readers of an error gradient that was stored already multiplied by a
  *                    ReLU mask load the mask tensor and apply it again (same values)
  *   DDG_NO_LDS32=1   fp32 3x3 layers run the gather kernels instead of the LDS-staged ones
+ *   DDG_CHECK_ORDER=1  ddg_pipeline_step also runs its host-side model of the stream ordering
+ *                    (always on in dry-run pipelines) and fails with DDG_ERR_STATE, naming the
+ *                    tensor, if the events it issues leave two accesses of a tensor unordered
  *   DDG_TUNE_CONV_GRID_C16/_C32/_C64, DDG_TUNE_WGRAD_ROWS[_C16/_C32/_C64], DDG_TUNE_WGRAD_WIDE_WGS,
  *   DDG_TUNE_WGRAD_GENERIC_WGS, DDG_TUNE_WGRAD_LDS32_ROWS
  *                    workgroup counts of the LDS-tiled kernels (clamped to safe ranges)

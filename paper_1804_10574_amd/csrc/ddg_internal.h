@@ -17,4 +17,6 @@ void ddg_internal_external_sync(ddg_module* m, bool on);
 // The streams ddg_forward and ddg_backward_delayed/ddg_update enqueue on (equal unless the
 // module runs its forward pass on a stream of its own).
 void ddg_internal_streams(ddg_module* m, hipStream_t* fwd, hipStream_t* bwd);
+// Sets the message ddg_last_error returns on this thread.
+void ddg_internal_set_error(const char* msg);
 }

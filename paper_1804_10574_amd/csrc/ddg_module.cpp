@@ -1711,6 +1711,7 @@ void ddg_internal_external_sync(ddg_module* m, bool on) { m->external_sync = on;
 void ddg_internal_streams(ddg_module* m, hipStream_t* fwd, hipStream_t* bwd) { *fwd = m->fstream; *bwd = m->bstream; }
 void ddg_internal_lr_from(ddg_module* m, const float* lr_dev) { m->lr_dev = lr_dev; }
 bool ddg_internal_profiling(const ddg_module* m) { return m->prof; }
+void ddg_internal_set_error(const char* msg) { g_err = msg ? msg : ""; }
 
 int ddg_profile_kinds(void) { return PK_COUNT; }
 const char* ddg_profile_kind_name(int kind) { return (kind >= 0 && kind < PK_COUNT) ? kProfNames[kind] : ""; }

@@ -16,8 +16,62 @@
 #include <string>
 #include <vector>
 
+// Host-side model of what orders the streams. Every stream carries a vector clock; recording an
+// event keeps the recording stream's clock, waiting for it merges that clock into the waiter's.
+// A step declares which tensors each call reads and writes and on which stream; an access that is
+// not ordered after the last write of the tensor (for a write: also after every read since) is
+// a hazard that the events do not cover. Runs in dry-run pipelines (no device work) and, with
+// DDG_CHECK_ORDER=1, beside the real calls.
+struct OrderModel {
+  struct Acc { int s; long v; };
+  struct Buf { Acc w{-1, 0}; std::vector<Acc> r; };
+  std::vector<std::vector<long>> clk;           // [stream][stream]
+  std::map<int, std::vector<long>> ev;          // event id -> clock at its last record
+  std::map<std::string, Buf> bufs;
+  std::string msg;                              // first hazard found
+  long waits = 0, drop = -1;                    // test hook: the wait with this running number is ignored
+  void init(int nstreams) { clk.assign(nstreams, std::vector<long>(nstreams, 0)); }
+  bool before(const Acc& a, int s) const { return a.s < 0 || clk[s][a.s] >= a.v; }
+  void record(int eid, int s) { ev[eid] = clk[s]; }
+  void wait(int s, int eid) {
+    if (waits++ == drop) return;
+    auto it = ev.find(eid);
+    if (it == ev.end()) return;                 // never recorded: the wait returns at once
+    for (size_t i = 0; i < clk[s].size(); ++i) if (it->second[i] > clk[s][i]) clk[s][i] = it->second[i];
+  }
+  void host_sync() {                            // the host waited for every stream
+    std::vector<long> m(clk.size(), 0);
+    for (auto& c : clk) for (size_t i = 0; i < c.size(); ++i) if (c[i] > m[i]) m[i] = c[i];
+    for (auto& c : clk) c = m;
+  }
+  void op(int s, long t, const char* what, const std::vector<std::string>& reads, const std::vector<std::string>& writes) {
+    clk[s][s] += 1;
+    const Acc me{s, clk[s][s]};
+    auto hazard = [&](const char* kind, const std::string& b, const Acc& a) {
+      if (msg.empty())
+        msg = std::string(kind) + " hazard at iteration " + std::to_string(t) + ": " + what + " on stream " + std::to_string(s) +
+              " touches " + b + " unordered with an access on stream " + std::to_string(a.s);
+    };
+    for (const std::string& b : reads) {
+      Buf& q = bufs[b];
+      if (!before(q.w, s)) hazard("read-after-write", b, q.w);
+      q.r.push_back(me);
+    }
+    for (const std::string& b : writes) {
+      Buf& q = bufs[b];
+      if (!before(q.w, s)) hazard("write-after-write", b, q.w);
+      for (const Acc& a : q.r) if (!before(a, s)) hazard("write-after-read", b, a);
+      q.w = me; q.r.clear();
+    }
+  }
+};
+
 struct ddg_pipeline {
   int K = 0;
+  OrderModel order;
+  bool check_order = false;
+  std::vector<int> sid_f, sid_b;        // logical stream numbers of module k's forward / backward stream
+  bool stale = false;
   std::vector<ddg_module*> mods;
   std::vector<hipStream_t> streams;     // [k] backward / update stream of module k
   std::vector<hipStream_t> fstreams;    // [k] forward stream (== streams[k] unless the module has its own)
@@ -109,6 +163,14 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
   p->h_elems.assign(K + 1, 0);
   p->dtype.assign(K + 1, 0);
   p->fstreams.assign(K + 1, nullptr);
+  p->sid_f.assign(K + 1, 0);
+  p->sid_b.assign(K + 1, 0);
+  p->order.init(2 * K + 1);
+  p->stale = descs[0].stale_jacobian != 0;
+  {
+    const char* env = getenv("DDG_CHECK_ORDER");
+    p->check_order = p->dry || (env && env[0] == '1');
+  }
   for (int sl = 0; sl < 2; ++sl) {
     p->fwd_done[sl].assign(K + 1, nullptr);
     p->mail[sl].assign(K + 1, nullptr);
@@ -122,6 +184,10 @@ ddg_status ddg_pipeline_create(const ddg_module_desc* descs, int K, void* const*
     if (!streams) d.forward_stream = nullptr;
     ddg_status st = ddg_module_create(&d, &p->mods[k]);
     if (st != DDG_OK) { ddg_pipeline_destroy(p); return st; }
+    // logical stream numbers for the ordering model: 0 when everything runs on one stream
+    p->sid_b[k] = streams ? k : 0;
+    const bool own_fwd = streams && !d.stale_jacobian && d.forward_stream && d.forward_stream != d.stream && K - k > 0;
+    p->sid_f[k] = own_fwd ? K + k : p->sid_b[k];
     if (!p->dry) {
       ddg_internal_streams(p->mods[k], &p->fstreams[k], &p->streams[k]);
       ddg_internal_external_sync(p->mods[k], true);
@@ -246,6 +312,22 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
   bool use_graph = !p->dry && p->graphs && t >= K;   // steady state: every module has a gradient
   if (use_graph) for (int k = 1; k <= K; ++k) if (ddg_internal_profiling(p->mods[k])) use_graph = false;
 #define DDG_P(expr) do { if ((expr) != hipSuccess) return DDG_ERR_DEVICE; } while (0)
+  // Every wait and record goes through these two, so that the ordering model sees exactly the
+  // dependencies the streams get. Event numbers: fwd_done[sl][k] = sl*(K+1)+k, bwd_done after them.
+  OrderModel& om = p->order;
+  const bool model = p->check_order;
+  auto ev_f = [&](int sl, int k) { return sl * (K + 1) + k; };
+  auto ev_b = [&](int sl, int k) { return 2 * (K + 1) + sl * (K + 1) + k; };
+  auto wait_f = [&](int sid, hipStream_t s, int sl, int k) -> hipError_t {
+    if (model) om.wait(sid, ev_f(sl, k));
+    return p->dry ? hipSuccess : hipStreamWaitEvent(s, p->fwd_done[sl][k], 0); };
+  auto wait_b = [&](int sid, hipStream_t s, int sl, int k) -> hipError_t {
+    if (model) om.wait(sid, ev_b(sl, k));
+    return p->dry ? hipSuccess : hipStreamWaitEvent(s, p->bwd_done[sl][k], 0); };
+  auto nm = [](const char* base, int a, long b = -1) {
+    std::string r = std::string(base) + std::to_string(a);
+    if (b >= 0) r += "/" + std::to_string(b);
+    return r; };
   if (!p->dry) {
     // stage the caller's tensors at stable addresses; the step size lives in device memory
     DDG_P(ddg::copy_launch(x, p->xin, p->x_bytes, p->fstreams[1]));
@@ -257,6 +339,10 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
       DDG_P(hipStreamSynchronize(p->streams[1]));
       p->lr_host = lr;
     }
+  }
+  if (model) {
+    om.op(p->sid_f[1], t, "the copy of the network input", {}, {"xin"});
+    om.op(p->sid_b[K], t, "the copy of the labels", {}, {"labels"});
   }
   const void* x_in = p->dry ? x : p->xin;
   const int32_t* lab = p->dry ? labels : p->labels_dev;
@@ -283,58 +369,97 @@ ddg_status ddg_pipeline_step(ddg_pipeline* p, const void* x, const int32_t* labe
   // forward, k = 1..K in turn (Section 3.1), each on its module's forward stream
   for (int k = 1; k <= K; ++k) {
     hipStream_t fs = p->dry ? nullptr : p->fstreams[k];
-    if (!p->dry) {
-      if (k > 1) DDG_P(hipStreamWaitEvent(fs, p->fwd_done[cur][k - 1], 0));
-      // this iteration's h[k] buffer was last read by module k+1's forward two iterations ago
-      // (the event of this parity still carries that record: module k+1 re-records it later)
-      if (k < K && t > 1) DDG_P(hipStreamWaitEvent(fs, p->fwd_done[cur][k + 1], 0));
-      // a forward stream of its own: the weights of update(t-1), and the ring slot that
-      // backward(t-1) read, come from the module's other stream
-      if (fs != p->streams[k] && t > 0) DDG_P(hipStreamWaitEvent(fs, p->bwd_done[prev][k], 0));
+    const int sf = p->sid_f[k];
+    const bool split = sf != p->sid_b[k];
+    if (k > 1) DDG_P(wait_f(sf, fs, cur, k - 1));
+    // this iteration's h[k] buffer was last read by module k+1's forward two iterations ago
+    // (the event of this parity still carries that record: module k+1 re-records it later)
+    if (k < K && t > 1) DDG_P(wait_f(sf, fs, cur, k + 1));
+    // a forward stream of its own: the weights of update(t-1), and the ring slot that
+    // backward(t-1) read, come from the module's other stream
+    if (split && t > 0) DDG_P(wait_b(sf, fs, prev, k));
+    if (model) {
+      // what ddg_forward(t) of module k touches (delay d, ring of d+1 slots)
+      const int d = K - k, n = d + 1;
+      std::vector<std::string> rd{k == 1 ? std::string("xin") : nm("h", cur, k - 1), nm("w", k)}, wr{nm("ring", k, t % n)};
+      if (k < K) wr.push_back(nm("h", cur, k));
+      if (p->stale) { wr.push_back(nm("tape", k, t % n)); wr.push_back(nm("wsnap", k, t % n)); }
+      else if (split) wr.push_back(nm("fbuf", k));
+      else {
+        wr.push_back(nm("tape", k));
+        if (d > 0 && t >= d) rd.push_back(nm("ring", k, (t - d) % n));   // paired with the re-forward
+      }
+      om.op(sf, t, "forward", rd, wr);
     }
     ddg_status st = run(k, fs, p->gfwd[k], [&]() {
       std::vector<void*>& hb = cur ? p->h_odd : p->h;
       return ddg_forward(p->mods[k], t, k == 1 ? x_in : hb[k - 1], k < K ? hb[k] : nullptr); });
     if (st != DDG_OK) return st;
+    if (model) om.record(ev_f(cur, k), sf);
     if (!p->dry) DDG_P(hipEventRecord(p->fwd_done[cur][k], fs));
   }
   // backward + update: the K modules are independent within one iteration
   for (int k = 1; k <= K; ++k) {
     const long s = t - K + k;
     hipStream_t bs = p->dry ? nullptr : p->streams[k];
-    const bool split = !p->dry && p->fstreams[k] != bs;
-    if (!p->dry && s >= 0 && t > 0) {
+    const int sb = p->sid_b[k];
+    const bool split = p->sid_f[k] != sb;
+    if (s >= 0 && t > 0) {
       // read-after-write: the error gradient for iteration s was written by module k+1 during t-1
-      if (k < K) DDG_P(hipStreamWaitEvent(bs, p->bwd_done[prev][k + 1], 0));
+      if (k < K) DDG_P(wait_b(sb, bs, prev, k + 1));
       // write-after-read: slot `cur` of mailbox k-1 was read by module k-1 during t-1
-      if (k > 1) DDG_P(hipStreamWaitEvent(bs, p->bwd_done[prev][k - 1], 0));
+      if (k > 1) DDG_P(wait_b(sb, bs, prev, k - 1));
       // the stored input of iteration s <= t-1 was written by the forward stream
-      if (split) DDG_P(hipStreamWaitEvent(bs, p->fwd_done[prev][k], 0));
+      if (split) DDG_P(wait_f(sb, bs, prev, k));
     }
     const void* din = (k < K) ? p->mail[prev][k] : nullptr;
     void* dout = (k > 1) ? p->mail[cur][k - 1] : nullptr;
     int did = 0;
+    if (model && s >= 0) {
+      const int d = K - k, n = d + 1;
+      std::vector<std::string> rd{nm("ring", k, s % n), nm("w", k)}, wr{nm("g", k)};
+      rd.push_back(k < K ? nm("mail", prev, k) : std::string("labels"));
+      if (k > 1) wr.push_back(nm("mail", cur, k - 1));
+      if (k == K) wr.push_back("loss");
+      if (p->stale) { rd.push_back(nm("tape", k, s % n)); rd.push_back(nm("wsnap", k, s % n)); }
+      else if (split) wr.push_back(nm("tape", k));          // re-forwards on this stream, then reads it
+      else rd.push_back(nm("tape", k));
+      om.op(sb, t, "backward", rd, wr);
+    }
     ddg_status st = run(k, bs, p->gbwd[k], [&]() {
       return ddg_backward_delayed(p->mods[k], t, (s >= 0) ? din : nullptr, k == K ? lab : nullptr, dout,
                                   k == K ? (p->dry ? loss_out : p->loss_dev) : nullptr, &did); });
     if (st != DDG_OK) return st;
     if (k > 1) p->mail_iter[cur][k - 1] = did ? s : -1;
     // the update overwrites the weights that this iteration's forward pass reads
-    if (split) DDG_P(hipStreamWaitEvent(bs, p->fwd_done[cur][k], 0));
+    if (split) DDG_P(wait_f(sb, bs, cur, k));
+    if (model && s >= 0) om.op(sb, t, "update", {nm("g", k)}, {nm("w", k)});
     st = run(k, bs, p->gupd[k], [&]() { return ddg_update(p->mods[k], t, lr); });
     if (st != DDG_OK) return st;
+    if (model && k == K && loss_out && s >= 0) om.op(sb, t, "the copy of the loss", {"loss"}, {});
     if (!p->dry) {
       if (k == K && loss_out && s >= 0) DDG_P(ddg::copy_launch(p->loss_dev, loss_out, sizeof(float), bs));
-      DDG_P(hipEventRecord(p->bwd_done[cur][k], bs));
     }
+    if (model) om.record(ev_b(cur, k), sb);
+    if (!p->dry) DDG_P(hipEventRecord(p->bwd_done[cur][k], bs));
   }
 #undef DDG_P
   p->t = t + 1;
+  if (model && !om.msg.empty()) {
+    ddg_internal_set_error(om.msg.c_str());
+    return DDG_ERR_STATE;
+  }
   return DDG_OK;
 }
 
+// Test hooks of the ordering model (not part of the C boundary): the number of waits the model
+// has seen, and the running number of a wait it is to ignore.
+long ddg_internal_pipeline_waits(const ddg_pipeline* p) { return p ? p->order.waits : -1; }
+void ddg_internal_pipeline_drop_wait(ddg_pipeline* p, long n) { if (p) p->order.drop = n; }
+
 ddg_status ddg_pipeline_sync(ddg_pipeline* p) {
   if (!p) return DDG_ERR_INVALID_ARG;
+  if (p->check_order) p->order.host_sync();
   if (p->dry) return DDG_OK;
   for (int k = 1; k <= p->K; ++k) {
     if (hipStreamSynchronize(p->streams[k]) != hipSuccess) return DDG_ERR_DEVICE;

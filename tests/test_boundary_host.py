@@ -266,3 +266,73 @@ def test_checkpoint_calls_follow_the_state_machine():
     _, it = p.get_delta(1)
     assert it == 9 - 4 + 2                                  # module 2 wrote, during iteration 9, the gradient of 9-K+k+1
     p.close()
+
+
+def _order_hooks():
+    import ctypes as C
+    lib = ddg.load_library()
+    lib.ddg_internal_pipeline_waits.restype = C.c_long
+    lib.ddg_internal_pipeline_waits.argtypes = [C.c_void_p]
+    lib.ddg_internal_pipeline_drop_wait.restype = None
+    lib.ddg_internal_pipeline_drop_wait.argtypes = [C.c_void_p, C.c_long]
+    return lib
+
+
+def _dry_pipeline(K, own_forward_streams, stale=False):
+    from workloads.configs import custom_cifar
+    cuts = {1: [], 2: [4], 3: [3, 5], 4: [2, 4, 6], 5: [1, 3, 5, 7]}[K]
+    wl = custom_cifar(2, cuts, batch=2, num_classes=10, hw=8, dtype="f32", name=f"dry_k{K}")
+    assert wl.K == K
+    streams = [4096 * (i + 1) for i in range(K)]                 # handles are never used in a dry run
+    fstreams = [4096 * (i + 101) for i in range(K)] if own_forward_streams else None
+    return ddg.Pipeline(descs_for(wl, streams=streams, fstreams=fstreams, dry_run=True, stale_jacobian=stale), streams)
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("mode", ["streams", "forward_streams", "stale_jacobian"])
+def test_events_order_every_tensor_the_streams_share(K, mode):
+    """The pipeline's model of its own stream ordering (vector clocks over the event records and
+    waits it issues; every call's reads and writes of the exchanged activations, mailbox slots,
+    ring slots, tapes, weights and gradients declared) finds no access that the events leave
+    unordered, for K = 1..5 modules on K streams, with a forward stream per module, and in
+    stale-Jacobian mode."""
+    p = _dry_pipeline(K, mode == "forward_streams", stale=(mode == "stale_jacobian"))
+    fake = 4096
+    for t in range(3 * K + 6):
+        p.step(fake, fake, 0.01)
+    p.close()
+
+
+@pytest.mark.parametrize("own_forward_streams", [False, True])
+def test_a_missing_wait_is_found(own_forward_streams):
+    """Leaving out any single wait of a K = 3 schedule, in the model only: the model must report
+    a hazard for the waits that order two streams' accesses to a shared tensor, and name it."""
+    lib = _order_hooks()
+    K, steps = 3, 12
+    fake = 4096
+    p = _dry_pipeline(K, own_forward_streams)
+    for t in range(steps):
+        p.step(fake, fake, 0.01)
+    total = lib.ddg_internal_pipeline_waits(p._h)
+    p.close()
+    assert total > 4 * steps
+    found, kinds = 0, set()
+    for n in range(total):
+        p = _dry_pipeline(K, own_forward_streams)
+        lib.ddg_internal_pipeline_drop_wait(p._h, n)
+        try:
+            for t in range(steps):
+                p.step(fake, fake, 0.01)
+        except ddg.DDGError as e:
+            assert e.status == 3 and "hazard" in str(e), str(e)
+            found += 1
+            tensor = str(e).split("touches ")[1].split(" ")[0].split("/")[0].rstrip("0123456789")
+            kinds.add(str(e).split(" hazard")[0].split(": ")[-1] + " " + tensor)
+        p.close()
+    print(found, "of", total, sorted(kinds))
+    # most waits are the only thing that orders their pair of accesses
+    assert found >= total // 2, (found, total)
+    want = {"read-after-write h", "read-after-write mail", "write-after-read h"}
+    if own_forward_streams:
+        want |= {"read-after-write w", "write-after-read w", "write-after-read mail"}
+    assert want <= kinds, kinds
