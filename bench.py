@@ -305,6 +305,10 @@ def measure(wl, args, steps, warmup):
             roof["traffic_stale"] = read_source_digest(tpath) != source_digest()
         roof["kernel"] = dom
         roof["hip_kernel"] = HIP_KERNEL_OF.get(dom, dom)
+        if wl.dtype == "f32":   # the fp32 instances of the LDS-tiled kernels have names of their own
+            roof["hip_kernel"] = (roof["hip_kernel"].replace("conv3x3_tiled_kernel<", "conv3x3_tiled_f32_kernel<")
+                                  .replace("bwd_pair_kernel<", "bwd_pair_f32_kernel<")
+                                  .replace("wgrad_tiled_kernel<", "wgrad_tiled_f32_kernel<").replace("bf16_t", "float"))
         roof["avg_launch_us"] = d["avg_us"]
         roof["launches_per_step"] = d["launches_per_step"]
         roof["algorithmic_bytes_per_launch"] = nbytes / n

@@ -33,12 +33,13 @@
  *   DDG_NO_WGRAD_XCD=1  the wide weight-gradient kernel keeps the launch order of its workgroups
  *   DDG_NO_PREMASK=1 readers of an error gradient that was stored already multiplied by a
  *                    ReLU mask load the mask tensor and apply it again (same values)
- *   DDG_NO_LDS32=1   fp32 3x3 layers run the gather kernels instead of the LDS-staged ones
+ *   DDG_NO_LDS32=1   fp32 3x3 stride-1 layers run the gather kernels and separate batch-norm
+ *                    passes instead of the LDS-tiled kernels
  *   DDG_CHECK_ORDER=1  ddg_pipeline_step also runs its host-side model of the stream ordering
  *                    (always on in dry-run pipelines) and fails with DDG_ERR_STATE, naming the
  *                    tensor, if the events it issues leave two accesses of a tensor unordered
  *   DDG_TUNE_CONV_GRID_C16/_C32/_C64, DDG_TUNE_WGRAD_ROWS[_C16/_C32/_C64], DDG_TUNE_WGRAD_WIDE_WGS,
- *   DDG_TUNE_WGRAD_GENERIC_WGS, DDG_TUNE_WGRAD_LDS32_ROWS
+ *   DDG_TUNE_WGRAD_GENERIC_WGS, DDG_TUNE_CONV_GRID_F32, DDG_TUNE_WGRAD_ROWS_F32
  *                    workgroup counts of the LDS-tiled kernels (clamped to safe ranges)
  * None of them changes a result beyond the order of floating-point sums.
  *

@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libddg.so")
 PEAKS = os.path.join(HERE, "ddg_peaks")
 
-SOURCES = ["kernels_conv.hip", "kernels_conv_tiled.hip", "kernels_conv_lds32.hip", "kernels_conv_wide.hip", "kernels_wgrad.hip", "kernels_wgrad_tiled.hip", "kernels_wgrad_wide.hip", "kernels_elem.hip", "ddg_scratch.hip", "ddg_module.cpp", "ddg_pipeline.cpp"]
+SOURCES = ["kernels_conv.hip", "kernels_conv_tiled.hip", "kernels_conv_tiled_f32.hip", "kernels_conv_wide.hip", "kernels_wgrad.hip", "kernels_wgrad_tiled.hip", "kernels_wgrad_wide.hip", "kernels_elem.hip", "ddg_scratch.hip", "ddg_module.cpp", "ddg_pipeline.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

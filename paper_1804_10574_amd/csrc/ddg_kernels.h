@@ -65,9 +65,6 @@ struct ConvArgs {
   int dtype;
   int grid_x;               // filled by conv_plan
   int mb, nb;               // tile shape chosen by conv_plan
-  int lds32;                // filled by conv_plan: the LDS-staged fp32 kernel runs this layer (an input
-                            // gradient then takes the operand packed with mirrored taps, mode 2)
-  int no_lds32;             // set by the caller before conv_plan: keep the gather kernel
 };
 void conv_plan(ConvArgs& a);                       // chooses tile shape and grid
 hipError_t conv_launch(const ConvArgs& a, hipStream_t s);
@@ -77,20 +74,6 @@ size_t conv_wpack_elems(int kchannels, int nchannels, int R, int dtype, int* log
 // with mirrored taps (for kernels that run the input-gradient as a plain 3x3 correlation).
 hipError_t pack_weights_launch(const float* W, void* wpack, int Cout, int Cin, int R, int dgrad,
                                int dtype, hipStream_t s);
-
-// LDS-staged fp32 3x3/stride-1 convolution for 16/32/64 channels on 32/16/8-wide maps (forward, or
-// input gradient with an operand packed with mirrored taps). conv_lds32_grid: workgroups (= partial
-// statistics rows) or 0 if the shape is not covered.
-int conv_lds32_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
-hipError_t conv_lds32_launch(const void* in, const void* wpack, void* out, float* stat_partial, const void* in_b,
-                             void* out_b, float* stat_partial_b, const void* add_g, const void* add_mask, int N,
-                             int H, int W, int C, int grid, hipStream_t s);
-
-// LDS-staged fp32 weight gradient of the same layers: `rows` partial tiles [rows][C][9*C] (column
-// tap*C + ci), to be added by wgrad_reduce_all_launch. wgrad_lds32_rows: 0 if not covered.
-int wgrad_lds32_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype);
-hipError_t wgrad_lds32_launch(const void* x, const void* dz, float* partial, int N, int H, int W, int C, int rows,
-                              hipStream_t s);
 
 // Gradient w.r.t. the weights: dW[co][ci][r][s] = sum_{n,p,q} dz[n,p,q,co] * x[n,p*st+r-pad,q*st+s-pad,ci].
 // Two launches: per-split partial tiles, then a fixed-order sum into dW (deterministic).
@@ -179,6 +162,19 @@ hipError_t conv_tiled_launch(const void* in, const float* scale, const float* sh
                              const void* res = nullptr, void* y_out = nullptr, int groups = 1,
                              int vec_stride = 0, const WgradFuse* apply = nullptr, const WgradPair* pair = nullptr);
 
+
+// The same kernels with fp32 operands (kernels_conv_tiled_f32.hip): same arguments and rules;
+// conv_tiled_grid / wgrad_tiled_rows answer for both operand types.
+hipError_t conv_tiled_f32_launch(const void* in, const float* scale, const float* shift, const BnRows* in_rows,
+                                 const void* wpack, void* out, const ConvStat& st, const void* add_g,
+                                 const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
+                                 const void* res = nullptr, void* y_out = nullptr, int groups = 1,
+                                 int vec_stride = 0, const WgradFuse* apply = nullptr, const WgradPair* pair = nullptr);
+hipError_t wgrad_tiled_f32_launch(const void* x, const float* scale, const float* shift, const void* dz,
+                                  const WgradFuse* fuse, float* partial, int N, int H, int W, int C, int rows,
+                                  hipStream_t s);
+int conv_tiled_f32_grid(int N, int H, int W, int Cin, int Cout, int R, int stride);
+int wgrad_tiled_f32_rows(int N, int H, int W, int Cin, int Cout, int R, int stride);
 
 // GEMM-class kernel for wide bf16 layers (1x1 / 3x3, stride 1, contraction channels a power of
 // two >= 64, output channels a multiple of 128): forward, or input gradient with an operand

@@ -41,7 +41,6 @@ enum ProfKind {
   // the GEMM-class kernels of the wide layers
   PK_CONV_FPROP_WIDE = PK_BWD_PAIR_T64 + 1, PK_CONV_DGRAD_WIDE, PK_CONV_WGRAD_WIDE,
   PK_CONV_WGRAD_S2,   // the LDS-tiled weight gradient of the stride-2 layers between stages
-  PK_CONV_FPROP_LDS32, PK_CONV_DGRAD_LDS32, PK_CONV_WGRAD_LDS32,   // the LDS-staged fp32 kernels
   PK_WGRAD_REDUCE, PK_BN_FINALIZE, PK_BN_APPLY,
   PK_BN_BWD_REDUCE, PK_BN_BWD_FINALIZE, PK_BN_BWD_APPLY, PK_HEAD, PK_SGD, PK_PACK, PK_COPY, PK_ADAM, PK_BN_RUNNING, PK_COUNT
 };
@@ -51,7 +50,6 @@ static const char* kProfNames[PK_COUNT] = {
   "conv_wgrad.generic", "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c32_w16", "conv_wgrad.tiled_c64_w8",
   "conv_bwd_pair.tiled_c16_w32", "conv_bwd_pair.tiled_c32_w16", "conv_bwd_pair.tiled_c64_w8",
   "conv_fprop.wide", "conv_dgrad.wide", "conv_wgrad.wide", "conv_wgrad.tiled_stride2",
-  "conv_fprop.lds_f32", "conv_dgrad.lds_f32", "conv_wgrad.lds_f32",
   "wgrad_reduce", "bn_finalize", "bn_apply",
   "bn_bwd_reduce", "bn_bwd_finalize", "bn_bwd_apply", "head", "sgd", "pack_weights", "copy", "adam", "bn_running"};
 
@@ -83,7 +81,6 @@ struct Unit {  // convolution + batch normalisation
   float *escale = nullptr, *eshift = nullptr;  // evaluation-time scale and shift derived from them
   bool wide_f = false, wide_d = false;   // the GEMM-class kernel runs the forward conv / the input gradient
   int wide_splits = 0;                   // > 0: the GEMM-class weight-gradient kernel, this many pixel slices
-  int wg_lds32_rows = 0;                 // > 0: the LDS-staged fp32 weight-gradient kernel, this many partial tiles
   bool small_c() const { return cout == 16 || cout == 32 || cout == 64; }
   int tiled_instance() const { return cin == 16 ? 1 : cin == 32 ? 2 : 3; }   // offset of a tiled kernel's profile kind
   size_t out_elems() const { return (size_t)N * P * Q * cout; }
@@ -360,11 +357,11 @@ ddg_status build_plan(ddg_module* m) {
       ConvArgs& f = u.fprop;
       f.N = N; f.IH = u.H; f.IW = u.W; f.IC = u.cin; f.OH = u.P; f.OW = u.Q; f.OC = u.cout;
       f.R = u.R; f.stride = u.stride; f.pad = u.pad; f.ntaps = u.R * u.R;
-      f.M = N * u.P * u.Q; f.dgrad = 0; f.dtype = dt; f.no_lds32 = no_lds32;
+      f.M = N * u.P * u.Q; f.dgrad = 0; f.dtype = dt;
       size_t ne = conv_wpack_elems(u.cin, u.cout, u.R, dt, &f.log2cp, &f.ksteps);
       DDG_OKAY(dev_alloc(m, &u.wpack_f, ne * m->esz));
       conv_plan(f);
-      u.tiled_grid = conv_tiled_grid(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
+      u.tiled_grid = (dt == DDG_F32 && no_lds32) ? 0 : conv_tiled_grid(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
       if (u.tiled_grid > 0) f.grid_x = u.tiled_grid;   // the generic kernel never runs this layer
       u.wide_f = conv_wide_ok(u.cin, u.cout, u.R, u.stride, dt) && !getenv("DDG_NO_WIDE");
       u.wide_d = u.has_dgrad && conv_wide_ok(u.cout, u.cin, u.R, u.stride, dt) && !getenv("DDG_NO_WIDE");
@@ -389,7 +386,7 @@ ddg_status build_plan(ddg_module* m) {
         ConvArgs& g = u.dgrad;
         g.N = N; g.IH = u.P; g.IW = u.Q; g.IC = u.cout; g.OH = u.H; g.OW = u.W; g.OC = u.cin;
         g.R = u.R; g.stride = u.stride; g.pad = u.pad; g.ntaps = u.R * u.R;
-        g.M = N * u.H * u.W; g.dgrad = 1; g.dtype = dt; g.no_lds32 = no_lds32;
+        g.M = N * u.H * u.W; g.dgrad = 1; g.dtype = dt;
         ne = conv_wpack_elems(u.cout, u.cin, u.R, dt, &g.log2cp, &g.ksteps);
         u.wpack_d_bytes = (ne * m->esz + 255) & ~(size_t)255;
         DDG_OKAY(dev_alloc(m, &u.wpack_d, (m->stale ? (size_t)(d.K - d.k + 1) : 1) * u.wpack_d_bytes));
@@ -400,10 +397,8 @@ ddg_status build_plan(ddg_module* m) {
       wgd.N = N; wgd.H = u.H; wgd.W = u.W; wgd.Cin = u.cin; wgd.P = u.P; wgd.Q = u.Q; wgd.Cout = u.cout;
       wgd.R = u.R; wgd.stride = u.stride; wgd.pad = u.pad; wgd.M = N * u.P * u.Q; wgd.dtype = dt;
       wgrad_plan(wgd);
-      u.wg_tiled_rows = wgrad_tiled_rows(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
+      u.wg_tiled_rows = (dt == DDG_F32 && no_lds32) ? 0 : wgrad_tiled_rows(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
       if (u.wg_tiled_rows > 0) wgd.msplit = u.wg_tiled_rows;  // the reduce kernel sums this many rows
-      u.wg_lds32_rows = no_lds32 ? 0 : wgrad_lds32_rows(N, u.H, u.W, u.cin, u.cout, u.R, u.stride, dt);
-      if (u.wg_lds32_rows > 0) wgd.msplit = u.wg_lds32_rows;
       if (wgrad_wide_ok(u.cin, u.cout, u.R, u.stride, dt) && !getenv("DDG_NO_WIDE")) {
         u.wide_splits = wgrad_wide_splits(wgd.M, u.cin, u.cout, u.R);
         wgd.msplit = u.wide_splits;
@@ -475,7 +470,7 @@ ddg_status build_plan(ddg_module* m) {
       for (int mode = 0; mode < 2; ++mode) {
         if (mode == 1 && !u.has_dgrad) continue;
         PackDesc d{};
-        const int md = mode == 0 ? 0 : ((u.tiled_grid > 0 || u.wide_d || u.dgrad.lds32) ? 2 : 1);
+        const int md = mode == 0 ? 0 : ((u.tiled_grid > 0 || u.wide_d) ? 2 : 1);
         const int kc = md ? u.cout : u.cin, nc = md ? u.cin : u.cout;
         d.W = m->theta + u.ow; d.wpack = mode == 0 ? u.wpack_f : u.wpack_d;
         d.Cout = u.cout; d.Cin = u.cin; d.R = u.R; d.mode = md;
@@ -536,6 +531,26 @@ ddg_status pack_all(ddg_module* m) {
   return DDG_OK;
 }
 
+// The LDS-tiled kernels for the module's operand type (same arguments for both).
+static hipError_t conv_tiled_any(const ddg_module* m, const void* in, const float* scale, const float* shift,
+                                 const BnRows* in_rows, const void* wpack, void* out, const ConvStat& st, const void* add_g,
+                                 const void* add_mask, int N, int H, int W, int C, int grid, hipStream_t s,
+                                 const void* res = nullptr, void* y_out = nullptr, int groups = 1, int vec_stride = 0,
+                                 const WgradFuse* apply = nullptr, const WgradPair* pair = nullptr) {
+  if (m->d.compute == DDG_BF16)
+    return conv_tiled_launch(in, scale, shift, in_rows, wpack, out, st, add_g, add_mask, N, H, W, C, grid, s, res, y_out,
+                             groups, vec_stride, apply, pair);
+  return conv_tiled_f32_launch(in, scale, shift, in_rows, wpack, out, st, add_g, add_mask, N, H, W, C, grid, s, res, y_out,
+                               groups, vec_stride, apply, pair);
+}
+static hipError_t wgrad_tiled_any(const ddg_module* m, const void* x, const float* scale, const float* shift, const void* dz,
+                                  const WgradFuse* fuse, float* partial, int N, int H, int W, int C, int rows, hipStream_t s,
+                                  int Cout = 0, int R = 3, int stride = 1) {
+  if (m->d.compute == DDG_BF16) return wgrad_tiled_launch(x, scale, shift, dz, fuse, partial, N, H, W, C, rows, s, Cout, R, stride);
+  if ((Cout != 0 && Cout != C) || R != 3 || stride != 1) return hipErrorInvalidValue;
+  return wgrad_tiled_f32_launch(x, scale, shift, dz, fuse, partial, N, H, W, C, rows, s);
+}
+
 // Algorithmic work of one convolution pass over unit u.
 double conv_flops(const Unit& u) { return 2.0 * u.N * u.P * u.Q * (double)u.cout * u.cin * u.R * u.R; }
 double wbytes(const ddg_module* m, const Unit& u) { return (double)u.cout * u.cin * u.R * u.R * m->esz; }
@@ -582,7 +597,7 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
     const float* ssh = !src ? nullptr : (m->eval_mode ? src->eshift : src->shift + svo);
     Launch L(m, PK_CONV_FPROP + u.tiled_instance(),
              G * (((res ? 3.0 : 1.0) * u.in_elems() + u.out_elems()) * (double)m->esz) + wbytes(m, u), G * conv_flops(u));
-    DDG_TRY(conv_tiled_launch(in, (src && !from_rows) ? ssc : nullptr, (src && !from_rows) ? ssh : nullptr,
+    DDG_TRY(conv_tiled_any(m, in, (src && !from_rows) ? ssc : nullptr, (src && !from_rows) ? ssh : nullptr,
                               from_rows ? &ir : nullptr, u.wpack_f, z, st, nullptr, nullptr, G * u.N, u.H, u.W,
                               u.cin, G * u.tiled_grid, m->stream, res, y_store, G, src ? src->vec_stride() : 0));
   } else {
@@ -599,7 +614,7 @@ ddg_status unit_forward(ddg_module* m, Unit& u, const void* in, Unit* src, const
       conv_plan(a);
       u.frows = a.grid_x;
       a.in = in; a.wpack = u.wpack_f; a.out = z; a.stat_partial = fstat; a.add_g = nullptr; a.add_mask = nullptr;
-      Launch L(m, a.lds32 ? PK_CONV_FPROP_LDS32 : PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
+      Launch L(m, PK_CONV_FPROP, (u.in_elems() + u.out_elems()) * (double)m->esz + wbytes(m, u), conv_flops(u));
       DDG_TRY(conv_launch(a, m->stream));
     }
   }
@@ -684,7 +699,7 @@ ddg_status unit_forward_two(ddg_module* m, Unit& u, const void* in0, const void*
     u.frows = a.grid_x;
     a.in = in0; a.wpack = u.wpack_f; a.out = u.z; a.stat_partial = u.fstat; a.add_g = nullptr; a.add_mask = nullptr;
     a.in_b = in1; a.out_b = z1; a.stat_partial_b = fstat1;
-    Launch L(m, a.lds32 ? PK_CONV_FPROP_LDS32 : PK_CONV_FPROP, bytes, 2.0 * conv_flops(u));
+    Launch L(m, PK_CONV_FPROP, bytes, 2.0 * conv_flops(u));
     DDG_TRY(conv_launch(a, m->stream));
   }
   if (!u.small_c()) {
@@ -872,7 +887,7 @@ ddg_status flush_pending_wgrad(ddg_module* m) {
   const Unit& u = *w.u;
   Launch L(m, PK_CONV_WGRAD + u.tiled_instance(), (u.in_elems() + (double)u.out_elems()) * m->esz + wbytes(m, u) * 4.0 / m->esz,
            conv_flops(u));
-  DDG_TRY(wgrad_tiled_launch(w.x, w.xsc, w.xsh, w.dz, nullptr, u.wg_partial, u.N, u.H, u.W, u.cin, u.wg_tiled_rows,
+  DDG_TRY(wgrad_tiled_any(m, w.x, w.xsc, w.xsh, w.dz, nullptr, u.wg_partial, u.N, u.H, u.W, u.cin, u.wg_tiled_rows,
                              m->stream));
   return DDG_OK;
 }
@@ -940,7 +955,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
         m->pend_w.on = false;
       }
       Launch L(m, (ride ? PK_BWD_PAIR : PK_CONV_DGRAD) + u.tiled_instance(), bytes, flops);
-      DDG_TRY(conv_tiled_launch(dy, nullptr, nullptr, nullptr, u.wpack_d, dx, st, add_g, add_mask, u.N, u.H, u.W,
+      DDG_TRY(conv_tiled_any(m, dy, nullptr, nullptr, nullptr, u.wpack_d, dx, st, add_g, add_mask, u.N, u.H, u.W,
                                 u.cin, u.tiled_grid, m->stream, nullptr, nullptr, 1, 0, &f, ride ? &wp : nullptr));
     }
     m->pend_w.on = true; m->pend_w.u = &u; m->pend_w.x = x_in; m->pend_w.xsc = x_scale; m->pend_w.xsh = x_shift;
@@ -959,7 +974,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     // reads x, dy, z (and the mask tensor if it is a different one), writes dz and dW
     Launch L(m, u.stride == 2 ? PK_CONV_WGRAD_S2 : PK_CONV_WGRAD + u.tiled_instance(),
              (u.in_elems() + (mask && mask != u.z ? 4.0 : 3.0) * E) * m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
-    DDG_TRY(wgrad_tiled_launch(x_in, x_scale, x_shift, nullptr, &f, u.wg_partial, u.N, u.H, u.W, u.cin,
+    DDG_TRY(wgrad_tiled_any(m, x_in, x_scale, x_shift, nullptr, &f, u.wg_partial, u.N, u.H, u.W, u.cin,
                                u.wg_tiled_rows, m->stream, u.cout, u.R, u.stride));
   } else {
     if (u.small_c()) {
@@ -974,13 +989,11 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
       DDG_TRY(bn_bwd_apply_launch(dy, mask, mscale, mshift, u.z, u.coef, nullptr, dz_buf, E, u.cout, dt, m->stream));
     }
     if (x_scale && u.wide_splits == 0) return fail(DDG_ERR_STATE, "internal: generic weight gradient needs a materialised input");
-    Launch L(m, u.wide_splits > 0 ? PK_CONV_WGRAD_WIDE : (u.wg_lds32_rows > 0 ? PK_CONV_WGRAD_LDS32 : PK_CONV_WGRAD),
+    Launch L(m, u.wide_splits > 0 ? PK_CONV_WGRAD_WIDE : PK_CONV_WGRAD,
              (u.in_elems() + E) * (double)m->esz + wbytes(m, u) * 4.0 / m->esz, conv_flops(u));
     if (u.wide_splits > 0)
       DDG_TRY(wgrad_wide_launch(x_in, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.cout, u.R, u.wide_splits, m->stream,
                                 x_scale, x_shift));
-    else if (u.wg_lds32_rows > 0)
-      DDG_TRY(wgrad_lds32_launch(x_in, dz_buf, u.wg_partial, u.N, u.H, u.W, u.cin, u.wg_lds32_rows, m->stream));
     else
       DDG_TRY(wgrad_launch(w, m->stream));
   }
@@ -992,7 +1005,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
     const bool fuse_below = (u.tiled_grid > 0 && below && below->u) || wide_below;
     double extra = (add_g ? (add_mask ? 2.0 : 1.0) : 0.0);
     if (fuse_below) extra += (below->mask == below->u->z) ? 1.0 : 2.0;
-    Launch L(m, u.tiled_grid > 0 ? PK_CONV_DGRAD + u.tiled_instance() : (u.wide_d ? PK_CONV_DGRAD_WIDE : (u.dgrad.lds32 ? PK_CONV_DGRAD_LDS32 : PK_CONV_DGRAD)),
+    Launch L(m, u.tiled_grid > 0 ? PK_CONV_DGRAD + u.tiled_instance() : (u.wide_d ? PK_CONV_DGRAD_WIDE : PK_CONV_DGRAD),
              (E + (1.0 + extra) * u.in_elems()) * m->esz + wbytes(m, u), conv_flops(u));
     if (u.tiled_grid == 0 && u.wide_d) {
       ConvStat st{};
@@ -1012,7 +1025,7 @@ ddg_status unit_backward(ddg_module* m, Unit& u, const void* dy, const void* mas
         st.z = below->u->z; st.zmean = below->u->mean; st.zinvstd = below->u->invstd;
         if (below_rows) *below_rows = u.tiled_grid;
       }
-      DDG_TRY(conv_tiled_launch(dz_buf, nullptr, nullptr, nullptr, u.wpack_d, dx, st, add_g, add_mask, u.N, u.H, u.W,
+      DDG_TRY(conv_tiled_any(m, dz_buf, nullptr, nullptr, nullptr, u.wpack_d, dx, st, add_g, add_mask, u.N, u.H, u.W,
                                 u.cin, u.tiled_grid, m->stream));
     } else {
       ConvArgs a = u.dgrad;

@@ -212,11 +212,6 @@ size_t conv_wpack_elems(int kchannels, int nchannels, int R, int dtype, int* log
 }
 
 void conv_plan(ConvArgs& a) {
-  a.lds32 = 0;
-  {
-    const int g = a.no_lds32 ? 0 : conv_lds32_grid(a.N, a.IH, a.IW, a.IC, a.OC, a.R, a.stride, a.dtype);
-    if (g > 0) { a.lds32 = 1; a.grid_x = g; a.mb = 4; a.nb = 1; return; }
-  }
   const int ocb = a.OC / 16;
   if (ocb % 4 == 0) { a.nb = 4; a.mb = 2; }
   else if (ocb % 2 == 0) { a.nb = 2; a.mb = 2; }
@@ -238,9 +233,6 @@ void conv_plan(ConvArgs& a) {
 
 template <typename T>
 static hipError_t conv_dispatch(const ConvArgs& a, hipStream_t s) {
-  if (a.lds32)
-    return conv_lds32_launch(a.in, a.wpack, a.out, a.stat_partial, a.in_b, a.out_b, a.stat_partial_b, a.add_g,
-                             a.add_mask, a.N, a.IH, a.IW, a.IC, a.grid_x, s);
   dim3 grid(a.grid_x, (a.OC / 16) / a.nb, a.in_b ? 2 : 1), block(256);
   const bool vec = a.IC % Mma<T>::KV == 0;
 #define DDG_CONV_CASE(MB_, NB_)                                                                   \

@@ -437,6 +437,7 @@ int conv_tiled_max_grid() {
 }
 
 int conv_tiled_grid(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype) {
+  if (dtype == F32) return conv_tiled_f32_grid(N, H, W, Cin, Cout, R, stride);
   if (dtype != BF16 || R != 3 || stride != 1 || Cin != Cout) return 0;
   if (!((Cin == 16 && W == 32) || (Cin == 32 && W == 16) || (Cin == 64 && W == 8))) return 0;
   if (H % 8 != 0) return 0;

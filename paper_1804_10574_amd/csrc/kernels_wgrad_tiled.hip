@@ -61,6 +61,7 @@ static bool wgrad_tiled_stride2(int H, int W, int Cin, int Cout, int R, int stri
 // Returns the number of partial rows (grid.x) the tiled kernel will use for this shape, or 0
 // if the shape is not covered (then the generic kernel is used).
 int wgrad_tiled_rows(int N, int H, int W, int Cin, int Cout, int R, int stride, int dtype) {
+  if (dtype == F32) return wgrad_tiled_f32_rows(N, H, W, Cin, Cout, R, stride);
   if (dtype == BF16 && wgrad_tiled_stride2(H, W, Cin, Cout, R, stride)) {
     const int tiles = N * (H / 2 / 8);
     const int want = 64;
