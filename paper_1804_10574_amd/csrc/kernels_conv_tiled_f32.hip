@@ -47,7 +47,9 @@ struct WgradTiledF32Args {
 
 template <int C, int W>
 struct ConvTiledF32Cfg {
-  static constexpr int TH = 8, ROWS = TH + 2, WC = W + 2;
+  // 64 channels: tiles of 4 rows, so that a minibatch of 128 8x8 maps has a tile for every
+  // compute unit (the fp32 matrix instruction makes these layers compute-bound)
+  static constexpr int TH = C == 64 ? 4 : 8, ROWS = TH + 2, WC = W + 2;
   static constexpr int PIX = C * 4 + 16;                 // bytes per staged pixel
   static constexpr int TILE_BYTES = ROWS * WC * PIX;
   static constexpr int CH = C / 4;                       // 16-byte chunks per pixel
@@ -56,6 +58,7 @@ struct ConvTiledF32Cfg {
   static constexpr int KSTEPS = 9 * C / 16;              // fragments of 16 k-values (4 per lane)
   static constexpr int PG = W / 8;
   static constexpr int COB = C / 16;
+  static constexpr int NB = TH * W / (16 * PG);          // pixel blocks per wave: 4, 4, 2
   static constexpr bool WREG = C <= 32;                  // the wave's weights stay in registers
 };
 
@@ -68,7 +71,7 @@ __device__ __forceinline__ void conv3x3_tiled_f32_body(const ConvTiledF32Args& a
   using Cfg = ConvTiledF32Cfg<C, W>;
   constexpr bool RES = XF == XF32_RES, APPLY = XF == XF32_APPLY || XF == XF32_APPLY_MASK;
   constexpr int TH = Cfg::TH, WC = Cfg::WC, PIX = Cfg::PIX, CH = Cfg::CH, NCHUNK = Cfg::NCHUNK;
-  constexpr int PT = Cfg::PER_THREAD, KSTEPS = Cfg::KSTEPS, PG = Cfg::PG, COB = Cfg::COB;
+  constexpr int PT = Cfg::PER_THREAD, KSTEPS = Cfg::KSTEPS, PG = Cfg::PG, COB = Cfg::COB, NB = Cfg::NB;
   static_assert(PT <= 8, "four bits per chunk in one word");
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -126,7 +129,7 @@ __device__ __forceinline__ void conv3x3_tiled_f32_body(const ConvTiledF32Args& a
     for (int ks = 0; ks < KSTEPS; ++ks) wf[ks] = *reinterpret_cast<const float4*>(wsrc + (size_t)ks * COB * 64 * 4);
   }
 
-  const int ptl = pgrp * 64 + l16;
+  const int ptl = pgrp * (NB * 16) + l16;
   const int lane_base = ((ptl / W) * WC + (ptl % W)) * PIX + lg * 16;
   const int out_lane = ptl * C + cb * 16 + lg * 4;
 
@@ -216,25 +219,25 @@ __device__ __forceinline__ void conv3x3_tiled_f32_body(const ConvTiledF32Args& a
     const int n = t / tiles_per_img, r0 = (t - n * tiles_per_img) * TH;
     const unsigned obase = (unsigned)((n * a.H + r0) * W) * C + out_lane;
     // what the epilogue reads, requested now
-    float4 eg[4], em[4], ek[4], ez[4];
+    float4 eg[NB], em[NB], ek[NB], ez[NB];
     if (a.add_g) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NB; ++i) {
         eg[i] = *reinterpret_cast<const float4*>(a.add_g + obase + i * 16 * C);
         if (a.add_mask) em[i] = *reinterpret_cast<const float4*>(a.add_mask + obase + i * 16 * C);
       }
     }
     if (MODE == 2) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NB; ++i) {
         ek[i] = *reinterpret_cast<const float4*>(st_mask + obase + i * 16 * C);
         if (two_tensors) ez[i] = *reinterpret_cast<const float4*>(st_z + obase + i * 16 * C);
       }
     }
 
-    f32x4_t acc[4];
+    f32x4_t acc[NB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < NB; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     // 64 channels: the weight fragments do not fit the registers; they come from the packed
     // operand (L1/L2 resident) through a ring of four, requested three to four k-steps ahead
     float4 wq[Cfg::WREG ? 1 : 4];
@@ -250,7 +253,7 @@ __device__ __forceinline__ void conv3x3_tiled_f32_body(const ConvTiledF32Args& a
       const unsigned char* kp = tile + lane_base + ((tap / 3) * WC + (tap % 3)) * PIX + c0 * 4;
       const float4 w4 = Cfg::WREG ? wf[Cfg::WREG ? ks : 0] : wq[Cfg::WREG ? 0 : (ks & 3)];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NB; ++i) {
         const int blk = (((i * 16) / W) * WC + (i * 16) % W) * PIX;   // constant after unrolling
         const float4 af = *reinterpret_cast<const float4*>(kp + blk);
         acc[i] = Mma<float>::mma(w4, af, acc[i]);
@@ -267,7 +270,7 @@ __device__ __forceinline__ void conv3x3_tiled_f32_body(const ConvTiledF32Args& a
 
     // epilogue: lane = pixel l16 of block i, channels cb*16 + lg*4 .. +3
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NB; ++i) {
       float v[4] = {acc[i][0], acc[i][1], acc[i][2], acc[i][3]};
       if (a.add_g) {
         float g[4] = {eg[i].x, eg[i].y, eg[i].z, eg[i].w};
@@ -561,7 +564,9 @@ int conv_tiled_f32_grid(int N, int H, int W, int Cin, int Cout, int R, int strid
   int cap = 128;   // (measured on ResNet-20 at batch 128: 64 / 96 / 128 / 160 / 192 / 256 -> 110 / 116 / 135 / 129 / 130 / 131 K images/sec)
   if (const char* e = getenv("DDG_TUNE_CONV_GRID_F32")) { const int v = atoi(e); if (v >= 32 && v <= conv_tiled_max_grid()) cap = v; }
   if (cap > conv_tiled_max_grid()) cap = conv_tiled_max_grid();
-  const int tiles = N * (H / 8);
+  if (Cin == 64 && !getenv("DDG_TUNE_CONV_GRID_F32")) cap = 256;   // (4-row tiles: one per compute unit)
+  if (cap > conv_tiled_max_grid()) cap = conv_tiled_max_grid();
+  const int tiles = N * (H / (Cin == 64 ? 4 : 8));
   return tiles < cap ? tiles : cap;
 }
 int wgrad_tiled_f32_rows(int N, int H, int W, int Cin, int Cout, int R, int stride) {
@@ -633,7 +638,7 @@ hipError_t conv_tiled_f32_launch(const void* in, const float* scale, const float
   a.res = (const float*)res; a.y_out = (float*)y_out;
   if (in_rows) a.in_rows = *in_rows; else a.in_rows = BnRows{};
   a.out = (float*)out; a.st = st; a.add_g = (const float*)add_g; a.add_mask = (const float*)add_mask;
-  a.N = N; a.H = H; a.tiles = N * (H / 8);
+  a.N = N; a.H = H; a.tiles = N * (H / (C == 64 ? 4 : 8));
   WgradTiledF32Args wa{};
   if (pair) {
     const int wtiles = N * (H / (C == 64 ? 4 : 8));
