@@ -50,9 +50,16 @@ def kind_of(kernel_name: str) -> str:
     if m:
         fam = "conv_fprop" if m.group(3) == "1" else "conv_dgrad"
         return f"{fam}.tiled_c{m.group(1)}_w{m.group(2)}"
-    m = re.match(r"bwd_pair_kernel<(\d+), (\d+), ", n)
+    m = re.match(r"conv3x3_tiled_f32_kernel<(\d+), (\d+), (\d+)", n)
+    if m:   # the fp32 instances book the same kinds
+        fam = "conv_fprop" if m.group(3) == "1" else "conv_dgrad"
+        return f"{fam}.tiled_c{m.group(1)}_w{m.group(2)}"
+    m = re.match(r"bwd_pair(?:_f32)?_kernel<(\d+), (\d+), ", n)
     if m:
         return f"conv_bwd_pair.tiled_c{m.group(1)}_w{m.group(2)}"
+    m = re.match(r"wgrad_tiled_f32_kernel<(\d+), (\d+)>", n)
+    if m:
+        return f"conv_wgrad.tiled_c{m.group(1)}_w{m.group(2)}"
     m = re.match(r"wgrad_tiled_kernel<(\d+), (\d+), (\d+), (\d+), (\d+)>", n)
     if m:   # <Cin, Cout, output width, stride, kernel size>
         return "conv_wgrad.tiled_stride2" if m.group(4) == "2" else f"conv_wgrad.tiled_c{m.group(1)}_w{m.group(3)}"
