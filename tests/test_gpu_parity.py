@@ -612,6 +612,26 @@ def test_cifar_shaped_pipeline_f32(H):
     assert not report, "\n".join(report)
 
 
+@pytest.mark.parametrize("switch", ["DDG_NO_BWD_PAIR", "DDG_NO_PAIR", "DDG_NO_DEFER", "DDG_NO_PREMASK", "DDG_NO_GRAPH"])
+def test_cifar_shaped_pipeline_f32_other_launch_plans(H, monkeypatch, switch):
+    """The fp32 instances of the LDS-tiled kernels under each of the library's launch-plan switches
+    (see the bf16 cases above): every fused path of the fp32 kernels has a plan that leaves it out."""
+    monkeypatch.setenv(switch, "1")
+    wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="f32", name="cifar_k3")
+    _say(f"case cifar_k3 f32 steps=8, {switch}=1")
+    report, stats = H.run_pipeline_parity(wl, 8, 1e-4, say=_say, loose=2e-2)
+    assert not report, "\n".join(report)
+
+
+def test_stale_jacobian_cifar_shapes_f32(H):
+    """Eq. 6-7 as printed on the CIFAR layer shapes in fp32: the fp32 tiled kernels reading the
+    tape and the weight snapshot of the ring slot."""
+    wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="f32", name="cifar_k3")
+    _say("case cifar_k3 f32 steps=8, stale Jacobian")
+    report, stats = H.run_pipeline_parity(wl, 8, 1e-4, say=_say, loose=2e-2, stale_jacobian=True)
+    assert not report, "\n".join(report)
+
+
 def _deep_three_way(H, wl, steps, tol, factor, slack):
     report, d = H.run_pipeline_three_way(wl, steps, say=_say)
     bad = list(report)
@@ -629,7 +649,8 @@ def _deep_three_way(H, wl, steps, tol, factor, slack):
 
 def test_cifar_shaped_pipeline_f32_gather_kernels(H, monkeypatch):
     """The same fp32 pipeline with the library's environment switch that keeps the gather kernels
-    for the 3x3 layers the LDS-staged fp32 kernels otherwise run (read when a module is created)."""
+    and separate batch-norm passes for the 3x3 layers the LDS-tiled fp32 kernels otherwise run (read
+    when a module is created)."""
     monkeypatch.setenv("DDG_NO_LDS32", "1")
     wl = custom_cifar(2, [3, 5], batch=8, num_classes=10, hw=32, dtype="f32", name="cifar_k3")
     _say("case cifar_k3 f32 steps=8, DDG_NO_LDS32=1")
