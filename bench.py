@@ -12,6 +12,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import re
 import os
 import sys
 import time
@@ -306,9 +307,14 @@ def measure(wl, args, steps, warmup):
         roof["kernel"] = dom
         roof["hip_kernel"] = HIP_KERNEL_OF.get(dom, dom)
         if wl.dtype == "f32":   # the fp32 instances of the LDS-tiled kernels have names of their own
-            roof["hip_kernel"] = (roof["hip_kernel"].replace("conv3x3_tiled_kernel<", "conv3x3_tiled_f32_kernel<")
-                                  .replace("bwd_pair_kernel<", "bwd_pair_f32_kernel<")
-                                  .replace("wgrad_tiled_kernel<", "wgrad_tiled_f32_kernel<").replace("bf16_t", "float"))
+            m = re.match(r"conv_(fprop|dgrad|bwd_pair|wgrad)\.tiled_c(\d+)_w(\d+)$", dom)
+            if m:
+                fam, c, w = m.groups()
+                roof["hip_kernel"] = {"fprop": f"ddg::conv3x3_tiled_f32_kernel<{c}, {w}, 1, XF>",
+                                      "dgrad": f"ddg::conv3x3_tiled_f32_kernel<{c}, {w}, 2|0, XF>",
+                                      "bwd_pair": f"ddg::bwd_pair_f32_kernel<{c}, {w}, 2|0, XF>",
+                                      "wgrad": f"ddg::wgrad_tiled_f32_kernel<{c}, {w}>"}[fam]
+            roof["hip_kernel"] = roof["hip_kernel"].replace("bf16_t", "float")
         roof["avg_launch_us"] = d["avg_us"]
         roof["launches_per_step"] = d["launches_per_step"]
         roof["algorithmic_bytes_per_launch"] = nbytes / n
