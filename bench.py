@@ -309,11 +309,11 @@ def measure(wl, args, steps, warmup):
         if wl.dtype == "f32":   # the fp32 instances of the LDS-tiled kernels have names of their own
             m = re.match(r"conv_(fprop|dgrad|bwd_pair|wgrad)\.tiled_c(\d+)_w(\d+)$", dom)
             if m:
-                fam, c, w = m.groups()
+                what, c, w = m.groups()
                 roof["hip_kernel"] = {"fprop": f"ddg::conv3x3_tiled_f32_kernel<{c}, {w}, 1, XF>",
                                       "dgrad": f"ddg::conv3x3_tiled_f32_kernel<{c}, {w}, 2|0, XF>",
                                       "bwd_pair": f"ddg::bwd_pair_f32_kernel<{c}, {w}, 2|0, XF>",
-                                      "wgrad": f"ddg::wgrad_tiled_f32_kernel<{c}, {w}>"}[fam]
+                                      "wgrad": f"ddg::wgrad_tiled_f32_kernel<{c}, {w}>"}[what]
             roof["hip_kernel"] = roof["hip_kernel"].replace("bf16_t", "float")
         roof["avg_launch_us"] = d["avg_us"]
         roof["launches_per_step"] = d["launches_per_step"]
