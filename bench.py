@@ -50,6 +50,22 @@ HIP_KERNEL_OF = {
 }
 
 
+def hip_kernel_label(kind, dtype):
+    """The HIP kernel a profile kind times, as rocprofv3 names it (the fp32 instances of the
+    LDS-tiled kernels have names of their own)."""
+    name = HIP_KERNEL_OF.get(kind, kind)
+    if dtype == "f32":
+        m = re.match(r"conv_(fprop|dgrad|bwd_pair|wgrad)\.tiled_c(\d+)_w(\d+)$", kind)
+        if m:
+            what, c, w = m.groups()
+            name = {"fprop": f"ddg::conv3x3_tiled_f32_kernel<{c}, {w}, 1, XF>",
+                    "dgrad": f"ddg::conv3x3_tiled_f32_kernel<{c}, {w}, 2|0, XF>",
+                    "bwd_pair": f"ddg::bwd_pair_f32_kernel<{c}, {w}, 2|0, XF>",
+                    "wgrad": f"ddg::wgrad_tiled_f32_kernel<{c}, {w}>"}[what]
+        name = name.replace("bf16_t", "float")
+    return name
+
+
 def build_pipeline(wl, serial=False, forward_streams=False, stale_jacobian=False):
     import torch
     import numpy as np
@@ -305,16 +321,7 @@ def measure(wl, args, steps, warmup):
             roof["traffic_source"] = os.path.relpath(tpath, here)
             roof["traffic_stale"] = read_source_digest(tpath) != source_digest()
         roof["kernel"] = dom
-        roof["hip_kernel"] = HIP_KERNEL_OF.get(dom, dom)
-        if wl.dtype == "f32":   # the fp32 instances of the LDS-tiled kernels have names of their own
-            m = re.match(r"conv_(fprop|dgrad|bwd_pair|wgrad)\.tiled_c(\d+)_w(\d+)$", dom)
-            if m:
-                what, c, w = m.groups()
-                roof["hip_kernel"] = {"fprop": f"ddg::conv3x3_tiled_f32_kernel<{c}, {w}, 1, XF>",
-                                      "dgrad": f"ddg::conv3x3_tiled_f32_kernel<{c}, {w}, 2|0, XF>",
-                                      "bwd_pair": f"ddg::bwd_pair_f32_kernel<{c}, {w}, 2|0, XF>",
-                                      "wgrad": f"ddg::wgrad_tiled_f32_kernel<{c}, {w}>"}[what]
-            roof["hip_kernel"] = roof["hip_kernel"].replace("bf16_t", "float")
+        roof["hip_kernel"] = hip_kernel_label(dom, wl.dtype)
         roof["avg_launch_us"] = d["avg_us"]
         roof["launches_per_step"] = d["launches_per_step"]
         roof["algorithmic_bytes_per_launch"] = nbytes / n

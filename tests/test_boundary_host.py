@@ -336,3 +336,21 @@ def test_a_missing_wait_is_found(own_forward_streams):
     if own_forward_streams:
         want |= {"read-after-write w", "write-after-read w", "write-after-read mail"}
     assert want <= kinds, kinds
+
+
+def test_bench_names_kernels_as_the_profiler_does():
+    """bench.py's label of the kernel behind a profile kind agrees with the kind the profile
+    summaries derive from that kernel's name, for the bf16 and the fp32 instances."""
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    from paper_1804_10574_amd import profile_summary as ps
+    for kind in ("conv_fprop.tiled_c16_w32", "conv_dgrad.tiled_c32_w16", "conv_bwd_pair.tiled_c64_w8",
+                 "conv_wgrad.tiled_c16_w32", "conv_wgrad.tiled_c64_w8"):
+        for dtype in ("bf16", "f32"):
+            label = bench.hip_kernel_label(kind, dtype)
+            assert ("_f32_" in label) == (dtype == "f32"), label
+            concrete = label.replace("2|0", "2").replace("XF", "0").replace("ddg::", "void ddg::") + "(args)"
+            assert ps.kind_of(concrete) == kind, (label, ps.kind_of(concrete))
+    assert bench.hip_kernel_label("bn_apply", "f32").endswith("<float, U>")
+    assert bench.hip_kernel_label("sgd", "bf16") == bench.HIP_KERNEL_OF.get("sgd", "sgd")
